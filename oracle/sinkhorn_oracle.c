@@ -1,0 +1,439 @@
+/*
+ * sinkhorn_oracle.c -- TEST INFRASTRUCTURE, not part of the product.
+ *
+ * A plain, slow, fp64 CPU statement of what the Sinkhorn hot path computes,
+ * written from the paper's definitions so that it can be checked against the
+ * paper by eye.  Only the test-suite, the smoke check and the benchmark's
+ * "cpu_baseline" leg may call it.  It shares no code with the GPU library.
+ *
+ * What it follows:
+ *   - Gibbs kernel K = exp(-C/eps) and the scaling iteration
+ *       u <- a ./ (K v),  v <- b ./ (K^T u)            (Sec. 1, below Eq. 1)
+ *   - one iteration = u-update then v-update, u = v = 1 at start
+ *                                                      (Algorithm 1)
+ *   - row-partitioned form, n = c*m, contiguous index sets I_j
+ *                                                      (Sec. 3.1, Algorithm 1)
+ *   - blocked iterates equal centralised iterates      (Proposition 1)
+ *   - multitarget form: n x N matrices of scalings sharing K (Sec. 5.3.2)
+ *   - marginal error of P = diag(u) K diag(v)          (Sec. 5.4, App. DP protocol)
+ *   - damped updates, arithmetic and geometric         (Sec. 3.3 and its Remark)
+ *   - log-domain form: the paper only names it (Sec. 1, Sec. 2.1); the
+ *     formulas here are the exact logarithm of the iteration above with
+ *     f = eps*log u, g = eps*log v.
+ *
+ * Every sum is a single left-to-right fp64 loop.  K may be handed over as
+ * fp32 or fp64 storage; each entry is promoted to fp64 before use.  OpenMP is
+ * used only across independent outputs (one thread owns one output element's
+ * whole sum), so results do not depend on the thread count.
+ *
+ * Parity pins (see tests/test_oracle_*.py): exact marginals after each
+ * half-step, constant-cost closed form, 2x2 and 3x3 brute-force optimum of
+ * Eq. 1, dual ascent and duality gap, blocked == centralised, numpy matmul /
+ * scipy logsumexp on single steps, dense == log-domain, batched column ==
+ * single run, symmetric special case, resume, Hilbert-metric contraction.
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+int orc_num_threads(void) {
+#ifdef _OPENMP
+  return omp_get_max_threads();
+#else
+  return 1;
+#endif
+}
+
+void orc_set_threads(int t) {
+#ifdef _OPENMP
+  if (t > 0) omp_set_num_threads(t);
+#else
+  (void)t;
+#endif
+}
+
+/* K entry (i,j) of a row-major matrix with leading dimension ld, as fp64. */
+static inline double k_at(const void* K, int k_is_f32, int64_t ld, int64_t i, int64_t j) {
+  return k_is_f32 ? (double)((const float*)K)[i * ld + j] : ((const double*)K)[i * ld + j];
+}
+
+/* ------------------------------------------------------------------ setup */
+
+/* C_ij = sum_k (x_ik - y_jk)^2, x: nx x d, y: ny x d, C: nx x ny (Sec. 5.6). */
+void orc_cost_sqeuclid(const double* x, const double* y, int64_t nx, int64_t ny, int d, double* C) {
+#pragma omp parallel for schedule(static)
+  for (int64_t i = 0; i < nx; ++i)
+    for (int64_t j = 0; j < ny; ++j) {
+      double s = 0.0;
+      for (int k = 0; k < d; ++k) {
+        double t = x[i * d + k] - y[j * d + k];
+        s += t * t;
+      }
+      C[i * ny + j] = s;
+    }
+}
+
+double orc_max(const double* C, int64_t count) {
+  double m = C[0];
+  for (int64_t t = 1; t < count; ++t)
+    if (C[t] > m) m = C[t];
+  return m;
+}
+
+/* C <- C / s  (the "normalised by max(C)" step of the workloads). */
+void orc_divide_inplace(double* C, int64_t count, double s) {
+#pragma omp parallel for schedule(static)
+  for (int64_t t = 0; t < count; ++t) C[t] = C[t] / s;
+}
+
+/* K = exp(-C/eps), elementwise (Sec. 1). */
+void orc_gibbs(const double* C, int64_t count, double eps, double* K) {
+#pragma omp parallel for schedule(static)
+  for (int64_t t = 0; t < count; ++t) K[t] = exp(-C[t] / eps);
+}
+
+/* Same, fused for large n so that no n x n fp64 array is needed:
+ * K_ij = (float) exp(-(||x_i-y_j||^2 / cmax) / eps); pass cmax = 1 for no
+ * normalisation.  Written to fp32 storage (the value the fp32 GPU path is fed). */
+void orc_gibbs_from_points_f32(const double* x, const double* y, int64_t nx, int64_t ny, int d,
+                               double cmax, double eps, float* K) {
+#pragma omp parallel for schedule(static)
+  for (int64_t i = 0; i < nx; ++i)
+    for (int64_t j = 0; j < ny; ++j) {
+      double s = 0.0;
+      for (int k = 0; k < d; ++k) {
+        double t = x[i * d + k] - y[j * d + k];
+        s += t * t;
+      }
+      K[i * ny + j] = (float)exp(-(s / cmax) / eps);
+    }
+}
+
+/* max_ij ||x_i-y_j||^2 without storing C. */
+double orc_max_sqeuclid(const double* x, const double* y, int64_t nx, int64_t ny, int d) {
+  double m = 0.0;
+#pragma omp parallel for schedule(static) reduction(max : m)
+  for (int64_t i = 0; i < nx; ++i)
+    for (int64_t j = 0; j < ny; ++j) {
+      double s = 0.0;
+      for (int k = 0; k < d; ++k) {
+        double t = x[i * d + k] - y[j * d + k];
+        s += t * t;
+      }
+      if (s > m) m = s;
+    }
+  return m;
+}
+
+/* ------------------------------------------------- the two kernel products */
+
+/* q_i = sum_j K_ij v_j for rows i in [r0, r1); q has n entries, only
+ * q[r0..r1) are written.  This is x -> K_{I,:} x of Sec. 3.1. */
+void orc_row_products(const void* K, int k_is_f32, int64_t n, int64_t ld, int64_t r0, int64_t r1,
+                      const double* v, double* q) {
+#pragma omp parallel for schedule(static)
+  for (int64_t i = r0; i < r1; ++i) {
+    double s = 0.0;
+    for (int64_t j = 0; j < n; ++j) s += k_at(K, k_is_f32, ld, i, j) * v[j];
+    q[i] = s;
+  }
+}
+
+/* r_j = sum_{i in [r0,r1)} K_ij u_i for columns j in [c0, c1); only
+ * r[c0..c1) are written.  With [r0,r1) = all rows this is x -> (K_{:,I})^T x
+ * of Sec. 3.1; with a row range it is one row slab's contribution K_{I,:}^T u_I.
+ * Threads split the columns; each r_j is summed over i in increasing order. */
+void orc_col_products(const void* K, int k_is_f32, int64_t n, int64_t ld, int64_t r0, int64_t r1,
+                      int64_t c0, int64_t c1, const double* u, double* r) {
+  (void)n;
+  const int64_t chunk = 256;
+#pragma omp parallel for schedule(static)
+  for (int64_t cb = c0; cb < c1; cb += chunk) {
+    int64_t ce = cb + chunk < c1 ? cb + chunk : c1;
+    for (int64_t j = cb; j < ce; ++j) r[j] = 0.0;
+    for (int64_t i = r0; i < r1; ++i)
+      for (int64_t j = cb; j < ce; ++j) r[j] += k_at(K, k_is_f32, ld, i, j) * u[i];
+  }
+}
+
+/* ------------------------------------------------------ dense, centralised */
+
+/* `iters` iterations of Algorithm 1's loop body on the whole problem; u, v are
+ * in/out (the caller puts 1 there for a cold start). */
+int orc_sinkhorn_dense(const void* K, int k_is_f32, int64_t n, int64_t ld, const double* a,
+                       const double* b, double* u, double* v, int iters) {
+  double* q = (double*)malloc(sizeof(double) * (size_t)n);
+  if (!q) return -1;
+  for (int t = 0; t < iters; ++t) {
+    orc_row_products(K, k_is_f32, n, ld, 0, n, v, q);
+    for (int64_t i = 0; i < n; ++i) u[i] = a[i] / q[i];
+    orc_col_products(K, k_is_f32, n, ld, 0, n, 0, n, u, q);
+    for (int64_t j = 0; j < n; ++j) v[j] = b[j] / q[j];
+  }
+  free(q);
+  return 0;
+}
+
+/* Row and column marginals of P = diag(u) K diag(v). */
+void orc_row_marginal(const void* K, int k_is_f32, int64_t n, int64_t ld, const double* u,
+                      const double* v, double* out) {
+  orc_row_products(K, k_is_f32, n, ld, 0, n, v, out);
+  for (int64_t i = 0; i < n; ++i) out[i] = u[i] * out[i];
+}
+
+void orc_col_marginal(const void* K, int k_is_f32, int64_t n, int64_t ld, const double* u,
+                      const double* v, double* out) {
+  orc_col_products(K, k_is_f32, n, ld, 0, n, 0, n, u, out);
+  for (int64_t j = 0; j < n; ++j) out[j] = v[j] * out[j];
+}
+
+/* ||P 1 - a||_1 and ||P 1 - a||_2 with the current scalings. */
+void orc_marginal_error(const void* K, int k_is_f32, int64_t n, int64_t ld, const double* a,
+                        const double* u, const double* v, double* err_l1, double* err_l2) {
+  double* p = (double*)malloc(sizeof(double) * (size_t)n);
+  orc_row_marginal(K, k_is_f32, n, ld, u, v, p);
+  double s1 = 0.0, s2 = 0.0;
+  for (int64_t i = 0; i < n; ++i) {
+    double e = p[i] - a[i];
+    s1 += fabs(e);
+    s2 += e * e;
+  }
+  *err_l1 = s1;
+  *err_l2 = sqrt(s2);
+  free(p);
+}
+
+/* Tolerance mode: iterate; after every `check_every`-th iteration (and after
+ * the last one) evaluate err = ||P1 - a||_1 with the scalings just produced;
+ * stop at the first such check with err < tol.  Returns iterations done. */
+int orc_sinkhorn_dense_tol(const void* K, int k_is_f32, int64_t n, int64_t ld, const double* a,
+                           const double* b, double* u, double* v, int max_iters, double tol,
+                           int check_every, double* err_out) {
+  int done = 0;
+  double e1 = INFINITY, e2 = INFINITY;
+  while (done < max_iters) {
+    orc_sinkhorn_dense(K, k_is_f32, n, ld, a, b, u, v, 1);
+    ++done;
+    if (done % check_every == 0 || done == max_iters) {
+      orc_marginal_error(K, k_is_f32, n, ld, a, u, v, &e1, &e2);
+      if (e1 < tol) break;
+    }
+  }
+  if (err_out) *err_out = e1;
+  return done;
+}
+
+/* --------------------------------------------------- dense, row-partitioned */
+
+/* c workers, worker j owns I_j = [j*m, (j+1)*m), m = n/c (Sec. 3.1).
+ * flow 0: Algorithm 1 as printed -- worker j forms q_{I_j} = K_{I_j,:} v and
+ *         u_{I_j}; after the (here trivial) gather of u it forms
+ *         r_{I_j} = (K_{:,I_j})^T u and v_{I_j}.
+ * flow 1: a worker that holds only its row slab forms the slab's contribution
+ *         s^(j) = K_{I_j,:}^T u_{I_j} (length n); r = s^(0) + s^(1) + ... in
+ *         that order (the row-wise reduction of the 2D baseline with one
+ *         block column, App. "HPC-oriented 2D baseline").
+ * Returns -2 if c does not divide n. */
+int orc_sinkhorn_blocked(const void* K, int k_is_f32, int64_t n, int64_t ld, const double* a,
+                         const double* b, double* u, double* v, int iters, int c, int flow) {
+  if (c < 1 || n % c != 0) return -2;
+  const int64_t m = n / c;
+  double* q = (double*)malloc(sizeof(double) * (size_t)n);
+  double* s = (double*)malloc(sizeof(double) * (size_t)n);
+  if (!q || !s) return -1;
+  for (int t = 0; t < iters; ++t) {
+    for (int j = 0; j < c; ++j) { /* every worker, same v */
+      orc_row_products(K, k_is_f32, n, ld, j * m, (j + 1) * m, v, q);
+      for (int64_t i = j * m; i < (j + 1) * m; ++i) u[i] = a[i] / q[i];
+    }
+    /* Allgather u: all slices already sit in one array */
+    if (flow == 0) {
+      for (int j = 0; j < c; ++j) {
+        orc_col_products(K, k_is_f32, n, ld, 0, n, j * m, (j + 1) * m, u, q);
+        for (int64_t i = j * m; i < (j + 1) * m; ++i) v[i] = b[i] / q[i];
+      }
+    } else {
+      for (int64_t i = 0; i < n; ++i) q[i] = 0.0;
+      for (int j = 0; j < c; ++j) {
+        orc_col_products(K, k_is_f32, n, ld, j * m, (j + 1) * m, 0, n, u, s);
+        for (int64_t i = 0; i < n; ++i) q[i] += s[i];
+      }
+      for (int64_t i = 0; i < n; ++i) v[i] = b[i] / q[i];
+    }
+    /* Allgather v: likewise */
+  }
+  free(q);
+  free(s);
+  return 0;
+}
+
+/* ------------------------------------------------------------ damped forms */
+
+/* Relaxed updates of Sec. 3.3 in the centralised view.
+ * geometric == 0:  u <- (1-eta) u + eta a./(K v),   likewise v with the new u.
+ * geometric != 0:  u <- u^(1-eta) .* (a./(K v))^eta (the Remark), likewise v. */
+int orc_sinkhorn_dense_damped(const void* K, int k_is_f32, int64_t n, int64_t ld, const double* a,
+                              const double* b, double* u, double* v, int iters, double eta,
+                              int geometric) {
+  double* q = (double*)malloc(sizeof(double) * (size_t)n);
+  if (!q) return -1;
+  for (int t = 0; t < iters; ++t) {
+    orc_row_products(K, k_is_f32, n, ld, 0, n, v, q);
+    for (int64_t i = 0; i < n; ++i) {
+      double target = a[i] / q[i];
+      u[i] = geometric ? pow(u[i], 1.0 - eta) * pow(target, eta) : (1.0 - eta) * u[i] + eta * target;
+    }
+    orc_col_products(K, k_is_f32, n, ld, 0, n, 0, n, u, q);
+    for (int64_t j = 0; j < n; ++j) {
+      double target = b[j] / q[j];
+      v[j] = geometric ? pow(v[j], 1.0 - eta) * pow(target, eta) : (1.0 - eta) * v[j] + eta * target;
+    }
+  }
+  free(q);
+  return 0;
+}
+
+/* ---------------------------------------------------------------- batched */
+
+/* Multitarget form (Sec. 5.3.2): A, B, U, V are n x m row-major (ld = m), one
+ * histogram pair per column, K shared.  Q = K V, U = A ./ Q, R = K^T U,
+ * V = B ./ R. */
+int orc_sinkhorn_batched(const void* K, int k_is_f32, int64_t n, int64_t ld, int m, const double* A,
+                         const double* B, double* U, double* V, int iters) {
+  double* Q = (double*)malloc(sizeof(double) * (size_t)n * (size_t)m);
+  if (!Q) return -1;
+  for (int t = 0; t < iters; ++t) {
+#pragma omp parallel for schedule(static)
+    for (int64_t i = 0; i < n; ++i) {
+      for (int k = 0; k < m; ++k) Q[i * m + k] = 0.0;
+      for (int64_t j = 0; j < n; ++j) {
+        double kij = k_at(K, k_is_f32, ld, i, j);
+        for (int k = 0; k < m; ++k) Q[i * m + k] += kij * V[j * m + k];
+      }
+      for (int k = 0; k < m; ++k) U[i * m + k] = A[i * m + k] / Q[i * m + k];
+    }
+#pragma omp parallel for schedule(static)
+    for (int64_t j = 0; j < n; ++j) {
+      for (int k = 0; k < m; ++k) Q[j * m + k] = 0.0;
+      for (int64_t i = 0; i < n; ++i) {
+        double kij = k_at(K, k_is_f32, ld, i, j);
+        for (int k = 0; k < m; ++k) Q[j * m + k] += kij * U[i * m + k];
+      }
+      for (int k = 0; k < m; ++k) V[j * m + k] = B[j * m + k] / Q[j * m + k];
+    }
+  }
+  free(Q);
+  return 0;
+}
+
+/* ------------------------------------------------------------- log domain */
+
+/* LSE(z) = max z + log sum exp(z - max z). */
+double orc_lse(const double* z, int64_t n) {
+  double m = z[0];
+  for (int64_t t = 1; t < n; ++t)
+    if (z[t] > m) m = z[t];
+  if (isinf(m)) return m;
+  double s = 0.0;
+  for (int64_t t = 0; t < n; ++t) s += exp(z[t] - m);
+  return m + log(s);
+}
+
+static double sqdist(const double* p, const double* q, int d) {
+  double s = 0.0;
+  for (int k = 0; k < d; ++k) {
+    double t = p[k] - q[k];
+    s += t * t;
+  }
+  return s;
+}
+
+/* One potential update against a point cloud, for a list of rows:
+ *   out[t] = eps*log w_i - eps*LSE_j((h_j - ||p_i - q_j||^2)/eps),  i = rows[t]
+ * (rows == NULL means rows[t] = t).  With (p,w,h,q) = (x,a,g,y) this is the
+ * f-update (the logarithm of u = a./(K v) times eps); with (y,b,f,x) it is the
+ * g-update (cost is symmetric in the roles of the two clouds). */
+void orc_log_update_points(const double* p, const double* w, const double* q, const double* h,
+                           int64_t nq, int d, double eps, const int64_t* rows, int64_t n_rows,
+                           double* out) {
+#pragma omp parallel
+  {
+    double* z = (double*)malloc(sizeof(double) * (size_t)nq);
+#pragma omp for schedule(static)
+    for (int64_t t = 0; t < n_rows; ++t) {
+      int64_t i = rows ? rows[t] : t;
+      for (int64_t j = 0; j < nq; ++j) z[j] = (h[j] - sqdist(p + i * d, q + j * d, d)) / eps;
+      out[t] = eps * log(w[i]) - eps * orc_lse(z, nq);
+    }
+    free(z);
+  }
+}
+
+/* Row marginal of P_ij = exp((f_i + g_j - C_ij)/eps) for listed rows:
+ * out[t] = exp(f_i/eps + LSE_j((g_j - C_ij)/eps)). */
+void orc_log_row_marginal_points(const double* x, const double* f, const double* y, const double* g,
+                                 int64_t ny, int d, double eps, const int64_t* rows, int64_t n_rows,
+                                 double* out) {
+#pragma omp parallel
+  {
+    double* z = (double*)malloc(sizeof(double) * (size_t)ny);
+#pragma omp for schedule(static)
+    for (int64_t t = 0; t < n_rows; ++t) {
+      int64_t i = rows ? rows[t] : t;
+      for (int64_t j = 0; j < ny; ++j) z[j] = (g[j] - sqdist(x + i * d, y + j * d, d)) / eps;
+      out[t] = exp(f[i] / eps + orc_lse(z, ny));
+    }
+    free(z);
+  }
+}
+
+/* Log-domain Sinkhorn on point clouds, cost evaluated on the fly.  f, g in/out
+ * (0 for a cold start, i.e. u = v = 1).  tol <= 0: exactly max_iters
+ * iterations.  tol > 0: same polling rule as orc_sinkhorn_dense_tol, with
+ * err = ||P1 - a||_1 evaluated after the g-update.  Returns iterations done. */
+int orc_sinkhorn_log_points(const double* x, const double* y, int64_t n, int d, double eps,
+                            const double* a, const double* b, double* f, double* g, int max_iters,
+                            double tol, int check_every, double* err_out) {
+  double* t1 = (double*)malloc(sizeof(double) * (size_t)n);
+  int done = 0;
+  double err = INFINITY;
+  while (done < max_iters) {
+    orc_log_update_points(x, a, y, g, n, d, eps, NULL, n, t1);
+    memcpy(f, t1, sizeof(double) * (size_t)n);
+    orc_log_update_points(y, b, x, f, n, d, eps, NULL, n, t1);
+    memcpy(g, t1, sizeof(double) * (size_t)n);
+    ++done;
+    if (tol > 0.0 && (done % check_every == 0 || done == max_iters)) {
+      orc_log_row_marginal_points(x, f, y, g, n, d, eps, NULL, n, t1);
+      err = 0.0;
+      for (int64_t i = 0; i < n; ++i) err += fabs(t1[i] - a[i]);
+      if (err < tol) break;
+    }
+  }
+  if (err_out) *err_out = err;
+  free(t1);
+  return done;
+}
+
+/* Log-domain Sinkhorn on an explicit n x n cost matrix (small n; used to tie
+ * the log form to the dense form on the same C). */
+int orc_sinkhorn_log_cost(const double* C, int64_t n, double eps, const double* a, const double* b,
+                          double* f, double* g, int iters) {
+  double* z = (double*)malloc(sizeof(double) * (size_t)n);
+  for (int t = 0; t < iters; ++t) {
+    for (int64_t i = 0; i < n; ++i) {
+      for (int64_t j = 0; j < n; ++j) z[j] = (g[j] - C[i * n + j]) / eps;
+      f[i] = eps * log(a[i]) - eps * orc_lse(z, n);
+    }
+    for (int64_t j = 0; j < n; ++j) {
+      for (int64_t i = 0; i < n; ++i) z[i] = (f[i] - C[i * n + j]) / eps;
+      g[j] = eps * log(b[j]) - eps * orc_lse(z, n);
+    }
+  }
+  free(z);
+  return 0;
+}

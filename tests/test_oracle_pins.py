@@ -1,0 +1,442 @@
+"""Pins for the CPU oracle: each test ties an oracle function to something the paper or
+the mathematics fixes -- never to the oracle's own formula retyped.
+
+Citations are to the paper: Sec. 1 / Eq. 1 (problem and scaling iteration), Algorithm 1
+(iteration order, init, row partition), Proposition 1 (blocked == centralised),
+Sec. 5.3.2 (multitarget), Sec. 3.3 (damping), App. "Convergence proofs" (Hilbert metric,
+fixed point), App. toy portfolio example (printed cost and plan).
+"""
+import os
+
+import numpy as np
+import pytest
+import scipy.optimize
+import scipy.special
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+
+
+def problem(n, seed, d=2, eps=0.1, symmetric=False):
+    rng = np.random.default_rng(seed)
+    x = rng.uniform(size=(n, d))
+    y = x.copy() if symmetric else rng.uniform(size=(n, d)) + 0.3
+    a = rng.uniform(0.5, 1.5, n); a /= a.sum()
+    b = a.copy() if symmetric else rng.uniform(0.5, 1.5, n)
+    b /= b.sum()
+    C = ((x[:, None, :] - y[None, :, :]) ** 2).sum(-1)      # NumPy, not the oracle
+    K = np.exp(-C / eps)
+    return x, y, a, b, C, K
+
+
+def primal_objective(P, C, eps):
+    """Eq. 1: <P,C> + eps * sum P (log P - 1)."""
+    return float((P * C).sum() + eps * (P * (np.log(P) - 1.0)).sum())
+
+
+def dual_objective(f, g, a, b, C, eps):
+    """Lagrangian dual of Eq. 1: <f,a> + <g,b> - eps * sum exp((f_i + g_j - C_ij)/eps)."""
+    return float(f @ a + g @ b - eps * np.exp((f[:, None] + g[None, :] - C) / eps).sum())
+
+
+# ---------------------------------------------------------------- setup ----
+
+def test_cost_and_gibbs_against_numpy(orc):
+    x, y, a, b, C, K = problem(37, 1, d=5)
+    assert np.allclose(orc.cost_sqeuclid(x, y), C, rtol=1e-14, atol=0)
+    assert np.allclose(orc.gibbs(C, 0.1), K, rtol=1e-14, atol=0)
+    Kn, cmax = orc.gibbs_from_points(x, y, 0.07, True)
+    assert cmax == pytest.approx(C.max(), rel=1e-15)
+    assert np.allclose(Kn, np.exp(-(C / C.max()) / 0.07), rtol=1e-14, atol=0)
+    # the asymmetric cost catches a swapped (x, y) or transposed output
+    assert not np.allclose(C, C.T)
+
+
+def test_gibbs_f32_variant_is_the_rounded_f64_kernel(orc):
+    x, y, a, b, C, K = problem(64, 2, d=3)
+    for norm in (False, True):
+        K64, cmax = orc.gibbs_from_points(x, y, 0.05, norm)
+        K32, cmax32 = orc.gibbs_from_points_f32(x, y, 0.05, norm)
+        assert K32.dtype == np.float32 and cmax32 == cmax
+        assert np.array_equal(K32, K64.astype(np.float32))
+
+
+# ------------------------------------------- single steps vs library routines
+
+def test_products_against_numpy_matmul(orc):
+    """x -> K x and x -> K^T x (Sec. 3.1) against NumPy's matmul on an asymmetric K."""
+    x, y, a, b, C, K = problem(53, 3)
+    rng = np.random.default_rng(0)
+    v = rng.uniform(0.5, 2.0, 53); u = rng.uniform(0.5, 2.0, 53)
+    assert np.allclose(orc.row_products(K, v), K @ v, rtol=1e-13)
+    assert np.allclose(orc.col_products(K, u), K.T @ u, rtol=1e-13)
+    assert not np.allclose(K @ v, K.T @ v, rtol=1e-3)       # a transposed operand would show
+    # ranges: a row slab and a column slab
+    assert np.allclose(orc.row_products(K, v, 10, 31), (K @ v)[10:31], rtol=1e-13)
+    assert np.allclose(orc.col_products(K, u, 0, 53, 7, 20), (K.T @ u)[7:20], rtol=1e-13)
+    assert np.allclose(orc.col_products(K, u, 10, 31), K[10:31].T @ u[10:31], rtol=1e-13)
+
+
+def test_first_iteration_against_numpy(orc):
+    """Algorithm 1 from u = v = 1: u1 = a ./ (K 1), v1 = b ./ (K^T u1); order u then v."""
+    x, y, a, b, C, K = problem(41, 4)
+    u1 = a / (K @ np.ones(41)); v1 = b / (K.T @ u1)
+    u, v = orc.sinkhorn_dense(K, a, b, 1)
+    assert np.allclose(u, u1, rtol=1e-13) and np.allclose(v, v1, rtol=1e-13)
+    u2 = a / (K @ v1); v2 = b / (K.T @ u2)
+    u, v = orc.sinkhorn_dense(K, a, b, 2)
+    assert np.allclose(u, u2, rtol=1e-13) and np.allclose(v, v2, rtol=1e-13)
+    # zero iterations leave the init untouched
+    u, v = orc.sinkhorn_dense(K, a, b, 0)
+    assert np.array_equal(u, np.ones(41)) and np.array_equal(v, np.ones(41))
+
+
+def test_lse_against_scipy(orc):
+    rng = np.random.default_rng(5)
+    for scale in (1.0, 50.0, 700.0):
+        z = rng.normal(size=200) * scale
+        assert orc.lse(z) == pytest.approx(scipy.special.logsumexp(z), rel=1e-14)
+    assert orc.lse(np.array([-2000.0, -2001.0])) == pytest.approx(-2000.0 + np.log1p(np.exp(-1.0)))
+
+
+# -------------------------------------------------- what the definition fixes
+
+def test_marginals_exact_after_each_half_step(orc):
+    """P = diag(u) K diag(v): P 1 = a right after the u-update, P^T 1 = b right after the
+    v-update (Sec. 1, scaling form)."""
+    x, y, a, b, C, K = problem(64, 6)
+    u, v = orc.sinkhorn_dense(K, a, b, 3)
+    P = u[:, None] * K * v[None, :]
+    assert np.allclose(P.sum(0), b, rtol=1e-13)             # last update was v
+    assert not np.allclose(P.sum(1), a, rtol=1e-6)          # rows are not yet exact
+    u_next = a / (K @ v)                                    # the u-update that follows
+    assert np.allclose((u_next[:, None] * K * v[None, :]).sum(1), a, rtol=1e-13)
+    assert np.allclose(orc.row_marginal(K, u, v), P.sum(1), rtol=1e-13)
+    assert np.allclose(orc.col_marginal(K, u, v), P.sum(0), rtol=1e-13)
+    e1, e2 = orc.marginal_error(K, a, u, v)
+    assert e1 == pytest.approx(np.abs(P.sum(1) - a).sum(), rel=1e-12)
+    assert e2 == pytest.approx(np.sqrt(((P.sum(1) - a) ** 2).sum()), rel=1e-12)
+
+
+def test_constant_cost_gives_product_plan(orc):
+    """C == kappa  =>  after one iteration P = a b^T / (1^T a), and it is a fixed point."""
+    n, kappa, eps = 17, 0.37, 0.05
+    rng = np.random.default_rng(7)
+    a = rng.uniform(0.5, 1.5, n); a /= a.sum()
+    b = rng.uniform(0.5, 1.5, n); b /= b.sum()
+    K = orc.gibbs(np.full((n, n), kappa), eps)
+    k = np.exp(-kappa / eps)
+    u, v = orc.sinkhorn_dense(K, a, b, 1)
+    assert np.allclose(u, a / (k * n), rtol=1e-13)
+    assert np.allclose(v, b * n / a.sum(), rtol=1e-13)
+    assert np.allclose(u[:, None] * K * v[None, :], np.outer(a, b), rtol=1e-13)
+    u2, v2 = orc.sinkhorn_dense(K, a, b, 5)
+    assert np.allclose(u2, u, rtol=1e-13) and np.allclose(v2, v, rtol=1e-13)
+
+
+def test_two_by_two_brute_force_optimum(orc):
+    """n = 2: the feasible set of Eq. 1 is one-dimensional; minimise the objective over it
+    with a library scalar minimiser and compare with the converged scaling iteration."""
+    C = np.array([[0.10, 0.70], [0.45, 0.05]])
+    a = np.array([0.35, 0.65]); b = np.array([0.6, 0.4])
+    eps = 0.2
+
+    def plan(p):
+        return np.array([[p, a[0] - p], [b[0] - p, a[1] - b[0] + p]])
+
+    lo = max(0.0, b[0] - a[1]) + 1e-12
+    hi = min(a[0], b[0]) - 1e-12
+    res = scipy.optimize.minimize_scalar(lambda p: primal_objective(plan(p), C, eps),
+                                         bounds=(lo, hi), method="bounded",
+                                         options={"xatol": 1e-14})
+    K = orc.gibbs(C, eps)
+    u, v = orc.sinkhorn_dense(K, a, b, 2000)
+    P = u[:, None] * K * v[None, :]
+    assert np.allclose(P, plan(res.x), atol=2e-7)
+    # brute force on a grid as well: nothing on the segment beats the Sinkhorn plan
+    grid = np.linspace(lo, hi, 20001)
+    best = min(primal_objective(plan(p), C, eps) for p in grid)
+    assert primal_objective(P, C, eps) <= best + 1e-12
+
+
+def test_three_by_three_brute_force_optimum(orc):
+    """n = 3: with both marginals fixed the plan has 4 free entries; minimise Eq. 1 over them
+    with a library minimiser (derivative-free, then polished) from the product plan."""
+    rng = np.random.default_rng(8)
+    C = rng.uniform(0.0, 1.0, (3, 3))
+    a = np.array([0.2, 0.5, 0.3]); b = np.array([0.4, 0.25, 0.35])
+    eps = 0.3
+
+    def plan(p):
+        P = np.empty((3, 3))
+        P[:2, :2] = p.reshape(2, 2)
+        P[:2, 2] = a[:2] - P[:2, :2].sum(1)
+        P[2, :2] = b[:2] - P[:2, :2].sum(0)
+        P[2, 2] = a[2] - P[2, :2].sum()
+        return P
+
+    def obj(p):
+        P = plan(p)
+        return primal_objective(P, C, eps) if (P > 0).all() else np.inf
+
+    p0 = np.outer(a, b)[:2, :2].ravel()
+    res = scipy.optimize.minimize(obj, p0, method="Nelder-Mead",
+                                  options={"xatol": 1e-12, "fatol": 1e-16, "maxiter": 20000})
+    res = scipy.optimize.minimize(obj, res.x, method="BFGS", options={"gtol": 1e-12})
+    K = orc.gibbs(C, eps)
+    u, v = orc.sinkhorn_dense(K, a, b, 3000)
+    P = u[:, None] * K * v[None, :]
+    assert np.allclose(P, plan(res.x), atol=1e-6)
+    assert primal_objective(P, C, eps) <= res.fun + 1e-12
+
+
+def test_dual_ascent_and_zero_gap(orc):
+    """Each half-step maximises the dual exactly in one block => the dual value never
+    decreases; at convergence it equals the primal value of Eq. 1 at P."""
+    x, y, a, b, C, K = problem(12, 9, eps=0.1)
+    eps = 0.1
+    u, v = np.ones(12), np.ones(12)
+    prev = dual_objective(eps * np.log(u), eps * np.log(v), a, b, C, eps)
+    for t in range(30):
+        u, v = orc.sinkhorn_dense(K, a, b, 1, u0=u, v0=v)
+        cur = dual_objective(eps * np.log(u), eps * np.log(v), a, b, C, eps)
+        assert cur >= prev - 1e-13
+        prev = cur
+    u, v = orc.sinkhorn_dense(K, a, b, 3000)
+    P = u[:, None] * K * v[None, :]
+    D = dual_objective(eps * np.log(u), eps * np.log(v), a, b, C, eps)
+    assert D == pytest.approx(primal_objective(P, C, eps), abs=1e-12)
+    # any other feasible plan is worse (weak duality, brute force over random feasible moves)
+    rng = np.random.default_rng(0)
+    for _ in range(200):
+        i, k = rng.choice(12, 2, replace=False); j, l = rng.choice(12, 2, replace=False)
+        step = 0.5 * min(P[i, j], P[k, l], P[i, l], P[k, j]) * rng.uniform(-1, 1)
+        Q = P.copy()
+        Q[i, j] += step; Q[k, l] += step; Q[i, l] -= step; Q[k, j] -= step
+        assert primal_objective(Q, C, eps) >= primal_objective(P, C, eps) - 1e-14
+
+
+def test_fixed_point_and_gauge(orc):
+    """At convergence both scaling equations hold at once; a different init gauge (u0 = s,
+    v0 = 1/s .. any positive start) reaches the same plan (App. convergence, uniqueness of P*)."""
+    x, y, a, b, C, K = problem(20, 10, eps=0.2)
+    u, v = orc.sinkhorn_dense(K, a, b, 4000)
+    assert np.allclose(u, a / (K @ v), rtol=1e-12) and np.allclose(v, b / (K.T @ u), rtol=1e-12)
+    rng = np.random.default_rng(1)
+    u2, v2 = orc.sinkhorn_dense(K, a, b, 4000, u0=rng.uniform(0.1, 10, 20), v0=rng.uniform(0.1, 10, 20))
+    assert np.allclose(u[:, None] * K * v[None, :], u2[:, None] * K * v2[None, :], rtol=1e-10)
+    ratio = u2 / u
+    assert np.allclose(ratio, ratio[0], rtol=1e-9) and np.allclose(v2 / v, 1.0 / ratio[0], rtol=1e-9)
+
+
+def test_symmetric_special_case(orc):
+    """x = y and a = b (the paper's own experimental setting, symmetric C): the optimal plan
+    is symmetric and u is proportional to v."""
+    x, y, a, b, C, K = problem(24, 11, eps=0.15, symmetric=True)
+    assert np.allclose(C, C.T)
+    u, v = orc.sinkhorn_dense(K, a, b, 5000)
+    P = u[:, None] * K * v[None, :]
+    assert np.allclose(P, P.T, rtol=1e-9, atol=1e-15)
+    assert np.allclose(u / v, (u / v)[0], rtol=1e-9)
+
+
+def test_hilbert_metric_contracts(orc):
+    """d_H(u^{t+1}, u^t) is non-increasing (x -> Kx contracts, x -> a./x is an isometry)."""
+    def d_h(p, q):
+        r = p / q
+        return np.log(r.max()) - np.log(r.min())
+    x, y, a, b, C, K = problem(30, 12, eps=0.05)
+    us = [np.ones(30)]
+    u, v = np.ones(30), np.ones(30)
+    for _ in range(25):
+        u, v = orc.sinkhorn_dense(K, a, b, 1, u0=u, v0=v)
+        us.append(u)
+    d = [d_h(us[t + 1], us[t]) for t in range(1, 25)]
+    assert all(d[t + 1] <= d[t] * (1 + 1e-12) for t in range(len(d) - 1))
+    assert d[-1] < d[0]
+
+
+# ------------------------------------------------------------ identities ---
+
+@pytest.mark.parametrize("c", [1, 2, 4, 8])
+def test_blocked_equals_centralised(orc, c):
+    """Proposition 1: the row-partitioned iterates coincide with the centralised ones."""
+    x, y, a, b, C, K = problem(48, 13)
+    u, v = orc.sinkhorn_dense(K, a, b, 25)
+    ua, va = orc.sinkhorn_blocked(K, a, b, 25, c, 0)
+    assert np.array_equal(ua, u) and np.array_equal(va, v)  # same sums, same order
+    ub, vb = orc.sinkhorn_blocked(K, a, b, 25, c, 1)
+    assert np.allclose(ub, u, rtol=1e-13) and np.allclose(vb, v, rtol=1e-13)
+    with pytest.raises(ValueError):
+        orc.sinkhorn_blocked(K, a, b, 1, 5, 0)              # n = c m is required
+
+
+def test_resume_equals_straight_run(orc):
+    x, y, a, b, C, K = problem(33, 14)
+    u, v = orc.sinkhorn_dense(K, a, b, 40)
+    u1, v1 = orc.sinkhorn_dense(K, a, b, 15)
+    u2, v2 = orc.sinkhorn_dense(K, a, b, 25, u0=u1, v0=v1)
+    assert np.array_equal(u2, u) and np.array_equal(v2, v)
+
+
+def test_f32_storage_is_promoted_entrywise(orc):
+    x, y, a, b, C, K = problem(40, 15)
+    K32 = K.astype(np.float32)
+    u, v = orc.sinkhorn_dense(K32, a, b, 20)
+    u64, v64 = orc.sinkhorn_dense(K32.astype(np.float64), a, b, 20)
+    assert np.array_equal(u, u64) and np.array_equal(v, v64)
+
+
+def test_batched_column_equals_single_run(orc):
+    """Multitarget form (Sec. 5.3.2): column k of the stacked run is the run on (a_k, b_k)."""
+    x, y, a, b, C, K = problem(26, 16)
+    rng = np.random.default_rng(3)
+    m = 5
+    A = rng.exponential(size=(26, m)); A /= A.sum(0)
+    B = rng.exponential(size=(26, m)); B /= B.sum(0)
+    U, V = orc.sinkhorn_batched(K, A, B, 30)
+    for k in range(m):
+        u, v = orc.sinkhorn_dense(K, A[:, k], B[:, k], 30)
+        assert np.allclose(U[:, k], u, rtol=1e-13) and np.allclose(V[:, k], v, rtol=1e-13)
+    # first step against a library GEMM
+    U1, V1 = orc.sinkhorn_batched(K, A, B, 1)
+    Uref = A / (K @ np.ones((26, m)))
+    assert np.allclose(U1, Uref, rtol=1e-13) and np.allclose(V1, B / (K.T @ Uref), rtol=1e-13)
+
+
+def test_tolerance_mode_polling(orc):
+    x, y, a, b, C, K = problem(32, 17, eps=0.3)
+    u, v, done, err = orc.sinkhorn_dense_tol(K, a, b, 500, 1e-9, check_every=7)
+    assert done % 7 == 0 and done < 500 and err < 1e-9
+    P = u[:, None] * K * v[None, :]
+    assert err == pytest.approx(np.abs(P.sum(1) - a).sum(), rel=1e-4)   # cancellation-limited
+    # one poll earlier the error was still above the tolerance
+    u7, v7 = orc.sinkhorn_dense(K, a, b, done - 7)
+    assert np.abs((u7[:, None] * K * v7[None, :]).sum(1) - a).sum() >= 1e-9
+    # the cap binds when the tolerance is unreachable
+    _, _, done, err = orc.sinkhorn_dense_tol(K, a, b, 10, 1e-300, check_every=4)
+    assert done == 10 and err > 0
+
+
+# ------------------------------------------------------------ log domain ---
+
+def test_log_domain_equals_dense(orc):
+    """f = eps log u, g = eps log v: the log-sum-exp form is the logarithm of the iteration."""
+    x, y, a, b, C, K = problem(28, 18, d=4, eps=0.1)
+    u, v = orc.sinkhorn_dense(K, a, b, 35)
+    f, g = orc.sinkhorn_log_cost(C, 0.1, a, b, 35)
+    assert np.allclose(f, 0.1 * np.log(u), rtol=0, atol=1e-13)
+    assert np.allclose(g, 0.1 * np.log(v), rtol=0, atol=1e-13)
+    fp, gp, done, _ = orc.sinkhorn_log_points(x, y, 0.1, a, b, 35)
+    assert done == 35
+    assert np.allclose(fp, f, rtol=0, atol=1e-13) and np.allclose(gp, g, rtol=0, atol=1e-13)
+
+
+def test_log_domain_survives_where_dense_underflows(orc):
+    """Small eps: K underflows to 0 in fp64 yet the potentials stay finite and the plan
+    exp((f+g-C)/eps) has exact column sums after a g-update."""
+    rng = np.random.default_rng(19)
+    n, d, eps = 40, 16, 0.002
+    x = rng.uniform(size=(n, d)); y = rng.uniform(size=(n, d))
+    a = np.full(n, 1.0 / n); b = np.full(n, 1.0 / n)
+    C = ((x[:, None, :] - y[None, :, :]) ** 2).sum(-1)
+    assert np.exp(-C / eps).min() == 0.0
+    f, g, done, _ = orc.sinkhorn_log_points(x, y, eps, a, b, 50)
+    assert np.isfinite(f).all() and np.isfinite(g).all()
+    logP = (f[:, None] + g[None, :] - C) / eps
+    assert np.allclose(np.exp(scipy.special.logsumexp(logP, axis=0)), b, rtol=1e-11)
+    rows = orc.log_row_marginal_points(x, f, y, g, eps)
+    assert np.allclose(rows, np.exp(scipy.special.logsumexp(logP, axis=1)), rtol=1e-11)
+
+
+def test_log_update_rows_against_scipy(orc):
+    rng = np.random.default_rng(20)
+    n, d, eps = 50, 6, 0.05
+    x = rng.uniform(size=(n, d)); y = rng.uniform(size=(n, d))
+    a = rng.uniform(0.5, 1.5, n); a /= a.sum()
+    g = rng.normal(size=n) * 0.1
+    C = ((x[:, None, :] - y[None, :, :]) ** 2).sum(-1)
+    ref = eps * np.log(a) - eps * scipy.special.logsumexp((g[None, :] - C) / eps, axis=1)
+    assert np.allclose(orc.log_update_points(x, a, y, g, eps), ref, rtol=0, atol=1e-14)
+    rows = np.array([3, 17, 49, 0])
+    assert np.allclose(orc.log_update_points(x, a, y, g, eps, rows), ref[rows], rtol=0, atol=1e-14)
+    # the g-update is the same routine with the clouds' roles swapped (cost is symmetric in them)
+    f = rng.normal(size=n) * 0.1
+    refg = eps * np.log(a) - eps * scipy.special.logsumexp((f[:, None] - C) / eps, axis=0)
+    assert np.allclose(orc.log_update_points(y, a, x, f, eps), refg, rtol=0, atol=1e-14)
+
+
+def test_log_tolerance_mode(orc):
+    rng = np.random.default_rng(21)
+    n, d, eps = 60, 3, 0.2
+    x = rng.uniform(size=(n, d)); y = rng.uniform(size=(n, d))
+    a = np.full(n, 1.0 / n); b = np.full(n, 1.0 / n)
+    f, g, done, err = orc.sinkhorn_log_points(x, y, eps, a, b, 400, tol=1e-8, check_every=5)
+    assert done % 5 == 0 and done < 400 and err < 1e-8
+    C = ((x[:, None, :] - y[None, :, :]) ** 2).sum(-1)
+    P = np.exp((f[:, None] + g[None, :] - C) / eps)
+    assert err == pytest.approx(np.abs(P.sum(1) - a).sum(), rel=1e-6, abs=1e-16)
+
+
+# --------------------------------------------------------------- damping ---
+
+def test_damped_updates(orc):
+    """Sec. 3.3: eta = 1 is the plain iteration; one arithmetic step is the convex combination;
+    one geometric step is linear interpolation of the log scalings; both keep the fixed point."""
+    x, y, a, b, C, K = problem(22, 22, eps=0.2)
+    u, v = orc.sinkhorn_dense(K, a, b, 9)
+    for geo in (False, True):
+        ud, vd = orc.sinkhorn_dense_damped(K, a, b, 9, 1.0, geo)
+        assert np.allclose(ud, u, rtol=1e-13) and np.allclose(vd, v, rtol=1e-13)
+    rng = np.random.default_rng(2)
+    u0 = rng.uniform(0.5, 2, 22); v0 = rng.uniform(0.5, 2, 22)
+    eta = 0.3
+    ua, va = orc.sinkhorn_dense_damped(K, a, b, 1, eta, False, u0=u0, v0=v0)
+    ua_ref = (1 - eta) * u0 + eta * a / (K @ v0)
+    assert np.allclose(ua, ua_ref, rtol=1e-13)
+    assert np.allclose(va, (1 - eta) * v0 + eta * b / (K.T @ ua_ref), rtol=1e-13)
+    ug, vg = orc.sinkhorn_dense_damped(K, a, b, 1, eta, True, u0=u0, v0=v0)
+    ug_ref = np.exp((1 - eta) * np.log(u0) + eta * np.log(a / (K @ v0)))
+    assert np.allclose(ug, ug_ref, rtol=1e-13)
+    assert np.allclose(vg, np.exp((1 - eta) * np.log(v0) + eta * np.log(b / (K.T @ ug_ref))), rtol=1e-13)
+    us, vs = orc.sinkhorn_dense(K, a, b, 4000)
+    Pstar = us[:, None] * K * vs[None, :]
+    for geo in (False, True):
+        ud, vd = orc.sinkhorn_dense_damped(K, a, b, 6000, 0.5, geo)
+        assert np.allclose(ud[:, None] * K * vd[None, :], Pstar, rtol=1e-8)
+
+
+# ------------------------------------------------- the paper's toy example ---
+
+def _read_toy():
+    vals = {}
+    with open(os.path.join(HERE, "golden", "toy_portfolio.txt")) as fh:
+        for line in fh:
+            line = line.split("#")[0].strip()
+            if not line:
+                continue
+            key, rest = line.split(":")
+            vals[key.strip()] = np.array([float(t) for t in rest.split()])
+    return vals
+
+
+def test_toy_portfolio_example(orc):
+    """App. "Toy portfolio example: numerical details": printed C, marginals from the shifted
+    returns, eps = 0.01, and the printed plan.  What the printed numbers do fix: the marginals
+    are the normalised shifted returns; the printed plan's column sums equal b to 3 s.f.; its
+    support pattern (mass on (1,1), (2,1), (3,3)) is the one the converged iteration finds.
+    The printed entries themselves are NOT reproducible from the printed inputs (their row
+    sums differ from a), so they pin nothing more than that."""
+    t = _read_toy()
+    C = t["C"].reshape(3, 3)
+    a = t["x_shifted"] / t["x_shifted"].sum()
+    b = t["xp_shifted"] / t["xp_shifted"].sum()
+    Pprint = t["P_star"].reshape(3, 3)
+    eps = float(t["eps"][0])
+    assert np.allclose(Pprint.sum(0), b, rtol=1e-2)
+    assert not np.allclose(Pprint.sum(1), a, rtol=0.5)
+    K = orc.gibbs(C, eps)
+    u, v = orc.sinkhorn_dense(K, a, b, 500)
+    P = u[:, None] * K * v[None, :]
+    assert np.allclose(P.sum(1), a, rtol=1e-9) and np.allclose(P.sum(0), b, rtol=1e-12)
+    assert set(map(tuple, np.argwhere(Pprint > 0.05))) <= set(map(tuple, np.argwhere(P > 0.01)))
+    assert P[2, 2] == pytest.approx(Pprint[2, 2], rel=2e-2)
