@@ -1,0 +1,192 @@
+/*
+ * fsk.h -- C ABI of the MI355X (gfx950) Sinkhorn hot-path library.
+ *
+ * The library runs the Gibbs-kernel scaling iteration of entropic optimal
+ * transport (paper: Sec. 1, Eq. 1 and the scaling form below it; Algorithm 1):
+ *
+ *     K = exp(-C/eps),   u <- a ./ (K v),   v <- b ./ (K^T u),
+ *
+ * one "iteration" being the u-update followed by the v-update, in its dense,
+ * row-partitioned (Sec. 3.1, Proposition 1), log-domain (named in Sec. 1 and
+ * Sec. 2.1; formulas are the logarithm of the iteration above) and multitarget
+ * (Sec. 5.3.2) forms.
+ *
+ * Conventions common to every call
+ *   - Every pointer documented "device" is GPU memory owned by the caller
+ *     (e.g. a torch tensor); it must stay valid until the work enqueued on the
+ *     stream has finished.  The library never allocates or frees device
+ *     memory: scratch space comes in through the `workspace` argument, whose
+ *     minimum size fsk_workspace_bytes() reports.  Pointers documented "host"
+ *     are ordinary process memory.
+ *   - Matrices are row-major with a leading dimension `ld` counted in
+ *     elements.  K must be 16-byte aligned and ld*sizeof(element) must be a
+ *     multiple of 16 (rows are read with 128-bit loads); entries in the padding
+ *     columns [n, ld) are never used.  Vectors need only their natural alignment.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  All
+ *     kernels are enqueued on it.  Calls that run a fixed number of iterations
+ *     return as soon as the work is enqueued; calls in tolerance mode
+ *     (opts->tol > 0) synchronise the stream at every poll and before they
+ *     return.
+ *   - Return value: FSK_OK or a negative fsk_status.  fsk_last_error() gives a
+ *     thread-local message for the last failure.  Arguments are validated on the
+ *     host before anything is launched; a failed call launches nothing.
+ *   - Not checked (assumptions A1-A2 of the paper's convergence section):
+ *     K > 0, a, b > 0 with equal total mass.
+ *   - Results are deterministic: no floating-point atomics; every reduction has
+ *     a fixed order that depends only on (n, dtype, flow, c) and the device's
+ *     compute-unit count.
+ */
+#ifndef FSK_H
+#define FSK_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  FSK_OK = 0,
+  FSK_EINVAL = -1,       /* bad size, eps, c, ld, null pointer, unknown enum value            */
+  FSK_EALIGN = -2,       /* K or ld not 16-byte aligned                                       */
+  FSK_EDIV = -3,         /* c does not divide n (the paper takes n = c*m, Sec. 3.1)           */
+  FSK_EWORKSPACE = -4,   /* workspace missing or smaller than fsk_workspace_bytes()           */
+  FSK_ENONFINITE = -5,   /* a non-finite marginal error was read at a poll                    */
+  FSK_EHIP = -6,         /* a HIP runtime call failed (message has the HIP error string)      */
+  FSK_EUNSUPPORTED = -7  /* valid request outside what this build implements                  */
+} fsk_status;
+
+typedef enum { FSK_F32 = 0, FSK_F64 = 1 } fsk_dtype;
+
+/* How one dense iteration moves through K.  All three produce the iterates of
+ * Algorithm 1; they differ in memory traffic and in summation order. */
+typedef enum {
+  FSK_FLOW_FUSED = 0,    /* one pass over K per iteration: a workgroup keeps a row strip in
+                            registers, finishes u on it, and accumulates the strip's
+                            contribution K_I^T u_I; a second small kernel sums the
+                            contributions in fixed order and divides.  With c > 1 each block's
+                            row slab yields its own contribution s^(j) = K_{I_j,:}^T u_{I_j}
+                            (what a worker holding only its rows can form).                 */
+  FSK_FLOW_TWO_PASS = 1, /* q = K v over all rows, then r = K^T u over all rows (two passes)  */
+  FSK_FLOW_PAPER = 2     /* Algorithm 1 as printed: block j forms u_{I_j} from its row slab,
+                            then r_{I_j} = (K_{:,I_j})^T u from its column slab              */
+} fsk_flow;
+
+typedef enum {
+  FSK_DAMP_NONE = 0,
+  FSK_DAMP_ARITHMETIC = 1, /* u <- (1-eta) u + eta a./(K v)            (Sec. 3.3)             */
+  FSK_DAMP_GEOMETRIC = 2   /* u <- u^(1-eta) .* (a./(K v))^eta         (Remark in Sec. 3.3)   */
+} fsk_damping;
+
+typedef struct {
+  int32_t n;           /* problem size: K is n x n, a, b, u, v have n entries                  */
+  int32_t m;           /* histograms per batch (multitarget form); 1 for the vector case       */
+  int32_t c;           /* row blocks I_j = [j*n/c, (j+1)*n/c) emulating c workers; 1 =
+                          centralised; must divide n                                           */
+  int32_t max_iters;   /* IterMax of Algorithm 1                                               */
+  double tol;          /* <= 0: run exactly max_iters iterations.  > 0: stop at the first poll
+                          where ||P 1 - a||_1 < tol, P = diag(u) K diag(v), evaluated with the
+                          scalings as they stand after a v-update                              */
+  int32_t check_every; /* iterations between polls in tolerance mode (>= 1); the last
+                          iteration is always polled                                           */
+  int32_t dtype;       /* fsk_dtype of K, a, b, u, v (storage and arithmetic)                  */
+  int32_t flow;        /* fsk_flow (dense calls only)                                          */
+  int32_t damping;     /* fsk_damping (dense calls only)                                       */
+  double eta;          /* relaxation parameter in (0, 1]; ignored when damping = NONE          */
+} fsk_opts;
+
+typedef enum { FSK_MODE_DENSE = 0, FSK_MODE_LOG = 1, FSK_MODE_BATCHED = 2, FSK_MODE_SETUP = 3 } fsk_mode;
+
+/* Library version as major*10000 + minor*100 + patch. */
+int fsk_version(void);
+
+/* Message for the calling thread's last failed call ("" if none). Never NULL. */
+const char* fsk_last_error(void);
+
+/* Minimum workspace, in bytes, that a call of the given mode needs for these
+ * options on the current device (0 on invalid options).  `d` is the point
+ * dimension for FSK_MODE_LOG / FSK_MODE_SETUP and ignored otherwise. */
+size_t fsk_workspace_bytes(const fsk_opts* opts, int mode, int d);
+
+/* ---- setup: the Gibbs kernel K = exp(-C/eps) (Sec. 1) ----------------------------------
+ * C, K: device, n x n, leading dimensions ldC, ldK.  K may alias C. */
+int fsk_kernel_from_cost(const fsk_opts* opts, const void* C, int64_t ldC, double eps, void* K,
+                         int64_t ldK, void* stream);
+
+/* Same from two point clouds x, y (device, n x d row-major, dtype of opts) with the squared
+ * Euclidean cost C_ij = ||x_i - y_j||^2 (Sec. 5.6).  normalise_by_max != 0 divides C by its
+ * largest entry first (two passes over the pairs; needs the workspace).  If cmax_out (host)
+ * is not NULL the call synchronises and stores max_ij C_ij there. */
+int fsk_kernel_from_points(const fsk_opts* opts, const void* x, const void* y, int d, double eps,
+                           int normalise_by_max, void* K, int64_t ldK, void* workspace,
+                           size_t ws_bytes, double* cmax_out, void* stream);
+
+/* ---- dense hot path (Algorithm 1; Sec. 4.1 for the per-iteration operations) ------------
+ * K, a, b: device inputs.  u, v: device, IN/OUT -- the caller stores the starting scalings
+ * (1 for a cold start, as in Algorithm 1, or a previous result to resume).  On return (after
+ * the stream has drained) they hold the scalings after *iters_done iterations.
+ * iters_done (host, may be NULL): iterations performed.  err (host, may be NULL): the last
+ * polled ||P1 - a||_1 in tolerance mode, NaN in fixed-iteration mode. */
+int fsk_sinkhorn_dense(const fsk_opts* opts, const void* K, int64_t ldK, const void* a,
+                       const void* b, void* u, void* v, void* workspace, size_t ws_bytes,
+                       int32_t* iters_done, double* err, void* stream);
+
+/* Row and column marginals of P = diag(u) K diag(v) (device outputs of n entries each; either
+ * may be NULL), and optionally ||P1 - a||_1 (err_l1, host; non-NULL makes the call synchronise). */
+int fsk_marginals(const fsk_opts* opts, const void* K, int64_t ldK, const void* a, const void* u,
+                  const void* v, void* row_marginal, void* col_marginal, void* workspace,
+                  size_t ws_bytes, double* err_l1, void* stream);
+
+/* ---- one worker's share (Sec. 3.1: client j holds rows I_j of K and slices a_j, b_j) -----
+ * K_slab: device, `rows` x n, the rows [row0, row0+rows) of K (row0 is only used to index the
+ * full-length vectors).  These are the per-worker operations of Algorithm 1 and Sec. 4.1 at
+ * their real shape; a multi-GPU driver would put one exchange between them. */
+
+/* u_slab = a_slab ./ (K_slab v_full): a_slab, u_slab have `rows` entries, v_full has n. */
+int fsk_block_rowpass(const fsk_opts* opts, const void* K_slab, int64_t ldK, int32_t row0,
+                      int32_t rows, const void* a_slab, const void* v_full, void* u_slab,
+                      void* stream);
+
+/* s = K_slab^T u_slab (n entries): the slab's contribution to K^T u. */
+int fsk_block_colpartial(const fsk_opts* opts, const void* K_slab, int64_t ldK, int32_t row0,
+                         int32_t rows, const void* u_slab, void* s_partial, void* workspace,
+                         size_t ws_bytes, void* stream);
+
+/* Both at once, reading the slab one time: u_slab = a_slab ./ (K_slab v_full) and
+ * s = K_slab^T u_slab.  This is the kernel FSK_FLOW_FUSED runs, exposed on one slab. */
+int fsk_block_fused(const fsk_opts* opts, const void* K_slab, int64_t ldK, int32_t row0,
+                    int32_t rows, const void* a_slab, const void* v_full, void* u_slab,
+                    void* s_partial, void* workspace, size_t ws_bytes, void* stream);
+
+/* ---- log-domain hot path (stabilised form named in Sec. 1; implicit kernel, Sec. 4.1 Remark)
+ * x, y: device, n x d point clouds; the cost ||x_i - y_j||^2 is evaluated on the fly and K is
+ * never stored.  f, g: device, IN/OUT potentials (f = eps log u, g = eps log v; 0 for a cold
+ * start).  Each iteration does
+ *     f_i <- eps log a_i - eps LSE_j((g_j - C_ij)/eps),  g_j <- eps log b_j - eps LSE_i((f_i - C_ij)/eps).
+ * Only FSK_F32 is implemented.  iters_done / err as in fsk_sinkhorn_dense. */
+int fsk_sinkhorn_log_points(const fsk_opts* opts, const void* x, const void* y, int d, double eps,
+                            const void* a, const void* b, void* f, void* g, void* workspace,
+                            size_t ws_bytes, int32_t* iters_done, double* err, void* stream);
+
+/* ---- multitarget hot path (Sec. 5.3.2) -------------------------------------------------
+ * A, B (inputs), U, V (IN/OUT): device, n x m row-major with leading dimension m, one histogram
+ * pair per column, K shared.  Q = K V and R = K^T U are matrix products (MFMA).  Runs exactly
+ * opts->max_iters iterations.  Only FSK_F32 is implemented. */
+int fsk_sinkhorn_batched(const fsk_opts* opts, const void* K, int64_t ldK, const void* A,
+                         const void* B, void* U, void* V, void* workspace, size_t ws_bytes,
+                         void* stream);
+
+/* ---- measurement helpers -----------------------------------------------------------------
+ * A plain device copy dst <- src of `bytes` bytes (multiple of 16, both 16-byte aligned) with
+ * the same 128-bit access pattern as the hot kernels; used to calibrate profiler byte counters
+ * and to measure the achievable HBM rate next to the hot path. */
+int fsk_bench_copy(void* dst, const void* src, size_t bytes, void* stream);
+/* A plain streaming read of `bytes` bytes reduced to one float per workgroup in `sink`
+ * (device, at least 4096 floats): the read-only counterpart of fsk_bench_copy. */
+int fsk_bench_read(const void* src, size_t bytes, void* sink, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* FSK_H */

@@ -1,0 +1,214 @@
+"""ctypes binding of libfsk's C ABI (see ``include/fsk.h``).
+
+Argument marshalling only: every function here has the name of the C entry point it calls,
+takes torch tensors that live on the GPU (torch is used for device memory and streams, nothing
+else), turns them into raw pointers / leading dimensions and returns what the C call returns.
+No step of the method runs in Python, and there is no CPU fallback: if ``libfsk.so`` has not
+been built, the first call raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libfsk.so")
+
+FSK_OK = 0
+FSK_EINVAL, FSK_EALIGN, FSK_EDIV, FSK_EWORKSPACE, FSK_ENONFINITE, FSK_EHIP, FSK_EUNSUPPORTED = \
+    -1, -2, -3, -4, -5, -6, -7
+FSK_F32, FSK_F64 = 0, 1
+FSK_FLOW_FUSED, FSK_FLOW_TWO_PASS, FSK_FLOW_PAPER = 0, 1, 2
+FSK_DAMP_NONE, FSK_DAMP_ARITHMETIC, FSK_DAMP_GEOMETRIC = 0, 1, 2
+FSK_MODE_DENSE, FSK_MODE_LOG, FSK_MODE_BATCHED, FSK_MODE_SETUP = 0, 1, 2, 3
+
+EXPORTS = (
+    "fsk_version", "fsk_last_error", "fsk_workspace_bytes", "fsk_kernel_from_cost",
+    "fsk_kernel_from_points", "fsk_sinkhorn_dense", "fsk_marginals", "fsk_block_rowpass",
+    "fsk_block_colpartial", "fsk_block_fused", "fsk_sinkhorn_log_points", "fsk_sinkhorn_batched",
+    "fsk_bench_copy", "fsk_bench_read",
+)
+
+
+class fsk_opts(ctypes.Structure):
+    _fields_ = [
+        ("n", ctypes.c_int32), ("m", ctypes.c_int32), ("c", ctypes.c_int32),
+        ("max_iters", ctypes.c_int32), ("tol", ctypes.c_double), ("check_every", ctypes.c_int32),
+        ("dtype", ctypes.c_int32), ("flow", ctypes.c_int32), ("damping", ctypes.c_int32),
+        ("eta", ctypes.c_double),
+    ]
+
+
+class FskError(RuntimeError):
+    def __init__(self, status: int, message: str):
+        super().__init__(f"fsk status {status}: {message}")
+        self.status = status
+        self.message = message
+
+
+_lib = None
+
+
+def lib() -> ctypes.CDLL:
+    """The loaded library; raises if it has not been built (there is no fallback path)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(f"{LIB_PATH} is missing: build it with "
+                               "`python -m paper_2502_07021_amd.build` (needs hipcc)")
+        L = ctypes.CDLL(LIB_PATH)
+        L.fsk_last_error.restype = ctypes.c_char_p
+        L.fsk_workspace_bytes.restype = ctypes.c_size_t
+        L.fsk_workspace_bytes.argtypes = [ctypes.POINTER(fsk_opts), ctypes.c_int, ctypes.c_int]
+        _lib = L
+    return _lib
+
+
+def _check(status: int) -> int:
+    if status != FSK_OK:
+        raise FskError(status, lib().fsk_last_error().decode())
+    return status
+
+
+def make_opts(n: int, dtype: torch.dtype = torch.float32, m: int = 1, c: int = 1,
+              max_iters: int = 0, tol: float = 0.0, check_every: int = 1,
+              flow: int = FSK_FLOW_FUSED, damping: int = FSK_DAMP_NONE, eta: float = 1.0) -> fsk_opts:
+    return fsk_opts(n=n, m=m, c=c, max_iters=max_iters, tol=tol, check_every=check_every,
+                    dtype=FSK_F64 if dtype == torch.float64 else FSK_F32, flow=flow,
+                    damping=damping, eta=eta)
+
+
+def _p(t: Optional[torch.Tensor]) -> ctypes.c_void_p:
+    if t is None:
+        return ctypes.c_void_p(None)
+    if not t.is_cuda:
+        raise ValueError("fsk takes device tensors")
+    return ctypes.c_void_p(t.data_ptr())
+
+
+def _ld(t: torch.Tensor) -> ctypes.c_int64:
+    if t.dim() != 2 or t.stride(1) != 1:
+        raise ValueError("matrix must be 2-D with unit column stride")
+    return ctypes.c_int64(t.stride(0))
+
+
+def _vec(t: Optional[torch.Tensor]) -> ctypes.c_void_p:
+    if t is not None and not t.is_contiguous():
+        raise ValueError("vectors and n x m state matrices must be contiguous")
+    return _p(t)
+
+
+def _stream(stream) -> ctypes.c_void_p:
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return ctypes.c_void_p(stream.cuda_stream if hasattr(stream, "cuda_stream") else int(stream))
+
+
+def _ws(workspace: Optional[torch.Tensor]):
+    if workspace is None:
+        return ctypes.c_void_p(None), ctypes.c_size_t(0)
+    return _p(workspace), ctypes.c_size_t(workspace.numel() * workspace.element_size())
+
+
+def fsk_version() -> int:
+    return int(lib().fsk_version())
+
+
+def fsk_workspace_bytes(opts: fsk_opts, mode: int = FSK_MODE_DENSE, d: int = 0) -> int:
+    return int(lib().fsk_workspace_bytes(ctypes.byref(opts), mode, d))
+
+
+def alloc_workspace(opts: fsk_opts, mode: int = FSK_MODE_DENSE, d: int = 0,
+                    device="cuda") -> torch.Tensor:
+    """Device scratch of the size the library asks for (torch owns the memory)."""
+    nbytes = fsk_workspace_bytes(opts, mode, d)
+    return torch.empty(max(nbytes, 256), dtype=torch.uint8, device=device)
+
+
+def fsk_kernel_from_cost(opts, C, eps, K, stream=None) -> int:
+    return _check(lib().fsk_kernel_from_cost(ctypes.byref(opts), _p(C), _ld(C), ctypes.c_double(eps),
+                                             _p(K), _ld(K), _stream(stream)))
+
+
+def fsk_kernel_from_points(opts, x, y, eps, normalise_by_max, K, workspace=None, want_cmax=False,
+                           stream=None):
+    """Returns max_ij C_ij if ``want_cmax`` (synchronises), else None."""
+    wp, wn = _ws(workspace)
+    cmax = ctypes.c_double(0.0)
+    _check(lib().fsk_kernel_from_points(
+        ctypes.byref(opts), _vec(x), _vec(y), ctypes.c_int(x.shape[1]), ctypes.c_double(eps),
+        ctypes.c_int(1 if normalise_by_max else 0), _p(K), _ld(K), wp, wn,
+        ctypes.byref(cmax) if want_cmax else None, _stream(stream)))
+    return float(cmax.value) if want_cmax else None
+
+
+def fsk_sinkhorn_dense(opts, K, a, b, u, v, workspace, stream=None):
+    """Returns (iters_done, err); err is NaN in fixed-iteration mode."""
+    wp, wn = _ws(workspace)
+    done, err = ctypes.c_int32(0), ctypes.c_double(float("nan"))
+    _check(lib().fsk_sinkhorn_dense(ctypes.byref(opts), _p(K), _ld(K), _vec(a), _vec(b), _vec(u),
+                                    _vec(v), wp, wn, ctypes.byref(done), ctypes.byref(err),
+                                    _stream(stream)))
+    return int(done.value), float(err.value)
+
+
+def fsk_marginals(opts, K, a, u, v, row_marginal, col_marginal, workspace, want_err=False,
+                  stream=None):
+    wp, wn = _ws(workspace)
+    err = ctypes.c_double(float("nan"))
+    _check(lib().fsk_marginals(ctypes.byref(opts), _p(K), _ld(K), _vec(a), _vec(u), _vec(v),
+                               _vec(row_marginal), _vec(col_marginal), wp, wn,
+                               ctypes.byref(err) if want_err else None, _stream(stream)))
+    return float(err.value) if want_err else None
+
+
+def fsk_block_rowpass(opts, K_slab, row0, a_slab, v_full, u_slab, stream=None) -> int:
+    return _check(lib().fsk_block_rowpass(ctypes.byref(opts), _p(K_slab), _ld(K_slab),
+                                          ctypes.c_int32(row0), ctypes.c_int32(K_slab.shape[0]),
+                                          _vec(a_slab), _vec(v_full), _vec(u_slab), _stream(stream)))
+
+
+def fsk_block_colpartial(opts, K_slab, row0, u_slab, s_partial, workspace, stream=None) -> int:
+    wp, wn = _ws(workspace)
+    return _check(lib().fsk_block_colpartial(ctypes.byref(opts), _p(K_slab), _ld(K_slab),
+                                             ctypes.c_int32(row0), ctypes.c_int32(K_slab.shape[0]),
+                                             _vec(u_slab), _vec(s_partial), wp, wn, _stream(stream)))
+
+
+def fsk_block_fused(opts, K_slab, row0, a_slab, v_full, u_slab, s_partial, workspace,
+                    stream=None) -> int:
+    wp, wn = _ws(workspace)
+    return _check(lib().fsk_block_fused(ctypes.byref(opts), _p(K_slab), _ld(K_slab),
+                                        ctypes.c_int32(row0), ctypes.c_int32(K_slab.shape[0]),
+                                        _vec(a_slab), _vec(v_full), _vec(u_slab), _vec(s_partial),
+                                        wp, wn, _stream(stream)))
+
+
+def fsk_sinkhorn_log_points(opts, x, y, eps, a, b, f, g, workspace, stream=None):
+    """Returns (iters_done, err)."""
+    wp, wn = _ws(workspace)
+    done, err = ctypes.c_int32(0), ctypes.c_double(float("nan"))
+    _check(lib().fsk_sinkhorn_log_points(ctypes.byref(opts), _vec(x), _vec(y),
+                                         ctypes.c_int(x.shape[1]), ctypes.c_double(eps), _vec(a),
+                                         _vec(b), _vec(f), _vec(g), wp, wn, ctypes.byref(done),
+                                         ctypes.byref(err), _stream(stream)))
+    return int(done.value), float(err.value)
+
+
+def fsk_sinkhorn_batched(opts, K, A, B, U, V, workspace, stream=None) -> int:
+    wp, wn = _ws(workspace)
+    return _check(lib().fsk_sinkhorn_batched(ctypes.byref(opts), _p(K), _ld(K), _vec(A), _vec(B),
+                                             _vec(U), _vec(V), wp, wn, _stream(stream)))
+
+
+def fsk_bench_copy(dst, src, stream=None) -> int:
+    nbytes = src.numel() * src.element_size()
+    return _check(lib().fsk_bench_copy(_p(dst), _p(src), ctypes.c_size_t(nbytes), _stream(stream)))
+
+
+def fsk_bench_read(src, sink, stream=None) -> int:
+    nbytes = src.numel() * src.element_size()
+    return _check(lib().fsk_bench_read(_p(src), ctypes.c_size_t(nbytes), _p(sink), _stream(stream)))

@@ -1,0 +1,382 @@
+// C ABI of libfsk: argument validation, workspace carving and the host loops that
+// enqueue the kernels.  Declarations and the meaning of every argument are in
+// include/fsk.h.
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+
+#include "fsk_device.h"
+#include "fsk_internal.h"
+
+namespace fsk {
+
+static thread_local char g_err[512] = "";
+
+int set_error(int code, const char* fmt, ...) {
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(g_err, sizeof(g_err), fmt, ap);
+  va_end(ap);
+  return code;
+}
+void clear_error() { g_err[0] = '\0'; }
+
+int device_cu_count() {
+  static int cached[64] = {0};
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 0;
+  if (cached[dev] == 0) {
+    int cus = 0;
+    if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess)
+      return 0;
+    cached[dev] = cus;
+  }
+  return cached[dev];
+}
+
+// ------------------------------------------------------------------ validation
+static int check_common(const fsk_opts* o) {
+  if (!o) return set_error(FSK_EINVAL, "opts is NULL");
+  if (o->n <= 0) return set_error(FSK_EINVAL, "n = %d must be positive", o->n);
+  if (o->m < 1) return set_error(FSK_EINVAL, "m = %d must be >= 1", o->m);
+  if (o->c < 1) return set_error(FSK_EINVAL, "c = %d must be >= 1", o->c);
+  if (o->max_iters < 0) return set_error(FSK_EINVAL, "max_iters = %d must be >= 0", o->max_iters);
+  if (o->dtype != FSK_F32 && o->dtype != FSK_F64)
+    return set_error(FSK_EINVAL, "unknown dtype %d", o->dtype);
+  if (o->flow < FSK_FLOW_FUSED || o->flow > FSK_FLOW_PAPER)
+    return set_error(FSK_EINVAL, "unknown flow %d", o->flow);
+  if (o->damping < FSK_DAMP_NONE || o->damping > FSK_DAMP_GEOMETRIC)
+    return set_error(FSK_EINVAL, "unknown damping %d", o->damping);
+  if (o->damping != FSK_DAMP_NONE && !(o->eta > 0.0 && o->eta <= 1.0))
+    return set_error(FSK_EINVAL, "eta = %g must lie in (0, 1]", o->eta);
+  if (o->tol > 0.0 && o->check_every < 1)
+    return set_error(FSK_EINVAL, "check_every = %d must be >= 1 in tolerance mode", o->check_every);
+  if (std::isnan(o->tol)) return set_error(FSK_EINVAL, "tol is NaN");
+  if (o->n % o->c != 0)
+    return set_error(FSK_EDIV, "c = %d does not divide n = %d (n = c*m is required)", o->c, o->n);
+  return FSK_OK;
+}
+
+static int check_matrix(const char* name, const void* p, int64_t ld, int n, int dtype) {
+  if (!p) return set_error(FSK_EINVAL, "%s is NULL", name);
+  if (ld < n) return set_error(FSK_EINVAL, "leading dimension %lld of %s is below n = %d", (long long)ld, name, n);
+  if (!aligned16(p)) return set_error(FSK_EALIGN, "%s is not 16-byte aligned", name);
+  if ((ld * (int64_t)elem_size(dtype)) % 16 != 0)
+    return set_error(FSK_EALIGN, "row pitch of %s (%lld bytes) is not a multiple of 16", name,
+                     (long long)(ld * (int64_t)elem_size(dtype)));
+  return FSK_OK;
+}
+
+static int check_vec(const char* name, const void* p, bool need16) {
+  if (!p) return set_error(FSK_EINVAL, "%s is NULL", name);
+  if (need16 && !aligned16(p)) return set_error(FSK_EALIGN, "%s is not 16-byte aligned", name);
+  return FSK_OK;
+}
+
+#define FSK_TRY(expr)          \
+  do {                         \
+    int fsk_rc_ = (expr);      \
+    if (fsk_rc_ != FSK_OK) return fsk_rc_; \
+  } while (0)
+
+// ------------------------------------------------------------------ workspace
+struct DenseWs {
+  int64_t ld_ws;        // elements per partial row
+  size_t partial_rows;  // rows the partial area holds
+  size_t partial_off, vec_off, scalar_off, total;
+};
+
+static DenseWs dense_ws(const fsk_opts* o) {
+  DenseWs w{};
+  const size_t s = elem_size(o->dtype);
+  w.ld_ws = (int64_t)align_up((size_t)o->n, 64);
+  const int rows_blk = o->n / o->c;
+  size_t rows = (size_t)col_strips(o->n);
+  FusedPlan p = fused_plan(o->dtype, o->n, rows_blk);
+  int wgs = p.ok ? p.wgs : 0;
+  if (p.ok && device_cu_count() == 0) wgs = p.groups < 1024 ? p.groups : 1024;  // no device: be generous
+  if ((size_t)o->c * wgs > rows) rows = (size_t)o->c * wgs;
+  w.partial_rows = rows;
+  w.partial_off = 0;
+  w.vec_off = align_up(rows * (size_t)w.ld_ws * s, 256);
+  w.scalar_off = w.vec_off + align_up((size_t)o->n * s, 256);
+  w.total = w.scalar_off + 256;
+  return w;
+}
+
+static int epi_of(const fsk_opts* o) {
+  return o->damping == FSK_DAMP_ARITHMETIC ? kEpiDampArith
+         : o->damping == FSK_DAMP_GEOMETRIC ? kEpiDampGeom
+                                            : kEpiDivide;
+}
+
+}  // namespace fsk
+
+using namespace fsk;
+
+extern "C" {
+
+int fsk_version(void) { return 100; }
+
+const char* fsk_last_error(void) { return g_err; }
+
+size_t fsk_workspace_bytes(const fsk_opts* opts, int mode, int d) {
+  if (check_common(opts) != FSK_OK) return 0;
+  switch (mode) {
+    case FSK_MODE_DENSE: return dense_ws(opts).total;
+    case FSK_MODE_SETUP: (void)d; return align_up(max_sqdist_scratch_doubles(opts->n) * 8, 256) + 256;
+    default: return 0;
+  }
+}
+
+int fsk_kernel_from_cost(const fsk_opts* opts, const void* C, int64_t ldC, double eps, void* K,
+                         int64_t ldK, void* stream) {
+  clear_error();
+  FSK_TRY(check_common(opts));
+  if (!(eps > 0.0)) return set_error(FSK_EINVAL, "eps = %g must be positive", eps);
+  if (!C || !K) return set_error(FSK_EINVAL, "C or K is NULL");
+  if (ldC < opts->n || ldK < opts->n) return set_error(FSK_EINVAL, "leading dimension below n");
+  return launch_gibbs_from_cost(opts->dtype, C, ldC, opts->n, eps, K, ldK, (hipStream_t)stream);
+}
+
+int fsk_kernel_from_points(const fsk_opts* opts, const void* x, const void* y, int d, double eps,
+                           int normalise_by_max, void* K, int64_t ldK, void* workspace,
+                           size_t ws_bytes, double* cmax_out, void* stream) {
+  clear_error();
+  FSK_TRY(check_common(opts));
+  if (!(eps > 0.0)) return set_error(FSK_EINVAL, "eps = %g must be positive", eps);
+  if (d < 1) return set_error(FSK_EINVAL, "d = %d must be >= 1", d);
+  if (!x || !y || !K) return set_error(FSK_EINVAL, "x, y or K is NULL");
+  if (ldK < opts->n) return set_error(FSK_EINVAL, "leading dimension below n");
+  hipStream_t st = (hipStream_t)stream;
+  const bool need_max = normalise_by_max || cmax_out;
+  double* cmax_dev = nullptr;
+  if (need_max) {
+    const size_t need = fsk_workspace_bytes(opts, FSK_MODE_SETUP, d);
+    if (!workspace || ws_bytes < need)
+      return set_error(FSK_EWORKSPACE, "setup needs %zu workspace bytes, got %zu", need, ws_bytes);
+    const size_t cnt = max_sqdist_scratch_doubles(opts->n);
+    double* scratch = (double*)workspace;
+    cmax_dev = (double*)((char*)workspace + align_up(cnt * 8, 256));
+    FSK_TRY(launch_max_sqdist(opts->dtype, x, y, opts->n, d, scratch, cnt, cmax_dev, st));
+  }
+  FSK_TRY(launch_gibbs_from_points(opts->dtype, x, y, opts->n, d, eps,
+                                   normalise_by_max ? cmax_dev : nullptr, K, ldK, st));
+  if (cmax_out) {
+    FSK_HIP(hipMemcpyAsync(cmax_out, cmax_dev, sizeof(double), hipMemcpyDeviceToHost, st));
+    FSK_HIP(hipStreamSynchronize(st));
+  }
+  return FSK_OK;
+}
+
+// One dense iteration, enqueued.
+static int dense_iteration(const fsk_opts* o, const DenseWs& w, const char* K, int64_t ld,
+                           const char* a, const char* b, char* u, char* v, char* ws,
+                           hipStream_t st) {
+  const int n = o->n, c = o->c, m = n / c, dt = o->dtype;
+  const size_t s = elem_size(dt);
+  const int epi = epi_of(o);
+  void* partial = ws + w.partial_off;
+  int flow = o->flow;
+  FusedPlan plan{};
+  if (flow == FSK_FLOW_FUSED) {
+    plan = fused_plan(dt, n, m);
+    // rows too long to hold in registers, or an update the fused kernel does not carry
+    if (!plan.ok || epi == kEpiDampGeom) flow = FSK_FLOW_TWO_PASS;
+  }
+  if (flow == FSK_FLOW_FUSED) {
+    FSK_TRY(launch_fused(dt, plan, K, ld, n, m, c, a, v, u, u, partial, w.ld_ws, epi, o->eta, st));
+    return launch_colreduce(dt, partial, w.ld_ws, c * plan.wgs, 0, n, b, v, v, epi, o->eta, st);
+  }
+  for (int j = 0; j < c; ++j) {  // worker j: u_{I_j} from its row slab and the shared v
+    const size_t off = (size_t)j * m;
+    FSK_TRY(launch_rowpass(dt, K + off * (size_t)ld * s, ld, n, m, v, a + off * s, u + off * s,
+                           u + off * s, epi, o->eta, st));
+  }
+  if (flow == FSK_FLOW_TWO_PASS) {
+    FSK_TRY(launch_colpartial(dt, K, ld, n, n, 0, n, u, partial, w.ld_ws, st));
+    return launch_colreduce(dt, partial, w.ld_ws, col_strips(n), 0, n, b, v, v, epi, o->eta, st);
+  }
+  for (int j = 0; j < c; ++j) {  // worker j: r_{I_j} = (K_{:,I_j})^T u from its column slab
+    FSK_TRY(launch_colpartial(dt, K, ld, n, n, j * m, (j + 1) * m, u, partial, w.ld_ws, st));
+    FSK_TRY(launch_colreduce(dt, partial, w.ld_ws, col_strips(n), j * m, (j + 1) * m, b, v, v, epi,
+                             o->eta, st));
+  }
+  return FSK_OK;
+}
+
+// err = ||diag(u) K v - a||_1, synchronising.
+static int dense_error(const fsk_opts* o, const DenseWs& w, const void* K, int64_t ld,
+                       const void* a, const void* u, const void* v, char* ws, double* err,
+                       hipStream_t st) {
+  void* errvec = ws + w.vec_off;
+  double* scalar = (double*)(ws + w.scalar_off);
+  FSK_TRY(launch_rowpass(o->dtype, K, ld, o->n, o->n, v, a, u, errvec, kEpiAbsErr, 0.0, st));
+  FSK_TRY(launch_sum_to_double(o->dtype, errvec, o->n, scalar, st));
+  FSK_HIP(hipMemcpyAsync(err, scalar, sizeof(double), hipMemcpyDeviceToHost, st));
+  FSK_HIP(hipStreamSynchronize(st));
+  return FSK_OK;
+}
+
+int fsk_sinkhorn_dense(const fsk_opts* opts, const void* K, int64_t ldK, const void* a,
+                       const void* b, void* u, void* v, void* workspace, size_t ws_bytes,
+                       int32_t* iters_done, double* err, void* stream) {
+  clear_error();
+  FSK_TRY(check_common(opts));
+  if (opts->m != 1) return set_error(FSK_EINVAL, "dense call takes m = 1 (use fsk_sinkhorn_batched)");
+  FSK_TRY(check_matrix("K", K, ldK, opts->n, opts->dtype));
+  FSK_TRY(check_vec("a", a, false));
+  FSK_TRY(check_vec("b", b, false));
+  FSK_TRY(check_vec("u", u, true));
+  FSK_TRY(check_vec("v", v, true));
+  const DenseWs w = dense_ws(opts);
+  if (!workspace || ws_bytes < w.total)
+    return set_error(FSK_EWORKSPACE, "dense call needs %zu workspace bytes, got %zu", w.total, ws_bytes);
+  if (!aligned16(workspace)) return set_error(FSK_EALIGN, "workspace is not 16-byte aligned");
+  hipStream_t st = (hipStream_t)stream;
+  int done = 0;
+  double e = NAN;
+  for (int it = 0; it < opts->max_iters; ++it) {
+    FSK_TRY(dense_iteration(opts, w, (const char*)K, ldK, (const char*)a, (const char*)b, (char*)u,
+                            (char*)v, (char*)workspace, st));
+    done = it + 1;
+    if (opts->tol > 0.0 && (done % opts->check_every == 0 || done == opts->max_iters)) {
+      FSK_TRY(dense_error(opts, w, K, ldK, a, u, v, (char*)workspace, &e, st));
+      if (!std::isfinite(e)) {
+        if (iters_done) *iters_done = done;
+        if (err) *err = e;
+        return set_error(FSK_ENONFINITE, "marginal error is not finite after %d iterations", done);
+      }
+      if (e < opts->tol) break;
+    }
+  }
+  if (iters_done) *iters_done = done;
+  if (err) *err = e;
+  return FSK_OK;
+}
+
+int fsk_marginals(const fsk_opts* opts, const void* K, int64_t ldK, const void* a, const void* u,
+                  const void* v, void* row_marginal, void* col_marginal, void* workspace,
+                  size_t ws_bytes, double* err_l1, void* stream) {
+  clear_error();
+  FSK_TRY(check_common(opts));
+  FSK_TRY(check_matrix("K", K, ldK, opts->n, opts->dtype));
+  FSK_TRY(check_vec("u", u, true));
+  FSK_TRY(check_vec("v", v, true));
+  const DenseWs w = dense_ws(opts);
+  if (!workspace || ws_bytes < w.total)
+    return set_error(FSK_EWORKSPACE, "marginals need %zu workspace bytes, got %zu", w.total, ws_bytes);
+  hipStream_t st = (hipStream_t)stream;
+  const int n = opts->n, dt = opts->dtype;
+  char* ws = (char*)workspace;
+  if (row_marginal)
+    FSK_TRY(launch_rowpass(dt, K, ldK, n, n, v, nullptr, u, row_marginal, kEpiMarginal, 0.0, st));
+  if (col_marginal) {
+    FSK_TRY(launch_colpartial(dt, K, ldK, n, n, 0, n, u, ws + w.partial_off, w.ld_ws, st));
+    FSK_TRY(launch_colreduce(dt, ws + w.partial_off, w.ld_ws, col_strips(n), 0, n, nullptr, v,
+                             col_marginal, kEpiMarginal, 0.0, st));
+  }
+  if (err_l1) {
+    FSK_TRY(check_vec("a", a, false));
+    FSK_TRY(dense_error(opts, w, K, ldK, a, u, v, ws, err_l1, st));
+  }
+  return FSK_OK;
+}
+
+// ------------------------------------------------------------- one worker's share
+static int check_block(const fsk_opts* opts, const void* K_slab, int64_t ldK, int32_t row0,
+                       int32_t rows) {
+  FSK_TRY(check_common(opts));
+  FSK_TRY(check_matrix("K_slab", K_slab, ldK, opts->n, opts->dtype));
+  if (rows < 1 || row0 < 0 || (int64_t)row0 + rows > opts->n)
+    return set_error(FSK_EINVAL, "rows [%d, %d) are not inside [0, %d)", row0, row0 + rows, opts->n);
+  return FSK_OK;
+}
+
+int fsk_block_rowpass(const fsk_opts* opts, const void* K_slab, int64_t ldK, int32_t row0,
+                      int32_t rows, const void* a_slab, const void* v_full, void* u_slab,
+                      void* stream) {
+  clear_error();
+  FSK_TRY(check_block(opts, K_slab, ldK, row0, rows));
+  FSK_TRY(check_vec("a_slab", a_slab, false));
+  FSK_TRY(check_vec("v_full", v_full, true));
+  FSK_TRY(check_vec("u_slab", u_slab, false));
+  return launch_rowpass(opts->dtype, K_slab, ldK, opts->n, rows, v_full, a_slab, u_slab, u_slab,
+                        epi_of(opts), opts->eta, (hipStream_t)stream);
+}
+
+int fsk_block_colpartial(const fsk_opts* opts, const void* K_slab, int64_t ldK, int32_t row0,
+                         int32_t rows, const void* u_slab, void* s_partial, void* workspace,
+                         size_t ws_bytes, void* stream) {
+  clear_error();
+  FSK_TRY(check_block(opts, K_slab, ldK, row0, rows));
+  FSK_TRY(check_vec("u_slab", u_slab, false));
+  FSK_TRY(check_vec("s_partial", s_partial, false));
+  const DenseWs w = dense_ws(opts);
+  if (!workspace || ws_bytes < w.total)
+    return set_error(FSK_EWORKSPACE, "block call needs %zu workspace bytes, got %zu", w.total, ws_bytes);
+  hipStream_t st = (hipStream_t)stream;
+  char* ws = (char*)workspace;
+  FSK_TRY(launch_colpartial(opts->dtype, K_slab, ldK, opts->n, rows, 0, opts->n, u_slab,
+                            ws + w.partial_off, w.ld_ws, st));
+  return launch_colreduce(opts->dtype, ws + w.partial_off, w.ld_ws, col_strips(rows), 0, opts->n,
+                          nullptr, nullptr, s_partial, kEpiProduct, 0.0, st);
+}
+
+int fsk_block_fused(const fsk_opts* opts, const void* K_slab, int64_t ldK, int32_t row0,
+                    int32_t rows, const void* a_slab, const void* v_full, void* u_slab,
+                    void* s_partial, void* workspace, size_t ws_bytes, void* stream) {
+  clear_error();
+  FSK_TRY(check_block(opts, K_slab, ldK, row0, rows));
+  FSK_TRY(check_vec("a_slab", a_slab, false));
+  FSK_TRY(check_vec("v_full", v_full, true));
+  FSK_TRY(check_vec("u_slab", u_slab, false));
+  FSK_TRY(check_vec("s_partial", s_partial, false));
+  const FusedPlan plan = fused_plan(opts->dtype, opts->n, rows);
+  if (!plan.ok)
+    return set_error(FSK_EUNSUPPORTED, "n = %d is too long for the register-resident fused kernel",
+                     opts->n);
+  if (opts->damping == FSK_DAMP_GEOMETRIC)
+    return set_error(FSK_EUNSUPPORTED, "the fused kernel does not carry the geometric relaxation");
+  const size_t s = elem_size(opts->dtype);
+  const int64_t ld_ws = (int64_t)align_up((size_t)opts->n, 64);
+  const size_t need = (size_t)plan.wgs * (size_t)ld_ws * s;
+  if (!workspace || ws_bytes < need)
+    return set_error(FSK_EWORKSPACE, "fused block call needs %zu workspace bytes, got %zu", need, ws_bytes);
+  hipStream_t st = (hipStream_t)stream;
+  FSK_TRY(launch_fused(opts->dtype, plan, K_slab, ldK, opts->n, rows, 1, a_slab, v_full, u_slab,
+                       u_slab, workspace, ld_ws, epi_of(opts), opts->eta, st));
+  return launch_colreduce(opts->dtype, workspace, ld_ws, plan.wgs, 0, opts->n, nullptr, nullptr,
+                          s_partial, kEpiProduct, 0.0, st);
+}
+
+// ------------------------------------------------------------- not built yet
+int fsk_sinkhorn_log_points(const fsk_opts*, const void*, const void*, int, double, const void*,
+                            const void*, void*, void*, void*, size_t, int32_t*, double*, void*) {
+  return set_error(FSK_EUNSUPPORTED, "log-domain path is not built yet");
+}
+
+int fsk_sinkhorn_batched(const fsk_opts*, const void*, int64_t, const void*, const void*, void*,
+                         void*, void*, size_t, void*) {
+  return set_error(FSK_EUNSUPPORTED, "batched path is not built yet");
+}
+
+// ------------------------------------------------------------- measurement helpers
+int fsk_bench_copy(void* dst, const void* src, size_t bytes, void* stream) {
+  clear_error();
+  if (!dst || !src) return set_error(FSK_EINVAL, "dst or src is NULL");
+  if (bytes % 16 != 0 || !aligned16(dst) || !aligned16(src))
+    return set_error(FSK_EALIGN, "copy needs 16-byte aligned pointers and size");
+  return launch_copy(dst, src, bytes, (hipStream_t)stream);
+}
+
+int fsk_bench_read(const void* src, size_t bytes, void* sink, void* stream) {
+  clear_error();
+  if (!sink || !src) return set_error(FSK_EINVAL, "src or sink is NULL");
+  if (bytes % 16 != 0 || !aligned16(src))
+    return set_error(FSK_EALIGN, "read needs a 16-byte aligned pointer and size");
+  return launch_read(src, bytes, (float*)sink, (hipStream_t)stream);
+}
+
+}  // extern "C"

@@ -1,0 +1,460 @@
+// Dense Sinkhorn kernels for gfx950: the two kernel products of one iteration
+// (paper: Sec. 1 scaling form, Algorithm 1 loop body, Sec. 4.1 local operations)
+//
+//     q = K v,  u = a ./ q            (row pass)
+//     r = K^T u, v = b ./ r           (column pass)
+//
+// as (1) a generic two-pass pair that works for any n and any row / column range
+// (one worker's slab, Sec. 3.1), and (2) a fused one-pass kernel that reads K
+// once per iteration: a workgroup keeps whole rows in registers, finishes u on
+// them and immediately accumulates their contribution to K^T u.
+//
+// All of them are HBM-bound streams over K with 128-bit loads; sums use a fixed
+// order (per-thread sequential, wave butterfly, per-wave slots added in index
+// order), no atomics.
+#include "fsk_device.h"
+#include "fsk_internal.h"
+
+namespace fsk {
+
+// ============================================================== row pass (generic)
+// One workgroup of 256 threads takes ROWS consecutive rows; thread t walks the
+// 16-byte packs t, t+256, ... of each row, so a wave reads 1 KiB contiguous per
+// load and v is fetched once for all ROWS rows.
+template <typename T, int ROWS>
+__global__ __launch_bounds__(256) void rowpass_kernel(const T* __restrict__ K, int64_t ld, int n,
+                                                      int rows, const T* __restrict__ vin,
+                                                      const T* marg, const T* old, T* out, int epi,
+                                                      T eta) {
+  constexpr int W = Pack<T>::W;
+  constexpr int NT = 256, NW = NT / kWave;
+  const int tid = threadIdx.x;
+  const int r_base = blockIdx.x * ROWS;
+  const int nvec_full = n / W;
+
+  const T* rowp[ROWS];
+#pragma unroll
+  for (int r = 0; r < ROWS; ++r) {
+    int row = r_base + r;
+    row = row < rows ? row : rows - 1;  // clamp: duplicates are computed and dropped
+    rowp[r] = K + (int64_t)row * ld;
+  }
+  T acc[ROWS];
+#pragma unroll
+  for (int r = 0; r < ROWS; ++r) acc[r] = T(0);
+
+#pragma unroll 2
+  for (int c = tid; c < nvec_full; c += NT) {
+    const Pack<T> vv = load_pack(vin + (int64_t)c * W);
+#pragma unroll
+    for (int r = 0; r < ROWS; ++r) {
+      const Pack<T> kk = load_pack(rowp[r] + (int64_t)c * W);
+#pragma unroll
+      for (int e = 0; e < W; ++e) acc[r] = fma(kk.e[e], vv.e[e], acc[r]);
+    }
+  }
+  if (tid == 0) {  // ragged tail of fewer than W columns
+    for (int j = nvec_full * W; j < n; ++j) {
+      const T vj = vin[j];
+#pragma unroll
+      for (int r = 0; r < ROWS; ++r) acc[r] = fma(rowp[r][j], vj, acc[r]);
+    }
+  }
+
+  __shared__ T red[ROWS][NW];
+  const int lane = tid & (kWave - 1), wave = tid / kWave;
+#pragma unroll
+  for (int r = 0; r < ROWS; ++r) {
+    const T s = wave_sum(acc[r]);
+    if (lane == 0) red[r][wave] = s;
+  }
+  __syncthreads();
+  if (tid < ROWS) {
+    const int row = r_base + tid;
+    if (row < rows) {
+      T q = T(0);
+#pragma unroll
+      for (int k = 0; k < NW; ++k) q += red[tid][k];
+      const T mg = epi_needs_marg(epi) ? marg[row] : T(0);
+      const T od = epi_needs_old(epi) ? old[row] : T(0);
+      out[row] = apply_epilogue(epi, mg, q, od, eta);
+    }
+  }
+}
+
+template <typename T>
+static int rowpass_typed(const void* K, int64_t ld, int n, int rows, const void* vin,
+                         const void* marg, const void* old, void* out, int epi, double eta,
+                         hipStream_t stream) {
+  if (rows <= 0) return FSK_OK;
+  constexpr int ROWS = 4;
+  dim3 grid((rows + ROWS - 1) / ROWS), block(256);
+  hipLaunchKernelGGL((rowpass_kernel<T, ROWS>), grid, block, 0, stream, (const T*)K, ld, n, rows,
+                     (const T*)vin, (const T*)marg, (const T*)old, (T*)out, epi, (T)eta);
+  FSK_LAUNCH_CHECK("rowpass_kernel");
+  return FSK_OK;
+}
+
+int launch_rowpass(int dtype, const void* K, int64_t ld, int n, int rows, const void* vin,
+                   const void* marg, const void* old, void* out, int epi, double eta,
+                   hipStream_t stream) {
+  return dtype == FSK_F64
+             ? rowpass_typed<double>(K, ld, n, rows, vin, marg, old, out, epi, eta, stream)
+             : rowpass_typed<float>(K, ld, n, rows, vin, marg, old, out, epi, eta, stream);
+}
+
+// ========================================================== column pass (generic)
+// Grid (column tiles, row strips).  A thread owns one 16-byte pack of columns and
+// adds K[i][cols] * u[i] over the rows of its strip in increasing i; the strip
+// partition depends only on the row count, so a column-restricted launch sums
+// every column exactly like an unrestricted one.
+template <typename T>
+__global__ __launch_bounds__(256) void colpartial_kernel(const T* __restrict__ K, int64_t ld,
+                                                         int rows, int vec_lo, int vec_hi,
+                                                         const T* __restrict__ u,
+                                                         T* __restrict__ partial, int64_t ld_ws) {
+  constexpr int W = Pack<T>::W;
+  const int vc = vec_lo + blockIdx.x * 256 + threadIdx.x;
+  const int s = blockIdx.y;
+  const int i0 = s * kColStrip;
+  const int i1 = i0 + kColStrip < rows ? i0 + kColStrip : rows;
+  if (vc >= vec_hi) return;  // no barrier below
+  Pack<T> acc;
+#pragma unroll
+  for (int e = 0; e < W; ++e) acc.e[e] = T(0);
+  const T* kp = K + (int64_t)i0 * ld + (int64_t)vc * W;
+#pragma unroll 8
+  for (int i = i0; i < i1; ++i) {
+    const T ui = u[i];
+    const Pack<T> kk = load_pack(kp);
+    kp += ld;
+#pragma unroll
+    for (int e = 0; e < W; ++e) acc.e[e] = fma(kk.e[e], ui, acc.e[e]);
+  }
+  store_pack(partial + (int64_t)s * ld_ws + (int64_t)vc * W, acc);
+}
+
+template <typename T>
+static int colpartial_typed(const void* K, int64_t ld, int n, int rows, int c0, int c1,
+                            const void* u, void* partial, int64_t ld_ws, hipStream_t stream) {
+  constexpr int W = Pack<T>::W;
+  if (rows <= 0 || c1 <= c0) return FSK_OK;
+  const int vec_lo = c0 / W, vec_hi = (c1 + W - 1) / W;
+  (void)n;
+  dim3 grid((vec_hi - vec_lo + 255) / 256, col_strips(rows)), block(256);
+  hipLaunchKernelGGL((colpartial_kernel<T>), grid, block, 0, stream, (const T*)K, ld, rows, vec_lo,
+                     vec_hi, (const T*)u, (T*)partial, ld_ws);
+  FSK_LAUNCH_CHECK("colpartial_kernel");
+  return FSK_OK;
+}
+
+int launch_colpartial(int dtype, const void* K, int64_t ld, int n, int rows, int c0, int c1,
+                      const void* u, void* partial, int64_t ld_ws, hipStream_t stream) {
+  return dtype == FSK_F64 ? colpartial_typed<double>(K, ld, n, rows, c0, c1, u, partial, ld_ws, stream)
+                          : colpartial_typed<float>(K, ld, n, rows, c0, c1, u, partial, ld_ws, stream);
+}
+
+// ======================================================= partial sums -> result
+// 64 columns per workgroup; the partial rows are split into 4 contiguous groups
+// (one per wave), each summed in increasing index, then the 4 group sums are
+// added in group order.  The grouping depends only on the number of partials.
+template <typename T>
+__global__ __launch_bounds__(256) void colreduce_kernel(const T* __restrict__ partial,
+                                                        int64_t ld_ws, int n_partials, int c0,
+                                                        int c1, const T* marg, const T* old, T* out,
+                                                        int epi, T eta) {
+  const int lane = threadIdx.x & 63, grp = threadIdx.x >> 6;
+  const int j = c0 + blockIdx.x * 64 + lane;
+  const int per = (n_partials + 3) / 4;
+  const int s0 = grp * per;
+  const int s1 = s0 + per < n_partials ? s0 + per : n_partials;
+  T acc = T(0);
+  if (j < c1) {
+    const T* p = partial + (int64_t)s0 * ld_ws + j;
+#pragma unroll 4
+    for (int s = s0; s < s1; ++s) {
+      acc += *p;
+      p += ld_ws;
+    }
+  }
+  __shared__ T sm[4][64];
+  sm[grp][lane] = acc;
+  __syncthreads();
+  if (grp == 0 && j < c1) {
+    const T r = ((sm[0][lane] + sm[1][lane]) + sm[2][lane]) + sm[3][lane];
+    const T mg = epi_needs_marg(epi) ? marg[j] : T(0);
+    const T od = epi_needs_old(epi) ? old[j] : T(0);
+    out[j] = apply_epilogue(epi, mg, r, od, eta);
+  }
+}
+
+template <typename T>
+static int colreduce_typed(const void* partial, int64_t ld_ws, int n_partials, int c0, int c1,
+                           const void* marg, const void* old, void* out, int epi, double eta,
+                           hipStream_t stream) {
+  if (c1 <= c0) return FSK_OK;
+  dim3 grid((c1 - c0 + 63) / 64), block(256);
+  hipLaunchKernelGGL((colreduce_kernel<T>), grid, block, 0, stream, (const T*)partial, ld_ws,
+                     n_partials, c0, c1, (const T*)marg, (const T*)old, (T*)out, epi, (T)eta);
+  FSK_LAUNCH_CHECK("colreduce_kernel");
+  return FSK_OK;
+}
+
+int launch_colreduce(int dtype, const void* partial, int64_t ld_ws, int n_partials, int c0, int c1,
+                     const void* marg, const void* old, void* out, int epi, double eta,
+                     hipStream_t stream) {
+  return dtype == FSK_F64
+             ? colreduce_typed<double>(partial, ld_ws, n_partials, c0, c1, marg, old, out, epi, eta, stream)
+             : colreduce_typed<float>(partial, ld_ws, n_partials, c0, c1, marg, old, out, epi, eta, stream);
+}
+
+// ============================================================ fused one-pass kernel
+// One workgroup of 512 threads (8 waves, 2 per SIMD, up to 256 VGPRs each) per
+// compute unit.  Thread t owns the packs t, t+512, ... of every row: VPT packs
+// per row, R rows at a time, so a group of R rows (R*VPT = 16 packs = 64 VGPRs)
+// sits in registers while the next group is in flight into a second register
+// set.  v lives in LDS (up to 128 KiB of the 160 KiB), the thread's slice of the
+// column accumulator in registers.  Per group: partial dot products, butterfly
+// wave sums, one barrier, u = a ./ q, then acc += K_row * u from the same
+// registers.  K is read exactly once; row groups are dealt round-robin to the
+// workgroups of a block so every compute unit streams the same number of rows.
+template <typename T, int VPT, int R, bool EXACT>
+__global__ __launch_bounds__(512) void fused_kernel(const T* __restrict__ K, int64_t ld, int n,
+                                                    int rows, const T* marg,
+                                                    const T* __restrict__ vin, const T* old_u,
+                                                    T* u_out, T* __restrict__ partial,
+                                                    int64_t ld_ws, T eta) {
+  // EXACT: n == VPT*512*W, every pack of every thread is a full pack inside the row.
+  // eta < 1 selects the arithmetic relaxation u <- (1-eta) u + eta a./(K v) (Sec. 3.3).
+  constexpr int W = Pack<T>::W;
+  constexpr int NT = 512, NW = NT / kWave;
+  extern __shared__ __align__(16) unsigned char fsk_smem[];
+  T* v_lds = reinterpret_cast<T*>(fsk_smem);  // VPT*NT*W entries, zero beyond n
+  T* red = v_lds + VPT * NT * W;              // [2][R][NW]
+
+  const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
+  const int G = gridDim.x, w = blockIdx.x, blk = blockIdx.y;
+  const int nvec = (n + W - 1) / W, nvec_full = n / W;
+  const int64_t rbase = (int64_t)blk * rows;  // first row of this row block
+  const int groups = (rows + R - 1) / R;
+  const bool damped = eta < T(1);
+
+  // stage v into LDS
+#pragma unroll
+  for (int i = 0; i < VPT; ++i) {
+    const int vi = i * NT + tid;
+    Pack<T> p;
+#pragma unroll
+    for (int e = 0; e < W; ++e) p.e[e] = T(0);
+    if (EXACT || vi < nvec_full) {
+      p = load_pack(vin + (int64_t)vi * W);
+    } else if (vi < nvec) {
+#pragma unroll
+      for (int e = 0; e < W; ++e)
+        if (vi * W + e < n) p.e[e] = vin[vi * W + e];
+    }
+    store_pack(v_lds + (int64_t)vi * W, p);
+  }
+  __syncthreads();
+
+  Pack<T> bufA[R][VPT], bufB[R][VPT], acc[VPT];
+  T mgA[R], mgB[R], odA[R], odB[R];
+#pragma unroll
+  for (int i = 0; i < VPT; ++i)
+#pragma unroll
+    for (int e = 0; e < W; ++e) acc[i].e[e] = T(0);
+
+  // Row groups past the end are clamped to the last group (a redundant, in-bounds
+  // read) and contribute nothing because their u is forced to 0 in process().
+  auto load_group = [&](Pack<T>(&buf)[R][VPT], T(&mg)[R], T(&od)[R], int g) {
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+      int row = g * R + r;
+      row = row < rows ? row : rows - 1;
+      const T* kp = K + (rbase + row) * ld + (int64_t)tid * W;
+      mg[r] = marg[rbase + row];
+      od[r] = damped ? old_u[rbase + row] : T(0);
+#pragma unroll
+      for (int i = 0; i < VPT; ++i) {
+        if (EXACT) {
+          buf[r][i] = load_pack(kp + i * NT * W);
+        } else {
+          const int vi = i * NT + tid;
+          const int back = vi < nvec ? 0 : (vi - (nvec - 1)) * W;  // clamp to the last pack
+          Pack<T> p = load_pack(kp + i * NT * W - back);
+#pragma unroll
+          for (int e = 0; e < W; ++e)
+            if (vi * W + e >= n) p.e[e] = T(0);  // padding columns and clamped duplicates
+          buf[r][i] = p;
+        }
+      }
+    }
+  };
+
+  auto process = [&](Pack<T>(&buf)[R][VPT], T(&mg)[R], T(&od)[R], int g, int parity) {
+    T d[R];
+#pragma unroll
+    for (int r = 0; r < R; ++r) d[r] = T(0);
+#pragma unroll
+    for (int i = 0; i < VPT; ++i) {
+      const Pack<T> vv = load_pack(v_lds + (int64_t)(i * NT + tid) * W);
+#pragma unroll
+      for (int r = 0; r < R; ++r)
+#pragma unroll
+        for (int e = 0; e < W; ++e) d[r] = fma(buf[r][i].e[e], vv.e[e], d[r]);
+    }
+    T* slot = red + parity * R * NW;
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+      const T s = wave_sum(d[r]);
+      if (lane == 0) slot[r * NW + wave] = s;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+      T q = T(0);
+#pragma unroll
+      for (int k = 0; k < NW; ++k) q += slot[r * NW + k];
+      const int row = g * R + r;
+      T ur = T(0);
+      if (row < rows) {
+        ur = mg[r] / q;
+        if (damped) ur = (T(1) - eta) * od[r] + eta * ur;
+        if (tid == 0) u_out[rbase + row] = ur;
+      }
+#pragma unroll
+      for (int i = 0; i < VPT; ++i)
+#pragma unroll
+        for (int e = 0; e < W; ++e) acc[i].e[e] = fma(buf[r][i].e[e], ur, acc[i].e[e]);
+    }
+  };
+
+  // w < groups is guaranteed by the launcher.  Two register sets alternate: while one
+  // group is being reduced the next one is already in flight.
+  int g = w;
+  load_group(bufA, mgA, odA, g);
+  while (true) {
+    load_group(bufB, mgB, odB, g + G);
+    process(bufA, mgA, odA, g, 0);
+    g += G;
+    if (g >= groups) break;
+    load_group(bufA, mgA, odA, g + G);
+    process(bufB, mgB, odB, g, 1);
+    g += G;
+    if (g >= groups) break;
+  }
+
+  T* prow = partial + ((int64_t)blk * G + w) * ld_ws;
+#pragma unroll
+  for (int i = 0; i < VPT; ++i) {
+    const int vi = i * NT + tid;
+    if (EXACT || vi < nvec) store_pack(prow + (int64_t)vi * W, acc[i]);
+  }
+}
+
+// Rows held in one register set: 16 packs (64 VGPRs) per thread, at most 8 rows.
+constexpr int fused_rows_per_group(int vpt) { return 16 / vpt < 8 ? 16 / vpt : 8; }
+
+FusedPlan fused_plan(int dtype, int n, int rows) {
+  FusedPlan p{};
+  const int W = pack_width(dtype);
+  const int nvec = (n + W - 1) / W;
+  int vpt = 1;
+  while (vpt * 512 < nvec) vpt *= 2;
+  p.ok = vpt <= 16 && rows > 0 && n > 0;
+  if (!p.ok) return p;
+  p.vpt = vpt;
+  p.r = fused_rows_per_group(vpt);
+  p.groups = (rows + p.r - 1) / p.r;
+  const int cus = device_cu_count();
+  p.wgs = p.groups < cus ? p.groups : cus;
+  if (p.wgs < 1) p.wgs = 1;
+  p.lds_bytes = (size_t)vpt * 512 * 16 + (size_t)2 * p.r * 8 * elem_size(dtype);
+  return p;
+}
+
+template <typename T, int VPT, bool EXACT>
+static int fused_typed(const FusedPlan& plan, const void* K, int64_t ld, int n, int rows, int c,
+                       const void* marg, const void* vin, const void* old_u, void* u_out,
+                       void* partial, int64_t ld_ws, double eta, hipStream_t stream) {
+  constexpr int R = fused_rows_per_group(VPT);
+  auto kern = fused_kernel<T, VPT, R, EXACT>;
+  static bool attr_set = false;  // benign race: setting it twice is harmless
+  if (!attr_set) {
+    FSK_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024));
+    attr_set = true;
+  }
+  dim3 grid(plan.wgs, c), block(512);
+  hipLaunchKernelGGL(kern, grid, block, plan.lds_bytes, stream, (const T*)K, ld, n, rows,
+                     (const T*)marg, (const T*)vin, (const T*)old_u, (T*)u_out, (T*)partial, ld_ws,
+                     (T)eta);
+  FSK_LAUNCH_CHECK("fused_kernel");
+  return FSK_OK;
+}
+
+template <typename T>
+static int fused_dispatch(const FusedPlan& plan, const void* K, int64_t ld, int n, int rows, int c,
+                          const void* marg, const void* vin, const void* old_u, void* u_out,
+                          void* partial, int64_t ld_ws, double eta, hipStream_t stream) {
+  const bool exact = n == plan.vpt * 512 * Pack<T>::W;
+#define FSK_FUSED_CASE(V)                                                                         \
+  case V:                                                                                         \
+    return exact ? fused_typed<T, V, true>(plan, K, ld, n, rows, c, marg, vin, old_u, u_out,      \
+                                           partial, ld_ws, eta, stream)                           \
+                 : fused_typed<T, V, false>(plan, K, ld, n, rows, c, marg, vin, old_u, u_out,     \
+                                            partial, ld_ws, eta, stream)
+  switch (plan.vpt) {
+    FSK_FUSED_CASE(1);
+    FSK_FUSED_CASE(2);
+    FSK_FUSED_CASE(4);
+    FSK_FUSED_CASE(8);
+    FSK_FUSED_CASE(16);
+    default: return set_error(FSK_EUNSUPPORTED, "fused kernel: n = %d does not fit in registers", n);
+  }
+#undef FSK_FUSED_CASE
+}
+
+int launch_fused(int dtype, const FusedPlan& plan, const void* K, int64_t ld, int n, int rows,
+                 int c, const void* marg, const void* vin, const void* old_u, void* u_out,
+                 void* partial, int64_t ld_ws, int epi, double eta, hipStream_t stream) {
+  if (!plan.ok) return set_error(FSK_EUNSUPPORTED, "fused kernel: n = %d does not fit in registers", n);
+  if (epi != kEpiDivide && epi != kEpiDampArith)
+    return set_error(FSK_EUNSUPPORTED, "fused kernel: only the plain and the arithmetic-damped update");
+  if (epi == kEpiDivide) eta = 1.0;
+  return dtype == FSK_F64
+             ? fused_dispatch<double>(plan, K, ld, n, rows, c, marg, vin, old_u, u_out, partial,
+                                      ld_ws, eta, stream)
+             : fused_dispatch<float>(plan, K, ld, n, rows, c, marg, vin, old_u, u_out, partial,
+                                     ld_ws, eta, stream);
+}
+
+// ================================================================= fp64 sum of a vector
+template <typename T>
+__global__ __launch_bounds__(1024) void sum_to_double_kernel(const T* __restrict__ x, int n,
+                                                             double* out) {
+  double s = 0.0;
+  for (int i = threadIdx.x; i < n; i += 1024) s += (double)x[i];
+  s = wave_sum(s);
+  __shared__ double sm[16];
+  if ((threadIdx.x & 63) == 0) sm[threadIdx.x >> 6] = s;
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    double t = 0.0;
+    for (int k = 0; k < 16; ++k) t += sm[k];
+    *out = t;
+  }
+}
+
+int launch_sum_to_double(int dtype, const void* x, int n, double* out, hipStream_t stream) {
+  if (dtype == FSK_F64)
+    hipLaunchKernelGGL((sum_to_double_kernel<double>), dim3(1), dim3(1024), 0, stream,
+                       (const double*)x, n, out);
+  else
+    hipLaunchKernelGGL((sum_to_double_kernel<float>), dim3(1), dim3(1024), 0, stream,
+                       (const float*)x, n, out);
+  FSK_LAUNCH_CHECK("sum_to_double_kernel");
+  return FSK_OK;
+}
+
+}  // namespace fsk

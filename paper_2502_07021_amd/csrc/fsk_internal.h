@@ -1,0 +1,95 @@
+// Host-side declarations shared by the translation units of libfsk.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "../../include/fsk.h"
+
+namespace fsk {
+
+// Records a thread-local message and returns `code`.
+int set_error(int code, const char* fmt, ...) __attribute__((format(printf, 2, 3)));
+void clear_error();
+
+#define FSK_HIP(call)                                                                     \
+  do {                                                                                    \
+    hipError_t fsk_e_ = (call);                                                           \
+    if (fsk_e_ != hipSuccess)                                                             \
+      return ::fsk::set_error(FSK_EHIP, "%s failed: %s", #call, hipGetErrorString(fsk_e_)); \
+  } while (0)
+
+#define FSK_LAUNCH_CHECK(name)                                                            \
+  do {                                                                                    \
+    hipError_t fsk_e_ = hipGetLastError();                                                \
+    if (fsk_e_ != hipSuccess)                                                             \
+      return ::fsk::set_error(FSK_EHIP, "launch of %s failed: %s", name,                  \
+                              hipGetErrorString(fsk_e_));                                 \
+  } while (0)
+
+inline size_t elem_size(int dtype) { return dtype == FSK_F64 ? 8 : 4; }
+inline int pack_width(int dtype) { return dtype == FSK_F64 ? 2 : 4; }
+inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+// Compute units of the current device (cached per device), 0 on failure.
+int device_cu_count();
+
+// ------------------------------------------------------------------ dense kernels
+constexpr int kColStrip = 128;  // rows summed sequentially into one partial column sum
+
+// Row strip count of the generic column pass over `rows` rows.
+inline int col_strips(int rows) { return (rows + kColStrip - 1) / kColStrip; }
+
+// out[i] = epilogue(marg[i], sum_j K[i][j] vin[j], old[i]) for the `rows` rows of K.
+int launch_rowpass(int dtype, const void* K, int64_t ld, int n, int rows, const void* vin,
+                   const void* marg, const void* old, void* out, int epi, double eta,
+                   hipStream_t stream);
+
+// partial[s][j] = sum over rows of strip s of K[i][j] u[i], for the 16-byte column packs that
+// intersect [c0, c1).  partial has col_strips(rows) rows of ld_ws elements.
+int launch_colpartial(int dtype, const void* K, int64_t ld, int n, int rows, int c0, int c1,
+                      const void* u, void* partial, int64_t ld_ws, hipStream_t stream);
+
+// out[j] = epilogue(marg[j], sum_s partial[s][j], old[j]) for j in [c0, c1).
+int launch_colreduce(int dtype, const void* partial, int64_t ld_ws, int n_partials, int c0, int c1,
+                     const void* marg, const void* old, void* out, int epi, double eta,
+                     hipStream_t stream);
+
+// Geometry of the fused one-pass kernel for a block of `rows` rows of an n-column K.
+struct FusedPlan {
+  bool ok;          // false: n exceeds what a workgroup can hold in registers
+  int vpt;          // 16-byte packs per thread per row
+  int r;            // rows processed together
+  int groups;       // ceil(rows / r)
+  int wgs;          // workgroups per row block (= partial rows per block)
+  size_t lds_bytes;
+};
+FusedPlan fused_plan(int dtype, int n, int rows);
+
+// For each of `c` row blocks of `rows` rows (block b starts at row b*rows of K, marg, old_u,
+// u_out): u_out = epilogue(marg, K v, old_u) and partial[(b*wgs + w)][:] = contribution of the
+// rows workgroup w handled to K_block^T u_block.
+int launch_fused(int dtype, const FusedPlan& plan, const void* K, int64_t ld, int n, int rows,
+                 int c, const void* marg, const void* vin, const void* old_u, void* u_out,
+                 void* partial, int64_t ld_ws, int epi, double eta, hipStream_t stream);
+
+// out (one double) = sum of x[0..n) accumulated in fp64 in a fixed order.
+int launch_sum_to_double(int dtype, const void* x, int n, double* out, hipStream_t stream);
+
+// ------------------------------------------------------------------ setup kernels
+int launch_gibbs_from_cost(int dtype, const void* C, int64_t ldC, int n, double eps, void* K,
+                           int64_t ldK, hipStream_t stream);
+// cmax_dev (one double, device) = max_ij ||x_i - y_j||^2; scratch holds one double per workgroup.
+int launch_max_sqdist(int dtype, const void* x, const void* y, int n, int d, double* scratch,
+                      size_t scratch_doubles, double* cmax_dev, hipStream_t stream);
+// K_ij = exp(-(||x_i-y_j||^2 / cmax) / eps); cmax read from cmax_dev, or 1 if it is NULL.
+int launch_gibbs_from_points(int dtype, const void* x, const void* y, int n, int d, double eps,
+                             const double* cmax_dev, void* K, int64_t ldK, hipStream_t stream);
+size_t max_sqdist_scratch_doubles(int n);
+
+// ------------------------------------------------------------------ measurement helpers
+int launch_copy(void* dst, const void* src, size_t bytes, hipStream_t stream);
+int launch_read(const void* src, size_t bytes, float* sink, hipStream_t stream);
+
+}  // namespace fsk

@@ -1,0 +1,85 @@
+"""Host-only checks of the C ABI: the library loads, exports every symbol the header declares,
+and rejects bad arguments before touching the GPU (no kernel is launched here)."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def api():
+    from paper_2502_07021_amd import api as _api
+    if not os.path.exists(_api.LIB_PATH):
+        from paper_2502_07021_amd import build
+        build.build_library()
+    return _api
+
+
+def declared_functions():
+    text = open(os.path.join(ROOT, "include", "fsk.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(fsk_[a-z_0-9]+)\s*\(", text)))
+
+
+def test_header_symbols_are_exported(api):
+    names = declared_functions()
+    assert len(names) >= 12
+    L = api.lib()
+    for name in names:
+        assert hasattr(L, name), f"{name} declared in fsk.h but not exported"
+    assert set(names) == set(api.EXPORTS)      # the binding covers the same set
+
+
+def test_opts_struct_layout_matches_header(api):
+    # int32 x4, double, int32 x4, double  -> 8-byte aligned, 48 bytes
+    assert ctypes.sizeof(api.fsk_opts) == 48
+    assert api.fsk_opts.tol.offset == 16 and api.fsk_opts.check_every.offset == 24
+    assert api.fsk_opts.eta.offset == 40
+
+
+def test_version_and_error_string(api):
+    assert api.fsk_version() >= 100
+    assert isinstance(api.lib().fsk_last_error(), bytes)
+
+
+@pytest.mark.parametrize("field,value,status", [
+    ("n", 0, -1), ("m", 0, -1), ("c", 0, -1), ("max_iters", -1, -1), ("dtype", 7, -1),
+    ("flow", 9, -1), ("damping", 5, -1), ("c", 3, -3),
+])
+def test_bad_options_are_rejected_on_the_host(api, field, value, status):
+    import torch
+    opts = api.make_opts(64, torch.float32, max_iters=1)
+    setattr(opts, field, value)
+    dummy = ctypes.c_void_p(256)     # never dereferenced: validation fails first
+    rc = api.lib().fsk_sinkhorn_dense(ctypes.byref(opts), dummy, ctypes.c_int64(64), dummy, dummy,
+                                      dummy, dummy, dummy, ctypes.c_size_t(1 << 30), None, None, None)
+    assert rc == status
+    assert api.lib().fsk_last_error() != b""
+    assert api.fsk_workspace_bytes(opts) == 0
+
+
+def test_bad_pointers_and_alignment_are_rejected_on_the_host(api):
+    import torch
+    L = api.lib()
+    opts = api.make_opts(64, torch.float32, max_iters=1)
+    ok = ctypes.c_void_p(4096)
+    args = lambda K, ld, u: (ctypes.byref(opts), K, ctypes.c_int64(ld), ok, ok, u, ok, ok,
+                             ctypes.c_size_t(1 << 30), None, None, None)
+    assert L.fsk_sinkhorn_dense(*args(None, 64, ok)) == api.FSK_EINVAL
+    assert L.fsk_sinkhorn_dense(*args(ctypes.c_void_p(4100), 64, ok)) == api.FSK_EALIGN
+    assert L.fsk_sinkhorn_dense(*args(ok, 66, ok)) == api.FSK_EALIGN       # pitch not 16 B
+    assert L.fsk_sinkhorn_dense(*args(ok, 32, ok)) == api.FSK_EINVAL       # ld < n
+    assert L.fsk_sinkhorn_dense(*args(ok, 64, ctypes.c_void_p(4100))) == api.FSK_EALIGN
+    opts.damping = api.FSK_DAMP_ARITHMETIC; opts.eta = 0.0
+    assert L.fsk_sinkhorn_dense(*args(ok, 64, ok)) == api.FSK_EINVAL
+    opts.damping = 0; opts.tol = 1e-3; opts.check_every = 0
+    assert L.fsk_sinkhorn_dense(*args(ok, 64, ok)) == api.FSK_EINVAL
+    # workspace too small
+    opts.tol = 0.0
+    small = (ctypes.byref(opts), ok, ctypes.c_int64(64), ok, ok, ok, ok, ok, ctypes.c_size_t(16),
+             None, None, None)
+    assert L.fsk_sinkhorn_dense(*small) == api.FSK_EWORKSPACE
+    assert b"workspace" in L.fsk_last_error()
