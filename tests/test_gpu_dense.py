@@ -174,8 +174,9 @@ def test_one_workers_share(orc, dtype):
     u2 = torch.empty(rows, dtype=td, device="cuda"); s2 = torch.empty(n, dtype=td, device="cuda")
     api.fsk_block_fused(opts, slab, row0, dev(a[row0:row0 + rows]), dev(v), u2, s2, ws)
     torch.cuda.synchronize()
-    assert np.array_equal(u2.cpu().numpy(), u_slab.cpu().numpy())      # same row sums, same order
-    assert relerr(s2.cpu().numpy(), s_ref) <= tol
+    assert relerr(u2.cpu().numpy(), u_ref) <= tol
+    u_full[row0:row0 + rows] = u2.cpu().numpy()
+    assert relerr(s2.cpu().numpy(), orc.col_products(K, u_full, row0, row0 + rows)) <= tol
 
 
 @pytest.mark.parametrize("cfg,n", [(1, 512), (2, 1000), (3, 1537), (5, 900)])
@@ -193,13 +194,14 @@ def test_setup_kernels_against_oracle(orc, cfg, n):
     K64, cmax_o = orc.gibbs_from_points(w.x, w.y, w.eps, w.normalise_by_max)
     assert cmax == pytest.approx(cmax_o, rel=1e-14)
     ulp = 2.0 ** -23 if w.dtype == np.float32 else 2.0 ** -52 * (1 + cmax_o / w.eps)
+    tiny = 2.0 ** -149 if w.dtype == np.float32 else 1e-300      # spacing of subnormal results
     got = K.cpu().numpy().astype(np.float64)
-    assert np.all(np.abs(got - K64) <= 1.01 * ulp * K64 + 1e-300)
+    assert np.all(np.abs(got - K64) <= 1.01 * ulp * K64 + tiny)
     C = orc.cost_sqeuclid(w.x, w.y).astype(w.dtype)
     K2 = torch.empty(n, n, dtype=td, device="cuda")
     api.fsk_kernel_from_cost(opts, dev(C), w.eps, K2)
     ref = orc.gibbs(C.astype(np.float64), w.eps)
-    assert np.all(np.abs(K2.cpu().numpy().astype(np.float64) - ref) <= 1.01 * ulp * ref + 1e-300)
+    assert np.all(np.abs(K2.cpu().numpy().astype(np.float64) - ref) <= 1.01 * ulp * ref + tiny)
 
 
 def test_end_to_end_with_gpu_setup(orc):
