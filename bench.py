@@ -1,0 +1,157 @@
+#!/usr/bin/env python3
+"""Benchmark of the dense Sinkhorn hot path on one MI355X.
+
+Workload: configuration 3 -- n = 32768, fp32 dense K (4 GiB) built on the GPU from seeded
+point clouds, row-partitioned into c = 8 blocks of 4096 rows, fused one-pass flow.  A "step" is
+one Sinkhorn iteration (u-update then v-update over the whole of K).  Inputs are resident in
+HBM before the timed region; the K build is setup and is not timed.
+
+Prints ONE JSON line: iterations/s (metric), the HBM roofline of the dominant kernel measured
+live with HIP events on the launch stream, and the CPU oracle timed on this machine's host cores
+on a bounded sample of the same workload.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import re
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_HBM_GBS = 8000.0   # MI355X published HBM3E peak
+
+
+def traffic_from_profile(name: str):
+    """HBM bytes per launch of the dominant kernel from the committed counter summary, if any."""
+    path = os.path.join(ROOT, "profiles", name)
+    if not os.path.exists(path):
+        return None
+    m = re.search(r"^traffic_bytes_per_launch:\s*([0-9.eE+]+)", open(path).read(), flags=re.M)
+    return float(m.group(1)) if m else None
+
+
+def cpu_baseline(w, seconds_budget: float = 20.0):
+    """The oracle as it stands on the host cores: K built by the oracle, then a few full
+    iterations of the same n = 32768 problem (blocked, c = 8, row-slab flow)."""
+    import numpy as np
+    import oracle
+    t0 = time.perf_counter()
+    K, _ = oracle.gibbs_from_points_f32(w.x, w.y, w.eps, w.normalise_by_max)
+    t_setup = time.perf_counter() - t0
+    t0 = time.perf_counter()
+    u, v = oracle.sinkhorn_blocked(K, w.a, w.b, 1, w.c, 1)
+    t_one = time.perf_counter() - t0
+    iters = int(max(1, min(10, (seconds_budget - t_one) // max(t_one, 1e-3))))
+    t0 = time.perf_counter()
+    oracle.sinkhorn_blocked(K, w.a, w.b, iters, w.c, 1, u0=u, v0=v)
+    dt = time.perf_counter() - t0
+    return {"value": iters / dt, "unit": "iterations/s", "cores": oracle.num_threads(),
+            "kind": "oracle",
+            "sample": f"{iters} full iterations at n={w.n} (c={w.c}, fp64 arithmetic on the fp32 K; "
+                      f"oracle K build {t_setup:.1f} s not counted)"}
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=1000)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--n", type=int, default=32768, help="problem size (default: configuration 3)")
+    ap.add_argument("--c", type=int, default=8)
+    ap.add_argument("--flow", type=int, default=0, help="0 fused, 1 two-pass, 2 Algorithm 1")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--profile-reps", type=int, default=50)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (no collectives are part of it); "
+              "use --gpus 1", file=sys.stderr)
+        return 2
+
+    import torch
+    from paper_2502_07021_amd import api, workloads
+
+    torch.cuda.set_device(0)
+    n, c = args.n, args.c
+    w = workloads.make(3, n=n)
+    w.c = c
+    dev = lambda t: torch.from_numpy(t).cuda()
+    x, y, a, b = dev(w.x), dev(w.y), dev(w.a), dev(w.b)
+
+    # setup (untimed): K on the GPU from the points
+    opts = api.make_opts(n, torch.float32, c=c, max_iters=args.steps, flow=args.flow)
+    K = torch.empty(n, n, dtype=torch.float32, device="cuda")
+    api.fsk_kernel_from_points(opts, x, y, w.eps, True, K,
+                               api.alloc_workspace(opts, api.FSK_MODE_SETUP, w.d))
+    ws = api.alloc_workspace(opts, api.FSK_MODE_DENSE)
+    u = torch.ones(n, device="cuda"); v = torch.ones(n, device="cuda")
+
+    def run(iters):
+        o = api.make_opts(n, torch.float32, c=c, max_iters=iters, flow=args.flow)
+        api.fsk_sinkhorn_dense(o, K, a, b, u, v, ws)
+
+    if args.warmup > 0:
+        run(args.warmup)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    run(args.steps)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    if not bool(torch.isfinite(u).all() and torch.isfinite(v).all()):
+        print("bench.py: non-finite scalings", file=sys.stderr)
+        return 1
+
+    # dominant kernel alone, same launch configuration, HIP events on the launch stream
+    stream_ms, other_ms, launches = api.fsk_dense_profile(opts, K, a, b, u, v, ws, args.profile_reps)
+    alg_bytes = float(n) * n * 4 * (1 if args.flow == 0 else 2)   # K read once (fused) or twice
+    achieved = alg_bytes / (stream_ms * 1e-3) / 1e9
+    roofline = {"bound": "hbm", "achieved": achieved, "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                "frac": achieved / PEAK_HBM_GBS,
+                "traffic": traffic_from_profile("dense_fused_cfg3_pmc.txt") if args.flow == 0 and n == 32768 and c == 8 else None,
+                "kernel": "fused_kernel<float,16,1,exact>" if args.flow == 0 else "rowpass+colpartial",
+                "kernel_ms": stream_ms, "launches_per_step": launches,
+                "algorithmic_bytes_per_step": alg_bytes, "other_kernels_ms": other_ms}
+
+    # same problem with c = 1 (the iterates the blocked run must reproduce), for reference
+    extra = {}
+    if c != 1:
+        o1 = api.make_opts(n, torch.float32, c=1, max_iters=args.steps, flow=args.flow)
+        ws1 = api.alloc_workspace(o1, api.FSK_MODE_DENSE)
+        u.fill_(1.0); v.fill_(1.0)
+        api.fsk_sinkhorn_dense(api.make_opts(n, torch.float32, c=1, max_iters=max(args.warmup, 1),
+                                             flow=args.flow), K, a, b, u, v, ws1)
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+        api.fsk_sinkhorn_dense(o1, K, a, b, u, v, ws1)
+        torch.cuda.synchronize()
+        dt1 = time.perf_counter() - t1
+        s1, _, _ = api.fsk_dense_profile(o1, K, a, b, u, v, ws1, args.profile_reps)
+        extra = {"c1_iterations_per_s": args.steps / dt1, "c1_kernel_ms": s1,
+                 "c1_kernel_GBps": alg_bytes / (s1 * 1e-3) / 1e9}
+
+    out = {
+        "metric": "Sinkhorn iters/sec (Kv+K^Tu) at n=32768 fp32; achieved HBM GB/s vs peak",
+        "value": args.steps / dt, "unit": "iterations/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": dt / args.steps * 1e3, "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": f"cfg3: n={n} fp32 dense K ({n * n * 4 / 2**30:.0f} GiB), "
+                               f"x~N(0,I_8), y~N(0.5,I_8), C/max C, eps=0.05, "
+                               f"row-partitioned c={c} on one GPU, flow={['fused','two_pass','algorithm1'][args.flow]}",
+                   "n": n, "c": c, "eps": w.eps, "iterations": args.steps},
+        "roofline": roofline,
+    }
+    out.update(extra)
+    if not args.no_cpu_baseline:
+        del K
+        torch.cuda.empty_cache()
+        out["cpu_baseline"] = cpu_baseline(w)
+    print(json.dumps(out))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -21,7 +21,9 @@
  *   - Matrices are row-major with a leading dimension `ld` counted in
  *     elements.  K must be 16-byte aligned and ld*sizeof(element) must be a
  *     multiple of 16 (rows are read with 128-bit loads); entries in the padding
- *     columns [n, ld) are never used.  Vectors need only their natural alignment.
+ *     columns [n, ld) are never used.  Full-length scaling vectors (u, v, v_full)
+ *     must be 16-byte aligned as well; every other vector needs only its natural
+ *     alignment.
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  All
  *     kernels are enqueued on it.  Calls that run a fixed number of iterations
  *     return as soon as the work is enqueued; calls in tolerance mode
@@ -178,7 +180,17 @@ int fsk_sinkhorn_batched(const fsk_opts* opts, const void* K, int64_t ldK, const
                          void* stream);
 
 /* ---- measurement helpers -----------------------------------------------------------------
- * A plain device copy dst <- src of `bytes` bytes (multiple of 16, both 16-byte aligned) with
+ * fsk_dense_profile runs `reps` iterations exactly as fsk_sinkhorn_dense does in
+ * fixed-iteration mode (same kernels, same launch shapes, u and v advance), but brackets the
+ * launches of each iteration with HIP events recorded on `stream` and synchronises after each
+ * iteration.  Outputs (host): stream_ms = average time per iteration spent in the kernels that
+ * stream K (the HBM-bound ones), other_ms = average time per iteration in the small reduction
+ * kernels, stream_launches = number of K-streaming launches per iteration.  */
+int fsk_dense_profile(const fsk_opts* opts, const void* K, int64_t ldK, const void* a,
+                      const void* b, void* u, void* v, void* workspace, size_t ws_bytes, int reps,
+                      double* stream_ms, double* other_ms, int32_t* stream_launches, void* stream);
+
+/* A plain device copy dst <- src of `bytes` bytes (multiple of 16, both 16-byte aligned) with
  * the same 128-bit access pattern as the hot kernels; used to calibrate profiler byte counters
  * and to measure the achievable HBM rate next to the hot path. */
 int fsk_bench_copy(void* dst, const void* src, size_t bytes, void* stream);

@@ -29,7 +29,7 @@ EXPORTS = (
     "fsk_version", "fsk_last_error", "fsk_workspace_bytes", "fsk_kernel_from_cost",
     "fsk_kernel_from_points", "fsk_sinkhorn_dense", "fsk_marginals", "fsk_block_rowpass",
     "fsk_block_colpartial", "fsk_block_fused", "fsk_sinkhorn_log_points", "fsk_sinkhorn_batched",
-    "fsk_bench_copy", "fsk_bench_read",
+    "fsk_dense_profile", "fsk_bench_copy", "fsk_bench_read",
 )
 
 
@@ -153,6 +153,16 @@ def fsk_sinkhorn_dense(opts, K, a, b, u, v, workspace, stream=None):
                                     _vec(v), wp, wn, ctypes.byref(done), ctypes.byref(err),
                                     _stream(stream)))
     return int(done.value), float(err.value)
+
+
+def fsk_dense_profile(opts, K, a, b, u, v, workspace, reps, stream=None):
+    """Returns (stream_ms, other_ms, stream_launches) averaged per iteration over ``reps``."""
+    wp, wn = _ws(workspace)
+    t_stream, t_other, launches = ctypes.c_double(0.0), ctypes.c_double(0.0), ctypes.c_int32(0)
+    _check(lib().fsk_dense_profile(ctypes.byref(opts), _p(K), _ld(K), _vec(a), _vec(b), _vec(u),
+                                   _vec(v), wp, wn, ctypes.c_int(reps), ctypes.byref(t_stream),
+                                   ctypes.byref(t_other), ctypes.byref(launches), _stream(stream)))
+    return float(t_stream.value), float(t_other.value), int(launches.value)
 
 
 def fsk_marginals(opts, K, a, u, v, row_marginal, col_marginal, workspace, want_err=False,

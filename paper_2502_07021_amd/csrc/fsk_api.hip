@@ -93,7 +93,7 @@ static DenseWs dense_ws(const fsk_opts* o) {
   w.ld_ws = (int64_t)align_up((size_t)o->n, 64);
   const int rows_blk = o->n / o->c;
   size_t rows = (size_t)col_strips(o->n);
-  FusedPlan p = fused_plan(o->dtype, o->n, rows_blk);
+  FusedPlan p = fused_plan(o->dtype, o->n, rows_blk, o->c);
   int wgs = p.ok ? p.wgs : 0;
   if (p.ok && device_cu_count() == 0) wgs = p.groups < 1024 ? p.groups : 1024;  // no device: be generous
   if ((size_t)o->c * wgs > rows) rows = (size_t)o->c * wgs;
@@ -170,10 +170,13 @@ int fsk_kernel_from_points(const fsk_opts* opts, const void* x, const void* y, i
   return FSK_OK;
 }
 
-// One dense iteration, enqueued.
+// One dense iteration, enqueued.  With `ev` (three events) the K-streaming launches lie
+// between ev[0] and ev[1] and the small reduction launches between ev[1] and ev[2];
+// *stream_launches (if given) receives the number of K-streaming launches.
 static int dense_iteration(const fsk_opts* o, const DenseWs& w, const char* K, int64_t ld,
                            const char* a, const char* b, char* u, char* v, char* ws,
-                           hipStream_t st) {
+                           hipStream_t st, hipEvent_t* ev = nullptr,
+                           int32_t* stream_launches = nullptr) {
   const int n = o->n, c = o->c, m = n / c, dt = o->dtype;
   const size_t s = elem_size(dt);
   const int epi = epi_of(o);
@@ -181,13 +184,18 @@ static int dense_iteration(const fsk_opts* o, const DenseWs& w, const char* K, i
   int flow = o->flow;
   FusedPlan plan{};
   if (flow == FSK_FLOW_FUSED) {
-    plan = fused_plan(dt, n, m);
+    plan = fused_plan(dt, n, m, c);
     // rows too long to hold in registers, or an update the fused kernel does not carry
     if (!plan.ok || epi == kEpiDampGeom) flow = FSK_FLOW_TWO_PASS;
   }
+  if (ev) FSK_HIP(hipEventRecord(ev[0], st));
   if (flow == FSK_FLOW_FUSED) {
     FSK_TRY(launch_fused(dt, plan, K, ld, n, m, c, a, v, u, u, partial, w.ld_ws, epi, o->eta, st));
-    return launch_colreduce(dt, partial, w.ld_ws, c * plan.wgs, 0, n, b, v, v, epi, o->eta, st);
+    if (ev) FSK_HIP(hipEventRecord(ev[1], st));
+    FSK_TRY(launch_colreduce(dt, partial, w.ld_ws, c * plan.wgs, 0, n, b, v, v, epi, o->eta, st));
+    if (ev) FSK_HIP(hipEventRecord(ev[2], st));
+    if (stream_launches) *stream_launches = 1;
+    return FSK_OK;
   }
   for (int j = 0; j < c; ++j) {  // worker j: u_{I_j} from its row slab and the shared v
     const size_t off = (size_t)j * m;
@@ -196,13 +204,22 @@ static int dense_iteration(const fsk_opts* o, const DenseWs& w, const char* K, i
   }
   if (flow == FSK_FLOW_TWO_PASS) {
     FSK_TRY(launch_colpartial(dt, K, ld, n, n, 0, n, u, partial, w.ld_ws, st));
-    return launch_colreduce(dt, partial, w.ld_ws, col_strips(n), 0, n, b, v, v, epi, o->eta, st);
+    if (ev) FSK_HIP(hipEventRecord(ev[1], st));
+    FSK_TRY(launch_colreduce(dt, partial, w.ld_ws, col_strips(n), 0, n, b, v, v, epi, o->eta, st));
+    if (ev) FSK_HIP(hipEventRecord(ev[2], st));
+    if (stream_launches) *stream_launches = c + 1;
+    return FSK_OK;
   }
   for (int j = 0; j < c; ++j) {  // worker j: r_{I_j} = (K_{:,I_j})^T u from its column slab
     FSK_TRY(launch_colpartial(dt, K, ld, n, n, j * m, (j + 1) * m, u, partial, w.ld_ws, st));
     FSK_TRY(launch_colreduce(dt, partial, w.ld_ws, col_strips(n), j * m, (j + 1) * m, b, v, v, epi,
                              o->eta, st));
   }
+  if (ev) {  // the column-slab launches alternate with their reductions: counted as one span
+    FSK_HIP(hipEventRecord(ev[1], st));
+    FSK_HIP(hipEventRecord(ev[2], st));
+  }
+  if (stream_launches) *stream_launches = 2 * c;
   return FSK_OK;
 }
 
@@ -253,6 +270,49 @@ int fsk_sinkhorn_dense(const fsk_opts* opts, const void* K, int64_t ldK, const v
   }
   if (iters_done) *iters_done = done;
   if (err) *err = e;
+  return FSK_OK;
+}
+
+int fsk_dense_profile(const fsk_opts* opts, const void* K, int64_t ldK, const void* a,
+                      const void* b, void* u, void* v, void* workspace, size_t ws_bytes, int reps,
+                      double* stream_ms, double* other_ms, int32_t* stream_launches, void* stream) {
+  clear_error();
+  FSK_TRY(check_common(opts));
+  if (opts->m != 1) return set_error(FSK_EINVAL, "dense call takes m = 1");
+  if (reps < 1) return set_error(FSK_EINVAL, "reps = %d must be >= 1", reps);
+  FSK_TRY(check_matrix("K", K, ldK, opts->n, opts->dtype));
+  FSK_TRY(check_vec("a", a, false));
+  FSK_TRY(check_vec("b", b, false));
+  FSK_TRY(check_vec("u", u, true));
+  FSK_TRY(check_vec("v", v, true));
+  const DenseWs w = dense_ws(opts);
+  if (!workspace || ws_bytes < w.total)
+    return set_error(FSK_EWORKSPACE, "dense call needs %zu workspace bytes, got %zu", w.total, ws_bytes);
+  hipStream_t st = (hipStream_t)stream;
+  hipEvent_t ev[3];
+  for (int k = 0; k < 3; ++k) FSK_HIP(hipEventCreate(&ev[k]));
+  double t_stream = 0.0, t_other = 0.0;
+  int32_t launches = 0;
+  int rc = FSK_OK;
+  for (int it = 0; it < reps && rc == FSK_OK; ++it) {
+    rc = dense_iteration(opts, w, (const char*)K, ldK, (const char*)a, (const char*)b, (char*)u,
+                         (char*)v, (char*)workspace, st, ev, &launches);
+    if (rc != FSK_OK) break;
+    if (hipEventSynchronize(ev[2]) != hipSuccess) { rc = set_error(FSK_EHIP, "hipEventSynchronize failed"); break; }
+    float ms01 = 0.f, ms12 = 0.f;
+    if (hipEventElapsedTime(&ms01, ev[0], ev[1]) != hipSuccess ||
+        hipEventElapsedTime(&ms12, ev[1], ev[2]) != hipSuccess) {
+      rc = set_error(FSK_EHIP, "hipEventElapsedTime failed");
+      break;
+    }
+    t_stream += ms01;
+    t_other += ms12;
+  }
+  for (int k = 0; k < 3; ++k) (void)hipEventDestroy(ev[k]);
+  if (rc != FSK_OK) return rc;
+  if (stream_ms) *stream_ms = t_stream / reps;
+  if (other_ms) *other_ms = t_other / reps;
+  if (stream_launches) *stream_launches = launches;
   return FSK_OK;
 }
 
@@ -333,7 +393,7 @@ int fsk_block_fused(const fsk_opts* opts, const void* K_slab, int64_t ldK, int32
   FSK_TRY(check_vec("v_full", v_full, true));
   FSK_TRY(check_vec("u_slab", u_slab, false));
   FSK_TRY(check_vec("s_partial", s_partial, false));
-  const FusedPlan plan = fused_plan(opts->dtype, opts->n, rows);
+  const FusedPlan plan = fused_plan(opts->dtype, opts->n, rows, 1);
   if (!plan.ok)
     return set_error(FSK_EUNSUPPORTED, "n = %d is too long for the register-resident fused kernel",
                      opts->n);

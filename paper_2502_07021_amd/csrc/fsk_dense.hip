@@ -48,7 +48,7 @@ __global__ __launch_bounds__(256) void rowpass_kernel(const T* __restrict__ K, i
     const Pack<T> vv = load_pack(vin + (int64_t)c * W);
 #pragma unroll
     for (int r = 0; r < ROWS; ++r) {
-      const Pack<T> kk = load_pack(rowp[r] + (int64_t)c * W);
+      const Pack<T> kk = load_pack_stream(rowp[r] + (int64_t)c * W);
 #pragma unroll
       for (int e = 0; e < W; ++e) acc[r] = fma(kk.e[e], vv.e[e], acc[r]);
     }
@@ -126,7 +126,7 @@ __global__ __launch_bounds__(256) void colpartial_kernel(const T* __restrict__ K
 #pragma unroll 8
   for (int i = i0; i < i1; ++i) {
     const T ui = u[i];
-    const Pack<T> kk = load_pack(kp);
+    const Pack<T> kk = load_pack_stream(kp);
     kp += ld;
 #pragma unroll
     for (int e = 0; e < W; ++e) acc.e[e] = fma(kk.e[e], ui, acc.e[e]);
@@ -220,7 +220,7 @@ int launch_colreduce(int dtype, const void* partial, int64_t ld_ws, int n_partia
 // workgroups of a block so every compute unit streams the same number of rows.
 template <typename T, int VPT, int R, bool EXACT>
 __global__ __launch_bounds__(512) void fused_kernel(const T* __restrict__ K, int64_t ld, int n,
-                                                    int rows, const T* marg,
+                                                    int rows, int nblk, int gb, const T* marg,
                                                     const T* __restrict__ vin, const T* old_u,
                                                     T* u_out, T* __restrict__ partial,
                                                     int64_t ld_ws, T eta) {
@@ -233,10 +233,14 @@ __global__ __launch_bounds__(512) void fused_kernel(const T* __restrict__ K, int
   T* red = v_lds + VPT * NT * W;              // [2][R][NW]
 
   const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
-  const int G = gridDim.x, w = blockIdx.x, blk = blockIdx.y;
+  // The grid is `nb` teams of `gb` workgroups.  Team `team` owns the row blocks team,
+  // team + nb, ...; inside a block its row groups are dealt round-robin to the team's
+  // workgroups, so different blocks stream concurrently on disjoint sets of compute units.
+  const int G = gb, w = blockIdx.x % gb, team = blockIdx.x / gb, nb = gridDim.x / gb;
   const int nvec = (n + W - 1) / W, nvec_full = n / W;
-  const int64_t rbase = (int64_t)blk * rows;  // first row of this row block
-  const int groups = (rows + R - 1) / R;
+  const int groups = (rows + R - 1) / R;               // row groups per row block
+  const int spb = (groups + G - 1) / G;                // steps this workgroup spends on one block
+  const int total = ((nblk - team + nb - 1) / nb) * spb;  // steps over all blocks of the team
   const bool damped = eta < T(1);
 
   // stage v into LDS
@@ -264,9 +268,19 @@ __global__ __launch_bounds__(512) void fused_kernel(const T* __restrict__ K, int
 #pragma unroll
     for (int e = 0; e < W; ++e) acc[i].e[e] = T(0);
 
-  // Row groups past the end are clamped to the last group (a redundant, in-bounds
+  // Teams start their sweep at different offsets inside their blocks (a rotation of the
+  // group index), which keeps the concurrent streams of different teams from marching
+  // through DRAM in lock step.
+  const int rot = (team * 17) % groups;
+  auto rotate = [&](int g) { return g < groups ? (g + rot) % groups : g; };
+
+  // Step t of this workgroup is row group w + (t % spb)*G of row block t / spb.  Steps
+  // and rows past the end are clamped to the last valid one (a redundant, in-bounds
   // read) and contribute nothing because their u is forced to 0 in process().
-  auto load_group = [&](Pack<T>(&buf)[R][VPT], T(&mg)[R], T(&od)[R], int g) {
+  auto load_group = [&](Pack<T>(&buf)[R][VPT], T(&mg)[R], T(&od)[R], int t) {
+    t = t < total ? t : total - 1;
+    const int64_t rbase = (int64_t)(team + (t / spb) * nb) * rows;
+    const int g = rotate(w + (t % spb) * G);
 #pragma unroll
     for (int r = 0; r < R; ++r) {
       int row = g * R + r;
@@ -277,11 +291,11 @@ __global__ __launch_bounds__(512) void fused_kernel(const T* __restrict__ K, int
 #pragma unroll
       for (int i = 0; i < VPT; ++i) {
         if (EXACT) {
-          buf[r][i] = load_pack(kp + i * NT * W);
+          buf[r][i] = load_pack_stream(kp + i * NT * W);
         } else {
           const int vi = i * NT + tid;
           const int back = vi < nvec ? 0 : (vi - (nvec - 1)) * W;  // clamp to the last pack
-          Pack<T> p = load_pack(kp + i * NT * W - back);
+          Pack<T> p = load_pack_stream(kp + i * NT * W - back);
 #pragma unroll
           for (int e = 0; e < W; ++e)
             if (vi * W + e >= n) p.e[e] = T(0);  // padding columns and clamped duplicates
@@ -291,7 +305,10 @@ __global__ __launch_bounds__(512) void fused_kernel(const T* __restrict__ K, int
     }
   };
 
-  auto process = [&](Pack<T>(&buf)[R][VPT], T(&mg)[R], T(&od)[R], int g, int parity) {
+  auto process = [&](Pack<T>(&buf)[R][VPT], T(&mg)[R], T(&od)[R], int t, int parity) {
+    const int blk = team + (t / spb) * nb;
+    const int64_t rbase = (int64_t)blk * rows;
+    const int g = rotate(w + (t % spb) * G);
     T d[R];
 #pragma unroll
     for (int r = 0; r < R; ++r) d[r] = T(0);
@@ -327,35 +344,42 @@ __global__ __launch_bounds__(512) void fused_kernel(const T* __restrict__ K, int
 #pragma unroll
         for (int e = 0; e < W; ++e) acc[i].e[e] = fma(buf[r][i].e[e], ur, acc[i].e[e]);
     }
+    if (t % spb == spb - 1) {  // last step of a row block: hand over this block's contribution
+      T* prow = partial + ((int64_t)blk * G + w) * ld_ws;
+#pragma unroll
+      for (int i = 0; i < VPT; ++i) {
+        const int vi = i * NT + tid;
+        if (EXACT || vi < nvec) store_pack(prow + (int64_t)vi * W, acc[i]);
+#pragma unroll
+        for (int e = 0; e < W; ++e) acc[i].e[e] = T(0);
+      }
+    }
   };
 
-  // w < groups is guaranteed by the launcher.  Two register sets alternate: while one
-  // group is being reduced the next one is already in flight.
-  int g = w;
-  load_group(bufA, mgA, odA, g);
-  while (true) {
-    load_group(bufB, mgB, odB, g + G);
-    process(bufA, mgA, odA, g, 0);
-    g += G;
-    if (g >= groups) break;
-    load_group(bufA, mgA, odA, g + G);
-    process(bufB, mgB, odB, g, 1);
-    g += G;
-    if (g >= groups) break;
-  }
-
-  T* prow = partial + ((int64_t)blk * G + w) * ld_ws;
-#pragma unroll
-  for (int i = 0; i < VPT; ++i) {
-    const int vi = i * NT + tid;
-    if (EXACT || vi < nvec) store_pack(prow + (int64_t)vi * W, acc[i]);
+  // Two register sets alternate: while one group is being reduced the next one is
+  // already in flight, across row-block boundaries too.
+  load_group(bufA, mgA, odA, 0);
+  for (int t = 0; t < total; t += 2) {
+    load_group(bufB, mgB, odB, t + 1);
+    process(bufA, mgA, odA, t, 0);
+    if (t + 1 >= total) break;
+    load_group(bufA, mgA, odA, t + 2);
+    process(bufB, mgB, odB, t + 1, 1);
   }
 }
 
 // Rows held in one register set: 16 packs (64 VGPRs) per thread, at most 8 rows.
 constexpr int fused_rows_per_group(int vpt) { return 16 / vpt < 8 ? 16 / vpt : 8; }
 
-FusedPlan fused_plan(int dtype, int n, int rows) {
+int fused_teams(const FusedPlan& plan, int c) {
+  int cus = device_cu_count();
+  if (cus < 1) cus = 1;
+  int teams = cus / plan.wgs;
+  if (teams < 1) teams = 1;
+  return teams < c ? teams : c;
+}
+
+FusedPlan fused_plan(int dtype, int n, int rows, int c) {
   FusedPlan p{};
   const int W = pack_width(dtype);
   const int nvec = (n + W - 1) / W;
@@ -366,9 +390,10 @@ FusedPlan fused_plan(int dtype, int n, int rows) {
   p.vpt = vpt;
   p.r = fused_rows_per_group(vpt);
   p.groups = (rows + p.r - 1) / p.r;
-  const int cus = device_cu_count();
-  p.wgs = p.groups < cus ? p.groups : cus;
-  if (p.wgs < 1) p.wgs = 1;
+  // workgroups per row block: the device's compute units shared out among the c blocks
+  int per_block = device_cu_count() / (c < 1 ? 1 : c);
+  if (per_block < 1) per_block = 1;
+  p.wgs = p.groups < per_block ? p.groups : per_block;
   p.lds_bytes = (size_t)vpt * 512 * 16 + (size_t)2 * p.r * 8 * elem_size(dtype);
   return p;
 }
@@ -385,9 +410,10 @@ static int fused_typed(const FusedPlan& plan, const void* K, int64_t ld, int n, 
                                 hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024));
     attr_set = true;
   }
-  dim3 grid(plan.wgs, c), block(512);
-  hipLaunchKernelGGL(kern, grid, block, plan.lds_bytes, stream, (const T*)K, ld, n, rows,
-                     (const T*)marg, (const T*)vin, (const T*)old_u, (T*)u_out, (T*)partial, ld_ws,
+  const int teams = fused_teams(plan, c);
+  dim3 grid(plan.wgs * teams), block(512);
+  hipLaunchKernelGGL(kern, grid, block, plan.lds_bytes, stream, (const T*)K, ld, n, rows, c,
+                     plan.wgs, (const T*)marg, (const T*)vin, (const T*)old_u, (T*)u_out, (T*)partial, ld_ws,
                      (T)eta);
   FSK_LAUNCH_CHECK("fused_kernel");
   return FSK_OK;

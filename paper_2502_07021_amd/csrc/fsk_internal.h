@@ -65,7 +65,10 @@ struct FusedPlan {
   int wgs;          // workgroups per row block (= partial rows per block)
   size_t lds_bytes;
 };
-FusedPlan fused_plan(int dtype, int n, int rows);
+// `c` row blocks of `rows` rows each share the device: each block gets cus/c workgroups.
+FusedPlan fused_plan(int dtype, int n, int rows, int c);
+// Number of workgroup teams launched (each team walks the blocks team, team+teams, ...).
+int fused_teams(const FusedPlan& plan, int c);
 
 // For each of `c` row blocks of `rows` rows (block b starts at row b*rows of K, marg, old_u,
 // u_out): u_out = epilogue(marg, K v, old_u) and partial[(b*wgs + w)][:] = contribution of the
