@@ -90,6 +90,14 @@ def main() -> int:
     ws = api.alloc_workspace(opts, api.FSK_MODE_DENSE)
     u = torch.ones(n, device="cuda"); v = torch.ones(n, device="cuda")
 
+    # one plain 1 GiB device copy: the known-size stream against which profiler byte
+    # counters (FETCH_SIZE / WRITE_SIZE) of the same run are scaled
+    cal_src = torch.zeros(1 << 28, dtype=torch.float32, device="cuda")
+    cal_dst = torch.empty_like(cal_src)
+    api.fsk_bench_copy(cal_dst, cal_src)
+    torch.cuda.synchronize()
+    del cal_src, cal_dst
+
     def run(iters):
         o = api.make_opts(n, torch.float32, c=c, max_iters=iters, flow=args.flow)
         api.fsk_sinkhorn_dense(o, K, a, b, u, v, ws)
