@@ -74,12 +74,6 @@ static int check_vec(const char* name, const void* p, bool need16) {
   return FSK_OK;
 }
 
-#define FSK_TRY(expr)          \
-  do {                         \
-    int fsk_rc_ = (expr);      \
-    if (fsk_rc_ != FSK_OK) return fsk_rc_; \
-  } while (0)
-
 // ------------------------------------------------------------------ workspace
 struct DenseWs {
   int64_t ld_ws;        // elements per partial row
@@ -125,7 +119,8 @@ size_t fsk_workspace_bytes(const fsk_opts* opts, int mode, int d) {
   if (check_common(opts) != FSK_OK) return 0;
   switch (mode) {
     case FSK_MODE_DENSE: return dense_ws(opts).total;
-    case FSK_MODE_SETUP: (void)d; return align_up(max_sqdist_scratch_doubles(opts->n) * 8, 256) + 256;
+    case FSK_MODE_LOG: return log_workspace_bytes(opts->n, d);
+    case FSK_MODE_SETUP: return align_up(max_sqdist_scratch_doubles(opts->n) * 8, 256) + 256;
     default: return 0;
   }
 }
@@ -412,9 +407,24 @@ int fsk_block_fused(const fsk_opts* opts, const void* K_slab, int64_t ldK, int32
 }
 
 // ------------------------------------------------------------- not built yet
-int fsk_sinkhorn_log_points(const fsk_opts*, const void*, const void*, int, double, const void*,
-                            const void*, void*, void*, void*, size_t, int32_t*, double*, void*) {
-  return set_error(FSK_EUNSUPPORTED, "log-domain path is not built yet");
+int fsk_sinkhorn_log_points(const fsk_opts* opts, const void* x, const void* y, int d, double eps,
+                            const void* a, const void* b, void* f, void* g, void* workspace,
+                            size_t ws_bytes, int32_t* iters_done, double* err, void* stream) {
+  clear_error();
+  FSK_TRY(check_common(opts));
+  if (opts->m != 1) return set_error(FSK_EINVAL, "log-domain call takes m = 1");
+  if (opts->c != 1) return set_error(FSK_EUNSUPPORTED, "log-domain call takes c = 1");
+  if (!(eps > 0.0)) return set_error(FSK_EINVAL, "eps = %g must be positive", eps);
+  if (d < 1) return set_error(FSK_EINVAL, "d = %d must be >= 1", d);
+  FSK_TRY(check_vec("x", x, false));
+  FSK_TRY(check_vec("y", y, false));
+  FSK_TRY(check_vec("a", a, false));
+  FSK_TRY(check_vec("b", b, false));
+  FSK_TRY(check_vec("f", f, false));
+  FSK_TRY(check_vec("g", g, false));
+  if (workspace && !aligned16(workspace)) return set_error(FSK_EALIGN, "workspace is not 16-byte aligned");
+  return run_sinkhorn_log_points(opts, x, y, d, eps, a, b, f, g, workspace, ws_bytes, iters_done,
+                                 err, (hipStream_t)stream);
 }
 
 int fsk_sinkhorn_batched(const fsk_opts*, const void*, int64_t, const void*, const void*, void*,

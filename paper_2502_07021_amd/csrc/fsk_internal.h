@@ -27,6 +27,12 @@ void clear_error();
                               hipGetErrorString(fsk_e_));                                 \
   } while (0)
 
+#define FSK_TRY(expr)                       \
+  do {                                      \
+    int fsk_rc_ = (expr);                   \
+    if (fsk_rc_ != FSK_OK) return fsk_rc_;  \
+  } while (0)
+
 inline size_t elem_size(int dtype) { return dtype == FSK_F64 ? 8 : 4; }
 inline int pack_width(int dtype) { return dtype == FSK_F64 ? 2 : 4; }
 inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
@@ -90,6 +96,13 @@ int launch_max_sqdist(int dtype, const void* x, const void* y, int n, int d, dou
 int launch_gibbs_from_points(int dtype, const void* x, const void* y, int n, int d, double eps,
                              const double* cmax_dev, void* K, int64_t ldK, hipStream_t stream);
 size_t max_sqdist_scratch_doubles(int n);
+
+// ------------------------------------------------------------------ log-domain path
+size_t log_workspace_bytes(int n, int d);  // 0 if the point dimension is not supported
+int run_sinkhorn_log_points(const fsk_opts* o, const void* x, const void* y, int d, double eps,
+                            const void* a, const void* b, void* f, void* g, void* workspace,
+                            size_t ws_bytes, int32_t* iters_done, double* err_out,
+                            hipStream_t st);
 
 // ------------------------------------------------------------------ measurement helpers
 int launch_copy(void* dst, const void* src, size_t bytes, hipStream_t stream);

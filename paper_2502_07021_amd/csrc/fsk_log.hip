@@ -1,0 +1,359 @@
+// Log-domain Sinkhorn on point clouds for gfx950, cost evaluated on the fly (the
+// stabilised form the paper names in Sec. 1 / Sec. 2.1, with the kernel applied
+// implicitly as in the Remark of Sec. 4.1).  One half-step is
+//
+//     f_i <- eps ln a_i - eps LSE_j((g_j - ||x_i - y_j||^2)/eps)
+//
+// and the g-update is the same operation with the two clouds' roles swapped.
+//
+// Arithmetic.  Everything is moved to base 2 with s = log2(e)/eps and both clouds
+// are shifted by their common mean mu (distances do not change):
+//
+//     s (g_j - C_ij) = beta_j - s|x~_i|^2 + (2 s x~_i) . y~_j,   beta_j = s g_j - s|y~_j|^2
+//
+// so a pair costs d FMAs.  The expansion cancels badly in fp32 (terms of size
+// ~10^3 for a result known to ~10^-5), so the dot product runs in fp64 -- on
+// gfx950 a v_fma_f64 issues at the same rate as an unpacked v_fma_f32 -- and only
+// the exponential and the running sum are fp32 (v_exp_f32).  The potentials are
+// kept in fp64 shadow copies for the whole call; the caller's fp32 arrays are
+// read once at the start and written after every update.
+//
+// Work split.  A workgroup of 256 threads owns 256 rows (one per lane, the row's
+// scaled coordinates live in registers) and one slice of the columns; all four
+// waves walk the same columns, whose coordinates arrive through uniform (scalar)
+// loads and feed the FMAs straight from scalar registers.  One row per lane keeps
+// the scalar-register live ranges to a single column, which the compiler needs in
+// order not to shuffle them through vector lanes.  Each lane keeps (reference exponent, sum of 2^(z - reference)); the
+// reference is raised lazily, only when a chunk exceeds it by 2^16, so the
+// common case has no rescaling and every term that matters is rounded to fp32 at a
+// magnitude below 16.  A second kernel merges the column slices in
+// fixed order and applies the update.
+#include <cmath>
+#include <type_traits>
+
+#include "fsk_device.h"
+#include "fsk_internal.h"
+
+namespace fsk {
+
+constexpr int kLogRowsPerLane = 1;
+constexpr int kLogThreads = 256;
+constexpr int kLogRowTile = kLogThreads * kLogRowsPerLane;
+constexpr int kLogChunk = 4;          // columns reduced together
+constexpr float kLogRaise = 16.0f;    // raise the reference when a chunk exceeds it by this much
+
+// ---------------------------------------------------------------- preparation
+// mu[k] = mean over both clouds of coordinate k (fp64, fixed order).
+template <typename T>
+__global__ __launch_bounds__(1024) void log_mean_kernel(const T* __restrict__ x,
+                                                        const T* __restrict__ y, int n, int d,
+                                                        double* __restrict__ mu) {
+  __shared__ double sm[16];
+  for (int k = 0; k < d; ++k) {
+    double s = 0.0;
+    for (int i = threadIdx.x; i < n; i += 1024)
+      s += (double)x[(int64_t)i * d + k] + (double)y[(int64_t)i * d + k];
+    s = wave_sum(s);
+    if ((threadIdx.x & 63) == 0) sm[threadIdx.x >> 6] = s;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+      double t = 0.0;
+      for (int w = 0; w < 16; ++w) t += sm[w];
+      mu[k] = t / (2.0 * n);
+    }
+    __syncthreads();
+  }
+}
+
+// Per point of one cloud: centred coordinates (column role), 2s-scaled centred
+// coordinates (row role), s|p~|^2, ln w, the fp64 shadow potential and its beta.
+template <typename T>
+__global__ __launch_bounds__(256) void log_prep_kernel(const T* __restrict__ p,
+                                                       const T* __restrict__ w,
+                                                       const T* __restrict__ pot, int n, int d,
+                                                       int dp, double s,
+                                                       const double* __restrict__ mu,
+                                                       double* __restrict__ pc,
+                                                       double* __restrict__ ps,
+                                                       double* __restrict__ norm2,
+                                                       double* __restrict__ lnw,
+                                                       double* __restrict__ potd,
+                                                       double* __restrict__ beta) {
+  const int i = blockIdx.x * 256 + threadIdx.x;
+  if (i >= n) return;
+  double nn = 0.0;
+  for (int k = 0; k < dp; ++k) {
+    const double c = k < d ? (double)p[(int64_t)i * d + k] - mu[k] : 0.0;
+    pc[(int64_t)i * dp + k] = c;
+    ps[(int64_t)i * dp + k] = 2.0 * s * c;
+    nn += c * c;
+  }
+  norm2[i] = s * nn;
+  lnw[i] = log((double)w[i]);
+  const double f = (double)pot[i];
+  potd[i] = f;
+  beta[i] = s * f - s * nn;
+}
+
+// ------------------------------------------------------------------ main kernel
+// part_m[i*slices + sl], part_s[...]: reference exponent and sum of
+// 2^(z_ij - reference) over the columns j of slice sl, z_ij = beta_j + ps_i . qc_j.
+template <int DP>
+__global__ __launch_bounds__(kLogThreads) void log_lse_kernel(const double* __restrict__ ps,
+                                                              const double* __restrict__ qc,
+                                                              const double* __restrict__ beta,
+                                                              int n_rows, int n_cols,
+                                                              int cols_per_slice, int slices,
+                                                              double* __restrict__ part_m,
+                                                              float* __restrict__ part_s) {
+  constexpr int RI = kLogRowsPerLane;
+  constexpr int J = kLogChunk;
+  const int tid = threadIdx.x;
+  const int sl = blockIdx.y;
+  const int jb = sl * cols_per_slice;
+  const int je = jb + cols_per_slice < n_cols ? jb + cols_per_slice : n_cols;
+
+  double xs[RI][DP];
+  int row[RI];
+#pragma unroll
+  for (int r = 0; r < RI; ++r) {
+    row[r] = blockIdx.x * kLogRowTile + r * kLogThreads + tid;
+    const int rc = row[r] < n_rows ? row[r] : n_rows - 1;  // clamp; dropped at the store
+#pragma unroll
+    for (int k = 0; k < DP; ++k) xs[r][k] = ps[(int64_t)rc * DP + k];
+  }
+
+  // reference exponent = z of the slice's first column; sums start empty
+  double mref[RI];
+  float sum[RI];
+  {
+    const double b0 = beta[jb];
+#pragma unroll
+    for (int r = 0; r < RI; ++r) {
+      double z = b0;
+#pragma unroll
+      for (int k = 0; k < DP; ++k) z = fma(xs[r][k], qc[(int64_t)jb * DP + k], z);
+      mref[r] = z;
+      sum[r] = 0.f;
+    }
+  }
+
+  auto chunk = [&](int j0, auto jj_tag) {
+    constexpr int JJ = decltype(jj_tag)::value;
+    double zd[RI][JJ];
+#pragma unroll
+    for (int t = 0; t < JJ; ++t) {
+      const double* q = qc + (int64_t)(j0 + t) * DP;  // uniform address: scalar loads
+      const double bj = beta[j0 + t];
+      double z[RI];
+#pragma unroll
+      for (int r = 0; r < RI; ++r) z[r] = bj - mref[r];
+#pragma unroll
+      for (int k = 0; k < DP; ++k) {
+        const double qk = q[k];
+#pragma unroll
+        for (int r = 0; r < RI; ++r) z[r] = fma(xs[r][k], qk, z[r]);
+      }
+#pragma unroll
+      for (int r = 0; r < RI; ++r) zd[r][t] = z[r];
+    }
+#pragma unroll
+    for (int r = 0; r < RI; ++r) {
+      float zf[JJ];
+#pragma unroll
+      for (int t = 0; t < JJ; ++t) zf[t] = (float)zd[r][t];
+      float cm = zf[0];
+#pragma unroll
+      for (int t = 1; t < JJ; ++t) cm = fmaxf(cm, zf[t]);
+      if (cm > kLogRaise) {
+        // rare: move the reference up to this chunk's maximum, exactly (in fp64), so that
+        // the terms near the new maximum are rounded at their final, small magnitude
+        double zmax = zd[r][0];
+#pragma unroll
+        for (int t = 1; t < JJ; ++t) zmax = zd[r][t] > zmax ? zd[r][t] : zmax;
+        mref[r] += zmax;
+        sum[r] *= __builtin_amdgcn_exp2f(-(float)zmax);
+#pragma unroll
+        for (int t = 0; t < JJ; ++t) zf[t] = (float)(zd[r][t] - zmax);
+      }
+#pragma unroll
+      for (int t = 0; t < JJ; ++t) sum[r] += __builtin_amdgcn_exp2f(zf[t]);
+    }
+  };
+
+  int j = jb;
+  for (; j + J <= je; j += J) chunk(j, std::integral_constant<int, J>{});
+  for (; j < je; ++j) chunk(j, std::integral_constant<int, 1>{});
+
+#pragma unroll
+  for (int r = 0; r < RI; ++r) {
+    if (row[r] < n_rows) {
+      part_m[(int64_t)row[r] * slices + sl] = mref[r];
+      part_s[(int64_t)row[r] * slices + sl] = sum[r];
+    }
+  }
+}
+
+// ------------------------------------------------------------------ merge + update
+// L2_i = log2 sum_j 2^(z_ij) from the slices (merged in slice order), then
+//   pot_new = eps (ln w_i - ln2 (L2_i - s|p~_i|^2)).
+// mode 0: store pot_new (fp64 shadow, caller's array, beta for the column role).
+// mode 1: store |w_i exp((pot_i - pot_new)/eps) - w_i| -- the row-marginal error of the
+//         plan exp((f_i + g_j - C_ij)/eps) with the potentials as they stand.
+template <typename T>
+__global__ __launch_bounds__(256) void log_finalize_kernel(const double* __restrict__ part_m,
+                                                           const float* __restrict__ part_s,
+                                                           int slices, int n,
+                                                           const double* __restrict__ norm2,
+                                                           const double* __restrict__ lnw, double eps,
+                                                           double s, int mode, double* potd,
+                                                           T* __restrict__ pot_out,
+                                                           double* __restrict__ beta_out,
+                                                           double* __restrict__ errvec) {
+  const int i = blockIdx.x * 256 + threadIdx.x;
+  if (i >= n) return;
+  double M = part_m[(int64_t)i * slices];
+  for (int k = 1; k < slices; ++k) {
+    const double m = part_m[(int64_t)i * slices + k];
+    M = m > M ? m : M;
+  }
+  double S = 0.0;
+  for (int k = 0; k < slices; ++k)
+    S += (double)part_s[(int64_t)i * slices + k] * exp2(part_m[(int64_t)i * slices + k] - M);
+  const double L2 = M + log2(S);
+  const double ln2 = 0.693147180559945309417;
+  const double pot_new = eps * (lnw[i] - ln2 * (L2 - norm2[i]));
+  if (mode == 0) {
+    potd[i] = pot_new;
+    pot_out[i] = (T)pot_new;
+    beta_out[i] = s * pot_new - norm2[i];
+  } else {
+    const double w = exp(lnw[i]);
+    errvec[i] = fabs(w * exp((potd[i] - pot_new) / eps) - w);
+  }
+}
+
+// ------------------------------------------------------------------ host side
+struct LogWs {
+  int dp, slices, cols_per_slice;
+  size_t mu, xc, xs, yc, ys, nx2, ny2, lna, lnb, fd, gd, bx, by, pm, psum, err, scalar, total;
+};
+
+static int log_pad_dim(int d) { return d <= 4 ? 4 : d <= 8 ? 8 : d <= 16 ? 16 : d <= 32 ? 32 : 0; }
+
+static LogWs log_ws(int n, int d) {
+  LogWs w{};
+  w.dp = log_pad_dim(d);
+  // enough column slices for ~8 workgroups (32 waves) per compute unit, at most 64, at least
+  // 256 columns each
+  int cus = device_cu_count();
+  if (cus < 1) cus = 256;
+  const int row_tiles = (n + kLogRowTile - 1) / kLogRowTile;
+  int slices = (8 * cus + row_tiles - 1) / row_tiles;
+  const int max_by_cols = n / 256 > 0 ? n / 256 : 1;
+  if (slices > max_by_cols) slices = max_by_cols;
+  if (slices > 64) slices = 64;
+  if (slices < 1) slices = 1;
+  w.cols_per_slice = (n + slices - 1) / slices;
+  w.slices = (n + w.cols_per_slice - 1) / w.cols_per_slice;
+  size_t off = 0;
+  auto take = [&](size_t bytes) { size_t o = off; off += align_up(bytes, 256); return o; };
+  const size_t nd = (size_t)n * (size_t)(w.dp ? w.dp : 1) * 8, nv = (size_t)n * 8;
+  w.mu = take(32 * 8);
+  w.xc = take(nd); w.xs = take(nd); w.yc = take(nd); w.ys = take(nd);
+  w.nx2 = take(nv); w.ny2 = take(nv); w.lna = take(nv); w.lnb = take(nv);
+  w.fd = take(nv); w.gd = take(nv); w.bx = take(nv); w.by = take(nv);
+  w.pm = take(nv * w.slices); w.psum = take((size_t)n * 4 * w.slices);
+  w.err = take(nv); w.scalar = take(256);
+  w.total = off;
+  return w;
+}
+
+size_t log_workspace_bytes(int n, int d) { return log_pad_dim(d) ? log_ws(n, d).total : 0; }
+
+template <int DP>
+static int launch_lse(const LogWs& w, int n, const double* ps, const double* qc, const double* beta,
+                      double* pm, float* psum, hipStream_t st) {
+  dim3 grid((n + kLogRowTile - 1) / kLogRowTile, w.slices), block(kLogThreads);
+  hipLaunchKernelGGL((log_lse_kernel<DP>), grid, block, 0, st, ps, qc, beta, n, n, w.cols_per_slice,
+                     w.slices, pm, psum);
+  FSK_LAUNCH_CHECK("log_lse_kernel");
+  return FSK_OK;
+}
+
+static int lse_dispatch(const LogWs& w, int n, const double* ps, const double* qc,
+                        const double* beta, double* pm, float* psum, hipStream_t st) {
+  switch (w.dp) {
+    case 4: return launch_lse<4>(w, n, ps, qc, beta, pm, psum, st);
+    case 8: return launch_lse<8>(w, n, ps, qc, beta, pm, psum, st);
+    case 16: return launch_lse<16>(w, n, ps, qc, beta, pm, psum, st);
+    case 32: return launch_lse<32>(w, n, ps, qc, beta, pm, psum, st);
+    default: return set_error(FSK_EUNSUPPORTED, "point dimension above 32 is not built");
+  }
+}
+
+int run_sinkhorn_log_points(const fsk_opts* o, const void* x, const void* y, int d, double eps,
+                            const void* a, const void* b, void* f, void* g, void* workspace,
+                            size_t ws_bytes, int32_t* iters_done, double* err_out,
+                            hipStream_t st) {
+  if (o->dtype != FSK_F32) return set_error(FSK_EUNSUPPORTED, "log-domain path takes fp32 inputs");
+  if (log_pad_dim(d) == 0) return set_error(FSK_EUNSUPPORTED, "point dimension %d above 32 is not built", d);
+  const int n = o->n;
+  const LogWs w = log_ws(n, d);
+  if (!workspace || ws_bytes < w.total)
+    return set_error(FSK_EWORKSPACE, "log-domain call needs %zu workspace bytes, got %zu", w.total, ws_bytes);
+  char* ws = (char*)workspace;
+  auto D = [&](size_t off) { return (double*)(ws + off); };
+  const double s = 1.4426950408889634074 / eps;
+  const float *xf = (const float*)x, *yf = (const float*)y, *af = (const float*)a,
+              *bf = (const float*)b;
+  float *ff = (float*)f, *gf = (float*)g;
+  const int nb = (n + 255) / 256;
+
+  hipLaunchKernelGGL((log_mean_kernel<float>), dim3(1), dim3(1024), 0, st, xf, yf, n, d, D(w.mu));
+  FSK_LAUNCH_CHECK("log_mean_kernel");
+  hipLaunchKernelGGL((log_prep_kernel<float>), dim3(nb), dim3(256), 0, st, xf, af, ff, n, d, w.dp, s,
+                     D(w.mu), D(w.xc), D(w.xs), D(w.nx2), D(w.lna), D(w.fd), D(w.bx));
+  FSK_LAUNCH_CHECK("log_prep_kernel");
+  hipLaunchKernelGGL((log_prep_kernel<float>), dim3(nb), dim3(256), 0, st, yf, bf, gf, n, d, w.dp, s,
+                     D(w.mu), D(w.yc), D(w.ys), D(w.ny2), D(w.lnb), D(w.gd), D(w.by));
+  FSK_LAUNCH_CHECK("log_prep_kernel");
+
+  float* psum = (float*)(ws + w.psum);
+  auto half_step = [&](bool f_side, int mode) -> int {
+    // f-update: rows = x (scaled), columns = y with beta_y; g-update: the roles swapped
+    FSK_TRY(lse_dispatch(w, n, D(f_side ? w.xs : w.ys), D(f_side ? w.yc : w.xc),
+                            D(f_side ? w.by : w.bx), D(w.pm), psum, st));
+    hipLaunchKernelGGL((log_finalize_kernel<float>), dim3(nb), dim3(256), 0, st, D(w.pm), psum,
+                       w.slices, n, D(f_side ? w.nx2 : w.ny2), D(f_side ? w.lna : w.lnb), eps, s,
+                       mode, D(f_side ? w.fd : w.gd), f_side ? ff : gf, D(f_side ? w.bx : w.by),
+                       D(w.err));
+    FSK_LAUNCH_CHECK("log_finalize_kernel");
+    return FSK_OK;
+  };
+
+  int done = 0;
+  double e = NAN;
+  for (int it = 0; it < o->max_iters; ++it) {
+    FSK_TRY(half_step(true, 0));
+    FSK_TRY(half_step(false, 0));
+    done = it + 1;
+    if (o->tol > 0.0 && (done % o->check_every == 0 || done == o->max_iters)) {
+      FSK_TRY(half_step(true, 1));  // row-marginal error of the current (f, g)
+      FSK_TRY(launch_sum_to_double(FSK_F64, D(w.err), n, D(w.scalar), st));
+      FSK_HIP(hipMemcpyAsync(&e, D(w.scalar), sizeof(double), hipMemcpyDeviceToHost, st));
+      FSK_HIP(hipStreamSynchronize(st));
+      if (!std::isfinite(e)) {
+        if (iters_done) *iters_done = done;
+        if (err_out) *err_out = e;
+        return set_error(FSK_ENONFINITE, "marginal error is not finite after %d iterations", done);
+      }
+      if (e < o->tol) break;
+    }
+  }
+  if (iters_done) *iters_done = done;
+  if (err_out) *err_out = e;
+  return FSK_OK;
+}
+
+}  // namespace fsk

@@ -1,0 +1,104 @@
+"""GPU parity of the log-domain path (cost on the fly from point clouds) against the oracle.
+
+Bar: |f - f_oracle| / eps and |g - g_oracle| / eps <= 1e-4 (this is the relative error of
+u = exp(f/eps), v = exp(g/eps), which themselves overflow fp32), and relative error of the
+row / column marginals <= 1e-4, at fixed iteration counts.  Stop iterations are compared
+only up to one polling interval: the GPU evaluates exponentials in fp32.
+"""
+import numpy as np
+import pytest
+import torch
+
+from paper_2502_07021_amd import api, workloads
+from gpu_util import dev
+
+pytestmark = pytest.mark.gpu
+
+
+def run_log(x, y, a, b, eps, iters, tol=0.0, check_every=1, f0=None, g0=None):
+    n, d = x.shape
+    opts = api.make_opts(n, torch.float32, max_iters=iters, tol=tol, check_every=check_every)
+    ws = api.alloc_workspace(opts, api.FSK_MODE_LOG, d)
+    f = torch.zeros(n, device="cuda") if f0 is None else dev(f0.astype(np.float32))
+    g = torch.zeros(n, device="cuda") if g0 is None else dev(g0.astype(np.float32))
+    done, err = api.fsk_sinkhorn_log_points(opts, dev(x), dev(y), eps, dev(a), dev(b), f, g, ws)
+    torch.cuda.synchronize()
+    return f.cpu().numpy().astype(np.float64), g.cpu().numpy().astype(np.float64), done, err
+
+
+def check_potentials(orc, x, y, a, b, eps, f, g, fo, go):
+    assert np.max(np.abs(f - fo)) / eps <= 1e-4 and np.max(np.abs(g - go)) / eps <= 1e-4
+    rows = orc.log_row_marginal_points(x, f, y, g, eps)
+    rows_o = orc.log_row_marginal_points(x, fo, y, go, eps)
+    assert np.max(np.abs(rows - rows_o) / rows_o) <= 1e-4
+    cols = orc.log_row_marginal_points(y, g, x, f, eps)      # column marginal: roles swapped
+    assert np.max(np.abs(cols - b.astype(np.float64)) / b) <= 1e-4   # exact after a g-update
+
+
+@pytest.mark.parametrize("n", [1500, 4096])
+def test_cfg4_law_fixed_iterations(orc, n):
+    w = workloads.make(4, n=n)
+    for iters in (1, 10, 100):
+        fo, go, _, _ = orc.sinkhorn_log_points(w.x, w.y, w.eps, w.a, w.b, iters)
+        f, g, done, _ = run_log(w.x, w.y, w.a, w.b, w.eps, iters)
+        assert done == iters
+        check_potentials(orc, w.x, w.y, w.a, w.b, w.eps, f, g, fo, go)
+
+
+@pytest.mark.parametrize("n,d", [(1, 16), (2, 3), (3, 1), (65, 2), (257, 5), (513, 8), (700, 16),
+                                 (300, 20), (300, 32)])
+def test_ragged_sizes_and_dimensions(orc, n, d):
+    rng = np.random.default_rng(100 * n + d)
+    x = rng.uniform(size=(n, d)).astype(np.float32); y = rng.uniform(size=(n, d)).astype(np.float32)
+    a = rng.uniform(0.5, 1.5, n); a = (a / a.sum()).astype(np.float32)
+    b = rng.uniform(0.5, 1.5, n); b = (b / b.sum()).astype(np.float32)
+    eps = 0.02 * d
+    fo, go, _, _ = orc.sinkhorn_log_points(x, y, eps, a, b, 12)
+    f, g, _, _ = run_log(x, y, a, b, eps, 12)
+    check_potentials(orc, x, y, a, b, eps, f, g, fo, go)
+
+
+def test_dimension_above_32_is_refused():
+    x = torch.zeros(8, 40, device="cuda")
+    v = torch.full((8,), 0.125, device="cuda")
+    opts = api.make_opts(8, torch.float32, max_iters=1)
+    with pytest.raises(api.FskError) as e:
+        api.fsk_sinkhorn_log_points(opts, x, x, 0.1, v, v, v.clone(), v.clone(),
+                                    torch.empty(1 << 20, dtype=torch.uint8, device="cuda"))
+    assert e.value.status == api.FSK_EUNSUPPORTED
+
+
+def test_tolerance_mode_and_cap(orc):
+    w = workloads.make(4, n=900)
+    eps = 0.05
+    fo, go, done_o, err_o = orc.sinkhorn_log_points(w.x, w.y, eps, w.a, w.b, 3000, tol=1e-5, check_every=5)
+    f, g, done, err = run_log(w.x, w.y, w.a, w.b, eps, 3000, tol=1e-5, check_every=5)
+    assert done % 5 == 0 and abs(done - done_o) <= 5 and err < 1e-5
+    fo2, go2, _, _ = orc.sinkhorn_log_points(w.x, w.y, eps, w.a, w.b, done)
+    check_potentials(orc, w.x, w.y, w.a, w.b, eps, f, g, fo2, go2)
+    rows = orc.log_row_marginal_points(w.x, f, w.y, g, eps)
+    assert err == pytest.approx(np.abs(rows - w.a).sum(), rel=0.05, abs=2e-7)
+    f, g, done, err = run_log(w.x, w.y, w.a, w.b, eps, 9, tol=1e-30, check_every=4)
+    assert done == 9 and err > 0
+
+
+def test_warm_start_continues_the_run(orc):
+    w = workloads.make(4, n=777)
+    fo, go, _, _ = orc.sinkhorn_log_points(w.x, w.y, w.eps, w.a, w.b, 40)
+    f1, g1, _, _ = run_log(w.x, w.y, w.a, w.b, w.eps, 15)
+    f2, g2, _, _ = run_log(w.x, w.y, w.a, w.b, w.eps, 25, f0=f1, g0=g1)
+    check_potentials(orc, w.x, w.y, w.a, w.b, w.eps, f2, g2, fo, go)
+    fa, ga, _, _ = run_log(w.x, w.y, w.a, w.b, w.eps, 40)
+    fb, gb, _, _ = run_log(w.x, w.y, w.a, w.b, w.eps, 40)
+    assert np.array_equal(fa, fb) and np.array_equal(ga, gb)     # deterministic
+
+
+def test_small_eps_where_the_dense_kernel_underflows(orc):
+    rng = np.random.default_rng(7)
+    n, d, eps = 600, 16, 0.002
+    x = rng.uniform(size=(n, d)).astype(np.float32); y = rng.uniform(size=(n, d)).astype(np.float32)
+    a = np.full(n, 1.0 / n, dtype=np.float32); b = a.copy()
+    fo, go, _, _ = orc.sinkhorn_log_points(x, y, eps, a, b, 20)
+    f, g, _, _ = run_log(x, y, a, b, eps, 20)
+    assert np.isfinite(f).all() and np.isfinite(g).all()
+    check_potentials(orc, x, y, a, b, eps, f, g, fo, go)
