@@ -120,6 +120,7 @@ size_t fsk_workspace_bytes(const fsk_opts* opts, int mode, int d) {
   switch (mode) {
     case FSK_MODE_DENSE: return dense_ws(opts).total;
     case FSK_MODE_LOG: return log_workspace_bytes(opts->n, d);
+    case FSK_MODE_BATCHED: return batched_workspace_bytes(opts->n, opts->m);
     case FSK_MODE_SETUP: return align_up(max_sqdist_scratch_doubles(opts->n) * 8, 256) + 256;
     default: return 0;
   }
@@ -406,7 +407,7 @@ int fsk_block_fused(const fsk_opts* opts, const void* K_slab, int64_t ldK, int32
                           s_partial, kEpiProduct, 0.0, st);
 }
 
-// ------------------------------------------------------------- not built yet
+// ------------------------------------------------------------- log-domain and multitarget
 int fsk_sinkhorn_log_points(const fsk_opts* opts, const void* x, const void* y, int d, double eps,
                             const void* a, const void* b, void* f, void* g, void* workspace,
                             size_t ws_bytes, int32_t* iters_done, double* err, void* stream) {
@@ -427,9 +428,20 @@ int fsk_sinkhorn_log_points(const fsk_opts* opts, const void* x, const void* y, 
                                  err, (hipStream_t)stream);
 }
 
-int fsk_sinkhorn_batched(const fsk_opts*, const void*, int64_t, const void*, const void*, void*,
-                         void*, void*, size_t, void*) {
-  return set_error(FSK_EUNSUPPORTED, "batched path is not built yet");
+int fsk_sinkhorn_batched(const fsk_opts* opts, const void* K, int64_t ldK, const void* A,
+                         const void* B, void* U, void* V, void* workspace, size_t ws_bytes,
+                         void* stream) {
+  clear_error();
+  FSK_TRY(check_common(opts));
+  if (opts->c != 1) return set_error(FSK_EUNSUPPORTED, "batched call takes c = 1");
+  if (opts->tol > 0.0) return set_error(FSK_EUNSUPPORTED, "batched call runs a fixed number of iterations");
+  FSK_TRY(check_matrix("K", K, ldK, opts->n, opts->dtype));
+  FSK_TRY(check_vec("A", A, false));
+  FSK_TRY(check_vec("B", B, false));
+  FSK_TRY(check_vec("U", U, false));
+  FSK_TRY(check_vec("V", V, false));
+  if (workspace && !aligned16(workspace)) return set_error(FSK_EALIGN, "workspace is not 16-byte aligned");
+  return run_sinkhorn_batched(opts, K, ldK, A, B, U, V, workspace, ws_bytes, (hipStream_t)stream);
 }
 
 // ------------------------------------------------------------- measurement helpers

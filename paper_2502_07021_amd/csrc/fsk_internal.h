@@ -104,6 +104,11 @@ int run_sinkhorn_log_points(const fsk_opts* o, const void* x, const void* y, int
                             size_t ws_bytes, int32_t* iters_done, double* err_out,
                             hipStream_t st);
 
+// ------------------------------------------------------------------ multitarget path
+size_t batched_workspace_bytes(int n, int m);
+int run_sinkhorn_batched(const fsk_opts* o, const void* K, int64_t ldK, const void* A, const void* B,
+                         void* U, void* V, void* workspace, size_t ws_bytes, hipStream_t st);
+
 // ------------------------------------------------------------------ measurement helpers
 int launch_copy(void* dst, const void* src, size_t bytes, hipStream_t stream);
 int launch_read(const void* src, size_t bytes, float* sink, hipStream_t stream);

@@ -1,0 +1,71 @@
+"""GPU parity of the multitarget (batched) path against the oracle: n x m scalings sharing K,
+the two products done as matrix products on the matrix cores.  Bar: max relative error on U, V
+and the column marginals <= 1e-4 (fp32)."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2502_07021_amd import api, workloads
+from gpu_util import dev, relerr, run_dense
+
+pytestmark = pytest.mark.gpu
+
+
+def run_batched(K, A, B, iters, ld=None):
+    n, m = A.shape
+    opts = api.make_opts(n, torch.float32, m=m, max_iters=iters)
+    ws = api.alloc_workspace(opts, api.FSK_MODE_BATCHED)
+    if ld is None:
+        ld = (n + 3) // 4 * 4
+    full = torch.full((n, ld), float("nan"), dtype=torch.float32, device="cuda")
+    full[:, :n] = dev(K)
+    U = torch.ones(n, m, device="cuda"); V = torch.ones(n, m, device="cuda")
+    api.fsk_sinkhorn_batched(opts, full[:, :n], dev(A), dev(B), U, V, ws)
+    torch.cuda.synchronize()
+    return U.cpu().numpy(), V.cpu().numpy()
+
+
+def problem(orc, n, m, seed, eps=0.05):
+    w = workloads.make(5, n=n, m=m, seed=seed)
+    K64, _ = orc.gibbs_from_points(w.x, w.y, eps, False)
+    return np.ascontiguousarray(K64.astype(np.float32)), w.a, w.b
+
+
+@pytest.mark.parametrize("n,m", [(1, 1), (5, 3), (64, 64), (65, 33), (100, 1), (257, 64), (1000, 40),
+                                 (1030, 64), (2048, 64)])
+def test_batched_matches_oracle(orc, n, m):
+    K, A, B = problem(orc, n, m, 500 + n + m)
+    Uo, Vo = orc.sinkhorn_batched(K, A, B, 9)
+    U, V = run_batched(K, A, B, 9, ld=(n + 3) // 4 * 4 + 8)
+    assert relerr(U, Uo) <= 1e-4 and relerr(V, Vo) <= 1e-4
+    # column marginals of every plan, evaluated by the oracle on the GPU's scalings
+    for k in range(0, m, max(1, m // 4)):
+        cm = orc.col_marginal(K, U[:, k], V[:, k])
+        assert relerr(cm, B[:, k]) <= 1e-4
+
+
+def test_cfg5_law_full_iteration_count(orc):
+    """Configuration 5 at reduced n: Dirichlet(1) marginals (entries down to 1e-9), eps = 0.05,
+    300 iterations, m = 64."""
+    K, A, B = problem(orc, 1536, 64, 20250207 * 10 + 5)
+    Uo, Vo = orc.sinkhorn_batched(K, A, B, 300)
+    U, V = run_batched(K, A, B, 300)
+    assert relerr(U, Uo) <= 1e-4 and relerr(V, Vo) <= 1e-4
+
+
+def test_batched_column_equals_single_histogram_run(orc):
+    """Sec. 5.3.2: column k of the stacked run is the run on (a_k, b_k) alone."""
+    K, A, B = problem(orc, 700, 8, 77)
+    U, V = run_batched(K, A, B, 25)
+    for k in (0, 3, 7):
+        u, v, _, _ = run_dense(K, A[:, k].copy(), B[:, k].copy(), 25)
+        assert relerr(U[:, k], u) <= 2e-5 and relerr(V[:, k], v) <= 2e-5
+
+
+def test_more_than_64_histograms_is_refused():
+    opts = api.make_opts(128, torch.float32, m=65, max_iters=1)
+    K = torch.ones(128, 128, device="cuda"); X = torch.ones(128, 65, device="cuda")
+    with pytest.raises(api.FskError) as e:
+        api.fsk_sinkhorn_batched(opts, K, X, X, X.clone(), X.clone(),
+                                 torch.empty(1 << 24, dtype=torch.uint8, device="cuda"))
+    assert e.value.status == api.FSK_EUNSUPPORTED
