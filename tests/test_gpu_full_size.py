@@ -1,0 +1,137 @@
+"""Parity at the full benchmark sizes, in the launch configuration bench.py times.
+
+The oracle cannot follow a full trajectory at these sizes in test time, so each case combines
+(i) a short full run from the cold start compared element by element, and (ii) one-step
+consistency at a late state: the oracle recomputes sampled entries of the next update from the
+GPU's own previous half-step, which pins every later iteration to the definition.
+"""
+import numpy as np
+import pytest
+import torch
+
+from paper_2502_07021_amd import api, workloads
+from gpu_util import dev, relerr
+
+pytestmark = pytest.mark.gpu
+
+
+def test_cfg3_n32768_c8_equals_c1_and_oracle(orc):
+    w = workloads.make(3)
+    n = w.n
+    K, _ = orc.gibbs_from_points_f32(w.x, w.y, w.eps, True)
+    Kd = dev(K); a = dev(w.a); b = dev(w.b)
+
+    def run(c, iters, u=None, v=None, flow=api.FSK_FLOW_FUSED):
+        opts = api.make_opts(n, torch.float32, c=c, max_iters=iters, flow=flow)
+        ws = api.alloc_workspace(opts)
+        u = torch.ones(n, device="cuda") if u is None else u.clone()
+        v = torch.ones(n, device="cuda") if v is None else v.clone()
+        api.fsk_sinkhorn_dense(opts, Kd, a, b, u, v, ws)
+        torch.cuda.synchronize()
+        return u, v
+
+    # (i) 20 iterations against the oracle, blocked and centralised
+    uo, vo = orc.sinkhorn_blocked(K, w.a, w.b, 20, 8, 1)
+    for c in (8, 1):
+        u, v = run(c, 20)
+        assert relerr(u.cpu().numpy(), uo) <= 1e-4 and relerr(v.cpu().numpy(), vo) <= 1e-4
+
+    # the full 1000 iterations: c = 8 reproduces c = 1 (Proposition 1), to rounding
+    u8, v8 = run(8, 999)
+    u1, v1 = run(1, 999)
+    assert relerr(u8.cpu().numpy(), u1.cpu().numpy()) <= 1e-5
+    assert relerr(v8.cpu().numpy(), v1.cpu().numpy()) <= 1e-5
+    # the two-pass flow is bitwise independent of c at full size as well (one iteration suffices)
+    ut1, vt1 = run(1, 1, u8, v8, flow=api.FSK_FLOW_TWO_PASS)
+    ut8, vt8 = run(8, 1, u8, v8, flow=api.FSK_FLOW_PAPER)
+    assert torch.equal(ut1, ut8) and torch.equal(vt1, vt8)
+
+    # (ii) iteration 1000 from the GPU's state after 999, sampled rows and columns
+    u9, v9 = run(8, 1, u8, v8)
+    rng = np.random.default_rng(3)
+    rows = np.sort(rng.choice(n, 512, replace=False))
+    cols = np.sort(rng.choice(n, 512, replace=False))
+    v8h = v8.cpu().numpy(); u9h = u9.cpu().numpy(); v9h = v9.cpu().numpy()
+    q = np.array([orc.row_products(K, v8h, i, i + 1)[0] for i in rows])
+    assert relerr(u9h[rows], w.a[rows].astype(np.float64) / q) <= 1e-4
+    r = np.array([orc.col_products(K, u9h, 0, n, j, j + 1)[0] for j in cols])
+    assert relerr(v9h[cols], w.b[cols].astype(np.float64) / r) <= 1e-4
+    # column marginal exact after the v-update, row marginal converged
+    assert relerr(v9h[cols] * r, w.b[cols]) <= 1e-4
+    qn = np.array([orc.row_products(K, v9h, i, i + 1)[0] for i in rows])
+    assert np.max(np.abs(u9h[rows] * qn - w.a[rows]) / w.a[rows]) <= 1e-3
+
+
+def test_cfg4_n65536_log_domain(orc):
+    w = workloads.make(4)
+    n, d, eps = w.n, w.d, w.eps
+    x, y, a, b = dev(w.x), dev(w.y), dev(w.a), dev(w.b)
+
+    def run(iters, f=None, g=None, tol=0.0, check_every=1):
+        opts = api.make_opts(n, torch.float32, max_iters=iters, tol=tol, check_every=check_every)
+        ws = api.alloc_workspace(opts, api.FSK_MODE_LOG, d)
+        f = torch.zeros(n, device="cuda") if f is None else f.clone()
+        g = torch.zeros(n, device="cuda") if g is None else g.clone()
+        done, err = api.fsk_sinkhorn_log_points(opts, x, y, eps, a, b, f, g, ws)
+        torch.cuda.synchronize()
+        return f, g, done, err
+
+    # (i) two full oracle iterations from the cold start
+    fo, go, _, _ = orc.sinkhorn_log_points(w.x, w.y, eps, w.a, w.b, 2)
+    f, g, _, _ = run(2)
+    assert np.max(np.abs(f.cpu().numpy() - fo)) / eps <= 1e-4
+    assert np.max(np.abs(g.cpu().numpy() - go)) / eps <= 1e-4
+
+    # (ii) one-step consistency at t = 100 on sampled rows / columns
+    f99, g99, _, _ = run(99)
+    f100, g100, _, _ = run(1, f99, g99)
+    rng = np.random.default_rng(4)
+    rows = np.sort(rng.choice(n, 256, replace=False))
+    g99h = g99.cpu().numpy().astype(np.float64); f100h = f100.cpu().numpy().astype(np.float64)
+    g100h = g100.cpu().numpy().astype(np.float64)
+    f_ref = orc.log_update_points(w.x, w.a, w.y, g99h, eps, rows)
+    assert np.max(np.abs(f100h[rows] - f_ref)) / eps <= 1e-4
+    g_ref = orc.log_update_points(w.y, w.b, w.x, f100h, eps, rows)
+    assert np.max(np.abs(g100h[rows] - g_ref)) / eps <= 1e-4
+
+    # the stop rule of the configuration: L1 row-marginal error < 1e-6 or 2000 iterations
+    f, g, done, err = run(2000, f100, g100, tol=1e-6, check_every=50)
+    assert done % 50 == 0 and np.isfinite(err)
+    assert (err < 1e-6) or done == 2000
+    fh = f.cpu().numpy().astype(np.float64); gh = g.cpu().numpy().astype(np.float64)
+    rm = orc.log_row_marginal_points(w.x, fh, w.y, gh, eps, rows)
+    est = np.abs(rm - w.a[rows]).sum() * (n / rows.size)      # sampled estimate of the L1 error
+    assert est <= max(5 * err, 5e-6)
+    cm = orc.log_row_marginal_points(w.y, gh, w.x, fh, eps, rows)
+    assert np.max(np.abs(cm - w.b[rows]) / w.b[rows]) <= 1e-4
+
+
+def test_cfg5_n16384_m64_batched(orc):
+    w = workloads.make(5)
+    n, m = w.n, w.m
+    K, _ = orc.gibbs_from_points_f32(w.x, w.y, w.eps, False)
+    Kd = dev(K); A = dev(w.a); B = dev(w.b)
+
+    def run(iters, U=None, V=None):
+        opts = api.make_opts(n, torch.float32, m=m, max_iters=iters)
+        ws = api.alloc_workspace(opts, api.FSK_MODE_BATCHED)
+        U = torch.ones(n, m, device="cuda") if U is None else U.clone()
+        V = torch.ones(n, m, device="cuda") if V is None else V.clone()
+        api.fsk_sinkhorn_batched(opts, Kd, A, B, U, V, ws)
+        torch.cuda.synchronize()
+        return U, V
+
+    Uo, Vo = orc.sinkhorn_batched(K, w.a, w.b, 2)
+    U, V = run(2)
+    assert relerr(U.cpu().numpy(), Uo) <= 1e-4 and relerr(V.cpu().numpy(), Vo) <= 1e-4
+
+    U299, V299 = run(299)
+    U300, V300 = run(1, U299, V299)
+    rng = np.random.default_rng(5)
+    rows = np.sort(rng.choice(n, 128, replace=False))
+    V299h = V299.cpu().numpy(); U300h = U300.cpu().numpy(); V300h = V300.cpu().numpy()
+    for k in (0, 17, 63):
+        q = np.array([orc.row_products(K, V299h[:, k], i, i + 1)[0] for i in rows])
+        assert relerr(U300h[rows, k], w.a[rows, k].astype(np.float64) / q) <= 1e-4
+        r = np.array([orc.col_products(K, U300h[:, k], 0, n, j, j + 1)[0] for j in rows])
+        assert relerr(V300h[rows, k], w.b[rows, k].astype(np.float64) / r) <= 1e-4
