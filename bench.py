@@ -1,14 +1,17 @@
 #!/usr/bin/env python3
-"""Benchmark of the dense Sinkhorn hot path on one MI355X.
+"""Benchmark of the Sinkhorn hot path on one MI355X.
 
-Workload: configuration 3 -- n = 32768, fp32 dense K (4 GiB) built on the GPU from seeded
-point clouds, row-partitioned into c = 8 blocks of 4096 rows, fused one-pass flow.  A "step" is
-one Sinkhorn iteration (u-update then v-update over the whole of K).  Inputs are resident in
-HBM before the timed region; the K build is setup and is not timed.
+Default workload (the metric's): configuration 3 -- n = 32768, fp32 dense K (4 GiB) built on the
+GPU from seeded point clouds, row-partitioned into c = 8 blocks of 4096 rows, fused one-pass
+flow.  A "step" is one Sinkhorn iteration (u-update then v-update over the whole of K).  Inputs
+are resident in HBM before the timed region; the K build is setup and is not timed.
 
-Prints ONE JSON line: iterations/s (metric), the HBM roofline of the dominant kernel measured
-live with HIP events on the launch stream, and the CPU oracle timed on this machine's host cores
-on a bounded sample of the same workload.
+Prints ONE JSON line: iterations/s (metric), the roofline of the dominant kernel measured live
+with HIP events on the launch stream, and the CPU oracle timed on this machine's host cores on a
+bounded sample of the same workload.
+
+`--workload cfg1|cfg2|cfg4|cfg5` times the other configurations in the same format (secondary
+lines; the driver's default run is cfg3).
 """
 from __future__ import annotations
 
@@ -23,7 +26,10 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
-PEAK_HBM_GBS = 8000.0   # MI355X published HBM3E peak
+PEAK_HBM_GBS = 8000.0          # MI355X published HBM3E peak
+PEAK_FP32_MFMA_TFLOPS = 157.3  # dense fp32 matrix peak
+PEAK_FMA_TFLOPS = 78.6         # 256 CU x 64 lanes x 2.4 GHz x 2 flop: one (unpacked fp32 or fp64) FMA per lane per clock
+METRIC = "Sinkhorn iters/sec (Kv+K^Tu) at n=32768 fp32; achieved HBM GB/s vs peak"
 
 
 def traffic_from_profile(name: str):
@@ -35,60 +41,48 @@ def traffic_from_profile(name: str):
     return float(m.group(1)) if m else None
 
 
-def cpu_baseline(w, seconds_budget: float = 20.0):
-    """The oracle as it stands on the host cores: K built by the oracle, then a few full
-    iterations of the same n = 32768 problem (blocked, c = 8, row-slab flow)."""
+def timed(fn):
+    import torch
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    fn()
+    torch.cuda.synchronize()
+    return time.perf_counter() - t0
+
+
+def event_ms(fn):
+    """Duration of fn's GPU work by HIP events recorded on the stream the library launches on."""
+    import torch
+    e0 = torch.cuda.Event(enable_timing=True); e1 = torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    e0.record(); fn(); e1.record()
+    torch.cuda.synchronize()
+    return e0.elapsed_time(e1)
+
+
+# ------------------------------------------------------------------ dense (cfg 1, 2, 3)
+def bench_dense(args, cfg):
     import numpy as np
-    import oracle
-    t0 = time.perf_counter()
-    K, _ = oracle.gibbs_from_points_f32(w.x, w.y, w.eps, w.normalise_by_max)
-    t_setup = time.perf_counter() - t0
-    t0 = time.perf_counter()
-    u, v = oracle.sinkhorn_blocked(K, w.a, w.b, 1, w.c, 1)
-    t_one = time.perf_counter() - t0
-    iters = int(max(1, min(10, (seconds_budget - t_one) // max(t_one, 1e-3))))
-    t0 = time.perf_counter()
-    oracle.sinkhorn_blocked(K, w.a, w.b, iters, w.c, 1, u0=u, v0=v)
-    dt = time.perf_counter() - t0
-    return {"value": iters / dt, "unit": "iterations/s", "cores": oracle.num_threads(),
-            "kind": "oracle",
-            "sample": f"{iters} full iterations at n={w.n} (c={w.c}, fp64 arithmetic on the fp32 K; "
-                      f"oracle K build {t_setup:.1f} s not counted)"}
-
-
-def main() -> int:
-    ap = argparse.ArgumentParser()
-    ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=1000)
-    ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--n", type=int, default=32768, help="problem size (default: configuration 3)")
-    ap.add_argument("--c", type=int, default=8)
-    ap.add_argument("--flow", type=int, default=0, help="0 fused, 1 two-pass, 2 Algorithm 1")
-    ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--profile-reps", type=int, default=50)
-    args = ap.parse_args()
-    if args.gpus != 1:
-        print("bench.py: this build runs on ONE GPU (no collectives are part of it); "
-              "use --gpus 1", file=sys.stderr)
-        return 2
-
     import torch
     from paper_2502_07021_amd import api, workloads
 
-    torch.cuda.set_device(0)
-    n, c = args.n, args.c
-    w = workloads.make(3, n=n)
+    w = workloads.make(cfg, n=args.n)
+    n = w.n
+    c = args.c if args.c is not None else w.c
+    steps = args.steps if args.steps is not None else w.iters
     w.c = c
+    td = torch.float64 if w.dtype == np.float64 else torch.float32
+    esz = 8 if td == torch.float64 else 4
     dev = lambda t: torch.from_numpy(t).cuda()
     x, y, a, b = dev(w.x), dev(w.y), dev(w.a), dev(w.b)
 
     # setup (untimed): K on the GPU from the points
-    opts = api.make_opts(n, torch.float32, c=c, max_iters=args.steps, flow=args.flow)
-    K = torch.empty(n, n, dtype=torch.float32, device="cuda")
-    api.fsk_kernel_from_points(opts, x, y, w.eps, True, K,
+    opts = api.make_opts(n, td, c=c, max_iters=steps, flow=args.flow)
+    K = torch.empty(n, n, dtype=td, device="cuda")
+    api.fsk_kernel_from_points(opts, x, y, w.eps, w.normalise_by_max, K,
                                api.alloc_workspace(opts, api.FSK_MODE_SETUP, w.d))
     ws = api.alloc_workspace(opts, api.FSK_MODE_DENSE)
-    u = torch.ones(n, device="cuda"); v = torch.ones(n, device="cuda")
+    u = torch.ones(n, dtype=td, device="cuda"); v = torch.ones(n, dtype=td, device="cuda")
 
     # one plain 1 GiB device copy: the known-size stream against which profiler byte
     # counters (FETCH_SIZE / WRITE_SIZE) of the same run are scaled
@@ -98,65 +92,210 @@ def main() -> int:
     torch.cuda.synchronize()
     del cal_src, cal_dst
 
-    def run(iters):
-        o = api.make_opts(n, torch.float32, c=c, max_iters=iters, flow=args.flow)
-        api.fsk_sinkhorn_dense(o, K, a, b, u, v, ws)
+    def run(iters, cc=c, wsp=ws):
+        o = api.make_opts(n, td, c=cc, max_iters=iters, flow=args.flow)
+        api.fsk_sinkhorn_dense(o, K, a, b, u, v, wsp)
 
     if args.warmup > 0:
         run(args.warmup)
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    run(args.steps)
-    torch.cuda.synchronize()
-    dt = time.perf_counter() - t0
+    dt = timed(lambda: run(steps))
     if not bool(torch.isfinite(u).all() and torch.isfinite(v).all()):
-        print("bench.py: non-finite scalings", file=sys.stderr)
-        return 1
+        raise RuntimeError("non-finite scalings")
 
     # dominant kernel alone, same launch configuration, HIP events on the launch stream
     stream_ms, other_ms, launches = api.fsk_dense_profile(opts, K, a, b, u, v, ws, args.profile_reps)
-    alg_bytes = float(n) * n * 4 * (1 if args.flow == 0 else 2)   # K read once (fused) or twice
+    alg_bytes = float(n) * n * esz * (1 if args.flow == 0 else 2)   # K read once (fused) or twice
     achieved = alg_bytes / (stream_ms * 1e-3) / 1e9
+    headline = cfg == 3 and args.flow == 0 and n == 32768 and c == 8
     roofline = {"bound": "hbm", "achieved": achieved, "peak": PEAK_HBM_GBS, "unit": "GB/s",
                 "frac": achieved / PEAK_HBM_GBS,
-                "traffic": traffic_from_profile("dense_fused_cfg3_pmc.txt") if args.flow == 0 and n == 32768 and c == 8 else None,
-                "kernel": "fused_kernel<float,16,1,exact>" if args.flow == 0 else "rowpass+colpartial",
+                "traffic": traffic_from_profile("dense_fused_cfg3_pmc.txt") if headline else None,
+                "kernel": "fused_kernel" if args.flow == 0 else "rowpass_kernel+colpartial_kernel",
                 "kernel_ms": stream_ms, "launches_per_step": launches,
                 "algorithmic_bytes_per_step": alg_bytes, "other_kernels_ms": other_ms}
 
-    # same problem with c = 1 (the iterates the blocked run must reproduce), for reference
     extra = {}
-    if c != 1:
-        o1 = api.make_opts(n, torch.float32, c=1, max_iters=args.steps, flow=args.flow)
+    if c != 1:   # the same problem with c = 1 (the iterates the blocked run must reproduce)
+        o1 = api.make_opts(n, td, c=1, max_iters=steps, flow=args.flow)
         ws1 = api.alloc_workspace(o1, api.FSK_MODE_DENSE)
         u.fill_(1.0); v.fill_(1.0)
-        api.fsk_sinkhorn_dense(api.make_opts(n, torch.float32, c=1, max_iters=max(args.warmup, 1),
-                                             flow=args.flow), K, a, b, u, v, ws1)
-        torch.cuda.synchronize()
-        t1 = time.perf_counter()
-        api.fsk_sinkhorn_dense(o1, K, a, b, u, v, ws1)
-        torch.cuda.synchronize()
-        dt1 = time.perf_counter() - t1
+        run(max(args.warmup, 1), 1, ws1)
+        dt1 = timed(lambda: run(steps, 1, ws1))
         s1, _, _ = api.fsk_dense_profile(o1, K, a, b, u, v, ws1, args.profile_reps)
-        extra = {"c1_iterations_per_s": args.steps / dt1, "c1_kernel_ms": s1,
+        extra = {"c1_iterations_per_s": steps / dt1, "c1_kernel_ms": s1,
                  "c1_kernel_GBps": alg_bytes / (s1 * 1e-3) / 1e9}
 
+    laws = {1: "x,y~U[0,1]^2, C=|x-y|^2", 2: "x,y~N(0,I_3), C/max C", 3: "x~N(0,I_8), y~N(0.5,I_8), C/max C"}
     out = {
-        "metric": "Sinkhorn iters/sec (Kv+K^Tu) at n=32768 fp32; achieved HBM GB/s vs peak",
-        "value": args.steps / dt, "unit": "iterations/s", "n_gpus": 1, "steps": args.steps,
-        "warmup": args.warmup, "ms_per_step": dt / args.steps * 1e3, "higher_is_better": True,
-        "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
-        "config": {"workload": f"cfg3: n={n} fp32 dense K ({n * n * 4 / 2**30:.0f} GiB), "
-                               f"x~N(0,I_8), y~N(0.5,I_8), C/max C, eps=0.05, "
-                               f"row-partitioned c={c} on one GPU, flow={['fused','two_pass','algorithm1'][args.flow]}",
-                   "n": n, "c": c, "eps": w.eps, "iterations": args.steps},
+        "metric": METRIC if cfg == 3 else f"Sinkhorn iters/sec (Kv+K^Tu), cfg{cfg} n={n}",
+        "value": steps / dt, "unit": "iterations/s", "n_gpus": 1, "steps": steps,
+        "warmup": args.warmup, "ms_per_step": dt / steps * 1e3, "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "f64" if esz == 8 else "f32",
+        "data": "synthetic",
+        "config": {"workload": f"cfg{cfg}: n={n} {'fp64' if esz == 8 else 'fp32'} dense K "
+                               f"({n * n * esz / 2**20:.0f} MiB), {laws[cfg]}, eps={w.eps}, "
+                               f"row-partitioned c={c} on one GPU, "
+                               f"flow={['fused', 'two_pass', 'algorithm1'][args.flow]}",
+                   "n": n, "c": c, "eps": w.eps, "iterations": steps},
         "roofline": roofline,
     }
     out.update(extra)
     if not args.no_cpu_baseline:
         del K
         torch.cuda.empty_cache()
-        out["cpu_baseline"] = cpu_baseline(w)
+        import oracle
+        t0 = time.perf_counter()
+        Ko, _ = oracle.gibbs_from_points_f32(w.x, w.y, w.eps, w.normalise_by_max) if esz == 4 \
+            else oracle.gibbs_from_points(w.x, w.y, w.eps, w.normalise_by_max)
+        t_setup = time.perf_counter() - t0
+        t0 = time.perf_counter()
+        uo, vo = oracle.sinkhorn_blocked(Ko, w.a, w.b, 1, c, 1)
+        t_one = time.perf_counter() - t0
+        iters = int(max(1, min(steps, 10 if n >= 16384 else 200, 15.0 // max(t_one, 1e-4))))
+        t0 = time.perf_counter()
+        oracle.sinkhorn_blocked(Ko, w.a, w.b, iters, c, 1, u0=uo, v0=vo)
+        dto = time.perf_counter() - t0
+        out["cpu_baseline"] = {
+            "value": iters / dto, "unit": "iterations/s", "cores": oracle.num_threads(),
+            "kind": "oracle",
+            "sample": f"{iters} full iterations at n={n} (c={c}, fp64 arithmetic on the stored K; "
+                      f"oracle K build {t_setup:.1f} s not counted)"}
+    return out
+
+
+# ------------------------------------------------------------------ log domain (cfg 4)
+def bench_log(args):
+    import numpy as np
+    import torch
+    from paper_2502_07021_amd import api, workloads
+
+    w = workloads.make(4, n=args.n)
+    n, d = w.n, w.d
+    steps = args.steps if args.steps is not None else 100
+    dev = lambda t: torch.from_numpy(t).cuda()
+    x, y, a, b = dev(w.x), dev(w.y), dev(w.a), dev(w.b)
+    opts = api.make_opts(n, torch.float32, max_iters=steps)
+    ws = api.alloc_workspace(opts, api.FSK_MODE_LOG, d)
+    f = torch.zeros(n, device="cuda"); g = torch.zeros(n, device="cuda")
+
+    def run(iters):
+        api.fsk_sinkhorn_log_points(api.make_opts(n, torch.float32, max_iters=iters), x, y, w.eps,
+                                    a, b, f, g, ws)
+
+    run(max(args.warmup, 1))
+    dt = timed(lambda: run(steps))
+    ms = event_ms(lambda: run(args.profile_reps))       # 2 half-step launches per iteration
+    launch_ms = ms / (2 * args.profile_reps)
+    pairs = float(n) * n
+    flops_per_pair = 2 * 16 + 4                          # 16 FMA (fp64) + add, max, exp2, add
+    achieved = pairs * flops_per_pair / (launch_ms * 1e-3) / 1e12
+    out = {
+        "metric": f"Sinkhorn iters/sec (log-domain f,g updates), cfg4 n={n}",
+        "value": steps / dt, "unit": "iterations/s", "n_gpus": 1, "steps": steps,
+        "warmup": args.warmup, "ms_per_step": dt / steps * 1e3, "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "f32 (fp64 dot product)",
+        "data": "synthetic",
+        "config": {"workload": f"cfg4: n={n} log-domain, x,y~U[0,1]^{d} fp32, cost on the fly, "
+                               f"eps={w.eps}, a=b=1/n, fixed {steps} iterations", "n": n, "d": d},
+        "roofline": {"bound": "alu", "achieved": achieved, "peak": PEAK_FMA_TFLOPS,
+                     "unit": "TFLOP/s", "frac": achieved / PEAK_FMA_TFLOPS, "traffic": None,
+                     "kernel": "log_lse_kernel<16>", "kernel_ms": launch_ms,
+                     "launches_per_step": 2, "pair_evaluations_per_s": pairs / (launch_ms * 1e-3),
+                     "flops_per_pair": flops_per_pair,
+                     "note": "kernel_ms = event-timed run / launches; includes the ~0.1% finalize kernels"},
+    }
+    if not args.no_cpu_baseline:
+        import oracle
+        rows = np.arange(0, n, max(1, n // 2048))[:2048]
+        gz = np.zeros(n)
+        t0 = time.perf_counter()
+        oracle.log_update_points(w.x, w.a, w.y, gz, w.eps, rows)
+        dto = time.perf_counter() - t0
+        it_s = 1.0 / (dto * (n / rows.size) * 2)
+        out["cpu_baseline"] = {"value": it_s, "unit": "iterations/s", "cores": oracle.num_threads(),
+                               "kind": "oracle",
+                               "sample": f"one f-update on {rows.size} of {n} rows against all columns, "
+                                         f"scaled to 2 n^2 pairs per iteration"}
+    return out
+
+
+# ------------------------------------------------------------------ batched (cfg 5)
+def bench_batched(args):
+    import numpy as np
+    import torch
+    from paper_2502_07021_amd import api, workloads
+
+    w = workloads.make(5, n=args.n)
+    n, m = w.n, w.m
+    steps = args.steps if args.steps is not None else w.iters
+    dev = lambda t: torch.from_numpy(t).cuda()
+    x, y, A, B = dev(w.x), dev(w.y), dev(w.a), dev(w.b)
+    opts = api.make_opts(n, torch.float32, m=m, max_iters=steps)
+    K = torch.empty(n, n, device="cuda")
+    api.fsk_kernel_from_points(opts, x, y, w.eps, False, K, None)
+    ws = api.alloc_workspace(opts, api.FSK_MODE_BATCHED)
+    U = torch.ones(n, m, device="cuda"); V = torch.ones(n, m, device="cuda")
+
+    def run(iters):
+        api.fsk_sinkhorn_batched(api.make_opts(n, torch.float32, m=m, max_iters=iters), K, A, B, U, V, ws)
+
+    run(max(args.warmup, 1))
+    dt = timed(lambda: run(steps))
+    ms = event_ms(lambda: run(args.profile_reps))
+    launch_ms = ms / (2 * args.profile_reps)              # two products per iteration
+    flops = 2.0 * n * n * m
+    achieved = flops / (launch_ms * 1e-3) / 1e12
+    out = {
+        "metric": f"Sinkhorn iters/sec (multitarget K V, K^T U on MFMA), cfg5 n={n} m={m}",
+        "value": steps / dt, "unit": "iterations/s", "n_gpus": 1, "steps": steps,
+        "warmup": args.warmup, "ms_per_step": dt / steps * 1e3, "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": f"cfg5: n={n} fp32 dense K shared by m={m} Dirichlet(1) histogram "
+                               f"pairs, x,y~U[0,1]^2, eps={w.eps}", "n": n, "m": m},
+        "roofline": {"bound": "mfma", "achieved": achieved, "peak": PEAK_FP32_MFMA_TFLOPS,
+                     "unit": "TFLOP/s", "frac": achieved / PEAK_FP32_MFMA_TFLOPS, "traffic": None,
+                     "kernel": "batched_rowprod_kernel / batched_colprod_kernel",
+                     "kernel_ms": launch_ms, "launches_per_step": 2,
+                     "note": "kernel_ms = event-timed run / product launches; includes the small reduce kernels"},
+        "histogram_iterations_per_s": steps * m / dt,
+    }
+    if not args.no_cpu_baseline:
+        import oracle
+        Ko, _ = oracle.gibbs_from_points_f32(w.x, w.y, w.eps, False)
+        t0 = time.perf_counter()
+        oracle.sinkhorn_batched(Ko, w.a, w.b, 2)
+        dto = time.perf_counter() - t0
+        out["cpu_baseline"] = {"value": 2 / dto, "unit": "iterations/s",
+                               "cores": oracle.num_threads(), "kind": "oracle",
+                               "sample": f"2 full iterations at n={n}, m={m}"}
+    return out
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=None,
+                    help="timed iterations (default: the configuration's own count; cfg4: 100)")
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--workload", default="cfg3", choices=["cfg1", "cfg2", "cfg3", "cfg4", "cfg5"])
+    ap.add_argument("--n", type=int, default=None, help="override the problem size (same law)")
+    ap.add_argument("--c", type=int, default=None, help="row blocks (dense workloads)")
+    ap.add_argument("--flow", type=int, default=0, help="dense: 0 fused, 1 two-pass, 2 Algorithm 1")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--profile-reps", type=int, default=50)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (no collectives are part of it); "
+              "use --gpus 1", file=sys.stderr)
+        return 2
+    import torch
+    torch.cuda.set_device(0)
+    if args.workload == "cfg4":
+        out = bench_log(args)
+    elif args.workload == "cfg5":
+        out = bench_batched(args)
+    else:
+        out = bench_dense(args, int(args.workload[3]))
     print(json.dumps(out))
     return 0
 
