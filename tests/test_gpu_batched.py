@@ -11,10 +11,12 @@ from gpu_util import dev, relerr, run_dense
 pytestmark = pytest.mark.gpu
 
 
-def run_batched(K, A, B, iters, ld=None):
+def run_batched(K, A, B, iters, ld=None, small_workspace=False):
     n, m = A.shape
     opts = api.make_opts(n, torch.float32, m=m, max_iters=iters)
     ws = api.alloc_workspace(opts, api.FSK_MODE_BATCHED)
+    if small_workspace:      # no room for the transposed copy of K: the direct row kernel runs
+        ws = ws[: ws.numel() - n * n * 4]
     if ld is None:
         ld = (n + 3) // 4 * 4
     full = torch.full((n, ld), float("nan"), dtype=torch.float32, device="cuda")
@@ -42,6 +44,14 @@ def test_batched_matches_oracle(orc, n, m):
     for k in range(0, m, max(1, m // 4)):
         cm = orc.col_marginal(K, U[:, k], V[:, k])
         assert relerr(cm, B[:, k]) <= 1e-4
+
+
+@pytest.mark.parametrize("n,m", [(65, 33), (1030, 64)])
+def test_batched_without_room_for_the_transposed_kernel(orc, n, m):
+    K, A, B = problem(orc, n, m, 900 + n)
+    Uo, Vo = orc.sinkhorn_batched(K, A, B, 9)
+    U, V = run_batched(K, A, B, 9, small_workspace=True)
+    assert relerr(U, Uo) <= 1e-4 and relerr(V, Vo) <= 1e-4
 
 
 def test_cfg5_law_full_iteration_count(orc):
