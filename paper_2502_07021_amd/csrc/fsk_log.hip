@@ -18,12 +18,12 @@
 // kept in fp64 shadow copies for the whole call; the caller's fp32 arrays are
 // read once at the start and written after every update.
 //
-// Work split.  A workgroup of 256 threads owns 256 rows (one per lane, the row's
+// Work split.  A workgroup of 256 threads owns 512 rows (two per lane, the rows'
 // scaled coordinates live in registers) and one slice of the columns; all four
 // waves walk the same columns, whose coordinates arrive through uniform (scalar)
-// loads and feed the FMAs straight from scalar registers.  One row per lane keeps
-// the scalar-register live ranges to a single column, which the compiler needs in
-// order not to shuffle them through vector lanes.  Each lane keeps (reference exponent, sum of 2^(z - reference)); the
+// loads and feed the FMAs straight from scalar registers.  The scalar data cache is the
+// scarce resource of this kernel (measured: 100 % busy with one row per lane), so every
+// coordinate fetched is used for two rows.  Each lane keeps (reference exponent, sum of 2^(z - reference)); the
 // reference is raised lazily, only when a chunk exceeds it by 2^16, so the
 // common case has no rescaling and every term that matters is rounded to fp32 at a
 // magnitude below 16.  A second kernel merges the column slices in
@@ -36,7 +36,7 @@
 
 namespace fsk {
 
-constexpr int kLogRowsPerLane = 1;
+constexpr int kLogRowsPerLane = 2;
 constexpr int kLogThreads = 256;
 constexpr int kLogRowTile = kLogThreads * kLogRowsPerLane;
 constexpr int kLogChunk = 4;          // columns reduced together
@@ -96,6 +96,48 @@ __global__ __launch_bounds__(256) void log_prep_kernel(const T* __restrict__ p,
 }
 
 // ------------------------------------------------------------------ main kernel
+// z0 += sum_k x0[k] q[k], z1 += sum_k x1[k] q[k] for N coordinates, with q taken from scalar
+// registers and both rows consuming each coordinate back to back.  Written as one asm block
+// because the compiler, left alone, finishes row 0 first and parks the scalar values in
+// vector lanes (v_writelane) until row 1 needs them -- more instructions than the FMAs.
+template <int N>
+__device__ __forceinline__ void fma_rows2(double& z0, double& z1, const double* __restrict__ q,
+                                          const double* x0, const double* x1);
+
+template <>
+__device__ __forceinline__ void fma_rows2<4>(double& z0, double& z1, const double* __restrict__ q,
+                                             const double* x0, const double* x1) {
+  asm volatile(
+      "v_fmac_f64 %0, %2, %6\n\tv_fmac_f64 %1, %2, %10\n\t"
+      "v_fmac_f64 %0, %3, %7\n\tv_fmac_f64 %1, %3, %11\n\t"
+      "v_fmac_f64 %0, %4, %8\n\tv_fmac_f64 %1, %4, %12\n\t"
+      "v_fmac_f64 %0, %5, %9\n\tv_fmac_f64 %1, %5, %13"
+      : "+v"(z0), "+v"(z1)
+      : "s"(q[0]), "s"(q[1]), "s"(q[2]), "s"(q[3]), "v"(x0[0]), "v"(x0[1]), "v"(x0[2]), "v"(x0[3]),
+        "v"(x1[0]), "v"(x1[1]), "v"(x1[2]), "v"(x1[3])
+      : "memory");
+}
+
+template <>
+__device__ __forceinline__ void fma_rows2<8>(double& z0, double& z1, const double* __restrict__ q,
+                                             const double* x0, const double* x1) {
+  asm volatile(
+      "v_fmac_f64 %0, %2, %10\n\tv_fmac_f64 %1, %2, %18\n\t"
+      "v_fmac_f64 %0, %3, %11\n\tv_fmac_f64 %1, %3, %19\n\t"
+      "v_fmac_f64 %0, %4, %12\n\tv_fmac_f64 %1, %4, %20\n\t"
+      "v_fmac_f64 %0, %5, %13\n\tv_fmac_f64 %1, %5, %21\n\t"
+      "v_fmac_f64 %0, %6, %14\n\tv_fmac_f64 %1, %6, %22\n\t"
+      "v_fmac_f64 %0, %7, %15\n\tv_fmac_f64 %1, %7, %23\n\t"
+      "v_fmac_f64 %0, %8, %16\n\tv_fmac_f64 %1, %8, %24\n\t"
+      "v_fmac_f64 %0, %9, %17\n\tv_fmac_f64 %1, %9, %25"
+      : "+v"(z0), "+v"(z1)
+      : "s"(q[0]), "s"(q[1]), "s"(q[2]), "s"(q[3]), "s"(q[4]), "s"(q[5]), "s"(q[6]), "s"(q[7]),
+        "v"(x0[0]), "v"(x0[1]), "v"(x0[2]), "v"(x0[3]), "v"(x0[4]), "v"(x0[5]), "v"(x0[6]),
+        "v"(x0[7]), "v"(x1[0]), "v"(x1[1]), "v"(x1[2]), "v"(x1[3]), "v"(x1[4]), "v"(x1[5]),
+        "v"(x1[6]), "v"(x1[7])
+      : "memory");
+}
+
 // part_m[i*slices + sl], part_s[...]: reference exponent and sum of
 // 2^(z_ij - reference) over the columns j of slice sl, z_ij = beta_j + ps_i . qc_j.
 template <int DP>
@@ -140,20 +182,43 @@ __global__ __launch_bounds__(kLogThreads) void log_lse_kernel(const double* __re
 
   auto chunk = [&](int j0, auto jj_tag) {
     constexpr int JJ = decltype(jj_tag)::value;
+    static_assert(RI == 2, "fma_rows2 carries exactly two rows per lane");
+    constexpr int G = DP >= 8 ? 8 : 4;  // coordinates per FMA block
     double zd[RI][JJ];
+    // The column coordinates come through scalar loads, one whole column ahead of the FMAs
+    // that use them.  Scalar loads complete out of order, so the only wait is "all of
+    // them": the empty asm statement marks the place where the current column must have
+    // arrived; the next column is requested right after it and travels while the current
+    // column's FMAs run.
+    double qbuf[2][DP];
+    double bj[2];
+    auto fetch = [&](int t, int slot) {
+      const double* q = qc + (int64_t)(j0 + t) * DP;
+#pragma unroll
+      for (int k = 0; k < DP; ++k) qbuf[slot][k] = q[k];
+      bj[slot] = beta[j0 + t];
+    };
+    fetch(0, 0);
 #pragma unroll
     for (int t = 0; t < JJ; ++t) {
-      const double* q = qc + (int64_t)(j0 + t) * DP;  // uniform address: scalar loads
-      const double bj = beta[j0 + t];
+      const int slot = t & 1;
+#pragma unroll
+      for (int k0 = 0; k0 < DP; k0 += 8) {  // "use" every scalar of this column: forces the wait here
+        if (DP >= 8)
+          asm volatile("" : : "s"(qbuf[slot][k0]), "s"(qbuf[slot][k0 + 1]), "s"(qbuf[slot][k0 + 2]),
+                       "s"(qbuf[slot][k0 + 3]), "s"(qbuf[slot][k0 + 4]), "s"(qbuf[slot][k0 + 5]),
+                       "s"(qbuf[slot][k0 + 6]), "s"(qbuf[slot][k0 + 7]), "s"(bj[slot]) : "memory");
+        else
+          asm volatile("" : : "s"(qbuf[slot][0]), "s"(qbuf[slot][1]), "s"(qbuf[slot][2]),
+                       "s"(qbuf[slot][3]), "s"(bj[slot]) : "memory");
+      }
+      if (t + 1 < JJ) fetch(t + 1, slot ^ 1);
       double z[RI];
 #pragma unroll
-      for (int r = 0; r < RI; ++r) z[r] = bj - mref[r];
+      for (int r = 0; r < RI; ++r) z[r] = bj[slot] - mref[r];
 #pragma unroll
-      for (int k = 0; k < DP; ++k) {
-        const double qk = q[k];
-#pragma unroll
-        for (int r = 0; r < RI; ++r) z[r] = fma(xs[r][k], qk, z[r]);
-      }
+      for (int k0 = 0; k0 < DP; k0 += G)
+        fma_rows2<G>(z[0], z[1], &qbuf[slot][k0], &xs[0][k0], &xs[1][k0]);
 #pragma unroll
       for (int r = 0; r < RI; ++r) zd[r][t] = z[r];
     }
