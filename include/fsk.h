@@ -140,6 +140,21 @@ int fsk_marginals(const fsk_opts* opts, const void* K, int64_t ldK, const void* 
                   const void* v, void* row_marginal, void* col_marginal, void* workspace,
                   size_t ws_bytes, double* err_l1, void* stream);
 
+/* ---- bounded-delay emulation of the asynchronous schedule (Algorithm 3; assumption A3 of the
+ * convergence section) on one device, with a deterministic delay.  Client j owns rows/columns
+ * I_j (opts->c clients).  In iteration t it uses cached global vectors whose own slice is
+ * current and whose remote slices are what the peers held at the end of iteration
+ *     s(t) = floor((t-1-tau)/sync_every)*sync_every      (the initial vectors if <= 0):
+ *   u_{I_j} <- (1-eta) u_{I_j} + eta a_j ./ (K_{I_j,:} v_cached),
+ *   v_{I_j} <- (1-eta) v_{I_j} + eta b_j ./ ((K_{:,I_j})^T u_cached)   (u_cached has the new u_{I_j}).
+ * eta = opts->eta if opts->damping == FSK_DAMP_ARITHMETIC, else 1.  Runs exactly
+ * opts->max_iters iterations (tolerance mode is not offered); u, v are IN/OUT as in
+ * fsk_sinkhorn_dense.  tau >= 0, sync_every >= 1.  Workspace: fsk_async_workspace_bytes(). */
+size_t fsk_async_workspace_bytes(const fsk_opts* opts, int32_t tau, int32_t sync_every);
+int fsk_sinkhorn_async_emulated(const fsk_opts* opts, const void* K, int64_t ldK, const void* a,
+                                const void* b, void* u, void* v, int32_t tau, int32_t sync_every,
+                                void* workspace, size_t ws_bytes, void* stream);
+
 /* ---- one worker's share (Sec. 3.1: client j holds rows I_j of K and slices a_j, b_j) -----
  * K_slab: device, `rows` x n, the rows [row0, row0+rows) of K (row0 is only used to index the
  * full-length vectors).  These are the per-worker operations of Algorithm 1 and Sec. 4.1 at

@@ -43,6 +43,7 @@ def _load():
         L.orc_lse.restype = ctypes.c_double
         for name in ("orc_num_threads", "orc_sinkhorn_dense", "orc_sinkhorn_dense_tol",
                      "orc_sinkhorn_blocked", "orc_sinkhorn_dense_damped", "orc_sinkhorn_batched",
+                     "orc_sinkhorn_async_emulated",
                      "orc_sinkhorn_log_points", "orc_sinkhorn_log_cost"):
             getattr(L, name).restype = ctypes.c_int
         _lib = L
@@ -198,6 +199,21 @@ def sinkhorn_dense_damped(K, a, b, iters: int, eta: float, geometric: bool, u0=N
     u, v = _init(K.shape[0], u0), _init(K.shape[0], v0)
     rc = _load().orc_sinkhorn_dense_damped(kp, kf, n, ld, _ptr(a), _ptr(b), _ptr(u), _ptr(v),
                                            _INT(iters), _DBL(eta), _INT(1 if geometric else 0))
+    assert rc == 0
+    return u, v
+
+
+def sinkhorn_async_emulated(K, a, b, iters: int, c: int, eta: float, tau: int, w: int = 1,
+                            u0=None, v0=None):
+    """Bounded-delay emulation of Algorithm 3: remote slices are `tau` iterations old (and only
+    refreshed every `w` iterations), a client's own slice is always current."""
+    kp, kf, n, ld = _square(K)
+    a, b = _f64(a), _f64(b)
+    u, v = _init(K.shape[0], u0), _init(K.shape[0], v0)
+    rc = _load().orc_sinkhorn_async_emulated(kp, kf, n, ld, _ptr(a), _ptr(b), _ptr(u), _ptr(v),
+                                             _INT(iters), _INT(c), _DBL(eta), _INT(tau), _INT(w))
+    if rc == -2:
+        raise ValueError("need c | n, tau >= 0, w >= 1")
     assert rc == 0
     return u, v
 

@@ -17,6 +17,7 @@
  *   - multitarget form: n x N matrices of scalings sharing K (Sec. 5.3.2)
  *   - marginal error of P = diag(u) K diag(v)          (Sec. 5.4, App. DP protocol)
  *   - damped updates, arithmetic and geometric         (Sec. 3.3 and its Remark)
+ *   - bounded-delay emulation of the asynchronous schedule (Algorithm 3, assumption A3)
  *   - log-domain form: the paper only names it (Sec. 1, Sec. 2.1); the
  *     formulas here are the exact logarithm of the iteration above with
  *     f = eps*log u, g = eps*log v.
@@ -294,6 +295,55 @@ int orc_sinkhorn_dense_damped(const void* K, int k_is_f32, int64_t n, int64_t ld
     }
   }
   free(q);
+  return 0;
+}
+
+/* Bounded-delay emulation of the asynchronous All-to-All schedule (Algorithm 3; assumption
+ * A3 of the convergence section) with a deterministic delay: client j (rows/columns
+ * I_j = [j*m, (j+1)*m)) keeps cached global vectors whose own slice is always current and
+ * whose remote slices are what the peers held at the end of iteration s(t), the last exchange
+ * (every `w` iterations) that is at least `tau` iterations old:
+ *     s(t) = floor((t-1-tau)/w)*w   (the initial vectors if that is <= 0).
+ * Iteration t = 1, 2, ...: with v_hat = [remote: v^{s(t)}, own: v^{t-1}_{I_j}],
+ *     u^t_{I_j} = (1-eta) u^{t-1}_{I_j} + eta a_j ./ (K_{I_j,:} v_hat);
+ * then with u_hat = [remote: u^{s(t)}, own: u^t_{I_j}],
+ *     v^t_{I_j} = (1-eta) v^{t-1}_{I_j} + eta b_j ./ ((K_{:,I_j})^T u_hat).
+ * u, v in/out hold the global vectors (every client's own slice). */
+int orc_sinkhorn_async_emulated(const void* K, int k_is_f32, int64_t n, int64_t ld, const double* a,
+                                const double* b, double* u, double* v, int iters, int c, double eta,
+                                int tau, int w) {
+  if (c < 1 || n % c != 0 || tau < 0 || w < 1) return -2;
+  const int64_t m = n / c;
+  /* hist_u[s], hist_v[s]: the global vectors at the end of iteration s (s = 0: the init) */
+  double* hist_u = (double*)malloc(sizeof(double) * (size_t)n * (size_t)(iters + 1));
+  double* hist_v = (double*)malloc(sizeof(double) * (size_t)n * (size_t)(iters + 1));
+  double* view = (double*)malloc(sizeof(double) * (size_t)n);
+  double* prod = (double*)malloc(sizeof(double) * (size_t)n);
+  if (!hist_u || !hist_v || !view || !prod) return -1;
+  memcpy(hist_u, u, sizeof(double) * (size_t)n);
+  memcpy(hist_v, v, sizeof(double) * (size_t)n);
+  for (int t = 1; t <= iters; ++t) {
+    int s = t - 1 - tau;
+    s = s <= 0 ? 0 : (s / w) * w;
+    const double* su = hist_u + (size_t)s * n;       /* what the peers last sent */
+    const double* sv = hist_v + (size_t)s * n;
+    const double* pu = hist_u + (size_t)(t - 1) * n; /* own slices as of the previous iteration */
+    const double* pv = hist_v + (size_t)(t - 1) * n;
+    double* nu = hist_u + (size_t)t * n;
+    double* nv = hist_v + (size_t)t * n;
+    for (int j = 0; j < c; ++j) {
+      const int64_t lo = j * m, hi = (j + 1) * m;
+      for (int64_t i = 0; i < n; ++i) view[i] = (i >= lo && i < hi) ? pv[i] : sv[i];
+      orc_row_products(K, k_is_f32, n, ld, lo, hi, view, prod);
+      for (int64_t i = lo; i < hi; ++i) nu[i] = (1.0 - eta) * pu[i] + eta * (a[i] / prod[i]);
+      for (int64_t i = 0; i < n; ++i) view[i] = (i >= lo && i < hi) ? nu[i] : su[i];
+      orc_col_products(K, k_is_f32, n, ld, 0, n, lo, hi, view, prod);
+      for (int64_t i = lo; i < hi; ++i) nv[i] = (1.0 - eta) * pv[i] + eta * (b[i] / prod[i]);
+    }
+  }
+  memcpy(u, hist_u + (size_t)iters * n, sizeof(double) * (size_t)n);
+  memcpy(v, hist_v + (size_t)iters * n, sizeof(double) * (size_t)n);
+  free(hist_u); free(hist_v); free(view); free(prod);
   return 0;
 }
 

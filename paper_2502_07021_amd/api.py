@@ -29,7 +29,8 @@ EXPORTS = (
     "fsk_version", "fsk_last_error", "fsk_workspace_bytes", "fsk_kernel_from_cost",
     "fsk_kernel_from_points", "fsk_sinkhorn_dense", "fsk_marginals", "fsk_block_rowpass",
     "fsk_block_colpartial", "fsk_block_fused", "fsk_sinkhorn_log_points", "fsk_sinkhorn_batched",
-    "fsk_dense_profile", "fsk_bench_copy", "fsk_bench_read",
+    "fsk_dense_profile", "fsk_bench_copy", "fsk_bench_read", "fsk_async_workspace_bytes",
+    "fsk_sinkhorn_async_emulated",
 )
 
 
@@ -63,6 +64,8 @@ def lib() -> ctypes.CDLL:
         L.fsk_last_error.restype = ctypes.c_char_p
         L.fsk_workspace_bytes.restype = ctypes.c_size_t
         L.fsk_workspace_bytes.argtypes = [ctypes.POINTER(fsk_opts), ctypes.c_int, ctypes.c_int]
+        L.fsk_async_workspace_bytes.restype = ctypes.c_size_t
+        L.fsk_async_workspace_bytes.argtypes = [ctypes.POINTER(fsk_opts), ctypes.c_int32, ctypes.c_int32]
         _lib = L
     return _lib
 
@@ -163,6 +166,17 @@ def fsk_dense_profile(opts, K, a, b, u, v, workspace, reps, stream=None):
                                    _vec(v), wp, wn, ctypes.c_int(reps), ctypes.byref(t_stream),
                                    ctypes.byref(t_other), ctypes.byref(launches), _stream(stream)))
     return float(t_stream.value), float(t_other.value), int(launches.value)
+
+
+def fsk_async_workspace_bytes(opts, tau: int, sync_every: int) -> int:
+    return int(lib().fsk_async_workspace_bytes(ctypes.byref(opts), tau, sync_every))
+
+
+def fsk_sinkhorn_async_emulated(opts, K, a, b, u, v, tau, sync_every, workspace, stream=None) -> int:
+    wp, wn = _ws(workspace)
+    return _check(lib().fsk_sinkhorn_async_emulated(
+        ctypes.byref(opts), _p(K), _ld(K), _vec(a), _vec(b), _vec(u), _vec(v), ctypes.c_int32(tau),
+        ctypes.c_int32(sync_every), wp, wn, _stream(stream)))
 
 
 def fsk_marginals(opts, K, a, u, v, row_marginal, col_marginal, workspace, want_err=False,

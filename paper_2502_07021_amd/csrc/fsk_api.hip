@@ -340,6 +340,71 @@ int fsk_marginals(const fsk_opts* opts, const void* K, int64_t ldK, const void* 
   return FSK_OK;
 }
 
+// ------------------------------------------------------------- bounded-delay emulation
+size_t fsk_async_workspace_bytes(const fsk_opts* opts, int32_t tau, int32_t sync_every) {
+  if (check_common(opts) != FSK_OK || tau < 0 || sync_every < 1) return 0;
+  const size_t vec = align_up((size_t)opts->n * elem_size(opts->dtype), 256);
+  const size_t slots = (size_t)tau + (size_t)sync_every + 1;
+  return dense_ws(opts).total + vec * (2 * slots + 1);
+}
+
+int fsk_sinkhorn_async_emulated(const fsk_opts* opts, const void* K, int64_t ldK, const void* a,
+                                const void* b, void* u, void* v, int32_t tau, int32_t sync_every,
+                                void* workspace, size_t ws_bytes, void* stream) {
+  clear_error();
+  FSK_TRY(check_common(opts));
+  if (opts->m != 1) return set_error(FSK_EINVAL, "dense call takes m = 1");
+  if (tau < 0 || sync_every < 1)
+    return set_error(FSK_EINVAL, "tau = %d must be >= 0 and sync_every = %d >= 1", tau, sync_every);
+  if (opts->tol > 0.0) return set_error(FSK_EUNSUPPORTED, "the emulation runs a fixed number of iterations");
+  if (opts->damping == FSK_DAMP_GEOMETRIC)
+    return set_error(FSK_EUNSUPPORTED, "Algorithm 3 uses the arithmetic relaxation");
+  FSK_TRY(check_matrix("K", K, ldK, opts->n, opts->dtype));
+  FSK_TRY(check_vec("a", a, false));
+  FSK_TRY(check_vec("b", b, false));
+  FSK_TRY(check_vec("u", u, true));
+  FSK_TRY(check_vec("v", v, true));
+  const size_t need = fsk_async_workspace_bytes(opts, tau, sync_every);
+  if (!workspace || ws_bytes < need)
+    return set_error(FSK_EWORKSPACE, "emulation needs %zu workspace bytes, got %zu", need, ws_bytes);
+  if (!aligned16(workspace)) return set_error(FSK_EALIGN, "workspace is not 16-byte aligned");
+  hipStream_t st = (hipStream_t)stream;
+  const int n = opts->n, c = opts->c, m = n / c, dt = opts->dtype;
+  const size_t s = elem_size(dt), vec = align_up((size_t)n * s, 256);
+  const DenseWs w = dense_ws(opts);
+  const int slots = tau + sync_every + 1;
+  char* ws = (char*)workspace;
+  char* ring = ws + w.total;  // slot k: u at ring + 2k*vec, v at ring + (2k+1)*vec
+  char* view = ring + (size_t)2 * slots * vec;
+  auto U = [&](int it) { return ring + (size_t)2 * (it % slots) * vec; };
+  auto V = [&](int it) { return ring + ((size_t)2 * (it % slots) + 1) * vec; };
+  const int epi = opts->damping == FSK_DAMP_ARITHMETIC ? kEpiDampArith : kEpiDivide;
+  const double eta = opts->damping == FSK_DAMP_ARITHMETIC ? opts->eta : 1.0;
+  const char* Kc = (const char*)K;
+  FSK_HIP(hipMemcpyAsync(U(0), u, (size_t)n * s, hipMemcpyDeviceToDevice, st));
+  FSK_HIP(hipMemcpyAsync(V(0), v, (size_t)n * s, hipMemcpyDeviceToDevice, st));
+  for (int t = 1; t <= opts->max_iters; ++t) {
+    int sidx = t - 1 - tau;
+    sidx = sidx <= 0 ? 0 : (sidx / sync_every) * sync_every;
+    const char *su = U(sidx), *sv = V(sidx), *pu = U(t - 1), *pv = V(t - 1);
+    char *nu = U(t), *nv = V(t);
+    for (int j = 0; j < c; ++j) {
+      const int lo = j * m, hi = (j + 1) * m;
+      const size_t off = (size_t)lo * s;
+      FSK_TRY(launch_assemble_view(dt, view, sv, pv, n, lo, hi, st));
+      FSK_TRY(launch_rowpass(dt, Kc + (size_t)lo * (size_t)ldK * s, ldK, n, m, view,
+                             (const char*)a + off, pu + off, nu + off, epi, eta, st));
+      FSK_TRY(launch_assemble_view(dt, view, su, nu, n, lo, hi, st));
+      FSK_TRY(launch_colpartial(dt, K, ldK, n, n, lo, hi, view, ws + w.partial_off, w.ld_ws, st));
+      FSK_TRY(launch_colreduce(dt, ws + w.partial_off, w.ld_ws, col_strips(n), lo, hi, b, pv, nv,
+                               epi, eta, st));
+    }
+  }
+  FSK_HIP(hipMemcpyAsync(u, U(opts->max_iters), (size_t)n * s, hipMemcpyDeviceToDevice, st));
+  FSK_HIP(hipMemcpyAsync(v, V(opts->max_iters), (size_t)n * s, hipMemcpyDeviceToDevice, st));
+  return FSK_OK;
+}
+
 // ------------------------------------------------------------- one worker's share
 static int check_block(const fsk_opts* opts, const void* K_slab, int64_t ldK, int32_t row0,
                        int32_t rows) {

@@ -455,6 +455,29 @@ int launch_fused(int dtype, const FusedPlan& plan, const void* K, int64_t ld, in
                                      ld_ws, eta, stream);
 }
 
+// ================================================================= cached view of a vector
+template <typename T>
+__global__ __launch_bounds__(256) void assemble_view_kernel(T* __restrict__ dst,
+                                                            const T* __restrict__ remote,
+                                                            const T* __restrict__ own, int n, int lo,
+                                                            int hi) {
+  const int i = blockIdx.x * 256 + threadIdx.x;
+  if (i < n) dst[i] = (i >= lo && i < hi) ? own[i] : remote[i];
+}
+
+int launch_assemble_view(int dtype, void* dst, const void* remote, const void* own, int n, int lo,
+                         int hi, hipStream_t stream) {
+  dim3 grid((n + 255) / 256), block(256);
+  if (dtype == FSK_F64)
+    hipLaunchKernelGGL((assemble_view_kernel<double>), grid, block, 0, stream, (double*)dst,
+                       (const double*)remote, (const double*)own, n, lo, hi);
+  else
+    hipLaunchKernelGGL((assemble_view_kernel<float>), grid, block, 0, stream, (float*)dst,
+                       (const float*)remote, (const float*)own, n, lo, hi);
+  FSK_LAUNCH_CHECK("assemble_view_kernel");
+  return FSK_OK;
+}
+
 // ================================================================= fp64 sum of a vector
 template <typename T>
 __global__ __launch_bounds__(1024) void sum_to_double_kernel(const T* __restrict__ x, int n,

@@ -83,6 +83,10 @@ int launch_fused(int dtype, const FusedPlan& plan, const void* K, int64_t ld, in
                  int c, const void* marg, const void* vin, const void* old_u, void* u_out,
                  void* partial, int64_t ld_ws, int epi, double eta, hipStream_t stream);
 
+// dst[i] = own[i] for lo <= i < hi, remote[i] otherwise (a client's cached view of a vector).
+int launch_assemble_view(int dtype, void* dst, const void* remote, const void* own, int n, int lo,
+                         int hi, hipStream_t stream);
+
 // out (one double) = sum of x[0..n) accumulated in fp64 in a fixed order.
 int launch_sum_to_double(int dtype, const void* x, int n, double* out, hipStream_t stream);
 

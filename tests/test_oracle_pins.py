@@ -440,3 +440,62 @@ def test_toy_portfolio_example(orc):
     assert np.allclose(P.sum(1), a, rtol=1e-9) and np.allclose(P.sum(0), b, rtol=1e-12)
     assert set(map(tuple, np.argwhere(Pprint > 0.05))) <= set(map(tuple, np.argwhere(P > 0.01)))
     assert P[2, 2] == pytest.approx(Pprint[2, 2], rel=2e-2)
+
+
+# ------------------------------------- bounded-delay emulation (Algorithm 3) ---
+
+def test_async_emulation_with_one_client_is_the_damped_iteration(orc):
+    """c = 1: there are no remote slices, so any delay gives the centralised relaxed iteration
+    of Sec. 3.3."""
+    x, y, a, b, C, K = problem(30, 30, eps=0.2)
+    for eta in (1.0, 0.5):
+        ud, vd = orc.sinkhorn_dense_damped(K, a, b, 12, eta, False)
+        for tau, w in ((0, 1), (3, 1), (2, 4)):
+            ua, va = orc.sinkhorn_async_emulated(K, a, b, 12, 1, eta, tau, w)
+            assert np.allclose(ua, ud, rtol=1e-13) and np.allclose(va, vd, rtol=1e-13)
+
+
+def test_async_emulation_first_iterations_by_hand(orc):
+    """Two iterations of Algorithm 3 written out with NumPy for c = 2, tau = 1, eta = 0.7:
+    remote slices are still the initial ones in both iterations, own slices are current."""
+    n, m, eta = 8, 4, 0.7
+    x, y, a, b, C, K = problem(n, 31, eps=0.3)
+    u0 = np.ones(n); v0 = np.ones(n)
+    hist = [(u0, v0)]
+    for t in (1, 2):
+        pu, pv = hist[-1]
+        su, sv = hist[0]                      # s(t) = 0 for t <= tau + 1
+        nu, nv = pu.copy(), pv.copy()
+        for j in range(2):
+            I = slice(j * m, (j + 1) * m)
+            view = sv.copy(); view[I] = pv[I]
+            nu[I] = (1 - eta) * pu[I] + eta * a[I] / (K[I, :] @ view)
+            view = su.copy(); view[I] = nu[I]
+            nv[I] = (1 - eta) * pv[I] + eta * b[I] / (K[:, I].T @ view)
+        hist.append((nu, nv))
+    ua, va = orc.sinkhorn_async_emulated(K, a, b, 2, 2, eta, 1, 1)
+    assert np.allclose(ua, hist[-1][0], rtol=1e-13) and np.allclose(va, hist[-1][1], rtol=1e-13)
+    # third iteration sees the peers' slices from the end of iteration 1
+    pu, pv = hist[2]; su, sv = hist[1]
+    nu, nv = pu.copy(), pv.copy()
+    for j in range(2):
+        I = slice(j * m, (j + 1) * m)
+        view = sv.copy(); view[I] = pv[I]
+        nu[I] = (1 - eta) * pu[I] + eta * a[I] / (K[I, :] @ view)
+        view = su.copy(); view[I] = nu[I]
+        nv[I] = (1 - eta) * pv[I] + eta * b[I] / (K[:, I].T @ view)
+    ua, va = orc.sinkhorn_async_emulated(K, a, b, 3, 2, eta, 1, 1)
+    assert np.allclose(ua, nu, rtol=1e-13) and np.allclose(va, nv, rtol=1e-13)
+
+
+@pytest.mark.parametrize("c,tau,w,eta", [(4, 2, 1, 1.0), (4, 3, 2, 0.5), (8, 1, 3, 1.0)])
+def test_async_emulation_converges_to_the_sinkhorn_plan(orc, c, tau, w, eta):
+    """Proposition 2: under bounded delay the scalings converge to a Sinkhorn fixed point
+    (unique up to the scalar gauge), i.e. to the same plan P*."""
+    x, y, a, b, C, K = problem(32, 32, eps=0.25)
+    us, vs = orc.sinkhorn_dense(K, a, b, 4000)
+    Pstar = us[:, None] * K * vs[None, :]
+    ua, va = orc.sinkhorn_async_emulated(K, a, b, 3000, c, eta, tau, w)
+    assert np.allclose(ua[:, None] * K * va[None, :], Pstar, rtol=1e-7)
+    r = ua / us
+    assert np.allclose(r, r[0], rtol=1e-7)
