@@ -98,7 +98,8 @@ typedef struct {
   double eta;          /* relaxation parameter in (0, 1]; ignored when damping = NONE          */
 } fsk_opts;
 
-typedef enum { FSK_MODE_DENSE = 0, FSK_MODE_LOG = 1, FSK_MODE_BATCHED = 2, FSK_MODE_SETUP = 3 } fsk_mode;
+typedef enum { FSK_MODE_DENSE = 0, FSK_MODE_LOG = 1, FSK_MODE_BATCHED = 2, FSK_MODE_SETUP = 3,
+               FSK_MODE_PLAN = 4 } fsk_mode;
 
 /* Library version as major*10000 + minor*100 + patch. */
 int fsk_version(void);
@@ -139,6 +140,18 @@ int fsk_sinkhorn_dense(const fsk_opts* opts, const void* K, int64_t ldK, const v
 int fsk_marginals(const fsk_opts* opts, const void* K, int64_t ldK, const void* a, const void* u,
                   const void* v, void* row_marginal, void* col_marginal, void* workspace,
                   size_t ws_bytes, double* err_l1, void* stream);
+
+/* ---- objective of Eq. 1 at P = diag(u) K diag(v), without materialising P -----------------
+ * One pass over K and the cost matrix C (device, n x n, same dtype, leading dimension ldC).
+ * out (host, 5 doubles; the call synchronises):
+ *   out[0] = <P, C>                  out[1] = sum_ij P_ij (log P_ij - 1)      (0 log 0 = 0)
+ *   out[2] = out[0] + eps * out[1]   (the objective of Eq. 1)
+ *   out[3] = sum_ij P_ij             out[4] = sum_ij P_ij l_j, l a device n-vector or NULL (0)
+ * out[4] with l_j = l(x'_j) is the worst-case expected loss of the paper's finance example.
+ * Workspace: fsk_workspace_bytes(opts, FSK_MODE_PLAN, 0). */
+int fsk_plan_objective(const fsk_opts* opts, const void* K, int64_t ldK, const void* C, int64_t ldC,
+                       double eps, const void* u, const void* v, const void* l, double* out,
+                       void* workspace, size_t ws_bytes, void* stream);
 
 /* ---- bounded-delay emulation of the asynchronous schedule (Algorithm 3; assumption A3 of the
  * convergence section) on one device, with a deterministic delay.  Client j owns rows/columns

@@ -246,6 +246,19 @@ def col_marginal(K, u, v) -> np.ndarray:
     return out
 
 
+def plan_objective(K, C, eps: float, u, v, l=None) -> np.ndarray:
+    """[<P,C>, sum P(log P - 1), Eq. 1 objective, sum P, sum_ij P_ij l_j] at P = diag(u) K diag(v)."""
+    kp, kf, n, ld = _square(K)
+    C, u, v = _f64(C), _f64(u), _f64(v)
+    out = np.zeros(5, dtype=np.float64)
+    lp = _P(None)
+    if l is not None:
+        l = _f64(l)
+        lp = _ptr(l)
+    _load().orc_plan_objective(kp, kf, _ptr(C), n, ld, _DBL(eps), _ptr(u), _ptr(v), lp, _ptr(out))
+    return out
+
+
 def marginal_error(K, a, u, v) -> tuple[float, float]:
     """(||P1 - a||_1, ||P1 - a||_2) for P = diag(u) K diag(v)."""
     kp, kf, n, ld = _square(K)

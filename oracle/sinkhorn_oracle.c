@@ -16,6 +16,7 @@
  *   - blocked iterates equal centralised iterates      (Proposition 1)
  *   - multitarget form: n x N matrices of scalings sharing K (Sec. 5.3.2)
  *   - marginal error of P = diag(u) K diag(v)          (Sec. 5.4, App. DP protocol)
+ *   - the objective of Eq. 1 and the expected loss sum P_ij l(x'_j) of the finance example
  *   - damped updates, arithmetic and geometric         (Sec. 3.3 and its Remark)
  *   - bounded-delay emulation of the asynchronous schedule (Algorithm 3, assumption A3)
  *   - log-domain form: the paper only names it (Sec. 1, Sec. 2.1); the
@@ -206,6 +207,24 @@ void orc_marginal_error(const void* K, int k_is_f32, int64_t n, int64_t ld, cons
   *err_l1 = s1;
   *err_l2 = sqrt(s2);
   free(p);
+}
+
+/* Objective of Eq. 1 and related sums at P = diag(u) K diag(v), by explicit loops over P:
+ *   out[0] = <P, C>                      out[1] = sum P_ij (log P_ij - 1)   (0 log 0 = 0)
+ *   out[2] = out[0] + eps * out[1]       out[3] = sum P_ij
+ *   out[4] = sum_ij P_ij l_j (0 if l is NULL) -- the expected loss of the finance example. */
+void orc_plan_objective(const void* K, int k_is_f32, const double* C, int64_t n, int64_t ld,
+                        double eps, const double* u, const double* v, const double* l, double* out) {
+  double pc = 0.0, ent = 0.0, mass = 0.0, loss = 0.0;
+  for (int64_t i = 0; i < n; ++i)
+    for (int64_t j = 0; j < n; ++j) {
+      const double p = u[i] * k_at(K, k_is_f32, ld, i, j) * v[j];
+      pc += p * C[i * n + j];
+      if (p > 0.0) ent += p * (log(p) - 1.0);
+      mass += p;
+      if (l) loss += p * l[j];
+    }
+  out[0] = pc; out[1] = ent; out[2] = pc + eps * ent; out[3] = mass; out[4] = loss;
 }
 
 /* Tolerance mode: iterate; after every `check_every`-th iteration (and after

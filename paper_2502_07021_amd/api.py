@@ -23,14 +23,14 @@ FSK_EINVAL, FSK_EALIGN, FSK_EDIV, FSK_EWORKSPACE, FSK_ENONFINITE, FSK_EHIP, FSK_
 FSK_F32, FSK_F64 = 0, 1
 FSK_FLOW_FUSED, FSK_FLOW_TWO_PASS, FSK_FLOW_PAPER = 0, 1, 2
 FSK_DAMP_NONE, FSK_DAMP_ARITHMETIC, FSK_DAMP_GEOMETRIC = 0, 1, 2
-FSK_MODE_DENSE, FSK_MODE_LOG, FSK_MODE_BATCHED, FSK_MODE_SETUP = 0, 1, 2, 3
+FSK_MODE_DENSE, FSK_MODE_LOG, FSK_MODE_BATCHED, FSK_MODE_SETUP, FSK_MODE_PLAN = 0, 1, 2, 3, 4
 
 EXPORTS = (
     "fsk_version", "fsk_last_error", "fsk_workspace_bytes", "fsk_kernel_from_cost",
     "fsk_kernel_from_points", "fsk_sinkhorn_dense", "fsk_marginals", "fsk_block_rowpass",
     "fsk_block_colpartial", "fsk_block_fused", "fsk_sinkhorn_log_points", "fsk_sinkhorn_batched",
     "fsk_dense_profile", "fsk_bench_copy", "fsk_bench_read", "fsk_async_workspace_bytes",
-    "fsk_sinkhorn_async_emulated",
+    "fsk_sinkhorn_async_emulated", "fsk_plan_objective",
 )
 
 
@@ -166,6 +166,16 @@ def fsk_dense_profile(opts, K, a, b, u, v, workspace, reps, stream=None):
                                    _vec(v), wp, wn, ctypes.c_int(reps), ctypes.byref(t_stream),
                                    ctypes.byref(t_other), ctypes.byref(launches), _stream(stream)))
     return float(t_stream.value), float(t_other.value), int(launches.value)
+
+
+def fsk_plan_objective(opts, K, C, eps, u, v, l, workspace, stream=None):
+    """Returns [<P,C>, sum P(log P - 1), Eq. 1 objective, sum P, sum_ij P_ij l_j] (synchronises)."""
+    wp, wn = _ws(workspace)
+    out = (ctypes.c_double * 5)()
+    _check(lib().fsk_plan_objective(ctypes.byref(opts), _p(K), _ld(K), _p(C), _ld(C),
+                                    ctypes.c_double(eps), _vec(u), _vec(v), _vec(l), out, wp, wn,
+                                    _stream(stream)))
+    return [float(x) for x in out]
 
 
 def fsk_async_workspace_bytes(opts, tau: int, sync_every: int) -> int:

@@ -120,6 +120,7 @@ size_t fsk_workspace_bytes(const fsk_opts* opts, int mode, int d) {
   switch (mode) {
     case FSK_MODE_DENSE: return dense_ws(opts).total;
     case FSK_MODE_LOG: return log_workspace_bytes(opts->n, d);
+    case FSK_MODE_PLAN: return 4 * align_up((size_t)opts->n * elem_size(opts->dtype), 256) + 256;
     case FSK_MODE_BATCHED: return batched_workspace_bytes(opts->n, opts->m);
     case FSK_MODE_SETUP: return align_up(max_sqdist_scratch_doubles(opts->n) * 8, 256) + 256;
     default: return 0;
@@ -337,6 +338,43 @@ int fsk_marginals(const fsk_opts* opts, const void* K, int64_t ldK, const void* 
     FSK_TRY(check_vec("a", a, false));
     FSK_TRY(dense_error(opts, w, K, ldK, a, u, v, ws, err_l1, st));
   }
+  return FSK_OK;
+}
+
+// ------------------------------------------------------------- plan objective
+int fsk_plan_objective(const fsk_opts* opts, const void* K, int64_t ldK, const void* C, int64_t ldC,
+                       double eps, const void* u, const void* v, const void* l, double* out,
+                       void* workspace, size_t ws_bytes, void* stream) {
+  clear_error();
+  FSK_TRY(check_common(opts));
+  if (!out) return set_error(FSK_EINVAL, "out is NULL");
+  if (!(eps > 0.0)) return set_error(FSK_EINVAL, "eps = %g must be positive", eps);
+  FSK_TRY(check_matrix("K", K, ldK, opts->n, opts->dtype));
+  FSK_TRY(check_matrix("C", C, ldC, opts->n, opts->dtype));
+  FSK_TRY(check_vec("u", u, false));
+  FSK_TRY(check_vec("v", v, true));
+  if (l && !aligned16(l)) return set_error(FSK_EALIGN, "l is not 16-byte aligned");
+  const size_t need = fsk_workspace_bytes(opts, FSK_MODE_PLAN, 0);
+  if (!workspace || ws_bytes < need)
+    return set_error(FSK_EWORKSPACE, "plan objective needs %zu workspace bytes, got %zu", need, ws_bytes);
+  if (!aligned16(workspace)) return set_error(FSK_EALIGN, "workspace is not 16-byte aligned");
+  hipStream_t st = (hipStream_t)stream;
+  const int n = opts->n, dt = opts->dtype;
+  const size_t vec = align_up((size_t)n * elem_size(dt), 256);
+  const int64_t stride = (int64_t)(vec / elem_size(dt));
+  char* ws = (char*)workspace;
+  double* sums = (double*)(ws + 4 * vec);
+  FSK_TRY(launch_plan_rows(dt, K, ldK, C, ldC, n, u, v, l, ws, stride, st));
+  for (int q = 0; q < 4; ++q)
+    FSK_TRY(launch_sum_to_double(dt, ws + (size_t)q * vec, n, sums + q, st));
+  double h[4];
+  FSK_HIP(hipMemcpyAsync(h, sums, sizeof(h), hipMemcpyDeviceToHost, st));
+  FSK_HIP(hipStreamSynchronize(st));
+  out[0] = h[1];
+  out[1] = h[2] - h[0];
+  out[2] = out[0] + eps * out[1];
+  out[3] = h[0];
+  out[4] = l ? h[3] : 0.0;
   return FSK_OK;
 }
 

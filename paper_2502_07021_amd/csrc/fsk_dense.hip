@@ -455,6 +455,110 @@ int launch_fused(int dtype, const FusedPlan& plan, const void* K, int64_t ld, in
                                      ld_ws, eta, stream);
 }
 
+// ================================================================= plan sums (Eq. 1)
+// Same walk as the row pass, over two matrices at once (K and the cost C); four running sums
+// per row.  HBM bound: 2 n^2 s bytes.
+__device__ __forceinline__ float fsk_log(float x) { return logf(x); }
+__device__ __forceinline__ double fsk_log(double x) { return log(x); }
+
+template <typename T, int ROWS>
+__global__ __launch_bounds__(256) void plan_rows_kernel(const T* __restrict__ K, int64_t ldK,
+                                                        const T* __restrict__ C, int64_t ldC, int n,
+                                                        const T* __restrict__ u,
+                                                        const T* __restrict__ v,
+                                                        const T* __restrict__ l,
+                                                        T* __restrict__ rows, int64_t stride) {
+  constexpr int W = Pack<T>::W;
+  constexpr int NT = 256, NW = NT / kWave;
+  const int tid = threadIdx.x;
+  const int r_base = blockIdx.x * ROWS;
+  const int nvec_full = n / W;
+  const T* kp[ROWS];
+  const T* cp[ROWS];
+#pragma unroll
+  for (int r = 0; r < ROWS; ++r) {
+    int row = r_base + r;
+    row = row < n ? row : n - 1;
+    kp[r] = K + (int64_t)row * ldK;
+    cp[r] = C + (int64_t)row * ldC;
+  }
+  T acc[ROWS][4];
+#pragma unroll
+  for (int r = 0; r < ROWS; ++r)
+#pragma unroll
+    for (int q = 0; q < 4; ++q) acc[r][q] = T(0);
+  auto term = [&](int r, T k, T c, T vj, T lj) {
+    const T kv = k * vj;
+    acc[r][0] += kv;
+    acc[r][1] = fma(kv, c, acc[r][1]);
+    if (kv > T(0)) acc[r][2] = fma(kv, fsk_log(kv), acc[r][2]);
+    acc[r][3] = fma(kv, lj, acc[r][3]);
+  };
+  for (int cidx = tid; cidx < nvec_full; cidx += NT) {
+    const Pack<T> vv = load_pack(v + (int64_t)cidx * W);
+    Pack<T> ll;
+#pragma unroll
+    for (int e = 0; e < W; ++e) ll.e[e] = T(0);
+    if (l) ll = load_pack(l + (int64_t)cidx * W);
+#pragma unroll
+    for (int r = 0; r < ROWS; ++r) {
+      const Pack<T> kk = load_pack_stream(kp[r] + (int64_t)cidx * W);
+      const Pack<T> cc = load_pack_stream(cp[r] + (int64_t)cidx * W);
+#pragma unroll
+      for (int e = 0; e < W; ++e) term(r, kk.e[e], cc.e[e], vv.e[e], ll.e[e]);
+    }
+  }
+  if (tid == 0) {
+    for (int j = nvec_full * W; j < n; ++j)
+#pragma unroll
+      for (int r = 0; r < ROWS; ++r) term(r, kp[r][j], cp[r][j], v[j], l ? l[j] : T(0));
+  }
+  __shared__ T red[ROWS][4][NW];
+  const int lane = tid & (kWave - 1), wave = tid / kWave;
+#pragma unroll
+  for (int r = 0; r < ROWS; ++r)
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      const T s = wave_sum(acc[r][q]);
+      if (lane == 0) red[r][q][wave] = s;
+    }
+  __syncthreads();
+  if (tid < ROWS) {
+    const int row = r_base + tid;
+    if (row < n) {
+      T s[4];
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        s[q] = T(0);
+#pragma unroll
+        for (int k = 0; k < NW; ++k) s[q] += red[tid][q][k];
+      }
+      const T ui = u[row];
+      rows[row] = ui * s[0];
+      rows[stride + row] = ui * s[1];
+      rows[2 * stride + row] = ui > T(0) ? ui * (s[2] + fsk_log(ui) * s[0]) : T(0);
+      rows[3 * stride + row] = ui * s[3];
+    }
+  }
+}
+
+int launch_plan_rows(int dtype, const void* K, int64_t ldK, const void* C, int64_t ldC, int n,
+                     const void* u, const void* v, const void* l, void* rows, int64_t stride,
+                     hipStream_t stream) {
+  constexpr int ROWS = 2;
+  dim3 grid((n + ROWS - 1) / ROWS), block(256);
+  if (dtype == FSK_F64)
+    hipLaunchKernelGGL((plan_rows_kernel<double, ROWS>), grid, block, 0, stream, (const double*)K,
+                       ldK, (const double*)C, ldC, n, (const double*)u, (const double*)v,
+                       (const double*)l, (double*)rows, stride);
+  else
+    hipLaunchKernelGGL((plan_rows_kernel<float, ROWS>), grid, block, 0, stream, (const float*)K, ldK,
+                       (const float*)C, ldC, n, (const float*)u, (const float*)v, (const float*)l,
+                       (float*)rows, stride);
+  FSK_LAUNCH_CHECK("plan_rows_kernel");
+  return FSK_OK;
+}
+
 // ================================================================= cached view of a vector
 template <typename T>
 __global__ __launch_bounds__(256) void assemble_view_kernel(T* __restrict__ dst,

@@ -83,6 +83,14 @@ int launch_fused(int dtype, const FusedPlan& plan, const void* K, int64_t ld, in
                  int c, const void* marg, const void* vin, const void* old_u, void* u_out,
                  void* partial, int64_t ld_ws, int epi, double eta, hipStream_t stream);
 
+// Per-row terms of the plan sums: with kv_ij = K_ij v_j,
+//   rows[0][i] = u_i sum_j kv_ij            rows[1][i] = u_i sum_j kv_ij C_ij
+//   rows[2][i] = u_i (sum_j kv_ij log kv_ij + log(u_i) sum_j kv_ij)
+//   rows[3][i] = u_i sum_j kv_ij l_j        (0 if l is NULL);   rows: 4 arrays of `stride` elements.
+int launch_plan_rows(int dtype, const void* K, int64_t ldK, const void* C, int64_t ldC, int n,
+                     const void* u, const void* v, const void* l, void* rows, int64_t stride,
+                     hipStream_t stream);
+
 // dst[i] = own[i] for lo <= i < hi, remote[i] otherwise (a client's cached view of a vector).
 int launch_assemble_view(int dtype, void* dst, const void* remote, const void* own, int n, int lo,
                          int hi, hipStream_t stream);

@@ -499,3 +499,26 @@ def test_async_emulation_converges_to_the_sinkhorn_plan(orc, c, tau, w, eta):
     assert np.allclose(ua[:, None] * K * va[None, :], Pstar, rtol=1e-7)
     r = ua / us
     assert np.allclose(r, r[0], rtol=1e-7)
+
+
+# ------------------------------------------------------------ plan objective ---
+
+def test_plan_objective_against_numpy_and_duality(orc):
+    """Eq. 1 evaluated at P = diag(u) K diag(v): against NumPy on the explicit plan, and at
+    convergence against the dual value (an independent formula)."""
+    x, y, a, b, C, K = problem(14, 40, eps=0.15)
+    eps = 0.15
+    rng = np.random.default_rng(4)
+    l = rng.normal(size=14)
+    u, v = orc.sinkhorn_dense(K, a, b, 7)
+    P = u[:, None] * K * v[None, :]
+    out = orc.plan_objective(K, C, eps, u, v, l)
+    assert out[0] == pytest.approx((P * C).sum(), rel=1e-13)
+    assert out[1] == pytest.approx((P * (np.log(P) - 1)).sum(), rel=1e-13)
+    assert out[2] == pytest.approx(primal_objective(P, C, eps), rel=1e-13)
+    assert out[3] == pytest.approx(P.sum(), rel=1e-13)
+    assert out[4] == pytest.approx((P * l[None, :]).sum(), rel=1e-12)
+    u, v = orc.sinkhorn_dense(K, a, b, 5000)
+    out = orc.plan_objective(K, C, eps, u, v)
+    assert out[2] == pytest.approx(dual_objective(eps * np.log(u), eps * np.log(v), a, b, C, eps), abs=1e-12)
+    assert out[4] == 0.0
