@@ -255,7 +255,7 @@ def bench_batched(args):
                                f"pairs, x,y~U[0,1]^2, eps={w.eps}", "n": n, "m": m},
         "roofline": {"bound": "mfma", "achieved": achieved, "peak": PEAK_FP32_MFMA_TFLOPS,
                      "unit": "TFLOP/s", "frac": achieved / PEAK_FP32_MFMA_TFLOPS, "traffic": None,
-                     "kernel": "batched_prod_kernel<true> (both products)",
+                     "kernel": "batched_prod_wide_kernel (both products)",
                      "kernel_ms": launch_ms, "launches_per_step": 2,
                      "note": "kernel_ms = event-timed run / product launches; includes the small reduce "
                              "kernels and 1/reps of the K^T build"},

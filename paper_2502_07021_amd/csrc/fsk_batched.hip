@@ -5,35 +5,31 @@
 //
 // and run on the matrix cores with v_mfma_f32_32x32x2_f32 (fp32 in, fp32 accumulate).
 //
-// Both products use the same plan.  A workgroup of 4 waves owns a 256 x 64 output tile
-// (64 x 64 per wave: 2 x 2 MFMA blocks, 64 accumulator registers) and one part of the
-// contraction range, walked in chunks of 32 indices.  K, the operand that streams from
-// HBM, goes straight from global memory into registers (128-bit loads along a row for
-// K V, 64-bit loads for K^T U, non-temporal, one chunk ahead of the MFMAs).  The chunk of
-// the n x m operand (32 x 64 values) is shared by the four waves: it is staged in LDS,
-// double buffered, one barrier per chunk.  The grid splits the contraction range S ways;
-// the S partial tiles go to the workspace and a reduction kernel adds them in fixed order
-// and applies the division (S = 1: the division is fused into the tile store).
-//
-// The row-major walk of K^T U (lanes along a row of K, 64-bit loads, 256 contiguous bytes
-// per half-wave) costs the memory pipeline far fewer address operations than the walk of
-// K V (every lane on a different row), and that, not HBM, is what limits these kernels.
-// Since K is fixed over hundreds of iterations, the call therefore builds K^T once in the
-// workspace and runs BOTH products as "transposed" products (Q = (K^T)^T V).  When the
-// workspace has no room for K^T the direct row-product kernel is used instead.
+// A walk of K in which the lanes of a wave run along a row (R = K^T X: output rows are
+// columns of K) costs the memory pipeline far fewer address operations than one in which
+// every lane sits on its own row (Q = K X), and that, not HBM, limits these kernels.  K is
+// fixed over hundreds of iterations, so the call builds K^T once in the workspace and runs
+// BOTH products as transposed products (Q = (K^T)^T V) with batched_prod_wide_kernel: a
+// wave owns a 128 x 64 output tile (4 x 2 MFMA blocks, 128 accumulator registers, one wave
+// per SIMD), a workgroup of 4 waves 512 x 64 and one part of the contraction range, walked in
+// chunks of 32 indices.  K goes straight from global memory into registers (128-bit
+// non-temporal loads, one chunk ahead of the MFMAs); the chunk of the n x m operand (32 x 64
+// values) is shared by the four waves through LDS, double buffered, one barrier per chunk.
+// The grid splits the contraction range S ways; the S partial tiles go to the workspace and
+// a reduction kernel adds them in fixed order and applies the division (S = 1: the division
+// is fused into the tile store).  When the workspace has no room for K^T, Q = K V falls back
+// to batched_rowprod_kernel, the direct walk with a 64 x 64 tile per wave.
 //
 // MFMA 32x32x2 operand layout (lane l of 64): A[i = l%32][k = l/32],
 // B[k = l/32][j = l%32], D[i = 8(v/4) + 4(l/32) + v%4][j = l%32] for accumulator
 // register v.  MFMA e of a chunk of C indices contracts the chunk's indices {e, C/2 + e},
-// so lane (.., h = l/32) supplies index (C/2) h + e: with K row-major a lane fetches its
-// C/2 values of a chunk as 128-bit loads along its row.
+// so lane (.., h = l/32) supplies index (C/2) h + e.
 #include "fsk_device.h"
 #include "fsk_internal.h"
 
 namespace fsk {
 
 typedef float floatx16 __attribute__((ext_vector_type(16)));
-typedef float floatx2 __attribute__((ext_vector_type(2)));
 
 constexpr int kBtCols = 64;        // histogram columns per call (m <= 64)
 constexpr int kBtWaveTile = 64;    // output rows per wave
@@ -47,12 +43,11 @@ __device__ __forceinline__ floatx16 mfma32(float a, float b, floatx16 c) {
   return __builtin_amdgcn_mfma_f32_32x32x2f32(a, b, c, 0, 0, 0);
 }
 
-// One product.  COLPROD == false: out rows are rows of K, contraction over columns
-// (Q = K X).  COLPROD == true: out rows are columns of K, contraction over rows (R = K^T X).
-// X is the n x m operand.  final != 0: out = marg ./ product; else the partial product of
-// this grid slice goes to out + slice * n * m.
-template <bool COLPROD>
-__global__ __launch_bounds__(256) void batched_prod_kernel(const float* __restrict__ K, int64_t ld,
+// Q = K X by the direct walk: out rows are rows of K, contraction over columns, a lane
+// fetches its row's values of a chunk as 128-bit loads.  X is the n x m operand.
+// final != 0: out = marg ./ product; else the partial product of this grid slice goes to
+// out + slice * n * m.
+__global__ __launch_bounds__(256) void batched_rowprod_kernel(const float* __restrict__ K, int64_t ld,
                                                            int n, int m,
                                                            const float* __restrict__ X,
                                                            const float* __restrict__ marg,
@@ -81,41 +76,24 @@ __global__ __launch_bounds__(256) void batched_prod_kernel(const float* __restri
 
   // --- K addressing of this lane
   const float* kbase[2];
-  if (!COLPROD) {
 #pragma unroll
-    for (int a = 0; a < 2; ++a) {
-      int row = o0 + 32 * a + r;
-      row = row < n ? row : n - 1;  // clamp; rows past the end are dropped at the store
-      kbase[a] = K + (int64_t)row * ld;
-    }
-  } else {
-    int jc = o0 + 2 * r;  // two adjacent columns of K per lane, clamped inside the row pitch
-    const int jmax = (int)ld - 2;
-    jc = jc < jmax ? jc : jmax;
-    kbase[0] = kbase[1] = K + jc;
+  for (int a = 0; a < 2; ++a) {
+    int row = o0 + 32 * a + r;
+    row = row < n ? row : n - 1;  // clamp; rows past the end are dropped at the store
+    kbase[a] = K + (int64_t)row * ld;
   }
 
   // ka[a][e]: the K value of MFMA row r of block a for contraction index 16h + e of a chunk
   auto load_k = [&](int c, float(&ka)[2][kBtHalf]) {
     const int first = c * kBtChunk + kBtHalf * h;
-    if (!COLPROD) {
 #pragma unroll
-      for (int a = 0; a < 2; ++a)
+    for (int a = 0; a < 2; ++a)
 #pragma unroll
-        for (int t = 0; t < kBtHalf / 4; ++t) {
-          const Pack<float> p = load_pack_stream(kbase[a] + first + 4 * t);
+      for (int t = 0; t < kBtHalf / 4; ++t) {
+        const Pack<float> p = load_pack_stream(kbase[a] + first + 4 * t);
 #pragma unroll
-          for (int e = 0; e < 4; ++e) ka[a][4 * t + e] = p.e[e];
-        }
-    } else {
-#pragma unroll
-      for (int e = 0; e < kBtHalf; ++e) {
-        const floatx2 p = __builtin_nontemporal_load(
-            reinterpret_cast<const floatx2*>(kbase[0] + (int64_t)(first + e) * ld));
-        ka[0][e] = p[0];
-        ka[1][e] = p[1];
+        for (int e = 0; e < 4; ++e) ka[a][4 * t + e] = p.e[e];
       }
-    }
   };
   // same with the contraction indices >= n masked to zero (ragged last chunk)
   auto load_k_masked = [&](int c, float(&ka)[2][kBtHalf]) {
@@ -124,14 +102,8 @@ __global__ __launch_bounds__(256) void batched_prod_kernel(const float* __restri
     for (int e = 0; e < kBtHalf; ++e) {
       const bool ok = first + e < n;
       const int kk = ok ? first + e : n - 1;
-      if (!COLPROD) {
 #pragma unroll
-        for (int a = 0; a < 2; ++a) ka[a][e] = ok ? kbase[a][kk] : 0.f;
-      } else {
-        const floatx2 p = *reinterpret_cast<const floatx2*>(kbase[0] + (int64_t)kk * ld);
-        ka[0][e] = ok ? p[0] : 0.f;
-        ka[1][e] = ok ? p[1] : 0.f;
-      }
+      for (int a = 0; a < 2; ++a) ka[a][e] = ok ? kbase[a][kk] : 0.f;
     }
   };
 
@@ -182,6 +154,9 @@ __global__ __launch_bounds__(256) void batched_prod_kernel(const float* __restri
   for (; c + 2 <= full_end; c += 2) {
     load_k(c + 1, kaB);
     load_x(c + 1, st);
+    // keep the loads above the MFMAs: left alone the scheduler sinks them to the end of
+    // the chunk to shorten register live ranges, which throws the prefetch away
+    __builtin_amdgcn_sched_barrier(0);
     multiply(0, kaA);
     store_x(1, st);
     __syncthreads();
@@ -190,6 +165,7 @@ __global__ __launch_bounds__(256) void batched_prod_kernel(const float* __restri
       load_k(c + 2, kaA);
       load_x(c + 2, st);
     }
+    __builtin_amdgcn_sched_barrier(0);
     multiply(1, kaB);
     if (more) store_x(0, st);
     __syncthreads();
@@ -214,7 +190,161 @@ __global__ __launch_bounds__(256) void batched_prod_kernel(const float* __restri
 #pragma unroll
     for (int v = 0; v < 16; ++v) {
       const int i = 8 * (v / 4) + 4 * h + (v % 4);  // MFMA row of accumulator register v
-      const int row = COLPROD ? o0 + 2 * i + a : o0 + 32 * a + i;
+      const int row = o0 + 32 * a + i;
+      if (row < n) {
+#pragma unroll
+        for (int b = 0; b < 2; ++b) {
+          const int col = 32 * b + r;
+          if (col < m) {
+            const int64_t idx = (int64_t)row * m + col;
+            dst[idx] = final ? marg[idx] / acc[a][b][v] : acc[a][b][v];
+          }
+        }
+      }
+    }
+}
+
+// ------------------------------------------------------------------ wide transposed product
+// R = K^T X with a 128 x 64 output tile per wave (512 x 64 per workgroup): a lane fetches four
+// adjacent columns of K with one 128-bit load (512 contiguous bytes per half-wave), so MFMA
+// row i of block a is column o0 + 4 i + a of K; 4 x 2 MFMA blocks, 128 accumulator registers,
+// one wave per SIMD.  Twice the flops per load instruction and per LDS read of the 64 x 64
+// kernel above; the loads of the next chunk are in flight under the 128 MFMAs of this one.
+constexpr int kBtWideWaveTile = 128;
+constexpr int kBtWideTile = kBtWideWaveTile * kBtWaves;
+
+__global__ __launch_bounds__(256) void batched_prod_wide_kernel(const float* __restrict__ K,
+                                                                int64_t ld, int n, int m,
+                                                                const float* __restrict__ X,
+                                                                const float* __restrict__ marg,
+                                                                float* __restrict__ out, int final) {
+  __shared__ float xs[2][kBtChunk][kBtCols];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int r = lane & 31, h = lane >> 5;
+  const int o0 = blockIdx.x * kBtWideTile + wave * kBtWideWaveTile;
+
+  const int nchunks = (n + kBtChunk - 1) / kBtChunk;
+  const int per = (nchunks + gridDim.y - 1) / gridDim.y;
+  int c0 = blockIdx.y * per;
+  int c1 = c0 + per < nchunks ? c0 + per : nchunks;
+  if (c0 > c1) c0 = c1;
+  int full_end = n / kBtChunk < c1 ? n / kBtChunk : c1;
+  if (full_end < c0) full_end = c0;
+
+  floatx16 acc[4][2];
+#pragma unroll
+  for (int a = 0; a < 4; ++a)
+#pragma unroll
+    for (int b = 0; b < 2; ++b)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[a][b][v] = 0.f;
+
+  int jc = o0 + 4 * r;  // four adjacent columns of K per lane, clamped inside the row pitch
+  const int jmax = (int)ld - 4;
+  jc = jc < jmax ? jc : jmax;
+  const float* kcol = K + jc;
+
+  auto load_k = [&](int c, Pack<float>(&ka)[kBtHalf]) {
+    const int first = c * kBtChunk + kBtHalf * h;
+#pragma unroll
+    for (int e = 0; e < kBtHalf; ++e) ka[e] = load_pack_stream(kcol + (int64_t)(first + e) * ld);
+  };
+  auto load_k_masked = [&](int c, Pack<float>(&ka)[kBtHalf]) {
+    const int first = c * kBtChunk + kBtHalf * h;
+#pragma unroll
+    for (int e = 0; e < kBtHalf; ++e) {
+      const bool ok = first + e < n;
+      Pack<float> p = load_pack(kcol + (int64_t)(ok ? first + e : n - 1) * ld);
+#pragma unroll
+      for (int q = 0; q < 4; ++q) p.e[q] = ok ? p.e[q] : 0.f;
+      ka[e] = p;
+    }
+  };
+
+  const int sc = tid & 63, sk = tid >> 6;
+  const float* xcol = X + (sc < m ? sc : m - 1);
+  auto load_x = [&](int c, float(&st)[kBtStage]) {
+#pragma unroll
+    for (int i = 0; i < kBtStage; ++i) st[i] = xcol[(int64_t)(c * kBtChunk + sk + 4 * i) * m];
+  };
+  auto load_x_masked = [&](int c, float(&st)[kBtStage]) {
+#pragma unroll
+    for (int i = 0; i < kBtStage; ++i) {
+      const int kk = c * kBtChunk + sk + 4 * i;
+      const float val = xcol[(int64_t)(kk < n ? kk : n - 1) * m];
+      st[i] = kk < n ? val : 0.f;
+    }
+  };
+  auto store_x = [&](int buf, const float(&st)[kBtStage]) {
+#pragma unroll
+    for (int i = 0; i < kBtStage; ++i) xs[buf][sk + 4 * i][sc] = st[i];
+  };
+  auto multiply = [&](int buf, const Pack<float>(&ka)[kBtHalf]) {
+    float b0[kBtHalf], b1[kBtHalf];  // the chunk's B operands, fetched from LDS up front
+#pragma unroll
+    for (int e = 0; e < kBtHalf; ++e) {
+      b0[e] = xs[buf][kBtHalf * h + e][r];
+      b1[e] = xs[buf][kBtHalf * h + e][32 + r];
+    }
+    __builtin_amdgcn_sched_barrier(0);  // one LDS wait per chunk instead of one per k-step
+#pragma unroll
+    for (int e = 0; e < kBtHalf; ++e) {
+#pragma unroll
+      for (int a = 0; a < 4; ++a) {
+        acc[a][0] = mfma32(ka[e].e[a], b0[e], acc[a][0]);
+        acc[a][1] = mfma32(ka[e].e[a], b1[e], acc[a][1]);
+      }
+    }
+  };
+
+  Pack<float> kaA[kBtHalf], kaB[kBtHalf];
+  float st[kBtStage];
+  if (c0 < full_end) {
+    load_k(c0, kaA);
+    load_x(c0, st);
+    store_x(0, st);
+  }
+  __syncthreads();
+  int c = c0;
+  for (; c + 2 <= full_end; c += 2) {
+    load_k(c + 1, kaB);
+    load_x(c + 1, st);
+    // keep the loads above the MFMAs: left alone the scheduler sinks them to the end of
+    // the chunk to shorten register live ranges, which throws the prefetch away
+    __builtin_amdgcn_sched_barrier(0);
+    multiply(0, kaA);
+    store_x(1, st);
+    __syncthreads();
+    const bool more = c + 2 < full_end;
+    if (more) {
+      load_k(c + 2, kaA);
+      load_x(c + 2, st);
+    }
+    __builtin_amdgcn_sched_barrier(0);
+    multiply(1, kaB);
+    if (more) store_x(0, st);
+    __syncthreads();
+  }
+  if (c < full_end) {
+    multiply(0, kaA);
+    __syncthreads();
+  }
+  if (full_end < c1) {
+    load_k_masked(full_end, kaA);
+    load_x_masked(full_end, st);
+    __syncthreads();
+    store_x(0, st);
+    __syncthreads();
+    multiply(0, kaA);
+  }
+
+  float* dst = final ? out : out + (int64_t)blockIdx.y * n * m;
+#pragma unroll
+  for (int a = 0; a < 4; ++a)
+#pragma unroll
+    for (int v = 0; v < 16; ++v) {
+      const int i = 8 * (v / 4) + 4 * h + (v % 4);
+      const int row = o0 + 4 * i + a;
       if (row < n) {
 #pragma unroll
         for (int b = 0; b < 2; ++b) {
@@ -244,6 +374,20 @@ __global__ __launch_bounds__(256) void transpose_kernel(const float* __restrict_
 }
 
 // ------------------------------------------------------------------ host side
+// Grid slices of the contraction range.  The wide kernel keeps one workgroup per compute unit
+// busy (one wave per SIMD), the 64 x 64 kernel two.
+static int batched_splits_wide(int n) {
+  int cus = device_cu_count();
+  if (cus < 1) cus = 256;
+  const int tiles = (n + kBtWideTile - 1) / kBtWideTile;
+  int s = (cus + tiles - 1) / tiles;  // one workgroup (four waves, one per SIMD) per compute unit
+  const int nchunks = (n + kBtChunk - 1) / kBtChunk;
+  const int max_s = nchunks / 4 > 0 ? nchunks / 4 : 1;
+  if (s > max_s) s = max_s;
+  if (s > 32) s = 32;
+  return s < 1 ? 1 : s;
+}
+
 static int batched_splits(int n) {
   int cus = device_cu_count();
   if (cus < 1) cus = 256;
@@ -258,7 +402,8 @@ static int batched_splits(int n) {
 
 static size_t batched_partial_bytes(int n, int m) {
   const int mg = m < kBtCols ? m : kBtCols;
-  return align_up((size_t)batched_splits(n) * (size_t)n * (size_t)mg * 4, 256);
+  const int sw = batched_splits_wide(n), sn = batched_splits(n);
+  return align_up((size_t)(sw > sn ? sw : sn) * (size_t)n * (size_t)mg * 4, 256);
 }
 static int64_t batched_ldt(int n) { return (int64_t)align_up((size_t)n, 64); }
 
@@ -275,7 +420,7 @@ int run_sinkhorn_batched(const fsk_opts* o, const void* K, int64_t ldK, const vo
   const int n = o->n, m = o->m;
   const int S = batched_splits(n);
   const size_t part_bytes = batched_partial_bytes(n, m);
-  if (S > 1 && (!workspace || ws_bytes < part_bytes))
+  if ((S > 1 || batched_splits_wide(n) > 1) && (!workspace || ws_bytes < part_bytes))
     return set_error(FSK_EWORKSPACE, "batched call needs at least %zu workspace bytes (%zu to run at "
                      "full speed), got %zu", part_bytes, batched_workspace_bytes(n, m), ws_bytes);
   const float *Kf = (const float*)K, *Af = (const float*)A, *Bf = (const float*)B;
@@ -290,22 +435,28 @@ int run_sinkhorn_batched(const fsk_opts* o, const void* K, int64_t ldK, const vo
     FSK_LAUNCH_CHECK("transpose_kernel");
   }
   dim3 grid((n + kBtTile - 1) / kBtTile, S), block(256);
+  const int SW = batched_splits_wide(n);
+  dim3 gridw((n + kBtWideTile - 1) / kBtWideTile, SW);
   const int nm = n * m;
+  auto reduce = [&](int slices, const float* marg, float* dst) -> int {
+    return launch_colreduce(FSK_F32, part, nm, slices, 0, nm, marg, nullptr, dst, kEpiDivide, 1.0, st);
+  };
   for (int it = 0; it < o->max_iters; ++it) {
-    if (use_kt)  // Q = K V as the transposed product of K^T
-      hipLaunchKernelGGL((batched_prod_kernel<true>), grid, block, 0, st, (const float*)Kt, ldt, n, m,
+    if (use_kt) {  // Q = K V as the transposed product of K^T
+      hipLaunchKernelGGL(batched_prod_wide_kernel, gridw, block, 0, st, (const float*)Kt, ldt, n, m,
+                         (const float*)Vf, Af, SW == 1 ? Uf : part, SW == 1 ? 1 : 0);
+      FSK_LAUNCH_CHECK("batched_prod_wide_kernel (K V)");
+      if (SW > 1) FSK_TRY(reduce(SW, Af, Uf));
+    } else {
+      hipLaunchKernelGGL(batched_rowprod_kernel, grid, block, 0, st, Kf, ldK, n, m,
                          (const float*)Vf, Af, S == 1 ? Uf : part, S == 1 ? 1 : 0);
-    else
-      hipLaunchKernelGGL((batched_prod_kernel<false>), grid, block, 0, st, Kf, ldK, n, m,
-                         (const float*)Vf, Af, S == 1 ? Uf : part, S == 1 ? 1 : 0);
-    FSK_LAUNCH_CHECK("batched_prod_kernel (K V)");
-    if (S > 1)
-      FSK_TRY(launch_colreduce(FSK_F32, part, nm, S, 0, nm, Af, nullptr, Uf, kEpiDivide, 1.0, st));
-    hipLaunchKernelGGL((batched_prod_kernel<true>), grid, block, 0, st, Kf, ldK, n, m,
-                       (const float*)Uf, Bf, S == 1 ? Vf : part, S == 1 ? 1 : 0);
-    FSK_LAUNCH_CHECK("batched_prod_kernel (K^T U)");
-    if (S > 1)
-      FSK_TRY(launch_colreduce(FSK_F32, part, nm, S, 0, nm, Bf, nullptr, Vf, kEpiDivide, 1.0, st));
+      FSK_LAUNCH_CHECK("batched_rowprod_kernel (K V)");
+      if (S > 1) FSK_TRY(reduce(S, Af, Uf));
+    }
+    hipLaunchKernelGGL(batched_prod_wide_kernel, gridw, block, 0, st, Kf, ldK, n, m,
+                       (const float*)Uf, Bf, SW == 1 ? Vf : part, SW == 1 ? 1 : 0);
+    FSK_LAUNCH_CHECK("batched_prod_wide_kernel (K^T U)");
+    if (SW > 1) FSK_TRY(reduce(SW, Bf, Vf));
   }
   return FSK_OK;
 }
