@@ -155,36 +155,69 @@ int launch_colpartial(int dtype, const void* K, int64_t ld, int n, int rows, int
 }
 
 // ======================================================= partial sums -> result
-// 64 columns per workgroup; the partial rows are split into 4 contiguous groups
-// (one per wave), each summed in increasing index, then the 4 group sums are
-// added in group order.  The grouping depends only on the number of partials.
+// The partial rows are split into G contiguous groups (G = 4..32, a function of the number
+// of partials alone), each summed in increasing index, then the G group sums are added in
+// group order: the result does not depend on the column range, the alignment or the grid.
+// A workgroup is G x Q threads (Q = 256 / G); thread (g, q) sums group g for one 16-byte
+// pack of columns, so a group row is read as Q contiguous packs and every thread has its
+// whole group in flight at once.
+__host__ __device__ inline int colreduce_groups(int n_partials) {
+  return n_partials >= 128 ? 32 : n_partials >= 32 ? 16 : n_partials >= 16 ? 8 : 4;
+}
+
 template <typename T>
 __global__ __launch_bounds__(256) void colreduce_kernel(const T* __restrict__ partial,
                                                         int64_t ld_ws, int n_partials, int c0,
                                                         int c1, const T* marg, const T* old, T* out,
-                                                        int epi, T eta) {
-  const int lane = threadIdx.x & 63, grp = threadIdx.x >> 6;
-  const int j = c0 + blockIdx.x * 64 + lane;
-  const int per = (n_partials + 3) / 4;
-  const int s0 = grp * per;
+                                                        int epi, T eta, int aligned) {
+  constexpr int W = Pack<T>::W;
+  const int G = colreduce_groups(n_partials), Q = 256 / G;
+  const int q = threadIdx.x % Q, g = threadIdx.x / Q;
+  const int j = c0 + (blockIdx.x * Q + q) * W;  // first column of this thread's pack
+  const int per = (n_partials + G - 1) / G;
+  const int s0 = g * per;
   const int s1 = s0 + per < n_partials ? s0 + per : n_partials;
-  T acc = T(0);
+  const bool whole = aligned && j + W <= c1;  // the pack lies inside the range and is aligned
+  Pack<T> acc;
+#pragma unroll
+  for (int e = 0; e < W; ++e) acc.e[e] = T(0);
   if (j < c1) {
     const T* p = partial + (int64_t)s0 * ld_ws + j;
+    if (whole) {
+#pragma unroll 8
+      for (int s = s0; s < s1; ++s) {
+        const Pack<T> x = load_pack(p);
+#pragma unroll
+        for (int e = 0; e < W; ++e) acc.e[e] += x.e[e];
+        p += ld_ws;
+      }
+    } else {
 #pragma unroll 4
-    for (int s = s0; s < s1; ++s) {
-      acc += *p;
-      p += ld_ws;
+      for (int s = s0; s < s1; ++s) {
+#pragma unroll
+        for (int e = 0; e < W; ++e)
+          if (j + e < c1) acc.e[e] += p[e];
+        p += ld_ws;
+      }
     }
   }
-  __shared__ T sm[4][64];
-  sm[grp][lane] = acc;
+  __shared__ __align__(16) T sm[256 * W];
+  store_pack(sm + threadIdx.x * W, acc);
   __syncthreads();
-  if (grp == 0 && j < c1) {
-    const T r = ((sm[0][lane] + sm[1][lane]) + sm[2][lane]) + sm[3][lane];
-    const T mg = epi_needs_marg(epi) ? marg[j] : T(0);
-    const T od = epi_needs_old(epi) ? old[j] : T(0);
-    out[j] = apply_epilogue(epi, mg, r, od, eta);
+  if (g == 0 && j < c1) {
+    Pack<T> r = load_pack(sm + q * W);
+    for (int k = 1; k < G; ++k) {
+      const Pack<T> x = load_pack(sm + (k * Q + q) * W);
+#pragma unroll
+      for (int e = 0; e < W; ++e) r.e[e] += x.e[e];
+    }
+#pragma unroll
+    for (int e = 0; e < W; ++e)
+      if (j + e < c1) {
+        const T mg = epi_needs_marg(epi) ? marg[j + e] : T(0);
+        const T od = epi_needs_old(epi) ? old[j + e] : T(0);
+        out[j + e] = apply_epilogue(epi, mg, r.e[e], od, eta);
+      }
   }
 }
 
@@ -193,9 +226,12 @@ static int colreduce_typed(const void* partial, int64_t ld_ws, int n_partials, i
                            const void* marg, const void* old, void* out, int epi, double eta,
                            hipStream_t stream) {
   if (c1 <= c0) return FSK_OK;
-  dim3 grid((c1 - c0 + 63) / 64), block(256);
+  constexpr int W = Pack<T>::W;
+  const int cols_per_wg = 256 / colreduce_groups(n_partials) * W;
+  const int aligned = ld_ws % W == 0 && ((uintptr_t)((const T*)partial + c0)) % 16 == 0;
+  dim3 grid((c1 - c0 + cols_per_wg - 1) / cols_per_wg), block(256);
   hipLaunchKernelGGL((colreduce_kernel<T>), grid, block, 0, stream, (const T*)partial, ld_ws,
-                     n_partials, c0, c1, (const T*)marg, (const T*)old, (T*)out, epi, (T)eta);
+                     n_partials, c0, c1, (const T*)marg, (const T*)old, (T*)out, epi, (T)eta, aligned);
   FSK_LAUNCH_CHECK("colreduce_kernel");
   return FSK_OK;
 }
