@@ -259,6 +259,39 @@ def plan_objective(K, C, eps: float, u, v, l=None) -> np.ndarray:
     return out
 
 
+def gibbs_lambda(c, lam: float, l, eps: float, as_f32: bool = False) -> np.ndarray:
+    """K_ij = exp(-(lam c_ij - l_j)/eps), the kernel of the robust-risk example."""
+    c = _f64(c)
+    n = c.shape[0]
+    K = np.empty((n, n), dtype=np.float64)
+    lp = _P(None)
+    if l is not None:
+        l = _f64(l)
+        lp = _ptr(l)
+    _load().orc_gibbs_lambda(_ptr(c), ctypes.c_int64(n), _DBL(lam), lp, _DBL(eps), int(as_f32), _ptr(K))
+    return K
+
+
+def radius_search(c, l, a, b, eps: float, delta: float, lo: float, hi: float, max_steps: int,
+                  gtol: float, iters: int, as_f32: bool = False):
+    """Bisection on lambda until <P(lambda), c> = delta.  Returns (lambda, <P,c>, sum P_ij l_j,
+    solves, u, v, K) with u, v, K as of the last solve."""
+    c, a, b = _f64(c), _f64(a), _f64(b)
+    n = c.shape[0]
+    K = np.empty((n, n), dtype=np.float64)
+    u = np.empty(n, dtype=np.float64)
+    v = np.empty(n, dtype=np.float64)
+    out = np.zeros(4, dtype=np.float64)
+    lp = _P(None)
+    if l is not None:
+        l = _f64(l)
+        lp = _ptr(l)
+    _load().orc_radius_search(_ptr(c), lp, _ptr(a), _ptr(b), ctypes.c_int64(n), _DBL(eps), _DBL(delta),
+                              _DBL(lo), _DBL(hi), int(max_steps), _DBL(gtol), int(iters), int(as_f32),
+                              _ptr(K), _ptr(u), _ptr(v), _ptr(out))
+    return float(out[0]), float(out[1]), float(out[2]), int(out[3]), u, v, K
+
+
 def marginal_error(K, a, u, v) -> tuple[float, float]:
     """(||P1 - a||_1, ||P1 - a||_2) for P = diag(u) K diag(v)."""
     kp, kf, n, ld = _square(K)

@@ -227,6 +227,51 @@ void orc_plan_objective(const void* K, int k_is_f32, const double* C, int64_t n,
   out[0] = pc; out[1] = ent; out[2] = pc + eps * ent; out[3] = mass; out[4] = loss;
 }
 
+/* Kernel of the robust-risk example (Sec. "Illustrative application"): the combined cost is
+ * C_lambda,ij = lambda c_ij - l_j, so K_ij = exp(-(lambda c_ij - l_j)/eps).  l may be NULL (0).
+ * as_f32: round every entry to fp32 (the value an fp32 consumer holds). */
+void orc_gibbs_lambda(const double* c, int64_t n, double lambda, const double* l, double eps,
+                      int as_f32, double* K) {
+  for (int64_t i = 0; i < n; ++i)
+    for (int64_t j = 0; j < n; ++j) {
+      const double k = exp(-(lambda * c[i * n + j] - (l ? l[j] : 0.0)) / eps);
+      K[i * n + j] = as_f32 ? (double)(float)k : k;
+    }
+}
+
+/* Radius search (App. "Enforcing the Wasserstein radius", steps 1-3) by bisection on
+ * [lo, hi]: lambda = (lo + hi)/2; K from orc_gibbs_lambda; Algorithm 1 from u = v = 1 for
+ * `iters` iterations; g = <P, c> - delta; stop if |g| <= gtol, else lo = lambda when g > 0
+ * (the plan moves too far: raise the price of transport) and hi = lambda otherwise; at most
+ * max_steps solves.  K (n*n), u, v are left as of the last solve.
+ *   out[0] = lambda   out[1] = <P, c>   out[2] = sum_ij P_ij l_j   out[3] = solves done */
+void orc_radius_search(const double* c, const double* l, const double* a, const double* b,
+                       int64_t n, double eps, double delta, double lo, double hi, int max_steps,
+                       double gtol, int iters, int as_f32, double* K, double* u, double* v,
+                       double* out) {
+  double lambda = 0.5 * (lo + hi), cost = NAN, loss = NAN;
+  int steps = 0;
+  while (steps < max_steps) {
+    lambda = 0.5 * (lo + hi);
+    orc_gibbs_lambda(c, n, lambda, l, eps, as_f32, K);
+    for (int64_t i = 0; i < n; ++i) u[i] = v[i] = 1.0;
+    orc_sinkhorn_dense(K, 0, n, n, a, b, u, v, iters);
+    cost = 0.0;
+    loss = 0.0;
+    for (int64_t i = 0; i < n; ++i)
+      for (int64_t j = 0; j < n; ++j) {
+        const double p = u[i] * K[i * n + j] * v[j];
+        cost += p * c[i * n + j];
+        if (l) loss += p * l[j];
+      }
+    ++steps;
+    const double g = cost - delta;
+    if (fabs(g) <= gtol) break;
+    if (g > 0.0) lo = lambda; else hi = lambda;
+  }
+  out[0] = lambda; out[1] = cost; out[2] = loss; out[3] = (double)steps;
+}
+
 /* Tolerance mode: iterate; after every `check_every`-th iteration (and after
  * the last one) evaluate err = ||P1 - a||_1 with the scalings just produced;
  * stop at the first such check with err < tol.  Returns iterations done. */

@@ -522,3 +522,80 @@ def test_plan_objective_against_numpy_and_duality(orc):
     out = orc.plan_objective(K, C, eps, u, v)
     assert out[2] == pytest.approx(dual_objective(eps * np.log(u), eps * np.log(v), a, b, C, eps), abs=1e-12)
     assert out[4] == 0.0
+
+
+# ------------------------------- radius search of the robust-risk example ---
+
+def _two_by_two_root():
+    """n = 2: with both marginals fixed the plan has one free entry p.  A scaling of K has
+    P11 P22 / (P12 P21) = K11 K22 / (K12 K21) = exp(-lambda (c11 + c22 - c12 - c21)/eps) (the
+    column term l_j cancels), so the lambda that yields a chosen p is known in closed form."""
+    a = np.array([0.35, 0.65]); b = np.array([0.55, 0.45])
+    c = np.array([[0.1, 0.9], [0.7, 0.2]])
+    eps = 0.05
+    p = 0.30                                        # P11; then P12 = a1 - p, P21 = b1 - p, P22 = a2 - b1 + p
+    P = np.array([[p, a[0] - p], [b[0] - p, a[1] - b[0] + p]])
+    assert (P > 0).all()
+    ratio = P[0, 0] * P[1, 1] / (P[0, 1] * P[1, 0])
+    lam = -eps * np.log(ratio) / (c[0, 0] + c[1, 1] - c[0, 1] - c[1, 0])
+    return a, b, c, eps, P, lam, float((P * c).sum())
+
+
+def test_radius_search_two_by_two_closed_form(orc):
+    a, b, c, eps, P, lam_star, delta = _two_by_two_root()
+    l = np.array([0.02, -0.03])
+    lam, cost, loss, steps, u, v, K = orc.radius_search(c, l, a, b, eps, delta, 0.0, 1.0, 60, 0.0, 3000)
+    assert 0.0 < lam_star < 1.0 and 40 <= steps <= 60
+    assert lam == pytest.approx(lam_star, abs=1e-10)
+    assert np.allclose(u[:, None] * K * v[None, :], P, rtol=1e-8)
+    assert cost == pytest.approx(delta, rel=1e-9) and loss == pytest.approx(float(b @ l), rel=1e-12)
+    # a tolerance on g stops the search early, at a lambda whose cost is within it
+    lam2, cost2, _, steps2, _, _, _ = orc.radius_search(c, l, a, b, eps, delta, 0.0, 1.0, 60, 1e-4, 3000)
+    assert steps2 < 20 and abs(cost2 - delta) <= 1e-4
+
+
+def test_gibbs_lambda_and_the_role_of_l(orc):
+    """lambda = 0 leaves K_ij = exp(l_j/eps), whose scaling is the independent coupling a b^T,
+    so <P, c> = a^T c b.  For any lambda, l only rescales the columns of K: the converged plan is
+    the same as with l = 0, and sum_ij P_ij l_j = b^T l after any v-update."""
+    x, y, a, b, C, _ = problem(9, 77, eps=0.2)
+    eps = 0.2
+    rng = np.random.default_rng(5)
+    l = rng.uniform(-0.3, 0.3, 9)
+    assert np.allclose(orc.gibbs_lambda(C, 0.7, l, eps), np.exp(-(0.7 * C - l[None, :]) / eps), rtol=1e-14)
+    K32 = orc.gibbs_lambda(C, 0.7, l, eps, True)
+    assert np.array_equal(K32, K32.astype(np.float32).astype(np.float64))
+    lam, cost, loss, steps, u, v, K = orc.radius_search(C, l, a, b, eps, 0.0, 0.0, 0.0, 1, 0.0, 5)
+    assert lam == 0.0 and steps == 1
+    assert cost == pytest.approx(float(a @ C @ b), rel=1e-12)
+    assert np.allclose(u[:, None] * K * v[None, :], np.outer(a, b), rtol=1e-12)
+    r1 = orc.radius_search(C, l, a, b, eps, 0.0, 0.8, 0.8, 1, 0.0, 3000)
+    r0 = orc.radius_search(C, None, a, b, eps, 0.0, 0.8, 0.8, 1, 0.0, 3000)
+    P1 = r1[4][:, None] * r1[6] * r1[5][None, :]
+    P0 = r0[4][:, None] * r0[6] * r0[5][None, :]
+    assert np.allclose(P1, P0, rtol=1e-10)
+    assert r1[1] == pytest.approx(r0[1], rel=1e-10)
+    assert r1[2] == pytest.approx(float(b @ l), rel=1e-12) and r0[2] == 0.0
+
+
+def test_radius_search_against_scipy_root_of_the_log_domain_cost(orc):
+    """The transport cost of the optimal plan falls as lambda grows; the root that SciPy finds
+    for g(lambda) evaluated through the log-domain iteration on C_lambda (NumPy builds the cost)
+    is the one the bisection returns."""
+    x, y, a, b, C, _ = problem(12, 91, eps=0.1)
+    eps = 0.1
+    l = np.random.default_rng(6).uniform(-0.2, 0.2, 12)
+
+    def cost_at(lam):
+        Cl = lam * C - l[None, :]
+        f, g = orc.sinkhorn_log_cost(Cl, eps, a, b, 400)[:2]
+        P = np.exp((f[:, None] + g[None, :] - Cl) / eps)
+        return float((P * C).sum())
+
+    costs = [cost_at(t) for t in (0.0, 0.5, 1.0, 2.0, 4.0)]
+    assert all(c1 > c2 for c1, c2 in zip(costs, costs[1:]))
+    assert costs[0] == pytest.approx(float(a @ C @ b), rel=1e-10)
+    delta = 0.5 * (costs[1] + costs[3])
+    root = scipy.optimize.brentq(lambda t: cost_at(t) - delta, 0.0, 4.0, xtol=1e-12)
+    lam, cost, loss, steps, u, v, K = orc.radius_search(C, l, a, b, eps, delta, 0.0, 4.0, 45, 0.0, 400)
+    assert lam == pytest.approx(root, abs=1e-9) and cost == pytest.approx(delta, rel=1e-9)
