@@ -99,7 +99,7 @@ typedef struct {
 } fsk_opts;
 
 typedef enum { FSK_MODE_DENSE = 0, FSK_MODE_LOG = 1, FSK_MODE_BATCHED = 2, FSK_MODE_SETUP = 3,
-               FSK_MODE_PLAN = 4 } fsk_mode;
+               FSK_MODE_PLAN = 4, FSK_MODE_RADIUS = 5 } fsk_mode;
 
 /* Library version as major*10000 + minor*100 + patch. */
 int fsk_version(void);
@@ -152,6 +152,32 @@ int fsk_marginals(const fsk_opts* opts, const void* K, int64_t ldK, const void* 
 int fsk_plan_objective(const fsk_opts* opts, const void* K, int64_t ldK, const void* C, int64_t ldC,
                        double eps, const void* u, const void* v, const void* l, double* out,
                        void* workspace, size_t ws_bytes, void* stream);
+
+/* ---- radius search of the robust-risk example (Sec. "Illustrative application"; appendix
+ * "Enforcing the Wasserstein radius", steps 1-3) ------------------------------------------
+ * The combined cost is C_lambda,ij = lambda c_ij - l_j with c the ground cost (device, n x n,
+ * leading dimension ldc) and l_j the loss at target point j (device n-vector, or NULL for 0).
+ *
+ * fsk_kernel_from_cost_lambda: K_ij = exp(-(lambda c_ij - l_j)/eps), fp64 arithmetic with one
+ * rounding to the storage type.  K must not alias c if c is needed again.  Enqueue only. */
+int fsk_kernel_from_cost_lambda(const fsk_opts* opts, const void* c, int64_t ldc, double lambda,
+                                const void* l, double eps, void* K, int64_t ldK, void* stream);
+
+/* fsk_radius_search: bisection on [lambda_lo, lambda_hi] for <P(lambda), c> = delta.  Each
+ * step: lambda = (lo + hi)/2; K as above; u = v = 1; the dense solve that fsk_sinkhorn_dense
+ * would run with these opts (flow, c, max_iters, tol, check_every, damping); g = <P, c> - delta
+ * from the plan-sum kernel; stop if |g| <= gtol, else lo = lambda if g > 0 (transport too
+ * large: raise its price) and hi = lambda otherwise.  At most max_steps (>= 1) solves; the
+ * call synchronises once per step.
+ * K (device, n x n, not aliasing c), u, v (device): OUT, as of the last solve.
+ * out (host, 4 doubles): lambda, <P, c>, sum_ij P_ij l_j (the worst-case expected loss), solves.
+ * Workspace: fsk_workspace_bytes(opts, FSK_MODE_RADIUS, 0).
+ * Errors: FSK_EINVAL (sizes, eps, bracket, aliasing), FSK_EALIGN, FSK_EWORKSPACE,
+ * FSK_ENONFINITE (a solve produced a non-finite cost: K under- or overflowed for this lambda). */
+int fsk_radius_search(const fsk_opts* opts, const void* c, int64_t ldc, const void* l, const void* a,
+                      const void* b, double eps, double delta, double lambda_lo, double lambda_hi,
+                      int32_t max_steps, double gtol, void* K, int64_t ldK, void* u, void* v,
+                      void* workspace, size_t ws_bytes, double* out, void* stream);
 
 /* ---- bounded-delay emulation of the asynchronous schedule (Algorithm 3; assumption A3 of the
  * convergence section) on one device, with a deterministic delay.  Client j owns rows/columns

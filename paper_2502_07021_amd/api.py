@@ -24,13 +24,15 @@ FSK_F32, FSK_F64 = 0, 1
 FSK_FLOW_FUSED, FSK_FLOW_TWO_PASS, FSK_FLOW_PAPER = 0, 1, 2
 FSK_DAMP_NONE, FSK_DAMP_ARITHMETIC, FSK_DAMP_GEOMETRIC = 0, 1, 2
 FSK_MODE_DENSE, FSK_MODE_LOG, FSK_MODE_BATCHED, FSK_MODE_SETUP, FSK_MODE_PLAN = 0, 1, 2, 3, 4
+FSK_MODE_RADIUS = 5
 
 EXPORTS = (
     "fsk_version", "fsk_last_error", "fsk_workspace_bytes", "fsk_kernel_from_cost",
     "fsk_kernel_from_points", "fsk_sinkhorn_dense", "fsk_marginals", "fsk_block_rowpass",
     "fsk_block_colpartial", "fsk_block_fused", "fsk_sinkhorn_log_points", "fsk_sinkhorn_batched",
     "fsk_dense_profile", "fsk_bench_copy", "fsk_bench_read", "fsk_async_workspace_bytes",
-    "fsk_sinkhorn_async_emulated", "fsk_plan_objective",
+    "fsk_sinkhorn_async_emulated", "fsk_plan_objective", "fsk_kernel_from_cost_lambda",
+    "fsk_radius_search",
 )
 
 
@@ -176,6 +178,25 @@ def fsk_plan_objective(opts, K, C, eps, u, v, l, workspace, stream=None):
                                     ctypes.c_double(eps), _vec(u), _vec(v), _vec(l), out, wp, wn,
                                     _stream(stream)))
     return [float(x) for x in out]
+
+
+def fsk_kernel_from_cost_lambda(opts, c, lam, l, eps, K, stream=None) -> int:
+    return _check(lib().fsk_kernel_from_cost_lambda(
+        ctypes.byref(opts), _p(c), _ld(c), ctypes.c_double(lam), _vec(l), ctypes.c_double(eps),
+        _p(K), _ld(K), _stream(stream)))
+
+
+def fsk_radius_search(opts, c, l, a, b, eps, delta, lambda_lo, lambda_hi, max_steps, gtol, K, u, v,
+                      workspace, stream=None):
+    """Returns (lambda, <P,c>, sum_ij P_ij l_j, solves); K, u, v hold the last solve (synchronises)."""
+    wp, wn = _ws(workspace)
+    out = (ctypes.c_double * 4)()
+    _check(lib().fsk_radius_search(
+        ctypes.byref(opts), _p(c), _ld(c), _vec(l), _vec(a), _vec(b), ctypes.c_double(eps),
+        ctypes.c_double(delta), ctypes.c_double(lambda_lo), ctypes.c_double(lambda_hi),
+        ctypes.c_int32(max_steps), ctypes.c_double(gtol), _p(K), _ld(K), _vec(u), _vec(v), wp, wn, out,
+        _stream(stream)))
+    return float(out[0]), float(out[1]), float(out[2]), int(out[3])
 
 
 def fsk_async_workspace_bytes(opts, tau: int, sync_every: int) -> int:

@@ -115,12 +115,15 @@ int fsk_version(void) { return 100; }
 
 const char* fsk_last_error(void) { return g_err; }
 
+static size_t plan_ws_bytes(const fsk_opts* opts);
+
 size_t fsk_workspace_bytes(const fsk_opts* opts, int mode, int d) {
   if (check_common(opts) != FSK_OK) return 0;
   switch (mode) {
     case FSK_MODE_DENSE: return dense_ws(opts).total;
     case FSK_MODE_LOG: return log_workspace_bytes(opts->n, d);
-    case FSK_MODE_PLAN: return 4 * align_up((size_t)opts->n * elem_size(opts->dtype), 256) + 256;
+    case FSK_MODE_PLAN: return plan_ws_bytes(opts);
+    case FSK_MODE_RADIUS: return align_up(dense_ws(opts).total, 256) + plan_ws_bytes(opts);
     case FSK_MODE_BATCHED: return batched_workspace_bytes(opts->n, opts->m);
     case FSK_MODE_SETUP: return align_up(max_sqdist_scratch_doubles(opts->n) * 8, 256) + 256;
     default: return 0;
@@ -233,6 +236,32 @@ static int dense_error(const fsk_opts* o, const DenseWs& w, const void* K, int64
   return FSK_OK;
 }
 
+// Algorithm 1 on validated arguments: opts->max_iters iterations, or until a poll finds the
+// marginal error below opts->tol.
+static int dense_solve(const fsk_opts* opts, const DenseWs& w, const void* K, int64_t ldK,
+                       const void* a, const void* b, void* u, void* v, char* workspace,
+                       int32_t* iters_done, double* err, hipStream_t st) {
+  int done = 0;
+  double e = NAN;
+  for (int it = 0; it < opts->max_iters; ++it) {
+    FSK_TRY(dense_iteration(opts, w, (const char*)K, ldK, (const char*)a, (const char*)b, (char*)u,
+                            (char*)v, workspace, st));
+    done = it + 1;
+    if (opts->tol > 0.0 && (done % opts->check_every == 0 || done == opts->max_iters)) {
+      FSK_TRY(dense_error(opts, w, K, ldK, a, u, v, workspace, &e, st));
+      if (!std::isfinite(e)) {
+        if (iters_done) *iters_done = done;
+        if (err) *err = e;
+        return set_error(FSK_ENONFINITE, "marginal error is not finite after %d iterations", done);
+      }
+      if (e < opts->tol) break;
+    }
+  }
+  if (iters_done) *iters_done = done;
+  if (err) *err = e;
+  return FSK_OK;
+}
+
 int fsk_sinkhorn_dense(const fsk_opts* opts, const void* K, int64_t ldK, const void* a,
                        const void* b, void* u, void* v, void* workspace, size_t ws_bytes,
                        int32_t* iters_done, double* err, void* stream) {
@@ -248,26 +277,8 @@ int fsk_sinkhorn_dense(const fsk_opts* opts, const void* K, int64_t ldK, const v
   if (!workspace || ws_bytes < w.total)
     return set_error(FSK_EWORKSPACE, "dense call needs %zu workspace bytes, got %zu", w.total, ws_bytes);
   if (!aligned16(workspace)) return set_error(FSK_EALIGN, "workspace is not 16-byte aligned");
-  hipStream_t st = (hipStream_t)stream;
-  int done = 0;
-  double e = NAN;
-  for (int it = 0; it < opts->max_iters; ++it) {
-    FSK_TRY(dense_iteration(opts, w, (const char*)K, ldK, (const char*)a, (const char*)b, (char*)u,
-                            (char*)v, (char*)workspace, st));
-    done = it + 1;
-    if (opts->tol > 0.0 && (done % opts->check_every == 0 || done == opts->max_iters)) {
-      FSK_TRY(dense_error(opts, w, K, ldK, a, u, v, (char*)workspace, &e, st));
-      if (!std::isfinite(e)) {
-        if (iters_done) *iters_done = done;
-        if (err) *err = e;
-        return set_error(FSK_ENONFINITE, "marginal error is not finite after %d iterations", done);
-      }
-      if (e < opts->tol) break;
-    }
-  }
-  if (iters_done) *iters_done = done;
-  if (err) *err = e;
-  return FSK_OK;
+  return dense_solve(opts, w, K, ldK, a, b, u, v, (char*)workspace, iters_done, err,
+                     (hipStream_t)stream);
 }
 
 int fsk_dense_profile(const fsk_opts* opts, const void* K, int64_t ldK, const void* a,
@@ -342,6 +353,32 @@ int fsk_marginals(const fsk_opts* opts, const void* K, int64_t ldK, const void* 
 }
 
 // ------------------------------------------------------------- plan objective
+static size_t plan_ws_bytes(const fsk_opts* opts) {
+  return 4 * align_up((size_t)opts->n * elem_size(opts->dtype), 256) + 256;
+}
+
+// The five plan sums on validated arguments (synchronises).
+static int plan_sums(const fsk_opts* opts, const void* K, int64_t ldK, const void* C, int64_t ldC,
+                     double eps, const void* u, const void* v, const void* l, double* out, char* ws,
+                     hipStream_t st) {
+  const int n = opts->n, dt = opts->dtype;
+  const size_t vec = align_up((size_t)n * elem_size(dt), 256);
+  const int64_t stride = (int64_t)(vec / elem_size(dt));
+  double* sums = (double*)(ws + 4 * vec);
+  FSK_TRY(launch_plan_rows(dt, K, ldK, C, ldC, n, u, v, l, ws, stride, st));
+  for (int q = 0; q < 4; ++q)
+    FSK_TRY(launch_sum_to_double(dt, ws + (size_t)q * vec, n, sums + q, st));
+  double h[4];
+  FSK_HIP(hipMemcpyAsync(h, sums, sizeof(h), hipMemcpyDeviceToHost, st));
+  FSK_HIP(hipStreamSynchronize(st));
+  out[0] = h[1];
+  out[1] = h[2] - h[0];
+  out[2] = out[0] + eps * out[1];
+  out[3] = h[0];
+  out[4] = l ? h[3] : 0.0;
+  return FSK_OK;
+}
+
 int fsk_plan_objective(const fsk_opts* opts, const void* K, int64_t ldK, const void* C, int64_t ldC,
                        double eps, const void* u, const void* v, const void* l, double* out,
                        void* workspace, size_t ws_bytes, void* stream) {
@@ -358,23 +395,72 @@ int fsk_plan_objective(const fsk_opts* opts, const void* K, int64_t ldK, const v
   if (!workspace || ws_bytes < need)
     return set_error(FSK_EWORKSPACE, "plan objective needs %zu workspace bytes, got %zu", need, ws_bytes);
   if (!aligned16(workspace)) return set_error(FSK_EALIGN, "workspace is not 16-byte aligned");
+  return plan_sums(opts, K, ldK, C, ldC, eps, u, v, l, out, (char*)workspace, (hipStream_t)stream);
+}
+
+// ------------------------------------------------------------- radius search
+int fsk_kernel_from_cost_lambda(const fsk_opts* opts, const void* c, int64_t ldc, double lambda,
+                                const void* l, double eps, void* K, int64_t ldK, void* stream) {
+  clear_error();
+  FSK_TRY(check_common(opts));
+  if (!(eps > 0.0)) return set_error(FSK_EINVAL, "eps = %g must be positive", eps);
+  if (!std::isfinite(lambda)) return set_error(FSK_EINVAL, "lambda is not finite");
+  if (!c || !K) return set_error(FSK_EINVAL, "c or K is NULL");
+  if (ldc < opts->n || ldK < opts->n) return set_error(FSK_EINVAL, "leading dimension below n");
+  return launch_gibbs_lambda(opts->dtype, c, ldc, opts->n, lambda, l, eps, K, ldK, (hipStream_t)stream);
+}
+
+int fsk_radius_search(const fsk_opts* opts, const void* c, int64_t ldc, const void* l, const void* a,
+                      const void* b, double eps, double delta, double lambda_lo, double lambda_hi,
+                      int32_t max_steps, double gtol, void* K, int64_t ldK, void* u, void* v,
+                      void* workspace, size_t ws_bytes, double* out, void* stream) {
+  clear_error();
+  FSK_TRY(check_common(opts));
+  if (opts->m != 1) return set_error(FSK_EINVAL, "radius search takes m = 1");
+  if (!out) return set_error(FSK_EINVAL, "out is NULL");
+  if (!(eps > 0.0)) return set_error(FSK_EINVAL, "eps = %g must be positive", eps);
+  if (!std::isfinite(delta) || !std::isfinite(lambda_lo) || !std::isfinite(lambda_hi) ||
+      lambda_lo > lambda_hi)
+    return set_error(FSK_EINVAL, "need finite delta and lambda_lo <= lambda_hi");
+  if (max_steps < 1) return set_error(FSK_EINVAL, "max_steps = %d must be >= 1", max_steps);
+  if (!(gtol >= 0.0)) return set_error(FSK_EINVAL, "gtol = %g must be >= 0", gtol);
+  FSK_TRY(check_matrix("c", c, ldc, opts->n, opts->dtype));
+  FSK_TRY(check_matrix("K", K, ldK, opts->n, opts->dtype));
+  if (K == c) return set_error(FSK_EINVAL, "K must not alias c: every step rebuilds K from c");
+  FSK_TRY(check_vec("a", a, false));
+  FSK_TRY(check_vec("b", b, false));
+  FSK_TRY(check_vec("u", u, true));
+  FSK_TRY(check_vec("v", v, true));
+  if (l && !aligned16(l)) return set_error(FSK_EALIGN, "l is not 16-byte aligned");
+  const size_t need = fsk_workspace_bytes(opts, FSK_MODE_RADIUS, 0);
+  if (!workspace || ws_bytes < need)
+    return set_error(FSK_EWORKSPACE, "radius search needs %zu workspace bytes, got %zu", need, ws_bytes);
+  if (!aligned16(workspace)) return set_error(FSK_EALIGN, "workspace is not 16-byte aligned");
   hipStream_t st = (hipStream_t)stream;
+  const DenseWs w = dense_ws(opts);
+  char* ws_dense = (char*)workspace;
+  char* ws_plan = ws_dense + align_up(w.total, 256);
   const int n = opts->n, dt = opts->dtype;
-  const size_t vec = align_up((size_t)n * elem_size(dt), 256);
-  const int64_t stride = (int64_t)(vec / elem_size(dt));
-  char* ws = (char*)workspace;
-  double* sums = (double*)(ws + 4 * vec);
-  FSK_TRY(launch_plan_rows(dt, K, ldK, C, ldC, n, u, v, l, ws, stride, st));
-  for (int q = 0; q < 4; ++q)
-    FSK_TRY(launch_sum_to_double(dt, ws + (size_t)q * vec, n, sums + q, st));
-  double h[4];
-  FSK_HIP(hipMemcpyAsync(h, sums, sizeof(h), hipMemcpyDeviceToHost, st));
-  FSK_HIP(hipStreamSynchronize(st));
-  out[0] = h[1];
-  out[1] = h[2] - h[0];
-  out[2] = out[0] + eps * out[1];
-  out[3] = h[0];
-  out[4] = l ? h[3] : 0.0;
+  double lo = lambda_lo, hi = lambda_hi, lambda = 0.5 * (lo + hi), sums[5] = {NAN, NAN, NAN, NAN, NAN};
+  int steps = 0;
+  while (steps < max_steps) {
+    lambda = 0.5 * (lo + hi);
+    FSK_TRY(launch_gibbs_lambda(dt, c, ldc, n, lambda, l, eps, K, ldK, st));
+    FSK_TRY(launch_fill(dt, u, n, 1.0, st));
+    FSK_TRY(launch_fill(dt, v, n, 1.0, st));
+    FSK_TRY(dense_solve(opts, w, K, ldK, a, b, u, v, ws_dense, nullptr, nullptr, st));
+    FSK_TRY(plan_sums(opts, K, ldK, c, ldc, eps, u, v, l, sums, ws_plan, st));
+    ++steps;
+    if (!std::isfinite(sums[0]))
+      return set_error(FSK_ENONFINITE, "transport cost is not finite at lambda = %g", lambda);
+    const double g = sums[0] - delta;
+    if (std::fabs(g) <= gtol) break;
+    if (g > 0.0) lo = lambda; else hi = lambda;
+  }
+  out[0] = lambda;
+  out[1] = sums[0];
+  out[2] = sums[4];
+  out[3] = (double)steps;
   return FSK_OK;
 }
 

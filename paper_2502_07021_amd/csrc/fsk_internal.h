@@ -101,6 +101,9 @@ int launch_sum_to_double(int dtype, const void* x, int n, double* out, hipStream
 // ------------------------------------------------------------------ setup kernels
 int launch_gibbs_from_cost(int dtype, const void* C, int64_t ldC, int n, double eps, void* K,
                            int64_t ldK, hipStream_t stream);
+int launch_gibbs_lambda(int dtype, const void* c, int64_t ldc, int n, double lambda, const void* l,
+                        double eps, void* K, int64_t ldK, hipStream_t stream);
+int launch_fill(int dtype, void* x, int n, double value, hipStream_t stream);
 // cmax_dev (one double, device) = max_ij ||x_i - y_j||^2; scratch holds one double per workgroup.
 int launch_max_sqdist(int dtype, const void* x, const void* y, int n, int d, double* scratch,
                       size_t scratch_doubles, double* cmax_dev, hipStream_t stream);

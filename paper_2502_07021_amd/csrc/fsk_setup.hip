@@ -32,6 +32,49 @@ int launch_gibbs_from_cost(int dtype, const void* C, int64_t ldC, int n, double 
   return FSK_OK;
 }
 
+// K_ij = exp(-(lambda c_ij - l_j)/eps): the kernel of the combined cost of the robust-risk
+// example (paper: Sec. "Illustrative application").  l may be null (taken as zero).
+template <typename T>
+__global__ __launch_bounds__(256) void gibbs_lambda_kernel(const T* c, int64_t ldc, int n,
+                                                           double lambda, const T* l, double eps,
+                                                           T* K, int64_t ldK) {
+  const int j = blockIdx.x * 256 + threadIdx.x;
+  const int i = blockIdx.y;
+  if (j < n) {
+    const double lj = l ? (double)l[j] : 0.0;
+    K[(int64_t)i * ldK + j] = (T)exp(-(lambda * (double)c[(int64_t)i * ldc + j] - lj) / eps);
+  }
+}
+
+int launch_gibbs_lambda(int dtype, const void* c, int64_t ldc, int n, double lambda, const void* l,
+                        double eps, void* K, int64_t ldK, hipStream_t stream) {
+  dim3 grid((n + 255) / 256, n), block(256);
+  if (dtype == FSK_F64)
+    hipLaunchKernelGGL((gibbs_lambda_kernel<double>), grid, block, 0, stream, (const double*)c, ldc,
+                       n, lambda, (const double*)l, eps, (double*)K, ldK);
+  else
+    hipLaunchKernelGGL((gibbs_lambda_kernel<float>), grid, block, 0, stream, (const float*)c, ldc, n,
+                       lambda, (const float*)l, eps, (float*)K, ldK);
+  FSK_LAUNCH_CHECK("gibbs_lambda_kernel");
+  return FSK_OK;
+}
+
+template <typename T>
+__global__ __launch_bounds__(256) void fill_kernel(T* x, int n, T value) {
+  const int i = blockIdx.x * 256 + threadIdx.x;
+  if (i < n) x[i] = value;
+}
+
+int launch_fill(int dtype, void* x, int n, double value, hipStream_t stream) {
+  dim3 grid((n + 255) / 256), block(256);
+  if (dtype == FSK_F64)
+    hipLaunchKernelGGL((fill_kernel<double>), grid, block, 0, stream, (double*)x, n, value);
+  else
+    hipLaunchKernelGGL((fill_kernel<float>), grid, block, 0, stream, (float*)x, n, (float)value);
+  FSK_LAUNCH_CHECK("fill_kernel");
+  return FSK_OK;
+}
+
 // Tile of 16 rows x 256 columns per workgroup; thread t owns column j and keeps
 // y_j in registers/cache while it walks the 16 rows (x_i entries are uniform
 // loads).  MODE 0: running maximum of the cost; MODE 1: write K.
