@@ -43,7 +43,7 @@ def _load():
         L.orc_lse.restype = ctypes.c_double
         for name in ("orc_num_threads", "orc_sinkhorn_dense", "orc_sinkhorn_dense_tol",
                      "orc_sinkhorn_blocked", "orc_sinkhorn_dense_damped", "orc_sinkhorn_batched",
-                     "orc_sinkhorn_async_emulated",
+                     "orc_sinkhorn_async_emulated", "orc_sinkhorn_grid",
                      "orc_sinkhorn_log_points", "orc_sinkhorn_log_cost"):
             getattr(L, name).restype = ctypes.c_int
         _lib = L
@@ -188,6 +188,20 @@ def sinkhorn_blocked(K, a, b, iters: int, c: int, flow: int, u0=None, v0=None):
                                       _INT(iters), _INT(c), _INT(flow))
     if rc == -2:
         raise ValueError("c must divide n")
+    assert rc == 0
+    return u, v
+
+
+def sinkhorn_grid(K, a, b, iters: int, p_r: int, p_c: int, u0=None, v0=None):
+    """Iteration on a p_r x p_c block grid: block products reduced along block rows (for K v)
+    and block columns (for K^T u) in block order."""
+    kp, kf, n, ld = _square(K)
+    a, b = _f64(a), _f64(b)
+    u, v = _init(K.shape[0], u0), _init(K.shape[0], v0)
+    rc = _load().orc_sinkhorn_grid(kp, kf, n, ld, _ptr(a), _ptr(b), _ptr(u), _ptr(v), _INT(iters),
+                                   _INT(p_r), _INT(p_c))
+    if rc == -2:
+        raise ValueError("p_r and p_c must divide n")
     assert rc == 0
     return u, v
 

@@ -336,6 +336,44 @@ int orc_sinkhorn_blocked(const void* K, int k_is_f32, int64_t n, int64_t ld, con
   return 0;
 }
 
+/* 2D block distribution over a p_r x p_c grid (App. "HPC baseline: 2D block distribution"):
+ * rank (i, j) holds K_ij (rows R_i = [i n/p_r, (i+1) n/p_r), columns J_j likewise with p_c)
+ * and forms the block products K_ij v_j and K_ij^T u_i; the row-wise reduction adds the
+ * p_c block products of a block row in the order j = 0, 1, ..., the column-wise one the p_r
+ * block products of a block column in the order i = 0, 1, ....
+ * Returns -2 if p_r or p_c does not divide n. */
+int orc_sinkhorn_grid(const void* K, int k_is_f32, int64_t n, int64_t ld, const double* a,
+                      const double* b, double* u, double* v, int iters, int p_r, int p_c) {
+  if (p_r < 1 || p_c < 1 || n % p_r != 0 || n % p_c != 0) return -2;
+  const int64_t nr = n / p_r, nc = n / p_c;
+  double* q = (double*)malloc(sizeof(double) * (size_t)n);
+  if (!q) return -1;
+  for (int t = 0; t < iters; ++t) {
+    for (int64_t i = 0; i < n; ++i) { /* q_i = sum_j (K_ij v_j), then u = a ./ q */
+      double sum = 0.0;
+      for (int j = 0; j < p_c; ++j) {
+        double block = 0.0;
+        for (int64_t col = j * nc; col < (j + 1) * nc; ++col) block += k_at(K, k_is_f32, ld, i, col) * v[col];
+        sum += block;
+      }
+      q[i] = sum;
+    }
+    for (int64_t i = 0; i < n; ++i) u[i] = a[i] / q[i];
+    for (int64_t col = 0; col < n; ++col) { /* r_j = sum_i (K_ij^T u_i), then v = b ./ r */
+      double sum = 0.0;
+      for (int i = 0; i < p_r; ++i) {
+        double block = 0.0;
+        for (int64_t row = i * nr; row < (i + 1) * nr; ++row) block += k_at(K, k_is_f32, ld, row, col) * u[row];
+        sum += block;
+      }
+      q[col] = sum;
+    }
+    for (int64_t col = 0; col < n; ++col) v[col] = b[col] / q[col];
+  }
+  free(q);
+  return 0;
+}
+
 /* ------------------------------------------------------------ damped forms */
 
 /* Relaxed updates of Sec. 3.3 in the centralised view.

@@ -599,3 +599,35 @@ def test_radius_search_against_scipy_root_of_the_log_domain_cost(orc):
     root = scipy.optimize.brentq(lambda t: cost_at(t) - delta, 0.0, 4.0, xtol=1e-12)
     lam, cost, loss, steps, u, v, K = orc.radius_search(C, l, a, b, eps, delta, 0.0, 4.0, 45, 0.0, 400)
     assert lam == pytest.approx(root, abs=1e-9) and cost == pytest.approx(delta, rel=1e-9)
+
+
+# ---------------------------------------- 2D block grid (HPC baseline appendix) ---
+
+def test_grid_iteration_is_the_centralised_one(orc):
+    """Block products reduced along block rows / block columns only regroup the sums: every grid
+    gives the centralised iterates to rounding; with one block column the grouping is exactly
+    that of the row-slab flow; the first iteration matches NumPy block matmuls."""
+    x, y, a, b, C, K = problem(48, 48, eps=0.2)
+    uc, vc = orc.sinkhorn_dense(K, a, b, 30)
+    for p_r, p_c in ((1, 1), (2, 3), (4, 4), (6, 2), (48, 1), (1, 48), (8, 16)):
+        u, v = orc.sinkhorn_grid(K, a, b, 30, p_r, p_c)
+        assert np.allclose(u, uc, rtol=1e-13) and np.allclose(v, vc, rtol=1e-13)
+    u1, v1 = orc.sinkhorn_grid(K, a, b, 30, 1, 1)
+    assert np.array_equal(u1, uc) and np.array_equal(v1, vc)
+    for c in (2, 4, 8):
+        ub, vb = orc.sinkhorn_blocked(K, a, b, 30, c, 1)
+        ug, vg = orc.sinkhorn_grid(K, a, b, 30, c, 1)
+        assert np.array_equal(ub, ug) and np.array_equal(vb, vg)
+    p_r, p_c = 4, 3
+    rows = np.split(np.arange(48), p_r); cols = np.split(np.arange(48), p_c)
+    v0 = np.ones(48)
+    q = np.concatenate([sum(K[np.ix_(R, J)] @ v0[J] for J in cols) for R in rows])
+    u_np = a / q
+    r = np.concatenate([sum(K[np.ix_(R, J)].T @ u_np[R] for R in rows) for J in cols])
+    v_np = b / r
+    u, v = orc.sinkhorn_grid(K, a, b, 1, p_r, p_c)
+    assert np.allclose(u, u_np, rtol=1e-14) and np.allclose(v, v_np, rtol=1e-14)
+    with pytest.raises(ValueError):
+        orc.sinkhorn_grid(K, a, b, 1, 5, 2)
+    with pytest.raises(ValueError):
+        orc.sinkhorn_grid(K, a, b, 1, 2, 7)
