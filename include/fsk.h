@@ -194,6 +194,23 @@ int fsk_sinkhorn_async_emulated(const fsk_opts* opts, const void* K, int64_t ldK
                                 const void* b, void* u, void* v, int32_t tau, int32_t sync_every,
                                 void* workspace, size_t ws_bytes, void* stream);
 
+/* ---- 2D block distribution on one device (appendix "HPC baseline: 2D block distribution
+ * with row/column Allreduce") --------------------------------------------------------------
+ * K is cut into a p_r x p_c grid of blocks K_ij (block rows of n/p_r rows, block columns of
+ * n/p_c columns).  An iteration forms the block products K_ij v_j, adds them along each block
+ * row in the order j = 0, 1, ... (the row-wise reduction), u = a ./ q; then the block products
+ * K_ij^T u_i, added along each block column in the order i = 0, 1, ... (the column-wise
+ * reduction), v = b ./ r.  Same iterates as Algorithm 1 up to the grouping of the sums.
+ * Runs exactly opts->max_iters iterations, undamped; u, v IN/OUT as in fsk_sinkhorn_dense;
+ * opts->c and opts->flow are not used.  Enqueue only.
+ * Errors: FSK_EDIV if p_r or p_c does not divide n; FSK_EALIGN if a block column does not start
+ * on a 16-byte boundary (n/p_c must be a multiple of 4 entries in fp32, 2 in fp64);
+ * FSK_EUNSUPPORTED for tolerance mode or damping.  Workspace: fsk_grid_workspace_bytes(). */
+size_t fsk_grid_workspace_bytes(const fsk_opts* opts, int32_t p_r, int32_t p_c);
+int fsk_sinkhorn_grid(const fsk_opts* opts, const void* K, int64_t ldK, const void* a, const void* b,
+                      void* u, void* v, int32_t p_r, int32_t p_c, void* workspace, size_t ws_bytes,
+                      void* stream);
+
 /* ---- one worker's share (Sec. 3.1: client j holds rows I_j of K and slices a_j, b_j) -----
  * K_slab: device, `rows` x n, the rows [row0, row0+rows) of K (row0 is only used to index the
  * full-length vectors).  These are the per-worker operations of Algorithm 1 and Sec. 4.1 at

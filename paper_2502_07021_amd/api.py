@@ -32,7 +32,7 @@ EXPORTS = (
     "fsk_block_colpartial", "fsk_block_fused", "fsk_sinkhorn_log_points", "fsk_sinkhorn_batched",
     "fsk_dense_profile", "fsk_bench_copy", "fsk_bench_read", "fsk_async_workspace_bytes",
     "fsk_sinkhorn_async_emulated", "fsk_plan_objective", "fsk_kernel_from_cost_lambda",
-    "fsk_radius_search",
+    "fsk_radius_search", "fsk_grid_workspace_bytes", "fsk_sinkhorn_grid",
 )
 
 
@@ -68,6 +68,8 @@ def lib() -> ctypes.CDLL:
         L.fsk_workspace_bytes.argtypes = [ctypes.POINTER(fsk_opts), ctypes.c_int, ctypes.c_int]
         L.fsk_async_workspace_bytes.restype = ctypes.c_size_t
         L.fsk_async_workspace_bytes.argtypes = [ctypes.POINTER(fsk_opts), ctypes.c_int32, ctypes.c_int32]
+        L.fsk_grid_workspace_bytes.restype = ctypes.c_size_t
+        L.fsk_grid_workspace_bytes.argtypes = [ctypes.POINTER(fsk_opts), ctypes.c_int32, ctypes.c_int32]
         _lib = L
     return _lib
 
@@ -208,6 +210,17 @@ def fsk_sinkhorn_async_emulated(opts, K, a, b, u, v, tau, sync_every, workspace,
     return _check(lib().fsk_sinkhorn_async_emulated(
         ctypes.byref(opts), _p(K), _ld(K), _vec(a), _vec(b), _vec(u), _vec(v), ctypes.c_int32(tau),
         ctypes.c_int32(sync_every), wp, wn, _stream(stream)))
+
+
+def fsk_grid_workspace_bytes(opts, p_r: int, p_c: int) -> int:
+    return int(lib().fsk_grid_workspace_bytes(ctypes.byref(opts), p_r, p_c))
+
+
+def fsk_sinkhorn_grid(opts, K, a, b, u, v, p_r, p_c, workspace, stream=None) -> int:
+    wp, wn = _ws(workspace)
+    return _check(lib().fsk_sinkhorn_grid(
+        ctypes.byref(opts), _p(K), _ld(K), _vec(a), _vec(b), _vec(u), _vec(v), ctypes.c_int32(p_r),
+        ctypes.c_int32(p_c), wp, wn, _stream(stream)))
 
 
 def fsk_marginals(opts, K, a, u, v, row_marginal, col_marginal, workspace, want_err=False,

@@ -529,6 +529,82 @@ int fsk_sinkhorn_async_emulated(const fsk_opts* opts, const void* K, int64_t ldK
   return FSK_OK;
 }
 
+// ------------------------------------------------------------- 2D block grid
+struct GridWs { size_t stride_bytes, row_off, strip_off, tile_off, total; int64_t stride; };
+static GridWs grid_ws(const fsk_opts* o, int p_r, int p_c) {
+  GridWs g{};
+  g.stride_bytes = align_up((size_t)o->n * elem_size(o->dtype), 256);
+  g.stride = (int64_t)(g.stride_bytes / elem_size(o->dtype));
+  g.row_off = 0;                                                  // p_c block-row products
+  g.strip_off = g.row_off + (size_t)p_c * g.stride_bytes;         // strips of one block row
+  g.tile_off = g.strip_off + (size_t)col_strips(o->n / p_r) * g.stride_bytes;  // p_r block-column products
+  g.total = g.tile_off + (size_t)p_r * g.stride_bytes;
+  return g;
+}
+
+static int check_grid(const fsk_opts* opts, int32_t p_r, int32_t p_c) {
+  FSK_TRY(check_common(opts));
+  if (p_r < 1 || p_c < 1) return set_error(FSK_EINVAL, "grid %d x %d must be at least 1 x 1", p_r, p_c);
+  if (opts->n % p_r != 0 || opts->n % p_c != 0)
+    return set_error(FSK_EDIV, "grid %d x %d does not divide n = %d", p_r, p_c, opts->n);
+  if (((size_t)(opts->n / p_c) * elem_size(opts->dtype)) % 16 != 0)
+    return set_error(FSK_EALIGN, "block columns of %d entries do not start on 16-byte boundaries",
+                     opts->n / p_c);
+  return FSK_OK;
+}
+
+size_t fsk_grid_workspace_bytes(const fsk_opts* opts, int32_t p_r, int32_t p_c) {
+  if (check_grid(opts, p_r, p_c) != FSK_OK) return 0;
+  return grid_ws(opts, p_r, p_c).total;
+}
+
+int fsk_sinkhorn_grid(const fsk_opts* opts, const void* K, int64_t ldK, const void* a, const void* b,
+                      void* u, void* v, int32_t p_r, int32_t p_c, void* workspace, size_t ws_bytes,
+                      void* stream) {
+  clear_error();
+  FSK_TRY(check_grid(opts, p_r, p_c));
+  if (opts->m != 1) return set_error(FSK_EINVAL, "dense call takes m = 1");
+  if (opts->tol > 0.0) return set_error(FSK_EUNSUPPORTED, "the grid flow runs a fixed number of iterations");
+  if (opts->damping != FSK_DAMP_NONE) return set_error(FSK_EUNSUPPORTED, "the grid flow is undamped");
+  FSK_TRY(check_matrix("K", K, ldK, opts->n, opts->dtype));
+  FSK_TRY(check_vec("a", a, false));
+  FSK_TRY(check_vec("b", b, false));
+  FSK_TRY(check_vec("u", u, true));
+  FSK_TRY(check_vec("v", v, true));
+  const GridWs g = grid_ws(opts, p_r, p_c);
+  if (!workspace || ws_bytes < g.total)
+    return set_error(FSK_EWORKSPACE, "grid flow needs %zu workspace bytes, got %zu", g.total, ws_bytes);
+  if (!aligned16(workspace)) return set_error(FSK_EALIGN, "workspace is not 16-byte aligned");
+  hipStream_t st = (hipStream_t)stream;
+  const int n = opts->n, dt = opts->dtype, nr = n / p_r, nc = n / p_c;
+  const size_t s = elem_size(dt);
+  char* ws = (char*)workspace;
+  const char* Kc = (const char*)K;
+  for (int it = 0; it < opts->max_iters; ++it) {
+    // block products K_ij v_j for every block row at once, one launch per block column j;
+    // the row-wise reduction over j then divides
+    if (p_c == 1) {
+      FSK_TRY(launch_rowpass(dt, K, ldK, n, n, v, a, nullptr, u, kEpiDivide, 1.0, st));
+    } else {
+      for (int j = 0; j < p_c; ++j)
+        FSK_TRY(launch_rowpass(dt, Kc + (size_t)j * nc * s, ldK, nc, n, (const char*)v + (size_t)j * nc * s,
+                               nullptr, nullptr, ws + g.row_off + (size_t)j * g.stride_bytes,
+                               kEpiProduct, 1.0, st));
+      FSK_TRY(launch_colreduce(dt, ws + g.row_off, g.stride, p_c, 0, n, a, nullptr, u, kEpiDivide, 1.0, st));
+    }
+    // block products K_ij^T u_i for every block column at once, one block row i at a time;
+    // the column-wise reduction over i then divides
+    for (int i = 0; i < p_r; ++i) {
+      FSK_TRY(launch_colpartial(dt, Kc + (size_t)i * nr * (size_t)ldK * s, ldK, n, nr, 0, n,
+                                (const char*)u + (size_t)i * nr * s, ws + g.strip_off, g.stride, st));
+      FSK_TRY(launch_colreduce(dt, ws + g.strip_off, g.stride, col_strips(nr), 0, n, nullptr, nullptr,
+                               ws + g.tile_off + (size_t)i * g.stride_bytes, kEpiProduct, 1.0, st));
+    }
+    FSK_TRY(launch_colreduce(dt, ws + g.tile_off, g.stride, p_r, 0, n, b, nullptr, v, kEpiDivide, 1.0, st));
+  }
+  return FSK_OK;
+}
+
 // ------------------------------------------------------------- one worker's share
 static int check_block(const fsk_opts* opts, const void* K_slab, int64_t ldK, int32_t row0,
                        int32_t rows) {
