@@ -41,9 +41,11 @@ def _load():
         L.orc_max.restype = ctypes.c_double
         L.orc_max_sqeuclid.restype = ctypes.c_double
         L.orc_lse.restype = ctypes.c_double
+        L.orc_dp_normal.restype = ctypes.c_double
+        L.orc_rdp_epsilon.restype = ctypes.c_double
         for name in ("orc_num_threads", "orc_sinkhorn_dense", "orc_sinkhorn_dense_tol",
                      "orc_sinkhorn_blocked", "orc_sinkhorn_dense_damped", "orc_sinkhorn_batched",
-                     "orc_sinkhorn_async_emulated", "orc_sinkhorn_grid",
+                     "orc_sinkhorn_async_emulated", "orc_sinkhorn_grid", "orc_sinkhorn_batched_dp",
                      "orc_sinkhorn_log_points", "orc_sinkhorn_log_cost"):
             getattr(L, name).restype = ctypes.c_int
         _lib = L
@@ -242,6 +244,60 @@ def sinkhorn_batched(K, A, B, iters: int, U0=None, V0=None):
                                       _INT(iters))
     assert rc == 0
     return U, V
+
+
+# ---------------------------------------------------------- privacy layer ---
+
+_U64 = ctypes.c_uint64
+
+
+def philox4x32_10(ctr, key) -> np.ndarray:
+    """One Philox4x32-10 block: counter (4 x uint32), key (2 x uint32) -> 4 x uint32."""
+    c = (ctypes.c_uint32 * 4)(*[int(x) for x in ctr])
+    k = (ctypes.c_uint32 * 2)(*[int(x) for x in key])
+    out = (ctypes.c_uint32 * 4)()
+    _load().orc_philox4x32_10(c, k, out)
+    return np.array(list(out), dtype=np.uint32)
+
+
+def dp_normals(seed: int, release: int, first: int, count: int) -> np.ndarray:
+    """Standard normal numbers first .. first+count-1 of a release."""
+    out = np.empty(count, dtype=np.float64)
+    _load().orc_dp_normals(_U64(seed), _U64(release), _U64(first), _I64(count), _ptr(out))
+    return out
+
+
+def dp_release(X, S: float, sigma: float, seed: int, release: int) -> np.ndarray:
+    """Clip the rows of log X to l2 norm S, add sigma * N(0, 1), exponentiate; returns a new array."""
+    X = _f64(X).copy()
+    if X.ndim == 1:
+        X = X[:, None]
+    n, m = X.shape
+    _load().orc_dp_release(_ptr(X), _I64(n), _INT(m), _DBL(S), _DBL(sigma), _U64(seed), _U64(release))
+    return X
+
+
+def sinkhorn_batched_dp(K, A, B, iters: int, S_u, S_v, sigma_u, sigma_v, seed: int, release0: int = 0,
+                        U0=None, V0=None):
+    """Multitarget iteration with a clipped, noised release after every update."""
+    kp, kf, n, ld = _square(K)
+    A, B = _f64(A), _f64(B)
+    m = A.shape[1]
+    U, V = _init(K.shape[0], U0, m), _init(K.shape[0], V0, m)
+    rc = _load().orc_sinkhorn_batched_dp(kp, kf, n, ld, _INT(m), _ptr(A), _ptr(B), _ptr(U), _ptr(V),
+                                         _INT(iters), _DBL(S_u), _DBL(S_v), _DBL(sigma_u), _DBL(sigma_v),
+                                         _U64(seed), _U64(release0))
+    assert rc == 0
+    return U, V
+
+
+def rdp_epsilon(S: float, sigma: float, releases: int, delta: float, orders):
+    """(eps, minimising order) of the Renyi-DP accountant for `releases` clipped Gaussian releases."""
+    orders = _f64(orders)
+    best = _DBL(0.0)
+    eps = _load().orc_rdp_epsilon(_DBL(S), _DBL(sigma), _I64(releases), _DBL(delta), _ptr(orders),
+                                  _INT(orders.size), ctypes.byref(best))
+    return float(eps), float(best.value)
 
 
 def row_marginal(K, u, v) -> np.ndarray:

@@ -482,6 +482,110 @@ int orc_sinkhorn_batched(const void* K, int k_is_f32, int64_t n, int64_t ld, int
   return 0;
 }
 
+/* ------------------------------------------------- privacy layer (DP appendix) */
+
+/* Philox4x32-10 (Salmon, Moraes, Dror, Shaw: "Parallel random numbers: as easy as 1, 2, 3",
+ * SC'11): a counter-based generator; 128-bit counter, 64-bit key, ten rounds of two
+ * 32x32->64 multiplications with the key bumped by Weyl constants between rounds. */
+void orc_philox4x32_10(const uint32_t ctr[4], const uint32_t key[2], uint32_t out[4]) {
+  uint32_t c0 = ctr[0], c1 = ctr[1], c2 = ctr[2], c3 = ctr[3], k0 = key[0], k1 = key[1];
+  for (int round = 0; round < 10; ++round) {
+    const uint64_t p0 = (uint64_t)0xD2511F53u * c0, p1 = (uint64_t)0xCD9E8D57u * c2;
+    const uint32_t n0 = (uint32_t)(p1 >> 32) ^ c1 ^ k0, n1 = (uint32_t)p1;
+    const uint32_t n2 = (uint32_t)(p0 >> 32) ^ c3 ^ k1, n3 = (uint32_t)p0;
+    c0 = n0; c1 = n1; c2 = n2; c3 = n3;
+    k0 += 0x9E3779B9u;
+    k1 += 0xBB67AE85u;
+  }
+  out[0] = c0; out[1] = c1; out[2] = c2; out[3] = c3;
+}
+
+/* Standard normal number `e` of release `release` under `seed`: Philox call e/4 with counter
+ * (call, release) and key seed gives x0..x3; Box-Muller on (x0, x1) gives normals 0 and 1 of
+ * the call, on (x2, x3) normals 2 and 3: with u1 = (xa + 1/2) 2^-32, u2 = (xb + 1/2) 2^-32,
+ * z_even = sqrt(-2 ln u1) cos(2 pi u2), z_odd = sqrt(-2 ln u1) sin(2 pi u2). */
+double orc_dp_normal(uint64_t seed, uint64_t release, uint64_t e) {
+  const uint64_t call = e / 4;
+  const uint32_t ctr[4] = {(uint32_t)call, (uint32_t)(call >> 32), (uint32_t)release, (uint32_t)(release >> 32)};
+  const uint32_t key[2] = {(uint32_t)seed, (uint32_t)(seed >> 32)};
+  uint32_t x[4];
+  orc_philox4x32_10(ctr, key, x);
+  const int pair = (int)((e % 4) / 2);
+  const double u1 = ((double)x[2 * pair] + 0.5) * 0x1p-32, u2 = ((double)x[2 * pair + 1] + 0.5) * 0x1p-32;
+  const double r = sqrt(-2.0 * log(u1)), phi = 6.283185307179586476925286766559 * u2;
+  return (e % 2 == 0) ? r * cos(phi) : r * sin(phi);
+}
+
+void orc_dp_normals(uint64_t seed, uint64_t release, uint64_t first, int64_t count, double* out) {
+  for (int64_t t = 0; t < count; ++t) out[t] = orc_dp_normal(seed, release, first + (uint64_t)t);
+}
+
+/* One release of an n x m scaling matrix X (row-major, in place): L = log X; every row of L is
+ * scaled by min(1, S / ||L_i||_2) (the row-wise clip across the m targets; S <= 0 or infinite:
+ * no clipping, the Gaussian-only ablation); L_ik += sigma * normal number i*m + k of this
+ * release; X = exp(L). */
+void orc_dp_release(double* X, int64_t n, int m, double S, double sigma, uint64_t seed, uint64_t release) {
+  for (int64_t i = 0; i < n; ++i) {
+    double sq = 0.0;
+    for (int k = 0; k < m; ++k) {
+      const double l = log(X[i * m + k]);
+      sq += l * l;
+    }
+    const double norm = sqrt(sq);
+    const double scale = (S > 0.0 && isfinite(S) && norm > S) ? S / norm : 1.0;
+    for (int k = 0; k < m; ++k) {
+      const double l = log(X[i * m + k]) * scale + sigma * orc_dp_normal(seed, release, (uint64_t)(i * m + k));
+      X[i * m + k] = exp(l);
+    }
+  }
+}
+
+/* Multitarget iteration with a release after every update (centralised view: the noised
+ * scalings replace the held ones): U = A ./ (K V), release 2t of U, V = B ./ (K^T U), release
+ * 2t + 1 of V, for t = release0/2 ...; release0 (even) numbers the first release of this call. */
+int orc_sinkhorn_batched_dp(const void* K, int k_is_f32, int64_t n, int64_t ld, int m, const double* A,
+                            const double* B, double* U, double* V, int iters, double S_u, double S_v,
+                            double sigma_u, double sigma_v, uint64_t seed, uint64_t release0) {
+  double* Q = (double*)malloc(sizeof(double) * (size_t)n * (size_t)m);
+  if (!Q) return -1;
+  for (int t = 0; t < iters; ++t) {
+    for (int64_t i = 0; i < n; ++i) {
+      for (int k = 0; k < m; ++k) Q[i * m + k] = 0.0;
+      for (int64_t j = 0; j < n; ++j)
+        for (int k = 0; k < m; ++k) Q[i * m + k] += k_at(K, k_is_f32, ld, i, j) * V[j * m + k];
+      for (int k = 0; k < m; ++k) U[i * m + k] = A[i * m + k] / Q[i * m + k];
+    }
+    orc_dp_release(U, n, m, S_u, sigma_u, seed, release0 + 2 * (uint64_t)t);
+    for (int64_t j = 0; j < n; ++j) {
+      for (int k = 0; k < m; ++k) Q[j * m + k] = 0.0;
+      for (int64_t i = 0; i < n; ++i)
+        for (int k = 0; k < m; ++k) Q[j * m + k] += k_at(K, k_is_f32, ld, i, j) * U[i * m + k];
+      for (int k = 0; k < m; ++k) V[j * m + k] = B[j * m + k] / Q[j * m + k];
+    }
+    orc_dp_release(V, n, m, S_v, sigma_v, seed, release0 + 2 * (uint64_t)t + 1);
+  }
+  free(Q);
+  return 0;
+}
+
+/* Renyi-DP accountant: a Gaussian release with l2 sensitivity Delta = 2 S and noise sigma is
+ * (p, p Delta^2 / (2 sigma^2))-RDP; `releases` of them add up; the (eps, delta) bound is the
+ * minimum over the given orders p > 1 of eps_RDP(p) + log(1/delta)/(p - 1).  Returns the
+ * bound and stores the minimising order. */
+double orc_rdp_epsilon(double S, double sigma, int64_t releases, double delta, const double* orders,
+                       int n_orders, double* best_order) {
+  double best = INFINITY, arg = NAN;
+  for (int t = 0; t < n_orders; ++t) {
+    const double p = orders[t];
+    if (!(p > 1.0)) continue;
+    const double rdp = (double)releases * p * (2.0 * S) * (2.0 * S) / (2.0 * sigma * sigma);
+    const double eps = rdp + log(1.0 / delta) / (p - 1.0);
+    if (eps < best) { best = eps; arg = p; }
+  }
+  if (best_order) *best_order = arg;
+  return best;
+}
+
 /* ------------------------------------------------------------- log domain */
 
 /* LSE(z) = max z + log sum exp(z - max z). */

@@ -631,3 +631,99 @@ def test_grid_iteration_is_the_centralised_one(orc):
         orc.sinkhorn_grid(K, a, b, 1, 5, 2)
     with pytest.raises(ValueError):
         orc.sinkhorn_grid(K, a, b, 1, 2, 7)
+
+
+# ------------------------------------------------ privacy layer (DP appendix) ---
+
+def test_philox_known_answers(orc):
+    with open(os.path.join(HERE, "golden", "philox4x32_10_kat.txt")) as fh:
+        rows = [ln.split() for ln in fh if ln.strip() and not ln.startswith("#")]
+    assert len(rows) == 3
+    for r in rows:
+        w = [int(t, 16) for t in r]
+        assert list(orc.philox4x32_10(w[0:4], w[4:6])) == w[6:10]
+
+
+def test_dp_normals_are_standard_normal_and_counter_based(orc):
+    import scipy.stats
+    z = orc.dp_normals(11, 4, 0, 200000)
+    assert scipy.stats.kstest(z, "norm").pvalue > 1e-3
+    r2 = z[0::2] ** 2 + z[1::2] ** 2                      # a Box-Muller pair: chi-square, 2 dof
+    assert scipy.stats.kstest(r2, "chi2", args=(2,)).pvalue > 1e-3
+    assert abs(np.corrcoef(z[:-1], z[1:])[0, 1]) < 0.01
+    other = orc.dp_normals(11, 5, 0, 200000)              # another release, another seed: unrelated streams
+    assert abs(np.corrcoef(z, other)[0, 1]) < 0.01
+    assert abs(np.corrcoef(z, orc.dp_normals(12, 4, 0, 200000))[0, 1]) < 0.01
+    # counter-based: any sub-range can be drawn on its own, in any order
+    assert np.array_equal(orc.dp_normals(11, 4, 777, 100), z[777:877])
+    assert np.array_equal(orc.dp_normals(11, 4, 2 ** 34 + 3, 5), orc.dp_normals(11, 4, 2 ** 34, 8)[3:])
+
+
+def test_dp_release_clip_and_noise(orc):
+    rng = np.random.default_rng(8)
+    X = np.exp(rng.normal(scale=3.0, size=(50, 6)))
+    L = np.log(X)
+    # no clip, no noise: identity up to exp(log(.))
+    assert np.allclose(orc.dp_release(X, np.inf, 0.0, 1, 0), X, rtol=1e-14)
+    assert np.allclose(orc.dp_release(X, 0.0, 0.0, 1, 0), X, rtol=1e-14)
+    # clip only: rows keep their direction, norms become min(norm, S)
+    S = 5.0
+    Lc = np.log(orc.dp_release(X, S, 0.0, 1, 0))
+    norms = np.linalg.norm(L, axis=1)
+    assert (norms > S).any() and (norms < S).any()
+    assert np.allclose(np.linalg.norm(Lc, axis=1), np.minimum(norms, S), rtol=1e-12)
+    assert np.allclose(Lc * norms[:, None], L * np.linalg.norm(Lc, axis=1)[:, None], rtol=1e-10, atol=1e-12)
+    # l2 sensitivity of the clipped release is at most 2 S, whatever the inputs
+    Y = np.exp(rng.normal(scale=30.0, size=(50, 6)))
+    assert (np.linalg.norm(Lc - np.log(orc.dp_release(Y, S, 0.0, 1, 0)), axis=1) <= 2 * S + 1e-9).all()
+    # one target: the row clip is a clamp of the log-scaling to [-S, S]
+    x1 = np.exp(rng.normal(scale=3.0, size=40))
+    assert np.allclose(np.log(orc.dp_release(x1, 2.0, 0.0, 1, 0))[:, 0], np.clip(np.log(x1), -2.0, 2.0), rtol=1e-12)
+    # noise only: the log-scalings move by sigma times the release's normal numbers, element i*m + k
+    sigma = 0.3
+    Ln = np.log(orc.dp_release(X, np.inf, sigma, 21, 9))
+    assert np.allclose(Ln - L, sigma * orc.dp_normals(21, 9, 0, X.size).reshape(X.shape), rtol=0, atol=1e-12)
+    # both: clip first, then add
+    Lb = np.log(orc.dp_release(X, S, sigma, 21, 9))
+    assert np.allclose(Lb - Lc, sigma * orc.dp_normals(21, 9, 0, X.size).reshape(X.shape), rtol=0, atol=1e-12)
+
+
+def test_batched_dp_iteration(orc):
+    x, y, a, b, C, K = problem(24, 61, eps=0.3)
+    rng = np.random.default_rng(9)
+    A = rng.uniform(0.5, 1.5, (24, 3)); A /= A.sum(0)
+    B = rng.uniform(0.5, 1.5, (24, 3)); B /= B.sum(0)
+    U0, V0 = orc.sinkhorn_batched(K, A, B, 7)
+    U1, V1 = orc.sinkhorn_batched_dp(K, A, B, 7, np.inf, np.inf, 0.0, 0.0, 5)
+    assert np.allclose(U1, U0, rtol=1e-12) and np.allclose(V1, V0, rtol=1e-12)
+    # two iterations by hand: NumPy products, the oracle's release
+    S_u, S_v, s_u, s_v, seed = 4.0, 3.0, 0.05, 0.02, 77
+    U = np.ones((24, 3)); V = np.ones((24, 3))
+    for t in range(2):
+        U = orc.dp_release(A / (K @ V), S_u, s_u, seed, 10 + 2 * t)
+        V = orc.dp_release(B / (K.T @ U), S_v, s_v, seed, 10 + 2 * t + 1)
+    Ud, Vd = orc.sinkhorn_batched_dp(K, A, B, 2, S_u, S_v, s_u, s_v, seed, release0=10)
+    assert np.allclose(Ud, U, rtol=1e-12) and np.allclose(Vd, V, rtol=1e-12)
+    # resume: 2 + 3 iterations with the release counter carried on equal 5
+    U5, V5 = orc.sinkhorn_batched_dp(K, A, B, 5, S_u, S_v, s_u, s_v, seed, release0=10)
+    Ur, Vr = orc.sinkhorn_batched_dp(K, A, B, 3, S_u, S_v, s_u, s_v, seed, release0=14, U0=Ud, V0=Vd)
+    assert np.array_equal(Ur, U5) and np.array_equal(Vr, V5)
+
+
+def test_rdp_accountant_closed_form(orc):
+    """With c = T (2S)^2 / (2 sigma^2) the bound c p + log(1/delta)/(p - 1) is minimised at
+    p* = 1 + sqrt(log(1/delta)/c) with value c + 2 sqrt(c log(1/delta))."""
+    S, sigma, T, delta = 4.0, 50.0, 2000, 1e-5
+    c = T * (2 * S) ** 2 / (2 * sigma ** 2)
+    p_star = 1 + np.sqrt(np.log(1 / delta) / c)
+    best = c + 2 * np.sqrt(c * np.log(1 / delta))
+    eps, p = orc.rdp_epsilon(S, sigma, T, delta, [1.5, p_star, 8.0, 64.0])
+    assert p == p_star and eps == pytest.approx(best, rel=1e-13)
+    grid = np.concatenate([1 + np.arange(1, 100) / 10.0, np.arange(12, 64)])
+    eps_g, p_g = orc.rdp_epsilon(S, sigma, T, delta, grid)
+    assert best <= eps_g <= 1.01 * best and abs(p_g - p_star) <= 0.1
+    assert orc.rdp_epsilon(S, sigma, T, delta, [0.5, 1.0, 2.0])[1] == 2.0       # orders <= 1 are not RDP orders
+    # additive composition: twice the releases, twice the Renyi term
+    e1 = orc.rdp_epsilon(S, sigma, T, delta, [3.0])[0] - np.log(1 / delta) / 2
+    e2 = orc.rdp_epsilon(S, sigma, 2 * T, delta, [3.0])[0] - np.log(1 / delta) / 2
+    assert e2 == pytest.approx(2 * e1, rel=1e-13)
