@@ -250,6 +250,42 @@ int fsk_sinkhorn_batched(const fsk_opts* opts, const void* K, int64_t ldK, const
                          const void* B, void* U, void* V, void* workspace, size_t ws_bytes,
                          void* stream);
 
+/* ---- privacy layer (privacy appendix: "Gaussian noise on log-domain scalings", "RDP
+ * accountant") ---------------------------------------------------------------------------
+ * A release replaces an n x m scaling matrix X (device, row-major, leading dimension m, in
+ * place) by exp(clip_S(log X) + sigma Z): clip_S scales every row of log X (the m targets of
+ * one index) to l2 norm at most S; S <= 0 or +inf disables the clip (the Gaussian-only
+ * ablation).  Z_ik is standard normal number i*m + k of the stream (seed, release): Philox4x32-10
+ * with key = seed and counter = (call e/4, release) yields words x0..x3; with
+ * u1 = (xa + 1/2) 2^-32, u2 = (xb + 1/2) 2^-32 the pair (x0, x1) gives numbers 0 and 1 of the
+ * call as sqrt(-2 ln u1) cos(2 pi u2) and sqrt(-2 ln u1) sin(2 pi u2), the pair (x2, x3) numbers
+ * 2 and 3.  The stream is a pure function of (seed, release, element): no state is kept. */
+typedef struct {
+  double clip_u, clip_v;   /* S_u, S_v */
+  double sigma_u, sigma_v; /* noise scales, >= 0 */
+  uint64_t seed;
+  uint64_t release0;       /* index of the first release of the call (even); iteration t of the
+                              call releases U as release0 + 2t and V as release0 + 2t + 1, so a
+                              resumed run passes release0 + 2 * (iterations already done) */
+} fsk_dp;
+
+/* One release of X (n = opts->n rows, m = opts->m columns, dtype of opts).  Enqueue only. */
+int fsk_dp_release(const fsk_opts* opts, void* X, double clip, double sigma, uint64_t seed,
+                   uint64_t release, void* stream);
+
+/* fsk_sinkhorn_batched with a release after every update (the noised scalings replace the held
+ * ones, as in the appendix' experiments): U = A ./ (K V), release U, V = B ./ (K^T U), release V. */
+int fsk_sinkhorn_batched_dp(const fsk_opts* opts, const void* K, int64_t ldK, const void* A,
+                            const void* B, void* U, void* V, const fsk_dp* dp, void* workspace,
+                            size_t ws_bytes, void* stream);
+
+/* Host-only accountant: `releases` Gaussian releases with l2 sensitivity 2*clip and noise sigma
+ * compose to eps_RDP(p) = releases * p (2 clip)^2 / (2 sigma^2); *eps_out = min over the given
+ * orders p > 1 of eps_RDP(p) + log(1/delta)/(p - 1), *order_out (may be NULL) the minimiser.
+ * The paper does not list its grid of orders: the caller supplies one. */
+int fsk_rdp_epsilon(double clip, double sigma, int64_t releases, double delta, const double* orders,
+                    int32_t n_orders, double* eps_out, double* order_out);
+
 /* ---- measurement helpers -----------------------------------------------------------------
  * fsk_dense_profile runs `reps` iterations exactly as fsk_sinkhorn_dense does in
  * fixed-iteration mode (same kernels, same launch shapes, u and v advance), but brackets the

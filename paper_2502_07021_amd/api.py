@@ -32,7 +32,8 @@ EXPORTS = (
     "fsk_block_colpartial", "fsk_block_fused", "fsk_sinkhorn_log_points", "fsk_sinkhorn_batched",
     "fsk_dense_profile", "fsk_bench_copy", "fsk_bench_read", "fsk_async_workspace_bytes",
     "fsk_sinkhorn_async_emulated", "fsk_plan_objective", "fsk_kernel_from_cost_lambda",
-    "fsk_radius_search", "fsk_grid_workspace_bytes", "fsk_sinkhorn_grid",
+    "fsk_radius_search", "fsk_grid_workspace_bytes", "fsk_sinkhorn_grid", "fsk_dp_release",
+    "fsk_sinkhorn_batched_dp", "fsk_rdp_epsilon",
 )
 
 
@@ -210,6 +211,35 @@ def fsk_sinkhorn_async_emulated(opts, K, a, b, u, v, tau, sync_every, workspace,
     return _check(lib().fsk_sinkhorn_async_emulated(
         ctypes.byref(opts), _p(K), _ld(K), _vec(a), _vec(b), _vec(u), _vec(v), ctypes.c_int32(tau),
         ctypes.c_int32(sync_every), wp, wn, _stream(stream)))
+
+
+class fsk_dp(ctypes.Structure):
+    _fields_ = [("clip_u", ctypes.c_double), ("clip_v", ctypes.c_double),
+                ("sigma_u", ctypes.c_double), ("sigma_v", ctypes.c_double),
+                ("seed", ctypes.c_uint64), ("release0", ctypes.c_uint64)]
+
+
+def fsk_dp_release(opts, X, clip, sigma, seed, release, stream=None) -> int:
+    return _check(lib().fsk_dp_release(ctypes.byref(opts), _vec(X), ctypes.c_double(clip),
+                                       ctypes.c_double(sigma), ctypes.c_uint64(seed),
+                                       ctypes.c_uint64(release), _stream(stream)))
+
+
+def fsk_sinkhorn_batched_dp(opts, K, A, B, U, V, dp: "fsk_dp", workspace, stream=None) -> int:
+    wp, wn = _ws(workspace)
+    return _check(lib().fsk_sinkhorn_batched_dp(ctypes.byref(opts), _p(K), _ld(K), _vec(A), _vec(B),
+                                                _vec(U), _vec(V), ctypes.byref(dp), wp, wn,
+                                                _stream(stream)))
+
+
+def fsk_rdp_epsilon(clip, sigma, releases, delta, orders):
+    """(eps, minimising order) of the Renyi-DP accountant (host only)."""
+    arr = (ctypes.c_double * len(orders))(*[float(x) for x in orders])
+    eps, order = ctypes.c_double(0.0), ctypes.c_double(0.0)
+    _check(lib().fsk_rdp_epsilon(ctypes.c_double(clip), ctypes.c_double(sigma), ctypes.c_int64(releases),
+                                 ctypes.c_double(delta), arr, ctypes.c_int32(len(orders)),
+                                 ctypes.byref(eps), ctypes.byref(order)))
+    return float(eps.value), float(order.value)
 
 
 def fsk_grid_workspace_bytes(opts, p_r: int, p_c: int) -> int:

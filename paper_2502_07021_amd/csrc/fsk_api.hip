@@ -706,7 +706,67 @@ int fsk_sinkhorn_batched(const fsk_opts* opts, const void* K, int64_t ldK, const
   FSK_TRY(check_vec("U", U, false));
   FSK_TRY(check_vec("V", V, false));
   if (workspace && !aligned16(workspace)) return set_error(FSK_EALIGN, "workspace is not 16-byte aligned");
-  return run_sinkhorn_batched(opts, K, ldK, A, B, U, V, workspace, ws_bytes, (hipStream_t)stream);
+  return run_sinkhorn_batched(opts, K, ldK, A, B, U, V, workspace, ws_bytes, nullptr, (hipStream_t)stream);
+}
+
+// ------------------------------------------------------------- privacy layer
+static int check_dp(const fsk_dp* dp) {
+  if (!dp) return set_error(FSK_EINVAL, "dp is NULL");
+  if (!(dp->sigma_u >= 0.0) || !(dp->sigma_v >= 0.0) || !std::isfinite(dp->sigma_u) ||
+      !std::isfinite(dp->sigma_v))
+    return set_error(FSK_EINVAL, "noise scales must be finite and >= 0");
+  if (std::isnan(dp->clip_u) || std::isnan(dp->clip_v)) return set_error(FSK_EINVAL, "clip radius is NaN");
+  if (dp->release0 % 2 != 0) return set_error(FSK_EINVAL, "release0 must be even (a U release)");
+  return FSK_OK;
+}
+
+int fsk_dp_release(const fsk_opts* opts, void* X, double clip, double sigma, uint64_t seed,
+                   uint64_t release, void* stream) {
+  clear_error();
+  FSK_TRY(check_common(opts));
+  if (!X) return set_error(FSK_EINVAL, "X is NULL");
+  if (!(sigma >= 0.0) || !std::isfinite(sigma)) return set_error(FSK_EINVAL, "sigma must be finite and >= 0");
+  if (std::isnan(clip)) return set_error(FSK_EINVAL, "clip radius is NaN");
+  return launch_dp_release(opts->dtype, X, opts->n, opts->m, clip, sigma, seed, release, (hipStream_t)stream);
+}
+
+int fsk_sinkhorn_batched_dp(const fsk_opts* opts, const void* K, int64_t ldK, const void* A,
+                            const void* B, void* U, void* V, const fsk_dp* dp, void* workspace,
+                            size_t ws_bytes, void* stream) {
+  clear_error();
+  FSK_TRY(check_common(opts));
+  FSK_TRY(check_dp(dp));
+  if (opts->c != 1) return set_error(FSK_EUNSUPPORTED, "batched call takes c = 1");
+  if (opts->tol > 0.0) return set_error(FSK_EUNSUPPORTED, "batched call runs a fixed number of iterations");
+  FSK_TRY(check_matrix("K", K, ldK, opts->n, opts->dtype));
+  FSK_TRY(check_vec("A", A, false));
+  FSK_TRY(check_vec("B", B, false));
+  FSK_TRY(check_vec("U", U, false));
+  FSK_TRY(check_vec("V", V, false));
+  if (workspace && !aligned16(workspace)) return set_error(FSK_EALIGN, "workspace is not 16-byte aligned");
+  return run_sinkhorn_batched(opts, K, ldK, A, B, U, V, workspace, ws_bytes, dp, (hipStream_t)stream);
+}
+
+int fsk_rdp_epsilon(double clip, double sigma, int64_t releases, double delta, const double* orders,
+                    int32_t n_orders, double* eps_out, double* order_out) {
+  clear_error();
+  if (!(clip > 0.0) || !std::isfinite(clip) || !(sigma > 0.0) || !std::isfinite(sigma))
+    return set_error(FSK_EINVAL, "the accountant needs a finite clip radius > 0 and sigma > 0");
+  if (releases < 0 || !(delta > 0.0) || !(delta < 1.0))
+    return set_error(FSK_EINVAL, "need releases >= 0 and 0 < delta < 1");
+  if (!orders || n_orders < 1 || !eps_out) return set_error(FSK_EINVAL, "orders or eps_out is NULL/empty");
+  const double sens = 2.0 * clip, per_order = (double)releases * sens * sens / (2.0 * sigma * sigma);
+  double best = INFINITY, arg = NAN;
+  for (int t = 0; t < n_orders; ++t) {
+    const double p = orders[t];
+    if (!(p > 1.0)) continue;
+    const double eps = per_order * p + std::log(1.0 / delta) / (p - 1.0);
+    if (eps < best) { best = eps; arg = p; }
+  }
+  if (!std::isfinite(best)) return set_error(FSK_EINVAL, "no order above 1 in the grid");
+  *eps_out = best;
+  if (order_out) *order_out = arg;
+  return FSK_OK;
 }
 
 // ------------------------------------------------------------- measurement helpers

@@ -413,7 +413,8 @@ size_t batched_workspace_bytes(int n, int m) {
 }
 
 int run_sinkhorn_batched(const fsk_opts* o, const void* K, int64_t ldK, const void* A, const void* B,
-                         void* U, void* V, void* workspace, size_t ws_bytes, hipStream_t st) {
+                         void* U, void* V, void* workspace, size_t ws_bytes, const fsk_dp* dp,
+                         hipStream_t st) {
   if (o->dtype != FSK_F32) return set_error(FSK_EUNSUPPORTED, "batched path takes fp32");
   if (o->m > kBtCols)
     return set_error(FSK_EUNSUPPORTED, "batched path is built for m <= 64 histograms per call");
@@ -453,10 +454,16 @@ int run_sinkhorn_batched(const fsk_opts* o, const void* K, int64_t ldK, const vo
       FSK_LAUNCH_CHECK("batched_rowprod_kernel (K V)");
       if (S > 1) FSK_TRY(reduce(S, Af, Uf));
     }
+    if (dp)
+      FSK_TRY(launch_dp_release(FSK_F32, Uf, n, m, dp->clip_u, dp->sigma_u, dp->seed,
+                                dp->release0 + 2 * (uint64_t)it, st));
     hipLaunchKernelGGL(batched_prod_wide_kernel, gridw, block, 0, st, Kf, ldK, n, m,
                        (const float*)Uf, Bf, SW == 1 ? Vf : part, SW == 1 ? 1 : 0);
     FSK_LAUNCH_CHECK("batched_prod_wide_kernel (K^T U)");
     if (SW > 1) FSK_TRY(reduce(SW, Bf, Vf));
+    if (dp)
+      FSK_TRY(launch_dp_release(FSK_F32, Vf, n, m, dp->clip_v, dp->sigma_v, dp->seed,
+                                dp->release0 + 2 * (uint64_t)it + 1, st));
   }
   return FSK_OK;
 }

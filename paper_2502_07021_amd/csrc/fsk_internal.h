@@ -121,8 +121,15 @@ int run_sinkhorn_log_points(const fsk_opts* o, const void* x, const void* y, int
 
 // ------------------------------------------------------------------ multitarget path
 size_t batched_workspace_bytes(int n, int m);
+// `dp` (may be null): release U after every U-update and V after every V-update.
 int run_sinkhorn_batched(const fsk_opts* o, const void* K, int64_t ldK, const void* A, const void* B,
-                         void* U, void* V, void* workspace, size_t ws_bytes, hipStream_t st);
+                         void* U, void* V, void* workspace, size_t ws_bytes, const fsk_dp* dp,
+                         hipStream_t st);
+
+// ------------------------------------------------------------------ privacy layer
+// X (n x m, in place) <- exp(rowclip_S(log X) + sigma * normals of (seed, release)).
+int launch_dp_release(int dtype, void* X, int n, int m, double S, double sigma, uint64_t seed,
+                      uint64_t release, hipStream_t stream);
 
 // ------------------------------------------------------------------ measurement helpers
 int launch_copy(void* dst, const void* src, size_t bytes, hipStream_t stream);

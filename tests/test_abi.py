@@ -40,6 +40,21 @@ def test_opts_struct_layout_matches_header(api):
     assert api.fsk_opts.eta.offset == 40
 
 
+def test_dp_struct_layout_and_host_accountant(api, orc):
+    # double x4, uint64 x2 -> 48 bytes
+    assert ctypes.sizeof(api.fsk_dp) == 48 and api.fsk_dp.seed.offset == 32
+    # the accountant runs on the host: same bound as the oracle's, and bad arguments are refused
+    orders = [1.25, 1.5, 2.0, 3.0, 5.0, 8.0, 16.0, 32.0, 64.0]
+    for S, sigma, T in ((4.0, 50.0, 2000), (1.0, 1.0, 10), (20.0, 0.5, 2)):
+        eps, p = api.fsk_rdp_epsilon(S, sigma, T, 1e-5, orders)
+        eps_o, p_o = orc.rdp_epsilon(S, sigma, T, 1e-5, orders)
+        assert p == p_o and eps == pytest.approx(eps_o, rel=1e-14)
+    for bad in ((0.0, 1.0, 5, 1e-5, orders), (1.0, 0.0, 5, 1e-5, orders), (1.0, 1.0, -1, 1e-5, orders),
+                (1.0, 1.0, 5, 1.0, orders), (1.0, 1.0, 5, 1e-5, [0.5, 1.0])):
+        with pytest.raises(api.FskError):
+            api.fsk_rdp_epsilon(*bad)
+
+
 def test_version_and_error_string(api):
     assert api.fsk_version() >= 100
     assert isinstance(api.lib().fsk_last_error(), bytes)

@@ -1,0 +1,78 @@
+"""GPU parity of the privacy layer (privacy appendix): the clipped, noised release and the
+multitarget iteration with a release after every update, against the oracle."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2502_07021_amd import api, workloads
+from gpu_util import TOL, dev, relerr, tdtype
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.mark.parametrize("dtype,n,m", [(np.float64, 1000, 1), (np.float64, 333, 7), (np.float32, 1030, 64),
+                                       (np.float32, 4096, 1), (np.float32, 257, 3)])
+def test_release_matches_oracle(orc, dtype, n, m):
+    rng = np.random.default_rng(n + m)
+    X = np.exp(rng.normal(scale=2.5, size=(n, m))).astype(dtype)
+    td = tdtype(dtype)
+    opts = api.make_opts(n, td, m=m)
+    tol = TOL[np.dtype(dtype)]
+    for S, sigma in ((np.inf, 0.0), (3.0, 0.0), (0.0, 0.25), (3.0, 0.25)):
+        Xd = dev(X)
+        api.fsk_dp_release(opts, Xd, S, sigma, 1234567890123, 17)
+        torch.cuda.synchronize()
+        ref = orc.dp_release(X.astype(np.float64), S, sigma, 1234567890123, 17)
+        assert relerr(Xd.cpu().numpy(), ref) <= tol
+
+
+def test_device_normals_are_the_oracles(orc):
+    n, m = 5000, 5
+    opts = api.make_opts(n, torch.float64, m=m)
+    X = torch.ones(n, m, dtype=torch.float64, device="cuda")
+    seed, release = 2 ** 63 + 11, 2 ** 40 + 3
+    api.fsk_dp_release(opts, X, 0.0, 1.0, seed, release)
+    torch.cuda.synchronize()
+    z = np.log(X.cpu().numpy()).ravel()
+    assert np.max(np.abs(z - orc.dp_normals(seed, release, 0, n * m))) <= 1e-12
+
+
+def test_batched_dp_matches_oracle_and_resumes(orc):
+    n, m, iters = 515, 8, 6
+    w = workloads.make(5, n=n, m=m)
+    K, _ = orc.gibbs_from_points_f32(w.x, w.y, 0.2, False)
+    S_u, S_v, s_u, s_v, seed = 6.0, 5.0, 0.02, 0.01, 99
+    Uo, Vo = orc.sinkhorn_batched_dp(K, w.a, w.b, iters, S_u, S_v, s_u, s_v, seed, 4)
+    pack = 4
+    ld = (n + pack - 1) // pack * pack
+    Kd = torch.full((n, ld), float("nan"), device="cuda"); Kd[:, :n] = dev(K)
+    A, B = dev(w.a), dev(w.b)
+
+    def run(its, release0, U=None, V=None):
+        opts = api.make_opts(n, torch.float32, m=m, max_iters=its)
+        ws = api.alloc_workspace(opts, api.FSK_MODE_BATCHED)
+        U = torch.ones(n, m, device="cuda") if U is None else U.clone()
+        V = torch.ones(n, m, device="cuda") if V is None else V.clone()
+        dp = api.fsk_dp(S_u, S_v, s_u, s_v, seed, release0)
+        api.fsk_sinkhorn_batched_dp(opts, Kd[:, :n], A, B, U, V, dp, ws)
+        torch.cuda.synchronize()
+        return U, V
+
+    U, V = run(iters, 4)
+    assert relerr(U.cpu().numpy(), Uo) <= 1e-4 and relerr(V.cpu().numpy(), Vo) <= 1e-4
+    U2, V2 = run(2, 4)
+    U6, V6 = run(4, 8, U2, V2)
+    assert torch.equal(U6, U) and torch.equal(V6, V)
+    # no clip, no noise: the plain multitarget iteration
+    opts = api.make_opts(n, torch.float32, m=m, max_iters=iters)
+    ws = api.alloc_workspace(opts, api.FSK_MODE_BATCHED)
+    Up = torch.ones(n, m, device="cuda"); Vp = torch.ones(n, m, device="cuda")
+    api.fsk_sinkhorn_batched(opts, Kd[:, :n], A, B, Up, Vp, ws)
+    Un = torch.ones(n, m, device="cuda"); Vn = torch.ones(n, m, device="cuda")
+    api.fsk_sinkhorn_batched_dp(opts, Kd[:, :n], A, B, Un, Vn, api.fsk_dp(0.0, 0.0, 0.0, 0.0, 1, 0), ws)
+    torch.cuda.synchronize()
+    assert relerr(Un.cpu().numpy(), Up.cpu().numpy()) <= 1e-5
+    with pytest.raises(api.FskError):
+        api.fsk_sinkhorn_batched_dp(opts, Kd[:, :n], A, B, Un, Vn, api.fsk_dp(1.0, 1.0, 0.1, 0.1, 1, 3), ws)
+    with pytest.raises(api.FskError):
+        api.fsk_sinkhorn_batched_dp(opts, Kd[:, :n], A, B, Un, Vn, api.fsk_dp(1.0, 1.0, -0.1, 0.1, 1, 0), ws)
