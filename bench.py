@@ -104,15 +104,23 @@ def bench_dense(args, cfg):
 
     # dominant kernel alone, same launch configuration, HIP events on the launch stream
     stream_ms, other_ms, launches = api.fsk_dense_profile(opts, K, a, b, u, v, ws, args.profile_reps)
-    alg_bytes = float(n) * n * esz * (1 if args.flow == 0 else 2)   # K read once (fused) or twice
+    # K read once per iteration (fused), twice (two-pass flows), or once per CALL (resident:
+    # no HBM roofline applies; the figure below then only says how far from HBM-bound it is)
+    alg_bytes = float(n) * n * esz * (2 if args.flow in (1, 2) else 1)
     achieved = alg_bytes / (stream_ms * 1e-3) / 1e9
     headline = cfg == 3 and args.flow == 0 and n == 32768 and c == 8
+    if args.flow == 3:
+        roofline_note = ("register-resident flow: one launch runs every iteration, K is read from "
+                         "memory once per call; kernel_ms = launch time / iterations is barrier "
+                         "latency, not bandwidth")
     roofline = {"bound": "hbm", "achieved": achieved, "peak": PEAK_HBM_GBS, "unit": "GB/s",
                 "frac": achieved / PEAK_HBM_GBS,
                 "traffic": traffic_from_profile("dense_fused_cfg3_pmc.txt") if headline else None,
-                "kernel": "fused_kernel" if args.flow == 0 else "rowpass_kernel+colpartial_kernel",
+                "kernel": {0: "fused_kernel", 3: "resident_kernel"}.get(args.flow, "rowpass_kernel+colpartial_kernel"),
                 "kernel_ms": stream_ms, "launches_per_step": launches,
                 "algorithmic_bytes_per_step": alg_bytes, "other_kernels_ms": other_ms}
+    if args.flow == 3:
+        roofline["note"] = roofline_note
 
     extra = {}
     if c != 1:   # the same problem with c = 1 (the iterates the blocked run must reproduce)
@@ -135,7 +143,7 @@ def bench_dense(args, cfg):
         "config": {"workload": f"cfg{cfg}: n={n} {'fp64' if esz == 8 else 'fp32'} dense K "
                                f"({n * n * esz / 2**20:.0f} MiB), {laws[cfg]}, eps={w.eps}, "
                                f"row-partitioned c={c} on one GPU, "
-                               f"flow={['fused', 'two_pass', 'algorithm1'][args.flow]}",
+                               f"flow={['fused', 'two_pass', 'algorithm1', 'resident'][args.flow]}",
                    "n": n, "c": c, "eps": w.eps, "iterations": steps},
         "roofline": roofline,
     }
@@ -282,7 +290,9 @@ def main() -> int:
     ap.add_argument("--workload", default="cfg3", choices=["cfg1", "cfg2", "cfg3", "cfg4", "cfg5"])
     ap.add_argument("--n", type=int, default=None, help="override the problem size (same law)")
     ap.add_argument("--c", type=int, default=None, help="row blocks (dense workloads)")
-    ap.add_argument("--flow", type=int, default=0, help="dense: 0 fused, 1 two-pass, 2 Algorithm 1")
+    ap.add_argument("--flow", type=int, default=None,
+                    help="dense: 0 fused, 1 two-pass, 2 Algorithm 1, 3 register-resident "
+                         "(default: 3 for cfg1, 0 otherwise)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--profile-reps", type=int, default=50)
     args = ap.parse_args()
@@ -292,6 +302,8 @@ def main() -> int:
         return 2
     import torch
     torch.cuda.set_device(0)
+    if args.flow is None:
+        args.flow = 3 if args.workload == "cfg1" and args.n in (None, 512) else 0
     if args.workload == "cfg4":
         out = bench_log(args)
     elif args.workload == "cfg5":

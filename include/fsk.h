@@ -61,7 +61,7 @@ typedef enum {
 
 typedef enum { FSK_F32 = 0, FSK_F64 = 1 } fsk_dtype;
 
-/* How one dense iteration moves through K.  All three produce the iterates of
+/* How one dense iteration moves through K.  All produce the iterates of
  * Algorithm 1; they differ in memory traffic and in summation order. */
 typedef enum {
   FSK_FLOW_FUSED = 0,    /* one pass over K per iteration: a workgroup keeps a row strip in
@@ -71,8 +71,16 @@ typedef enum {
                             row slab yields its own contribution s^(j) = K_{I_j,:}^T u_{I_j}
                             (what a worker holding only its rows can form).                 */
   FSK_FLOW_TWO_PASS = 1, /* q = K v over all rows, then r = K^T u over all rows (two passes)  */
-  FSK_FLOW_PAPER = 2     /* Algorithm 1 as printed: block j forms u_{I_j} from its row slab,
+  FSK_FLOW_PAPER = 2,    /* Algorithm 1 as printed: block j forms u_{I_j} from its row slab,
                             then r_{I_j} = (K_{:,I_j})^T u from its column slab              */
+  FSK_FLOW_RESIDENT = 3  /* small K only (n <= 1024 in fp32, n <= 512 in fp64): a
+                            persistent grid of 8-32 workgroups holds K in registers and runs
+                            all the iterations between two polls in ONE launch, exchanging the
+                            workgroups' partial column sums across a grid-wide barrier.
+                            opts->c is accepted and has no effect on the arithmetic (the row
+                            blocks are the workgroups').  FSK_EUNSUPPORTED for a larger K or
+                            geometric damping.  If the barrier sees no progress for about a
+                            second the call writes NaN into u and v instead of hanging.      */
 } fsk_flow;
 
 typedef enum {

@@ -21,7 +21,7 @@ FSK_OK = 0
 FSK_EINVAL, FSK_EALIGN, FSK_EDIV, FSK_EWORKSPACE, FSK_ENONFINITE, FSK_EHIP, FSK_EUNSUPPORTED = \
     -1, -2, -3, -4, -5, -6, -7
 FSK_F32, FSK_F64 = 0, 1
-FSK_FLOW_FUSED, FSK_FLOW_TWO_PASS, FSK_FLOW_PAPER = 0, 1, 2
+FSK_FLOW_FUSED, FSK_FLOW_TWO_PASS, FSK_FLOW_PAPER, FSK_FLOW_RESIDENT = 0, 1, 2, 3
 FSK_DAMP_NONE, FSK_DAMP_ARITHMETIC, FSK_DAMP_GEOMETRIC = 0, 1, 2
 FSK_MODE_DENSE, FSK_MODE_LOG, FSK_MODE_BATCHED, FSK_MODE_SETUP, FSK_MODE_PLAN = 0, 1, 2, 3, 4
 FSK_MODE_RADIUS = 5

@@ -44,7 +44,7 @@ static int check_common(const fsk_opts* o) {
   if (o->max_iters < 0) return set_error(FSK_EINVAL, "max_iters = %d must be >= 0", o->max_iters);
   if (o->dtype != FSK_F32 && o->dtype != FSK_F64)
     return set_error(FSK_EINVAL, "unknown dtype %d", o->dtype);
-  if (o->flow < FSK_FLOW_FUSED || o->flow > FSK_FLOW_PAPER)
+  if (o->flow < FSK_FLOW_FUSED || o->flow > FSK_FLOW_RESIDENT)
     return set_error(FSK_EINVAL, "unknown flow %d", o->flow);
   if (o->damping < FSK_DAMP_NONE || o->damping > FSK_DAMP_GEOMETRIC)
     return set_error(FSK_EINVAL, "unknown damping %d", o->damping);
@@ -78,7 +78,7 @@ static int check_vec(const char* name, const void* p, bool need16) {
 struct DenseWs {
   int64_t ld_ws;        // elements per partial row
   size_t partial_rows;  // rows the partial area holds
-  size_t partial_off, vec_off, scalar_off, total;
+  size_t partial_off, vec_off, scalar_off, resident_off, total;
 };
 
 static DenseWs dense_ws(const fsk_opts* o) {
@@ -95,7 +95,8 @@ static DenseWs dense_ws(const fsk_opts* o) {
   w.partial_off = 0;
   w.vec_off = align_up(rows * (size_t)w.ld_ws * s, 256);
   w.scalar_off = w.vec_off + align_up((size_t)o->n * s, 256);
-  w.total = w.scalar_off + 256;
+  w.resident_off = w.scalar_off + 256;
+  w.total = w.resident_off + (o->flow == FSK_FLOW_RESIDENT ? resident_workspace_bytes(o->dtype, o->n) : 0);
   return w;
 }
 
@@ -236,6 +237,21 @@ static int dense_error(const fsk_opts* o, const DenseWs& w, const void* K, int64
   return FSK_OK;
 }
 
+// Polls a waiter of the register-resident flow's grid barrier makes before it gives up (each
+// poll is an atomic load plus a short sleep: of the order of a second in all).
+constexpr unsigned kResidentSpinLimit = 4000000u;
+
+static int check_resident(const fsk_opts* o) {
+  if (o->damping == FSK_DAMP_GEOMETRIC)
+    return set_error(FSK_EUNSUPPORTED, "the register-resident flow carries the arithmetic relaxation only");
+  if (!resident_plan(o->dtype, o->n).ok)
+    return set_error(FSK_EUNSUPPORTED, "n = %d: K does not fit the registers of the resident grid", o->n);
+  return FSK_OK;
+}
+static double resident_eta(const fsk_opts* o) {
+  return o->damping == FSK_DAMP_ARITHMETIC ? o->eta : 1.0;
+}
+
 // Algorithm 1 on validated arguments: opts->max_iters iterations, or until a poll finds the
 // marginal error below opts->tol.
 static int dense_solve(const fsk_opts* opts, const DenseWs& w, const void* K, int64_t ldK,
@@ -243,10 +259,22 @@ static int dense_solve(const fsk_opts* opts, const DenseWs& w, const void* K, in
                        int32_t* iters_done, double* err, hipStream_t st) {
   int done = 0;
   double e = NAN;
-  for (int it = 0; it < opts->max_iters; ++it) {
-    FSK_TRY(dense_iteration(opts, w, (const char*)K, ldK, (const char*)a, (const char*)b, (char*)u,
-                            (char*)v, workspace, st));
-    done = it + 1;
+  const bool resident = opts->flow == FSK_FLOW_RESIDENT;
+  if (resident) FSK_TRY(check_resident(opts));
+  for (int it = 0; it < opts->max_iters;) {
+    if (resident) {  // all the iterations up to the next poll in one launch
+      int chunk = opts->max_iters - it;
+      if (opts->tol > 0.0 && opts->check_every - it % opts->check_every < chunk)
+        chunk = opts->check_every - it % opts->check_every;
+      FSK_TRY(launch_resident(opts->dtype, K, ldK, opts->n, chunk, a, b, u, v,
+                              workspace + w.resident_off, resident_eta(opts), kResidentSpinLimit, st));
+      it += chunk;
+    } else {
+      FSK_TRY(dense_iteration(opts, w, (const char*)K, ldK, (const char*)a, (const char*)b, (char*)u,
+                              (char*)v, workspace, st));
+      ++it;
+    }
+    done = it;
     if (opts->tol > 0.0 && (done % opts->check_every == 0 || done == opts->max_iters)) {
       FSK_TRY(dense_error(opts, w, K, ldK, a, u, v, workspace, &e, st));
       if (!std::isfinite(e)) {
@@ -302,6 +330,24 @@ int fsk_dense_profile(const fsk_opts* opts, const void* K, int64_t ldK, const vo
   double t_stream = 0.0, t_other = 0.0;
   int32_t launches = 0;
   int rc = FSK_OK;
+  if (opts->flow == FSK_FLOW_RESIDENT) {  // one launch runs all `reps` iterations
+    rc = check_resident(opts);
+    if (rc == FSK_OK && hipEventRecord(ev[0], st) != hipSuccess) rc = set_error(FSK_EHIP, "hipEventRecord failed");
+    if (rc == FSK_OK)
+      rc = launch_resident(opts->dtype, K, ldK, opts->n, reps, a, b, u, v,
+                           (char*)workspace + w.resident_off, resident_eta(opts), kResidentSpinLimit, st);
+    if (rc == FSK_OK && (hipEventRecord(ev[1], st) != hipSuccess || hipEventSynchronize(ev[1]) != hipSuccess))
+      rc = set_error(FSK_EHIP, "event timing of the resident launch failed");
+    float ms = 0.f;
+    if (rc == FSK_OK && hipEventElapsedTime(&ms, ev[0], ev[1]) != hipSuccess)
+      rc = set_error(FSK_EHIP, "hipEventElapsedTime failed");
+    for (int k = 0; k < 3; ++k) (void)hipEventDestroy(ev[k]);
+    if (rc != FSK_OK) return rc;
+    if (stream_ms) *stream_ms = ms / reps;
+    if (other_ms) *other_ms = 0.0;
+    if (stream_launches) *stream_launches = 1;
+    return FSK_OK;
+  }
   for (int it = 0; it < reps && rc == FSK_OK; ++it) {
     rc = dense_iteration(opts, w, (const char*)K, ldK, (const char*)a, (const char*)b, (char*)u,
                          (char*)v, (char*)workspace, st, ev, &launches);

@@ -61,11 +61,96 @@ __device__ __forceinline__ void store_pack_stream(T* p, const Pack<T>& v) {
 
 // Butterfly sum over the 64 lanes; every lane ends with the same total and the
 // order of additions is the same in every launch.
+// ---- lane exchanges on the vector ALU (no LDS crossbar): gfx950's v_permlane32_swap and
+// v_permlane16_swap across halves / rows of a wave, DPP controls inside a row of 16 lanes.
+// Measured layouts: permlane32_swap(a, b) returns {a with lanes 32-63 replaced by b's lanes 0-31,
+// b with lanes 0-31 replaced by a's lanes 32-63}; permlane16_swap does the same per pair of rows;
+// row_ror:8, row_half_mirror, quad_perm [3,2,1,0] and [1,0,3,2] read lane l ^ 8, ^ 7, ^ 3, ^ 1.
+typedef unsigned fsk_uint2 __attribute__((ext_vector_type(2)));
+template <typename T>
+struct LaneWords {
+  static constexpr int N = sizeof(T) / 4;
+  unsigned w[N];
+  __device__ __forceinline__ explicit LaneWords(T x) { __builtin_memcpy(w, &x, sizeof(T)); }
+  __device__ __forceinline__ T value() const { T x; __builtin_memcpy(&x, w, sizeof(T)); return x; }
+};
+
+// a <- {a on the lower class, b of the partner on the upper class}, b <- the converse, for the
+// lane pairing l <-> l ^ 32 (HALF = 32) or l ^ 16 (HALF = 16); then a + b is, on the lower class,
+// the pair's sum of a and, on the upper class, the pair's sum of b.
+template <int HALF, typename T>
+__device__ __forceinline__ T pair_sum_swap(T a, T b) {
+  LaneWords<T> x(a), y(b);
+#pragma unroll
+  for (int i = 0; i < LaneWords<T>::N; ++i) {
+    const fsk_uint2 r = HALF == 32 ? __builtin_amdgcn_permlane32_swap(x.w[i], y.w[i], false, false)
+                                   : __builtin_amdgcn_permlane16_swap(x.w[i], y.w[i], false, false);
+    x.w[i] = r[0];
+    y.w[i] = r[1];
+  }
+  return x.value() + y.value();
+}
+
+// The value of lane l ^ MASK for MASK in {8, 7, 3, 1} (DPP inside a row of 16 lanes).
+template <int MASK, typename T>
+__device__ __forceinline__ T lane_xor_dpp(T v) {
+  constexpr int ctrl = MASK == 8 ? 0x128 : MASK == 7 ? 0x141 : MASK == 3 ? 0x1B : 0xB1;
+  static_assert(MASK == 8 || MASK == 7 || MASK == 3 || MASK == 1, "no DPP control for this mask");
+  LaneWords<T> x(v);
+#pragma unroll
+  for (int i = 0; i < LaneWords<T>::N; ++i)
+    x.w[i] = (unsigned)__builtin_amdgcn_update_dpp(0, (int)x.w[i], ctrl, 0xf, 0xf, false);
+  return x.value();
+}
+
+// All-lanes sum of a wave: the pairings ^32, ^16, ^8, ^7, ^3, ^1 span the 64 lanes; every
+// lane ends with the same value, formed in the same order in every launch.
 template <typename T>
 __device__ __forceinline__ T wave_sum(T x) {
-#pragma unroll
-  for (int o = 32; o > 0; o >>= 1) x += __shfl_xor(x, o, kWave);
+  x = pair_sum_swap<32>(x, x);
+  x = pair_sum_swap<16>(x, x);
+  x += lane_xor_dpp<8>(x);
+  x += lane_xor_dpp<7>(x);
+  x += lane_xor_dpp<3>(x);
+  x += lane_xor_dpp<1>(x);
   return x;
+}
+
+// Sums RPT (8 or 16) values per lane over the wave with RPT - 1 + log2(64 / RPT) exchanges
+// instead of 6 RPT: each of the first log2(RPT) steps pairs the lanes by one lane bit (5, 4,
+// 3, 2 in turn); the lane whose bit is clear completes the lower half of its values with the
+// partner's, the other lane the upper half.  On return val[0] of lane l is the wave's sum of
+// value number `which`, shared by the 64 / RPT lanes that differ in the low lane bits only.
+template <typename T, int RPT>
+__device__ __forceinline__ int wave_sum_rows(T (&val)[RPT], int lane) {
+  static_assert(RPT == 8 || RPT == 16, "8 or 16 values per lane");
+#pragma unroll
+  for (int i = 0; i < RPT / 2; ++i) val[i] = pair_sum_swap<32>(val[i], val[i + RPT / 2]);
+#pragma unroll
+  for (int i = 0; i < RPT / 4; ++i) val[i] = pair_sum_swap<16>(val[i], val[i + RPT / 4]);
+  int which = ((lane >> 5) & 1) * (RPT / 2) + ((lane >> 4) & 1) * (RPT / 4);
+  {
+    const bool upper = (lane & 8) != 0;
+#pragma unroll
+    for (int i = 0; i < RPT / 8; ++i) {
+      const T send = upper ? val[i] : val[i + RPT / 8];
+      const T keep = upper ? val[i + RPT / 8] : val[i];
+      val[i] = keep + lane_xor_dpp<8>(send);
+    }
+    which += upper ? RPT / 8 : 0;
+  }
+  if (RPT == 16) {
+    const bool upper = (lane & 4) != 0;
+    const T send = upper ? val[0] : val[1];
+    const T keep = upper ? val[1] : val[0];
+    val[0] = keep + lane_xor_dpp<7>(send);
+    which += upper ? 1 : 0;
+  } else {
+    val[0] += lane_xor_dpp<7>(val[0]);
+  }
+  val[0] += lane_xor_dpp<3>(val[0]);
+  val[0] += lane_xor_dpp<1>(val[0]);
+  return which;
 }
 
 template <typename T>

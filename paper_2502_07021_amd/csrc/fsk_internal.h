@@ -119,6 +119,24 @@ int run_sinkhorn_log_points(const fsk_opts* o, const void* x, const void* y, int
                             size_t ws_bytes, int32_t* iters_done, double* err_out,
                             hipStream_t st);
 
+// ------------------------------------------------------------------ register-resident flow
+struct ResidentPlan {
+  bool ok;          // false: K does not fit the registers of 32 workgroups
+  int wgs;          // workgroups of the persistent grid
+  int rows_per_wg;  // rows of K a workgroup owns
+  int p_pad;        // threads per row subgroup: 16-byte packs per row rounded up to whole waves
+  int rpt;          // packs per thread the kernel variant holds (8 or 16)
+  int64_t ld_ws;    // elements per partial row
+};
+ResidentPlan resident_plan(int dtype, int n);
+size_t resident_workspace_bytes(int dtype, int n);
+// `iters` iterations of Algorithm 1 (arithmetic relaxation if eta < 1) in one launch; u, v IN/OUT.
+// `workspace` must hold resident_workspace_bytes().  A grid barrier that sees no progress for
+// spin_limit polls makes the call write NaN results instead of hanging.
+int launch_resident(int dtype, const void* K, int64_t ld, int n, int iters, const void* a,
+                    const void* b, void* u, void* v, void* workspace, double eta,
+                    unsigned spin_limit, hipStream_t st);
+
 // ------------------------------------------------------------------ multitarget path
 size_t batched_workspace_bytes(int n, int m);
 // `dp` (may be null): release U after every U-update and V after every V-update.

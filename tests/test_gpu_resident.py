@@ -1,0 +1,79 @@
+"""GPU parity of the register-resident flow (K held in registers by a persistent grid, one
+launch for many iterations) against the oracle and the streaming flows."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2502_07021_amd import api, workloads
+from gpu_util import TOL, dev, relerr, run_dense
+
+pytestmark = pytest.mark.gpu
+
+RES = api.FSK_FLOW_RESIDENT
+
+
+def _kernel(orc, cfg, n, dtype):
+    w = workloads.make(cfg, n=n)
+    build = orc.gibbs_from_points_f32 if dtype == np.float32 else orc.gibbs_from_points
+    K, _ = build(w.x, w.y, w.eps, w.normalise_by_max)
+    return w, np.ascontiguousarray(K.astype(dtype))
+
+
+@pytest.mark.parametrize("cfg,dtype,n,iters", [
+    (1, np.float64, 512, 200),       # configuration 1 at full size
+    (1, np.float64, 509, 40), (1, np.float64, 130, 40), (1, np.float64, 5, 12),
+    (2, np.float32, 1024, 60), (2, np.float32, 1001, 60), (2, np.float32, 257, 60),
+    (2, np.float32, 64, 30), (2, np.float32, 3, 10), (2, np.float32, 1, 3),
+])
+def test_resident_matches_oracle(orc, cfg, dtype, n, iters):
+    w, K = _kernel(orc, cfg, n, dtype)
+    a = w.a.astype(dtype); b = w.b.astype(dtype)
+    uo, vo = orc.sinkhorn_dense(K, a, b, iters)
+    u, v, done, _ = run_dense(K, a, b, iters, flow=RES)
+    tol = TOL[np.dtype(dtype)]
+    assert done == iters
+    assert relerr(u, uo) <= tol and relerr(v, vo) <= tol
+
+
+def test_resident_resume_blocks_damping_and_other_flows(orc):
+    w, K = _kernel(orc, 2, 1000, np.float32)
+    u, v, _, _ = run_dense(K, w.a, w.b, 50, flow=RES)
+    # resume: 20 + 30 iterations equal 50 bitwise; the block count does not enter the arithmetic
+    u1, v1, _, _ = run_dense(K, w.a, w.b, 20, flow=RES)
+    u2, v2, _, _ = run_dense(K, w.a, w.b, 30, flow=RES, u0=u1, v0=v1)
+    assert np.array_equal(u2, u) and np.array_equal(v2, v)
+    u8, v8, _, _ = run_dense(K, w.a, w.b, 50, flow=RES, c=8)
+    assert np.array_equal(u8, u) and np.array_equal(v8, v)
+    # the streaming flows give the same iterates to rounding
+    for flow in (api.FSK_FLOW_FUSED, api.FSK_FLOW_TWO_PASS):
+        uf, vf, _, _ = run_dense(K, w.a, w.b, 50, flow=flow)
+        assert relerr(u, uf) <= 1e-5 and relerr(v, vf) <= 1e-5
+    # arithmetic relaxation (Sec. 3.3)
+    uo, vo = orc.sinkhorn_dense_damped(K, w.a, w.b, 40, 0.6, False)
+    ud, vd, _, _ = run_dense(K, w.a, w.b, 40, flow=RES, damping=api.FSK_DAMP_ARITHMETIC, eta=0.6)
+    assert relerr(ud, uo) <= 1e-4 and relerr(vd, vo) <= 1e-4
+
+
+def test_resident_tolerance_mode(orc):
+    w, K = _kernel(orc, 1, 256, np.float64)
+    for check_every in (1, 7, 25):
+        uo, vo, done_o, err_o = orc.sinkhorn_dense_tol(K, w.a, w.b, 400, 1e-6, check_every)
+        u, v, done, err = run_dense(K, w.a, w.b, 400, flow=RES, tol=1e-6, check_every=check_every)
+        assert done == done_o and done < 400
+        assert err == pytest.approx(err_o, rel=1e-6) and err < 1e-6
+        assert relerr(u, uo) <= 1e-10 and relerr(v, vo) <= 1e-10
+
+
+def test_resident_refuses_what_it_cannot_hold():
+    for n, dtype in ((1028, torch.float32), (516, torch.float64)):
+        opts = api.make_opts(n, dtype, max_iters=1, flow=RES)
+        K = torch.ones(n, n, dtype=dtype, device="cuda"); x = torch.ones(n, dtype=dtype, device="cuda")
+        ws = torch.empty(1 << 24, dtype=torch.uint8, device="cuda")
+        with pytest.raises(api.FskError) as e:
+            api.fsk_sinkhorn_dense(opts, K, x, x, x.clone(), x.clone(), ws)
+        assert e.value.status == api.FSK_EUNSUPPORTED
+    opts = api.make_opts(256, torch.float32, max_iters=1, flow=RES, damping=api.FSK_DAMP_GEOMETRIC, eta=0.5)
+    K = torch.ones(256, 256, device="cuda"); x = torch.ones(256, device="cuda")
+    with pytest.raises(api.FskError) as e:
+        api.fsk_sinkhorn_dense(opts, K, x, x, x.clone(), x.clone(), api.alloc_workspace(opts))
+    assert e.value.status == api.FSK_EUNSUPPORTED
