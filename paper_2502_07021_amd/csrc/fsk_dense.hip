@@ -155,14 +155,17 @@ int launch_colpartial(int dtype, const void* K, int64_t ld, int n, int rows, int
 }
 
 // ======================================================= partial sums -> result
-// The partial rows are split into G contiguous groups (G = 4..32, a function of the number
-// of partials alone), each summed in increasing index, then the G group sums are added in
-// group order: the result does not depend on the column range, the alignment or the grid.
-// A workgroup is G x Q threads (Q = 256 / G); thread (g, q) sums group g for one 16-byte
-// pack of columns, so a group row is read as Q contiguous packs and every thread has its
-// whole group in flight at once.
-__host__ __device__ inline int colreduce_groups(int n_partials) {
-  return n_partials >= 128 ? 32 : n_partials >= 32 ? 16 : n_partials >= 16 ? 8 : 4;
+// The partial rows are split into G contiguous groups (G = 4..32), each summed in increasing
+// index, then the G group sums are added in group order.  G is a function of the number of
+// partials and of the row pitch of the partial area alone, so the result does not depend on
+// the column range, the alignment or the grid.  A workgroup is G x Q threads (Q = 256 / G);
+// thread (g, q) sums group g for one 16-byte pack of columns, so a group row is read as Q
+// contiguous packs and every thread has its whole group in flight at once.  Wide problems
+// get few groups (long contiguous reads), narrow ones many (enough threads).
+__host__ __device__ inline int colreduce_groups(int n_partials, int64_t pitch_packs) {
+  int g = 4;
+  while (g < 32 && pitch_packs * g < 65536 && 4 * g <= n_partials) g *= 2;
+  return g;
 }
 
 template <typename T>
@@ -171,7 +174,7 @@ __global__ __launch_bounds__(256) void colreduce_kernel(const T* __restrict__ pa
                                                         int c1, const T* marg, const T* old, T* out,
                                                         int epi, T eta, int aligned) {
   constexpr int W = Pack<T>::W;
-  const int G = colreduce_groups(n_partials), Q = 256 / G;
+  const int G = colreduce_groups(n_partials, ld_ws / W), Q = 256 / G;
   const int q = threadIdx.x % Q, g = threadIdx.x / Q;
   const int j = c0 + (blockIdx.x * Q + q) * W;  // first column of this thread's pack
   const int per = (n_partials + G - 1) / G;
@@ -227,7 +230,7 @@ static int colreduce_typed(const void* partial, int64_t ld_ws, int n_partials, i
                            hipStream_t stream) {
   if (c1 <= c0) return FSK_OK;
   constexpr int W = Pack<T>::W;
-  const int cols_per_wg = 256 / colreduce_groups(n_partials) * W;
+  const int cols_per_wg = 256 / colreduce_groups(n_partials, ld_ws / W) * W;
   const int aligned = ld_ws % W == 0 && ((uintptr_t)((const T*)partial + c0)) % 16 == 0;
   dim3 grid((c1 - c0 + cols_per_wg - 1) / cols_per_wg), block(256);
   hipLaunchKernelGGL((colreduce_kernel<T>), grid, block, 0, stream, (const T*)partial, ld_ws,
