@@ -143,6 +143,13 @@ int fsk_sinkhorn_dense(const fsk_opts* opts, const void* K, int64_t ldK, const v
                        const void* b, void* u, void* v, void* workspace, size_t ws_bytes,
                        int32_t* iters_done, double* err, void* stream);
 
+/* Poll budget of the grid barrier in FSK_FLOW_RESIDENT (process-wide; default 4000000, about a
+ * second).  A waiter that exhausts it marks the launch failed: u and v come back NaN (and a
+ * tolerance-mode call returns FSK_ENONFINITE) instead of the kernel waiting for ever.  For
+ * callers that want a tighter bound, and for testing the failure path (0 = give up at the first
+ * unsuccessful poll). */
+void fsk_set_barrier_poll_limit(uint32_t polls);
+
 /* Row and column marginals of P = diag(u) K diag(v) (device outputs of n entries each; either
  * may be NULL), and optionally ||P1 - a||_1 (err_l1, host; non-NULL makes the call synchronise). */
 int fsk_marginals(const fsk_opts* opts, const void* K, int64_t ldK, const void* a, const void* u,

@@ -33,7 +33,7 @@ EXPORTS = (
     "fsk_dense_profile", "fsk_bench_copy", "fsk_bench_read", "fsk_async_workspace_bytes",
     "fsk_sinkhorn_async_emulated", "fsk_plan_objective", "fsk_kernel_from_cost_lambda",
     "fsk_radius_search", "fsk_grid_workspace_bytes", "fsk_sinkhorn_grid", "fsk_dp_release",
-    "fsk_sinkhorn_batched_dp", "fsk_rdp_epsilon",
+    "fsk_sinkhorn_batched_dp", "fsk_rdp_epsilon", "fsk_set_barrier_poll_limit",
 )
 
 
@@ -240,6 +240,10 @@ def fsk_rdp_epsilon(clip, sigma, releases, delta, orders):
                                  ctypes.c_double(delta), arr, ctypes.c_int32(len(orders)),
                                  ctypes.byref(eps), ctypes.byref(order)))
     return float(eps.value), float(order.value)
+
+
+def fsk_set_barrier_poll_limit(polls: int) -> None:
+    lib().fsk_set_barrier_poll_limit(ctypes.c_uint32(polls))
 
 
 def fsk_grid_workspace_bytes(opts, p_r: int, p_c: int) -> int:

@@ -9,6 +9,8 @@
 #include "fsk_device.h"
 #include "fsk_internal.h"
 
+#include <atomic>
+
 namespace fsk {
 
 static thread_local char g_err[512] = "";
@@ -238,8 +240,9 @@ static int dense_error(const fsk_opts* o, const DenseWs& w, const void* K, int64
 }
 
 // Polls a waiter of the register-resident flow's grid barrier makes before it gives up (each
-// poll is an atomic load plus a short sleep: of the order of a second in all).
-constexpr unsigned kResidentSpinLimit = 4000000u;
+// poll is an atomic load plus a short sleep: of the order of a second in all by default).
+static std::atomic<unsigned> g_resident_spin_limit{4000000u};
+#define kResidentSpinLimit (g_resident_spin_limit.load(std::memory_order_relaxed))
 
 static int check_resident(const fsk_opts* o) {
   if (o->damping == FSK_DAMP_GEOMETRIC)
@@ -288,6 +291,10 @@ static int dense_solve(const fsk_opts* opts, const DenseWs& w, const void* K, in
   if (iters_done) *iters_done = done;
   if (err) *err = e;
   return FSK_OK;
+}
+
+void fsk_set_barrier_poll_limit(uint32_t polls) {
+  g_resident_spin_limit.store(polls, std::memory_order_relaxed);
 }
 
 int fsk_sinkhorn_dense(const fsk_opts* opts, const void* K, int64_t ldK, const void* a,
@@ -381,6 +388,7 @@ int fsk_marginals(const fsk_opts* opts, const void* K, int64_t ldK, const void* 
   const DenseWs w = dense_ws(opts);
   if (!workspace || ws_bytes < w.total)
     return set_error(FSK_EWORKSPACE, "marginals need %zu workspace bytes, got %zu", w.total, ws_bytes);
+  if (!aligned16(workspace)) return set_error(FSK_EALIGN, "workspace is not 16-byte aligned");
   hipStream_t st = (hipStream_t)stream;
   const int n = opts->n, dt = opts->dtype;
   char* ws = (char*)workspace;
@@ -683,6 +691,7 @@ int fsk_block_colpartial(const fsk_opts* opts, const void* K_slab, int64_t ldK, 
   const DenseWs w = dense_ws(opts);
   if (!workspace || ws_bytes < w.total)
     return set_error(FSK_EWORKSPACE, "block call needs %zu workspace bytes, got %zu", w.total, ws_bytes);
+  if (!aligned16(workspace)) return set_error(FSK_EALIGN, "workspace is not 16-byte aligned");
   hipStream_t st = (hipStream_t)stream;
   char* ws = (char*)workspace;
   FSK_TRY(launch_colpartial(opts->dtype, K_slab, ldK, opts->n, rows, 0, opts->n, u_slab,
@@ -711,6 +720,7 @@ int fsk_block_fused(const fsk_opts* opts, const void* K_slab, int64_t ldK, int32
   const size_t need = (size_t)plan.wgs * (size_t)ld_ws * s;
   if (!workspace || ws_bytes < need)
     return set_error(FSK_EWORKSPACE, "fused block call needs %zu workspace bytes, got %zu", need, ws_bytes);
+  if (!aligned16(workspace)) return set_error(FSK_EALIGN, "workspace is not 16-byte aligned");
   hipStream_t st = (hipStream_t)stream;
   FSK_TRY(launch_fused(opts->dtype, plan, K_slab, ldK, opts->n, rows, 1, a_slab, v_full, u_slab,
                        u_slab, workspace, ld_ws, epi_of(opts), opts->eta, st));

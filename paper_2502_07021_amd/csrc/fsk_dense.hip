@@ -443,11 +443,15 @@ static int fused_typed(const FusedPlan& plan, const void* K, int64_t ld, int n, 
                        void* partial, int64_t ld_ws, double eta, hipStream_t stream) {
   constexpr int R = fused_rows_per_group(VPT);
   auto kern = fused_kernel<T, VPT, R, EXACT>;
-  static bool attr_set = false;  // benign race: setting it twice is harmless
-  if (!attr_set) {
+  // the attribute belongs to the kernel's code object on ONE device: kept per device
+  // (benign race: setting it twice is harmless)
+  static bool attr_set[64] = {false};
+  int dev = 0;
+  FSK_HIP(hipGetDevice(&dev));
+  if (dev < 0 || dev >= 64 || !attr_set[dev]) {
     FSK_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024));
-    attr_set = true;
+    if (dev >= 0 && dev < 64) attr_set[dev] = true;
   }
   const int teams = fused_teams(plan, c);
   dim3 grid(plan.wgs * teams), block(512);

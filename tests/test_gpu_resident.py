@@ -77,3 +77,22 @@ def test_resident_refuses_what_it_cannot_hold():
     with pytest.raises(api.FskError) as e:
         api.fsk_sinkhorn_dense(opts, K, x, x, x.clone(), x.clone(), api.alloc_workspace(opts))
     assert e.value.status == api.FSK_EUNSUPPORTED
+
+
+def test_resident_barrier_gives_up_instead_of_hanging(orc):
+    """The host shrinks the barrier's poll budget to nothing: waiters give up at once, every
+    kernel still ends normally, and the failure is loud (NaN results, FSK_ENONFINITE in
+    tolerance mode).  With the budget restored the same call works again."""
+    w, K = _kernel(orc, 1, 512, np.float64)
+    try:
+        api.fsk_set_barrier_poll_limit(0)
+        u, v, _, _ = run_dense(K, w.a, w.b, 50, flow=RES)
+        assert np.isnan(u).any() and np.isnan(v).any()
+        with pytest.raises(api.FskError) as e:
+            run_dense(K, w.a, w.b, 50, flow=RES, tol=1e-9, check_every=10)
+        assert e.value.status == api.FSK_ENONFINITE
+    finally:
+        api.fsk_set_barrier_poll_limit(4000000)
+    uo, vo = orc.sinkhorn_dense(K, w.a, w.b, 50)
+    u, v, _, _ = run_dense(K, w.a, w.b, 50, flow=RES)
+    assert relerr(u, uo) <= 1e-10 and relerr(v, vo) <= 1e-10
