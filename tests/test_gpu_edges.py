@@ -1,0 +1,85 @@
+"""Edge cases of the GPU entry points: zero iterations, the degenerate inputs the method has
+(an underflowed kernel row, which makes the scalings non-finite), and the sizes at which the
+fused kernel hands over to the two-pass kernels."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2502_07021_amd import api, workloads
+from gpu_util import dev, relerr, run_dense
+
+pytestmark = pytest.mark.gpu
+
+
+def test_zero_iterations_leave_the_state_alone(orc):
+    n, m = 300, 5
+    w = workloads.make(2, n=n)
+    K, _ = orc.gibbs_from_points_f32(w.x, w.y, w.eps, True)
+    rng = np.random.default_rng(0)
+    u0 = rng.uniform(0.5, 2.0, n).astype(np.float32); v0 = rng.uniform(0.5, 2.0, n).astype(np.float32)
+    for flow in (api.FSK_FLOW_FUSED, api.FSK_FLOW_TWO_PASS, api.FSK_FLOW_PAPER, api.FSK_FLOW_RESIDENT):
+        u, v, done, _ = run_dense(K, w.a, w.b, 0, flow=flow, u0=u0, v0=v0)
+        assert done == 0 and np.array_equal(u, u0) and np.array_equal(v, v0)
+    # log domain
+    w4 = workloads.make(4, n=n)
+    opts = api.make_opts(n, torch.float32, max_iters=0)
+    ws = api.alloc_workspace(opts, api.FSK_MODE_LOG, w4.d)
+    f = dev(u0.copy()); g = dev(v0.copy())
+    done, _ = api.fsk_sinkhorn_log_points(opts, dev(w4.x), dev(w4.y), w4.eps, dev(w4.a), dev(w4.b), f, g, ws)
+    torch.cuda.synchronize()
+    assert done == 0 and np.array_equal(f.cpu().numpy(), u0) and np.array_equal(g.cpu().numpy(), v0)
+    # multitarget
+    w5 = workloads.make(5, n=n, m=m)
+    opts = api.make_opts(n, torch.float32, m=m, max_iters=0)
+    ws = api.alloc_workspace(opts, api.FSK_MODE_BATCHED)
+    U0 = rng.uniform(0.5, 2.0, (n, m)).astype(np.float32)
+    U = dev(U0.copy()); V = dev(U0.copy())
+    pad = torch.zeros(n, 304, device="cuda"); pad[:, :n] = dev(K)
+    api.fsk_sinkhorn_batched(opts, pad[:, :n], dev(w5.a), dev(w5.b), U, V, ws)
+    torch.cuda.synchronize()
+    assert np.array_equal(U.cpu().numpy(), U0) and np.array_equal(V.cpu().numpy(), U0)
+
+
+@pytest.mark.parametrize("flow", [api.FSK_FLOW_FUSED, api.FSK_FLOW_TWO_PASS, api.FSK_FLOW_RESIDENT])
+def test_underflowed_kernel_row_is_reported(orc, flow):
+    """A row of K that underflowed to zero (the paper assumes K > 0) gives q_i = 0 and an
+    infinite scaling: tolerance mode reports it at the first poll instead of iterating on."""
+    n = 256
+    w = workloads.make(2, n=n)
+    K, _ = orc.gibbs_from_points_f32(w.x, w.y, w.eps, True)
+    K = K.copy(); K[17, :] = 0.0
+    with pytest.raises(api.FskError) as e:
+        run_dense(K, w.a, w.b, 20, flow=flow, tol=1e-6, check_every=5)
+    assert e.value.status == api.FSK_ENONFINITE
+    # fixed-iteration mode does not poll: the non-finite values are simply there to see
+    u, v, _, _ = run_dense(K, w.a, w.b, 3, flow=flow)
+    assert not np.isfinite(u[17]) or not np.isfinite(v).all()
+
+
+def test_above_the_fused_limit_the_call_falls_back_to_two_passes(orc):
+    """n = 32772 fp32 is four columns beyond what a workgroup of the fused kernel can hold:
+    FSK_FLOW_FUSED then runs the two-pass kernels, bitwise."""
+    w = workloads.make(3, n=32772)
+    n = w.n
+    K, _ = orc.gibbs_from_points_f32(w.x, w.y, w.eps, True)
+    Kd = dev(K); a = dev(w.a); b = dev(w.b)
+
+    def run(flow, iters):
+        opts = api.make_opts(n, torch.float32, max_iters=iters, flow=flow)
+        ws = api.alloc_workspace(opts)
+        u = torch.ones(n, device="cuda"); v = torch.ones(n, device="cuda")
+        api.fsk_sinkhorn_dense(opts, Kd, a, b, u, v, ws)
+        torch.cuda.synchronize()
+        return u, v
+
+    uf, vf = run(api.FSK_FLOW_FUSED, 3)
+    ut, vt = run(api.FSK_FLOW_TWO_PASS, 3)
+    assert torch.equal(uf, ut) and torch.equal(vf, vt)
+    uo, vo = orc.sinkhorn_dense(K, w.a, w.b, 3)
+    assert relerr(uf.cpu().numpy(), uo) <= 1e-4 and relerr(vf.cpu().numpy(), vo) <= 1e-4
+    with pytest.raises(api.FskError) as e:          # and the per-worker fused call says so
+        opts = api.make_opts(n, torch.float32, max_iters=1)
+        api.fsk_block_fused(opts, Kd[:4096], 0, a[:4096], torch.ones(n, device="cuda"),
+                            torch.empty(4096, device="cuda"), torch.empty(n, device="cuda"),
+                            torch.empty(1 << 26, dtype=torch.uint8, device="cuda"))
+    assert e.value.status == api.FSK_EUNSUPPORTED
