@@ -104,34 +104,46 @@ int launch_rowpass(int dtype, const void* K, int64_t ld, int n, int rows, const 
 }
 
 // ========================================================== column pass (generic)
-// Grid (column tiles, row strips).  A thread owns one 16-byte pack of columns and
-// adds K[i][cols] * u[i] over the rows of its strip in increasing i; the strip
-// partition depends only on the row count, so a column-restricted launch sums
-// every column exactly like an unrestricted one.
-template <typename T>
+// Grid (column tiles, row strips).  A thread owns PPT 16-byte packs of columns (256 packs
+// apart, so a workgroup reads PPT x 4 KiB contiguous bytes of every row) and adds
+// K[i][cols] * u[i] over the rows of its strip in increasing i; the strip partition depends
+// only on the row count and every column is summed on its own, so a column-restricted launch
+// (and either PPT) sums every column exactly like an unrestricted one.
+template <typename T, int PPT>
 __global__ __launch_bounds__(256) void colpartial_kernel(const T* __restrict__ K, int64_t ld,
                                                          int rows, int vec_lo, int vec_hi,
                                                          const T* __restrict__ u,
                                                          T* __restrict__ partial, int64_t ld_ws) {
   constexpr int W = Pack<T>::W;
-  const int vc = vec_lo + blockIdx.x * 256 + threadIdx.x;
+  const int vc0 = vec_lo + blockIdx.x * 256 * PPT + threadIdx.x;
   const int s = blockIdx.y;
   const int i0 = s * kColStrip;
   const int i1 = i0 + kColStrip < rows ? i0 + kColStrip : rows;
-  if (vc >= vec_hi) return;  // no barrier below
-  Pack<T> acc;
+  if (vc0 >= vec_hi) return;  // no barrier below
+  // packs past the end of the range are clamped to the thread's first pack: read again, not stored
+  int64_t off[PPT];
 #pragma unroll
-  for (int e = 0; e < W; ++e) acc.e[e] = T(0);
-  const T* kp = K + (int64_t)i0 * ld + (int64_t)vc * W;
-#pragma unroll 8
+  for (int k = 0; k < PPT; ++k) off[k] = (int64_t)(vc0 + k * 256 < vec_hi ? vc0 + k * 256 : vc0) * W;
+  Pack<T> acc[PPT];
+#pragma unroll
+  for (int k = 0; k < PPT; ++k)
+#pragma unroll
+    for (int e = 0; e < W; ++e) acc[k].e[e] = T(0);
+  const T* kp = K + (int64_t)i0 * ld;
+#pragma unroll 4
   for (int i = i0; i < i1; ++i) {
     const T ui = u[i];
-    const Pack<T> kk = load_pack_stream(kp);
-    kp += ld;
 #pragma unroll
-    for (int e = 0; e < W; ++e) acc.e[e] = fma(kk.e[e], ui, acc.e[e]);
+    for (int k = 0; k < PPT; ++k) {
+      const Pack<T> kk = load_pack_stream(kp + off[k]);
+#pragma unroll
+      for (int e = 0; e < W; ++e) acc[k].e[e] = fma(kk.e[e], ui, acc[k].e[e]);
+    }
+    kp += ld;
   }
-  store_pack(partial + (int64_t)s * ld_ws + (int64_t)vc * W, acc);
+#pragma unroll
+  for (int k = 0; k < PPT; ++k)
+    if (vc0 + k * 256 < vec_hi) store_pack(partial + (int64_t)s * ld_ws + off[k], acc[k]);
 }
 
 template <typename T>
@@ -141,9 +153,17 @@ static int colpartial_typed(const void* K, int64_t ld, int n, int rows, int c0, 
   if (rows <= 0 || c1 <= c0) return FSK_OK;
   const int vec_lo = c0 / W, vec_hi = (c1 + W - 1) / W;
   (void)n;
-  dim3 grid((vec_hi - vec_lo + 255) / 256, col_strips(rows)), block(256);
-  hipLaunchKernelGGL((colpartial_kernel<T>), grid, block, 0, stream, (const T*)K, ld, rows, vec_lo,
-                     vec_hi, (const T*)u, (T*)partial, ld_ws);
+  const int nvec = vec_hi - vec_lo;
+  dim3 block(256);
+  if (nvec >= 4096) {  // wide: 16 KiB of every row per workgroup (needs several column tiles)
+    dim3 grid((nvec + 1023) / 1024, col_strips(rows));
+    hipLaunchKernelGGL((colpartial_kernel<T, 4>), grid, block, 0, stream, (const T*)K, ld, rows,
+                       vec_lo, vec_hi, (const T*)u, (T*)partial, ld_ws);
+  } else {
+    dim3 grid((nvec + 255) / 256, col_strips(rows));
+    hipLaunchKernelGGL((colpartial_kernel<T, 1>), grid, block, 0, stream, (const T*)K, ld, rows,
+                       vec_lo, vec_hi, (const T*)u, (T*)partial, ld_ws);
+  }
   FSK_LAUNCH_CHECK("colpartial_kernel");
   return FSK_OK;
 }
