@@ -297,6 +297,39 @@ __global__ __launch_bounds__(256) void batched_prod_wide_kernel(const float* __r
     }
   };
 
+  // The MFMAs of chunk `buf` with the loads of chunk cn spread between them: one K load after
+  // every group of 8 MFMAs, one X load after every other group.  A burst of 24 loads at the top
+  // of the chunk holds the wave's (in-order) issue for longer than the matrix pipe has work
+  // queued; spread out, each load issues in the shadow of the MFMAs before it.  The scheduling
+  // barriers pin that order (left alone the scheduler sinks every load to the end of the chunk).
+  auto multiply_prefetch = [&](int buf, const Pack<float>(&ka)[kBtHalf], int cn,
+                               Pack<float>(&kn)[kBtHalf], float(&stn)[kBtStage]) {
+    static_assert(kBtStage * 2 == kBtHalf, "one X load per two k-steps");
+    float b0[kBtHalf], b1[kBtHalf];  // B operands: two k-steps ahead of the MFMAs that use them
+#pragma unroll
+    for (int e = 0; e < 2; ++e) {
+      b0[e] = xs[buf][kBtHalf * h + e][r];
+      b1[e] = xs[buf][kBtHalf * h + e][32 + r];
+    }
+    __builtin_amdgcn_sched_barrier(0);
+    const int first = cn * kBtChunk + kBtHalf * h;
+#pragma unroll
+    for (int e = 0; e < kBtHalf; ++e) {
+#pragma unroll
+      for (int a = 0; a < 4; ++a) {
+        acc[a][0] = mfma32(ka[e].e[a], b0[e], acc[a][0]);
+        acc[a][1] = mfma32(ka[e].e[a], b1[e], acc[a][1]);
+      }
+      if (e + 2 < kBtHalf) {
+        b0[e + 2] = xs[buf][kBtHalf * h + e + 2][r];
+        b1[e + 2] = xs[buf][kBtHalf * h + e + 2][32 + r];
+      }
+      kn[e] = load_pack_stream(kcol + (int64_t)(first + e) * ld);
+      if (e % 2 == 0) stn[e / 2] = xcol[(int64_t)(cn * kBtChunk + sk + 4 * (e / 2)) * m];
+      __builtin_amdgcn_sched_barrier(0);
+    }
+  };
+
   Pack<float> kaA[kBtHalf], kaB[kBtHalf];
   float st[kBtStage];
   if (c0 < full_end) {
@@ -306,26 +339,21 @@ __global__ __launch_bounds__(256) void batched_prod_wide_kernel(const float* __r
   }
   __syncthreads();
   int c = c0;
-  for (; c + 2 <= full_end; c += 2) {
-    load_k(c + 1, kaB);
-    load_x(c + 1, st);
-    // keep the loads above the MFMAs: left alone the scheduler sinks them to the end of
-    // the chunk to shorten register live ranges, which throws the prefetch away
-    __builtin_amdgcn_sched_barrier(0);
-    multiply(0, kaA);
+  for (; c + 2 < full_end; c += 2) {  // chunks c and c + 1 both have a successor to prefetch
+    multiply_prefetch(0, kaA, c + 1, kaB, st);
     store_x(1, st);
     __syncthreads();
-    const bool more = c + 2 < full_end;
-    if (more) {
-      load_k(c + 2, kaA);
-      load_x(c + 2, st);
-    }
-    __builtin_amdgcn_sched_barrier(0);
-    multiply(1, kaB);
-    if (more) store_x(0, st);
+    multiply_prefetch(1, kaB, c + 2, kaA, st);
+    store_x(0, st);
     __syncthreads();
   }
-  if (c < full_end) {
+  if (c + 1 < full_end) {  // two whole chunks left
+    multiply_prefetch(0, kaA, c + 1, kaB, st);
+    store_x(1, st);
+    __syncthreads();
+    multiply(1, kaB);
+    __syncthreads();
+  } else if (c < full_end) {  // one
     multiply(0, kaA);
     __syncthreads();
   }
