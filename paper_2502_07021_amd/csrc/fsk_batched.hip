@@ -298,13 +298,13 @@ __global__ __launch_bounds__(256) void batched_prod_wide_kernel(const float* __r
   };
 
   // The MFMAs of chunk `buf` with the loads of chunk cn spread between them: one K load after
-  // every group of 8 MFMAs, one X load after every other group.  A burst of 24 loads at the top
+  // every group of 8 MFMAs, the X loads after the first eight groups (they are needed first).  A burst of 24 loads at the top
   // of the chunk holds the wave's (in-order) issue for longer than the matrix pipe has work
   // queued; spread out, each load issues in the shadow of the MFMAs before it.  The scheduling
   // barriers pin that order (left alone the scheduler sinks every load to the end of the chunk).
   auto multiply_prefetch = [&](int buf, const Pack<float>(&ka)[kBtHalf], int cn,
                                Pack<float>(&kn)[kBtHalf], float(&stn)[kBtStage]) {
-    static_assert(kBtStage * 2 == kBtHalf, "one X load per two k-steps");
+    static_assert(kBtStage <= kBtHalf, "the X loads ride on the first k-steps");
     float b0[kBtHalf], b1[kBtHalf];  // B operands: two k-steps ahead of the MFMAs that use them
 #pragma unroll
     for (int e = 0; e < 2; ++e) {
@@ -325,7 +325,7 @@ __global__ __launch_bounds__(256) void batched_prod_wide_kernel(const float* __r
         b1[e + 2] = xs[buf][kBtHalf * h + e + 2][32 + r];
       }
       kn[e] = load_pack_stream(kcol + (int64_t)(first + e) * ld);
-      if (e % 2 == 0) stn[e / 2] = xcol[(int64_t)(cn * kBtChunk + sk + 4 * (e / 2)) * m];
+      if (e < kBtStage) stn[e] = xcol[(int64_t)(cn * kBtChunk + sk + 4 * e) * m];  // early: stored at the chunk's end
       __builtin_amdgcn_sched_barrier(0);
     }
   };
