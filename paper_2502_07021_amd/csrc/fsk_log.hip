@@ -180,25 +180,30 @@ __global__ __launch_bounds__(kLogThreads) void log_lse_kernel(const double* __re
     }
   }
 
-  auto chunk = [&](int j0, auto jj_tag) {
+  // The column coordinates come through scalar loads, one whole column ahead of the FMAs
+  // that use them.  Scalar loads complete out of order, so the only wait is "all of them":
+  // the empty asm statement marks the place where the current column must have arrived; the
+  // next column is requested right after it and travels while the current column's FMAs run.
+  // In the main loop (PIPE) that holds across chunks too: the last column of a chunk requests
+  // the first column of the next one (clamped to the last column of the matrix when there is
+  // none: a redundant, in-bounds read).
+  double qbuf[2][DP];
+  double bj[2];
+  auto fetch = [&](int col, int slot) {
+    const double* q = qc + (int64_t)col * DP;
+#pragma unroll
+    for (int k = 0; k < DP; ++k) qbuf[slot][k] = q[k];
+    bj[slot] = beta[col];
+  };
+
+  auto chunk = [&](int j0, auto jj_tag, auto pipe_tag) {
     constexpr int JJ = decltype(jj_tag)::value;
+    constexpr bool PIPE = decltype(pipe_tag)::value;
     static_assert(RI == 2, "fma_rows2 carries exactly two rows per lane");
+    static_assert(!PIPE || JJ % 2 == 0, "a pipelined chunk must hand slot 0 to its successor");
     constexpr int G = DP >= 8 ? 8 : 4;  // coordinates per FMA block
     double zd[RI][JJ];
-    // The column coordinates come through scalar loads, one whole column ahead of the FMAs
-    // that use them.  Scalar loads complete out of order, so the only wait is "all of
-    // them": the empty asm statement marks the place where the current column must have
-    // arrived; the next column is requested right after it and travels while the current
-    // column's FMAs run.
-    double qbuf[2][DP];
-    double bj[2];
-    auto fetch = [&](int t, int slot) {
-      const double* q = qc + (int64_t)(j0 + t) * DP;
-#pragma unroll
-      for (int k = 0; k < DP; ++k) qbuf[slot][k] = q[k];
-      bj[slot] = beta[j0 + t];
-    };
-    fetch(0, 0);
+    if (!PIPE) fetch(j0, 0);
 #pragma unroll
     for (int t = 0; t < JJ; ++t) {
       const int slot = t & 1;
@@ -212,7 +217,12 @@ __global__ __launch_bounds__(kLogThreads) void log_lse_kernel(const double* __re
           asm volatile("" : : "s"(qbuf[slot][0]), "s"(qbuf[slot][1]), "s"(qbuf[slot][2]),
                        "s"(qbuf[slot][3]), "s"(bj[slot]) : "memory");
       }
-      if (t + 1 < JJ) fetch(t + 1, slot ^ 1);
+      if (t + 1 < JJ) {
+        fetch(j0 + t + 1, slot ^ 1);
+      } else if (PIPE) {
+        const int nxt = j0 + JJ < n_cols ? j0 + JJ : n_cols - 1;
+        fetch(nxt, slot ^ 1);
+      }
       double z[RI];
 #pragma unroll
       for (int r = 0; r < RI; ++r) z[r] = bj[slot] - mref[r];
@@ -247,8 +257,9 @@ __global__ __launch_bounds__(kLogThreads) void log_lse_kernel(const double* __re
   };
 
   int j = jb;
-  for (; j + J <= je; j += J) chunk(j, std::integral_constant<int, J>{});
-  for (; j < je; ++j) chunk(j, std::integral_constant<int, 1>{});
+  if (j + J <= je) fetch(j, 0);
+  for (; j + J <= je; j += J) chunk(j, std::integral_constant<int, J>{}, std::true_type{});
+  for (; j < je; ++j) chunk(j, std::integral_constant<int, 1>{}, std::false_type{});
 
 #pragma unroll
   for (int r = 0; r < RI; ++r) {
