@@ -217,15 +217,20 @@ __global__ __launch_bounds__(256) void batched_prod_wide_kernel(const float* __r
                                                                 int64_t ld, int n, int m,
                                                                 const float* __restrict__ X,
                                                                 const float* __restrict__ marg,
-                                                                float* __restrict__ out, int final) {
+                                                                float* __restrict__ out, int final,
+                                                                int slices) {
   __shared__ float xs[2][kBtChunk][kBtCols];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int r = lane & 31, h = lane >> 5;
-  const int o0 = blockIdx.x * kBtWideTile + wave * kBtWideWaveTile;
+  // 1-D grid, slice fastest: workgroups are dealt to the 8 XCDs round-robin, so the workgroups
+  // of one contraction slice -- the ones that read the same rows of X -- meet on the same XCDs
+  // and share those rows in that XCD's L2 instead of every L2 holding all of X.
+  const int slice = blockIdx.x % slices, tile = blockIdx.x / slices;
+  const int o0 = tile * kBtWideTile + wave * kBtWideWaveTile;
 
   const int nchunks = (n + kBtChunk - 1) / kBtChunk;
-  const int per = (nchunks + gridDim.y - 1) / gridDim.y;
-  int c0 = blockIdx.y * per;
+  const int per = (nchunks + slices - 1) / slices;
+  int c0 = slice * per;
   int c1 = c0 + per < nchunks ? c0 + per : nchunks;
   if (c0 > c1) c0 = c1;
   int full_end = n / kBtChunk < c1 ? n / kBtChunk : c1;
@@ -366,7 +371,7 @@ __global__ __launch_bounds__(256) void batched_prod_wide_kernel(const float* __r
     multiply(0, kaA);
   }
 
-  float* dst = final ? out : out + (int64_t)blockIdx.y * n * m;
+  float* dst = final ? out : out + (int64_t)slice * n * m;
 #pragma unroll
   for (int a = 0; a < 4; ++a)
 #pragma unroll
@@ -465,7 +470,7 @@ int run_sinkhorn_batched(const fsk_opts* o, const void* K, int64_t ldK, const vo
   }
   dim3 grid((n + kBtTile - 1) / kBtTile, S), block(256);
   const int SW = batched_splits_wide(n);
-  dim3 gridw((n + kBtWideTile - 1) / kBtWideTile, SW);
+  dim3 gridw(((n + kBtWideTile - 1) / kBtWideTile) * SW);
   const int nm = n * m;
   auto reduce = [&](int slices, const float* marg, float* dst) -> int {
     return launch_colreduce(FSK_F32, part, nm, slices, 0, nm, marg, nullptr, dst, kEpiDivide, 1.0, st);
@@ -473,7 +478,7 @@ int run_sinkhorn_batched(const fsk_opts* o, const void* K, int64_t ldK, const vo
   for (int it = 0; it < o->max_iters; ++it) {
     if (use_kt) {  // Q = K V as the transposed product of K^T
       hipLaunchKernelGGL(batched_prod_wide_kernel, gridw, block, 0, st, (const float*)Kt, ldt, n, m,
-                         (const float*)Vf, Af, SW == 1 ? Uf : part, SW == 1 ? 1 : 0);
+                         (const float*)Vf, Af, SW == 1 ? Uf : part, SW == 1 ? 1 : 0, SW);
       FSK_LAUNCH_CHECK("batched_prod_wide_kernel (K V)");
       if (SW > 1) FSK_TRY(reduce(SW, Af, Uf));
     } else {
@@ -486,7 +491,7 @@ int run_sinkhorn_batched(const fsk_opts* o, const void* K, int64_t ldK, const vo
       FSK_TRY(launch_dp_release(FSK_F32, Uf, n, m, dp->clip_u, dp->sigma_u, dp->seed,
                                 dp->release0 + 2 * (uint64_t)it, st));
     hipLaunchKernelGGL(batched_prod_wide_kernel, gridw, block, 0, st, Kf, ldK, n, m,
-                       (const float*)Uf, Bf, SW == 1 ? Vf : part, SW == 1 ? 1 : 0);
+                       (const float*)Uf, Bf, SW == 1 ? Vf : part, SW == 1 ? 1 : 0, SW);
     FSK_LAUNCH_CHECK("batched_prod_wide_kernel (K^T U)");
     if (SW > 1) FSK_TRY(reduce(SW, Bf, Vf));
     if (dp)
