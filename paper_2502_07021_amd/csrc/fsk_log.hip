@@ -138,16 +138,23 @@ __device__ __forceinline__ void fma_rows2<8>(double& z0, double& z1, const doubl
       : "memory");
 }
 
+__device__ __forceinline__ float exp2_of(float x) { return __builtin_amdgcn_exp2f(x); }
+__device__ __forceinline__ double exp2_of(double x) { return exp2(x); }
+__device__ __forceinline__ float max_of(float x, float y) { return fmaxf(x, y); }
+__device__ __forceinline__ double max_of(double x, double y) { return fmax(x, y); }
+
 // part_m[i*slices + sl], part_s[...]: reference exponent and sum of
 // 2^(z_ij - reference) over the columns j of slice sl, z_ij = beta_j + ps_i . qc_j.
-template <int DP>
+// S: type of the exponentials and of the running sum (float for the fp32 interface: one
+// v_exp_f32 per pair; double for the fp64 interface).
+template <int DP, typename S>
 __global__ __launch_bounds__(kLogThreads) void log_lse_kernel(const double* __restrict__ ps,
                                                               const double* __restrict__ qc,
                                                               const double* __restrict__ beta,
                                                               int n_rows, int n_cols,
                                                               int cols_per_slice, int slices,
                                                               double* __restrict__ part_m,
-                                                              float* __restrict__ part_s) {
+                                                              S* __restrict__ part_s) {
   constexpr int RI = kLogRowsPerLane;
   constexpr int J = kLogChunk;
   const int tid = threadIdx.x;
@@ -167,7 +174,7 @@ __global__ __launch_bounds__(kLogThreads) void log_lse_kernel(const double* __re
 
   // reference exponent = z of the slice's first column; sums start empty
   double mref[RI];
-  float sum[RI];
+  S sum[RI];
   {
     const double b0 = beta[jb];
 #pragma unroll
@@ -176,7 +183,7 @@ __global__ __launch_bounds__(kLogThreads) void log_lse_kernel(const double* __re
 #pragma unroll
       for (int k = 0; k < DP; ++k) z = fma(xs[r][k], qc[(int64_t)jb * DP + k], z);
       mref[r] = z;
-      sum[r] = 0.f;
+      sum[r] = S(0);
     }
   }
 
@@ -234,25 +241,25 @@ __global__ __launch_bounds__(kLogThreads) void log_lse_kernel(const double* __re
     }
 #pragma unroll
     for (int r = 0; r < RI; ++r) {
-      float zf[JJ];
+      S zf[JJ];
 #pragma unroll
-      for (int t = 0; t < JJ; ++t) zf[t] = (float)zd[r][t];
-      float cm = zf[0];
+      for (int t = 0; t < JJ; ++t) zf[t] = (S)zd[r][t];
+      S cm = zf[0];
 #pragma unroll
-      for (int t = 1; t < JJ; ++t) cm = fmaxf(cm, zf[t]);
-      if (cm > kLogRaise) {
+      for (int t = 1; t < JJ; ++t) cm = max_of(cm, zf[t]);
+      if (cm > (S)kLogRaise) {
         // rare: move the reference up to this chunk's maximum, exactly (in fp64), so that
         // the terms near the new maximum are rounded at their final, small magnitude
         double zmax = zd[r][0];
 #pragma unroll
         for (int t = 1; t < JJ; ++t) zmax = zd[r][t] > zmax ? zd[r][t] : zmax;
         mref[r] += zmax;
-        sum[r] *= __builtin_amdgcn_exp2f(-(float)zmax);
+        sum[r] *= exp2_of(-(S)zmax);
 #pragma unroll
-        for (int t = 0; t < JJ; ++t) zf[t] = (float)(zd[r][t] - zmax);
+        for (int t = 0; t < JJ; ++t) zf[t] = (S)(zd[r][t] - zmax);
       }
 #pragma unroll
-      for (int t = 0; t < JJ; ++t) sum[r] += __builtin_amdgcn_exp2f(zf[t]);
+      for (int t = 0; t < JJ; ++t) sum[r] += exp2_of(zf[t]);
     }
   };
 
@@ -276,9 +283,9 @@ __global__ __launch_bounds__(kLogThreads) void log_lse_kernel(const double* __re
 // mode 0: store pot_new (fp64 shadow, caller's array, beta for the column role).
 // mode 1: store |w_i exp((pot_i - pot_new)/eps) - w_i| -- the row-marginal error of the
 //         plan exp((f_i + g_j - C_ij)/eps) with the potentials as they stand.
-template <typename T>
+template <typename T, typename TS>
 __global__ __launch_bounds__(256) void log_finalize_kernel(const double* __restrict__ part_m,
-                                                           const float* __restrict__ part_s,
+                                                           const TS* __restrict__ part_s,
                                                            int slices, int n,
                                                            const double* __restrict__ norm2,
                                                            const double* __restrict__ lnw, double eps,
@@ -339,7 +346,7 @@ static LogWs log_ws(int n, int d) {
   w.xc = take(nd); w.xs = take(nd); w.yc = take(nd); w.ys = take(nd);
   w.nx2 = take(nv); w.ny2 = take(nv); w.lna = take(nv); w.lnb = take(nv);
   w.fd = take(nv); w.gd = take(nv); w.bx = take(nv); w.by = take(nv);
-  w.pm = take(nv * w.slices); w.psum = take((size_t)n * 4 * w.slices);
+  w.pm = take(nv * w.slices); w.psum = take(nv * w.slices);  // sums: fp32 or fp64
   w.err = take(nv); w.scalar = take(256);
   w.total = off;
   return w;
@@ -347,33 +354,32 @@ static LogWs log_ws(int n, int d) {
 
 size_t log_workspace_bytes(int n, int d) { return log_pad_dim(d) ? log_ws(n, d).total : 0; }
 
-template <int DP>
+template <int DP, typename S>
 static int launch_lse(const LogWs& w, int n, const double* ps, const double* qc, const double* beta,
-                      double* pm, float* psum, hipStream_t st) {
+                      double* pm, S* psum, hipStream_t st) {
   dim3 grid((n + kLogRowTile - 1) / kLogRowTile, w.slices), block(kLogThreads);
-  hipLaunchKernelGGL((log_lse_kernel<DP>), grid, block, 0, st, ps, qc, beta, n, n, w.cols_per_slice,
-                     w.slices, pm, psum);
+  hipLaunchKernelGGL((log_lse_kernel<DP, S>), grid, block, 0, st, ps, qc, beta, n, n,
+                     w.cols_per_slice, w.slices, pm, psum);
   FSK_LAUNCH_CHECK("log_lse_kernel");
   return FSK_OK;
 }
 
+template <typename S>
 static int lse_dispatch(const LogWs& w, int n, const double* ps, const double* qc,
-                        const double* beta, double* pm, float* psum, hipStream_t st) {
+                        const double* beta, double* pm, S* psum, hipStream_t st) {
   switch (w.dp) {
-    case 4: return launch_lse<4>(w, n, ps, qc, beta, pm, psum, st);
-    case 8: return launch_lse<8>(w, n, ps, qc, beta, pm, psum, st);
-    case 16: return launch_lse<16>(w, n, ps, qc, beta, pm, psum, st);
-    case 32: return launch_lse<32>(w, n, ps, qc, beta, pm, psum, st);
+    case 4: return launch_lse<4, S>(w, n, ps, qc, beta, pm, psum, st);
+    case 8: return launch_lse<8, S>(w, n, ps, qc, beta, pm, psum, st);
+    case 16: return launch_lse<16, S>(w, n, ps, qc, beta, pm, psum, st);
+    case 32: return launch_lse<32, S>(w, n, ps, qc, beta, pm, psum, st);
     default: return set_error(FSK_EUNSUPPORTED, "point dimension above 32 is not built");
   }
 }
 
-int run_sinkhorn_log_points(const fsk_opts* o, const void* x, const void* y, int d, double eps,
-                            const void* a, const void* b, void* f, void* g, void* workspace,
-                            size_t ws_bytes, int32_t* iters_done, double* err_out,
-                            hipStream_t st) {
-  if (o->dtype != FSK_F32) return set_error(FSK_EUNSUPPORTED, "log-domain path takes fp32 inputs");
-  if (log_pad_dim(d) == 0) return set_error(FSK_EUNSUPPORTED, "point dimension %d above 32 is not built", d);
+template <typename T>
+static int run_log_typed(const fsk_opts* o, const void* x, const void* y, int d, double eps,
+                         const void* a, const void* b, void* f, void* g, void* workspace,
+                         size_t ws_bytes, int32_t* iters_done, double* err_out, hipStream_t st) {
   const int n = o->n;
   const LogWs w = log_ws(n, d);
   if (!workspace || ws_bytes < w.total)
@@ -381,26 +387,25 @@ int run_sinkhorn_log_points(const fsk_opts* o, const void* x, const void* y, int
   char* ws = (char*)workspace;
   auto D = [&](size_t off) { return (double*)(ws + off); };
   const double s = 1.4426950408889634074 / eps;
-  const float *xf = (const float*)x, *yf = (const float*)y, *af = (const float*)a,
-              *bf = (const float*)b;
-  float *ff = (float*)f, *gf = (float*)g;
+  const T *xf = (const T*)x, *yf = (const T*)y, *af = (const T*)a, *bf = (const T*)b;
+  T *ff = (T*)f, *gf = (T*)g;
   const int nb = (n + 255) / 256;
 
-  hipLaunchKernelGGL((log_mean_kernel<float>), dim3(1), dim3(1024), 0, st, xf, yf, n, d, D(w.mu));
+  hipLaunchKernelGGL((log_mean_kernel<T>), dim3(1), dim3(1024), 0, st, xf, yf, n, d, D(w.mu));
   FSK_LAUNCH_CHECK("log_mean_kernel");
-  hipLaunchKernelGGL((log_prep_kernel<float>), dim3(nb), dim3(256), 0, st, xf, af, ff, n, d, w.dp, s,
+  hipLaunchKernelGGL((log_prep_kernel<T>), dim3(nb), dim3(256), 0, st, xf, af, ff, n, d, w.dp, s,
                      D(w.mu), D(w.xc), D(w.xs), D(w.nx2), D(w.lna), D(w.fd), D(w.bx));
   FSK_LAUNCH_CHECK("log_prep_kernel");
-  hipLaunchKernelGGL((log_prep_kernel<float>), dim3(nb), dim3(256), 0, st, yf, bf, gf, n, d, w.dp, s,
+  hipLaunchKernelGGL((log_prep_kernel<T>), dim3(nb), dim3(256), 0, st, yf, bf, gf, n, d, w.dp, s,
                      D(w.mu), D(w.yc), D(w.ys), D(w.ny2), D(w.lnb), D(w.gd), D(w.by));
   FSK_LAUNCH_CHECK("log_prep_kernel");
 
-  float* psum = (float*)(ws + w.psum);
+  T* psum = (T*)(ws + w.psum);  // the exponentials and their sums run in the interface type
   auto half_step = [&](bool f_side, int mode) -> int {
     // f-update: rows = x (scaled), columns = y with beta_y; g-update: the roles swapped
-    FSK_TRY(lse_dispatch(w, n, D(f_side ? w.xs : w.ys), D(f_side ? w.yc : w.xc),
+    FSK_TRY(lse_dispatch<T>(w, n, D(f_side ? w.xs : w.ys), D(f_side ? w.yc : w.xc),
                             D(f_side ? w.by : w.bx), D(w.pm), psum, st));
-    hipLaunchKernelGGL((log_finalize_kernel<float>), dim3(nb), dim3(256), 0, st, D(w.pm), psum,
+    hipLaunchKernelGGL((log_finalize_kernel<T, T>), dim3(nb), dim3(256), 0, st, D(w.pm), psum,
                        w.slices, n, D(f_side ? w.nx2 : w.ny2), D(f_side ? w.lna : w.lnb), eps, s,
                        mode, D(f_side ? w.fd : w.gd), f_side ? ff : gf, D(f_side ? w.bx : w.by),
                        D(w.err));
@@ -430,6 +435,16 @@ int run_sinkhorn_log_points(const fsk_opts* o, const void* x, const void* y, int
   if (iters_done) *iters_done = done;
   if (err_out) *err_out = e;
   return FSK_OK;
+}
+
+int run_sinkhorn_log_points(const fsk_opts* o, const void* x, const void* y, int d, double eps,
+                            const void* a, const void* b, void* f, void* g, void* workspace,
+                            size_t ws_bytes, int32_t* iters_done, double* err_out,
+                            hipStream_t st) {
+  if (log_pad_dim(d) == 0) return set_error(FSK_EUNSUPPORTED, "point dimension %d above 32 is not built", d);
+  return o->dtype == FSK_F64
+             ? run_log_typed<double>(o, x, y, d, eps, a, b, f, g, workspace, ws_bytes, iters_done, err_out, st)
+             : run_log_typed<float>(o, x, y, d, eps, a, b, f, g, workspace, ws_bytes, iters_done, err_out, st);
 }
 
 }  // namespace fsk

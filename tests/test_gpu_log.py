@@ -15,24 +15,26 @@ from gpu_util import dev
 pytestmark = pytest.mark.gpu
 
 
-def run_log(x, y, a, b, eps, iters, tol=0.0, check_every=1, f0=None, g0=None):
+def run_log(x, y, a, b, eps, iters, tol=0.0, check_every=1, f0=None, g0=None, dtype=np.float32):
     n, d = x.shape
-    opts = api.make_opts(n, torch.float32, max_iters=iters, tol=tol, check_every=check_every)
+    td = torch.float64 if dtype == np.float64 else torch.float32
+    opts = api.make_opts(n, td, max_iters=iters, tol=tol, check_every=check_every)
     ws = api.alloc_workspace(opts, api.FSK_MODE_LOG, d)
-    f = torch.zeros(n, device="cuda") if f0 is None else dev(f0.astype(np.float32))
-    g = torch.zeros(n, device="cuda") if g0 is None else dev(g0.astype(np.float32))
-    done, err = api.fsk_sinkhorn_log_points(opts, dev(x), dev(y), eps, dev(a), dev(b), f, g, ws)
+    f = torch.zeros(n, dtype=td, device="cuda") if f0 is None else dev(f0.astype(dtype))
+    g = torch.zeros(n, dtype=td, device="cuda") if g0 is None else dev(g0.astype(dtype))
+    cast = lambda t: dev(np.ascontiguousarray(t.astype(dtype)))
+    done, err = api.fsk_sinkhorn_log_points(opts, cast(x), cast(y), eps, cast(a), cast(b), f, g, ws)
     torch.cuda.synchronize()
     return f.cpu().numpy().astype(np.float64), g.cpu().numpy().astype(np.float64), done, err
 
 
-def check_potentials(orc, x, y, a, b, eps, f, g, fo, go):
-    assert np.max(np.abs(f - fo)) / eps <= 1e-4 and np.max(np.abs(g - go)) / eps <= 1e-4
+def check_potentials(orc, x, y, a, b, eps, f, g, fo, go, tol=1e-4):
+    assert np.max(np.abs(f - fo)) / eps <= tol and np.max(np.abs(g - go)) / eps <= tol
     rows = orc.log_row_marginal_points(x, f, y, g, eps)
     rows_o = orc.log_row_marginal_points(x, fo, y, go, eps)
-    assert np.max(np.abs(rows - rows_o) / rows_o) <= 1e-4
+    assert np.max(np.abs(rows - rows_o) / rows_o) <= tol
     cols = orc.log_row_marginal_points(y, g, x, f, eps)      # column marginal: roles swapped
-    assert np.max(np.abs(cols - b.astype(np.float64)) / b) <= 1e-4   # exact after a g-update
+    assert np.max(np.abs(cols - b.astype(np.float64)) / b) <= tol   # exact after a g-update
 
 
 @pytest.mark.parametrize("n", [1500, 4096])
@@ -102,3 +104,28 @@ def test_small_eps_where_the_dense_kernel_underflows(orc):
     f, g, _, _ = run_log(x, y, a, b, eps, 20)
     assert np.isfinite(f).all() and np.isfinite(g).all()
     check_potentials(orc, x, y, a, b, eps, f, g, fo, go)
+
+
+@pytest.mark.parametrize("n,d", [(1500, 16), (257, 5), (64, 32), (3, 2)])
+def test_fp64_interface(orc, n, d):
+    """FSK_F64: potentials, exponentials and sums in fp64; the bar is 1e-10."""
+    rng = np.random.default_rng(7 * n + d)
+    x = rng.uniform(size=(n, d)); y = rng.uniform(size=(n, d))
+    a = rng.uniform(0.5, 1.5, n); a /= a.sum()
+    b = rng.uniform(0.5, 1.5, n); b /= b.sum()
+    eps = 0.01 * d
+    for iters in (1, 25):
+        fo, go, _, _ = orc.sinkhorn_log_points(x, y, eps, a, b, iters)
+        f, g, done, _ = run_log(x, y, a, b, eps, iters, dtype=np.float64)
+        assert done == iters
+        check_potentials(orc, x, y, a, b, eps, f, g, fo, go, tol=1e-10)
+
+
+def test_fp64_tolerance_mode_reaches_what_fp32_cannot(orc):
+    w = workloads.make(4, n=512)
+    x, y, a, b = (t.astype(np.float64) for t in (w.x, w.y, w.a, w.b))
+    eps = 0.5
+    fo, go, done_o, err_o = orc.sinkhorn_log_points(x, y, eps, a, b, 1000, tol=1e-11, check_every=10)
+    f, g, done, err = run_log(x, y, a, b, eps, 1000, tol=1e-11, check_every=10, dtype=np.float64)
+    assert done == done_o and done < 1000 and err < 1e-11
+    assert np.max(np.abs(f - fo)) / eps <= 1e-10 and np.max(np.abs(g - go)) / eps <= 1e-10
