@@ -83,3 +83,19 @@ def test_above_the_fused_limit_the_call_falls_back_to_two_passes(orc):
                             torch.empty(4096, device="cuda"), torch.empty(n, device="cuda"),
                             torch.empty(1 << 26, dtype=torch.uint8, device="cuda"))
     assert e.value.status == api.FSK_EUNSUPPORTED
+
+
+@pytest.mark.parametrize("n,c", [(1024, 1024), (1024, 512), (1536, 384), (600, 300)])
+def test_more_blocks_than_compute_units(orc, n, c):
+    """c far above the number of compute units (down to one row per block): teams of workgroups
+    walk several blocks each; every flow still reproduces the centralised iterates."""
+    w = workloads.make(3, n=n)
+    K, _ = orc.gibbs_from_points_f32(w.x, w.y, w.eps, True)
+    uo, vo = orc.sinkhorn_blocked(K, w.a, w.b, 15, c, 1)
+    ref = None
+    for flow in (api.FSK_FLOW_FUSED, api.FSK_FLOW_TWO_PASS, api.FSK_FLOW_PAPER):
+        u, v, _, _ = run_dense(K, w.a, w.b, 15, flow=flow, c=c)
+        assert relerr(u, uo) <= 1e-4 and relerr(v, vo) <= 1e-4
+        if flow != api.FSK_FLOW_FUSED:      # the two-pass flows are bitwise independent of c
+            u1, v1, _, _ = run_dense(K, w.a, w.b, 15, flow=api.FSK_FLOW_TWO_PASS, c=1)
+            assert np.array_equal(u, u1) and np.array_equal(v, v1)
