@@ -50,6 +50,13 @@ def timed(fn):
     return time.perf_counter() - t0
 
 
+def repeats(fn, steps, first_dt, n=5):
+    """The timed region again, n - 1 more times: spread of the measurement (not used for `value`)."""
+    ms = sorted([first_dt / steps * 1e3] + [timed(fn) / steps * 1e3 for _ in range(n - 1)])
+    return {"runs": n, "median_ms_per_step": ms[len(ms) // 2], "min_ms_per_step": ms[0],
+            "max_ms_per_step": ms[-1]}
+
+
 def event_ms(fn):
     """Duration of fn's GPU work by HIP events recorded on the stream the library launches on."""
     import torch
@@ -104,6 +111,7 @@ def bench_dense(args, cfg):
 
     # dominant kernel alone, same launch configuration, HIP events on the launch stream
     stream_ms, other_ms, launches = api.fsk_dense_profile(opts, K, a, b, u, v, ws, args.profile_reps)
+    spread = repeats(lambda: run(steps), steps, dt)
     # K read once per iteration (fused), twice (two-pass flows), or once per CALL (resident:
     # no HBM roofline applies; the figure below then only says how far from HBM-bound it is)
     alg_bytes = float(n) * n * esz * (2 if args.flow in (1, 2) else 1)
@@ -146,6 +154,7 @@ def bench_dense(args, cfg):
                                f"flow={['fused', 'two_pass', 'algorithm1', 'resident'][args.flow]}",
                    "n": n, "c": c, "eps": w.eps, "iterations": steps},
         "roofline": roofline,
+        "repeats": spread,
     }
     out.update(extra)
     if not args.no_cpu_baseline:
