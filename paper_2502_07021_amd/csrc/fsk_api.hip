@@ -80,7 +80,7 @@ static int check_vec(const char* name, const void* p, bool need16) {
 struct DenseWs {
   int64_t ld_ws;        // elements per partial row
   size_t partial_rows;  // rows the partial area holds
-  size_t partial_off, vec_off, scalar_off, resident_off, total;
+  size_t partial_off, vec_off, scalar_off, save_off, resident_off, total;
 };
 
 static DenseWs dense_ws(const fsk_opts* o) {
@@ -97,7 +97,8 @@ static DenseWs dense_ws(const fsk_opts* o) {
   w.partial_off = 0;
   w.vec_off = align_up(rows * (size_t)w.ld_ws * s, 256);
   w.scalar_off = w.vec_off + align_up((size_t)o->n * s, 256);
-  w.resident_off = w.scalar_off + 256;
+  w.save_off = w.scalar_off + 256;  // u and v as they stood at a polled state
+  w.resident_off = w.save_off + 2 * align_up((size_t)o->n * s, 256);
   w.total = w.resident_off + (o->flow == FSK_FLOW_RESIDENT ? resident_workspace_bytes(o->dtype, o->n) : 0);
   return w;
 }
@@ -176,10 +177,12 @@ int fsk_kernel_from_points(const fsk_opts* opts, const void* x, const void* y, i
 // One dense iteration, enqueued.  With `ev` (three events) the K-streaming launches lie
 // between ev[0] and ev[1] and the small reduction launches between ev[1] and ev[2];
 // *stream_launches (if given) receives the number of K-streaming launches.
+// `errvec` (n entries, optional): the u-update also leaves |u_i (K v)_i - a_i| there for the
+// scalings as they stood BEFORE this iteration (the row-marginal error terms, for free).
 static int dense_iteration(const fsk_opts* o, const DenseWs& w, const char* K, int64_t ld,
                            const char* a, const char* b, char* u, char* v, char* ws,
                            hipStream_t st, hipEvent_t* ev = nullptr,
-                           int32_t* stream_launches = nullptr) {
+                           int32_t* stream_launches = nullptr, char* errvec = nullptr) {
   const int n = o->n, c = o->c, m = n / c, dt = o->dtype;
   const size_t s = elem_size(dt);
   const int epi = epi_of(o);
@@ -193,7 +196,7 @@ static int dense_iteration(const fsk_opts* o, const DenseWs& w, const char* K, i
   }
   if (ev) FSK_HIP(hipEventRecord(ev[0], st));
   if (flow == FSK_FLOW_FUSED) {
-    FSK_TRY(launch_fused(dt, plan, K, ld, n, m, c, a, v, u, u, partial, w.ld_ws, epi, o->eta, st));
+    FSK_TRY(launch_fused(dt, plan, K, ld, n, m, c, a, v, u, u, partial, w.ld_ws, epi, o->eta, st, errvec));
     if (ev) FSK_HIP(hipEventRecord(ev[1], st));
     FSK_TRY(launch_colreduce(dt, partial, w.ld_ws, c * plan.wgs, 0, n, b, v, v, epi, o->eta, st));
     if (ev) FSK_HIP(hipEventRecord(ev[2], st));
@@ -203,7 +206,7 @@ static int dense_iteration(const fsk_opts* o, const DenseWs& w, const char* K, i
   for (int j = 0; j < c; ++j) {  // worker j: u_{I_j} from its row slab and the shared v
     const size_t off = (size_t)j * m;
     FSK_TRY(launch_rowpass(dt, K + off * (size_t)ld * s, ld, n, m, v, a + off * s, u + off * s,
-                           u + off * s, epi, o->eta, st));
+                           u + off * s, epi, o->eta, st, errvec ? errvec + off * s : nullptr));
   }
   if (flow == FSK_FLOW_TWO_PASS) {
     FSK_TRY(launch_colpartial(dt, K, ld, n, n, 0, n, u, partial, w.ld_ws, st));
@@ -264,28 +267,65 @@ static int dense_solve(const fsk_opts* opts, const DenseWs& w, const void* K, in
   double e = NAN;
   const bool resident = opts->flow == FSK_FLOW_RESIDENT;
   if (resident) FSK_TRY(check_resident(opts));
-  for (int it = 0; it < opts->max_iters;) {
-    if (resident) {  // all the iterations up to the next poll in one launch
+  const bool check = opts->tol > 0.0;
+  auto nonfinite = [&](int at) {
+    if (iters_done) *iters_done = at;
+    if (err) *err = e;
+    return set_error(FSK_ENONFINITE, "marginal error is not finite after %d iterations", at);
+  };
+  if (resident) {
+    for (int it = 0; it < opts->max_iters;) {  // all the iterations up to the next poll in one launch
       int chunk = opts->max_iters - it;
-      if (opts->tol > 0.0 && opts->check_every - it % opts->check_every < chunk)
+      if (check && opts->check_every - it % opts->check_every < chunk)
         chunk = opts->check_every - it % opts->check_every;
       FSK_TRY(launch_resident(opts->dtype, K, ldK, opts->n, chunk, a, b, u, v,
                               workspace + w.resident_off, resident_eta(opts), kResidentSpinLimit, st));
       it += chunk;
-    } else {
-      FSK_TRY(dense_iteration(opts, w, (const char*)K, ldK, (const char*)a, (const char*)b, (char*)u,
-                              (char*)v, workspace, st));
-      ++it;
-    }
-    done = it;
-    if (opts->tol > 0.0 && (done % opts->check_every == 0 || done == opts->max_iters)) {
-      FSK_TRY(dense_error(opts, w, K, ldK, a, u, v, workspace, &e, st));
-      if (!std::isfinite(e)) {
-        if (iters_done) *iters_done = done;
-        if (err) *err = e;
-        return set_error(FSK_ENONFINITE, "marginal error is not finite after %d iterations", done);
+      done = it;
+      if (check && (done % opts->check_every == 0 || done == opts->max_iters)) {
+        FSK_TRY(dense_error(opts, w, K, ldK, a, u, v, workspace, &e, st));
+        if (!std::isfinite(e)) return nonfinite(done);
+        if (e < opts->tol) break;
       }
-      if (e < opts->tol) break;
+    }
+  } else {
+    // The error of the state after `it` iterations falls out of the u-update of iteration
+    // it + 1 (its row products are K v of that state): a poll costs two n-vector copies, a
+    // sum and a synchronisation, not a pass over K.  If the state turns out to have met the
+    // tolerance, the iteration that revealed it is undone by restoring the saved vectors.
+    const size_t vec_bytes = (size_t)opts->n * elem_size(opts->dtype);
+    char* errvec = workspace + w.vec_off;
+    char* save_u = workspace + w.save_off;
+    char* save_v = save_u + align_up(vec_bytes, 256);
+    double* scalar = (double*)(workspace + w.scalar_off);
+    bool converged = false;
+    for (int it = 0; it < opts->max_iters; ++it) {
+      const bool poll = check && it > 0 && it % opts->check_every == 0;
+      if (poll) {
+        FSK_HIP(hipMemcpyAsync(save_u, u, vec_bytes, hipMemcpyDeviceToDevice, st));
+        FSK_HIP(hipMemcpyAsync(save_v, v, vec_bytes, hipMemcpyDeviceToDevice, st));
+      }
+      FSK_TRY(dense_iteration(opts, w, (const char*)K, ldK, (const char*)a, (const char*)b, (char*)u,
+                              (char*)v, workspace, st, nullptr, nullptr, poll ? errvec : nullptr));
+      if (poll) {
+        FSK_TRY(launch_sum_to_double(opts->dtype, errvec, opts->n, scalar, st));
+        FSK_HIP(hipMemcpyAsync(&e, scalar, sizeof(double), hipMemcpyDeviceToHost, st));
+        FSK_HIP(hipStreamSynchronize(st));
+        if (!std::isfinite(e)) return nonfinite(it);
+        if (e < opts->tol) {
+          FSK_HIP(hipMemcpyAsync(u, save_u, vec_bytes, hipMemcpyDeviceToDevice, st));
+          FSK_HIP(hipMemcpyAsync(v, save_v, vec_bytes, hipMemcpyDeviceToDevice, st));
+          FSK_HIP(hipStreamSynchronize(st));
+          done = it;
+          converged = true;
+          break;
+        }
+      }
+      done = it + 1;
+    }
+    if (check && !converged && done > 0) {  // the state after the last iteration is always polled
+      FSK_TRY(dense_error(opts, w, K, ldK, a, u, v, workspace, &e, st));
+      if (!std::isfinite(e)) return nonfinite(done);
     }
   }
   if (iters_done) *iters_done = done;

@@ -25,7 +25,10 @@ template <typename T, int ROWS>
 __global__ __launch_bounds__(256) void rowpass_kernel(const T* __restrict__ K, int64_t ld, int n,
                                                       int rows, const T* __restrict__ vin,
                                                       const T* marg, const T* old, T* out, int epi,
-                                                      T eta) {
+                                                      T eta, T* err_out) {
+  // err_out (may be null): |old_i * product_i - marg_i|, the row-marginal error term of the
+  // scalings as they stood before this update (old is read before out is written: out may
+  // alias old).
   constexpr int W = Pack<T>::W;
   constexpr int NT = 256, NW = NT / kWave;
   const int tid = threadIdx.x;
@@ -76,7 +79,8 @@ __global__ __launch_bounds__(256) void rowpass_kernel(const T* __restrict__ K, i
 #pragma unroll
       for (int k = 0; k < NW; ++k) q += red[tid][k];
       const T mg = epi_needs_marg(epi) ? marg[row] : T(0);
-      const T od = epi_needs_old(epi) ? old[row] : T(0);
+      const T od = (epi_needs_old(epi) || err_out) ? old[row] : T(0);
+      if (err_out) err_out[row] = fsk_abs(od * q - marg[row]);
       out[row] = apply_epilogue(epi, mg, q, od, eta);
     }
   }
@@ -85,22 +89,22 @@ __global__ __launch_bounds__(256) void rowpass_kernel(const T* __restrict__ K, i
 template <typename T>
 static int rowpass_typed(const void* K, int64_t ld, int n, int rows, const void* vin,
                          const void* marg, const void* old, void* out, int epi, double eta,
-                         hipStream_t stream) {
+                         void* err_out, hipStream_t stream) {
   if (rows <= 0) return FSK_OK;
   constexpr int ROWS = 4;
   dim3 grid((rows + ROWS - 1) / ROWS), block(256);
   hipLaunchKernelGGL((rowpass_kernel<T, ROWS>), grid, block, 0, stream, (const T*)K, ld, n, rows,
-                     (const T*)vin, (const T*)marg, (const T*)old, (T*)out, epi, (T)eta);
+                     (const T*)vin, (const T*)marg, (const T*)old, (T*)out, epi, (T)eta, (T*)err_out);
   FSK_LAUNCH_CHECK("rowpass_kernel");
   return FSK_OK;
 }
 
 int launch_rowpass(int dtype, const void* K, int64_t ld, int n, int rows, const void* vin,
                    const void* marg, const void* old, void* out, int epi, double eta,
-                   hipStream_t stream) {
+                   hipStream_t stream, void* err_out) {
   return dtype == FSK_F64
-             ? rowpass_typed<double>(K, ld, n, rows, vin, marg, old, out, epi, eta, stream)
-             : rowpass_typed<float>(K, ld, n, rows, vin, marg, old, out, epi, eta, stream);
+             ? rowpass_typed<double>(K, ld, n, rows, vin, marg, old, out, epi, eta, err_out, stream)
+             : rowpass_typed<float>(K, ld, n, rows, vin, marg, old, out, epi, eta, err_out, stream);
 }
 
 // ========================================================== column pass (generic)
@@ -282,7 +286,9 @@ __global__ __launch_bounds__(512) void fused_kernel(const T* __restrict__ K, int
                                                     int rows, int nblk, int gb, const T* marg,
                                                     const T* __restrict__ vin, const T* old_u,
                                                     T* u_out, T* __restrict__ partial,
-                                                    int64_t ld_ws, T eta) {
+                                                    int64_t ld_ws, T eta, T* err_out) {
+  // err_out (may be null): |old_u_i (K v)_i - marg_i| per row, the row-marginal error term of
+  // the scalings as they stood before this update (free: the product is at hand).
   // EXACT: n == VPT*512*W, every pack of every thread is a full pack inside the row.
   // eta < 1 selects the arithmetic relaxation u <- (1-eta) u + eta a./(K v) (Sec. 3.3).
   constexpr int W = Pack<T>::W;
@@ -346,7 +352,7 @@ __global__ __launch_bounds__(512) void fused_kernel(const T* __restrict__ K, int
       row = row < rows ? row : rows - 1;
       const T* kp = K + (rbase + row) * ld + (int64_t)tid * W;
       mg[r] = marg[rbase + row];
-      od[r] = damped ? old_u[rbase + row] : T(0);
+      od[r] = (damped || err_out) ? old_u[rbase + row] : T(0);
 #pragma unroll
       for (int i = 0; i < VPT; ++i) {
         if (EXACT) {
@@ -396,7 +402,10 @@ __global__ __launch_bounds__(512) void fused_kernel(const T* __restrict__ K, int
       if (row < rows) {
         ur = mg[r] / q;
         if (damped) ur = (T(1) - eta) * od[r] + eta * ur;
-        if (tid == 0) u_out[rbase + row] = ur;
+        if (tid == 0) {
+          if (err_out) err_out[rbase + row] = fsk_abs(od[r] * q - mg[r]);
+          u_out[rbase + row] = ur;
+        }
       }
 #pragma unroll
       for (int i = 0; i < VPT; ++i)
@@ -460,7 +469,7 @@ FusedPlan fused_plan(int dtype, int n, int rows, int c) {
 template <typename T, int VPT, bool EXACT>
 static int fused_typed(const FusedPlan& plan, const void* K, int64_t ld, int n, int rows, int c,
                        const void* marg, const void* vin, const void* old_u, void* u_out,
-                       void* partial, int64_t ld_ws, double eta, hipStream_t stream) {
+                       void* partial, int64_t ld_ws, double eta, void* err_out, hipStream_t stream) {
   constexpr int R = fused_rows_per_group(VPT);
   auto kern = fused_kernel<T, VPT, R, EXACT>;
   // the attribute belongs to the kernel's code object on ONE device: kept per device
@@ -477,7 +486,7 @@ static int fused_typed(const FusedPlan& plan, const void* K, int64_t ld, int n, 
   dim3 grid(plan.wgs * teams), block(512);
   hipLaunchKernelGGL(kern, grid, block, plan.lds_bytes, stream, (const T*)K, ld, n, rows, c,
                      plan.wgs, (const T*)marg, (const T*)vin, (const T*)old_u, (T*)u_out, (T*)partial, ld_ws,
-                     (T)eta);
+                     (T)eta, (T*)err_out);
   FSK_LAUNCH_CHECK("fused_kernel");
   return FSK_OK;
 }
@@ -485,14 +494,15 @@ static int fused_typed(const FusedPlan& plan, const void* K, int64_t ld, int n, 
 template <typename T>
 static int fused_dispatch(const FusedPlan& plan, const void* K, int64_t ld, int n, int rows, int c,
                           const void* marg, const void* vin, const void* old_u, void* u_out,
-                          void* partial, int64_t ld_ws, double eta, hipStream_t stream) {
+                          void* partial, int64_t ld_ws, double eta, void* err_out,
+                          hipStream_t stream) {
   const bool exact = n == plan.vpt * 512 * Pack<T>::W;
 #define FSK_FUSED_CASE(V)                                                                         \
   case V:                                                                                         \
     return exact ? fused_typed<T, V, true>(plan, K, ld, n, rows, c, marg, vin, old_u, u_out,      \
-                                           partial, ld_ws, eta, stream)                           \
+                                           partial, ld_ws, eta, err_out, stream)                  \
                  : fused_typed<T, V, false>(plan, K, ld, n, rows, c, marg, vin, old_u, u_out,     \
-                                            partial, ld_ws, eta, stream)
+                                            partial, ld_ws, eta, err_out, stream)
   switch (plan.vpt) {
     FSK_FUSED_CASE(1);
     FSK_FUSED_CASE(2);
@@ -506,16 +516,17 @@ static int fused_dispatch(const FusedPlan& plan, const void* K, int64_t ld, int 
 
 int launch_fused(int dtype, const FusedPlan& plan, const void* K, int64_t ld, int n, int rows,
                  int c, const void* marg, const void* vin, const void* old_u, void* u_out,
-                 void* partial, int64_t ld_ws, int epi, double eta, hipStream_t stream) {
+                 void* partial, int64_t ld_ws, int epi, double eta, hipStream_t stream,
+                 void* err_out) {
   if (!plan.ok) return set_error(FSK_EUNSUPPORTED, "fused kernel: n = %d does not fit in registers", n);
   if (epi != kEpiDivide && epi != kEpiDampArith)
     return set_error(FSK_EUNSUPPORTED, "fused kernel: only the plain and the arithmetic-damped update");
   if (epi == kEpiDivide) eta = 1.0;
   return dtype == FSK_F64
              ? fused_dispatch<double>(plan, K, ld, n, rows, c, marg, vin, old_u, u_out, partial,
-                                      ld_ws, eta, stream)
+                                      ld_ws, eta, err_out, stream)
              : fused_dispatch<float>(plan, K, ld, n, rows, c, marg, vin, old_u, u_out, partial,
-                                     ld_ws, eta, stream);
+                                     ld_ws, eta, err_out, stream);
 }
 
 // ================================================================= plan sums (Eq. 1)

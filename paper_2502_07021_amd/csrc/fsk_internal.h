@@ -48,9 +48,10 @@ constexpr int kColStrip = 128;  // rows summed sequentially into one partial col
 inline int col_strips(int rows) { return (rows + kColStrip - 1) / kColStrip; }
 
 // out[i] = epilogue(marg[i], sum_j K[i][j] vin[j], old[i]) for the `rows` rows of K.
+// err_out (optional, needs marg and old): also |old[i] * product_i - marg[i]|.
 int launch_rowpass(int dtype, const void* K, int64_t ld, int n, int rows, const void* vin,
                    const void* marg, const void* old, void* out, int epi, double eta,
-                   hipStream_t stream);
+                   hipStream_t stream, void* err_out = nullptr);
 
 // partial[s][j] = sum over rows of strip s of K[i][j] u[i], for the 16-byte column packs that
 // intersect [c0, c1).  partial has col_strips(rows) rows of ld_ws elements.
@@ -81,7 +82,8 @@ int fused_teams(const FusedPlan& plan, int c);
 // rows workgroup w handled to K_block^T u_block.
 int launch_fused(int dtype, const FusedPlan& plan, const void* K, int64_t ld, int n, int rows,
                  int c, const void* marg, const void* vin, const void* old_u, void* u_out,
-                 void* partial, int64_t ld_ws, int epi, double eta, hipStream_t stream);
+                 void* partial, int64_t ld_ws, int epi, double eta, hipStream_t stream,
+                 void* err_out = nullptr);
 
 // Per-row terms of the plan sums: with kv_ij = K_ij v_j,
 //   rows[0][i] = u_i sum_j kv_ij            rows[1][i] = u_i sum_j kv_ij C_ij

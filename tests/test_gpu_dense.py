@@ -117,9 +117,22 @@ def test_tolerance_mode(orc):
         assert done == done_o and done % 7 == 0
         assert err < 1e-9 and err == pytest.approx(err_o, rel=1e-3)
         assert relerr(u, uo) <= 1e-10 and relerr(v, vo) <= 1e-10
+        # the state handed back is exactly the state after `done` iterations: the iteration whose
+        # u-update revealed the error of that state has been undone
+        uf, vf, _, _ = run_dense(K, w.a, w.b, done, flow=flow)
+        assert np.array_equal(u, uf) and np.array_equal(v, vf)
     # the cap binds and the last iteration is polled
     u, v, done, err = run_dense(K, w.a, w.b, 10, tol=1e-300, check_every=4)
     assert done == 10 and err > 0
+    # polling every iteration, blocks, damping: same stop as the oracle's rule
+    w3 = workloads.make(3, n=512)
+    K3, _ = orc.gibbs_from_points_f32(w3.x, w3.y, w3.eps, True)
+    uo, vo, done_o, err_o = orc.sinkhorn_dense_tol(K3, w3.a, w3.b, 3000, 1e-4, check_every=1)
+    for flow, c in ((api.FSK_FLOW_FUSED, 8), (api.FSK_FLOW_PAPER, 4), (api.FSK_FLOW_TWO_PASS, 1)):
+        u, v, done, err = run_dense(K3, w3.a, w3.b, 3000, flow=flow, c=c, tol=1e-4, check_every=1)
+        assert abs(done - done_o) <= 1 and err < 1e-4
+        uf, vf, _, _ = run_dense(K3, w3.a, w3.b, done, flow=flow, c=c)
+        assert np.array_equal(u, uf) and np.array_equal(v, vf)
 
 
 @pytest.mark.parametrize("dtype", [np.float32, np.float64])
