@@ -283,6 +283,7 @@ __global__ __launch_bounds__(kLogThreads) void log_lse_kernel(const double* __re
 // mode 0: store pot_new (fp64 shadow, caller's array, beta for the column role).
 // mode 1: store |w_i exp((pot_i - pot_new)/eps) - w_i| -- the row-marginal error of the
 //         plan exp((f_i + g_j - C_ij)/eps) with the potentials as they stand.
+// mode 2: both (the error terms of the state before this update come for free with it).
 template <typename T, typename TS>
 __global__ __launch_bounds__(256) void log_finalize_kernel(const double* __restrict__ part_m,
                                                            const TS* __restrict__ part_s,
@@ -306,20 +307,21 @@ __global__ __launch_bounds__(256) void log_finalize_kernel(const double* __restr
   const double L2 = M + log2(S);
   const double ln2 = 0.693147180559945309417;
   const double pot_new = eps * (lnw[i] - ln2 * (L2 - norm2[i]));
-  if (mode == 0) {
+  if (mode != 0) {  // before potd is overwritten: the error term belongs to the potentials as they stand
+    const double w = exp(lnw[i]);
+    errvec[i] = fabs(w * exp((potd[i] - pot_new) / eps) - w);
+  }
+  if (mode != 1) {
     potd[i] = pot_new;
     pot_out[i] = (T)pot_new;
     beta_out[i] = s * pot_new - norm2[i];
-  } else {
-    const double w = exp(lnw[i]);
-    errvec[i] = fabs(w * exp((potd[i] - pot_new) / eps) - w);
   }
 }
 
 // ------------------------------------------------------------------ host side
 struct LogWs {
   int dp, slices, cols_per_slice;
-  size_t mu, xc, xs, yc, ys, nx2, ny2, lna, lnb, fd, gd, bx, by, pm, psum, err, scalar, total;
+  size_t mu, xc, xs, yc, ys, nx2, ny2, lna, lnb, fd, gd, bx, by, pm, psum, err, scalar, save, total;
 };
 
 static int log_pad_dim(int d) { return d <= 4 ? 4 : d <= 8 ? 8 : d <= 16 ? 16 : d <= 32 ? 32 : 0; }
@@ -348,6 +350,7 @@ static LogWs log_ws(int n, int d) {
   w.fd = take(nv); w.gd = take(nv); w.bx = take(nv); w.by = take(nv);
   w.pm = take(nv * w.slices); w.psum = take(nv * w.slices);  // sums: fp32 or fp64
   w.err = take(nv); w.scalar = take(256);
+  w.save = take(6 * align_up(nv, 256));  // f, g, their fp64 shadows and betas at a polled state
   w.total = off;
   return w;
 }
@@ -413,24 +416,60 @@ static int run_log_typed(const fsk_opts* o, const void* x, const void* y, int d,
     return FSK_OK;
   };
 
+  // Tolerance mode: the f-update of iteration it + 1 evaluates the LSE with the potentials of
+  // the state after `it` iterations, so that state's error terms come with it (mode 2); a poll
+  // costs a few n-vector copies, a sum and a synchronisation.  If the state met the tolerance
+  // the iteration that revealed it is undone from the saved copies.
+  const size_t tb = (size_t)n * sizeof(T), db = (size_t)n * 8;
+  char* sv = ws + w.save;
+  char* keep[6] = {(char*)ff, (char*)gf, (char*)D(w.fd), (char*)D(w.gd), (char*)D(w.bx), (char*)D(w.by)};
+  const size_t keep_bytes[6] = {tb, tb, db, db, db, db};
+  auto copy_state = [&](bool restore) -> int {
+    size_t off = 0;
+    for (int k = 0; k < 6; ++k) {
+      FSK_HIP(hipMemcpyAsync(restore ? keep[k] : sv + off, restore ? sv + off : keep[k], keep_bytes[k],
+                             hipMemcpyDeviceToDevice, st));
+      off += align_up(db, 256);
+    }
+    return FSK_OK;
+  };
+  auto read_error = [&](double* out) -> int {
+    FSK_TRY(launch_sum_to_double(FSK_F64, D(w.err), n, D(w.scalar), st));
+    FSK_HIP(hipMemcpyAsync(out, D(w.scalar), sizeof(double), hipMemcpyDeviceToHost, st));
+    FSK_HIP(hipStreamSynchronize(st));
+    return FSK_OK;
+  };
+  auto nonfinite = [&](int at, double e) {
+    if (iters_done) *iters_done = at;
+    if (err_out) *err_out = e;
+    return set_error(FSK_ENONFINITE, "marginal error is not finite after %d iterations", at);
+  };
+
   int done = 0;
   double e = NAN;
+  bool converged = false;
   for (int it = 0; it < o->max_iters; ++it) {
-    FSK_TRY(half_step(true, 0));
+    const bool poll = o->tol > 0.0 && it > 0 && it % o->check_every == 0;
+    if (poll) FSK_TRY(copy_state(false));
+    FSK_TRY(half_step(true, poll ? 2 : 0));
     FSK_TRY(half_step(false, 0));
-    done = it + 1;
-    if (o->tol > 0.0 && (done % o->check_every == 0 || done == o->max_iters)) {
-      FSK_TRY(half_step(true, 1));  // row-marginal error of the current (f, g)
-      FSK_TRY(launch_sum_to_double(FSK_F64, D(w.err), n, D(w.scalar), st));
-      FSK_HIP(hipMemcpyAsync(&e, D(w.scalar), sizeof(double), hipMemcpyDeviceToHost, st));
-      FSK_HIP(hipStreamSynchronize(st));
-      if (!std::isfinite(e)) {
-        if (iters_done) *iters_done = done;
-        if (err_out) *err_out = e;
-        return set_error(FSK_ENONFINITE, "marginal error is not finite after %d iterations", done);
+    if (poll) {
+      FSK_TRY(read_error(&e));
+      if (!std::isfinite(e)) return nonfinite(it, e);
+      if (e < o->tol) {
+        FSK_TRY(copy_state(true));
+        FSK_HIP(hipStreamSynchronize(st));
+        done = it;
+        converged = true;
+        break;
       }
-      if (e < o->tol) break;
     }
+    done = it + 1;
+  }
+  if (o->tol > 0.0 && !converged && done > 0) {  // the state after the last iteration is always polled
+    FSK_TRY(half_step(true, 1));
+    FSK_TRY(read_error(&e));
+    if (!std::isfinite(e)) return nonfinite(done, e);
   }
   if (iters_done) *iters_done = done;
   if (err_out) *err_out = e;

@@ -80,6 +80,14 @@ def test_tolerance_mode_and_cap(orc):
     check_potentials(orc, w.x, w.y, w.a, w.b, eps, f, g, fo2, go2)
     rows = orc.log_row_marginal_points(w.x, f, w.y, g, eps)
     assert err == pytest.approx(np.abs(rows - w.a).sum(), rel=0.05, abs=2e-7)
+    # the state handed back is exactly the one after `done` iterations (the iteration whose
+    # f-update revealed its error has been undone), also when every iteration is polled
+    ff, gf, _, _ = run_log(w.x, w.y, w.a, w.b, eps, done)
+    assert np.array_equal(f, ff) and np.array_equal(g, gf)
+    f1, g1, done1, err1 = run_log(w.x, w.y, w.a, w.b, eps, 3000, tol=1e-5, check_every=1)
+    assert done1 <= done and done - done1 < 5 and err1 < 1e-5
+    ff, gf, _, _ = run_log(w.x, w.y, w.a, w.b, eps, done1)
+    assert np.array_equal(f1, ff) and np.array_equal(g1, gf)
     f, g, done, err = run_log(w.x, w.y, w.a, w.b, eps, 9, tol=1e-30, check_every=4)
     assert done == 9 and err > 0
 
