@@ -123,7 +123,9 @@ def bench_dense(args, cfg):
                          "latency, not bandwidth")
     roofline = {"bound": "hbm", "achieved": achieved, "peak": PEAK_HBM_GBS, "unit": "GB/s",
                 "frac": achieved / PEAK_HBM_GBS,
-                "traffic": traffic_from_profile("dense_fused_cfg3_pmc.txt") if headline else None,
+                "traffic": traffic_from_profile("dense_fused_cfg3_pmc.txt") if headline
+                else traffic_from_profile("dense_fused_cfg2_pmc.txt")
+                if (cfg == 2 and args.flow == 0 and n == 8192 and c == 1) else None,
                 "kernel": {0: "fused_kernel", 3: "resident_kernel"}.get(args.flow, "rowpass_kernel+colpartial_kernel"),
                 "kernel_ms": stream_ms, "launches_per_step": launches,
                 "algorithmic_bytes_per_step": alg_bytes, "other_kernels_ms": other_ms}
@@ -271,7 +273,8 @@ def bench_batched(args):
         "config": {"workload": f"cfg5: n={n} fp32 dense K shared by m={m} Dirichlet(1) histogram "
                                f"pairs, x,y~U[0,1]^2, eps={w.eps}", "n": n, "m": m},
         "roofline": {"bound": "mfma", "achieved": achieved, "peak": PEAK_FP32_MFMA_TFLOPS,
-                     "unit": "TFLOP/s", "frac": achieved / PEAK_FP32_MFMA_TFLOPS, "traffic": None,
+                     "unit": "TFLOP/s", "frac": achieved / PEAK_FP32_MFMA_TFLOPS,
+                     "traffic": traffic_from_profile("batched_mfma_cfg5.txt") if (n == 16384 and m == 64) else None,
                      "kernel": "batched_prod_wide_kernel (both products)",
                      "kernel_ms": launch_ms, "launches_per_step": 2,
                      "note": "kernel_ms = event-timed run / product launches; includes the small reduce "

@@ -426,12 +426,14 @@ __global__ __launch_bounds__(512) void fused_kernel(const T* __restrict__ K, int
 
   // Two register sets alternate: while one group is being reduced the next one is
   // already in flight, across row-block boundaries too.
+  // The step after the last one is not fetched: at 8 steps per workgroup (n = 8192) a redundant
+  // group would be an eighth of the kernel's reads.
   load_group(bufA, mgA, odA, 0);
   for (int t = 0; t < total; t += 2) {
-    load_group(bufB, mgB, odB, t + 1);
+    if (t + 1 < total) load_group(bufB, mgB, odB, t + 1);
     process(bufA, mgA, odA, t, 0);
     if (t + 1 >= total) break;
-    load_group(bufA, mgA, odA, t + 2);
+    if (t + 2 < total) load_group(bufA, mgA, odA, t + 2);
     process(bufB, mgB, odB, t + 1, 1);
   }
 }
