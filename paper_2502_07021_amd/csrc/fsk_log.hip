@@ -43,26 +43,44 @@ constexpr int kLogChunk = 4;          // columns reduced together
 constexpr float kLogRaise = 16.0f;    // raise the reference when a chunk exceeds it by this much
 
 // ---------------------------------------------------------------- preparation
-// mu[k] = mean over both clouds of coordinate k (fp64, fixed order).
-template <typename T>
-__global__ __launch_bounds__(1024) void log_mean_kernel(const T* __restrict__ x,
-                                                        const T* __restrict__ y, int n, int d,
-                                                        double* __restrict__ mu) {
-  __shared__ double sm[16];
-  for (int k = 0; k < d; ++k) {
-    double s = 0.0;
-    for (int i = threadIdx.x; i < n; i += 1024)
-      s += (double)x[(int64_t)i * d + k] + (double)y[(int64_t)i * d + k];
-    s = wave_sum(s);
-    if ((threadIdx.x & 63) == 0) sm[threadIdx.x >> 6] = s;
-    __syncthreads();
-    if (threadIdx.x == 0) {
-      double t = 0.0;
-      for (int w = 0; w < 16; ++w) t += sm[w];
-      mu[k] = t / (2.0 * n);
-    }
-    __syncthreads();
+// mu[k] = mean over both clouds of coordinate k (fp64, fixed order): every workgroup sums its
+// points once for all coordinates (a point's d values are contiguous), a second launch adds
+// the workgroups' sums in order.  Any mu would do -- it only centres the clouds -- but a fixed
+// order keeps runs reproducible.
+constexpr int kLogMeanGroups = 256;
+
+template <typename T, int DP>
+__global__ __launch_bounds__(256) void log_mean_partial_kernel(const T* __restrict__ x,
+                                                               const T* __restrict__ y, int n, int d,
+                                                               double* __restrict__ partial) {
+  __shared__ double sm[4][DP];
+  double s[DP];
+#pragma unroll
+  for (int k = 0; k < DP; ++k) s[k] = 0.0;
+  for (int i = blockIdx.x * 256 + threadIdx.x; i < n; i += gridDim.x * 256) {
+#pragma unroll
+    for (int k = 0; k < DP; ++k)
+      if (k < d) s[k] += (double)x[(int64_t)i * d + k] + (double)y[(int64_t)i * d + k];
   }
+#pragma unroll
+  for (int k = 0; k < DP; ++k) {
+    const double t = wave_sum(s[k]);
+    if ((threadIdx.x & 63) == 0) sm[threadIdx.x >> 6][k] = t;
+  }
+  __syncthreads();
+  if (threadIdx.x < DP)
+    partial[(int64_t)blockIdx.x * DP + threadIdx.x] =
+        ((sm[0][threadIdx.x] + sm[1][threadIdx.x]) + sm[2][threadIdx.x]) + sm[3][threadIdx.x];
+}
+
+__global__ __launch_bounds__(64) void log_mean_final_kernel(const double* __restrict__ partial,
+                                                            int groups, int dp, int n,
+                                                            double* __restrict__ mu) {
+  const int k = threadIdx.x;
+  if (k >= dp) return;
+  double t = 0.0;
+  for (int g = 0; g < groups; ++g) t += partial[(int64_t)g * dp + k];
+  mu[k] = t / (2.0 * n);
 }
 
 // Per point of one cloud: centred coordinates (column role), 2s-scaled centred
@@ -394,8 +412,20 @@ static int run_log_typed(const fsk_opts* o, const void* x, const void* y, int d,
   T *ff = (T*)f, *gf = (T*)g;
   const int nb = (n + 255) / 256;
 
-  hipLaunchKernelGGL((log_mean_kernel<T>), dim3(1), dim3(1024), 0, st, xf, yf, n, d, D(w.mu));
-  FSK_LAUNCH_CHECK("log_mean_kernel");
+  {  // the (still unused) slice area holds the per-workgroup coordinate sums
+    int groups = (n + 255) / 256;
+    if (groups > kLogMeanGroups) groups = kLogMeanGroups;
+    double* part = D(w.pm);
+    switch (w.dp) {
+      case 4: hipLaunchKernelGGL((log_mean_partial_kernel<T, 4>), dim3(groups), dim3(256), 0, st, xf, yf, n, d, part); break;
+      case 8: hipLaunchKernelGGL((log_mean_partial_kernel<T, 8>), dim3(groups), dim3(256), 0, st, xf, yf, n, d, part); break;
+      case 16: hipLaunchKernelGGL((log_mean_partial_kernel<T, 16>), dim3(groups), dim3(256), 0, st, xf, yf, n, d, part); break;
+      default: hipLaunchKernelGGL((log_mean_partial_kernel<T, 32>), dim3(groups), dim3(256), 0, st, xf, yf, n, d, part); break;
+    }
+    FSK_LAUNCH_CHECK("log_mean_partial_kernel");
+    hipLaunchKernelGGL(log_mean_final_kernel, dim3(1), dim3(64), 0, st, (const double*)part, groups, w.dp, n, D(w.mu));
+    FSK_LAUNCH_CHECK("log_mean_final_kernel");
+  }
   hipLaunchKernelGGL((log_prep_kernel<T>), dim3(nb), dim3(256), 0, st, xf, af, ff, n, d, w.dp, s,
                      D(w.mu), D(w.xc), D(w.xs), D(w.nx2), D(w.lna), D(w.fd), D(w.bx));
   FSK_LAUNCH_CHECK("log_prep_kernel");
