@@ -90,7 +90,29 @@ __device__ __forceinline__ double sqdist(const T* __restrict__ xi, const T* __re
   return s;
 }
 
-template <typename T>
+// The same sum with y_j already in registers (DP >= d values, zero padded) and the terms in
+// the same order, so that both forms round alike.
+template <typename T, int DP>
+__device__ __forceinline__ double sqdist_reg(const T* __restrict__ xi, const double (&yj)[DP], int d) {
+  double s = 0.0;
+#pragma unroll
+  for (int k = 0; k < DP; ++k)
+    if (k < d) {
+      const double t = (double)xi[k] - yj[k];
+      s += t * t;
+    }
+  return s;
+}
+
+template <typename T, int DP>
+__device__ __forceinline__ void load_point(const T* __restrict__ p, int d, double (&out)[DP]) {
+#pragma unroll
+  for (int k = 0; k < DP; ++k) out[k] = k < d ? (double)p[k] : 0.0;
+}
+
+// DP > 0: d <= DP and y_j is held in registers for the tile's 16 rows; DP == 0: any d, y_j
+// re-read per row.
+template <typename T, int DP>
 __global__ __launch_bounds__(256) void max_sqdist_kernel(const T* __restrict__ x,
                                                          const T* __restrict__ y, int n, int d,
                                                          double* __restrict__ wg_max) {
@@ -98,10 +120,13 @@ __global__ __launch_bounds__(256) void max_sqdist_kernel(const T* __restrict__ x
   const int i0 = blockIdx.y * kSetupRows;
   double m = 0.0;
   if (j < n) {
+    double yj[DP > 0 ? DP : 1];
+    if (DP > 0) load_point<T, (DP > 0 ? DP : 1)>(y + (int64_t)j * d, d, yj);
     for (int r = 0; r < kSetupRows; ++r) {
       const int i = i0 + r;
       if (i < n) {
-        const double s = sqdist(x + (int64_t)i * d, y + (int64_t)j * d, d);
+        const double s = DP > 0 ? sqdist_reg<T, (DP > 0 ? DP : 1)>(x + (int64_t)i * d, yj, d)
+                                : sqdist(x + (int64_t)i * d, y + (int64_t)j * d, d);
         m = s > m ? s : m;
       }
     }
@@ -141,12 +166,19 @@ int launch_max_sqdist(int dtype, const void* x, const void* y, int n, int d, dou
   const size_t need = max_sqdist_scratch_doubles(n);
   if (scratch_doubles < need) return set_error(FSK_EWORKSPACE, "max-cost scratch too small");
   dim3 grid((n + 255) / 256, (n + kSetupRows - 1) / kSetupRows), block(256);
-  if (dtype == FSK_F64)
-    hipLaunchKernelGGL((max_sqdist_kernel<double>), grid, block, 0, stream, (const double*)x,
-                       (const double*)y, n, d, scratch);
-  else
-    hipLaunchKernelGGL((max_sqdist_kernel<float>), grid, block, 0, stream, (const float*)x,
-                       (const float*)y, n, d, scratch);
+#define FSK_MAXSQ(TT, DPV)                                                                        \
+  hipLaunchKernelGGL((max_sqdist_kernel<TT, DPV>), grid, block, 0, stream, (const TT*)x,         \
+                     (const TT*)y, n, d, scratch)
+  if (dtype == FSK_F64) {
+    if (d <= 4) FSK_MAXSQ(double, 4); else if (d <= 8) FSK_MAXSQ(double, 8);
+    else if (d <= 16) FSK_MAXSQ(double, 16); else if (d <= 32) FSK_MAXSQ(double, 32);
+    else FSK_MAXSQ(double, 0);
+  } else {
+    if (d <= 4) FSK_MAXSQ(float, 4); else if (d <= 8) FSK_MAXSQ(float, 8);
+    else if (d <= 16) FSK_MAXSQ(float, 16); else if (d <= 32) FSK_MAXSQ(float, 32);
+    else FSK_MAXSQ(float, 0);
+  }
+#undef FSK_MAXSQ
   FSK_LAUNCH_CHECK("max_sqdist_kernel");
   hipLaunchKernelGGL(max_reduce_kernel, dim3(1), dim3(1024), 0, stream, scratch, (int64_t)need,
                      cmax_dev);
@@ -154,7 +186,7 @@ int launch_max_sqdist(int dtype, const void* x, const void* y, int n, int d, dou
   return FSK_OK;
 }
 
-template <typename T>
+template <typename T, int DP>
 __global__ __launch_bounds__(256) void gibbs_from_points_kernel(const T* __restrict__ x,
                                                                 const T* __restrict__ y, int n,
                                                                 int d, double eps,
@@ -164,10 +196,13 @@ __global__ __launch_bounds__(256) void gibbs_from_points_kernel(const T* __restr
   const int i0 = blockIdx.y * kSetupRows;
   const double cmax = cmax_dev ? *cmax_dev : 1.0;
   if (j >= n) return;
+  double yj[DP > 0 ? DP : 1];
+  if (DP > 0) load_point<T, (DP > 0 ? DP : 1)>(y + (int64_t)j * d, d, yj);
   for (int r = 0; r < kSetupRows; ++r) {
     const int i = i0 + r;
     if (i < n) {
-      const double s = sqdist(x + (int64_t)i * d, y + (int64_t)j * d, d);
+      const double s = DP > 0 ? sqdist_reg<T, (DP > 0 ? DP : 1)>(x + (int64_t)i * d, yj, d)
+                              : sqdist(x + (int64_t)i * d, y + (int64_t)j * d, d);
       K[(int64_t)i * ldK + j] = (T)exp(-(s / cmax) / eps);
     }
   }
@@ -176,12 +211,19 @@ __global__ __launch_bounds__(256) void gibbs_from_points_kernel(const T* __restr
 int launch_gibbs_from_points(int dtype, const void* x, const void* y, int n, int d, double eps,
                              const double* cmax_dev, void* K, int64_t ldK, hipStream_t stream) {
   dim3 grid((n + 255) / 256, (n + kSetupRows - 1) / kSetupRows), block(256);
-  if (dtype == FSK_F64)
-    hipLaunchKernelGGL((gibbs_from_points_kernel<double>), grid, block, 0, stream,
-                       (const double*)x, (const double*)y, n, d, eps, cmax_dev, (double*)K, ldK);
-  else
-    hipLaunchKernelGGL((gibbs_from_points_kernel<float>), grid, block, 0, stream, (const float*)x,
-                       (const float*)y, n, d, eps, cmax_dev, (float*)K, ldK);
+#define FSK_GIBBS(TT, DPV)                                                                        \
+  hipLaunchKernelGGL((gibbs_from_points_kernel<TT, DPV>), grid, block, 0, stream, (const TT*)x,  \
+                     (const TT*)y, n, d, eps, cmax_dev, (TT*)K, ldK)
+  if (dtype == FSK_F64) {
+    if (d <= 4) FSK_GIBBS(double, 4); else if (d <= 8) FSK_GIBBS(double, 8);
+    else if (d <= 16) FSK_GIBBS(double, 16); else if (d <= 32) FSK_GIBBS(double, 32);
+    else FSK_GIBBS(double, 0);
+  } else {
+    if (d <= 4) FSK_GIBBS(float, 4); else if (d <= 8) FSK_GIBBS(float, 8);
+    else if (d <= 16) FSK_GIBBS(float, 16); else if (d <= 32) FSK_GIBBS(float, 32);
+    else FSK_GIBBS(float, 0);
+  }
+#undef FSK_GIBBS
   FSK_LAUNCH_CHECK("gibbs_from_points_kernel");
   return FSK_OK;
 }
