@@ -159,7 +159,8 @@ static int colpartial_typed(const void* K, int64_t ld, int n, int rows, int c0, 
   (void)n;
   const int nvec = vec_hi - vec_lo;
   dim3 block(256);
-  if (nvec >= 4096) {  // wide: 16 KiB of every row per workgroup (needs several column tiles)
+  // wide and tall enough for >= 1024 workgroups of the wide shape: 16 KiB of every row per workgroup
+  if (nvec >= 4096 && (int64_t)((nvec + 1023) / 1024) * col_strips(rows) >= 1024) {
     dim3 grid((nvec + 1023) / 1024, col_strips(rows));
     hipLaunchKernelGGL((colpartial_kernel<T, 4>), grid, block, 0, stream, (const T*)K, ld, rows,
                        vec_lo, vec_hi, (const T*)u, (T*)partial, ld_ws);
