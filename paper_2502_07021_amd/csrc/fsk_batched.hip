@@ -31,7 +31,7 @@ namespace fsk {
 
 typedef float floatx16 __attribute__((ext_vector_type(16)));
 
-constexpr int kBtCols = 64;        // histogram columns per call (m <= 64)
+constexpr int kBtCols = 64;        // histogram columns per launch (wider problems go in groups)
 constexpr int kBtWaveTile = 64;    // output rows per wave
 constexpr int kBtWaves = 4;
 constexpr int kBtTile = kBtWaveTile * kBtWaves;  // output rows per workgroup
@@ -44,11 +44,12 @@ __device__ __forceinline__ floatx16 mfma32(float a, float b, floatx16 c) {
 }
 
 // Q = K X by the direct walk: out rows are rows of K, contraction over columns, a lane
-// fetches its row's values of a chunk as 128-bit loads.  X is the n x m operand.
-// final != 0: out = marg ./ product; else the partial product of this grid slice goes to
-// out + slice * n * m.
+// fetches its row's values of a chunk as 128-bit loads.  X holds the n x m operand (m <= 64
+// columns of a wider matrix with row pitch ldm).  final != 0: out = marg ./ product, with marg
+// and out laid out like X; else the partial product of this grid slice goes, densely packed
+// (pitch m), to out + slice * n * m.
 __global__ __launch_bounds__(256) void batched_rowprod_kernel(const float* __restrict__ K, int64_t ld,
-                                                           int n, int m,
+                                                           int n, int m, int64_t ldm,
                                                            const float* __restrict__ X,
                                                            const float* __restrict__ marg,
                                                            float* __restrict__ out, int final) {
@@ -113,13 +114,13 @@ __global__ __launch_bounds__(256) void batched_rowprod_kernel(const float* __res
   const float* xcol = X + (sc < m ? sc : m - 1);
   auto load_x = [&](int c, float(&st)[kBtStage]) {  // whole chunk: every contraction index < n
 #pragma unroll
-    for (int i = 0; i < kBtStage; ++i) st[i] = xcol[(int64_t)(c * kBtChunk + sk + 4 * i) * m];
+    for (int i = 0; i < kBtStage; ++i) st[i] = xcol[(int64_t)(c * kBtChunk + sk + 4 * i) * ldm];
   };
   auto load_x_masked = [&](int c, float(&st)[kBtStage]) {  // ragged chunk: indices >= n give zero
 #pragma unroll
     for (int i = 0; i < kBtStage; ++i) {
       const int kk = c * kBtChunk + sk + 4 * i;
-      const float val = xcol[(int64_t)(kk < n ? kk : n - 1) * m];
+      const float val = xcol[(int64_t)(kk < n ? kk : n - 1) * ldm];
       st[i] = kk < n ? val : 0.f;
     }
   };
@@ -196,8 +197,12 @@ __global__ __launch_bounds__(256) void batched_rowprod_kernel(const float* __res
         for (int b = 0; b < 2; ++b) {
           const int col = 32 * b + r;
           if (col < m) {
-            const int64_t idx = (int64_t)row * m + col;
-            dst[idx] = final ? marg[idx] / acc[a][b][v] : acc[a][b][v];
+            if (final) {
+              const int64_t idx = (int64_t)row * ldm + col;
+              dst[idx] = marg[idx] / acc[a][b][v];
+            } else {
+              dst[(int64_t)row * m + col] = acc[a][b][v];
+            }
           }
         }
       }
@@ -215,6 +220,7 @@ constexpr int kBtWideTile = kBtWideWaveTile * kBtWaves;
 
 __global__ __launch_bounds__(256) void batched_prod_wide_kernel(const float* __restrict__ K,
                                                                 int64_t ld, int n, int m,
+                                                                int64_t ldm,
                                                                 const float* __restrict__ X,
                                                                 const float* __restrict__ marg,
                                                                 float* __restrict__ out, int final,
@@ -270,13 +276,13 @@ __global__ __launch_bounds__(256) void batched_prod_wide_kernel(const float* __r
   const float* xcol = X + (sc < m ? sc : m - 1);
   auto load_x = [&](int c, float(&st)[kBtStage]) {
 #pragma unroll
-    for (int i = 0; i < kBtStage; ++i) st[i] = xcol[(int64_t)(c * kBtChunk + sk + 4 * i) * m];
+    for (int i = 0; i < kBtStage; ++i) st[i] = xcol[(int64_t)(c * kBtChunk + sk + 4 * i) * ldm];
   };
   auto load_x_masked = [&](int c, float(&st)[kBtStage]) {
 #pragma unroll
     for (int i = 0; i < kBtStage; ++i) {
       const int kk = c * kBtChunk + sk + 4 * i;
-      const float val = xcol[(int64_t)(kk < n ? kk : n - 1) * m];
+      const float val = xcol[(int64_t)(kk < n ? kk : n - 1) * ldm];
       st[i] = kk < n ? val : 0.f;
     }
   };
@@ -330,7 +336,7 @@ __global__ __launch_bounds__(256) void batched_prod_wide_kernel(const float* __r
         b1[e + 2] = xs[buf][kBtHalf * h + e + 2][32 + r];
       }
       kn[e] = load_pack_stream(kcol + (int64_t)(first + e) * ld);
-      if (e < kBtStage) stn[e] = xcol[(int64_t)(cn * kBtChunk + sk + 4 * e) * m];  // early: stored at the chunk's end
+      if (e < kBtStage) stn[e] = xcol[(int64_t)(cn * kBtChunk + sk + 4 * e) * ldm];  // early: stored at the chunk's end
       __builtin_amdgcn_sched_barrier(0);
     }
   };
@@ -383,8 +389,12 @@ __global__ __launch_bounds__(256) void batched_prod_wide_kernel(const float* __r
         for (int b = 0; b < 2; ++b) {
           const int col = 32 * b + r;
           if (col < m) {
-            const int64_t idx = (int64_t)row * m + col;
-            dst[idx] = final ? marg[idx] / acc[a][b][v] : acc[a][b][v];
+            if (final) {
+              const int64_t idx = (int64_t)row * ldm + col;
+              dst[idx] = marg[idx] / acc[a][b][v];
+            } else {
+              dst[(int64_t)row * m + col] = acc[a][b][v];
+            }
           }
         }
       }
@@ -445,12 +455,41 @@ size_t batched_workspace_bytes(int n, int m) {
   return batched_partial_bytes(n, m) + align_up((size_t)n * (size_t)batched_ldt(n) * 4, 256) + 256;
 }
 
+// out[row][col] = marg[row][col] / sum_s partial[s][row][col] for one column group: the partial
+// tiles are dense (pitch cols), marg and out are `cols` columns of matrices with pitch ldm.
+// The slices are added in slice order.
+template <bool VEC>  // VEC: cols, ldm and the column offset are multiples of 4 -> 16-byte accesses
+__global__ __launch_bounds__(256) void batched_reduce_kernel(const float* __restrict__ partial,
+                                                             int slices, int n, int cols, int64_t ldm,
+                                                             const float* __restrict__ marg,
+                                                             float* __restrict__ out) {
+  constexpr int E = VEC ? 4 : 1;
+  const int64_t total = (int64_t)n * cols;
+  const int64_t idx = ((int64_t)blockIdx.x * 256 + threadIdx.x) * E;
+  if (idx >= total) return;
+  const int64_t o = (idx / cols) * ldm + idx % cols;
+  if (VEC) {
+    Pack<float> s = load_pack(partial + idx);
+    for (int k = 1; k < slices; ++k) {
+      const Pack<float> y = load_pack(partial + (int64_t)k * total + idx);
+#pragma unroll
+      for (int e = 0; e < 4; ++e) s.e[e] += y.e[e];
+    }
+    const Pack<float> mg = load_pack(marg + o);
+#pragma unroll
+    for (int e = 0; e < 4; ++e) s.e[e] = mg.e[e] / s.e[e];
+    store_pack(out + o, s);
+  } else {
+    float s = partial[idx];
+    for (int k = 1; k < slices; ++k) s += partial[(int64_t)k * total + idx];
+    out[o] = marg[o] / s;
+  }
+}
+
 int run_sinkhorn_batched(const fsk_opts* o, const void* K, int64_t ldK, const void* A, const void* B,
                          void* U, void* V, void* workspace, size_t ws_bytes, const fsk_dp* dp,
                          hipStream_t st) {
   if (o->dtype != FSK_F32) return set_error(FSK_EUNSUPPORTED, "batched path takes fp32");
-  if (o->m > kBtCols)
-    return set_error(FSK_EUNSUPPORTED, "batched path is built for m <= 64 histograms per call");
   const int n = o->n, m = o->m;
   const int S = batched_splits(n);
   const size_t part_bytes = batched_partial_bytes(n, m);
@@ -471,29 +510,47 @@ int run_sinkhorn_batched(const fsk_opts* o, const void* K, int64_t ldK, const vo
   dim3 grid((n + kBtTile - 1) / kBtTile, S), block(256);
   const int SW = batched_splits_wide(n);
   dim3 gridw(((n + kBtWideTile - 1) / kBtWideTile) * SW);
-  const int nm = n * m;
-  auto reduce = [&](int slices, const float* marg, float* dst) -> int {
-    return launch_colreduce(FSK_F32, part, nm, slices, 0, nm, marg, nullptr, dst, kEpiDivide, 1.0, st);
+  // The m histogram columns go through the kernels in groups of up to 64 (the kernels' tile
+  // width); a group costs one pass over K per product, so the time grows with ceil(m / 64).
+  // The partial area is reused by every group (the launches are ordered on the stream).
+  auto reduce = [&](int slices, int cols, const float* marg, float* dst) -> int {
+    const int64_t total = (int64_t)n * cols;
+    const bool vec = cols % 4 == 0 && m % 4 == 0 && ((uintptr_t)marg % 16 == 0) && ((uintptr_t)dst % 16 == 0);
+    if (vec)
+      hipLaunchKernelGGL(batched_reduce_kernel<true>, dim3((unsigned)((total / 4 + 255) / 256)), dim3(256),
+                         0, st, (const float*)part, slices, n, cols, (int64_t)m, marg, dst);
+    else
+      hipLaunchKernelGGL(batched_reduce_kernel<false>, dim3((unsigned)((total + 255) / 256)), dim3(256), 0,
+                         st, (const float*)part, slices, n, cols, (int64_t)m, marg, dst);
+    FSK_LAUNCH_CHECK("batched_reduce_kernel");
+    return FSK_OK;
   };
   for (int it = 0; it < o->max_iters; ++it) {
-    if (use_kt) {  // Q = K V as the transposed product of K^T
-      hipLaunchKernelGGL(batched_prod_wide_kernel, gridw, block, 0, st, (const float*)Kt, ldt, n, m,
-                         (const float*)Vf, Af, SW == 1 ? Uf : part, SW == 1 ? 1 : 0, SW);
-      FSK_LAUNCH_CHECK("batched_prod_wide_kernel (K V)");
-      if (SW > 1) FSK_TRY(reduce(SW, Af, Uf));
-    } else {
-      hipLaunchKernelGGL(batched_rowprod_kernel, grid, block, 0, st, Kf, ldK, n, m,
-                         (const float*)Vf, Af, S == 1 ? Uf : part, S == 1 ? 1 : 0);
-      FSK_LAUNCH_CHECK("batched_rowprod_kernel (K V)");
-      if (S > 1) FSK_TRY(reduce(S, Af, Uf));
+    for (int c0 = 0; c0 < m; c0 += kBtCols) {  // U = A ./ (K V), column group by column group
+      const int cols = m - c0 < kBtCols ? m - c0 : kBtCols;
+      if (use_kt) {  // Q = K V as the transposed product of K^T
+        hipLaunchKernelGGL(batched_prod_wide_kernel, gridw, block, 0, st, (const float*)Kt, ldt, n, cols,
+                           (int64_t)m, (const float*)Vf + c0, Af + c0, SW == 1 ? Uf + c0 : part,
+                           SW == 1 ? 1 : 0, SW);
+        FSK_LAUNCH_CHECK("batched_prod_wide_kernel (K V)");
+        if (SW > 1) FSK_TRY(reduce(SW, cols, Af + c0, Uf + c0));
+      } else {
+        hipLaunchKernelGGL(batched_rowprod_kernel, grid, block, 0, st, Kf, ldK, n, cols, (int64_t)m,
+                           (const float*)Vf + c0, Af + c0, S == 1 ? Uf + c0 : part, S == 1 ? 1 : 0);
+        FSK_LAUNCH_CHECK("batched_rowprod_kernel (K V)");
+        if (S > 1) FSK_TRY(reduce(S, cols, Af + c0, Uf + c0));
+      }
     }
-    if (dp)
+    if (dp)  // the release clips every row across ALL m targets
       FSK_TRY(launch_dp_release(FSK_F32, Uf, n, m, dp->clip_u, dp->sigma_u, dp->seed,
                                 dp->release0 + 2 * (uint64_t)it, st));
-    hipLaunchKernelGGL(batched_prod_wide_kernel, gridw, block, 0, st, Kf, ldK, n, m,
-                       (const float*)Uf, Bf, SW == 1 ? Vf : part, SW == 1 ? 1 : 0, SW);
-    FSK_LAUNCH_CHECK("batched_prod_wide_kernel (K^T U)");
-    if (SW > 1) FSK_TRY(reduce(SW, Bf, Vf));
+    for (int c0 = 0; c0 < m; c0 += kBtCols) {  // V = B ./ (K^T U)
+      const int cols = m - c0 < kBtCols ? m - c0 : kBtCols;
+      hipLaunchKernelGGL(batched_prod_wide_kernel, gridw, block, 0, st, Kf, ldK, n, cols, (int64_t)m,
+                         (const float*)Uf + c0, Bf + c0, SW == 1 ? Vf + c0 : part, SW == 1 ? 1 : 0, SW);
+      FSK_LAUNCH_CHECK("batched_prod_wide_kernel (K^T U)");
+      if (SW > 1) FSK_TRY(reduce(SW, cols, Bf + c0, Vf + c0));
+    }
     if (dp)
       FSK_TRY(launch_dp_release(FSK_F32, Vf, n, m, dp->clip_v, dp->sigma_v, dp->seed,
                                 dp->release0 + 2 * (uint64_t)it + 1, st));

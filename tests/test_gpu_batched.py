@@ -72,10 +72,15 @@ def test_batched_column_equals_single_histogram_run(orc):
         assert relerr(U[:, k], u) <= 2e-5 and relerr(V[:, k], v) <= 2e-5
 
 
-def test_more_than_64_histograms_is_refused():
-    opts = api.make_opts(128, torch.float32, m=65, max_iters=1)
-    K = torch.ones(128, 128, device="cuda"); X = torch.ones(128, 65, device="cuda")
-    with pytest.raises(api.FskError) as e:
-        api.fsk_sinkhorn_batched(opts, K, X, X, X.clone(), X.clone(),
-                                 torch.empty(1 << 24, dtype=torch.uint8, device="cuda"))
-    assert e.value.status == api.FSK_EUNSUPPORTED
+@pytest.mark.parametrize("n,m,small", [(300, 65, False), (513, 130, False), (1000, 200, False),
+                                         (257, 67, True), (400, 500, False)])
+def test_more_than_64_histograms_go_in_column_groups(orc, n, m, small):
+    """The paper stacks hundreds of targets: columns beyond 64 are served in groups of 64, each
+    column still an independent run."""
+    K, A, B = problem(orc, n, m, 1300 + n + m)
+    Uo, Vo = orc.sinkhorn_batched(K, A, B, 7)
+    U, V = run_batched(K, A, B, 7, small_workspace=small)
+    assert relerr(U, Uo) <= 1e-4 and relerr(V, Vo) <= 1e-4
+    for k in (0, 63, 64, m - 1):
+        cm = orc.col_marginal(K, U[:, k], V[:, k])
+        assert relerr(cm, B[:, k]) <= 1e-4

@@ -76,3 +76,17 @@ def test_batched_dp_matches_oracle_and_resumes(orc):
         api.fsk_sinkhorn_batched_dp(opts, Kd[:, :n], A, B, Un, Vn, api.fsk_dp(1.0, 1.0, 0.1, 0.1, 1, 3), ws)
     with pytest.raises(api.FskError):
         api.fsk_sinkhorn_batched_dp(opts, Kd[:, :n], A, B, Un, Vn, api.fsk_dp(1.0, 1.0, -0.1, 0.1, 1, 0), ws)
+
+
+def test_batched_dp_with_more_than_64_targets(orc):
+    """The release clips a row across ALL targets, also when the products run in column groups."""
+    n, m, iters = 260, 100, 4
+    w = workloads.make(5, n=n, m=m)
+    K, _ = orc.gibbs_from_points_f32(w.x, w.y, 0.2, False)
+    Uo, Vo = orc.sinkhorn_batched_dp(K, w.a, w.b, iters, 9.0, 8.0, 0.02, 0.01, 5, 0)
+    opts = api.make_opts(n, torch.float32, m=m, max_iters=iters)
+    ws = api.alloc_workspace(opts, api.FSK_MODE_BATCHED)
+    U = torch.ones(n, m, device="cuda"); V = torch.ones(n, m, device="cuda")
+    api.fsk_sinkhorn_batched_dp(opts, dev(K), dev(w.a), dev(w.b), U, V, api.fsk_dp(9.0, 8.0, 0.02, 0.01, 5, 0), ws)
+    torch.cuda.synchronize()
+    assert relerr(U.cpu().numpy(), Uo) <= 1e-4 and relerr(V.cpu().numpy(), Vo) <= 1e-4
