@@ -15,7 +15,7 @@ CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libfsk.so")
 
-SOURCES = ["fsk_api.hip", "fsk_dense.hip", "fsk_setup.hip", "fsk_log.hip", "fsk_batched.hip", "fsk_dp.hip", "fsk_resident.hip"]
+SOURCES = ["fsk_api.hip", "fsk_dense.hip", "fsk_setup.hip", "fsk_log.hip", "fsk_batched.hip", "fsk_batched64.hip", "fsk_dp.hip", "fsk_resident.hip"]
 
 # packed-fp32 VALU forms are switched off on purpose (compiler-generated v_pk_*_f32 is not
 # trusted on the target boxes); everything else is stock -O3 for gfx950.

@@ -128,7 +128,9 @@ size_t fsk_workspace_bytes(const fsk_opts* opts, int mode, int d) {
     case FSK_MODE_LOG: return log_workspace_bytes(opts->n, d);
     case FSK_MODE_PLAN: return plan_ws_bytes(opts);
     case FSK_MODE_RADIUS: return align_up(dense_ws(opts).total, 256) + plan_ws_bytes(opts);
-    case FSK_MODE_BATCHED: return batched_workspace_bytes(opts->n, opts->m);
+    case FSK_MODE_BATCHED:
+      return opts->dtype == FSK_F64 ? batched_f64_workspace_bytes(opts->n, opts->m)
+                                    : batched_workspace_bytes(opts->n, opts->m);
     case FSK_MODE_SETUP: return align_up(max_sqdist_scratch_doubles(opts->n) * 8, 256) + 256;
     default: return 0;
   }

@@ -489,7 +489,8 @@ __global__ __launch_bounds__(256) void batched_reduce_kernel(const float* __rest
 int run_sinkhorn_batched(const fsk_opts* o, const void* K, int64_t ldK, const void* A, const void* B,
                          void* U, void* V, void* workspace, size_t ws_bytes, const fsk_dp* dp,
                          hipStream_t st) {
-  if (o->dtype != FSK_F32) return set_error(FSK_EUNSUPPORTED, "batched path takes fp32");
+  if (o->dtype == FSK_F64)
+    return run_sinkhorn_batched_f64(o, K, ldK, A, B, U, V, workspace, ws_bytes, dp, st);
   const int n = o->n, m = o->m;
   const int S = batched_splits(n);
   const size_t part_bytes = batched_partial_bytes(n, m);

@@ -1,0 +1,302 @@
+// Multitarget Sinkhorn in fp64 for gfx950 (paper: Sec. 5.3.2; the paper's own multitarget runs
+// store everything in double precision): the same plan as the fp32 path -- both products run
+// as transposed products R = K^T X, the second one on a copy of K^T built once per call -- on
+// v_mfma_f64_16x16x4_f64.
+//
+// MFMA 16x16x4 f64 operand layout (lane l of 64, measured): A[i = l%16][k = l/16],
+// B[k = l/16][j = l%16], D[i = 4 v + l/16][j = l%16] for accumulator element v of 4.
+//
+// A wave owns a 64 x 64 output tile: 4 x 4 MFMA blocks, 64 fp64 accumulators (128 registers).
+// A lane fetches four adjacent columns of K (two 128-bit loads, 512 contiguous bytes per
+// quarter-wave), so MFMA row i of block a is column o0 + 4 i + a of K.  A chunk is 32
+// contraction indices = 8 MFMA k-steps; quarter-wave q supplies indices 8 q + e of the chunk at
+// k-step e.  The 32 x 64 chunk of the n x m operand is shared by the workgroup's four waves
+// through LDS (double buffered, one barrier per chunk); the next chunk's loads are spread
+// between the MFMAs of the current one (a wave issues in order: a burst of loads would starve
+// the matrix pipe).  The contraction range is split over grid slices; partial tiles go to the
+// workspace and a reduction kernel adds them in slice order and divides.
+#include "fsk_device.h"
+#include "fsk_internal.h"
+
+namespace fsk {
+
+typedef double doublex4 __attribute__((ext_vector_type(4)));
+
+constexpr int kB64Cols = 64;       // histogram columns per launch
+constexpr int kB64WaveTile = 64;   // output rows per wave
+constexpr int kB64Tile = 4 * kB64WaveTile;
+constexpr int kB64Chunk = 32;      // contraction indices per chunk
+constexpr int kB64Steps = kB64Chunk / 4;  // MFMA k-steps per chunk
+constexpr int kB64Stage = kB64Chunk * kB64Cols / 256;
+
+struct K4 { Pack<double> lo, hi; };  // four adjacent columns of one row of K
+
+__global__ __launch_bounds__(256) void batched_prod_f64_kernel(const double* __restrict__ K, int64_t ld,
+                                                               int n, int m, int64_t ldm,
+                                                               const double* __restrict__ X,
+                                                               const double* __restrict__ marg,
+                                                               double* __restrict__ out, int final,
+                                                               int slices) {
+  __shared__ double xs[2][kB64Chunk][kB64Cols];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int r = lane & 15, q = lane >> 4;
+  // 1-D grid, slice fastest: the workgroups of one contraction slice share rows of X in an XCD's L2
+  const int slice = blockIdx.x % slices, tile = blockIdx.x / slices;
+  const int o0 = tile * kB64Tile + wave * kB64WaveTile;
+
+  const int nchunks = (n + kB64Chunk - 1) / kB64Chunk;
+  const int per = (nchunks + slices - 1) / slices;
+  int c0 = slice * per;
+  int c1 = c0 + per < nchunks ? c0 + per : nchunks;
+  if (c0 > c1) c0 = c1;
+  int full_end = n / kB64Chunk < c1 ? n / kB64Chunk : c1;
+  if (full_end < c0) full_end = c0;
+
+  doublex4 acc[4][4];
+#pragma unroll
+  for (int a = 0; a < 4; ++a)
+#pragma unroll
+    for (int b = 0; b < 4; ++b)
+#pragma unroll
+      for (int v = 0; v < 4; ++v) acc[a][b][v] = 0.0;
+
+  // two 16-byte column pairs per lane, each clamped inside the row pitch (clamped duplicates
+  // only feed output rows >= n, which are never stored)
+  const int jmax = (int)ld - 2;
+  const int j0 = o0 + 4 * r < jmax ? o0 + 4 * r : jmax;
+  const int j1 = o0 + 4 * r + 2 < jmax ? o0 + 4 * r + 2 : jmax;
+  const double* kc0 = K + j0;
+  const double* kc1 = K + j1;
+
+  auto load_k = [&](int c, K4(&ka)[kB64Steps]) {
+    const int first = c * kB64Chunk + kB64Steps * q;
+#pragma unroll
+    for (int e = 0; e < kB64Steps; ++e) {
+      ka[e].lo = load_pack_stream(kc0 + (int64_t)(first + e) * ld);
+      ka[e].hi = load_pack_stream(kc1 + (int64_t)(first + e) * ld);
+    }
+  };
+  auto load_k_masked = [&](int c, K4(&ka)[kB64Steps]) {
+    const int first = c * kB64Chunk + kB64Steps * q;
+#pragma unroll
+    for (int e = 0; e < kB64Steps; ++e) {
+      const bool ok = first + e < n;
+      const int64_t row = ok ? first + e : n - 1;
+      Pack<double> lo = load_pack(kc0 + row * ld), hi = load_pack(kc1 + row * ld);
+#pragma unroll
+      for (int t = 0; t < 2; ++t) {
+        lo.e[t] = ok ? lo.e[t] : 0.0;
+        hi.e[t] = ok ? hi.e[t] : 0.0;
+      }
+      ka[e].lo = lo;
+      ka[e].hi = hi;
+    }
+  };
+
+  const int sc = tid & 63, sk = tid >> 6;
+  const double* xcol = X + (sc < m ? sc : m - 1);
+  auto load_x = [&](int c, double(&st)[kB64Stage]) {
+#pragma unroll
+    for (int i = 0; i < kB64Stage; ++i) st[i] = xcol[(int64_t)(c * kB64Chunk + sk + 4 * i) * ldm];
+  };
+  auto load_x_masked = [&](int c, double(&st)[kB64Stage]) {
+#pragma unroll
+    for (int i = 0; i < kB64Stage; ++i) {
+      const int kk = c * kB64Chunk + sk + 4 * i;
+      const double val = xcol[(int64_t)(kk < n ? kk : n - 1) * ldm];
+      st[i] = kk < n ? val : 0.0;
+    }
+  };
+  auto store_x = [&](int buf, const double(&st)[kB64Stage]) {
+#pragma unroll
+    for (int i = 0; i < kB64Stage; ++i) xs[buf][sk + 4 * i][sc] = st[i];
+  };
+
+  auto mfma_step = [&](int buf, const K4& k4, int e) {
+    double bv[4];
+#pragma unroll
+    for (int b = 0; b < 4; ++b) bv[b] = xs[buf][kB64Steps * q + e][16 * b + r];
+    const double av[4] = {k4.lo.e[0], k4.lo.e[1], k4.hi.e[0], k4.hi.e[1]};
+#pragma unroll
+    for (int a = 0; a < 4; ++a)
+#pragma unroll
+      for (int b = 0; b < 4; ++b)
+        acc[a][b] = __builtin_amdgcn_mfma_f64_16x16x4f64(av[a], bv[b], acc[a][b], 0, 0, 0);
+  };
+  auto multiply = [&](int buf, const K4(&ka)[kB64Steps]) {
+#pragma unroll
+    for (int e = 0; e < kB64Steps; ++e) mfma_step(buf, ka[e], e);
+  };
+  // the MFMAs of the chunk in `ka` / xs[buf] with the loads of chunk cn spread between them
+  auto multiply_prefetch = [&](int buf, const K4(&ka)[kB64Steps], int cn, K4(&kn)[kB64Steps],
+                               double(&stn)[kB64Stage]) {
+    static_assert(kB64Stage <= kB64Steps, "one X load per k-step");
+    const int first = cn * kB64Chunk + kB64Steps * q;
+#pragma unroll
+    for (int e = 0; e < kB64Steps; ++e) {
+      mfma_step(buf, ka[e], e);
+      kn[e].lo = load_pack_stream(kc0 + (int64_t)(first + e) * ld);
+      kn[e].hi = load_pack_stream(kc1 + (int64_t)(first + e) * ld);
+      if (e < kB64Stage) stn[e] = xcol[(int64_t)(cn * kB64Chunk + sk + 4 * e) * ldm];
+      __builtin_amdgcn_sched_barrier(0);
+    }
+  };
+
+  K4 kaA[kB64Steps], kaB[kB64Steps];
+  double st[kB64Stage];
+  if (c0 < full_end) {
+    load_k(c0, kaA);
+    load_x(c0, st);
+    store_x(0, st);
+  }
+  __syncthreads();
+  int c = c0;
+  for (; c + 2 < full_end; c += 2) {  // chunks c and c + 1 both have a successor to prefetch
+    multiply_prefetch(0, kaA, c + 1, kaB, st);
+    store_x(1, st);
+    __syncthreads();
+    multiply_prefetch(1, kaB, c + 2, kaA, st);
+    store_x(0, st);
+    __syncthreads();
+  }
+  if (c + 1 < full_end) {  // two whole chunks left
+    multiply_prefetch(0, kaA, c + 1, kaB, st);
+    store_x(1, st);
+    __syncthreads();
+    multiply(1, kaB);
+    __syncthreads();
+  } else if (c < full_end) {  // one
+    multiply(0, kaA);
+    __syncthreads();
+  }
+  if (full_end < c1) {  // the one ragged chunk at the end of the contraction range
+    load_k_masked(full_end, kaA);
+    load_x_masked(full_end, st);
+    __syncthreads();
+    store_x(0, st);
+    __syncthreads();
+    multiply(0, kaA);
+  }
+
+  double* dst = final ? out : out + (int64_t)slice * n * m;
+#pragma unroll
+  for (int a = 0; a < 4; ++a)
+#pragma unroll
+    for (int v = 0; v < 4; ++v) {
+      const int i = 4 * v + q;  // MFMA row of accumulator element v
+      const int row = o0 + 4 * i + a;
+      if (row < n) {
+#pragma unroll
+        for (int b = 0; b < 4; ++b) {
+          const int col = 16 * b + r;
+          if (col < m) {
+            if (final) {
+              const int64_t idx = (int64_t)row * ldm + col;
+              dst[idx] = marg[idx] / acc[a][b][v];
+            } else {
+              dst[(int64_t)row * m + col] = acc[a][b][v];
+            }
+          }
+        }
+      }
+    }
+}
+
+__global__ __launch_bounds__(256) void transpose_f64_kernel(const double* __restrict__ K, int64_t ld,
+                                                            int n, double* __restrict__ Kt, int64_t ldt) {
+  __shared__ double tile[64][65];
+  const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
+  const int i0 = blockIdx.y * 64, j0 = blockIdx.x * 64;
+#pragma unroll 4
+  for (int r = ty; r < 64; r += 4)
+    if (i0 + r < n && j0 + tx < n) tile[r][tx] = K[(int64_t)(i0 + r) * ld + j0 + tx];
+  __syncthreads();
+#pragma unroll 4
+  for (int r = ty; r < 64; r += 4)
+    if (j0 + r < n && i0 + tx < n) Kt[(int64_t)(j0 + r) * ldt + i0 + tx] = tile[tx][r];
+}
+
+// out[row][col] = marg[row][col] / sum_s partial[s][row][col], slices added in slice order.
+__global__ __launch_bounds__(256) void batched_reduce_f64_kernel(const double* __restrict__ partial,
+                                                                 int slices, int n, int cols,
+                                                                 int64_t ldm,
+                                                                 const double* __restrict__ marg,
+                                                                 double* __restrict__ out) {
+  const int64_t total = (int64_t)n * cols;
+  const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (idx >= total) return;
+  double s = partial[idx];
+  for (int k = 1; k < slices; ++k) s += partial[(int64_t)k * total + idx];
+  const int64_t o = (idx / cols) * ldm + idx % cols;
+  out[o] = marg[o] / s;
+}
+
+static int b64_splits(int n) {
+  int cus = device_cu_count();
+  if (cus < 1) cus = 256;
+  const int tiles = (n + kB64Tile - 1) / kB64Tile;
+  int s = (cus + tiles - 1) / tiles;  // one workgroup (one wave per SIMD) per compute unit
+  const int nchunks = (n + kB64Chunk - 1) / kB64Chunk;
+  const int max_s = nchunks / 4 > 0 ? nchunks / 4 : 1;
+  if (s > max_s) s = max_s;
+  if (s > 32) s = 32;
+  return s < 1 ? 1 : s;
+}
+static size_t b64_partial_bytes(int n, int m) {
+  const int mg = m < kB64Cols ? m : kB64Cols;
+  return align_up((size_t)b64_splits(n) * (size_t)n * (size_t)mg * 8, 256);
+}
+static int64_t b64_ldt(int n) { return (int64_t)align_up((size_t)n, 32); }
+
+size_t batched_f64_workspace_bytes(int n, int m) {
+  return b64_partial_bytes(n, m) + align_up((size_t)n * (size_t)b64_ldt(n) * 8, 256) + 256;
+}
+
+int run_sinkhorn_batched_f64(const fsk_opts* o, const void* K, int64_t ldK, const void* A, const void* B,
+                             void* U, void* V, void* workspace, size_t ws_bytes, const fsk_dp* dp,
+                             hipStream_t st) {
+  const int n = o->n, m = o->m;
+  const size_t need = batched_f64_workspace_bytes(n, m);
+  if (!workspace || ws_bytes < need)
+    return set_error(FSK_EWORKSPACE, "fp64 batched call needs %zu workspace bytes (partial products and a "
+                     "transposed copy of K), got %zu", need, ws_bytes);
+  const double *Kd = (const double*)K, *Ad = (const double*)A, *Bd = (const double*)B;
+  double *Ud = (double*)U, *Vd = (double*)V, *part = (double*)workspace;
+  const int64_t ldt = b64_ldt(n);
+  double* Kt = (double*)((char*)workspace + b64_partial_bytes(n, m));
+  if (o->max_iters > 0) {
+    dim3 tg((n + 63) / 64, (n + 63) / 64);
+    hipLaunchKernelGGL(transpose_f64_kernel, tg, dim3(256), 0, st, Kd, ldK, n, Kt, ldt);
+    FSK_LAUNCH_CHECK("transpose_f64_kernel");
+  }
+  const int S = b64_splits(n);
+  dim3 grid(((n + kB64Tile - 1) / kB64Tile) * S), block(256);
+  auto product = [&](const double* Km, int64_t ldm_k, const double* X, const double* marg, double* dst,
+                     int c0, int cols) -> int {
+    hipLaunchKernelGGL(batched_prod_f64_kernel, grid, block, 0, st, Km, ldm_k, n, cols, (int64_t)m,
+                       X + c0, marg + c0, S == 1 ? dst + c0 : part, S == 1 ? 1 : 0, S);
+    FSK_LAUNCH_CHECK("batched_prod_f64_kernel");
+    if (S > 1) {
+      const int64_t total = (int64_t)n * cols;
+      hipLaunchKernelGGL(batched_reduce_f64_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st,
+                         (const double*)part, S, n, cols, (int64_t)m, marg + c0, dst + c0);
+      FSK_LAUNCH_CHECK("batched_reduce_f64_kernel");
+    }
+    return FSK_OK;
+  };
+  for (int it = 0; it < o->max_iters; ++it) {
+    for (int c0 = 0; c0 < m; c0 += kB64Cols)  // U = A ./ (K V) as the transposed product of K^T
+      FSK_TRY(product(Kt, ldt, Vd, Ad, Ud, c0, m - c0 < kB64Cols ? m - c0 : kB64Cols));
+    if (dp)
+      FSK_TRY(launch_dp_release(FSK_F64, Ud, n, m, dp->clip_u, dp->sigma_u, dp->seed,
+                                dp->release0 + 2 * (uint64_t)it, st));
+    for (int c0 = 0; c0 < m; c0 += kB64Cols)  // V = B ./ (K^T U)
+      FSK_TRY(product(Kd, ldK, Ud, Bd, Vd, c0, m - c0 < kB64Cols ? m - c0 : kB64Cols));
+    if (dp)
+      FSK_TRY(launch_dp_release(FSK_F64, Vd, n, m, dp->clip_v, dp->sigma_v, dp->seed,
+                                dp->release0 + 2 * (uint64_t)it + 1, st));
+  }
+  return FSK_OK;
+}
+
+}  // namespace fsk

@@ -146,6 +146,12 @@ int run_sinkhorn_batched(const fsk_opts* o, const void* K, int64_t ldK, const vo
                          void* U, void* V, void* workspace, size_t ws_bytes, const fsk_dp* dp,
                          hipStream_t st);
 
+// fp64 form (MFMA f64 16x16x4): needs the full workspace (partial products + K^T).
+size_t batched_f64_workspace_bytes(int n, int m);
+int run_sinkhorn_batched_f64(const fsk_opts* o, const void* K, int64_t ldK, const void* A, const void* B,
+                             void* U, void* V, void* workspace, size_t ws_bytes, const fsk_dp* dp,
+                             hipStream_t st);
+
 // ------------------------------------------------------------------ privacy layer
 // X (n x m, in place) <- exp(rowclip_S(log X) + sigma * normals of (seed, release)).
 int launch_dp_release(int dtype, void* X, int n, int m, double S, double sigma, uint64_t seed,

@@ -11,18 +11,20 @@ from gpu_util import dev, relerr, run_dense
 pytestmark = pytest.mark.gpu
 
 
-def run_batched(K, A, B, iters, ld=None, small_workspace=False):
+def run_batched(K, A, B, iters, ld=None, small_workspace=False, dtype=np.float32):
     n, m = A.shape
-    opts = api.make_opts(n, torch.float32, m=m, max_iters=iters)
+    td = torch.float64 if dtype == np.float64 else torch.float32
+    opts = api.make_opts(n, td, m=m, max_iters=iters)
     ws = api.alloc_workspace(opts, api.FSK_MODE_BATCHED)
     if small_workspace:      # no room for the transposed copy of K: the direct row kernel runs
         ws = ws[: ws.numel() - n * n * 4]
     if ld is None:
         ld = (n + 3) // 4 * 4
-    full = torch.full((n, ld), float("nan"), dtype=torch.float32, device="cuda")
-    full[:, :n] = dev(K)
-    U = torch.ones(n, m, device="cuda"); V = torch.ones(n, m, device="cuda")
-    api.fsk_sinkhorn_batched(opts, full[:, :n], dev(A), dev(B), U, V, ws)
+    full = torch.full((n, ld), float("nan"), dtype=td, device="cuda")
+    full[:, :n] = dev(np.ascontiguousarray(K.astype(dtype)))
+    U = torch.ones(n, m, dtype=td, device="cuda"); V = torch.ones(n, m, dtype=td, device="cuda")
+    api.fsk_sinkhorn_batched(opts, full[:, :n], dev(np.ascontiguousarray(A.astype(dtype))),
+                             dev(np.ascontiguousarray(B.astype(dtype))), U, V, ws)
     torch.cuda.synchronize()
     return U.cpu().numpy(), V.cpu().numpy()
 
@@ -84,3 +86,29 @@ def test_more_than_64_histograms_go_in_column_groups(orc, n, m, small):
     for k in (0, 63, 64, m - 1):
         cm = orc.col_marginal(K, U[:, k], V[:, k])
         assert relerr(cm, B[:, k]) <= 1e-4
+
+
+@pytest.mark.parametrize("n,m", [(1, 1), (2, 2), (5, 3), (64, 64), (65, 33), (100, 1), (257, 64),
+                                 (1000, 40), (1030, 64), (515, 130), (300, 200)])
+def test_batched_fp64_matches_oracle(orc, n, m):
+    """FSK_F64: the same products on the fp64 matrix instruction; the bar is 1e-10."""
+    w = workloads.make(5, n=n, m=m, seed=2100 + n + m)
+    K, _ = orc.gibbs_from_points(w.x, w.y, 0.05, False)
+    A = w.a.astype(np.float64); B = w.b.astype(np.float64)
+    Uo, Vo = orc.sinkhorn_batched(K, A, B, 9)
+    U, V = run_batched(K, A, B, 9, ld=(n + 1) // 2 * 2 + 6, dtype=np.float64)
+    assert relerr(U, Uo) <= 1e-10 and relerr(V, Vo) <= 1e-10
+    for k in (0, m // 2, m - 1):
+        cm = orc.col_marginal(K, U[:, k], V[:, k])
+        assert relerr(cm, B[:, k]) <= 1e-10
+
+
+def test_batched_fp64_needs_the_full_workspace():
+    n, m = 300, 8
+    opts = api.make_opts(n, torch.float64, m=m, max_iters=2)
+    ws = api.alloc_workspace(opts, api.FSK_MODE_BATCHED)
+    K = torch.ones(n, n, dtype=torch.float64, device="cuda")
+    X = torch.ones(n, m, dtype=torch.float64, device="cuda")
+    with pytest.raises(api.FskError) as e:
+        api.fsk_sinkhorn_batched(opts, K, X, X, X.clone(), X.clone(), ws[: ws.numel() // 2])
+    assert e.value.status == api.FSK_EWORKSPACE

@@ -90,3 +90,17 @@ def test_batched_dp_with_more_than_64_targets(orc):
     api.fsk_sinkhorn_batched_dp(opts, dev(K), dev(w.a), dev(w.b), U, V, api.fsk_dp(9.0, 8.0, 0.02, 0.01, 5, 0), ws)
     torch.cuda.synchronize()
     assert relerr(U.cpu().numpy(), Uo) <= 1e-4 and relerr(V.cpu().numpy(), Vo) <= 1e-4
+
+
+def test_batched_dp_fp64(orc):
+    n, m, iters = 260, 70, 4
+    w = workloads.make(5, n=n, m=m)
+    K, _ = orc.gibbs_from_points(w.x, w.y, 0.2, False)
+    A = w.a.astype(np.float64); B = w.b.astype(np.float64)
+    Uo, Vo = orc.sinkhorn_batched_dp(K, A, B, iters, 9.0, 8.0, 0.02, 0.01, 5, 6)
+    opts = api.make_opts(n, torch.float64, m=m, max_iters=iters)
+    ws = api.alloc_workspace(opts, api.FSK_MODE_BATCHED)
+    U = torch.ones(n, m, dtype=torch.float64, device="cuda"); V = torch.ones(n, m, dtype=torch.float64, device="cuda")
+    api.fsk_sinkhorn_batched_dp(opts, dev(K), dev(A), dev(B), U, V, api.fsk_dp(9.0, 8.0, 0.02, 0.01, 5, 6), ws)
+    torch.cuda.synchronize()
+    assert relerr(U.cpu().numpy(), Uo) <= 1e-10 and relerr(V.cpu().numpy(), Vo) <= 1e-10
