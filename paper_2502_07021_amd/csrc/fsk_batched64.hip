@@ -112,10 +112,12 @@ __global__ __launch_bounds__(256) void batched_prod_f64_kernel(const double* __r
     for (int i = 0; i < kB64Stage; ++i) xs[buf][sk + 4 * i][sc] = st[i];
   };
 
-  auto mfma_step = [&](int buf, const K4& k4, int e) {
-    double bv[4];
+  // B operands of k-step e of the chunk in xs[buf]
+  auto read_b = [&](int buf, int e, double(&bv)[4]) {
 #pragma unroll
     for (int b = 0; b < 4; ++b) bv[b] = xs[buf][kB64Steps * q + e][16 * b + r];
+  };
+  auto mfma_step = [&](const K4& k4, const double(&bv)[4]) {
     const double av[4] = {k4.lo.e[0], k4.lo.e[1], k4.hi.e[0], k4.hi.e[1]};
 #pragma unroll
     for (int a = 0; a < 4; ++a)
@@ -124,17 +126,25 @@ __global__ __launch_bounds__(256) void batched_prod_f64_kernel(const double* __r
         acc[a][b] = __builtin_amdgcn_mfma_f64_16x16x4f64(av[a], bv[b], acc[a][b], 0, 0, 0);
   };
   auto multiply = [&](int buf, const K4(&ka)[kB64Steps]) {
+    double bv[kB64Steps][4];
 #pragma unroll
-    for (int e = 0; e < kB64Steps; ++e) mfma_step(buf, ka[e], e);
+    for (int e = 0; e < kB64Steps; ++e) read_b(buf, e, bv[e]);
+#pragma unroll
+    for (int e = 0; e < kB64Steps; ++e) mfma_step(ka[e], bv[e]);
   };
-  // the MFMAs of the chunk in `ka` / xs[buf] with the loads of chunk cn spread between them
+  // the MFMAs of the chunk in `ka` / xs[buf] with the loads of chunk cn spread between them and
+  // the LDS operand reads one k-step ahead of the MFMAs that use them
   auto multiply_prefetch = [&](int buf, const K4(&ka)[kB64Steps], int cn, K4(&kn)[kB64Steps],
                                double(&stn)[kB64Stage]) {
     static_assert(kB64Stage <= kB64Steps, "one X load per k-step");
     const int first = cn * kB64Chunk + kB64Steps * q;
+    double bv[kB64Steps][4];
+    read_b(buf, 0, bv[0]);
+    __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
     for (int e = 0; e < kB64Steps; ++e) {
-      mfma_step(buf, ka[e], e);
+      mfma_step(ka[e], bv[e]);
+      if (e + 1 < kB64Steps) read_b(buf, e + 1, bv[e + 1]);
       kn[e].lo = load_pack_stream(kc0 + (int64_t)(first + e) * ld);
       kn[e].hi = load_pack_stream(kc1 + (int64_t)(first + e) * ld);
       if (e < kB64Stage) stn[e] = xcol[(int64_t)(cn * kB64Chunk + sk + 4 * e) * ldm];
