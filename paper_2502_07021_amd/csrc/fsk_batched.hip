@@ -218,21 +218,30 @@ __global__ __launch_bounds__(256) void batched_rowprod_kernel(const float* __res
 constexpr int kBtWideWaveTile = 128;
 constexpr int kBtWideTile = kBtWideWaveTile * kBtWaves;
 
+// X, marg and out (final) are n x mtot with row pitch mtot; the grid covers `groups` column
+// groups of up to 64 columns, `slices` contraction slices and the row tiles.  final == 0: the
+// partial product of (group g, slice s) goes, densely packed with pitch = the group's column
+// count, to out + (g * slices + s) * n * 64.
 __global__ __launch_bounds__(256) void batched_prod_wide_kernel(const float* __restrict__ K,
-                                                                int64_t ld, int n, int m,
-                                                                int64_t ldm,
+                                                                int64_t ld, int n, int mtot,
                                                                 const float* __restrict__ X,
                                                                 const float* __restrict__ marg,
                                                                 float* __restrict__ out, int final,
-                                                                int slices) {
+                                                                int slices, int groups) {
   __shared__ float xs[2][kBtChunk][kBtCols];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int r = lane & 31, h = lane >> 5;
   // 1-D grid, slice fastest: workgroups are dealt to the 8 XCDs round-robin, so the workgroups
   // of one contraction slice -- the ones that read the same rows of X -- meet on the same XCDs
   // and share those rows in that XCD's L2 instead of every L2 holding all of X.
-  const int slice = blockIdx.x % slices, tile = blockIdx.x / slices;
+  const int slice = blockIdx.x % slices, grp = (blockIdx.x / slices) % groups;
+  const int tile = blockIdx.x / (slices * groups);
   const int o0 = tile * kBtWideTile + wave * kBtWideWaveTile;
+  const int col0 = grp * kBtCols;
+  const int m = mtot - col0 < kBtCols ? mtot - col0 : kBtCols;  // columns of this group
+  const int64_t ldm = mtot;
+  X += col0;
+  marg += col0;
 
   const int nchunks = (n + kBtChunk - 1) / kBtChunk;
   const int per = (nchunks + slices - 1) / slices;
@@ -377,7 +386,7 @@ __global__ __launch_bounds__(256) void batched_prod_wide_kernel(const float* __r
     multiply(0, kaA);
   }
 
-  float* dst = final ? out : out + (int64_t)slice * n * m;
+  float* dst = final ? out + col0 : out + ((int64_t)grp * slices + slice) * n * kBtCols;
 #pragma unroll
   for (int a = 0; a < 4; ++a)
 #pragma unroll
@@ -419,16 +428,24 @@ __global__ __launch_bounds__(256) void transpose_kernel(const float* __restrict_
 // ------------------------------------------------------------------ host side
 // Grid slices of the contraction range.  The wide kernel keeps one workgroup per compute unit
 // busy (one wave per SIMD), the 64 x 64 kernel two.
-static int batched_splits_wide(int n) {
+static int batched_splits_wide(int n, int groups) {
   int cus = device_cu_count();
   if (cus < 1) cus = 256;
-  const int tiles = (n + kBtWideTile - 1) / kBtWideTile;
-  int s = (cus + tiles - 1) / tiles;  // one workgroup (four waves, one per SIMD) per compute unit
+  const int tiles = ((n + kBtWideTile - 1) / kBtWideTile) * groups;
+  // One workgroup (one wave per SIMD) per compute unit.  The grid runs in rounds of `cus`
+  // workgroups: take the slice count whose last round is fullest, a little in favour of fewer
+  // slices (every slice writes and re-reads one partial tile).
   const int nchunks = (n + kBtChunk - 1) / kBtChunk;
-  const int max_s = nchunks / 4 > 0 ? nchunks / 4 : 1;
-  if (s > max_s) s = max_s;
-  if (s > 32) s = 32;
-  return s < 1 ? 1 : s;
+  int max_s = nchunks / 4 > 0 ? nchunks / 4 : 1;  // at least 4 chunks per slice
+  if (max_s > 32) max_s = 32;
+  int s = 1;
+  double best = -1.0;
+  for (int q = 1; q <= max_s; ++q) {
+    const int wgs = tiles * q, rounds = (wgs + cus - 1) / cus;
+    const double score = (double)wgs / ((double)rounds * cus) - 0.02 * q;
+    if (score > best) best = score, s = q;
+  }
+  return s;
 }
 
 static int batched_splits(int n) {
@@ -444,9 +461,10 @@ static int batched_splits(int n) {
 }
 
 static size_t batched_partial_bytes(int n, int m) {
-  const int mg = m < kBtCols ? m : kBtCols;
-  const int sw = batched_splits_wide(n), sn = batched_splits(n);
-  return align_up((size_t)(sw > sn ? sw : sn) * (size_t)n * (size_t)mg * 4, 256);
+  const int groups = (m + kBtCols - 1) / kBtCols;
+  const size_t wide = (size_t)batched_splits_wide(n, groups) * groups;  // tiles of n x 64
+  const size_t direct = (size_t)batched_splits(n);                      // one group at a time
+  return align_up((wide > direct ? wide : direct) * (size_t)n * kBtCols * 4, 256);
 }
 static int64_t batched_ldt(int n) { return (int64_t)align_up((size_t)n, 64); }
 
@@ -455,23 +473,26 @@ size_t batched_workspace_bytes(int n, int m) {
   return batched_partial_bytes(n, m) + align_up((size_t)n * (size_t)batched_ldt(n) * 4, 256) + 256;
 }
 
-// out[row][col] = marg[row][col] / sum_s partial[s][row][col] for one column group: the partial
-// tiles are dense (pitch cols), marg and out are `cols` columns of matrices with pitch ldm.
-// The slices are added in slice order.
-template <bool VEC>  // VEC: cols, ldm and the column offset are multiples of 4 -> 16-byte accesses
+// out[row][col] = marg[row][col] / sum_s partial[g][s][row][col] for every column group g
+// (blockIdx.y): the partial tiles of a group are dense with pitch = the group's column count and
+// sit n * 64 apart; marg and out are n x mtot.  The slices are added in slice order.
+template <bool VEC>  // VEC: mtot is a multiple of 4 and marg, out are 16-byte aligned
 __global__ __launch_bounds__(256) void batched_reduce_kernel(const float* __restrict__ partial,
-                                                             int slices, int n, int cols, int64_t ldm,
+                                                             int slices, int n, int mtot,
                                                              const float* __restrict__ marg,
                                                              float* __restrict__ out) {
   constexpr int E = VEC ? 4 : 1;
-  const int64_t total = (int64_t)n * cols;
+  const int grp = blockIdx.y, col0 = grp * kBtCols;
+  const int cols = mtot - col0 < kBtCols ? mtot - col0 : kBtCols;
+  const int64_t total = (int64_t)n * cols, stride = (int64_t)n * kBtCols;
   const int64_t idx = ((int64_t)blockIdx.x * 256 + threadIdx.x) * E;
   if (idx >= total) return;
-  const int64_t o = (idx / cols) * ldm + idx % cols;
+  const float* p = partial + (int64_t)grp * slices * stride + idx;
+  const int64_t o = (idx / cols) * mtot + col0 + idx % cols;
   if (VEC) {
-    Pack<float> s = load_pack(partial + idx);
+    Pack<float> s = load_pack(p);
     for (int k = 1; k < slices; ++k) {
-      const Pack<float> y = load_pack(partial + (int64_t)k * total + idx);
+      const Pack<float> y = load_pack(p + (int64_t)k * stride);
 #pragma unroll
       for (int e = 0; e < 4; ++e) s.e[e] += y.e[e];
     }
@@ -480,10 +501,25 @@ __global__ __launch_bounds__(256) void batched_reduce_kernel(const float* __rest
     for (int e = 0; e < 4; ++e) s.e[e] = mg.e[e] / s.e[e];
     store_pack(out + o, s);
   } else {
-    float s = partial[idx];
-    for (int k = 1; k < slices; ++k) s += partial[(int64_t)k * total + idx];
+    float s = p[0];
+    for (int k = 1; k < slices; ++k) s += p[(int64_t)k * stride];
     out[o] = marg[o] / s;
   }
+}
+
+// The same for one column group of the direct row kernel: dense partial tiles n * cols apart.
+__global__ __launch_bounds__(256) void batched_rowreduce_kernel(const float* __restrict__ partial,
+                                                                int slices, int n, int cols,
+                                                                int64_t ldm,
+                                                                const float* __restrict__ marg,
+                                                                float* __restrict__ out) {
+  const int64_t total = (int64_t)n * cols;
+  const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (idx >= total) return;
+  float s = partial[idx];
+  for (int k = 1; k < slices; ++k) s += partial[(int64_t)k * total + idx];
+  const int64_t o = (idx / cols) * ldm + idx % cols;
+  out[o] = marg[o] / s;
 }
 
 int run_sinkhorn_batched(const fsk_opts* o, const void* K, int64_t ldK, const void* A, const void* B,
@@ -494,7 +530,7 @@ int run_sinkhorn_batched(const fsk_opts* o, const void* K, int64_t ldK, const vo
   const int n = o->n, m = o->m;
   const int S = batched_splits(n);
   const size_t part_bytes = batched_partial_bytes(n, m);
-  if ((S > 1 || batched_splits_wide(n) > 1) && (!workspace || ws_bytes < part_bytes))
+  if (!workspace || ws_bytes < part_bytes)
     return set_error(FSK_EWORKSPACE, "batched call needs at least %zu workspace bytes (%zu to run at "
                      "full speed), got %zu", part_bytes, batched_workspace_bytes(n, m), ws_bytes);
   const float *Kf = (const float*)K, *Af = (const float*)A, *Bf = (const float*)B;
@@ -509,49 +545,54 @@ int run_sinkhorn_batched(const fsk_opts* o, const void* K, int64_t ldK, const vo
     FSK_LAUNCH_CHECK("transpose_kernel");
   }
   dim3 grid((n + kBtTile - 1) / kBtTile, S), block(256);
-  const int SW = batched_splits_wide(n);
-  dim3 gridw(((n + kBtWideTile - 1) / kBtWideTile) * SW);
   // The m histogram columns go through the kernels in groups of up to 64 (the kernels' tile
   // width); a group costs one pass over K per product, so the time grows with ceil(m / 64).
-  // The partial area is reused by every group (the launches are ordered on the stream).
-  auto reduce = [&](int slices, int cols, const float* marg, float* dst) -> int {
-    const int64_t total = (int64_t)n * cols;
-    const bool vec = cols % 4 == 0 && m % 4 == 0 && ((uintptr_t)marg % 16 == 0) && ((uintptr_t)dst % 16 == 0);
+  // The transposed-product kernel takes all groups in one launch and splits the contraction
+  // range only as far as the grid still needs it (tiles x groups x slices ~ compute units).
+  const int groups = (m + kBtCols - 1) / kBtCols;
+  const int SW = batched_splits_wide(n, groups);
+  dim3 gridw(((n + kBtWideTile - 1) / kBtWideTile) * SW * groups);
+  auto reduce_all = [&](const float* marg, float* dst) -> int {
+    const bool vec = m % 4 == 0 && ((uintptr_t)marg % 16 == 0) && ((uintptr_t)dst % 16 == 0);
+    const int64_t per_group = (int64_t)n * kBtCols;
     if (vec)
-      hipLaunchKernelGGL(batched_reduce_kernel<true>, dim3((unsigned)((total / 4 + 255) / 256)), dim3(256),
-                         0, st, (const float*)part, slices, n, cols, (int64_t)m, marg, dst);
+      hipLaunchKernelGGL(batched_reduce_kernel<true>, dim3((unsigned)((per_group / 4 + 255) / 256), groups),
+                         dim3(256), 0, st, (const float*)part, SW, n, m, marg, dst);
     else
-      hipLaunchKernelGGL(batched_reduce_kernel<false>, dim3((unsigned)((total + 255) / 256)), dim3(256), 0,
-                         st, (const float*)part, slices, n, cols, (int64_t)m, marg, dst);
+      hipLaunchKernelGGL(batched_reduce_kernel<false>, dim3((unsigned)((per_group + 255) / 256), groups),
+                         dim3(256), 0, st, (const float*)part, SW, n, m, marg, dst);
     FSK_LAUNCH_CHECK("batched_reduce_kernel");
     return FSK_OK;
   };
+  auto wide = [&](const float* Km, int64_t ldm_k, const float* X, const float* marg, float* dst,
+                  const char* what) -> int {
+    hipLaunchKernelGGL(batched_prod_wide_kernel, gridw, block, 0, st, Km, ldm_k, n, m, X, marg,
+                       SW == 1 ? dst : part, SW == 1 ? 1 : 0, SW, groups);
+    FSK_LAUNCH_CHECK(what);
+    if (SW > 1) FSK_TRY(reduce_all(marg, dst));
+    return FSK_OK;
+  };
   for (int it = 0; it < o->max_iters; ++it) {
-    for (int c0 = 0; c0 < m; c0 += kBtCols) {  // U = A ./ (K V), column group by column group
-      const int cols = m - c0 < kBtCols ? m - c0 : kBtCols;
-      if (use_kt) {  // Q = K V as the transposed product of K^T
-        hipLaunchKernelGGL(batched_prod_wide_kernel, gridw, block, 0, st, (const float*)Kt, ldt, n, cols,
-                           (int64_t)m, (const float*)Vf + c0, Af + c0, SW == 1 ? Uf + c0 : part,
-                           SW == 1 ? 1 : 0, SW);
-        FSK_LAUNCH_CHECK("batched_prod_wide_kernel (K V)");
-        if (SW > 1) FSK_TRY(reduce(SW, cols, Af + c0, Uf + c0));
-      } else {
+    if (use_kt) {  // Q = K V as the transposed product of K^T
+      FSK_TRY(wide(Kt, ldt, Vf, Af, Uf, "batched_prod_wide_kernel (K V)"));
+    } else {       // direct row walk, one column group per launch
+      for (int c0 = 0; c0 < m; c0 += kBtCols) {
+        const int cols = m - c0 < kBtCols ? m - c0 : kBtCols;
         hipLaunchKernelGGL(batched_rowprod_kernel, grid, block, 0, st, Kf, ldK, n, cols, (int64_t)m,
                            (const float*)Vf + c0, Af + c0, S == 1 ? Uf + c0 : part, S == 1 ? 1 : 0);
         FSK_LAUNCH_CHECK("batched_rowprod_kernel (K V)");
-        if (S > 1) FSK_TRY(reduce(S, cols, Af + c0, Uf + c0));
+        if (S > 1) {
+          const int64_t total = (int64_t)n * cols;
+          hipLaunchKernelGGL(batched_rowreduce_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0,
+                             st, (const float*)part, S, n, cols, (int64_t)m, Af + c0, Uf + c0);
+          FSK_LAUNCH_CHECK("batched_rowreduce_kernel");
+        }
       }
     }
     if (dp)  // the release clips every row across ALL m targets
       FSK_TRY(launch_dp_release(FSK_F32, Uf, n, m, dp->clip_u, dp->sigma_u, dp->seed,
                                 dp->release0 + 2 * (uint64_t)it, st));
-    for (int c0 = 0; c0 < m; c0 += kBtCols) {  // V = B ./ (K^T U)
-      const int cols = m - c0 < kBtCols ? m - c0 : kBtCols;
-      hipLaunchKernelGGL(batched_prod_wide_kernel, gridw, block, 0, st, Kf, ldK, n, cols, (int64_t)m,
-                         (const float*)Uf + c0, Bf + c0, SW == 1 ? Vf + c0 : part, SW == 1 ? 1 : 0, SW);
-      FSK_LAUNCH_CHECK("batched_prod_wide_kernel (K^T U)");
-      if (SW > 1) FSK_TRY(reduce(SW, cols, Bf + c0, Vf + c0));
-    }
+    FSK_TRY(wide(Kf, ldK, Uf, Bf, Vf, "batched_prod_wide_kernel (K^T U)"));  // V = B ./ (K^T U)
     if (dp)
       FSK_TRY(launch_dp_release(FSK_F32, Vf, n, m, dp->clip_v, dp->sigma_v, dp->seed,
                                 dp->release0 + 2 * (uint64_t)it + 1, st));

@@ -31,18 +31,28 @@ constexpr int kB64Stage = kB64Chunk * kB64Cols / 256;
 
 struct K4 { Pack<double> lo, hi; };  // four adjacent columns of one row of K
 
+// X, marg and out (final) are n x mtot with row pitch mtot; the grid covers `groups` column groups
+// of up to 64 columns, `slices` contraction slices and the row tiles.  final == 0: the partial
+// product of (group g, slice s) goes, densely packed with pitch = the group's column count, to
+// out + (g * slices + s) * n * 64.
 __global__ __launch_bounds__(256) void batched_prod_f64_kernel(const double* __restrict__ K, int64_t ld,
-                                                               int n, int m, int64_t ldm,
+                                                               int n, int mtot,
                                                                const double* __restrict__ X,
                                                                const double* __restrict__ marg,
                                                                double* __restrict__ out, int final,
-                                                               int slices) {
+                                                               int slices, int groups) {
   __shared__ double xs[2][kB64Chunk][kB64Cols];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int r = lane & 15, q = lane >> 4;
   // 1-D grid, slice fastest: the workgroups of one contraction slice share rows of X in an XCD's L2
-  const int slice = blockIdx.x % slices, tile = blockIdx.x / slices;
+  const int slice = blockIdx.x % slices, grp = (blockIdx.x / slices) % groups;
+  const int tile = blockIdx.x / (slices * groups);
   const int o0 = tile * kB64Tile + wave * kB64WaveTile;
+  const int col0 = grp * kB64Cols;
+  const int m = mtot - col0 < kB64Cols ? mtot - col0 : kB64Cols;  // columns of this group
+  const int64_t ldm = mtot;
+  X += col0;
+  marg += col0;
 
   const int nchunks = (n + kB64Chunk - 1) / kB64Chunk;
   const int per = (nchunks + slices - 1) / slices;
@@ -188,7 +198,7 @@ __global__ __launch_bounds__(256) void batched_prod_f64_kernel(const double* __r
     multiply(0, kaA);
   }
 
-  double* dst = final ? out : out + (int64_t)slice * n * m;
+  double* dst = final ? out + col0 : out + ((int64_t)grp * slices + slice) * n * kB64Cols;
 #pragma unroll
   for (int a = 0; a < 4; ++a)
 #pragma unroll
@@ -226,35 +236,49 @@ __global__ __launch_bounds__(256) void transpose_f64_kernel(const double* __rest
     if (j0 + r < n && i0 + tx < n) Kt[(int64_t)(j0 + r) * ldt + i0 + tx] = tile[tx][r];
 }
 
-// out[row][col] = marg[row][col] / sum_s partial[s][row][col], slices added in slice order.
+// out[row][col] = marg[row][col] / sum_s partial[g][s][row][col] for every column group g
+// (blockIdx.y), the slices added in slice order; partial tiles of a group are dense with pitch =
+// the group's column count and sit n * 64 apart; marg and out are n x mtot.
 __global__ __launch_bounds__(256) void batched_reduce_f64_kernel(const double* __restrict__ partial,
-                                                                 int slices, int n, int cols,
-                                                                 int64_t ldm,
+                                                                 int slices, int n, int mtot,
                                                                  const double* __restrict__ marg,
                                                                  double* __restrict__ out) {
-  const int64_t total = (int64_t)n * cols;
+  const int grp = blockIdx.y, col0 = grp * kB64Cols;
+  const int cols = mtot - col0 < kB64Cols ? mtot - col0 : kB64Cols;
+  const int64_t total = (int64_t)n * cols, stride = (int64_t)n * kB64Cols;
   const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
   if (idx >= total) return;
-  double s = partial[idx];
-  for (int k = 1; k < slices; ++k) s += partial[(int64_t)k * total + idx];
-  const int64_t o = (idx / cols) * ldm + idx % cols;
+  const double* p = partial + (int64_t)grp * slices * stride + idx;
+  double s = p[0];
+  for (int k = 1; k < slices; ++k) s += p[(int64_t)k * stride];
+  const int64_t o = (idx / cols) * mtot + col0 + idx % cols;
   out[o] = marg[o] / s;
 }
 
-static int b64_splits(int n) {
+static int b64_groups(int m) { return (m + kB64Cols - 1) / kB64Cols; }
+
+static int b64_splits(int n, int groups) {
   int cus = device_cu_count();
   if (cus < 1) cus = 256;
-  const int tiles = (n + kB64Tile - 1) / kB64Tile;
-  int s = (cus + tiles - 1) / tiles;  // one workgroup (one wave per SIMD) per compute unit
+  const int tiles = ((n + kB64Tile - 1) / kB64Tile) * groups;
+  // One workgroup (one wave per SIMD) per compute unit.  The grid runs in rounds of `cus`
+  // workgroups: take the slice count whose last round is fullest, a little in favour of fewer
+  // slices (every slice writes and re-reads one partial tile).
   const int nchunks = (n + kB64Chunk - 1) / kB64Chunk;
-  const int max_s = nchunks / 4 > 0 ? nchunks / 4 : 1;
-  if (s > max_s) s = max_s;
-  if (s > 32) s = 32;
-  return s < 1 ? 1 : s;
+  int max_s = nchunks / 4 > 0 ? nchunks / 4 : 1;  // at least 4 chunks per slice
+  if (max_s > 32) max_s = 32;
+  int s = 1;
+  double best = -1.0;
+  for (int q = 1; q <= max_s; ++q) {
+    const int wgs = tiles * q, rounds = (wgs + cus - 1) / cus;
+    const double score = (double)wgs / ((double)rounds * cus) - 0.02 * q;
+    if (score > best) best = score, s = q;
+  }
+  return s;
 }
 static size_t b64_partial_bytes(int n, int m) {
-  const int mg = m < kB64Cols ? m : kB64Cols;
-  return align_up((size_t)b64_splits(n) * (size_t)n * (size_t)mg * 8, 256);
+  const int groups = b64_groups(m);
+  return align_up((size_t)b64_splits(n, groups) * groups * (size_t)n * kB64Cols * 8, 256);
 }
 static int64_t b64_ldt(int n) { return (int64_t)align_up((size_t)n, 32); }
 
@@ -279,29 +303,29 @@ int run_sinkhorn_batched_f64(const fsk_opts* o, const void* K, int64_t ldK, cons
     hipLaunchKernelGGL(transpose_f64_kernel, tg, dim3(256), 0, st, Kd, ldK, n, Kt, ldt);
     FSK_LAUNCH_CHECK("transpose_f64_kernel");
   }
-  const int S = b64_splits(n);
-  dim3 grid(((n + kB64Tile - 1) / kB64Tile) * S), block(256);
-  auto product = [&](const double* Km, int64_t ldm_k, const double* X, const double* marg, double* dst,
-                     int c0, int cols) -> int {
-    hipLaunchKernelGGL(batched_prod_f64_kernel, grid, block, 0, st, Km, ldm_k, n, cols, (int64_t)m,
-                       X + c0, marg + c0, S == 1 ? dst + c0 : part, S == 1 ? 1 : 0, S);
+  // all column groups of 64 in one launch; the contraction range is split only as far as the
+  // grid still needs it (tiles x groups x slices ~ compute units)
+  const int groups = b64_groups(m), S = b64_splits(n, groups);
+  dim3 grid(((n + kB64Tile - 1) / kB64Tile) * S * groups), block(256);
+  auto product = [&](const double* Km, int64_t ldm_k, const double* X, const double* marg,
+                     double* dst) -> int {
+    hipLaunchKernelGGL(batched_prod_f64_kernel, grid, block, 0, st, Km, ldm_k, n, m, X, marg,
+                       S == 1 ? dst : part, S == 1 ? 1 : 0, S, groups);
     FSK_LAUNCH_CHECK("batched_prod_f64_kernel");
     if (S > 1) {
-      const int64_t total = (int64_t)n * cols;
-      hipLaunchKernelGGL(batched_reduce_f64_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st,
-                         (const double*)part, S, n, cols, (int64_t)m, marg + c0, dst + c0);
+      const int64_t per_group = (int64_t)n * kB64Cols;
+      hipLaunchKernelGGL(batched_reduce_f64_kernel, dim3((unsigned)((per_group + 255) / 256), groups),
+                         dim3(256), 0, st, (const double*)part, S, n, m, marg, dst);
       FSK_LAUNCH_CHECK("batched_reduce_f64_kernel");
     }
     return FSK_OK;
   };
   for (int it = 0; it < o->max_iters; ++it) {
-    for (int c0 = 0; c0 < m; c0 += kB64Cols)  // U = A ./ (K V) as the transposed product of K^T
-      FSK_TRY(product(Kt, ldt, Vd, Ad, Ud, c0, m - c0 < kB64Cols ? m - c0 : kB64Cols));
+    FSK_TRY(product(Kt, ldt, Vd, Ad, Ud));  // U = A ./ (K V) as the transposed product of K^T
     if (dp)
       FSK_TRY(launch_dp_release(FSK_F64, Ud, n, m, dp->clip_u, dp->sigma_u, dp->seed,
                                 dp->release0 + 2 * (uint64_t)it, st));
-    for (int c0 = 0; c0 < m; c0 += kB64Cols)  // V = B ./ (K^T U)
-      FSK_TRY(product(Kd, ldK, Ud, Bd, Vd, c0, m - c0 < kB64Cols ? m - c0 : kB64Cols));
+    FSK_TRY(product(Kd, ldK, Ud, Bd, Vd));  // V = B ./ (K^T U)
     if (dp)
       FSK_TRY(launch_dp_release(FSK_F64, Vd, n, m, dp->clip_v, dp->sigma_v, dp->seed,
                                 dp->release0 + 2 * (uint64_t)it + 1, st));
