@@ -28,6 +28,7 @@ if ROOT not in sys.path:
 
 PEAK_HBM_GBS = 8000.0          # MI355X published HBM3E peak
 PEAK_FP32_MFMA_TFLOPS = 157.3  # dense fp32 matrix peak
+PEAK_FP64_MFMA_TFLOPS = 78.6   # dense fp64 matrix peak
 PEAK_FMA_TFLOPS = 78.6         # 256 CU x 64 lanes x 2.4 GHz x 2 flop: one (unpacked fp32 or fp64) FMA per lane per clock
 METRIC = "Sinkhorn iters/sec (Kv+K^Tu) at n=32768 fp32; achieved HBM GB/s vs peak"
 
@@ -245,18 +246,27 @@ def bench_batched(args):
     from paper_2502_07021_amd import api, workloads
 
     w = workloads.make(5, n=args.n)
-    n, m = w.n, w.m
+    n = w.n
+    m = args.m if args.m is not None else w.m
+    f64 = args.dtype == "f64"
+    td, nd = (torch.float64, np.float64) if f64 else (torch.float32, np.float32)
     steps = args.steps if args.steps is not None else w.iters
-    dev = lambda t: torch.from_numpy(t).cuda()
-    x, y, A, B = dev(w.x), dev(w.y), dev(w.a), dev(w.b)
-    opts = api.make_opts(n, torch.float32, m=m, max_iters=steps)
-    K = torch.empty(n, n, device="cuda")
+    dev = lambda t: torch.from_numpy(np.ascontiguousarray(t.astype(nd))).cuda()
+    if m == w.m:
+        a_np, b_np = w.a, w.b
+    else:                                                # the same Dirichlet(1) law at another m
+        rng = np.random.default_rng(12345)
+        a_np = rng.dirichlet(np.ones(n), size=m).T
+        b_np = rng.dirichlet(np.ones(n), size=m).T
+    x, y, A, B = dev(w.x), dev(w.y), dev(a_np), dev(b_np)
+    opts = api.make_opts(n, td, m=m, max_iters=steps)
+    K = torch.empty(n, n, dtype=td, device="cuda")
     api.fsk_kernel_from_points(opts, x, y, w.eps, False, K, None)
     ws = api.alloc_workspace(opts, api.FSK_MODE_BATCHED)
-    U = torch.ones(n, m, device="cuda"); V = torch.ones(n, m, device="cuda")
+    U = torch.ones(n, m, dtype=td, device="cuda"); V = torch.ones(n, m, dtype=td, device="cuda")
 
     def run(iters):
-        api.fsk_sinkhorn_batched(api.make_opts(n, torch.float32, m=m, max_iters=iters), K, A, B, U, V, ws)
+        api.fsk_sinkhorn_batched(api.make_opts(n, td, m=m, max_iters=iters), K, A, B, U, V, ws)
 
     run(max(args.warmup, 1))
     dt = timed(lambda: run(steps))
@@ -265,17 +275,20 @@ def bench_batched(args):
     launch_ms = ms / (2 * reps)                           # two products per iteration
     flops = 2.0 * n * n * m
     achieved = flops / (launch_ms * 1e-3) / 1e12
+    peak = PEAK_FP64_MFMA_TFLOPS if f64 else PEAK_FP32_MFMA_TFLOPS
     out = {
         "metric": f"Sinkhorn iters/sec (multitarget K V, K^T U on MFMA), cfg5 n={n} m={m}",
         "value": steps / dt, "unit": "iterations/s", "n_gpus": 1, "steps": steps,
         "warmup": args.warmup, "ms_per_step": dt / steps * 1e3, "higher_is_better": True,
-        "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
-        "config": {"workload": f"cfg5: n={n} fp32 dense K shared by m={m} Dirichlet(1) histogram "
-                               f"pairs, x,y~U[0,1]^2, eps={w.eps}", "n": n, "m": m},
-        "roofline": {"bound": "mfma", "achieved": achieved, "peak": PEAK_FP32_MFMA_TFLOPS,
-                     "unit": "TFLOP/s", "frac": achieved / PEAK_FP32_MFMA_TFLOPS,
-                     "traffic": traffic_from_profile("batched_mfma_cfg5.txt") if (n == 16384 and m == 64) else None,
-                     "kernel": "batched_prod_wide_kernel (both products)",
+        "scaling": "weak", "vs_baseline": None, "dtype": args.dtype, "data": "synthetic",
+        "config": {"workload": f"cfg5: n={n} {'fp64' if f64 else 'fp32'} dense K shared by m={m} "
+                               f"Dirichlet(1) histogram pairs, x,y~U[0,1]^2, eps={w.eps}", "n": n, "m": m},
+        "roofline": {"bound": "mfma", "achieved": achieved, "peak": peak,
+                     "unit": "TFLOP/s", "frac": achieved / peak,
+                     "traffic": traffic_from_profile("batched_mfma_cfg5.txt")
+                     if (n == 16384 and m == 64 and not f64) else None,
+                     "kernel": ("batched_prod_f64_kernel" if f64 else "batched_prod_wide_kernel")
+                               + " (both products)",
                      "kernel_ms": launch_ms, "launches_per_step": 2,
                      "note": "kernel_ms = event-timed run / product launches; includes the small reduce "
                              "kernels and 1/reps of the K^T build"},
@@ -283,13 +296,16 @@ def bench_batched(args):
     }
     if not args.no_cpu_baseline:
         import oracle
-        Ko, _ = oracle.gibbs_from_points_f32(w.x, w.y, w.eps, False)
+        Ko, _ = oracle.gibbs_from_points(w.x, w.y, w.eps, False) if f64 \
+            else oracle.gibbs_from_points_f32(w.x, w.y, w.eps, False)
+        mo = min(m, 64)                                  # bounded sample: at most 64 columns
         t0 = time.perf_counter()
-        oracle.sinkhorn_batched(Ko, w.a, w.b, 2)
+        oracle.sinkhorn_batched(Ko, np.ascontiguousarray(a_np[:, :mo]), np.ascontiguousarray(b_np[:, :mo]), 2)
         dto = time.perf_counter() - t0
-        out["cpu_baseline"] = {"value": 2 / dto, "unit": "iterations/s",
+        out["cpu_baseline"] = {"value": 2 / dto * mo / m, "unit": "iterations/s",
                                "cores": oracle.num_threads(), "kind": "oracle",
-                               "sample": f"2 full iterations at n={n}, m={m}"}
+                               "sample": f"2 full iterations at n={n} on {mo} of the {m} columns"
+                                         + ("" if mo == m else ", scaled by columns")}
     return out
 
 
@@ -302,6 +318,9 @@ def main() -> int:
     ap.add_argument("--workload", default="cfg3", choices=["cfg1", "cfg2", "cfg3", "cfg4", "cfg5"])
     ap.add_argument("--n", type=int, default=None, help="override the problem size (same law)")
     ap.add_argument("--c", type=int, default=None, help="row blocks (dense workloads)")
+    ap.add_argument("--m", type=int, default=None, help="histogram pairs (cfg5; default 64)")
+    ap.add_argument("--dtype", default="f32", choices=["f32", "f64"],
+                    help="arithmetic of the cfg5 products (the dense workloads fix theirs)")
     ap.add_argument("--flow", type=int, default=None,
                     help="dense: 0 fused, 1 two-pass, 2 Algorithm 1, 3 register-resident "
                          "(default: 3 for cfg1, 0 otherwise)")
