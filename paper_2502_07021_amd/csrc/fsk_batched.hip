@@ -15,10 +15,13 @@
 // chunks of 32 indices.  K goes straight from global memory into registers (128-bit
 // non-temporal loads, one chunk ahead of the MFMAs); the chunk of the n x m operand (32 x 64
 // values) is shared by the four waves through LDS, double buffered, one barrier per chunk.
-// The grid splits the contraction range S ways; the S partial tiles go to the workspace and
-// a reduction kernel adds them in fixed order and applies the division (S = 1: the division
-// is fused into the tile store).  When the workspace has no room for K^T, Q = K V falls back
-// to batched_rowprod_kernel, the direct walk with a 64 x 64 tile per wave.
+// Wider problems (the paper stacks N = 500 targets and more) run as ceil(m / 64) column groups
+// inside the same launch.  The 1-D grid is row tiles x column groups x S parts of the
+// contraction range, S chosen so that the grid fills the compute units; for S > 1 the partial
+// tiles go to the workspace and a reduction kernel adds them in fixed order and applies the
+// division (S = 1: the division is fused into the tile store).  When the workspace has no room
+// for K^T, Q = K V falls back to batched_rowprod_kernel, the direct walk with a 64 x 64 tile per
+// wave, one column group per launch.
 //
 // MFMA 32x32x2 operand layout (lane l of 64): A[i = l%32][k = l/32],
 // B[k = l/32][j = l%32], D[i = 8(v/4) + 4(l/32) + v%4][j = l%32] for accumulator
@@ -31,7 +34,7 @@ namespace fsk {
 
 typedef float floatx16 __attribute__((ext_vector_type(16)));
 
-constexpr int kBtCols = 64;        // histogram columns per launch (wider problems go in groups)
+constexpr int kBtCols = 64;        // histogram columns per tile (wider problems go in groups)
 constexpr int kBtWaveTile = 64;    // output rows per wave
 constexpr int kBtWaves = 4;
 constexpr int kBtTile = kBtWaveTile * kBtWaves;  // output rows per workgroup

@@ -135,3 +135,24 @@ def test_cfg5_n16384_m64_batched(orc):
         assert relerr(U300h[rows, k], w.a[rows, k].astype(np.float64) / q) <= 1e-4
         r = np.array([orc.col_products(K, U300h[:, k], 0, n, j, j + 1)[0] for j in rows])
         assert relerr(V300h[rows, k], w.b[rows, k].astype(np.float64) / r) <= 1e-4
+
+
+def test_multitarget_instance_n5000_m500(orc):
+    """The multitarget experiment's own shape (Sec. 5.3.2: n = 5000, N = 500 targets, 15
+    iterations; the paper runs it in fp64), all column groups in one launch, whole trajectory
+    against the oracle.  Both precisions get the same fp32-representable K, A, B, so one oracle
+    run serves both."""
+    n, m, iters = 5000, 500, 15
+    w = workloads.make(5, n=n, m=m, seed=5500)
+    K, _ = orc.gibbs_from_points_f32(w.x, w.y, w.eps, False)
+    A = np.ascontiguousarray(w.a.astype(np.float32)); B = np.ascontiguousarray(w.b.astype(np.float32))
+    Uo, Vo = orc.sinkhorn_batched(K, A, B, iters)
+    for td, nd, tol in ((torch.float32, np.float32, 1e-4), (torch.float64, np.float64, 1e-10)):
+        opts = api.make_opts(n, td, m=m, max_iters=iters)
+        ws = api.alloc_workspace(opts, api.FSK_MODE_BATCHED)
+        U = torch.ones(n, m, dtype=td, device="cuda"); V = torch.ones(n, m, dtype=td, device="cuda")
+        Kd = torch.empty(n, n + 8, dtype=td, device="cuda")[:, :n]
+        Kd.copy_(dev(K))
+        api.fsk_sinkhorn_batched(opts, Kd, dev(A.astype(nd)), dev(B.astype(nd)), U, V, ws)
+        torch.cuda.synchronize()
+        assert relerr(U.cpu().numpy(), Uo) <= tol and relerr(V.cpu().numpy(), Vo) <= tol
