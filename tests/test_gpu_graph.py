@@ -1,0 +1,90 @@
+"""The fixed-iteration entry points only enqueue kernels on the caller's stream (no allocation,
+no synchronisation, no memset nodes), so a caller can record them into a HIP graph.  Each case
+records one call, then replays the graph several times with ordinary eager work and
+synchronisations in between, and compares every replay bit for bit with the eager call."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2502_07021_amd import api, workloads
+from gpu_util import dev
+
+pytestmark = pytest.mark.gpu
+
+
+def _replay_matches_eager(call, outputs, reset):
+    """call(): the library call; outputs: tensors it writes; reset(): restore the start state."""
+    reset(); call(); torch.cuda.synchronize()          # eager run (also the warm-up of the capture)
+    want = [t.clone() for t in outputs]
+    reset(); torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        call()
+    for rep in range(3):
+        reset()                                         # eager kernels between the replays
+        scratch = torch.rand(1 << 16, device="cuda").sum().item()   # unrelated eager work + a sync
+        assert np.isfinite(scratch)
+        g.replay()
+        torch.cuda.synchronize()
+        for got, ref in zip(outputs, want):
+            assert torch.equal(got, ref), f"replay {rep} differs from the eager call"
+
+
+@pytest.mark.parametrize("n,td,flow,c", [
+    (2048, torch.float32, api.FSK_FLOW_FUSED, 1),
+    (2048, torch.float32, api.FSK_FLOW_FUSED, 8),
+    (1030, torch.float32, api.FSK_FLOW_TWO_PASS, 1),
+    (1024, torch.float32, api.FSK_FLOW_PAPER, 4),
+    (512, torch.float64, api.FSK_FLOW_RESIDENT, 1),
+])
+def test_dense_call_in_a_graph(n, td, flow, c):
+    w = workloads.make(2, n=n)
+    nd = np.float64 if td == torch.float64 else np.float32
+    opts = api.make_opts(n, td, c=c, max_iters=40, flow=flow)
+    pack = 16 // np.dtype(nd).itemsize
+    ld = (n + pack - 1) // pack * pack
+    K = torch.empty(n, ld, dtype=td, device="cuda")[:, :n]
+    api.fsk_kernel_from_points(opts, dev(w.x.astype(nd)), dev(w.y.astype(nd)), w.eps, True, K,
+                               api.alloc_workspace(opts, api.FSK_MODE_SETUP))
+    a, b = dev(w.a.astype(nd)), dev(w.b.astype(nd))
+    u = torch.empty(n, dtype=td, device="cuda"); v = torch.empty(n, dtype=td, device="cuda")
+    ws = api.alloc_workspace(opts)
+
+    def reset():
+        u.fill_(1.0); v.fill_(1.0)
+
+    _replay_matches_eager(lambda: api.fsk_sinkhorn_dense(opts, K, a, b, u, v, ws), [u, v], reset)
+
+
+@pytest.mark.parametrize("td,m", [(torch.float32, 64), (torch.float32, 150), (torch.float64, 64)])
+def test_batched_call_in_a_graph(td, m):
+    n = 1030
+    nd = np.float64 if td == torch.float64 else np.float32
+    w = workloads.make(5, n=n, m=m, seed=77)
+    opts = api.make_opts(n, td, m=m, max_iters=10)
+    pack = 16 // np.dtype(nd).itemsize
+    ld = (n + pack - 1) // pack * pack
+    K = torch.empty(n, ld, dtype=td, device="cuda")[:, :n]
+    api.fsk_kernel_from_points(opts, dev(w.x.astype(nd)), dev(w.y.astype(nd)), w.eps, False, K, None)
+    A, B = dev(np.ascontiguousarray(w.a.astype(nd))), dev(np.ascontiguousarray(w.b.astype(nd)))
+    U = torch.empty(n, m, dtype=td, device="cuda"); V = torch.empty(n, m, dtype=td, device="cuda")
+    ws = api.alloc_workspace(opts, api.FSK_MODE_BATCHED)
+
+    def reset():
+        U.fill_(1.0); V.fill_(1.0)
+
+    _replay_matches_eager(lambda: api.fsk_sinkhorn_batched(opts, K, A, B, U, V, ws), [U, V], reset)
+
+
+def test_log_domain_call_in_a_graph():
+    n, d = 1500, 16
+    w = workloads.make(4, n=n)
+    opts = api.make_opts(n, torch.float32, max_iters=12)
+    x, y, a, b = dev(w.x), dev(w.y), dev(w.a), dev(w.b)
+    f = torch.empty(n, device="cuda"); g = torch.empty(n, device="cuda")
+    ws = api.alloc_workspace(opts, api.FSK_MODE_LOG, d)
+
+    def reset():
+        f.zero_(); g.zero_()
+
+    _replay_matches_eager(lambda: api.fsk_sinkhorn_log_points(opts, x, y, w.eps, a, b, f, g, ws), [f, g], reset)
