@@ -253,7 +253,9 @@ int fsk_block_fused(const fsk_opts* opts, const void* K_slab, int64_t ldK, int32
  * start).  Each iteration does
  *     f_i <- eps log a_i - eps LSE_j((g_j - C_ij)/eps),  g_j <- eps log b_j - eps LSE_i((f_i - C_ij)/eps).
  * FSK_F32: the cost term runs in fp64, exponentials and their sums in fp32.  FSK_F64: everything in
- * fp64.  d <= 32 (FSK_EUNSUPPORTED above).  iters_done / err as in fsk_sinkhorn_dense. */
+ * fp64.  1 <= d <= 4096 (FSK_EUNSUPPORTED outside); d <= 32 runs the kernel that keeps a row's
+ * coordinates in registers, larger d a generic, slower one.  iters_done / err as in
+ * fsk_sinkhorn_dense. */
 int fsk_sinkhorn_log_points(const fsk_opts* opts, const void* x, const void* y, int d, double eps,
                             const void* a, const void* b, void* f, void* g, void* workspace,
                             size_t ws_bytes, int32_t* iters_done, double* err, void* stream);

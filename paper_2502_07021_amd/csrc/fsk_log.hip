@@ -73,10 +73,26 @@ __global__ __launch_bounds__(256) void log_mean_partial_kernel(const T* __restri
         ((sm[0][threadIdx.x] + sm[1][threadIdx.x]) + sm[2][threadIdx.x]) + sm[3][threadIdx.x];
 }
 
+// The same for any dp: thread k of a workgroup owns coordinates k, k + 256, ... and walks the
+// workgroup's points (g, g + groups, ...) in order.
+template <typename T>
+__global__ __launch_bounds__(256) void log_mean_partial_generic_kernel(const T* __restrict__ x,
+                                                                       const T* __restrict__ y, int n,
+                                                                       int d, int dp,
+                                                                       double* __restrict__ partial) {
+  for (int k = threadIdx.x; k < dp; k += 256) {
+    double s = 0.0;
+    if (k < d)
+      for (int i = blockIdx.x; i < n; i += gridDim.x)
+        s += (double)x[(int64_t)i * d + k] + (double)y[(int64_t)i * d + k];
+    partial[(int64_t)blockIdx.x * dp + k] = s;
+  }
+}
+
 __global__ __launch_bounds__(64) void log_mean_final_kernel(const double* __restrict__ partial,
                                                             int groups, int dp, int n,
                                                             double* __restrict__ mu) {
-  const int k = threadIdx.x;
+  const int k = blockIdx.x * 64 + threadIdx.x;
   if (k >= dp) return;
   double t = 0.0;
   for (int g = 0; g < groups; ++g) t += partial[(int64_t)g * dp + k];
@@ -161,6 +177,31 @@ __device__ __forceinline__ double exp2_of(double x) { return exp2(x); }
 __device__ __forceinline__ float max_of(float x, float y) { return fmaxf(x, y); }
 __device__ __forceinline__ double max_of(double x, double y) { return fmax(x, y); }
 
+// Adds 2^(zd[t]) for JJ values zd[t] = z_t - mref to the running pair (mref, sum), sum being
+// sum of 2^(z - mref).  The reference is raised lazily: only when a value exceeds it by
+// kLogRaise, and then exactly (in fp64) to the largest of the JJ values, so that the terms near
+// the new maximum are rounded at their final, small magnitude.
+template <typename S, int JJ>
+__device__ __forceinline__ void lse_fold(const double (&zd)[JJ], double& mref, S& sum) {
+  S zf[JJ];
+#pragma unroll
+  for (int t = 0; t < JJ; ++t) zf[t] = (S)zd[t];
+  S cm = zf[0];
+#pragma unroll
+  for (int t = 1; t < JJ; ++t) cm = max_of(cm, zf[t]);
+  if (cm > (S)kLogRaise) {  // rare
+    double zmax = zd[0];
+#pragma unroll
+    for (int t = 1; t < JJ; ++t) zmax = zd[t] > zmax ? zd[t] : zmax;
+    mref += zmax;
+    sum *= exp2_of(-(S)zmax);
+#pragma unroll
+    for (int t = 0; t < JJ; ++t) zf[t] = (S)(zd[t] - zmax);
+  }
+#pragma unroll
+  for (int t = 0; t < JJ; ++t) sum += exp2_of(zf[t]);
+}
+
 // part_m[i*slices + sl], part_s[...]: reference exponent and sum of
 // 2^(z_ij - reference) over the columns j of slice sl, z_ij = beta_j + ps_i . qc_j.
 // S: type of the exponentials and of the running sum (float for the fp32 interface: one
@@ -205,19 +246,23 @@ __global__ __launch_bounds__(kLogThreads) void log_lse_kernel(const double* __re
     }
   }
 
-  // The column coordinates come through scalar loads, one whole column ahead of the FMAs
-  // that use them.  Scalar loads complete out of order, so the only wait is "all of them":
+  // The column coordinates come through scalar loads, one fetch ahead of the FMAs that use
+  // them.  Scalar loads complete out of order, so the only wait is "all of them":
   // the empty asm statement marks the place where the current column must have arrived; the
   // next column is requested right after it and travels while the current column's FMAs run.
   // In the main loop (PIPE) that holds across chunks too: the last column of a chunk requests
   // the first column of the next one (clamped to the last column of the matrix when there is
   // none: a redundant, in-bounds read).
-  double qbuf[2][DP];
+  // A fetch brings at most 16 coordinates (32 scalar registers; two fetches are in flight), so a
+  // column of 32 coordinates travels as two parts and its FMAs run part by part.
+  constexpr int QB = DP < 16 ? DP : 16;  // coordinates per fetch
+  constexpr int H = DP / QB;             // fetches per column
+  double qbuf[2][QB];
   double bj[2];
-  auto fetch = [&](int col, int slot) {
-    const double* q = qc + (int64_t)col * DP;
+  auto fetch = [&](int col, int part, int slot) {
+    const double* q = qc + (int64_t)col * DP + part * QB;
 #pragma unroll
-    for (int k = 0; k < DP; ++k) qbuf[slot][k] = q[k];
+    for (int k = 0; k < QB; ++k) qbuf[slot][k] = q[k];
     bj[slot] = beta[col];
   };
 
@@ -225,15 +270,16 @@ __global__ __launch_bounds__(kLogThreads) void log_lse_kernel(const double* __re
     constexpr int JJ = decltype(jj_tag)::value;
     constexpr bool PIPE = decltype(pipe_tag)::value;
     static_assert(RI == 2, "fma_rows2 carries exactly two rows per lane");
-    static_assert(!PIPE || JJ % 2 == 0, "a pipelined chunk must hand slot 0 to its successor");
+    static_assert(!PIPE || (JJ * H) % 2 == 0, "a pipelined chunk must hand slot 0 to its successor");
     constexpr int G = DP >= 8 ? 8 : 4;  // coordinates per FMA block
     double zd[RI][JJ];
-    if (!PIPE) fetch(j0, 0);
+    double z[RI];
+    if (!PIPE) fetch(j0, 0, 0);
 #pragma unroll
-    for (int t = 0; t < JJ; ++t) {
-      const int slot = t & 1;
+    for (int t = 0; t < JJ * H; ++t) {  // unit t: part t % H of column t / H
+      const int slot = t & 1, col = t / H, part = t % H;
 #pragma unroll
-      for (int k0 = 0; k0 < DP; k0 += 8) {  // "use" every scalar of this column: forces the wait here
+      for (int k0 = 0; k0 < QB; k0 += 8) {  // "use" every scalar of this unit: forces the wait here
         if (DP >= 8)
           asm volatile("" : : "s"(qbuf[slot][k0]), "s"(qbuf[slot][k0 + 1]), "s"(qbuf[slot][k0 + 2]),
                        "s"(qbuf[slot][k0 + 3]), "s"(qbuf[slot][k0 + 4]), "s"(qbuf[slot][k0 + 5]),
@@ -242,50 +288,119 @@ __global__ __launch_bounds__(kLogThreads) void log_lse_kernel(const double* __re
           asm volatile("" : : "s"(qbuf[slot][0]), "s"(qbuf[slot][1]), "s"(qbuf[slot][2]),
                        "s"(qbuf[slot][3]), "s"(bj[slot]) : "memory");
       }
-      if (t + 1 < JJ) {
-        fetch(j0 + t + 1, slot ^ 1);
+      if (t + 1 < JJ * H) {
+        fetch(j0 + (t + 1) / H, (t + 1) % H, slot ^ 1);
       } else if (PIPE) {
         const int nxt = j0 + JJ < n_cols ? j0 + JJ : n_cols - 1;
-        fetch(nxt, slot ^ 1);
+        fetch(nxt, 0, slot ^ 1);
       }
-      double z[RI];
+      if (part == 0) {
 #pragma unroll
-      for (int r = 0; r < RI; ++r) z[r] = bj[slot] - mref[r];
-#pragma unroll
-      for (int k0 = 0; k0 < DP; k0 += G)
-        fma_rows2<G>(z[0], z[1], &qbuf[slot][k0], &xs[0][k0], &xs[1][k0]);
-#pragma unroll
-      for (int r = 0; r < RI; ++r) zd[r][t] = z[r];
-    }
-#pragma unroll
-    for (int r = 0; r < RI; ++r) {
-      S zf[JJ];
-#pragma unroll
-      for (int t = 0; t < JJ; ++t) zf[t] = (S)zd[r][t];
-      S cm = zf[0];
-#pragma unroll
-      for (int t = 1; t < JJ; ++t) cm = max_of(cm, zf[t]);
-      if (cm > (S)kLogRaise) {
-        // rare: move the reference up to this chunk's maximum, exactly (in fp64), so that
-        // the terms near the new maximum are rounded at their final, small magnitude
-        double zmax = zd[r][0];
-#pragma unroll
-        for (int t = 1; t < JJ; ++t) zmax = zd[r][t] > zmax ? zd[r][t] : zmax;
-        mref[r] += zmax;
-        sum[r] *= exp2_of(-(S)zmax);
-#pragma unroll
-        for (int t = 0; t < JJ; ++t) zf[t] = (S)(zd[r][t] - zmax);
+        for (int r = 0; r < RI; ++r) z[r] = bj[slot] - mref[r];
       }
 #pragma unroll
-      for (int t = 0; t < JJ; ++t) sum[r] += exp2_of(zf[t]);
+      for (int k0 = 0; k0 < QB; k0 += G)
+        fma_rows2<G>(z[0], z[1], &qbuf[slot][k0], &xs[0][part * QB + k0], &xs[1][part * QB + k0]);
+      if (part == H - 1) {
+#pragma unroll
+        for (int r = 0; r < RI; ++r) zd[r][col] = z[r];
+      }
     }
+#pragma unroll
+    for (int r = 0; r < RI; ++r) lse_fold<S, JJ>(zd[r], mref[r], sum[r]);
   };
 
   int j = jb;
-  if (j + J <= je) fetch(j, 0);
+  if (j + J <= je) fetch(j, 0, 0);
   for (; j + J <= je; j += J) chunk(j, std::integral_constant<int, J>{}, std::true_type{});
   for (; j < je; ++j) chunk(j, std::integral_constant<int, 1>{}, std::false_type{});
 
+#pragma unroll
+  for (int r = 0; r < RI; ++r) {
+    if (row[r] < n_rows) {
+      part_m[(int64_t)row[r] * slices + sl] = mref[r];
+      part_s[(int64_t)row[r] * slices + sl] = sum[r];
+    }
+  }
+}
+
+// The same for any point dimension (dp a multiple of 8): the rows' coordinates do not stay in
+// registers but are re-read (cache hits) block of 8 coordinates by block of 8 for every chunk
+// of 8 columns, whose coordinates are uniform loads.  Far from the tuned kernel's rate; it
+// exists so that the dimension is not a limit of the interface.
+template <typename S>
+__global__ __launch_bounds__(kLogThreads) void log_lse_generic_kernel(const double* __restrict__ ps,
+                                                                      const double* __restrict__ qc,
+                                                                      const double* __restrict__ beta,
+                                                                      int n_rows, int n_cols, int dp,
+                                                                      int cols_per_slice, int slices,
+                                                                      double* __restrict__ part_m,
+                                                                      S* __restrict__ part_s) {
+  constexpr int RI = kLogRowsPerLane;
+  constexpr int J = 8, KB = 8;
+  const int tid = threadIdx.x;
+  const int sl = blockIdx.y;
+  const int jb = sl * cols_per_slice;
+  const int je = jb + cols_per_slice < n_cols ? jb + cols_per_slice : n_cols;
+  int row[RI];
+  const double* xrow[RI];
+#pragma unroll
+  for (int r = 0; r < RI; ++r) {
+    row[r] = blockIdx.x * kLogRowTile + r * kLogThreads + tid;
+    const int rc = row[r] < n_rows ? row[r] : n_rows - 1;  // clamp; dropped at the store
+    xrow[r] = ps + (int64_t)rc * dp;
+  }
+  // z of JJ columns starting at j0 for both rows, relative to each row's reference
+  auto dots = [&](int j0, auto jj_tag, double (&zd)[RI][J], const double (&mref)[RI]) {
+    constexpr int JJ = decltype(jj_tag)::value;
+#pragma unroll
+    for (int t = 0; t < JJ; ++t) {
+      const double bj = beta[j0 + t];
+#pragma unroll
+      for (int r = 0; r < RI; ++r) zd[r][t] = bj - mref[r];
+    }
+    for (int k0 = 0; k0 < dp; k0 += KB) {
+      double xs[RI][KB];
+#pragma unroll
+      for (int r = 0; r < RI; ++r)
+#pragma unroll
+        for (int k = 0; k < KB; ++k) xs[r][k] = xrow[r][k0 + k];
+#pragma unroll
+      for (int t = 0; t < JJ; ++t) {
+        const double* q = qc + (int64_t)(j0 + t) * dp + k0;
+#pragma unroll
+        for (int k = 0; k < KB; ++k) {
+          const double qk = q[k];
+#pragma unroll
+          for (int r = 0; r < RI; ++r) zd[r][t] = fma(xs[r][k], qk, zd[r][t]);
+        }
+      }
+    }
+  };
+
+  double mref[RI] = {};
+  S sum[RI];
+  double zd[RI][J];
+  dots(jb, std::integral_constant<int, 1>{}, zd, mref);  // reference = z of the slice's first column
+#pragma unroll
+  for (int r = 0; r < RI; ++r) {
+    mref[r] = zd[r][0];
+    sum[r] = S(0);
+  }
+  int j = jb;
+  for (; j + J <= je; j += J) {
+    dots(j, std::integral_constant<int, J>{}, zd, mref);
+#pragma unroll
+    for (int r = 0; r < RI; ++r) lse_fold<S, J>(zd[r], mref[r], sum[r]);
+  }
+  for (; j < je; ++j) {
+    dots(j, std::integral_constant<int, 1>{}, zd, mref);
+#pragma unroll
+    for (int r = 0; r < RI; ++r) {
+      const double one[1] = {zd[r][0]};
+      lse_fold<S, 1>(one, mref[r], sum[r]);
+    }
+  }
 #pragma unroll
   for (int r = 0; r < RI; ++r) {
     if (row[r] < n_rows) {
@@ -339,10 +454,16 @@ __global__ __launch_bounds__(256) void log_finalize_kernel(const double* __restr
 // ------------------------------------------------------------------ host side
 struct LogWs {
   int dp, slices, cols_per_slice;
-  size_t mu, xc, xs, yc, ys, nx2, ny2, lna, lnb, fd, gd, bx, by, pm, psum, err, scalar, save, total;
+  size_t mu, mpart, xc, xs, yc, ys, nx2, ny2, lna, lnb, fd, gd, bx, by, pm, psum, err, scalar, save, total;
 };
 
-static int log_pad_dim(int d) { return d <= 4 ? 4 : d <= 8 ? 8 : d <= 16 ? 16 : d <= 32 ? 32 : 0; }
+constexpr int kLogMaxDim = 4096;
+// Padded dimension: 4, 8, 16, 32 select the register-resident kernel, larger multiples of 8 the
+// generic one; 0 = not supported.
+static int log_pad_dim(int d) {
+  if (d < 1 || d > kLogMaxDim) return 0;
+  return d <= 4 ? 4 : d <= 8 ? 8 : d <= 16 ? 16 : d <= 32 ? 32 : (d + 7) / 8 * 8;
+}
 
 static LogWs log_ws(int n, int d) {
   LogWs w{};
@@ -362,7 +483,8 @@ static LogWs log_ws(int n, int d) {
   size_t off = 0;
   auto take = [&](size_t bytes) { size_t o = off; off += align_up(bytes, 256); return o; };
   const size_t nd = (size_t)n * (size_t)(w.dp ? w.dp : 1) * 8, nv = (size_t)n * 8;
-  w.mu = take(32 * 8);
+  w.mu = take((size_t)(w.dp > 32 ? w.dp : 32) * 8);
+  w.mpart = take((size_t)kLogMeanGroups * (size_t)(w.dp ? w.dp : 1) * 8);  // per-workgroup coordinate sums
   w.xc = take(nd); w.xs = take(nd); w.yc = take(nd); w.ys = take(nd);
   w.nx2 = take(nv); w.ny2 = take(nv); w.lna = take(nv); w.lnb = take(nv);
   w.fd = take(nv); w.gd = take(nv); w.bx = take(nv); w.by = take(nv);
@@ -393,7 +515,13 @@ static int lse_dispatch(const LogWs& w, int n, const double* ps, const double* q
     case 8: return launch_lse<8, S>(w, n, ps, qc, beta, pm, psum, st);
     case 16: return launch_lse<16, S>(w, n, ps, qc, beta, pm, psum, st);
     case 32: return launch_lse<32, S>(w, n, ps, qc, beta, pm, psum, st);
-    default: return set_error(FSK_EUNSUPPORTED, "point dimension above 32 is not built");
+    default: {
+      dim3 grid((n + kLogRowTile - 1) / kLogRowTile, w.slices), block(kLogThreads);
+      hipLaunchKernelGGL((log_lse_generic_kernel<S>), grid, block, 0, st, ps, qc, beta, n, n, w.dp,
+                         w.cols_per_slice, w.slices, pm, psum);
+      FSK_LAUNCH_CHECK("log_lse_generic_kernel");
+      return FSK_OK;
+    }
   }
 }
 
@@ -412,18 +540,19 @@ static int run_log_typed(const fsk_opts* o, const void* x, const void* y, int d,
   T *ff = (T*)f, *gf = (T*)g;
   const int nb = (n + 255) / 256;
 
-  {  // the (still unused) slice area holds the per-workgroup coordinate sums
+  {
     int groups = (n + 255) / 256;
     if (groups > kLogMeanGroups) groups = kLogMeanGroups;
-    double* part = D(w.pm);
+    double* part = D(w.mpart);
     switch (w.dp) {
       case 4: hipLaunchKernelGGL((log_mean_partial_kernel<T, 4>), dim3(groups), dim3(256), 0, st, xf, yf, n, d, part); break;
       case 8: hipLaunchKernelGGL((log_mean_partial_kernel<T, 8>), dim3(groups), dim3(256), 0, st, xf, yf, n, d, part); break;
       case 16: hipLaunchKernelGGL((log_mean_partial_kernel<T, 16>), dim3(groups), dim3(256), 0, st, xf, yf, n, d, part); break;
-      default: hipLaunchKernelGGL((log_mean_partial_kernel<T, 32>), dim3(groups), dim3(256), 0, st, xf, yf, n, d, part); break;
+      case 32: hipLaunchKernelGGL((log_mean_partial_kernel<T, 32>), dim3(groups), dim3(256), 0, st, xf, yf, n, d, part); break;
+      default: hipLaunchKernelGGL((log_mean_partial_generic_kernel<T>), dim3(groups), dim3(256), 0, st, xf, yf, n, d, w.dp, part); break;
     }
     FSK_LAUNCH_CHECK("log_mean_partial_kernel");
-    hipLaunchKernelGGL(log_mean_final_kernel, dim3(1), dim3(64), 0, st, (const double*)part, groups, w.dp, n, D(w.mu));
+    hipLaunchKernelGGL(log_mean_final_kernel, dim3((w.dp + 63) / 64), dim3(64), 0, st, (const double*)part, groups, w.dp, n, D(w.mu));
     FSK_LAUNCH_CHECK("log_mean_final_kernel");
   }
   hipLaunchKernelGGL((log_prep_kernel<T>), dim3(nb), dim3(256), 0, st, xf, af, ff, n, d, w.dp, s,
@@ -510,7 +639,8 @@ int run_sinkhorn_log_points(const fsk_opts* o, const void* x, const void* y, int
                             const void* a, const void* b, void* f, void* g, void* workspace,
                             size_t ws_bytes, int32_t* iters_done, double* err_out,
                             hipStream_t st) {
-  if (log_pad_dim(d) == 0) return set_error(FSK_EUNSUPPORTED, "point dimension %d above 32 is not built", d);
+  if (log_pad_dim(d) == 0)
+    return set_error(FSK_EUNSUPPORTED, "point dimension %d is outside 1..%d", d, kLogMaxDim);
   return o->dtype == FSK_F64
              ? run_log_typed<double>(o, x, y, d, eps, a, b, f, g, workspace, ws_bytes, iters_done, err_out, st)
              : run_log_typed<float>(o, x, y, d, eps, a, b, f, g, workspace, ws_bytes, iters_done, err_out, st);

@@ -60,10 +60,26 @@ def test_ragged_sizes_and_dimensions(orc, n, d):
     check_potentials(orc, x, y, a, b, eps, f, g, fo, go)
 
 
-def test_dimension_above_32_is_refused():
-    x = torch.zeros(8, 40, device="cuda")
+@pytest.mark.parametrize("n,d,dtype,tol", [(1, 33, np.float32, 1e-4), (70, 33, np.float32, 1e-4),
+                                           (300, 40, np.float32, 1e-4), (521, 64, np.float32, 1e-4),
+                                           (1030, 100, np.float32, 1e-4), (300, 257, np.float32, 1e-4),
+                                           (257, 50, np.float64, 1e-10), (600, 64, np.float64, 1e-10)])
+def test_dimensions_above_32_take_the_generic_kernel(orc, n, d, dtype, tol):
+    rng = np.random.default_rng(7000 + 10 * n + d)
+    x = rng.uniform(size=(n, d)).astype(np.float32); y = rng.uniform(size=(n, d)).astype(np.float32)
+    a = rng.uniform(0.5, 1.5, n); a = (a / a.sum()).astype(np.float32)
+    b = rng.uniform(0.5, 1.5, n); b = (b / b.sum()).astype(np.float32)
+    eps = 0.02 * d
+    fo, go, _, _ = orc.sinkhorn_log_points(x, y, eps, a, b, 12)
+    f, g, _, _ = run_log(x, y, a, b, eps, 12, dtype=dtype)
+    check_potentials(orc, x, y, a, b, eps, f, g, fo, go, tol)
+
+
+def test_dimension_outside_the_supported_range_is_refused():
     v = torch.full((8,), 0.125, device="cuda")
     opts = api.make_opts(8, torch.float32, max_iters=1)
+    x = torch.zeros(8, 4097, device="cuda")
+    assert api.fsk_workspace_bytes(opts, api.FSK_MODE_LOG, 4097) == 0
     with pytest.raises(api.FskError) as e:
         api.fsk_sinkhorn_log_points(opts, x, x, 0.1, v, v, v.clone(), v.clone(),
                                     torch.empty(1 << 20, dtype=torch.uint8, device="cuda"))
