@@ -265,12 +265,15 @@ __global__ __launch_bounds__(256) void batched_prod_wide_kernel(const float* __r
   int jc = o0 + 4 * r;  // four adjacent columns of K per lane, clamped inside the row pitch
   const int jmax = (int)ld - 4;
   jc = jc < jmax ? jc : jmax;
+  // The lane's part of every K address (its column and its half-wave's row offset inside a
+  // chunk) is formed once; what changes per load, (chunk, k-step) * ld, is the same for the
+  // whole wave and stays on the scalar unit.
   const float* kcol = K + jc;
+  const float* klane = kcol + (int64_t)(kBtHalf * h) * ld;
 
   auto load_k = [&](int c, Pack<float>(&ka)[kBtHalf]) {
-    const int first = c * kBtChunk + kBtHalf * h;
 #pragma unroll
-    for (int e = 0; e < kBtHalf; ++e) ka[e] = load_pack_stream(kcol + (int64_t)(first + e) * ld);
+    for (int e = 0; e < kBtHalf; ++e) ka[e] = load_pack_stream(klane + (int64_t)(c * kBtChunk + e) * ld);
   };
   auto load_k_masked = [&](int c, Pack<float>(&ka)[kBtHalf]) {
     const int first = c * kBtChunk + kBtHalf * h;
@@ -286,9 +289,10 @@ __global__ __launch_bounds__(256) void batched_prod_wide_kernel(const float* __r
 
   const int sc = tid & 63, sk = tid >> 6;
   const float* xcol = X + (sc < m ? sc : m - 1);
+  const float* xlane = xcol + (int64_t)sk * ldm;
   auto load_x = [&](int c, float(&st)[kBtStage]) {
 #pragma unroll
-    for (int i = 0; i < kBtStage; ++i) st[i] = xcol[(int64_t)(c * kBtChunk + sk + 4 * i) * ldm];
+    for (int i = 0; i < kBtStage; ++i) st[i] = xlane[(int64_t)(c * kBtChunk + 4 * i) * ldm];
   };
   auto load_x_masked = [&](int c, float(&st)[kBtStage]) {
 #pragma unroll
@@ -335,7 +339,6 @@ __global__ __launch_bounds__(256) void batched_prod_wide_kernel(const float* __r
       b1[e] = xs[buf][kBtHalf * h + e][32 + r];
     }
     __builtin_amdgcn_sched_barrier(0);
-    const int first = cn * kBtChunk + kBtHalf * h;
 #pragma unroll
     for (int e = 0; e < kBtHalf; ++e) {
 #pragma unroll
@@ -347,8 +350,8 @@ __global__ __launch_bounds__(256) void batched_prod_wide_kernel(const float* __r
         b0[e + 2] = xs[buf][kBtHalf * h + e + 2][r];
         b1[e + 2] = xs[buf][kBtHalf * h + e + 2][32 + r];
       }
-      kn[e] = load_pack_stream(kcol + (int64_t)(first + e) * ld);
-      if (e < kBtStage) stn[e] = xcol[(int64_t)(cn * kBtChunk + sk + 4 * e) * ldm];  // early: stored at the chunk's end
+      kn[e] = load_pack_stream(klane + (int64_t)(cn * kBtChunk + e) * ld);
+      if (e < kBtStage) stn[e] = xlane[(int64_t)(cn * kBtChunk + 4 * e) * ldm];  // early: stored at the chunk's end
       __builtin_amdgcn_sched_barrier(0);
     }
   };

@@ -77,13 +77,17 @@ __global__ __launch_bounds__(256) void batched_prod_f64_kernel(const double* __r
   const int j1 = o0 + 4 * r + 2 < jmax ? o0 + 4 * r + 2 : jmax;
   const double* kc0 = K + j0;
   const double* kc1 = K + j1;
+  // The lane's part of every K address (its columns and its quarter-wave's row offset inside a
+  // chunk) is formed once; what changes per load, (chunk, k-step) * ld, is the same for the
+  // whole wave and stays on the scalar unit.
+  const double* kl0 = kc0 + (int64_t)(kB64Steps * q) * ld;
+  const double* kl1 = kc1 + (int64_t)(kB64Steps * q) * ld;
 
   auto load_k = [&](int c, K4(&ka)[kB64Steps]) {
-    const int first = c * kB64Chunk + kB64Steps * q;
 #pragma unroll
     for (int e = 0; e < kB64Steps; ++e) {
-      ka[e].lo = load_pack_stream(kc0 + (int64_t)(first + e) * ld);
-      ka[e].hi = load_pack_stream(kc1 + (int64_t)(first + e) * ld);
+      ka[e].lo = load_pack_stream(kl0 + (int64_t)(c * kB64Chunk + e) * ld);
+      ka[e].hi = load_pack_stream(kl1 + (int64_t)(c * kB64Chunk + e) * ld);
     }
   };
   auto load_k_masked = [&](int c, K4(&ka)[kB64Steps]) {
@@ -105,9 +109,10 @@ __global__ __launch_bounds__(256) void batched_prod_f64_kernel(const double* __r
 
   const int sc = tid & 63, sk = tid >> 6;
   const double* xcol = X + (sc < m ? sc : m - 1);
+  const double* xlane = xcol + (int64_t)sk * ldm;
   auto load_x = [&](int c, double(&st)[kB64Stage]) {
 #pragma unroll
-    for (int i = 0; i < kB64Stage; ++i) st[i] = xcol[(int64_t)(c * kB64Chunk + sk + 4 * i) * ldm];
+    for (int i = 0; i < kB64Stage; ++i) st[i] = xlane[(int64_t)(c * kB64Chunk + 4 * i) * ldm];
   };
   auto load_x_masked = [&](int c, double(&st)[kB64Stage]) {
 #pragma unroll
@@ -147,7 +152,6 @@ __global__ __launch_bounds__(256) void batched_prod_f64_kernel(const double* __r
   auto multiply_prefetch = [&](int buf, const K4(&ka)[kB64Steps], int cn, K4(&kn)[kB64Steps],
                                double(&stn)[kB64Stage]) {
     static_assert(kB64Stage <= kB64Steps, "one X load per k-step");
-    const int first = cn * kB64Chunk + kB64Steps * q;
     double bv[kB64Steps][4];
     read_b(buf, 0, bv[0]);
     __builtin_amdgcn_sched_barrier(0);
@@ -155,11 +159,21 @@ __global__ __launch_bounds__(256) void batched_prod_f64_kernel(const double* __r
     for (int e = 0; e < kB64Steps; ++e) {
       mfma_step(ka[e], bv[e]);
       if (e + 1 < kB64Steps) read_b(buf, e + 1, bv[e + 1]);
-      kn[e].lo = load_pack_stream(kc0 + (int64_t)(first + e) * ld);
-      kn[e].hi = load_pack_stream(kc1 + (int64_t)(first + e) * ld);
-      if (e < kB64Stage) stn[e] = xcol[(int64_t)(cn * kB64Chunk + sk + 4 * e) * ldm];
+      kn[e].lo = load_pack_stream(kl0 + (int64_t)(cn * kB64Chunk + e) * ld);
+      kn[e].hi = load_pack_stream(kl1 + (int64_t)(cn * kB64Chunk + e) * ld);
+      if (e < kB64Stage) stn[e] = xlane[(int64_t)(cn * kB64Chunk + 4 * e) * ldm];
       __builtin_amdgcn_sched_barrier(0);
     }
+  };
+
+  // Empty statements that name the accumulators as accumulation registers: left alone, the
+  // register allocator carries them across the loop's back edge in ordinary vector registers
+  // and copies all 128 of them to the accumulation file and back on every trip.
+  auto pin_acc = [&]() {
+#pragma unroll
+    for (int a = 0; a < 4; ++a)
+#pragma unroll
+      for (int b = 0; b < 4; ++b) asm volatile("" : "+a"(acc[a][b]));
   };
 
   K4 kaA[kB64Steps], kaB[kB64Steps];
@@ -171,13 +185,16 @@ __global__ __launch_bounds__(256) void batched_prod_f64_kernel(const double* __r
   }
   __syncthreads();
   int c = c0;
+  pin_acc();
   for (; c + 2 < full_end; c += 2) {  // chunks c and c + 1 both have a successor to prefetch
+    pin_acc();
     multiply_prefetch(0, kaA, c + 1, kaB, st);
     store_x(1, st);
     __syncthreads();
     multiply_prefetch(1, kaB, c + 2, kaA, st);
     store_x(0, st);
     __syncthreads();
+    pin_acc();
   }
   if (c + 1 < full_end) {  // two whole chunks left
     multiply_prefetch(0, kaA, c + 1, kaB, st);
