@@ -7,13 +7,15 @@
 // B[k = l/16][j = l%16], D[i = 4 v + l/16][j = l%16] for accumulator element v of 4.
 //
 // A wave owns a 64 x 64 output tile: 4 x 4 MFMA blocks, 64 fp64 accumulators (128 registers).
-// A lane fetches four adjacent columns of K (two 128-bit loads, 512 contiguous bytes per
-// quarter-wave), so MFMA row i of block a is column o0 + 4 i + a of K.  A chunk is 32
+// A lane fetches two pairs of adjacent columns of K with two 128-bit loads, each of which
+// covers 256 contiguous bytes (two whole cache lines) per quarter-wave: MFMA row i of block a is
+// column o0 + 32 (a / 2) + 2 i + a % 2 of K.  A chunk is 32
 // contraction indices = 8 MFMA k-steps; quarter-wave q supplies indices 8 q + e of the chunk at
 // k-step e.  The 32 x 64 chunk of the n x m operand is shared by the workgroup's four waves
-// through LDS (double buffered, one barrier per chunk); the next chunk's loads are spread
-// between the MFMAs of the current one (a wave issues in order: a burst of loads would starve
-// the matrix pipe).  The contraction range is split over grid slices; partial tiles go to the
+// through LDS (double buffered, one barrier per chunk, placed inside the chunk so that the matrix
+// pipe has work queued while the waves meet); the next chunk's loads are spread between the
+// MFMAs of the current one (a wave issues in order: a burst of loads would starve the matrix
+// pipe).  The contraction range is split over grid slices; partial tiles go to the
 // workspace and a reduction kernel adds them in slice order and divides.
 #include "fsk_device.h"
 #include "fsk_internal.h"
@@ -73,21 +75,25 @@ __global__ __launch_bounds__(256) void batched_prod_f64_kernel(const double* __r
   // two 16-byte column pairs per lane, each clamped inside the row pitch (clamped duplicates
   // only feed output rows >= n, which are never stored)
   const int jmax = (int)ld - 2;
-  const int j0 = o0 + 4 * r < jmax ? o0 + 4 * r : jmax;
-  const int j1 = o0 + 4 * r + 2 < jmax ? o0 + 4 * r + 2 : jmax;
+  const int j0 = o0 + 2 * r < jmax ? o0 + 2 * r : jmax;
+  const int j1 = o0 + 32 + 2 * r < jmax ? o0 + 32 + 2 * r : jmax;
   const double* kc0 = K + j0;
   const double* kc1 = K + j1;
-  // The lane's part of every K address (its columns and its quarter-wave's row offset inside a
-  // chunk) is formed once; what changes per load, (chunk, k-step) * ld, is the same for the
-  // whole wave and stays on the scalar unit.
-  const double* kl0 = kc0 + (int64_t)(kB64Steps * q) * ld;
-  const double* kl1 = kc1 + (int64_t)(kB64Steps * q) * ld;
-
+  // Addresses are split into a byte offset that belongs to the lane (its columns and its
+  // quarter-wave's row inside a chunk; 32 bits, formed once) and a row pointer that is the same
+  // for the whole wave and advances by one row pitch per k-step on the scalar unit, so that a
+  // load costs no vector instruction besides itself.
+  const uint32_t kb0 = (uint32_t)(((int64_t)(kB64Steps * q) * ld + j0) * 8);
+  const uint32_t kb1 = (uint32_t)(((int64_t)(kB64Steps * q) * ld + j1) * 8);
+  auto k_at = [&](const double* row, uint32_t lane_bytes) {
+    return reinterpret_cast<const double*>(reinterpret_cast<const char*>(row) + lane_bytes);
+  };
   auto load_k = [&](int c, K4(&ka)[kB64Steps]) {
+    const double* row = K + (int64_t)c * kB64Chunk * ld;
 #pragma unroll
-    for (int e = 0; e < kB64Steps; ++e) {
-      ka[e].lo = load_pack_stream(kl0 + (int64_t)(c * kB64Chunk + e) * ld);
-      ka[e].hi = load_pack_stream(kl1 + (int64_t)(c * kB64Chunk + e) * ld);
+    for (int e = 0; e < kB64Steps; ++e, row += ld) {
+      ka[e].lo = load_pack_stream(k_at(row, kb0));
+      ka[e].hi = load_pack_stream(k_at(row, kb1));
     }
   };
   auto load_k_masked = [&](int c, K4(&ka)[kB64Steps]) {
@@ -109,10 +115,11 @@ __global__ __launch_bounds__(256) void batched_prod_f64_kernel(const double* __r
 
   const int sc = tid & 63, sk = tid >> 6;
   const double* xcol = X + (sc < m ? sc : m - 1);
-  const double* xlane = xcol + (int64_t)sk * ldm;
+  const uint32_t xb = (uint32_t)(((int64_t)sk * ldm + (sc < m ? sc : m - 1)) * 8);  // lane's bytes
   auto load_x = [&](int c, double(&st)[kB64Stage]) {
+    const double* row = X + (int64_t)c * kB64Chunk * ldm;
 #pragma unroll
-    for (int i = 0; i < kB64Stage; ++i) st[i] = xlane[(int64_t)(c * kB64Chunk + 4 * i) * ldm];
+    for (int i = 0; i < kB64Stage; ++i, row += 4 * ldm) st[i] = *k_at(row, xb);
   };
   auto load_x_masked = [&](int c, double(&st)[kB64Stage]) {
 #pragma unroll
@@ -147,22 +154,57 @@ __global__ __launch_bounds__(256) void batched_prod_f64_kernel(const double* __r
 #pragma unroll
     for (int e = 0; e < kB64Steps; ++e) mfma_step(ka[e], bv[e]);
   };
-  // the MFMAs of the chunk in `ka` / xs[buf] with the loads of chunk cn spread between them and
-  // the LDS operand reads one k-step ahead of the MFMAs that use them
-  auto multiply_prefetch = [&](int buf, const K4(&ka)[kB64Steps], int cn, K4(&kn)[kB64Steps],
-                               double(&stn)[kB64Stage]) {
-    static_assert(kB64Stage <= kB64Steps, "one X load per k-step");
+  // One chunk of the steady state: the MFMAs of the chunk in `ka` / xs[buf], whose first two
+  // k-steps' B operands arrive in `bcur`, with everything the NEXT chunk (cn) needs spread
+  // between them: its K loads (two per k-step), its X loads (all in the first half, so that they
+  // have landed when they are staged), the staging into xs[buf ^ 1] and the workgroup barrier
+  // after k-step kB64Steps - 2, and the LDS reads of its first two k-steps (into `bnext`) before
+  // the last k-step.  The matrix pipe therefore never drains at a chunk boundary: no wait for
+  // memory, for the barrier or for LDS stands between the last MFMA of one chunk and the first
+  // of the next.  Two LDS buffers suffice: every read of xs[buf] has completed (the barrier's
+  // own wait) before any wave passes the barrier after which xs[buf] is written again.
+  auto chunk_step = [&](int buf, const K4(&ka)[kB64Steps], const double(&bcur)[2][4], int cn,
+                        K4(&kn)[kB64Steps], double(&bnext)[2][4]) {
+    static_assert(kB64Stage == kB64Steps, "two X loads on each of the first kB64Steps / 2 k-steps");
     double bv[kB64Steps][4];
-    read_b(buf, 0, bv[0]);
-    __builtin_amdgcn_sched_barrier(0);
+    double stn[kB64Stage];
+    const double* krow = K + (int64_t)cn * kB64Chunk * ld;
+    const double* xrow = X + (int64_t)cn * kB64Chunk * ldm;
+#pragma unroll
+    for (int b = 0; b < 4; ++b) bv[0][b] = bcur[0][b], bv[1][b] = bcur[1][b];
+#pragma unroll
+    for (int e = 0; e < kB64Steps; ++e) {
+      if (e == kB64Steps - 1) {  // after the barrier: the next chunk's first operands
+        read_b(buf ^ 1, 0, bnext[0]);
+        read_b(buf ^ 1, 1, bnext[1]);
+      }
+      mfma_step(ka[e], bv[e]);
+      if (e + 2 < kB64Steps) read_b(buf, e + 2, bv[e + 2]);
+      kn[e].lo = load_pack_stream(k_at(krow, kb0));
+      kn[e].hi = load_pack_stream(k_at(krow, kb1));
+      krow += ld;
+      if (e < kB64Steps / 2) {
+        stn[2 * e] = *k_at(xrow, xb);
+        stn[2 * e + 1] = *k_at(xrow + 4 * ldm, xb);
+        xrow += 8 * ldm;
+      }
+      if (e == kB64Steps - 2) {
+        store_x(buf ^ 1, stn);
+        __syncthreads();
+      }
+      __builtin_amdgcn_sched_barrier(0);
+    }
+  };
+  // A chunk with no successor to prepare: operands of k-steps 0, 1 in `bcur`, the rest read two
+  // k-steps ahead.
+  auto chunk_last = [&](int buf, const K4(&ka)[kB64Steps], const double(&bcur)[2][4]) {
+    double bv[kB64Steps][4];
+#pragma unroll
+    for (int b = 0; b < 4; ++b) bv[0][b] = bcur[0][b], bv[1][b] = bcur[1][b];
 #pragma unroll
     for (int e = 0; e < kB64Steps; ++e) {
       mfma_step(ka[e], bv[e]);
-      if (e + 1 < kB64Steps) read_b(buf, e + 1, bv[e + 1]);
-      kn[e].lo = load_pack_stream(kl0 + (int64_t)(cn * kB64Chunk + e) * ld);
-      kn[e].hi = load_pack_stream(kl1 + (int64_t)(cn * kB64Chunk + e) * ld);
-      if (e < kB64Stage) stn[e] = xlane[(int64_t)(cn * kB64Chunk + 4 * e) * ldm];
-      __builtin_amdgcn_sched_barrier(0);
+      if (e + 2 < kB64Steps) read_b(buf, e + 2, bv[e + 2]);
     }
   };
 
@@ -178,32 +220,28 @@ __global__ __launch_bounds__(256) void batched_prod_f64_kernel(const double* __r
 
   K4 kaA[kB64Steps], kaB[kB64Steps];
   double st[kB64Stage];
+  double bA[2][4], bB[2][4];
+  int c = c0;
   if (c0 < full_end) {
     load_k(c0, kaA);
     load_x(c0, st);
     store_x(0, st);
-  }
-  __syncthreads();
-  int c = c0;
-  pin_acc();
-  for (; c + 2 < full_end; c += 2) {  // chunks c and c + 1 both have a successor to prefetch
+    __syncthreads();
+    read_b(0, 0, bA[0]);
+    read_b(0, 1, bA[1]);
     pin_acc();
-    multiply_prefetch(0, kaA, c + 1, kaB, st);
-    store_x(1, st);
-    __syncthreads();
-    multiply_prefetch(1, kaB, c + 2, kaA, st);
-    store_x(0, st);
-    __syncthreads();
-    pin_acc();
-  }
-  if (c + 1 < full_end) {  // two whole chunks left
-    multiply_prefetch(0, kaA, c + 1, kaB, st);
-    store_x(1, st);
-    __syncthreads();
-    multiply(1, kaB);
-    __syncthreads();
-  } else if (c < full_end) {  // one
-    multiply(0, kaA);
+    for (; c + 2 < full_end; c += 2) {  // chunks c and c + 1 both have a successor to prepare
+      pin_acc();
+      chunk_step(0, kaA, bA, c + 1, kaB, bB);
+      chunk_step(1, kaB, bB, c + 2, kaA, bA);
+      pin_acc();
+    }
+    if (c + 1 < full_end) {  // two whole chunks left
+      chunk_step(0, kaA, bA, c + 1, kaB, bB);
+      chunk_last(1, kaB, bB);
+    } else {                 // one
+      chunk_last(0, kaA, bA);
+    }
     __syncthreads();
   }
   if (full_end < c1) {  // the one ragged chunk at the end of the contraction range
@@ -221,7 +259,7 @@ __global__ __launch_bounds__(256) void batched_prod_f64_kernel(const double* __r
 #pragma unroll
     for (int v = 0; v < 4; ++v) {
       const int i = 4 * v + q;  // MFMA row of accumulator element v
-      const int row = o0 + 4 * i + a;
+      const int row = o0 + 32 * (a >> 1) + 2 * i + (a & 1);
       if (row < n) {
 #pragma unroll
         for (int b = 0; b < 4; ++b) {
