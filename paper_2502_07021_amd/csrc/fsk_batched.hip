@@ -265,15 +265,18 @@ __global__ __launch_bounds__(256) void batched_prod_wide_kernel(const float* __r
   int jc = o0 + 4 * r;  // four adjacent columns of K per lane, clamped inside the row pitch
   const int jmax = (int)ld - 4;
   jc = jc < jmax ? jc : jmax;
-  // The lane's part of every K address (its column and its half-wave's row offset inside a
-  // chunk) is formed once; what changes per load, (chunk, k-step) * ld, is the same for the
-  // whole wave and stays on the scalar unit.
   const float* kcol = K + jc;
-  const float* klane = kcol + (int64_t)(kBtHalf * h) * ld;
-
+  // Addresses are split into a byte offset that belongs to the lane (its columns and its
+  // half-wave's row inside a chunk; 32 bits, formed once) and a row pointer that is the same for
+  // the whole wave and advances by one row pitch per k-step on the scalar unit.
+  const uint32_t kb = (uint32_t)(((int64_t)(kBtHalf * h) * ld + jc) * 4);
+  auto at = [&](const float* row, uint32_t lane_bytes) {
+    return reinterpret_cast<const float*>(reinterpret_cast<const char*>(row) + lane_bytes);
+  };
   auto load_k = [&](int c, Pack<float>(&ka)[kBtHalf]) {
+    const float* row = K + (int64_t)c * kBtChunk * ld;
 #pragma unroll
-    for (int e = 0; e < kBtHalf; ++e) ka[e] = load_pack_stream(klane + (int64_t)(c * kBtChunk + e) * ld);
+    for (int e = 0; e < kBtHalf; ++e, row += ld) ka[e] = load_pack_stream(at(row, kb));
   };
   auto load_k_masked = [&](int c, Pack<float>(&ka)[kBtHalf]) {
     const int first = c * kBtChunk + kBtHalf * h;
@@ -289,10 +292,11 @@ __global__ __launch_bounds__(256) void batched_prod_wide_kernel(const float* __r
 
   const int sc = tid & 63, sk = tid >> 6;
   const float* xcol = X + (sc < m ? sc : m - 1);
-  const float* xlane = xcol + (int64_t)sk * ldm;
+  const uint32_t xb = (uint32_t)(((int64_t)sk * ldm + (sc < m ? sc : m - 1)) * 4);  // lane's bytes
   auto load_x = [&](int c, float(&st)[kBtStage]) {
+    const float* row = X + (int64_t)c * kBtChunk * ldm;
 #pragma unroll
-    for (int i = 0; i < kBtStage; ++i) st[i] = xlane[(int64_t)(c * kBtChunk + 4 * i) * ldm];
+    for (int i = 0; i < kBtStage; ++i, row += 4 * ldm) st[i] = *at(row, xb);
   };
   auto load_x_masked = [&](int c, float(&st)[kBtStage]) {
 #pragma unroll
@@ -324,21 +328,63 @@ __global__ __launch_bounds__(256) void batched_prod_wide_kernel(const float* __r
     }
   };
 
-  // The MFMAs of chunk `buf` with the loads of chunk cn spread between them: one K load after
-  // every group of 8 MFMAs, the X loads after the first eight groups (they are needed first).  A burst of 24 loads at the top
-  // of the chunk holds the wave's (in-order) issue for longer than the matrix pipe has work
-  // queued; spread out, each load issues in the shadow of the MFMAs before it.  The scheduling
-  // barriers pin that order (left alone the scheduler sinks every load to the end of the chunk).
-  auto multiply_prefetch = [&](int buf, const Pack<float>(&ka)[kBtHalf], int cn,
-                               Pack<float>(&kn)[kBtHalf], float(&stn)[kBtStage]) {
-    static_assert(kBtStage <= kBtHalf, "the X loads ride on the first k-steps");
+  // One chunk of the steady state: the MFMAs of the chunk in `ka` / xs[buf], whose first two
+  // k-steps' B operands arrive in `bcur`, with everything the NEXT chunk (cn) needs spread
+  // between them: one K load per k-step, the X loads on the first kBtStage k-steps (so that they
+  // have landed when they are staged), the staging into xs[buf ^ 1] and the workgroup barrier
+  // after k-step kBtHalf - 2, and the LDS reads of the next chunk's first two k-steps (into
+  // `bnext`) before the last k-step.  A wave issues in order, so a burst of loads, a wait for
+  // memory or a barrier at the chunk boundary would leave the matrix pipe without work; spread
+  // out like this, nothing stands between the last MFMA of one chunk and the first of the next.
+  // The scheduling barriers pin the order (left alone the scheduler sinks the loads to the end
+  // of the chunk).  Two LDS buffers suffice: every read of xs[buf] has completed (the barrier's
+  // own wait) before any wave passes the barrier after which xs[buf] is written again.
+  auto chunk_step = [&](int buf, const Pack<float>(&ka)[kBtHalf], const float(&bcur)[2][2], int cn,
+                        Pack<float>(&kn)[kBtHalf], float(&bnext)[2][2]) {
+    static_assert(kBtStage <= kBtHalf - 2, "the X loads must be issued before they are staged");
     float b0[kBtHalf], b1[kBtHalf];  // B operands: two k-steps ahead of the MFMAs that use them
+    float stn[kBtStage];
+    const float* krow = K + (int64_t)cn * kBtChunk * ld;
+    const float* xrow = X + (int64_t)cn * kBtChunk * ldm;
 #pragma unroll
-    for (int e = 0; e < 2; ++e) {
-      b0[e] = xs[buf][kBtHalf * h + e][r];
-      b1[e] = xs[buf][kBtHalf * h + e][32 + r];
+    for (int e = 0; e < 2; ++e) b0[e] = bcur[e][0], b1[e] = bcur[e][1];
+#pragma unroll
+    for (int e = 0; e < kBtHalf; ++e) {
+      if (e == kBtHalf - 1) {  // after the barrier: the next chunk's first operands
+#pragma unroll
+        for (int t = 0; t < 2; ++t) {
+          bnext[t][0] = xs[buf ^ 1][kBtHalf * h + t][r];
+          bnext[t][1] = xs[buf ^ 1][kBtHalf * h + t][32 + r];
+        }
+      }
+#pragma unroll
+      for (int a = 0; a < 4; ++a) {
+        acc[a][0] = mfma32(ka[e].e[a], b0[e], acc[a][0]);
+        acc[a][1] = mfma32(ka[e].e[a], b1[e], acc[a][1]);
+      }
+      if (e + 2 < kBtHalf) {
+        b0[e + 2] = xs[buf][kBtHalf * h + e + 2][r];
+        b1[e + 2] = xs[buf][kBtHalf * h + e + 2][32 + r];
+      }
+      kn[e] = load_pack_stream(at(krow, kb));
+      krow += ld;
+      if (e < kBtStage) {
+        stn[e] = *at(xrow, xb);
+        xrow += 4 * ldm;
+      }
+      if (e == kBtHalf - 2) {
+        store_x(buf ^ 1, stn);
+        __syncthreads();
+      }
+      __builtin_amdgcn_sched_barrier(0);
     }
-    __builtin_amdgcn_sched_barrier(0);
+  };
+  // A chunk with no successor to prepare: operands of k-steps 0, 1 in `bcur`, the rest read two
+  // k-steps ahead.
+  auto chunk_last = [&](int buf, const Pack<float>(&ka)[kBtHalf], const float(&bcur)[2][2]) {
+    float b0[kBtHalf], b1[kBtHalf];
+#pragma unroll
+    for (int e = 0; e < 2; ++e) b0[e] = bcur[e][0], b1[e] = bcur[e][1];
 #pragma unroll
     for (int e = 0; e < kBtHalf; ++e) {
 #pragma unroll
@@ -350,37 +396,33 @@ __global__ __launch_bounds__(256) void batched_prod_wide_kernel(const float* __r
         b0[e + 2] = xs[buf][kBtHalf * h + e + 2][r];
         b1[e + 2] = xs[buf][kBtHalf * h + e + 2][32 + r];
       }
-      kn[e] = load_pack_stream(klane + (int64_t)(cn * kBtChunk + e) * ld);
-      if (e < kBtStage) stn[e] = xlane[(int64_t)(cn * kBtChunk + 4 * e) * ldm];  // early: stored at the chunk's end
-      __builtin_amdgcn_sched_barrier(0);
     }
   };
 
   Pack<float> kaA[kBtHalf], kaB[kBtHalf];
   float st[kBtStage];
+  float bA[2][2], bB[2][2];
+  int c = c0;
   if (c0 < full_end) {
     load_k(c0, kaA);
     load_x(c0, st);
     store_x(0, st);
-  }
-  __syncthreads();
-  int c = c0;
-  for (; c + 2 < full_end; c += 2) {  // chunks c and c + 1 both have a successor to prefetch
-    multiply_prefetch(0, kaA, c + 1, kaB, st);
-    store_x(1, st);
     __syncthreads();
-    multiply_prefetch(1, kaB, c + 2, kaA, st);
-    store_x(0, st);
-    __syncthreads();
-  }
-  if (c + 1 < full_end) {  // two whole chunks left
-    multiply_prefetch(0, kaA, c + 1, kaB, st);
-    store_x(1, st);
-    __syncthreads();
-    multiply(1, kaB);
-    __syncthreads();
-  } else if (c < full_end) {  // one
-    multiply(0, kaA);
+#pragma unroll
+    for (int t = 0; t < 2; ++t) {
+      bA[t][0] = xs[0][kBtHalf * h + t][r];
+      bA[t][1] = xs[0][kBtHalf * h + t][32 + r];
+    }
+    for (; c + 2 < full_end; c += 2) {  // chunks c and c + 1 both have a successor to prepare
+      chunk_step(0, kaA, bA, c + 1, kaB, bB);
+      chunk_step(1, kaB, bB, c + 2, kaA, bA);
+    }
+    if (c + 1 < full_end) {  // two whole chunks left
+      chunk_step(0, kaA, bA, c + 1, kaB, bB);
+      chunk_last(1, kaB, bB);
+    } else {                 // one
+      chunk_last(0, kaA, bA);
+    }
     __syncthreads();
   }
   if (full_end < c1) {
