@@ -28,7 +28,9 @@
  *     kernels are enqueued on it.  Calls that run a fixed number of iterations
  *     return as soon as the work is enqueued; calls in tolerance mode
  *     (opts->tol > 0) synchronise the stream at every poll and before they
- *     return.
+ *     return.  A fixed-iteration call only enqueues kernels (the bounded-delay
+ *     emulation also device-to-device copies): no allocation, no synchronisation,
+ *     no memset, so a caller may record it into a HIP graph and replay it.
  *   - Return value: FSK_OK or a negative fsk_status.  fsk_last_error() gives a
  *     thread-local message for the last failure.  Arguments are validated on the
  *     host before anything is launched; a failed call launches nothing.

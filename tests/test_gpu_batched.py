@@ -75,7 +75,7 @@ def test_batched_column_equals_single_histogram_run(orc):
 
 
 @pytest.mark.parametrize("n,m,small", [(300, 65, False), (513, 130, False), (1000, 200, False),
-                                         (257, 67, True), (400, 500, False)])
+                                         (257, 67, True), (400, 500, False), (200, 5000, False)])
 def test_more_than_64_histograms_go_in_column_groups(orc, n, m, small):
     """The paper stacks hundreds of targets: columns beyond 64 are served in groups of 64, each
     column still an independent run."""
