@@ -115,6 +115,13 @@ def gibbs_from_points(x, y, eps: float, normalise_by_max: bool) -> tuple[np.ndar
     return gibbs(C, eps), cmax
 
 
+def max_sqeuclid(x, y) -> float:
+    """max_ij ||x_i - y_j||^2 without forming the cost matrix (large n)."""
+    x, y = _f64(x), _f64(y)
+    return float(_load().orc_max_sqeuclid(_ptr(x), _ptr(y), _I64(x.shape[0]), _I64(y.shape[0]),
+                                          _INT(x.shape[1])))
+
+
 def gibbs_from_points_f32(x, y, eps: float, normalise_by_max: bool) -> tuple[np.ndarray, float]:
     """Same values rounded to fp32 storage, without any n x n fp64 temporary (large n)."""
     x, y = _f64(x), _f64(y)

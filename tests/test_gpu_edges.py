@@ -99,3 +99,33 @@ def test_more_blocks_than_compute_units(orc, n, c):
         if flow != api.FSK_FLOW_FUSED:      # the two-pass flows are bitwise independent of c
             u1, v1, _, _ = run_dense(K, w.a, w.b, 15, flow=api.FSK_FLOW_TWO_PASS, c=1)
             assert np.array_equal(u, u1) and np.array_equal(v, v1)
+
+
+def test_more_than_2_to_31_matrix_entries(orc):
+    """n = 46400: K has 2.15e9 entries (8.6 GB in fp32), so every element index beyond 2^31 and
+    every byte offset beyond 2^33 is exercised: the setup kernel (sampled entries against the
+    oracle's cost and exponential), then two iterations of the two-pass flow and of the blocked
+    Algorithm-1 flow against the oracle on the very K the GPU built."""
+    n = 46400
+    w = workloads.make(3, n=n)
+    opts = api.make_opts(n, torch.float32, max_iters=2, flow=api.FSK_FLOW_TWO_PASS)
+    Kd = torch.empty(n, n, device="cuda")
+    x, y = dev(w.x), dev(w.y)
+    cmax = api.fsk_kernel_from_points(opts, x, y, w.eps, True, Kd,
+                                      api.alloc_workspace(opts, api.FSK_MODE_SETUP), want_cmax=True)
+    K = Kd.cpu().numpy()
+    rng = np.random.default_rng(46)
+    rows = np.concatenate([[0, n - 1], rng.choice(n, 6, replace=False)])
+    C = orc.cost_sqeuclid(w.x[rows].astype(np.float64), w.y.astype(np.float64))
+    assert abs(cmax - orc.max_sqeuclid(w.x, w.y)) <= 1e-12 * cmax
+    ref = np.exp(-(C / cmax) / w.eps)
+    assert relerr(K[rows], ref) <= 4 * np.finfo(np.float32).eps + 20 * 2.0 ** -24
+
+    a, b = dev(w.a), dev(w.b)
+    uo, vo = orc.sinkhorn_dense(K, w.a, w.b, 2)
+    for flow, c in ((api.FSK_FLOW_TWO_PASS, 1), (api.FSK_FLOW_PAPER, 8)):
+        o = api.make_opts(n, torch.float32, c=c, max_iters=2, flow=flow)
+        u = torch.ones(n, device="cuda"); v = torch.ones(n, device="cuda")
+        api.fsk_sinkhorn_dense(o, Kd, a, b, u, v, api.alloc_workspace(o))
+        torch.cuda.synchronize()
+        assert relerr(u.cpu().numpy(), uo) <= 1e-4 and relerr(v.cpu().numpy(), vo) <= 1e-4

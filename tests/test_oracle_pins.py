@@ -58,6 +58,8 @@ def test_gibbs_f32_variant_is_the_rounded_f64_kernel(orc):
         K32, cmax32 = orc.gibbs_from_points_f32(x, y, 0.05, norm)
         assert K32.dtype == np.float32 and cmax32 == cmax
         assert np.array_equal(K32, K64.astype(np.float32))
+    assert orc.max_sqeuclid(x, y) == pytest.approx(C.max(), rel=1e-15)
+    assert orc.max_sqeuclid(x[:5], y) == pytest.approx(C[:5].max(), rel=1e-15)   # rectangular
 
 
 # ------------------------------------------- single steps vs library routines
