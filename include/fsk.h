@@ -88,7 +88,9 @@ typedef enum {
 typedef enum {
   FSK_DAMP_NONE = 0,
   FSK_DAMP_ARITHMETIC = 1, /* u <- (1-eta) u + eta a./(K v)            (Sec. 3.3)             */
-  FSK_DAMP_GEOMETRIC = 2   /* u <- u^(1-eta) .* (a./(K v))^eta         (Remark in Sec. 3.3)   */
+  FSK_DAMP_GEOMETRIC = 2   /* u <- u^(1-eta) .* (a./(K v))^eta         (Remark in Sec. 3.3);
+                              FSK_FLOW_FUSED carries it in fp32 (as exp2 of the weighted log2's);
+                              in fp64 the call runs the two-pass kernels instead               */
 } fsk_damping;
 
 typedef struct {

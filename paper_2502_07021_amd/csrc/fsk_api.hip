@@ -193,8 +193,9 @@ static int dense_iteration(const fsk_opts* o, const DenseWs& w, const char* K, i
   FusedPlan plan{};
   if (flow == FSK_FLOW_FUSED) {
     plan = fused_plan(dt, n, m, c);
-    // rows too long to hold in registers, or an update the fused kernel does not carry
-    if (!plan.ok || epi == kEpiDampGeom) flow = FSK_FLOW_TWO_PASS;
+    // rows too long to hold in registers, or the geometric relaxation in fp64 (its log2 / exp2
+    // do not fit the fused kernel's register budget)
+    if (!plan.ok || (epi == kEpiDampGeom && dt == FSK_F64)) flow = FSK_FLOW_TWO_PASS;
   }
   if (ev) FSK_HIP(hipEventRecord(ev[0], st));
   if (flow == FSK_FLOW_FUSED) {
@@ -755,8 +756,6 @@ int fsk_block_fused(const fsk_opts* opts, const void* K_slab, int64_t ldK, int32
   if (!plan.ok)
     return set_error(FSK_EUNSUPPORTED, "n = %d is too long for the register-resident fused kernel",
                      opts->n);
-  if (opts->damping == FSK_DAMP_GEOMETRIC)
-    return set_error(FSK_EUNSUPPORTED, "the fused kernel does not carry the geometric relaxation");
   const size_t s = elem_size(opts->dtype);
   const int64_t ld_ws = (int64_t)align_up((size_t)opts->n, 64);
   const size_t need = (size_t)plan.wgs * (size_t)ld_ws * s;

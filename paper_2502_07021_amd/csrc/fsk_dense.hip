@@ -272,6 +272,11 @@ int launch_colreduce(int dtype, const void* partial, int64_t ld_ws, int n_partia
              : colreduce_typed<float>(partial, ld_ws, n_partials, c0, c1, marg, old, out, epi, eta, stream);
 }
 
+__device__ __forceinline__ float fsk_log2(float x) { return log2f(x); }
+__device__ __forceinline__ double fsk_log2(double x) { return (double)log2f((float)x); }  // never reached
+__device__ __forceinline__ float fsk_exp2(float x) { return exp2f(x); }
+__device__ __forceinline__ double fsk_exp2(double x) { return (double)exp2f((float)x); }  // never reached
+
 // ============================================================ fused one-pass kernel
 // One workgroup of 512 threads (8 waves, 2 per SIMD, up to 256 VGPRs each) per
 // compute unit.  Thread t owns the packs t, t+512, ... of every row: VPT packs
@@ -291,7 +296,10 @@ __global__ __launch_bounds__(512) void fused_kernel(const T* __restrict__ K, int
   // err_out (may be null): |old_u_i (K v)_i - marg_i| per row, the row-marginal error term of
   // the scalings as they stood before this update (free: the product is at hand).
   // EXACT: n == VPT*512*W, every pack of every thread is a full pack inside the row.
-  // eta < 1 selects the arithmetic relaxation u <- (1-eta) u + eta a./(K v) (Sec. 3.3).
+  // |eta| < 1 selects a relaxation (Sec. 3.3): eta > 0 the arithmetic one,
+  // u <- (1-eta) u + eta a./(K v); eta < 0 the geometric one with parameter -eta,
+  // u <- u^(1+eta) (a./(K v))^(-eta), evaluated as exp2 of the weighted log2's (a general pow
+  // would not fit the kernel's register budget); fp32 only, the launcher refuses it in fp64.
   constexpr int W = Pack<T>::W;
   constexpr int NT = 512, NW = NT / kWave;
   extern __shared__ __align__(16) unsigned char fsk_smem[];
@@ -307,7 +315,9 @@ __global__ __launch_bounds__(512) void fused_kernel(const T* __restrict__ K, int
   const int groups = (rows + R - 1) / R;               // row groups per row block
   const int spb = (groups + G - 1) / G;                // steps this workgroup spends on one block
   const int total = ((nblk - team + nb - 1) / nb) * spb;  // steps over all blocks of the team
-  const bool damped = eta < T(1);
+  const bool geom = eta < T(0);
+  const T et = geom ? -eta : eta;
+  const bool damped = et < T(1);
 
   // stage v into LDS
 #pragma unroll
@@ -402,7 +412,12 @@ __global__ __launch_bounds__(512) void fused_kernel(const T* __restrict__ K, int
       T ur = T(0);
       if (row < rows) {
         ur = mg[r] / q;
-        if (damped) ur = (T(1) - eta) * od[r] + eta * ur;
+        if (damped) {
+          if (sizeof(T) == 4 && geom)  // fp32 only: the fp64 log2 / exp2 would spill
+            ur = fsk_exp2(fma(T(1) - et, fsk_log2(od[r]), et * fsk_log2(ur)));
+          else
+            ur = (T(1) - et) * od[r] + et * ur;
+        }
         if (tid == 0) {
           if (err_out) err_out[rbase + row] = fsk_abs(od[r] * q - mg[r]);
           u_out[rbase + row] = ur;
@@ -522,9 +537,14 @@ int launch_fused(int dtype, const FusedPlan& plan, const void* K, int64_t ld, in
                  void* partial, int64_t ld_ws, int epi, double eta, hipStream_t stream,
                  void* err_out) {
   if (!plan.ok) return set_error(FSK_EUNSUPPORTED, "fused kernel: n = %d does not fit in registers", n);
-  if (epi != kEpiDivide && epi != kEpiDampArith)
-    return set_error(FSK_EUNSUPPORTED, "fused kernel: only the plain and the arithmetic-damped update");
+  if (epi != kEpiDivide && epi != kEpiDampArith && epi != kEpiDampGeom)
+    return set_error(FSK_EUNSUPPORTED, "fused kernel: only the plain and the damped updates");
   if (epi == kEpiDivide) eta = 1.0;
+  if (epi == kEpiDampGeom) {
+    if (dtype == FSK_F64)
+      return set_error(FSK_EUNSUPPORTED, "fused kernel: the geometric relaxation exists in fp32 only");
+    eta = -eta;  // the kernel's encoding of the geometric relaxation
+  }
   return dtype == FSK_F64
              ? fused_dispatch<double>(plan, K, ld, n, rows, c, marg, vin, old_u, u_out, partial,
                                       ld_ws, eta, err_out, stream)
