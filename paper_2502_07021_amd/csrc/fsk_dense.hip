@@ -295,7 +295,9 @@ __global__ __launch_bounds__(512) void fused_kernel(const T* __restrict__ K, int
                                                     int64_t ld_ws, T eta, T* err_out) {
   // err_out (may be null): |old_u_i (K v)_i - marg_i| per row, the row-marginal error term of
   // the scalings as they stood before this update (free: the product is at hand).
-  // EXACT: n == VPT*512*W, every pack of every thread is a full pack inside the row.
+  // VPT = ceil(packs per row / 512), so the packs of slots i < VPT - 1 are whole and inside the
+  // row for every thread and only the last slot can hold a partial pack or none.
+  // EXACT: n == VPT*512*W, the last slot is whole too and nothing is masked.
   // |eta| < 1 selects a relaxation (Sec. 3.3): eta > 0 the arithmetic one,
   // u <- (1-eta) u + eta a./(K v); eta < 0 the geometric one with parameter -eta,
   // u <- u^(1+eta) (a./(K v))^(-eta), evaluated as exp2 of the weighted log2's (a general pow
@@ -326,7 +328,7 @@ __global__ __launch_bounds__(512) void fused_kernel(const T* __restrict__ K, int
     Pack<T> p;
 #pragma unroll
     for (int e = 0; e < W; ++e) p.e[e] = T(0);
-    if (EXACT || vi < nvec_full) {
+    if (EXACT || i < VPT - 1 || vi < nvec_full) {
       p = load_pack(vin + (int64_t)vi * W);
     } else if (vi < nvec) {
 #pragma unroll
@@ -343,6 +345,14 @@ __global__ __launch_bounds__(512) void fused_kernel(const T* __restrict__ K, int
   for (int i = 0; i < VPT; ++i)
 #pragma unroll
     for (int e = 0; e < W; ++e) acc[i].e[e] = T(0);
+
+  // The last slot of a thread: its pack index clamped into the row (a redundant, in-bounds read
+  // for threads past the end) and which of its elements are columns of K.
+  const int tail_vi = (VPT - 1) * NT + tid;
+  const int tail_back = tail_vi < nvec ? 0 : (tail_vi - (nvec - 1)) * W;
+  bool tail_ok[W];
+#pragma unroll
+  for (int e = 0; e < W; ++e) tail_ok[e] = tail_vi * W + e < n;
 
   // Teams start their sweep at different offsets inside their blocks (a rotation of the
   // group index), which keeps the concurrent streams of different teams from marching
@@ -366,15 +376,13 @@ __global__ __launch_bounds__(512) void fused_kernel(const T* __restrict__ K, int
       od[r] = (damped || err_out) ? old_u[rbase + row] : T(0);
 #pragma unroll
       for (int i = 0; i < VPT; ++i) {
-        if (EXACT) {
+        if (EXACT || i < VPT - 1) {
           buf[r][i] = load_pack_stream(kp + i * NT * W);
         } else {
-          const int vi = i * NT + tid;
-          const int back = vi < nvec ? 0 : (vi - (nvec - 1)) * W;  // clamp to the last pack
-          Pack<T> p = load_pack_stream(kp + i * NT * W - back);
+          Pack<T> p = load_pack_stream(kp + i * NT * W - tail_back);
 #pragma unroll
           for (int e = 0; e < W; ++e)
-            if (vi * W + e >= n) p.e[e] = T(0);  // padding columns and clamped duplicates
+            if (!tail_ok[e]) p.e[e] = T(0);  // padding columns and clamped duplicates
           buf[r][i] = p;
         }
       }
@@ -433,7 +441,7 @@ __global__ __launch_bounds__(512) void fused_kernel(const T* __restrict__ K, int
 #pragma unroll
       for (int i = 0; i < VPT; ++i) {
         const int vi = i * NT + tid;
-        if (EXACT || vi < nvec) store_pack(prow + (int64_t)vi * W, acc[i]);
+        if (EXACT || i < VPT - 1 || vi < nvec) store_pack(prow + (int64_t)vi * W, acc[i]);
 #pragma unroll
         for (int e = 0; e < W; ++e) acc[i].e[e] = T(0);
       }
@@ -469,9 +477,8 @@ FusedPlan fused_plan(int dtype, int n, int rows, int c) {
   FusedPlan p{};
   const int W = pack_width(dtype);
   const int nvec = (n + W - 1) / W;
-  int vpt = 1;
-  while (vpt * 512 < nvec) vpt *= 2;
-  p.ok = vpt <= 16 && rows > 0 && n > 0;
+  const int vpt = (nvec + 511) / 512;
+  p.ok = vpt >= 1 && vpt <= 16 && rows > 0 && n > 0;
   if (!p.ok) return p;
   p.vpt = vpt;
   p.r = fused_rows_per_group(vpt);
@@ -524,8 +531,19 @@ static int fused_dispatch(const FusedPlan& plan, const void* K, int64_t ld, int 
   switch (plan.vpt) {
     FSK_FUSED_CASE(1);
     FSK_FUSED_CASE(2);
+    FSK_FUSED_CASE(3);
     FSK_FUSED_CASE(4);
+    FSK_FUSED_CASE(5);
+    FSK_FUSED_CASE(6);
+    FSK_FUSED_CASE(7);
     FSK_FUSED_CASE(8);
+    FSK_FUSED_CASE(9);
+    FSK_FUSED_CASE(10);
+    FSK_FUSED_CASE(11);
+    FSK_FUSED_CASE(12);
+    FSK_FUSED_CASE(13);
+    FSK_FUSED_CASE(14);
+    FSK_FUSED_CASE(15);
     FSK_FUSED_CASE(16);
     default: return set_error(FSK_EUNSUPPORTED, "fused kernel: n = %d does not fit in registers", n);
   }
