@@ -287,6 +287,8 @@ __device__ __forceinline__ double fsk_exp2(double x) { return (double)exp2f((flo
 // wave sums, one barrier, u = a ./ q, then acc += K_row * u from the same
 // registers.  K is read exactly once; row groups are dealt round-robin to the
 // workgroups of a block so every compute unit streams the same number of rows.
+constexpr int kFusedWindow = 5;
+
 template <typename T, int VPT, int R, bool EXACT>
 __global__ __launch_bounds__(512) void fused_kernel(const T* __restrict__ K, int64_t ld, int n,
                                                     int rows, int nblk, int gb, const T* marg,
@@ -378,6 +380,12 @@ __global__ __launch_bounds__(512) void fused_kernel(const T* __restrict__ K, int
       for (int i = 0; i < VPT; ++i) {
         if (EXACT || i < VPT - 1) {
           buf[r][i] = load_pack_stream(kp + i * NT * W);
+          // Long rows: a thread keeps at most kFusedWindow K loads in flight.  The memory system
+          // delivers a little more when the 256 streams ask for ~40 KiB at a time than when each
+          // posts a whole 128 KiB row at once (measured: 607 against 618 us per launch at
+          // n = 32768, 349 against 360 at 24576, 162.1 against 163.8 at 16384; shorter rows and
+          // the 9-11 packs per thread around n = 20000 lose from it).
+          if (VPT == 8 || VPT >= 12) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(kFusedWindow - 1) : "memory");
         } else {
           Pack<T> p = load_pack_stream(kp + i * NT * W - tail_back);
 #pragma unroll
