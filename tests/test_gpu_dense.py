@@ -228,3 +228,42 @@ def test_end_to_end_with_gpu_setup(orc):
     K64, _ = orc.gibbs_from_points(w.x, w.y, w.eps, True)
     uo, vo = orc.sinkhorn_dense(K64, w.a, w.b, 200)
     assert relerr(u, uo) <= 1e-4 and relerr(v, vo) <= 1e-4
+
+
+@pytest.mark.parametrize("dtype", [np.float32, np.float64])
+def test_every_pack_count_of_the_fused_kernel(dtype):
+    """The fused kernel has one variant per number of 16-byte packs a thread holds of a row (1 to
+    16), each with and without masking of the last slot.  For every variant: one-step consistency
+    of the second iteration on sampled rows and columns, the definition written out in NumPy fp64
+    on slices of the K the GPU holds (row pitch padded with NaN columns where n is ragged)."""
+    td = tdtype(dtype)
+    es = np.dtype(dtype).itemsize
+    pack = 16 // es
+    tol = TOL[np.dtype(dtype)]
+    rng = np.random.default_rng(99)
+    for vpt in range(1, 17):
+        for ragged in (0, 5):
+            n = 512 * pack * vpt - ragged
+            ld = (n + pack - 1) // pack * pack + (pack if ragged else 0)
+            x = dev(rng.standard_normal((n, 3)).astype(dtype)); y = dev(rng.standard_normal((n, 3)).astype(dtype))
+            a64 = rng.uniform(0.5, 1.5, n); a64 /= a64.sum()
+            b64 = rng.uniform(0.5, 1.5, n); b64 /= b64.sum()
+            a = dev(a64.astype(dtype)); b = dev(b64.astype(dtype))
+            full = torch.full((n, ld), float("nan"), dtype=td, device="cuda")
+            K = full[:, :n]
+            opts = api.make_opts(n, td, max_iters=1)
+            api.fsk_kernel_from_points(opts, x, y, 0.1, True, K, api.alloc_workspace(opts, api.FSK_MODE_SETUP))
+            ws = api.alloc_workspace(opts)
+            u = torch.ones(n, dtype=td, device="cuda"); v = torch.ones(n, dtype=td, device="cuda")
+            api.fsk_sinkhorn_dense(opts, K, a, b, u, v, ws)
+            v1 = v.clone()
+            api.fsk_sinkhorn_dense(opts, K, a, b, u, v, ws)
+            torch.cuda.synchronize()
+            idx = np.unique(np.concatenate([[0, n - 1], rng.choice(n, 30, replace=False)]))
+            tix = torch.from_numpy(idx).cuda()
+            q = K[tix].double().cpu().numpy() @ v1.double().cpu().numpy()
+            assert relerr(u[tix].cpu().numpy(), a.double().cpu().numpy()[idx] / q) <= tol, (vpt, ragged)
+            r = K[:, tix].double().cpu().numpy().T @ u.double().cpu().numpy()
+            assert relerr(v[tix].cpu().numpy(), b.double().cpu().numpy()[idx] / r) <= tol, (vpt, ragged)
+            assert bool(torch.isfinite(u).all()) and bool(torch.isfinite(v).all())
+            del full, K
