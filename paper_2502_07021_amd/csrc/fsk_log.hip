@@ -255,8 +255,8 @@ __global__ __launch_bounds__(kLogThreads) void log_lse_kernel(const double* __re
   // none: a redundant, in-bounds read).
   // A fetch brings at most 16 coordinates (32 scalar registers; two fetches are in flight), so a
   // column of 32 coordinates travels as two parts and its FMAs run part by part.
-  constexpr int QB = DP < 16 ? DP : 16;  // coordinates per fetch
-  constexpr int H = DP / QB;             // fetches per column
+  constexpr int H = DP > 16 ? 2 : 1;     // fetches per column
+  constexpr int QB = DP / H;             // coordinates per fetch: 4, 8, 12 or 16
   double qbuf[2][QB];
   double bj[2];
   auto fetch = [&](int col, int part, int slot) {
@@ -271,7 +271,6 @@ __global__ __launch_bounds__(kLogThreads) void log_lse_kernel(const double* __re
     constexpr bool PIPE = decltype(pipe_tag)::value;
     static_assert(RI == 2, "fma_rows2 carries exactly two rows per lane");
     static_assert(!PIPE || (JJ * H) % 2 == 0, "a pipelined chunk must hand slot 0 to its successor");
-    constexpr int G = DP >= 8 ? 8 : 4;  // coordinates per FMA block
     double zd[RI][JJ];
     double z[RI];
     if (!PIPE) fetch(j0, 0, 0);
@@ -279,15 +278,9 @@ __global__ __launch_bounds__(kLogThreads) void log_lse_kernel(const double* __re
     for (int t = 0; t < JJ * H; ++t) {  // unit t: part t % H of column t / H
       const int slot = t & 1, col = t / H, part = t % H;
 #pragma unroll
-      for (int k0 = 0; k0 < QB; k0 += 8) {  // "use" every scalar of this unit: forces the wait here
-        if (DP >= 8)
-          asm volatile("" : : "s"(qbuf[slot][k0]), "s"(qbuf[slot][k0 + 1]), "s"(qbuf[slot][k0 + 2]),
-                       "s"(qbuf[slot][k0 + 3]), "s"(qbuf[slot][k0 + 4]), "s"(qbuf[slot][k0 + 5]),
-                       "s"(qbuf[slot][k0 + 6]), "s"(qbuf[slot][k0 + 7]), "s"(bj[slot]) : "memory");
-        else
-          asm volatile("" : : "s"(qbuf[slot][0]), "s"(qbuf[slot][1]), "s"(qbuf[slot][2]),
-                       "s"(qbuf[slot][3]), "s"(bj[slot]) : "memory");
-      }
+      for (int k0 = 0; k0 < QB; k0 += 4)  // "use" every scalar of this unit: forces the wait here
+        asm volatile("" : : "s"(qbuf[slot][k0]), "s"(qbuf[slot][k0 + 1]), "s"(qbuf[slot][k0 + 2]),
+                     "s"(qbuf[slot][k0 + 3]), "s"(bj[slot]) : "memory");
       if (t + 1 < JJ * H) {
         fetch(j0 + (t + 1) / H, (t + 1) % H, slot ^ 1);
       } else if (PIPE) {
@@ -299,8 +292,12 @@ __global__ __launch_bounds__(kLogThreads) void log_lse_kernel(const double* __re
         for (int r = 0; r < RI; ++r) z[r] = bj[slot] - mref[r];
       }
 #pragma unroll
-      for (int k0 = 0; k0 < QB; k0 += G)
-        fma_rows2<G>(z[0], z[1], &qbuf[slot][k0], &xs[0][part * QB + k0], &xs[1][part * QB + k0]);
+      for (int k0 = 0; k0 < QB; k0 += 8) {  // FMA blocks of 8 coordinates, a last one of 4
+        if (QB - k0 >= 8)
+          fma_rows2<8>(z[0], z[1], &qbuf[slot][k0], &xs[0][part * QB + k0], &xs[1][part * QB + k0]);
+        else
+          fma_rows2<4>(z[0], z[1], &qbuf[slot][k0], &xs[0][part * QB + k0], &xs[1][part * QB + k0]);
+      }
       if (part == H - 1) {
 #pragma unroll
         for (int r = 0; r < RI; ++r) zd[r][col] = z[r];
@@ -458,11 +455,11 @@ struct LogWs {
 };
 
 constexpr int kLogMaxDim = 4096;
-// Padded dimension: 4, 8, 16, 32 select the register-resident kernel, larger multiples of 8 the
+// Padded dimension: 4, 8, 12, 16, 24, 32 select the register-resident kernel, larger multiples of 8 the
 // generic one; 0 = not supported.
 static int log_pad_dim(int d) {
   if (d < 1 || d > kLogMaxDim) return 0;
-  return d <= 4 ? 4 : d <= 8 ? 8 : d <= 16 ? 16 : d <= 32 ? 32 : (d + 7) / 8 * 8;
+  return d <= 4 ? 4 : d <= 8 ? 8 : d <= 12 ? 12 : d <= 16 ? 16 : d <= 24 ? 24 : d <= 32 ? 32 : (d + 7) / 8 * 8;
 }
 
 static LogWs log_ws(int n, int d) {
@@ -513,7 +510,9 @@ static int lse_dispatch(const LogWs& w, int n, const double* ps, const double* q
   switch (w.dp) {
     case 4: return launch_lse<4, S>(w, n, ps, qc, beta, pm, psum, st);
     case 8: return launch_lse<8, S>(w, n, ps, qc, beta, pm, psum, st);
+    case 12: return launch_lse<12, S>(w, n, ps, qc, beta, pm, psum, st);
     case 16: return launch_lse<16, S>(w, n, ps, qc, beta, pm, psum, st);
+    case 24: return launch_lse<24, S>(w, n, ps, qc, beta, pm, psum, st);
     case 32: return launch_lse<32, S>(w, n, ps, qc, beta, pm, psum, st);
     default: {
       dim3 grid((n + kLogRowTile - 1) / kLogRowTile, w.slices), block(kLogThreads);
@@ -547,7 +546,9 @@ static int run_log_typed(const fsk_opts* o, const void* x, const void* y, int d,
     switch (w.dp) {
       case 4: hipLaunchKernelGGL((log_mean_partial_kernel<T, 4>), dim3(groups), dim3(256), 0, st, xf, yf, n, d, part); break;
       case 8: hipLaunchKernelGGL((log_mean_partial_kernel<T, 8>), dim3(groups), dim3(256), 0, st, xf, yf, n, d, part); break;
+      case 12: hipLaunchKernelGGL((log_mean_partial_kernel<T, 12>), dim3(groups), dim3(256), 0, st, xf, yf, n, d, part); break;
       case 16: hipLaunchKernelGGL((log_mean_partial_kernel<T, 16>), dim3(groups), dim3(256), 0, st, xf, yf, n, d, part); break;
+      case 24: hipLaunchKernelGGL((log_mean_partial_kernel<T, 24>), dim3(groups), dim3(256), 0, st, xf, yf, n, d, part); break;
       case 32: hipLaunchKernelGGL((log_mean_partial_kernel<T, 32>), dim3(groups), dim3(256), 0, st, xf, yf, n, d, part); break;
       default: hipLaunchKernelGGL((log_mean_partial_generic_kernel<T>), dim3(groups), dim3(256), 0, st, xf, yf, n, d, w.dp, part); break;
     }

@@ -48,7 +48,8 @@ def test_cfg4_law_fixed_iterations(orc, n):
 
 
 @pytest.mark.parametrize("n,d", [(1, 16), (2, 3), (3, 1), (65, 2), (257, 5), (513, 8), (700, 16),
-                                 (300, 20), (300, 32)])
+                                 (300, 20), (300, 32), (400, 10), (333, 12), (300, 17), (515, 24),
+                                 (300, 25)])
 def test_ragged_sizes_and_dimensions(orc, n, d):
     rng = np.random.default_rng(100 * n + d)
     x = rng.uniform(size=(n, d)).astype(np.float32); y = rng.uniform(size=(n, d)).astype(np.float32)
