@@ -1,0 +1,112 @@
+"""Seeded random VALID problems (size, precision, flow, block count, damping, row pitch, iteration
+count drawn at random) through the C ABI against the oracle, at the usual bars: 1e-4 (fp32) and
+1e-10 (fp64) on the scalings (|f - f_oracle| / eps in the log domain).  Complements the
+hand-picked sizes of the other files."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2502_07021_amd import api
+from gpu_util import dev, relerr
+
+pytestmark = pytest.mark.gpu
+
+
+def _pick(rng):
+    dtype = np.float32 if rng.random() < 0.6 else np.float64
+    return dtype, (torch.float32 if dtype == np.float32 else torch.float64), (1e-4 if dtype == np.float32 else 1e-10)
+
+
+def _padded(K, td, extra_packs):
+    n = K.shape[0]
+    pack = 16 // K.dtype.itemsize
+    ld = (n + pack - 1) // pack * pack + pack * extra_packs
+    full = torch.full((n, ld), float("nan"), dtype=td, device="cuda")
+    full[:, :n] = dev(K)
+    return full
+
+
+@pytest.mark.parametrize("seed", [11, 12, 13, 14])
+def test_random_dense_problems(orc, seed):
+    rng = np.random.default_rng(seed)
+    for case in range(25):
+        dtype, td, tol = _pick(rng)
+        n = int(rng.choice([rng.integers(1, 70), rng.integers(1, 1200), rng.integers(1000, 4200),
+                            rng.integers(4000, 9000)], p=[0.2, 0.4, 0.3, 0.1]))
+        resident_ok = n <= (1024 if dtype == np.float32 else 512)
+        flow = int(rng.choice([api.FSK_FLOW_FUSED, api.FSK_FLOW_TWO_PASS, api.FSK_FLOW_PAPER]
+                              + ([api.FSK_FLOW_RESIDENT] if resident_ok else [])))
+        c = int(rng.choice([k for k in range(1, min(n, 64) + 1) if n % k == 0]))
+        damping = int(rng.choice([api.FSK_DAMP_NONE, api.FSK_DAMP_ARITHMETIC, api.FSK_DAMP_GEOMETRIC],
+                                 p=[0.6, 0.25, 0.15]))
+        if flow == api.FSK_FLOW_RESIDENT and damping == api.FSK_DAMP_GEOMETRIC:
+            damping = api.FSK_DAMP_ARITHMETIC
+        eta = float(rng.uniform(0.3, 1.0))
+        iters = int(rng.integers(1, 6))
+        d = int(rng.integers(1, 5))
+        x = rng.standard_normal((n, d)); y = rng.standard_normal((n, d)) + 0.3
+        K64, _ = orc.gibbs_from_points(x, y, float(rng.uniform(0.2, 1.0)), True)
+        K = np.ascontiguousarray(K64.astype(dtype))
+        a = rng.uniform(0.5, 1.5, n); a = (a / a.sum()).astype(dtype)
+        b = rng.uniform(0.5, 1.5, n); b = (b / b.sum()).astype(dtype)
+        full = _padded(K, td, int(rng.integers(0, 3)))
+        opts = api.make_opts(n, td, c=c, max_iters=iters, flow=flow, damping=damping, eta=eta)
+        u = torch.ones(n, dtype=td, device="cuda"); v = torch.ones(n, dtype=td, device="cuda")
+        api.fsk_sinkhorn_dense(opts, full[:, :n], dev(a), dev(b), u, v, api.alloc_workspace(opts))
+        torch.cuda.synchronize()
+        if damping == api.FSK_DAMP_NONE:
+            uo, vo = orc.sinkhorn_dense(K, a, b, iters)
+        else:
+            uo, vo = orc.sinkhorn_dense_damped(K, a, b, iters, eta, damping == api.FSK_DAMP_GEOMETRIC)
+        what = (seed, case, n, np.dtype(dtype).name, flow, c, damping, iters)
+        assert relerr(u.cpu().numpy(), uo) <= tol and relerr(v.cpu().numpy(), vo) <= tol, what
+        assert bool(torch.isnan(full[:, n:]).all()), what          # the padding columns are never written
+
+
+@pytest.mark.parametrize("seed", [21, 22])
+def test_random_multitarget_problems(orc, seed):
+    rng = np.random.default_rng(seed)
+    for case in range(20):
+        dtype, td, tol = _pick(rng)
+        n = int(rng.choice([rng.integers(1, 100), rng.integers(100, 1500), rng.integers(1500, 3000)]))
+        m = int(rng.choice([1, rng.integers(1, 65), rng.integers(65, 300)]))
+        iters = int(rng.integers(1, 5))
+        x = rng.uniform(size=(n, 2)); y = rng.uniform(size=(n, 2))
+        K64, _ = orc.gibbs_from_points(x, y, float(rng.uniform(0.2, 1.0)), False)
+        K = np.ascontiguousarray(K64.astype(dtype))
+        A = rng.exponential(size=(n, m)); A = np.ascontiguousarray((A / A.sum(0)).astype(dtype))
+        B = rng.exponential(size=(n, m)); B = np.ascontiguousarray((B / B.sum(0)).astype(dtype))
+        full = _padded(K, td, int(rng.integers(0, 2)))
+        opts = api.make_opts(n, td, m=m, max_iters=iters)
+        ws = api.alloc_workspace(opts, api.FSK_MODE_BATCHED)
+        if dtype == np.float32 and rng.random() < 0.25:            # no room for K^T: the direct row kernel
+            ws = ws[: ws.numel() - n * n * 4]
+        U = torch.ones(n, m, dtype=td, device="cuda"); V = torch.ones(n, m, dtype=td, device="cuda")
+        api.fsk_sinkhorn_batched(opts, full[:, :n], dev(A), dev(B), U, V, ws)
+        torch.cuda.synchronize()
+        Uo, Vo = orc.sinkhorn_batched(K, A, B, iters)
+        what = (seed, case, n, m, np.dtype(dtype).name, iters)
+        assert relerr(U.cpu().numpy(), Uo) <= tol and relerr(V.cpu().numpy(), Vo) <= tol, what
+
+
+@pytest.mark.parametrize("seed", [31, 32])
+def test_random_log_domain_problems(orc, seed):
+    rng = np.random.default_rng(seed)
+    for case in range(20):
+        dtype, td, tol = _pick(rng)
+        n = int(rng.choice([rng.integers(1, 100), rng.integers(100, 1500), rng.integers(1500, 3000)]))
+        d = int(rng.choice([rng.integers(1, 33), rng.integers(33, 80)], p=[0.8, 0.2]))
+        iters = int(rng.integers(1, 6))
+        eps = float(rng.uniform(0.01, 0.1)) * d
+        x = rng.uniform(size=(n, d)).astype(np.float32); y = rng.uniform(size=(n, d)).astype(np.float32)
+        a = rng.uniform(0.5, 1.5, n); a = (a / a.sum()).astype(np.float32)
+        b = rng.uniform(0.5, 1.5, n); b = (b / b.sum()).astype(np.float32)
+        opts = api.make_opts(n, td, max_iters=iters)
+        f = torch.zeros(n, dtype=td, device="cuda"); g = torch.zeros(n, dtype=td, device="cuda")
+        api.fsk_sinkhorn_log_points(opts, dev(x.astype(dtype)), dev(y.astype(dtype)), eps, dev(a.astype(dtype)),
+                                    dev(b.astype(dtype)), f, g, api.alloc_workspace(opts, api.FSK_MODE_LOG, d))
+        torch.cuda.synchronize()
+        fo, go, _, _ = orc.sinkhorn_log_points(x, y, eps, a, b, iters)
+        what = (seed, case, n, d, np.dtype(dtype).name, iters)
+        assert np.max(np.abs(f.cpu().numpy() - fo)) / eps <= tol, what
+        assert np.max(np.abs(g.cpu().numpy() - go)) / eps <= tol, what
