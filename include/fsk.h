@@ -80,17 +80,18 @@ typedef enum {
                             all the iterations between two polls in ONE launch, exchanging the
                             workgroups' partial column sums across a grid-wide barrier.
                             opts->c is accepted and has no effect on the arithmetic (the row
-                            blocks are the workgroups').  FSK_EUNSUPPORTED for a larger K or
-                            geometric damping.  If the barrier sees no progress for about a
-                            second the call writes NaN into u and v instead of hanging.      */
+                            blocks are the workgroups').  FSK_EUNSUPPORTED for a larger K.
+                            If the barrier sees no progress for about a second the call
+                            writes NaN into u and v instead of hanging.                      */
 } fsk_flow;
 
 typedef enum {
   FSK_DAMP_NONE = 0,
   FSK_DAMP_ARITHMETIC = 1, /* u <- (1-eta) u + eta a./(K v)            (Sec. 3.3)             */
   FSK_DAMP_GEOMETRIC = 2   /* u <- u^(1-eta) .* (a./(K v))^eta         (Remark in Sec. 3.3);
-                              FSK_FLOW_FUSED carries it in fp32 (as exp2 of the weighted log2's);
-                              in fp64 the call runs the two-pass kernels instead               */
+                              FSK_FLOW_FUSED carries it in fp32 and FSK_FLOW_RESIDENT in both
+                              precisions as exp2 of the weighted log2's; an fp64 FUSED call
+                              runs the two-pass kernels instead                                */
 } fsk_damping;
 
 typedef struct {

@@ -251,14 +251,13 @@ static std::atomic<unsigned> g_resident_spin_limit{4000000u};
 #define kResidentSpinLimit (g_resident_spin_limit.load(std::memory_order_relaxed))
 
 static int check_resident(const fsk_opts* o) {
-  if (o->damping == FSK_DAMP_GEOMETRIC)
-    return set_error(FSK_EUNSUPPORTED, "the register-resident flow carries the arithmetic relaxation only");
   if (!resident_plan(o->dtype, o->n).ok)
     return set_error(FSK_EUNSUPPORTED, "n = %d: K does not fit the registers of the resident grid", o->n);
   return FSK_OK;
 }
+// The resident kernel's encoding: 1 = plain, (0, 1) arithmetic, negative = geometric with -eta.
 static double resident_eta(const fsk_opts* o) {
-  return o->damping == FSK_DAMP_ARITHMETIC ? o->eta : 1.0;
+  return o->damping == FSK_DAMP_ARITHMETIC ? o->eta : o->damping == FSK_DAMP_GEOMETRIC ? -o->eta : 1.0;
 }
 
 // Algorithm 1 on validated arguments: opts->max_iters iterations, or until a poll finds the

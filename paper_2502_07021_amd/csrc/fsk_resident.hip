@@ -54,6 +54,17 @@ __device__ __forceinline__ Pack<T> load_agent(const T* p) {
   return v;
 }
 
+__device__ __forceinline__ float res_log2(float x) { return log2f(x); }
+__device__ __forceinline__ double res_log2(double x) { return log2(x); }
+__device__ __forceinline__ float res_exp2(float x) { return exp2f(x); }
+__device__ __forceinline__ double res_exp2(double x) { return exp2(x); }
+// (1 - et) old + et fresh, or old^(1 - et) fresh^et
+template <typename T>
+__device__ __forceinline__ T relax(T old, T fresh, T et, bool geom) {
+  return geom ? res_exp2(fma(T(1) - et, res_log2(old), et * res_log2(fresh)))
+              : (T(1) - et) * old + et * fresh;
+}
+
 // RPT: rows per thread (register-resident packs per thread).
 template <typename T, int RPT>
 __global__ __launch_bounds__(kResThreads) void resident_kernel(
@@ -73,7 +84,11 @@ __global__ __launch_bounds__(kResThreads) void resident_kernel(
   const int row_lo = w * rows_per_wg;
   const int row_hi = row_lo + rows_per_wg < n ? row_lo + rows_per_wg : n;
   const int my_rows = row_hi > row_lo ? row_hi - row_lo : 0;
-  const bool damped = eta < T(1);
+  // |eta| < 1 selects a relaxation (Sec. 3.3): eta > 0 the arithmetic one, eta < 0 the geometric
+  // one with parameter -eta, x <- x^(1+eta) (new)^(-eta), as exp2 of the weighted log2's.
+  const bool geom = eta < T(0);
+  const T et = geom ? -eta : eta;
+  const bool damped = et < T(1);
 
   __shared__ T red[kMaxRows][NW];  // [row of the workgroup][wave of its subgroup]
   __shared__ __align__(16) T colred[kResThreads * W];
@@ -133,7 +148,7 @@ __global__ __launch_bounds__(kResThreads) void resident_kernel(
         T q = T(0);
         for (int x = 0; x < wps; ++x) q += red[tid][x];
         un = a_s[tid] / q;
-        if (damped) un = (T(1) - eta) * u_s[it & 1][tid] + eta * un;
+        if (damped) un = relax(u_s[it & 1][tid], un, et, geom);
       }
       u_s[(it + 1) & 1][tid] = un;
     }
@@ -204,7 +219,7 @@ __global__ __launch_bounds__(kResThreads) void resident_kernel(
         T vn = T(0);
         if (col + e < n) {
           vn = b_p.e[e] / r.e[e];
-          if (damped) vn = (T(1) - eta) * v_p.e[e] + eta * vn;
+          if (damped) vn = relax(v_p.e[e], vn, et, geom);
         }
         v_p.e[e] = vn;
       }

@@ -39,8 +39,6 @@ def test_random_dense_problems(orc, seed):
         c = int(rng.choice([k for k in range(1, min(n, 64) + 1) if n % k == 0]))
         damping = int(rng.choice([api.FSK_DAMP_NONE, api.FSK_DAMP_ARITHMETIC, api.FSK_DAMP_GEOMETRIC],
                                  p=[0.6, 0.25, 0.15]))
-        if flow == api.FSK_FLOW_RESIDENT and damping == api.FSK_DAMP_GEOMETRIC:
-            damping = api.FSK_DAMP_ARITHMETIC
         eta = float(rng.uniform(0.3, 1.0))
         iters = int(rng.integers(1, 6))
         d = int(rng.integers(1, 5))

@@ -72,11 +72,16 @@ def test_resident_refuses_what_it_cannot_hold():
         with pytest.raises(api.FskError) as e:
             api.fsk_sinkhorn_dense(opts, K, x, x, x.clone(), x.clone(), ws)
         assert e.value.status == api.FSK_EUNSUPPORTED
-    opts = api.make_opts(256, torch.float32, max_iters=1, flow=RES, damping=api.FSK_DAMP_GEOMETRIC, eta=0.5)
-    K = torch.ones(256, 256, device="cuda"); x = torch.ones(256, device="cuda")
-    with pytest.raises(api.FskError) as e:
-        api.fsk_sinkhorn_dense(opts, K, x, x, x.clone(), x.clone(), api.alloc_workspace(opts))
-    assert e.value.status == api.FSK_EUNSUPPORTED
+
+
+@pytest.mark.parametrize("n,dtype,tol", [(256, np.float32, 1e-4), (1000, np.float32, 1e-4),
+                                         (300, np.float64, 1e-10), (512, np.float64, 1e-10)])
+def test_resident_geometric_relaxation(orc, n, dtype, tol):
+    w, K = _kernel(orc, 1, n, dtype)
+    a = w.a.astype(dtype); b = w.b.astype(dtype)
+    uo, vo = orc.sinkhorn_dense_damped(K, a, b, 40, 0.6, True)
+    u, v, _, _ = run_dense(K, a, b, 40, flow=RES, damping=api.FSK_DAMP_GEOMETRIC, eta=0.6)
+    assert relerr(u, uo) <= tol and relerr(v, vo) <= tol
 
 
 def test_resident_barrier_gives_up_instead_of_hanging(orc):
