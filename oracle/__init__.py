@@ -43,7 +43,7 @@ def _load():
         L.orc_lse.restype = ctypes.c_double
         L.orc_dp_normal.restype = ctypes.c_double
         L.orc_rdp_epsilon.restype = ctypes.c_double
-        for name in ("orc_num_threads", "orc_sinkhorn_dense", "orc_sinkhorn_dense_tol",
+        for name in ("orc_num_threads", "orc_sinkhorn_dense", "orc_sinkhorn_dense_tol", "orc_sinkhorn_batched_tol",
                      "orc_sinkhorn_blocked", "orc_sinkhorn_dense_damped", "orc_sinkhorn_batched",
                      "orc_sinkhorn_async_emulated", "orc_sinkhorn_grid", "orc_sinkhorn_batched_dp",
                      "orc_sinkhorn_log_points", "orc_sinkhorn_log_cost"):
@@ -251,6 +251,20 @@ def sinkhorn_batched(K, A, B, iters: int, U0=None, V0=None):
                                       _INT(iters))
     assert rc == 0
     return U, V
+
+
+def sinkhorn_batched_tol(K, A, B, max_iters: int, tol: float, check_every: int = 1, U0=None, V0=None):
+    """Multitarget form until every column's row-marginal L1 error is below tol at a poll.
+    Returns (U, V, iterations done, max over columns of the error at the last poll)."""
+    kp, kf, n, ld = _square(K)
+    A, B = _f64(A), _f64(B)
+    m = A.shape[1]
+    U, V = _init(K.shape[0], U0, m), _init(K.shape[0], V0, m)
+    err = ctypes.c_double(float("inf"))
+    done = _load().orc_sinkhorn_batched_tol(kp, kf, n, ld, _INT(m), _ptr(A), _ptr(B), _ptr(U), _ptr(V),
+                                            _INT(max_iters), _DBL(tol), _INT(check_every), ctypes.byref(err))
+    assert done >= 0
+    return U, V, int(done), float(err.value)
 
 
 # ---------------------------------------------------------- privacy layer ---

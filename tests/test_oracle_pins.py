@@ -305,6 +305,35 @@ def test_batched_column_equals_single_run(orc):
     assert np.allclose(U1, Uref, rtol=1e-13) and np.allclose(V1, B / (K.T @ Uref), rtol=1e-13)
 
 
+def test_batched_tolerance_mode(orc):
+    """The stacked run stops at the first poll where EVERY target is below the tolerance: its
+    error is the largest of the per-target errors (NumPy, from the plan), its iterates are those
+    of the fixed-count run, and with a poll every iteration it stops where the slowest
+    single-target run stops (the L1 marginal error of Sinkhorn never increases)."""
+    x, y, a, b, C, K = problem(30, 23, eps=0.3)
+    rng = np.random.default_rng(4)
+    m = 6
+    A = rng.exponential(size=(30, m)); A /= A.sum(0)
+    B = rng.exponential(size=(30, m)); B /= B.sum(0)
+    U, V, done, err = orc.sinkhorn_batched_tol(K, A, B, 500, 1e-8, check_every=1)
+    assert 1 < done < 500 and err < 1e-8
+    errs = [np.abs((U[:, k, None] * K * V[None, :, k]).sum(1) - A[:, k]).sum() for k in range(m)]
+    assert err == pytest.approx(max(errs), rel=1e-5)                     # cancellation-limited
+    Uf, Vf = orc.sinkhorn_batched(K, A, B, done)
+    assert np.array_equal(U, Uf) and np.array_equal(V, Vf)
+    singles = [orc.sinkhorn_dense_tol(K, A[:, k], B[:, k], 500, 1e-8, check_every=1)[2] for k in range(m)]
+    assert done == max(singles) and min(singles) < done                   # the targets differ
+    # polling interval and cap
+    _, _, done5, err5 = orc.sinkhorn_batched_tol(K, A, B, 500, 1e-8, check_every=5)
+    assert done5 % 5 == 0 and done <= done5 < done + 5 and err5 < 1e-8
+    _, _, done_cap, err_cap = orc.sinkhorn_batched_tol(K, A, B, 3, 1e-30, check_every=2)
+    assert done_cap == 3 and err_cap > 1e-30
+    # one target: the dense tolerance run
+    U1, V1, d1, e1 = orc.sinkhorn_batched_tol(K, A[:, :1], B[:, :1], 500, 1e-8, check_every=3)
+    us, vs, ds, es = orc.sinkhorn_dense_tol(K, A[:, 0], B[:, 0], 500, 1e-8, check_every=3)
+    assert d1 == ds and e1 == pytest.approx(es, rel=1e-9) and np.allclose(U1[:, 0], us, rtol=1e-13)
+
+
 def test_tolerance_mode_polling(orc):
     x, y, a, b, C, K = problem(32, 17, eps=0.3)
     u, v, done, err = orc.sinkhorn_dense_tol(K, a, b, 500, 1e-9, check_every=7)
