@@ -272,12 +272,26 @@ int fsk_sinkhorn_log_points(const fsk_opts* opts, const void* x, const void* y, 
  * FSK_EWORKSPACE otherwise).  Any m >= 1: the columns go through
  * the kernels in groups of up to 64, one pass over K per group and product, so the time grows
  * with ceil(m / 64).  Workspace: fsk_workspace_bytes(opts, FSK_MODE_BATCHED, 0) holds the
- * partial products of one group and a transposed copy of K; with at least the partial products
+ * partial products of all groups and a transposed copy of K; with at least the partial products
  * (the size the error message of a too-small workspace states) the call still runs, with a
  * slower kernel for K V. */
 int fsk_sinkhorn_batched(const fsk_opts* opts, const void* K, int64_t ldK, const void* A,
                          const void* B, void* U, void* V, void* workspace, size_t ws_bytes,
                          void* stream);
+
+/* The same with the stop rule of fsk_sinkhorn_dense applied to all targets at once (the
+ * multitarget experiment of Sec. 5.3.2 iterates until every target meets the threshold):
+ * opts->tol > 0 stops at the first poll (every opts->check_every iterations, and after
+ * opts->max_iters) at which max over columns k of ||P_k 1 - a_k||_1 < tol, P_k = diag(u_k) K
+ * diag(v_k), with the scalings as they stand after a V-update; opts->tol <= 0 runs max_iters
+ * iterations and leaves *err NaN.  iters_done (host, required) and err (host, may be NULL)
+ * receive the iteration count and that maximum; U, V hold the state they describe.  The call
+ * synchronises at every poll.  Workspace: fsk_workspace_bytes(opts, FSK_MODE_BATCHED, 0) with
+ * the same opts (in tolerance mode it also holds a copy of U).  FSK_ENONFINITE as in the dense
+ * call. */
+int fsk_sinkhorn_batched_tol(const fsk_opts* opts, const void* K, int64_t ldK, const void* A,
+                             const void* B, void* U, void* V, void* workspace, size_t ws_bytes,
+                             int32_t* iters_done, double* err, void* stream);
 
 /* ---- privacy layer (privacy appendix: "Gaussian noise on log-domain scalings", "RDP
  * accountant") ---------------------------------------------------------------------------

@@ -30,6 +30,7 @@ EXPORTS = (
     "fsk_version", "fsk_last_error", "fsk_workspace_bytes", "fsk_kernel_from_cost",
     "fsk_kernel_from_points", "fsk_sinkhorn_dense", "fsk_marginals", "fsk_block_rowpass",
     "fsk_block_colpartial", "fsk_block_fused", "fsk_sinkhorn_log_points", "fsk_sinkhorn_batched",
+    "fsk_sinkhorn_batched_tol",
     "fsk_dense_profile", "fsk_bench_copy", "fsk_bench_read", "fsk_async_workspace_bytes",
     "fsk_sinkhorn_async_emulated", "fsk_plan_objective", "fsk_kernel_from_cost_lambda",
     "fsk_radius_search", "fsk_grid_workspace_bytes", "fsk_sinkhorn_grid", "fsk_dp_release",
@@ -304,6 +305,16 @@ def fsk_sinkhorn_batched(opts, K, A, B, U, V, workspace, stream=None) -> int:
     wp, wn = _ws(workspace)
     return _check(lib().fsk_sinkhorn_batched(ctypes.byref(opts), _p(K), _ld(K), _vec(A), _vec(B),
                                              _vec(U), _vec(V), wp, wn, _stream(stream)))
+
+
+def fsk_sinkhorn_batched_tol(opts, K, A, B, U, V, workspace, stream=None):
+    """Returns (iters_done, err); err is NaN in fixed-iteration mode."""
+    wp, wn = _ws(workspace)
+    done, err = ctypes.c_int32(0), ctypes.c_double(float("nan"))
+    _check(lib().fsk_sinkhorn_batched_tol(ctypes.byref(opts), _p(K), _ld(K), _vec(A), _vec(B), _vec(U),
+                                          _vec(V), wp, wn, ctypes.byref(done), ctypes.byref(err),
+                                          _stream(stream)))
+    return int(done.value), float(err.value)
 
 
 def fsk_bench_copy(dst, src, stream=None) -> int:

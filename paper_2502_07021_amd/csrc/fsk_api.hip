@@ -121,6 +121,21 @@ const char* fsk_last_error(void) { return g_err; }
 
 static size_t plan_ws_bytes(const fsk_opts* opts);
 
+// Multitarget workspace: [partial products | K^T] and, in tolerance mode, a copy of U and the
+// error kernels' scratch behind them.
+static size_t batched_base_bytes(const fsk_opts* o) {
+  return align_up(o->dtype == FSK_F64 ? batched_f64_workspace_bytes(o->n, o->m)
+                                      : batched_workspace_bytes(o->n, o->m), 256);
+}
+static size_t batched_save_bytes(const fsk_opts* o) {
+  return align_up((size_t)o->n * (size_t)o->m * elem_size(o->dtype), 256);
+}
+static size_t batched_total_bytes(const fsk_opts* o) {
+  if (!(o->tol > 0.0)) return batched_base_bytes(o);
+  return batched_base_bytes(o) + batched_save_bytes(o) +
+         align_up(batched_poll_scratch_doubles(o->n, o->m) * 8, 256);
+}
+
 size_t fsk_workspace_bytes(const fsk_opts* opts, int mode, int d) {
   if (check_common(opts) != FSK_OK) return 0;
   switch (mode) {
@@ -128,9 +143,7 @@ size_t fsk_workspace_bytes(const fsk_opts* opts, int mode, int d) {
     case FSK_MODE_LOG: return log_workspace_bytes(opts->n, d);
     case FSK_MODE_PLAN: return plan_ws_bytes(opts);
     case FSK_MODE_RADIUS: return align_up(dense_ws(opts).total, 256) + plan_ws_bytes(opts);
-    case FSK_MODE_BATCHED:
-      return opts->dtype == FSK_F64 ? batched_f64_workspace_bytes(opts->n, opts->m)
-                                    : batched_workspace_bytes(opts->n, opts->m);
+    case FSK_MODE_BATCHED: return batched_total_bytes(opts);
     case FSK_MODE_SETUP: return align_up(max_sqdist_scratch_doubles(opts->n) * 8, 256) + 256;
     default: return 0;
   }
@@ -803,6 +816,36 @@ int fsk_sinkhorn_batched(const fsk_opts* opts, const void* K, int64_t ldK, const
   FSK_TRY(check_vec("V", V, false));
   if (workspace && !aligned16(workspace)) return set_error(FSK_EALIGN, "workspace is not 16-byte aligned");
   return run_sinkhorn_batched(opts, K, ldK, A, B, U, V, workspace, ws_bytes, nullptr, (hipStream_t)stream);
+}
+
+int fsk_sinkhorn_batched_tol(const fsk_opts* opts, const void* K, int64_t ldK, const void* A,
+                             const void* B, void* U, void* V, void* workspace, size_t ws_bytes,
+                             int32_t* iters_done, double* err, void* stream) {
+  clear_error();
+  FSK_TRY(check_common(opts));
+  if (opts->c != 1) return set_error(FSK_EUNSUPPORTED, "batched call takes c = 1");
+  if (!iters_done) return set_error(FSK_EINVAL, "iters_done is NULL");
+  FSK_TRY(check_matrix("K", K, ldK, opts->n, opts->dtype));
+  FSK_TRY(check_vec("A", A, false));
+  FSK_TRY(check_vec("B", B, false));
+  FSK_TRY(check_vec("U", U, false));
+  FSK_TRY(check_vec("V", V, false));
+  const size_t need = batched_total_bytes(opts);
+  if (!workspace || ws_bytes < need)
+    return set_error(FSK_EWORKSPACE, "batched call in tolerance mode needs %zu workspace bytes, got %zu",
+                     need, ws_bytes);
+  if (!aligned16(workspace)) return set_error(FSK_EALIGN, "workspace is not 16-byte aligned");
+  const size_t base = batched_base_bytes(opts);
+  BatchedPoll poll{};
+  poll.tol = opts->tol;
+  poll.check_every = opts->check_every;
+  poll.save = (char*)workspace + base;
+  poll.scratch = (double*)((char*)workspace + base + batched_save_bytes(opts));
+  poll.iters_done = iters_done;
+  poll.err = err;
+  if (err) *err = NAN;
+  return run_sinkhorn_batched(opts, K, ldK, A, B, U, V, workspace, base, nullptr, (hipStream_t)stream,
+                              &poll);
 }
 
 // ------------------------------------------------------------- privacy layer

@@ -572,9 +572,9 @@ __global__ __launch_bounds__(256) void batched_rowreduce_kernel(const float* __r
 
 int run_sinkhorn_batched(const fsk_opts* o, const void* K, int64_t ldK, const void* A, const void* B,
                          void* U, void* V, void* workspace, size_t ws_bytes, const fsk_dp* dp,
-                         hipStream_t st) {
+                         hipStream_t st, const BatchedPoll* poll) {
   if (o->dtype == FSK_F64)
-    return run_sinkhorn_batched_f64(o, K, ldK, A, B, U, V, workspace, ws_bytes, dp, st);
+    return run_sinkhorn_batched_f64(o, K, ldK, A, B, U, V, workspace, ws_bytes, dp, st, poll);
   const int n = o->n, m = o->m;
   const int S = batched_splits(n);
   const size_t part_bytes = batched_partial_bytes(n, m);
@@ -620,31 +620,102 @@ int run_sinkhorn_batched(const fsk_opts* o, const void* K, int64_t ldK, const vo
     if (SW > 1) FSK_TRY(reduce_all(marg, dst));
     return FSK_OK;
   };
-  for (int it = 0; it < o->max_iters; ++it) {
-    if (use_kt) {  // Q = K V as the transposed product of K^T
-      FSK_TRY(wide(Kt, ldt, Vf, Af, Uf, "batched_prod_wide_kernel (K V)"));
-    } else {       // direct row walk, one column group per launch
-      for (int c0 = 0; c0 < m; c0 += kBtCols) {
-        const int cols = m - c0 < kBtCols ? m - c0 : kBtCols;
-        hipLaunchKernelGGL(batched_rowprod_kernel, grid, block, 0, st, Kf, ldK, n, cols, (int64_t)m,
-                           (const float*)Vf + c0, Af + c0, S == 1 ? Uf + c0 : part, S == 1 ? 1 : 0);
-        FSK_LAUNCH_CHECK("batched_rowprod_kernel (K V)");
-        if (S > 1) {
-          const int64_t total = (int64_t)n * cols;
-          hipLaunchKernelGGL(batched_rowreduce_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0,
-                             st, (const float*)part, S, n, cols, (int64_t)m, Af + c0, Uf + c0);
-          FSK_LAUNCH_CHECK("batched_rowreduce_kernel");
-        }
+  auto u_update = [&](void* dst_v) -> int {
+    float* dst = (float*)dst_v;
+    if (use_kt) return wide(Kt, ldt, Vf, Af, dst, "batched_prod_wide_kernel (K V)");  // Q = K V on K^T
+    for (int c0 = 0; c0 < m; c0 += kBtCols) {  // direct row walk, one column group per launch
+      const int cols = m - c0 < kBtCols ? m - c0 : kBtCols;
+      hipLaunchKernelGGL(batched_rowprod_kernel, grid, block, 0, st, Kf, ldK, n, cols, (int64_t)m,
+                         (const float*)Vf + c0, Af + c0, S == 1 ? dst + c0 : part, S == 1 ? 1 : 0);
+      FSK_LAUNCH_CHECK("batched_rowprod_kernel (K V)");
+      if (S > 1) {
+        const int64_t total = (int64_t)n * cols;
+        hipLaunchKernelGGL(batched_rowreduce_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0,
+                           st, (const float*)part, S, n, cols, (int64_t)m, Af + c0, dst + c0);
+        FSK_LAUNCH_CHECK("batched_rowreduce_kernel");
       }
     }
-    if (dp)  // the release clips every row across ALL m targets
-      FSK_TRY(launch_dp_release(FSK_F32, Uf, n, m, dp->clip_u, dp->sigma_u, dp->seed,
-                                dp->release0 + 2 * (uint64_t)it, st));
-    FSK_TRY(wide(Kf, ldK, Uf, Bf, Vf, "batched_prod_wide_kernel (K^T U)"));  // V = B ./ (K^T U)
-    if (dp)
-      FSK_TRY(launch_dp_release(FSK_F32, Vf, n, m, dp->clip_v, dp->sigma_v, dp->seed,
-                                dp->release0 + 2 * (uint64_t)it + 1, st));
+    return FSK_OK;
+  };
+  auto v_update = [&]() -> int {  // V = B ./ (K^T U)
+    return wide(Kf, ldK, Uf, Bf, Vf, "batched_prod_wide_kernel (K^T U)");
+  };
+  auto release = [&](int it, bool is_v) -> int {  // the release clips every row across ALL m targets
+    if (!dp) return FSK_OK;
+    return is_v ? launch_dp_release(FSK_F32, Vf, n, m, dp->clip_v, dp->sigma_v, dp->seed,
+                                    dp->release0 + 2 * (uint64_t)it + 1, st)
+                : launch_dp_release(FSK_F32, Uf, n, m, dp->clip_u, dp->sigma_u, dp->seed,
+                                    dp->release0 + 2 * (uint64_t)it, st);
+  };
+  return batched_iterate(o, Af, Uf, poll, st, u_update, v_update, release);
+}
+
+// ------------------------------------------------------------------ error of a polled state
+// partial[strip][k] = sum over the 256 rows i of the strip of A_ik |Uold_ik / Unew_ik - 1| (fp64,
+// rows in increasing order per thread, then the four row lanes in order).
+template <typename T>
+__global__ __launch_bounds__(256) void batched_poll_partial_kernel(const T* __restrict__ A,
+                                                                   const T* __restrict__ Uold,
+                                                                   const T* __restrict__ Unew, int n,
+                                                                   int m, double* __restrict__ partial) {
+  __shared__ double sm[4][64];
+  const int cl = threadIdx.x & 63, rl = threadIdx.x >> 6;
+  const int k = blockIdx.x * 64 + cl, strip = blockIdx.y;
+  const int i1 = (strip + 1) * 256 < n ? (strip + 1) * 256 : n;
+  double s = 0.0;
+  if (k < m)
+    for (int i = strip * 256 + rl; i < i1; i += 4) {
+      const int64_t idx = (int64_t)i * m + k;
+      s += (double)A[idx] * fabs((double)Uold[idx] / (double)Unew[idx] - 1.0);
+    }
+  sm[rl][cl] = s;
+  __syncthreads();
+  if (rl == 0 && k < m) partial[(int64_t)strip * m + k] = ((sm[0][cl] + sm[1][cl]) + sm[2][cl]) + sm[3][cl];
+}
+
+// out[0] = max over columns of the strips' sum (strips in order); NaN wins the maximum.
+__global__ __launch_bounds__(256) void batched_poll_final_kernel(const double* __restrict__ partial,
+                                                                 int strips, int m,
+                                                                 double* __restrict__ out) {
+  __shared__ double sm[256];
+  double best = 0.0;
+  bool bad = false;
+  for (int k = threadIdx.x; k < m; k += 256) {
+    double s = 0.0;
+    for (int t = 0; t < strips; ++t) s += partial[(int64_t)t * m + k];
+    if (!(s == s)) bad = true;
+    best = s > best ? s : best;
   }
+  sm[threadIdx.x] = bad ? NAN : best;
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    double r = 0.0;
+    bool any_bad = false;
+    for (int t = 0; t < 256; ++t) {
+      if (!(sm[t] == sm[t])) any_bad = true;
+      else r = sm[t] > r ? sm[t] : r;
+    }
+    out[0] = any_bad ? NAN : r;
+  }
+}
+
+size_t batched_poll_scratch_doubles(int n, int m) { return 8 + (size_t)((n + 255) / 256) * (size_t)m; }
+
+int launch_batched_poll_error(int dtype, const void* A, const void* Uold, const void* Unew, int n,
+                              int m, double* scratch, hipStream_t st) {
+  const int strips = (n + 255) / 256;
+  dim3 grid((m + 63) / 64, strips);
+  double* partial = scratch + 8;
+  if (dtype == FSK_F64)
+    hipLaunchKernelGGL((batched_poll_partial_kernel<double>), grid, dim3(256), 0, st, (const double*)A,
+                       (const double*)Uold, (const double*)Unew, n, m, partial);
+  else
+    hipLaunchKernelGGL((batched_poll_partial_kernel<float>), grid, dim3(256), 0, st, (const float*)A,
+                       (const float*)Uold, (const float*)Unew, n, m, partial);
+  FSK_LAUNCH_CHECK("batched_poll_partial_kernel");
+  hipLaunchKernelGGL(batched_poll_final_kernel, dim3(1), dim3(256), 0, st, (const double*)partial, strips, m,
+                     scratch);
+  FSK_LAUNCH_CHECK("batched_poll_final_kernel");
   return FSK_OK;
 }
 

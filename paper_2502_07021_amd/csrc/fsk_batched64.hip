@@ -343,7 +343,7 @@ size_t batched_f64_workspace_bytes(int n, int m) {
 
 int run_sinkhorn_batched_f64(const fsk_opts* o, const void* K, int64_t ldK, const void* A, const void* B,
                              void* U, void* V, void* workspace, size_t ws_bytes, const fsk_dp* dp,
-                             hipStream_t st) {
+                             hipStream_t st, const BatchedPoll* poll) {
   const int n = o->n, m = o->m;
   const size_t need = batched_f64_workspace_bytes(n, m);
   if (!workspace || ws_bytes < need)
@@ -375,17 +375,18 @@ int run_sinkhorn_batched_f64(const fsk_opts* o, const void* K, int64_t ldK, cons
     }
     return FSK_OK;
   };
-  for (int it = 0; it < o->max_iters; ++it) {
-    FSK_TRY(product(Kt, ldt, Vd, Ad, Ud));  // U = A ./ (K V) as the transposed product of K^T
-    if (dp)
-      FSK_TRY(launch_dp_release(FSK_F64, Ud, n, m, dp->clip_u, dp->sigma_u, dp->seed,
-                                dp->release0 + 2 * (uint64_t)it, st));
-    FSK_TRY(product(Kd, ldK, Ud, Bd, Vd));  // V = B ./ (K^T U)
-    if (dp)
-      FSK_TRY(launch_dp_release(FSK_F64, Vd, n, m, dp->clip_v, dp->sigma_v, dp->seed,
-                                dp->release0 + 2 * (uint64_t)it + 1, st));
-  }
-  return FSK_OK;
+  auto u_update = [&](void* dst) -> int {  // U = A ./ (K V) as the transposed product of K^T
+    return product(Kt, ldt, Vd, Ad, (double*)dst);
+  };
+  auto v_update = [&]() -> int { return product(Kd, ldK, Ud, Bd, Vd); };  // V = B ./ (K^T U)
+  auto release = [&](int it, bool is_v) -> int {
+    if (!dp) return FSK_OK;
+    return is_v ? launch_dp_release(FSK_F64, Vd, n, m, dp->clip_v, dp->sigma_v, dp->seed,
+                                    dp->release0 + 2 * (uint64_t)it + 1, st)
+                : launch_dp_release(FSK_F64, Ud, n, m, dp->clip_u, dp->sigma_u, dp->seed,
+                                    dp->release0 + 2 * (uint64_t)it, st);
+  };
+  return batched_iterate(o, Ad, Ud, poll, st, u_update, v_update, release);
 }
 
 }  // namespace fsk

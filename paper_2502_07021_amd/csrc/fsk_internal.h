@@ -1,6 +1,7 @@
 // Host-side declarations shared by the translation units of libfsk.
 #pragma once
 #include <hip/hip_runtime.h>
+#include <math.h>
 #include <stddef.h>
 #include <stdint.h>
 
@@ -141,16 +142,87 @@ int launch_resident(int dtype, const void* K, int64_t ld, int n, int iters, cons
 
 // ------------------------------------------------------------------ multitarget path
 size_t batched_workspace_bytes(int n, int m);
+// Tolerance mode of the multitarget iteration (may be null: fixed iteration count).  The error of
+// the state after `it` iterations falls out of the U-update of iteration it + 1: with
+// Q = K V of that state, |U_ik Q_ik - A_ik| = A_ik |U_ik / U_ik^new - 1|, so a poll costs a copy
+// of U, one elementwise pass and a synchronisation; a state that met the tolerance is restored
+// from the copy.  Only the state after max_iters needs one extra product.
+struct BatchedPoll {
+  double tol;
+  int check_every;
+  void* save;          // n x m elements of the call's dtype
+  double* scratch;     // batched_poll_scratch_doubles(n, m) doubles; [0] receives the error
+  int32_t* iters_done; // host
+  double* err;         // host, may be null
+};
+size_t batched_poll_scratch_doubles(int n, int m);
+// scratch[0] = max over columns k of sum_i A_ik |Uold_ik / Unew_ik - 1| (fp64, fixed order).
+int launch_batched_poll_error(int dtype, const void* A, const void* Uold, const void* Unew, int n,
+                              int m, double* scratch, hipStream_t st);
 // `dp` (may be null): release U after every U-update and V after every V-update.
 int run_sinkhorn_batched(const fsk_opts* o, const void* K, int64_t ldK, const void* A, const void* B,
                          void* U, void* V, void* workspace, size_t ws_bytes, const fsk_dp* dp,
-                         hipStream_t st);
+                         hipStream_t st, const BatchedPoll* poll = nullptr);
 
 // fp64 form (MFMA f64 16x16x4): needs the full workspace (partial products + K^T).
 size_t batched_f64_workspace_bytes(int n, int m);
 int run_sinkhorn_batched_f64(const fsk_opts* o, const void* K, int64_t ldK, const void* A, const void* B,
                              void* U, void* V, void* workspace, size_t ws_bytes, const fsk_dp* dp,
-                             hipStream_t st);
+                             hipStream_t st, const BatchedPoll* poll = nullptr);
+// The loop both precisions share: `u_update(dst)` / `v_update()` enqueue one half-step (the
+// U-update into dst, normally U itself), `release(it, is_v)` the privacy layer's step (may do
+// nothing).  `poll` null or with tol <= 0: exactly max_iters iterations, nothing synchronises.
+template <class UUpdate, class VUpdate, class Release>
+inline int batched_iterate(const fsk_opts* o, const void* A, void* U, const BatchedPoll* poll,
+                           hipStream_t st, UUpdate u_update, VUpdate v_update, Release release) {
+  const int n = o->n, m = o->m;
+  const size_t bytes = (size_t)n * (size_t)m * elem_size(o->dtype);
+  const bool check = poll && poll->tol > 0.0;
+  int done = 0;
+  double e = NAN;
+  bool converged = false;
+  auto read_error = [&](const void* u_old, const void* u_new) -> int {
+    FSK_TRY(launch_batched_poll_error(o->dtype, A, u_old, u_new, n, m, poll->scratch, st));
+    FSK_HIP(hipMemcpyAsync(&e, poll->scratch, sizeof(double), hipMemcpyDeviceToHost, st));
+    FSK_HIP(hipStreamSynchronize(st));
+    return FSK_OK;
+  };
+  auto nonfinite = [&](int at) {
+    if (poll->iters_done) *poll->iters_done = at;
+    if (poll->err) *poll->err = e;
+    return set_error(FSK_ENONFINITE, "marginal error is not finite after %d iterations", at);
+  };
+  for (int it = 0; it < o->max_iters; ++it) {
+    const bool p = check && it > 0 && it % poll->check_every == 0;
+    if (p) FSK_HIP(hipMemcpyAsync(poll->save, U, bytes, hipMemcpyDeviceToDevice, st));
+    FSK_TRY(u_update(U));
+    if (p) {  // the U-update just formed K V of the state after `it` iterations
+      FSK_TRY(read_error(poll->save, U));
+      if (!(e == e) || e > 1.7e308) return nonfinite(it);
+      if (e < poll->tol) {
+        FSK_HIP(hipMemcpyAsync(U, poll->save, bytes, hipMemcpyDeviceToDevice, st));
+        FSK_HIP(hipStreamSynchronize(st));
+        done = it;
+        converged = true;
+        break;
+      }
+    }
+    FSK_TRY(release(it, false));
+    FSK_TRY(v_update());
+    FSK_TRY(release(it, true));
+    done = it + 1;
+  }
+  if (check && !converged && done > 0) {  // the state after the last iteration is always polled
+    FSK_TRY(u_update(poll->save));         // its next U, only to read the error off it
+    FSK_TRY(read_error(U, poll->save));
+    if (!(e == e) || e > 1.7e308) return nonfinite(done);
+  }
+  if (poll) {
+    if (poll->iters_done) *poll->iters_done = done;
+    if (poll->err) *poll->err = e;
+  }
+  return FSK_OK;
+}
 
 // ------------------------------------------------------------------ privacy layer
 // X (n x m, in place) <- exp(rowclip_S(log X) + sigma * normals of (seed, release)).

@@ -112,3 +112,65 @@ def test_batched_fp64_needs_the_full_workspace():
     with pytest.raises(api.FskError) as e:
         api.fsk_sinkhorn_batched(opts, K, X, X, X.clone(), X.clone(), ws[: ws.numel() // 2])
     assert e.value.status == api.FSK_EWORKSPACE
+
+
+def _run_tol(K, A, B, max_iters, tol, check_every, dtype):
+    n, m = A.shape
+    td = torch.float64 if dtype == np.float64 else torch.float32
+    opts = api.make_opts(n, td, m=m, max_iters=max_iters, tol=tol, check_every=check_every)
+    ws = api.alloc_workspace(opts, api.FSK_MODE_BATCHED)
+    pack = 16 // np.dtype(dtype).itemsize
+    full = torch.full((n, (n + pack - 1) // pack * pack), float("nan"), dtype=td, device="cuda")
+    full[:, :n] = dev(np.ascontiguousarray(K.astype(dtype)))
+    Kd = full[:, :n]
+    U = torch.ones(n, m, dtype=td, device="cuda"); V = torch.ones(n, m, dtype=td, device="cuda")
+    done, err = api.fsk_sinkhorn_batched_tol(opts, Kd, dev(np.ascontiguousarray(A.astype(dtype))),
+                                             dev(np.ascontiguousarray(B.astype(dtype))), U, V, ws)
+    return U.cpu().numpy(), V.cpu().numpy(), done, err
+
+
+@pytest.mark.parametrize("dtype,n,m,tol,check_every", [
+    (np.float64, 300, 70, 1e-9, 1), (np.float64, 515, 5, 1e-9, 7),
+    (np.float32, 1030, 64, 2e-5, 1), (np.float32, 400, 150, 2e-5, 4),
+])
+def test_batched_tolerance_mode(orc, dtype, n, m, tol, check_every):
+    """Stop rule over all targets at once (Sec. 5.3.2): the polled state, its iteration count
+    and its error against the oracle's; the handed-back state is the fixed-count run's."""
+    rng = np.random.default_rng(4000 + n + m)
+    x = rng.uniform(size=(n, 2)); y = rng.uniform(size=(n, 2))
+    K64, _ = orc.gibbs_from_points(x, y, 0.3, False)
+    K = np.ascontiguousarray(K64.astype(dtype))
+    A = rng.uniform(0.5, 1.5, (n, m)) ** 3; A = np.ascontiguousarray((A / A.sum(0)).astype(dtype))   # targets of
+    B = rng.uniform(0.5, 1.5, (n, m)) ** 3; B = np.ascontiguousarray((B / B.sum(0)).astype(dtype))   # unequal speed
+    Uo, Vo, done_o, err_o = orc.sinkhorn_batched_tol(K, A, B, 400, tol, check_every)
+    U, V, done, err = _run_tol(K, A, B, 400, tol, check_every, dtype)
+    assert done_o < 400 and err < tol
+    if dtype == np.float64:
+        assert done == done_o and err == pytest.approx(err_o, rel=1e-5)
+        assert relerr(U, Uo) <= 1e-10 and relerr(V, Vo) <= 1e-10
+    else:  # fp32 sums may cross the threshold one poll earlier or later
+        assert abs(done - done_o) <= check_every
+    assert done % check_every == 0
+    Uf, Vf = run_batched(K, A, B, done, dtype=dtype)         # same state as the fixed-count run
+    assert np.array_equal(U, Uf) and np.array_equal(V, Vf)
+    # the error it reports is the error of the state it hands back (oracle's evaluation, fp64)
+    errs = [orc.marginal_error(K, A[:, k], U[:, k], V[:, k])[0] for k in range(0, m, max(1, m // 8))]
+    assert max(errs) <= err * (1 + 1e-3) + (1e-6 if dtype == np.float32 else 1e-13)
+
+
+def test_batched_tolerance_cap_fixed_mode_and_workspace(orc):
+    K, A, B = problem(orc, 257, 33, 77)
+    U, V, done, err = _run_tol(K, A, B, 6, 1e-30, 4, np.float32)           # cap: last iteration polled
+    assert done == 6 and err > 1e-30
+    Uf, Vf = run_batched(K, A, B, 6)
+    assert np.array_equal(U, Uf) and np.array_equal(V, Vf)
+    U, V, done, err = _run_tol(K, A, B, 5, 0.0, 1, np.float32)             # tol <= 0: fixed count
+    assert done == 5 and np.isnan(err)
+    opts = api.make_opts(257, torch.float32, m=33, max_iters=5, tol=1e-6, check_every=1)
+    small = api.alloc_workspace(api.make_opts(257, torch.float32, m=33, max_iters=5), api.FSK_MODE_BATCHED)
+    Kd = torch.zeros(257, 260, device="cuda")[:, :257]; Kd.copy_(dev(K))
+    Ad = dev(A.astype(np.float32)); Bd = dev(B.astype(np.float32))
+    X = torch.ones(257, 33, device="cuda")
+    with pytest.raises(api.FskError) as e:                                  # no room for the copy of U
+        api.fsk_sinkhorn_batched_tol(opts, Kd, Ad, Bd, X.clone(), X.clone(), small)
+    assert e.value.status == api.FSK_EWORKSPACE
