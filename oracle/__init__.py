@@ -46,7 +46,7 @@ def _load():
         for name in ("orc_num_threads", "orc_sinkhorn_dense", "orc_sinkhorn_dense_tol", "orc_sinkhorn_batched_tol",
                      "orc_sinkhorn_blocked", "orc_sinkhorn_dense_damped", "orc_sinkhorn_batched",
                      "orc_sinkhorn_async_emulated", "orc_sinkhorn_grid", "orc_sinkhorn_batched_dp",
-                     "orc_sinkhorn_log_points", "orc_sinkhorn_log_cost"):
+                     "orc_sinkhorn_log_points", "orc_sinkhorn_log_cost", "orc_sinkhorn_log_points_damped"):
             getattr(L, name).restype = ctypes.c_int
         _lib = L
     return _lib
@@ -439,6 +439,20 @@ def sinkhorn_log_points(x, y, eps: float, a, b, max_iters: int, tol: float = 0.0
                                            _ptr(a), _ptr(b), _ptr(f), _ptr(g), _INT(max_iters),
                                            _DBL(tol), _INT(check_every), ctypes.byref(err))
     return f, g, int(done), float(err.value)
+
+
+def sinkhorn_log_points_damped(x, y, eps: float, a, b, iters: int, eta: float, geometric: bool,
+                               f0=None, g0=None):
+    """Log-domain iteration with the relaxed updates of Sec. 3.3; returns (f, g)."""
+    x, y, a, b = _f64(x), _f64(y), _f64(a), _f64(b)
+    n = x.shape[0]
+    f = np.zeros(n) if f0 is None else _f64(f0).copy()
+    g = np.zeros(n) if g0 is None else _f64(g0).copy()
+    rc = _load().orc_sinkhorn_log_points_damped(_ptr(x), _ptr(y), _I64(n), _INT(x.shape[1]), _DBL(eps),
+                                                _ptr(a), _ptr(b), _ptr(f), _ptr(g), _INT(iters), _DBL(eta),
+                                                _INT(1 if geometric else 0))
+    assert rc == 0
+    return f, g
 
 
 def sinkhorn_log_cost(C, eps: float, a, b, iters: int, f0=None, g0=None):

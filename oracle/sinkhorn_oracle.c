@@ -714,6 +714,35 @@ int orc_sinkhorn_log_points(const double* x, const double* y, int64_t n, int d, 
   return done;
 }
 
+/* The relaxed updates of Sec. 3.3 in the log domain, f = eps log u, g = eps log v.
+ * geometric != 0:  u <- u^(1-eta) (u_new)^eta  is  f <- (1-eta) f + eta f_new.
+ * geometric == 0:  u <- (1-eta) u + eta u_new  is  f <- eps log((1-eta) e^(f/eps) + eta e^(f_new/eps)),
+ *                  evaluated with the larger of the two exponents taken out.
+ * Exactly max_iters iterations. */
+int orc_sinkhorn_log_points_damped(const double* x, const double* y, int64_t n, int d, double eps,
+                                   const double* a, const double* b, double* f, double* g,
+                                   int max_iters, double eta, int geometric) {
+  double* t1 = (double*)malloc(sizeof(double) * (size_t)n);
+  if (!t1) return -1;
+  for (int t = 0; t < max_iters; ++t) {
+    for (int side = 0; side < 2; ++side) {
+      double* pot = side == 0 ? f : g;
+      if (side == 0) orc_log_update_points(x, a, y, g, n, d, eps, NULL, n, t1);
+      else orc_log_update_points(y, b, x, f, n, d, eps, NULL, n, t1);
+      for (int64_t i = 0; i < n; ++i) {
+        if (geometric) {
+          pot[i] = (1.0 - eta) * pot[i] + eta * t1[i];
+        } else {
+          double M = pot[i] > t1[i] ? pot[i] : t1[i];
+          pot[i] = M + eps * log((1.0 - eta) * exp((pot[i] - M) / eps) + eta * exp((t1[i] - M) / eps));
+        }
+      }
+    }
+  }
+  free(t1);
+  return 0;
+}
+
 /* Log-domain Sinkhorn on an explicit n x n cost matrix (small n; used to tie
  * the log form to the dense form on the same C). */
 int orc_sinkhorn_log_cost(const double* C, int64_t n, double eps, const double* a, const double* b,

@@ -334,6 +334,35 @@ def test_batched_tolerance_mode(orc):
     assert d1 == ds and e1 == pytest.approx(es, rel=1e-9) and np.allclose(U1[:, 0], us, rtol=1e-13)
 
 
+def test_log_domain_relaxed_updates(orc):
+    """Both relaxations of Sec. 3.3 in the log domain against the dense damped iteration
+    (f = eps log u, a fp64 identity at moderate eps), eta = 1 against the plain log iteration,
+    and one arithmetic step written out with SciPy's logsumexp."""
+    from scipy.special import logsumexp
+    rng = np.random.default_rng(8)
+    n, d, eps = 40, 3, 0.4
+    x = rng.uniform(size=(n, d)); y = rng.uniform(size=(n, d))
+    a = rng.uniform(0.5, 1.5, n); a /= a.sum()
+    b = rng.uniform(0.5, 1.5, n); b /= b.sum()
+    K = np.exp(-orc.cost_sqeuclid(x, y) / eps)
+    for geometric in (False, True):
+        u, v = orc.sinkhorn_dense_damped(K, a, b, 25, 0.6, geometric)
+        f, g = orc.sinkhorn_log_points_damped(x, y, eps, a, b, 25, 0.6, geometric)
+        assert np.allclose(f, eps * np.log(u), rtol=0, atol=1e-12) and np.allclose(g, eps * np.log(v), rtol=0, atol=1e-12)
+        f1, g1 = orc.sinkhorn_log_points_damped(x, y, eps, a, b, 9, 1.0, geometric)
+        f0, g0, _, _ = orc.sinkhorn_log_points(x, y, eps, a, b, 9)
+        assert np.allclose(f1, f0, rtol=0, atol=1e-14) and np.allclose(g1, g0, rtol=0, atol=1e-14)
+    # first arithmetic f-step from f = g = 0 by hand
+    C = orc.cost_sqeuclid(x, y)
+    f_new = eps * np.log(a) - eps * logsumexp(-C / eps, axis=1)
+    want = eps * logsumexp(np.stack([np.log(0.3) + np.zeros(n), np.log(0.7) + f_new / eps]), axis=0)
+    f, g = orc.sinkhorn_log_points_damped(x, y, eps, a, b, 1, 0.7, False)
+    assert np.allclose(f, want, rtol=0, atol=1e-13)
+    # small eps: the arithmetic form must not overflow where exp(f / eps) would
+    fs, gs = orc.sinkhorn_log_points_damped(x, y, 1e-4, a, b, 5, 0.5, False)
+    assert np.isfinite(fs).all() and np.isfinite(gs).all() and np.abs(fs / 1e-4).max() > 710   # exp would overflow
+
+
 def test_tolerance_mode_polling(orc):
     x, y, a, b, C, K = problem(32, 17, eps=0.3)
     u, v, done, err = orc.sinkhorn_dense_tol(K, a, b, 500, 1e-9, check_every=7)
