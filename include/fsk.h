@@ -107,7 +107,7 @@ typedef struct {
                           iteration is always polled                                           */
   int32_t dtype;       /* fsk_dtype of K, a, b, u, v (storage and arithmetic)                  */
   int32_t flow;        /* fsk_flow (dense calls only)                                          */
-  int32_t damping;     /* fsk_damping (dense calls only)                                       */
+  int32_t damping;     /* fsk_damping (dense and log-domain calls)                             */
   double eta;          /* relaxation parameter in (0, 1]; ignored when damping = NONE          */
 } fsk_opts;
 
@@ -257,6 +257,8 @@ int fsk_block_fused(const fsk_opts* opts, const void* K_slab, int64_t ldK, int32
  * never stored.  f, g: device, IN/OUT potentials (f = eps log u, g = eps log v; 0 for a cold
  * start).  Each iteration does
  *     f_i <- eps log a_i - eps LSE_j((g_j - C_ij)/eps),  g_j <- eps log b_j - eps LSE_i((f_i - C_ij)/eps).
+ * With opts->damping the relaxed updates of Sec. 3.3 apply to both potentials: geometric is
+ * f <- (1-eta) f + eta f_new, arithmetic is f <- eps log((1-eta) e^(f/eps) + eta e^(f_new/eps)).
  * FSK_F32: the cost term runs in fp64, exponentials and their sums in fp32.  FSK_F64: everything in
  * fp64.  1 <= d <= 4096 (FSK_EUNSUPPORTED outside); d <= 32 runs the kernel that keeps a row's
  * coordinates in registers, larger d a generic, slower one.  iters_done / err as in

@@ -420,7 +420,8 @@ __global__ __launch_bounds__(256) void log_finalize_kernel(const double* __restr
                                                            int slices, int n,
                                                            const double* __restrict__ norm2,
                                                            const double* __restrict__ lnw, double eps,
-                                                           double s, int mode, double* potd,
+                                                           double s, int mode, double eta, int geometric,
+                                                           double* potd,
                                                            T* __restrict__ pot_out,
                                                            double* __restrict__ beta_out,
                                                            double* __restrict__ errvec) {
@@ -442,9 +443,21 @@ __global__ __launch_bounds__(256) void log_finalize_kernel(const double* __restr
     errvec[i] = fabs(w * exp((potd[i] - pot_new) / eps) - w);
   }
   if (mode != 1) {
-    potd[i] = pot_new;
-    pot_out[i] = (T)pot_new;
-    beta_out[i] = s * pot_new - norm2[i];
+    // relaxed updates of Sec. 3.3 (eta < 1): geometric = linear in the potential; arithmetic =
+    // eps log((1 - eta) e^(old/eps) + eta e^(new/eps)) with the larger exponent taken out
+    double keep = pot_new;
+    if (eta < 1.0) {
+      const double old = potd[i];
+      if (geometric) {
+        keep = (1.0 - eta) * old + eta * pot_new;
+      } else {
+        const double M = old > pot_new ? old : pot_new;
+        keep = M + eps * log((1.0 - eta) * exp((old - M) / eps) + eta * exp((pot_new - M) / eps));
+      }
+    }
+    potd[i] = keep;
+    pot_out[i] = (T)keep;
+    beta_out[i] = s * keep - norm2[i];
   }
 }
 
@@ -535,6 +548,8 @@ static int run_log_typed(const fsk_opts* o, const void* x, const void* y, int d,
   char* ws = (char*)workspace;
   auto D = [&](size_t off) { return (double*)(ws + off); };
   const double s = 1.4426950408889634074 / eps;
+  const double eta = o->damping == FSK_DAMP_NONE ? 1.0 : o->eta;
+  const int geometric = o->damping == FSK_DAMP_GEOMETRIC ? 1 : 0;
   const T *xf = (const T*)x, *yf = (const T*)y, *af = (const T*)a, *bf = (const T*)b;
   T *ff = (T*)f, *gf = (T*)g;
   const int nb = (n + 255) / 256;
@@ -570,7 +585,8 @@ static int run_log_typed(const fsk_opts* o, const void* x, const void* y, int d,
                             D(f_side ? w.by : w.bx), D(w.pm), psum, st));
     hipLaunchKernelGGL((log_finalize_kernel<T, T>), dim3(nb), dim3(256), 0, st, D(w.pm), psum,
                        w.slices, n, D(f_side ? w.nx2 : w.ny2), D(f_side ? w.lna : w.lnb), eps, s,
-                       mode, D(f_side ? w.fd : w.gd), f_side ? ff : gf, D(f_side ? w.bx : w.by),
+                       mode, eta, geometric, D(f_side ? w.fd : w.gd), f_side ? ff : gf,
+                       D(f_side ? w.bx : w.by),
                        D(w.err));
     FSK_LAUNCH_CHECK("log_finalize_kernel");
     return FSK_OK;

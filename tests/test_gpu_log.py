@@ -15,10 +15,11 @@ from gpu_util import dev
 pytestmark = pytest.mark.gpu
 
 
-def run_log(x, y, a, b, eps, iters, tol=0.0, check_every=1, f0=None, g0=None, dtype=np.float32):
+def run_log(x, y, a, b, eps, iters, tol=0.0, check_every=1, f0=None, g0=None, dtype=np.float32,
+            damping=api.FSK_DAMP_NONE, eta=1.0):
     n, d = x.shape
     td = torch.float64 if dtype == np.float64 else torch.float32
-    opts = api.make_opts(n, td, max_iters=iters, tol=tol, check_every=check_every)
+    opts = api.make_opts(n, td, max_iters=iters, tol=tol, check_every=check_every, damping=damping, eta=eta)
     ws = api.alloc_workspace(opts, api.FSK_MODE_LOG, d)
     f = torch.zeros(n, dtype=td, device="cuda") if f0 is None else dev(f0.astype(dtype))
     g = torch.zeros(n, dtype=td, device="cuda") if g0 is None else dev(g0.astype(dtype))
@@ -154,3 +155,19 @@ def test_fp64_tolerance_mode_reaches_what_fp32_cannot(orc):
     f, g, done, err = run_log(x, y, a, b, eps, 1000, tol=1e-11, check_every=10, dtype=np.float64)
     assert done == done_o and done < 1000 and err < 1e-11
     assert np.max(np.abs(f - fo)) / eps <= 1e-10 and np.max(np.abs(g - go)) / eps <= 1e-10
+
+
+@pytest.mark.parametrize("dtype,tol", [(np.float32, 1e-4), (np.float64, 1e-10)])
+@pytest.mark.parametrize("damping,geometric", [(api.FSK_DAMP_ARITHMETIC, False), (api.FSK_DAMP_GEOMETRIC, True)])
+def test_relaxed_updates_in_the_log_domain(orc, dtype, tol, damping, geometric):
+    """Sec. 3.3 on the potentials, at an eps small enough that exp(f / eps) overflows fp64."""
+    rng = np.random.default_rng(55)
+    n, d = 700, 6
+    x = rng.uniform(size=(n, d)).astype(np.float32); y = rng.uniform(size=(n, d)).astype(np.float32)
+    a = rng.uniform(0.5, 1.5, n); a = (a / a.sum()).astype(np.float32)
+    b = rng.uniform(0.5, 1.5, n); b = (b / b.sum()).astype(np.float32)
+    for eps, eta in ((0.05, 0.6), (0.0005, 0.35)):
+        fo, go = orc.sinkhorn_log_points_damped(x, y, eps, a, b, 15, eta, geometric)
+        f, g, done, _ = run_log(x, y, a, b, eps, 15, dtype=dtype, damping=damping, eta=eta)
+        assert done == 15
+        assert np.max(np.abs(f - fo)) / eps <= tol and np.max(np.abs(g - go)) / eps <= tol
