@@ -270,7 +270,8 @@ int fsk_sinkhorn_log_points(const fsk_opts* opts, const void* x, const void* y, 
 /* ---- multitarget hot path (Sec. 5.3.2) -------------------------------------------------
  * A, B (inputs), U, V (IN/OUT): device, n x m row-major with leading dimension m, one histogram
  * pair per column, K shared.  Q = K V and R = K^T U are matrix products (MFMA).  Runs exactly
- * opts->max_iters iterations.  FSK_F32 (fp32 MFMA) or FSK_F64 (fp64 MFMA; needs the whole workspace,
+ * opts->max_iters iterations (FSK_EUNSUPPORTED for opts->tol > 0: see the _tol call below; and
+ * for a damping other than FSK_DAMP_NONE: the multitarget iteration is undamped).  FSK_F32 (fp32 MFMA) or FSK_F64 (fp64 MFMA; needs the whole workspace,
  * FSK_EWORKSPACE otherwise).  Any m >= 1: the columns go through
  * the kernels in groups of up to 64, one pass over K per group and product, so the time grows
  * with ceil(m / 64).  Workspace: fsk_workspace_bytes(opts, FSK_MODE_BATCHED, 0) holds the

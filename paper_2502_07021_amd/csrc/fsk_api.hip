@@ -808,7 +808,9 @@ int fsk_sinkhorn_batched(const fsk_opts* opts, const void* K, int64_t ldK, const
   clear_error();
   FSK_TRY(check_common(opts));
   if (opts->c != 1) return set_error(FSK_EUNSUPPORTED, "batched call takes c = 1");
-  if (opts->tol > 0.0) return set_error(FSK_EUNSUPPORTED, "batched call runs a fixed number of iterations");
+  if (opts->damping != FSK_DAMP_NONE) return set_error(FSK_EUNSUPPORTED, "the multitarget iteration is undamped");
+  if (opts->tol > 0.0)
+    return set_error(FSK_EUNSUPPORTED, "this call runs a fixed number of iterations (fsk_sinkhorn_batched_tol polls)");
   FSK_TRY(check_matrix("K", K, ldK, opts->n, opts->dtype));
   FSK_TRY(check_vec("A", A, false));
   FSK_TRY(check_vec("B", B, false));
@@ -824,6 +826,7 @@ int fsk_sinkhorn_batched_tol(const fsk_opts* opts, const void* K, int64_t ldK, c
   clear_error();
   FSK_TRY(check_common(opts));
   if (opts->c != 1) return set_error(FSK_EUNSUPPORTED, "batched call takes c = 1");
+  if (opts->damping != FSK_DAMP_NONE) return set_error(FSK_EUNSUPPORTED, "the multitarget iteration is undamped");
   if (!iters_done) return set_error(FSK_EINVAL, "iters_done is NULL");
   FSK_TRY(check_matrix("K", K, ldK, opts->n, opts->dtype));
   FSK_TRY(check_vec("A", A, false));
@@ -876,6 +879,7 @@ int fsk_sinkhorn_batched_dp(const fsk_opts* opts, const void* K, int64_t ldK, co
   FSK_TRY(check_common(opts));
   FSK_TRY(check_dp(dp));
   if (opts->c != 1) return set_error(FSK_EUNSUPPORTED, "batched call takes c = 1");
+  if (opts->damping != FSK_DAMP_NONE) return set_error(FSK_EUNSUPPORTED, "the multitarget iteration is undamped");
   if (opts->tol > 0.0) return set_error(FSK_EUNSUPPORTED, "batched call runs a fixed number of iterations");
   FSK_TRY(check_matrix("K", K, ldK, opts->n, opts->dtype));
   FSK_TRY(check_vec("A", A, false));

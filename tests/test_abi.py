@@ -98,3 +98,27 @@ def test_bad_pointers_and_alignment_are_rejected_on_the_host(api):
              None, None, None)
     assert L.fsk_sinkhorn_dense(*small) == api.FSK_EWORKSPACE
     assert b"workspace" in L.fsk_last_error()
+
+
+def test_multitarget_calls_refuse_what_they_do_not_carry(api):
+    """Options a call would otherwise ignore are refused on the host, before any launch."""
+    import torch
+    L = api.lib()
+    ok = ctypes.c_void_p(4096)
+    big = ctypes.c_size_t(1 << 40)
+    opts = api.make_opts(64, torch.float32, m=8, max_iters=3, damping=api.FSK_DAMP_ARITHMETIC, eta=0.5)
+    done, err = ctypes.c_int32(0), ctypes.c_double(0.0)
+    fixed = lambda: L.fsk_sinkhorn_batched(ctypes.byref(opts), ok, ctypes.c_int64(64), ok, ok, ok, ok, ok, big, None)
+    tolc = lambda: L.fsk_sinkhorn_batched_tol(ctypes.byref(opts), ok, ctypes.c_int64(64), ok, ok, ok, ok, ok, big,
+                                              ctypes.byref(done), ctypes.byref(err), None)
+    assert fixed() == api.FSK_EUNSUPPORTED and b"undamped" in L.fsk_last_error()
+    assert tolc() == api.FSK_EUNSUPPORTED
+    opts.damping = api.FSK_DAMP_NONE; opts.tol = 1e-6
+    assert fixed() == api.FSK_EUNSUPPORTED and b"fsk_sinkhorn_batched_tol" in L.fsk_last_error()
+    opts.c = 2
+    assert tolc() == api.FSK_EUNSUPPORTED
+    # tolerance mode asks for more workspace than the fixed-count mode (the copy of U)
+    opts.c = 1
+    with_tol = api.fsk_workspace_bytes(opts, api.FSK_MODE_BATCHED)
+    opts.tol = 0.0
+    assert with_tol >= api.fsk_workspace_bytes(opts, api.FSK_MODE_BATCHED) + 64 * 8 * 4
