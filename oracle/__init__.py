@@ -43,7 +43,7 @@ def _load():
         L.orc_lse.restype = ctypes.c_double
         L.orc_dp_normal.restype = ctypes.c_double
         L.orc_rdp_epsilon.restype = ctypes.c_double
-        for name in ("orc_num_threads", "orc_sinkhorn_dense", "orc_sinkhorn_dense_tol", "orc_sinkhorn_batched_tol",
+        for name in ("orc_num_threads", "orc_sinkhorn_dense", "orc_sinkhorn_dense_tol", "orc_sinkhorn_batched_tol", "orc_sinkhorn_batched_damped",
                      "orc_sinkhorn_blocked", "orc_sinkhorn_dense_damped", "orc_sinkhorn_batched",
                      "orc_sinkhorn_async_emulated", "orc_sinkhorn_grid", "orc_sinkhorn_batched_dp",
                      "orc_sinkhorn_log_points", "orc_sinkhorn_log_cost", "orc_sinkhorn_log_points_damped"):
@@ -249,6 +249,18 @@ def sinkhorn_batched(K, A, B, iters: int, U0=None, V0=None):
     U, V = _init(K.shape[0], U0, m), _init(K.shape[0], V0, m)
     rc = _load().orc_sinkhorn_batched(kp, kf, n, ld, _INT(m), _ptr(A), _ptr(B), _ptr(U), _ptr(V),
                                       _INT(iters))
+    assert rc == 0
+    return U, V
+
+
+def sinkhorn_batched_damped(K, A, B, iters: int, eta: float, geometric: bool, U0=None, V0=None):
+    """Multitarget form with the relaxed updates of Sec. 3.3 on every target."""
+    kp, kf, n, ld = _square(K)
+    A, B = _f64(A), _f64(B)
+    m = A.shape[1]
+    U, V = _init(K.shape[0], U0, m), _init(K.shape[0], V0, m)
+    rc = _load().orc_sinkhorn_batched_damped(kp, kf, n, ld, _INT(m), _ptr(A), _ptr(B), _ptr(U), _ptr(V),
+                                             _INT(iters), _DBL(eta), _INT(1 if geometric else 0))
     assert rc == 0
     return U, V
 

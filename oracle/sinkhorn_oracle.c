@@ -482,6 +482,36 @@ int orc_sinkhorn_batched(const void* K, int k_is_f32, int64_t n, int64_t ld, int
   return 0;
 }
 
+/* Multitarget form with the relaxed updates of Sec. 3.3 applied to every target
+ * (geometric == 0: X <- (1-eta) X + eta X_new; else X <- X^(1-eta) .* X_new^eta, X = U or V). */
+int orc_sinkhorn_batched_damped(const void* K, int k_is_f32, int64_t n, int64_t ld, int m,
+                                const double* A, const double* B, double* U, double* V, int iters,
+                                double eta, int geometric) {
+  double* Q = (double*)malloc(sizeof(double) * (size_t)n * (size_t)m);
+  if (!Q) return -1;
+  for (int t = 0; t < iters; ++t) {
+    for (int side = 0; side < 2; ++side) {
+      const double* X = side == 0 ? V : U;     /* the factor the product runs over */
+      double* Y = side == 0 ? U : V;           /* the factor being updated */
+      const double* M = side == 0 ? A : B;
+#pragma omp parallel for schedule(static)
+      for (int64_t i = 0; i < n; ++i) {
+        for (int k = 0; k < m; ++k) Q[i * m + k] = 0.0;
+        for (int64_t j = 0; j < n; ++j) {
+          double kij = side == 0 ? k_at(K, k_is_f32, ld, i, j) : k_at(K, k_is_f32, ld, j, i);
+          for (int k = 0; k < m; ++k) Q[i * m + k] += kij * X[j * m + k];
+        }
+      }
+      for (int64_t e = 0; e < n * (int64_t)m; ++e) {
+        double target = M[e] / Q[e];
+        Y[e] = geometric ? pow(Y[e], 1.0 - eta) * pow(target, eta) : (1.0 - eta) * Y[e] + eta * target;
+      }
+    }
+  }
+  free(Q);
+  return 0;
+}
+
 /* Multitarget form with the stop rule of orc_sinkhorn_dense_tol applied to all targets at once
  * (the multitarget experiment of Sec. 5.3.2 iterates until every target meets the threshold):
  * err = max over columns k of ||P_k 1 - a_k||_1, P_k = diag(u_k) K diag(v_k), evaluated after a

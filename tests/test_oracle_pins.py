@@ -305,6 +305,23 @@ def test_batched_column_equals_single_run(orc):
     assert np.allclose(U1, Uref, rtol=1e-13) and np.allclose(V1, B / (K.T @ Uref), rtol=1e-13)
 
 
+def test_batched_damped_column_equals_single_damped_run(orc):
+    x, y, a, b, C, K = problem(22, 29, eps=0.3)
+    K = K + 0.05 * np.random.default_rng(1).uniform(size=K.shape)      # K != K^T: a transposed walk would show
+    rng = np.random.default_rng(6)
+    m = 4
+    A = rng.exponential(size=(22, m)); A /= A.sum(0)
+    B = rng.exponential(size=(22, m)); B /= B.sum(0)
+    for geometric in (False, True):
+        U, V = orc.sinkhorn_batched_damped(K, A, B, 17, 0.55, geometric)
+        for k in range(m):
+            u, v = orc.sinkhorn_dense_damped(K, A[:, k], B[:, k], 17, 0.55, geometric)
+            assert np.allclose(U[:, k], u, rtol=1e-13) and np.allclose(V[:, k], v, rtol=1e-13)
+        U1, V1 = orc.sinkhorn_batched_damped(K, A, B, 9, 1.0, geometric)   # eta = 1: the plain iteration
+        U0, V0 = orc.sinkhorn_batched(K, A, B, 9)
+        assert np.allclose(U1, U0, rtol=1e-13) and np.allclose(V1, V0, rtol=1e-13)
+
+
 def test_batched_tolerance_mode(orc):
     """The stacked run stops at the first poll where EVERY target is below the tolerance: its
     error is the largest of the per-target errors (NumPy, from the plan), its iterates are those
