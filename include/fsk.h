@@ -270,14 +270,19 @@ int fsk_sinkhorn_log_points(const fsk_opts* opts, const void* x, const void* y, 
 /* ---- multitarget hot path (Sec. 5.3.2) -------------------------------------------------
  * A, B (inputs), U, V (IN/OUT): device, n x m row-major with leading dimension m, one histogram
  * pair per column, K shared.  Q = K V and R = K^T U are matrix products (MFMA).  Runs exactly
- * opts->max_iters iterations (FSK_EUNSUPPORTED for opts->tol > 0: see the _tol call below; and
- * for a damping other than FSK_DAMP_NONE: the multitarget iteration is undamped).  FSK_F32 (fp32 MFMA) or FSK_F64 (fp64 MFMA; needs the whole workspace,
- * FSK_EWORKSPACE otherwise).  Any m >= 1: the columns go through
- * the kernels in groups of up to 64, one pass over K per group and product, so the time grows
- * with ceil(m / 64).  Workspace: fsk_workspace_bytes(opts, FSK_MODE_BATCHED, 0) holds the
- * partial products of all groups and a transposed copy of K; with at least the partial products
- * (the size the error message of a too-small workspace states) the call still runs, with a
- * slower kernel for K V. */
+ * opts->max_iters iterations (FSK_EUNSUPPORTED for opts->tol > 0: see the _tol call below).
+ * FSK_F32 (fp32 MFMA) or FSK_F64 (fp64 MFMA; needs the whole workspace, FSK_EWORKSPACE
+ * otherwise).  Any m >= 1: the columns go through the kernels in groups of up to 64, one pass
+ * over K per group and product, so the time grows with ceil(m / 64).
+ * Workspace: fsk_workspace_bytes(opts, FSK_MODE_BATCHED, 0) holds the partial products of all
+ * groups and a transposed copy of K; with at least the partial products (the size the error
+ * message of a too-small workspace states) an undamped call still runs, with a slower kernel
+ * for K V.
+ * opts->damping / opts->eta apply the relaxed updates of Sec. 3.3 to every target: each
+ * half-step is written to a scratch n x m matrix and an elementwise kernel folds it into U or V
+ * (arithmetic: (1 - eta) X + eta X_new; geometric: exp2((1 - eta) log2 X + eta log2 X_new) in
+ * the call's precision).  A damped call needs the whole workspace of its opts (it holds that
+ * scratch matrix too): FSK_EWORKSPACE otherwise. */
 int fsk_sinkhorn_batched(const fsk_opts* opts, const void* K, int64_t ldK, const void* A,
                          const void* B, void* U, void* V, void* workspace, size_t ws_bytes,
                          void* stream);
@@ -286,11 +291,12 @@ int fsk_sinkhorn_batched(const fsk_opts* opts, const void* K, int64_t ldK, const
  * multitarget experiment of Sec. 5.3.2 iterates until every target meets the threshold):
  * opts->tol > 0 stops at the first poll (every opts->check_every iterations, and after
  * opts->max_iters) at which max over columns k of ||P_k 1 - a_k||_1 < tol, P_k = diag(u_k) K
- * diag(v_k), with the scalings as they stand after a V-update; opts->tol <= 0 runs max_iters
- * iterations and leaves *err NaN.  iters_done (host, required) and err (host, may be NULL)
+ * diag(v_k), with the scalings as they stand after a V-update (damped or not: in a damped run
+ * the error is read off the undamped U-update of that state before it is relaxed);
+ * opts->tol <= 0 runs max_iters iterations and leaves *err NaN.  iters_done (host, required) and err (host, may be NULL)
  * receive the iteration count and that maximum; U, V hold the state they describe.  The call
  * synchronises at every poll.  Workspace: fsk_workspace_bytes(opts, FSK_MODE_BATCHED, 0) with
- * the same opts (in tolerance mode it also holds a copy of U).  FSK_ENONFINITE as in the dense
+ * the same opts (in tolerance mode, as in a damped run, it also holds an n x m scratch matrix).  FSK_ENONFINITE as in the dense
  * call. */
 int fsk_sinkhorn_batched_tol(const fsk_opts* opts, const void* K, int64_t ldK, const void* A,
                              const void* B, void* U, void* V, void* workspace, size_t ws_bytes,
@@ -320,7 +326,8 @@ int fsk_dp_release(const fsk_opts* opts, void* X, double clip, double sigma, uin
                    uint64_t release, void* stream);
 
 /* fsk_sinkhorn_batched with a release after every update (the noised scalings replace the held
- * ones, as in the appendix' experiments): U = A ./ (K V), release U, V = B ./ (K^T U), release V. */
+ * ones, as in the appendix' experiments): U = A ./ (K V), release U, V = B ./ (K^T U), release V.
+ * Undamped, fixed iteration count: FSK_EUNSUPPORTED for a damping or a tolerance in opts. */
 int fsk_sinkhorn_batched_dp(const fsk_opts* opts, const void* K, int64_t ldK, const void* A,
                             const void* B, void* U, void* V, const fsk_dp* dp, void* workspace,
                             size_t ws_bytes, void* stream);

@@ -130,10 +130,12 @@ static size_t batched_base_bytes(const fsk_opts* o) {
 static size_t batched_save_bytes(const fsk_opts* o) {
   return align_up((size_t)o->n * (size_t)o->m * elem_size(o->dtype), 256);
 }
+static bool batched_needs_tmp(const fsk_opts* o) { return o->tol > 0.0 || o->damping != FSK_DAMP_NONE; }
 static size_t batched_total_bytes(const fsk_opts* o) {
-  if (!(o->tol > 0.0)) return batched_base_bytes(o);
-  return batched_base_bytes(o) + batched_save_bytes(o) +
-         align_up(batched_poll_scratch_doubles(o->n, o->m) * 8, 256);
+  size_t total = batched_base_bytes(o);
+  if (batched_needs_tmp(o)) total += batched_save_bytes(o);
+  if (o->tol > 0.0) total += align_up(batched_poll_scratch_doubles(o->n, o->m) * 8, 256);
+  return total;
 }
 
 size_t fsk_workspace_bytes(const fsk_opts* opts, int mode, int d) {
@@ -808,7 +810,6 @@ int fsk_sinkhorn_batched(const fsk_opts* opts, const void* K, int64_t ldK, const
   clear_error();
   FSK_TRY(check_common(opts));
   if (opts->c != 1) return set_error(FSK_EUNSUPPORTED, "batched call takes c = 1");
-  if (opts->damping != FSK_DAMP_NONE) return set_error(FSK_EUNSUPPORTED, "the multitarget iteration is undamped");
   if (opts->tol > 0.0)
     return set_error(FSK_EUNSUPPORTED, "this call runs a fixed number of iterations (fsk_sinkhorn_batched_tol polls)");
   FSK_TRY(check_matrix("K", K, ldK, opts->n, opts->dtype));
@@ -817,7 +818,14 @@ int fsk_sinkhorn_batched(const fsk_opts* opts, const void* K, int64_t ldK, const
   FSK_TRY(check_vec("U", U, false));
   FSK_TRY(check_vec("V", V, false));
   if (workspace && !aligned16(workspace)) return set_error(FSK_EALIGN, "workspace is not 16-byte aligned");
-  return run_sinkhorn_batched(opts, K, ldK, A, B, U, V, workspace, ws_bytes, nullptr, (hipStream_t)stream);
+  if (opts->damping == FSK_DAMP_NONE)
+    return run_sinkhorn_batched(opts, K, ldK, A, B, U, V, workspace, ws_bytes, nullptr, (hipStream_t)stream);
+  // relaxed updates: every half-step lands in a scratch matrix behind the usual workspace first
+  const size_t need = batched_total_bytes(opts), base = batched_base_bytes(opts);
+  if (!workspace || ws_bytes < need)
+    return set_error(FSK_EWORKSPACE, "damped batched call needs %zu workspace bytes, got %zu", need, ws_bytes);
+  return run_sinkhorn_batched(opts, K, ldK, A, B, U, V, workspace, base, nullptr, (hipStream_t)stream,
+                              nullptr, (char*)workspace + base);
 }
 
 int fsk_sinkhorn_batched_tol(const fsk_opts* opts, const void* K, int64_t ldK, const void* A,
@@ -826,7 +834,6 @@ int fsk_sinkhorn_batched_tol(const fsk_opts* opts, const void* K, int64_t ldK, c
   clear_error();
   FSK_TRY(check_common(opts));
   if (opts->c != 1) return set_error(FSK_EUNSUPPORTED, "batched call takes c = 1");
-  if (opts->damping != FSK_DAMP_NONE) return set_error(FSK_EUNSUPPORTED, "the multitarget iteration is undamped");
   if (!iters_done) return set_error(FSK_EINVAL, "iters_done is NULL");
   FSK_TRY(check_matrix("K", K, ldK, opts->n, opts->dtype));
   FSK_TRY(check_vec("A", A, false));
@@ -842,13 +849,13 @@ int fsk_sinkhorn_batched_tol(const fsk_opts* opts, const void* K, int64_t ldK, c
   BatchedPoll poll{};
   poll.tol = opts->tol;
   poll.check_every = opts->check_every;
-  poll.save = (char*)workspace + base;
-  poll.scratch = (double*)((char*)workspace + base + batched_save_bytes(opts));
+  void* tmp = batched_needs_tmp(opts) ? (char*)workspace + base : nullptr;
+  poll.scratch = (double*)((char*)workspace + base + (tmp ? batched_save_bytes(opts) : 0));
   poll.iters_done = iters_done;
   poll.err = err;
   if (err) *err = NAN;
   return run_sinkhorn_batched(opts, K, ldK, A, B, U, V, workspace, base, nullptr, (hipStream_t)stream,
-                              &poll);
+                              &poll, tmp);
 }
 
 // ------------------------------------------------------------- privacy layer

@@ -572,9 +572,9 @@ __global__ __launch_bounds__(256) void batched_rowreduce_kernel(const float* __r
 
 int run_sinkhorn_batched(const fsk_opts* o, const void* K, int64_t ldK, const void* A, const void* B,
                          void* U, void* V, void* workspace, size_t ws_bytes, const fsk_dp* dp,
-                         hipStream_t st, const BatchedPoll* poll) {
+                         hipStream_t st, const BatchedPoll* poll, void* tmp) {
   if (o->dtype == FSK_F64)
-    return run_sinkhorn_batched_f64(o, K, ldK, A, B, U, V, workspace, ws_bytes, dp, st, poll);
+    return run_sinkhorn_batched_f64(o, K, ldK, A, B, U, V, workspace, ws_bytes, dp, st, poll, tmp);
   const int n = o->n, m = o->m;
   const int S = batched_splits(n);
   const size_t part_bytes = batched_partial_bytes(n, m);
@@ -637,8 +637,8 @@ int run_sinkhorn_batched(const fsk_opts* o, const void* K, int64_t ldK, const vo
     }
     return FSK_OK;
   };
-  auto v_update = [&]() -> int {  // V = B ./ (K^T U)
-    return wide(Kf, ldK, Uf, Bf, Vf, "batched_prod_wide_kernel (K^T U)");
+  auto v_update = [&](void* dst) -> int {  // V = B ./ (K^T U)
+    return wide(Kf, ldK, Uf, Bf, (float*)dst, "batched_prod_wide_kernel (K^T U)");
   };
   auto release = [&](int it, bool is_v) -> int {  // the release clips every row across ALL m targets
     if (!dp) return FSK_OK;
@@ -647,7 +647,7 @@ int run_sinkhorn_batched(const fsk_opts* o, const void* K, int64_t ldK, const vo
                 : launch_dp_release(FSK_F32, Uf, n, m, dp->clip_u, dp->sigma_u, dp->seed,
                                     dp->release0 + 2 * (uint64_t)it, st);
   };
-  return batched_iterate(o, Af, Uf, poll, st, u_update, v_update, release);
+  return batched_iterate(o, Af, Uf, Vf, poll, tmp, st, u_update, v_update, release);
 }
 
 // ------------------------------------------------------------------ error of a polled state
@@ -697,6 +697,35 @@ __global__ __launch_bounds__(256) void batched_poll_final_kernel(const double* _
     }
     out[0] = any_bad ? NAN : r;
   }
+}
+
+// ------------------------------------------------------------------ relaxed updates (Sec. 3.3)
+__device__ __forceinline__ float relax_log2(float x) { return log2f(x); }
+__device__ __forceinline__ double relax_log2(double x) { return log2(x); }
+__device__ __forceinline__ float relax_exp2(float x) { return exp2f(x); }
+__device__ __forceinline__ double relax_exp2(double x) { return exp2(x); }
+
+template <typename T>
+__global__ __launch_bounds__(256) void batched_relax_kernel(T* __restrict__ X, const T* __restrict__ Xnew,
+                                                            int64_t count, T eta, int geometric) {
+  const int64_t e = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (e >= count) return;
+  const T old = X[e], fresh = Xnew[e];
+  X[e] = geometric ? relax_exp2(fma(T(1) - eta, relax_log2(old), eta * relax_log2(fresh)))
+                   : (T(1) - eta) * old + eta * fresh;
+}
+
+int launch_batched_relax(int dtype, void* X, const void* Xnew, int64_t count, double eta, int geometric,
+                         hipStream_t st) {
+  const dim3 grid((unsigned)((count + 255) / 256));
+  if (dtype == FSK_F64)
+    hipLaunchKernelGGL((batched_relax_kernel<double>), grid, dim3(256), 0, st, (double*)X, (const double*)Xnew,
+                       count, eta, geometric);
+  else
+    hipLaunchKernelGGL((batched_relax_kernel<float>), grid, dim3(256), 0, st, (float*)X, (const float*)Xnew,
+                       count, (float)eta, geometric);
+  FSK_LAUNCH_CHECK("batched_relax_kernel");
+  return FSK_OK;
 }
 
 size_t batched_poll_scratch_doubles(int n, int m) { return 8 + (size_t)((n + 255) / 256) * (size_t)m; }

@@ -343,7 +343,7 @@ size_t batched_f64_workspace_bytes(int n, int m) {
 
 int run_sinkhorn_batched_f64(const fsk_opts* o, const void* K, int64_t ldK, const void* A, const void* B,
                              void* U, void* V, void* workspace, size_t ws_bytes, const fsk_dp* dp,
-                             hipStream_t st, const BatchedPoll* poll) {
+                             hipStream_t st, const BatchedPoll* poll, void* tmp) {
   const int n = o->n, m = o->m;
   const size_t need = batched_f64_workspace_bytes(n, m);
   if (!workspace || ws_bytes < need)
@@ -378,7 +378,7 @@ int run_sinkhorn_batched_f64(const fsk_opts* o, const void* K, int64_t ldK, cons
   auto u_update = [&](void* dst) -> int {  // U = A ./ (K V) as the transposed product of K^T
     return product(Kt, ldt, Vd, Ad, (double*)dst);
   };
-  auto v_update = [&]() -> int { return product(Kd, ldK, Ud, Bd, Vd); };  // V = B ./ (K^T U)
+  auto v_update = [&](void* dst) -> int { return product(Kd, ldK, Ud, Bd, (double*)dst); };  // V = B ./ (K^T U)
   auto release = [&](int it, bool is_v) -> int {
     if (!dp) return FSK_OK;
     return is_v ? launch_dp_release(FSK_F64, Vd, n, m, dp->clip_v, dp->sigma_v, dp->seed,
@@ -386,7 +386,7 @@ int run_sinkhorn_batched_f64(const fsk_opts* o, const void* K, int64_t ldK, cons
                 : launch_dp_release(FSK_F64, Ud, n, m, dp->clip_u, dp->sigma_u, dp->seed,
                                     dp->release0 + 2 * (uint64_t)it, st);
   };
-  return batched_iterate(o, Ad, Ud, poll, st, u_update, v_update, release);
+  return batched_iterate(o, Ad, Ud, Vd, poll, tmp, st, u_update, v_update, release);
 }
 
 }  // namespace fsk

@@ -150,7 +150,6 @@ size_t batched_workspace_bytes(int n, int m);
 struct BatchedPoll {
   double tol;
   int check_every;
-  void* save;          // n x m elements of the call's dtype
   double* scratch;     // batched_poll_scratch_doubles(n, m) doubles; [0] receives the error
   int32_t* iters_done; // host
   double* err;         // host, may be null
@@ -159,25 +158,37 @@ size_t batched_poll_scratch_doubles(int n, int m);
 // scratch[0] = max over columns k of sum_i A_ik |Uold_ik / Unew_ik - 1| (fp64, fixed order).
 int launch_batched_poll_error(int dtype, const void* A, const void* Uold, const void* Unew, int n,
                               int m, double* scratch, hipStream_t st);
-// `dp` (may be null): release U after every U-update and V after every V-update.
+// X <- (1 - eta) X + eta Xnew, or X <- X^(1-eta) Xnew^eta (as exp2 of the weighted log2's), over
+// `count` elements (Sec. 3.3 on every target).
+int launch_batched_relax(int dtype, void* X, const void* Xnew, int64_t count, double eta, int geometric,
+                         hipStream_t st);
+// `dp` (may be null): release U after every U-update and V after every V-update.  `tmp`: n x m
+// elements of scratch, needed when opts->damping != FSK_DAMP_NONE or `poll` asks for a tolerance.
 int run_sinkhorn_batched(const fsk_opts* o, const void* K, int64_t ldK, const void* A, const void* B,
                          void* U, void* V, void* workspace, size_t ws_bytes, const fsk_dp* dp,
-                         hipStream_t st, const BatchedPoll* poll = nullptr);
+                         hipStream_t st, const BatchedPoll* poll = nullptr, void* tmp = nullptr);
 
 // fp64 form (MFMA f64 16x16x4): needs the full workspace (partial products + K^T).
 size_t batched_f64_workspace_bytes(int n, int m);
 int run_sinkhorn_batched_f64(const fsk_opts* o, const void* K, int64_t ldK, const void* A, const void* B,
                              void* U, void* V, void* workspace, size_t ws_bytes, const fsk_dp* dp,
-                             hipStream_t st, const BatchedPoll* poll = nullptr);
-// The loop both precisions share: `u_update(dst)` / `v_update()` enqueue one half-step (the
-// U-update into dst, normally U itself), `release(it, is_v)` the privacy layer's step (may do
-// nothing).  `poll` null or with tol <= 0: exactly max_iters iterations, nothing synchronises.
+                             hipStream_t st, const BatchedPoll* poll = nullptr, void* tmp = nullptr);
+// The loop both precisions share: `u_update(dst)` / `v_update(dst)` enqueue one half-step into dst
+// (normally U or V itself), `release(it, is_v)` the privacy layer's step (may do nothing).
+// `poll` null or with tol <= 0: exactly max_iters iterations, nothing synchronises.
+// With a relaxation (Sec. 3.3) every half-step lands in `tmp` first and an elementwise kernel
+// folds it into the scaling; the undamped U in `tmp` is also what a poll reads the error off.
 template <class UUpdate, class VUpdate, class Release>
-inline int batched_iterate(const fsk_opts* o, const void* A, void* U, const BatchedPoll* poll,
-                           hipStream_t st, UUpdate u_update, VUpdate v_update, Release release) {
+inline int batched_iterate(const fsk_opts* o, const void* A, void* U, void* V, const BatchedPoll* poll,
+                           void* tmp, hipStream_t st, UUpdate u_update, VUpdate v_update,
+                           Release release) {
   const int n = o->n, m = o->m;
-  const size_t bytes = (size_t)n * (size_t)m * elem_size(o->dtype);
+  const int64_t count = (int64_t)n * m;
+  const size_t bytes = (size_t)count * elem_size(o->dtype);
   const bool check = poll && poll->tol > 0.0;
+  const bool damped = o->damping != FSK_DAMP_NONE && o->eta < 1.0;
+  const int geometric = o->damping == FSK_DAMP_GEOMETRIC ? 1 : 0;
+  if ((check || damped) && !tmp) return set_error(FSK_EWORKSPACE, "multitarget call: scratch for U is missing");
   int done = 0;
   double e = NAN;
   bool converged = false;
@@ -193,28 +204,48 @@ inline int batched_iterate(const fsk_opts* o, const void* A, void* U, const Batc
     return set_error(FSK_ENONFINITE, "marginal error is not finite after %d iterations", at);
   };
   for (int it = 0; it < o->max_iters; ++it) {
+    // the U-update forms K V of the state after `it` iterations: a poll reads its error there
     const bool p = check && it > 0 && it % poll->check_every == 0;
-    if (p) FSK_HIP(hipMemcpyAsync(poll->save, U, bytes, hipMemcpyDeviceToDevice, st));
-    FSK_TRY(u_update(U));
-    if (p) {  // the U-update just formed K V of the state after `it` iterations
-      FSK_TRY(read_error(poll->save, U));
-      if (!(e == e) || e > 1.7e308) return nonfinite(it);
-      if (e < poll->tol) {
-        FSK_HIP(hipMemcpyAsync(U, poll->save, bytes, hipMemcpyDeviceToDevice, st));
-        FSK_HIP(hipStreamSynchronize(st));
-        done = it;
-        converged = true;
-        break;
+    if (damped) {
+      FSK_TRY(u_update(tmp));
+      if (p) {
+        FSK_TRY(read_error(U, tmp));
+        if (!(e == e) || e > 1.7e308) return nonfinite(it);
+        if (e < poll->tol) {  // U has not been touched yet
+          done = it;
+          converged = true;
+          break;
+        }
+      }
+      FSK_TRY(launch_batched_relax(o->dtype, U, tmp, count, o->eta, geometric, st));
+    } else {
+      if (p) FSK_HIP(hipMemcpyAsync(tmp, U, bytes, hipMemcpyDeviceToDevice, st));
+      FSK_TRY(u_update(U));
+      if (p) {
+        FSK_TRY(read_error(tmp, U));
+        if (!(e == e) || e > 1.7e308) return nonfinite(it);
+        if (e < poll->tol) {  // undo the update that revealed it
+          FSK_HIP(hipMemcpyAsync(U, tmp, bytes, hipMemcpyDeviceToDevice, st));
+          FSK_HIP(hipStreamSynchronize(st));
+          done = it;
+          converged = true;
+          break;
+        }
       }
     }
     FSK_TRY(release(it, false));
-    FSK_TRY(v_update());
+    if (damped) {
+      FSK_TRY(v_update(tmp));
+      FSK_TRY(launch_batched_relax(o->dtype, V, tmp, count, o->eta, geometric, st));
+    } else {
+      FSK_TRY(v_update(V));
+    }
     FSK_TRY(release(it, true));
     done = it + 1;
   }
   if (check && !converged && done > 0) {  // the state after the last iteration is always polled
-    FSK_TRY(u_update(poll->save));         // its next U, only to read the error off it
-    FSK_TRY(read_error(U, poll->save));
+    FSK_TRY(u_update(tmp));                // its next (undamped) U, only to read the error off it
+    FSK_TRY(read_error(U, tmp));
     if (!(e == e) || e > 1.7e308) return nonfinite(done);
   }
   if (poll) {

@@ -111,8 +111,17 @@ def test_multitarget_calls_refuse_what_they_do_not_carry(api):
     fixed = lambda: L.fsk_sinkhorn_batched(ctypes.byref(opts), ok, ctypes.c_int64(64), ok, ok, ok, ok, ok, big, None)
     tolc = lambda: L.fsk_sinkhorn_batched_tol(ctypes.byref(opts), ok, ctypes.c_int64(64), ok, ok, ok, ok, ok, big,
                                               ctypes.byref(done), ctypes.byref(err), None)
-    assert fixed() == api.FSK_EUNSUPPORTED and b"undamped" in L.fsk_last_error()
-    assert tolc() == api.FSK_EUNSUPPORTED
+    dp = api.fsk_dp(1.0, 1.0, 0.1, 0.1, 7, 0)
+    noisy = lambda: L.fsk_sinkhorn_batched_dp(ctypes.byref(opts), ok, ctypes.c_int64(64), ok, ok, ok, ok,
+                                              ctypes.byref(dp), ok, big, None)
+    assert noisy() == api.FSK_EUNSUPPORTED and b"undamped" in L.fsk_last_error()
+    # a damped multitarget run keeps every half-step in a scratch matrix: more workspace, or a refusal
+    undamped = api.make_opts(64, torch.float32, m=8, max_iters=3)
+    need = api.fsk_workspace_bytes(opts, api.FSK_MODE_BATCHED)
+    assert need >= api.fsk_workspace_bytes(undamped, api.FSK_MODE_BATCHED) + 64 * 8 * 4
+    short = lambda: L.fsk_sinkhorn_batched(ctypes.byref(opts), ok, ctypes.c_int64(64), ok, ok, ok, ok, ok,
+                                           ctypes.c_size_t(need - 16), None)
+    assert short() == api.FSK_EWORKSPACE and b"damped" in L.fsk_last_error()
     opts.damping = api.FSK_DAMP_NONE; opts.tol = 1e-6
     assert fixed() == api.FSK_EUNSUPPORTED and b"fsk_sinkhorn_batched_tol" in L.fsk_last_error()
     opts.c = 2

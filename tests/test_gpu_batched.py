@@ -174,3 +174,75 @@ def test_batched_tolerance_cap_fixed_mode_and_workspace(orc):
     with pytest.raises(api.FskError) as e:                                  # no room for the copy of U
         api.fsk_sinkhorn_batched_tol(opts, Kd, Ad, Bd, X.clone(), X.clone(), small)
     assert e.value.status == api.FSK_EWORKSPACE
+
+
+def _run_damped(K, A, B, iters, eta, geometric, dtype, tol=0.0, check_every=1, small_workspace=False):
+    n, m = A.shape
+    td = torch.float64 if dtype == np.float64 else torch.float32
+    damping = api.FSK_DAMP_GEOMETRIC if geometric else api.FSK_DAMP_ARITHMETIC
+    opts = api.make_opts(n, td, m=m, max_iters=iters, damping=damping, eta=eta, tol=tol, check_every=check_every)
+    ws = api.alloc_workspace(opts, api.FSK_MODE_BATCHED)
+    if small_workspace:
+        ws = ws[: ws.numel() - 256]
+    pack = 16 // np.dtype(dtype).itemsize
+    full = torch.full((n, (n + pack - 1) // pack * pack), float("nan"), dtype=td, device="cuda")
+    full[:, :n] = dev(np.ascontiguousarray(K.astype(dtype)))
+    U = torch.ones(n, m, dtype=td, device="cuda"); V = torch.ones(n, m, dtype=td, device="cuda")
+    Ad = dev(np.ascontiguousarray(A.astype(dtype))); Bd = dev(np.ascontiguousarray(B.astype(dtype)))
+    if tol > 0:
+        done, err = api.fsk_sinkhorn_batched_tol(opts, full[:, :n], Ad, Bd, U, V, ws)
+    else:
+        api.fsk_sinkhorn_batched(opts, full[:, :n], Ad, Bd, U, V, ws)
+        done, err = iters, float("nan")
+    torch.cuda.synchronize()
+    return U.cpu().numpy(), V.cpu().numpy(), done, err
+
+
+@pytest.mark.parametrize("dtype,n,m,eta,geometric", [
+    (np.float64, 300, 70, 0.6, False), (np.float64, 515, 5, 0.35, True), (np.float64, 64, 64, 1.0, False),
+    (np.float32, 1030, 64, 0.5, False), (np.float32, 400, 150, 0.7, True), (np.float32, 5, 3, 0.25, True),
+])
+def test_batched_relaxed_updates(orc, dtype, n, m, eta, geometric):
+    """Relaxed updates (Sec. 3.3) on every target of the multitarget iteration, both means."""
+    K, A, B = problem(orc, n, m, 6100 + n + m, eps=0.1)
+    K = np.ascontiguousarray(K.astype(dtype)); A = A.astype(dtype); B = B.astype(dtype)
+    ones = np.ones((n, m))
+    Uo, Vo = orc.sinkhorn_batched_damped(K, A, B, 12, eta, geometric, ones, ones)
+    U, V, _, _ = _run_damped(K, A, B, 12, eta, geometric, dtype)
+    bar = 1e-10 if dtype == np.float64 else 1e-4
+    assert relerr(U, Uo) <= bar and relerr(V, Vo) <= bar
+    if eta == 1.0:                                             # eta = 1 is the plain iteration
+        Up, Vp = run_batched(K, A, B, 12, dtype=dtype)
+        assert np.array_equal(U, Up) and np.array_equal(V, Vp)
+
+
+@pytest.mark.parametrize("dtype,geometric", [(np.float64, False), (np.float32, True)])
+def test_batched_relaxed_updates_with_the_stop_rule(orc, dtype, geometric):
+    """Damped run with a tolerance: the error polled is that of the damped state (its undamped
+    next U against it), and the state handed back is the fixed-count damped run's."""
+    n, m, eta, ce = 300, 40, 0.6, 3
+    tol = 1e-8 if dtype == np.float64 else 3e-5
+    rng = np.random.default_rng(93)
+    x = rng.uniform(size=(n, 2)); y = rng.uniform(size=(n, 2))
+    K64, _ = orc.gibbs_from_points(x, y, 0.3, False)
+    K = np.ascontiguousarray(K64.astype(dtype))
+    A = rng.uniform(0.5, 1.5, (n, m)) ** 3; A = np.ascontiguousarray((A / A.sum(0)).astype(dtype))
+    B = rng.uniform(0.5, 1.5, (n, m)) ** 3; B = np.ascontiguousarray((B / B.sum(0)).astype(dtype))
+    U, V, done, err = _run_damped(K, A, B, 600, eta, geometric, dtype, tol=tol, check_every=ce)
+    assert 0 < done < 600 and done % ce == 0 and err < tol
+    Uf, Vf, _, _ = _run_damped(K, A, B, done, eta, geometric, dtype)
+    assert np.array_equal(U, Uf) and np.array_equal(V, Vf)
+    ones = np.ones((n, m))
+    worst = lambda UU, VV: max(orc.marginal_error(K, A[:, k], UU[:, k], VV[:, k])[0] for k in range(m))
+    Uo, Vo = orc.sinkhorn_batched_damped(K, A, B, done, eta, geometric, ones, ones)
+    assert worst(Uo, Vo) == pytest.approx(err, rel=1e-6 if dtype == np.float64 else 0.2)
+    if dtype == np.float64:                                    # the poll before it had not converged
+        Up, Vp = orc.sinkhorn_batched_damped(K, A, B, done - ce, eta, geometric, ones, ones)
+        assert worst(Up, Vp) >= tol and relerr(U, Uo) <= 1e-10
+
+
+def test_batched_relaxed_updates_need_the_scratch_matrix(orc):
+    K, A, B = problem(orc, 100, 8, 5)
+    with pytest.raises(api.FskError) as e:
+        _run_damped(K, A, B, 3, 0.5, False, np.float32, small_workspace=True)
+    assert e.value.status == api.FSK_EWORKSPACE
