@@ -451,8 +451,8 @@ __global__ __launch_bounds__(256) void log_finalize_kernel(const double* __restr
       if (geometric) {
         keep = (1.0 - eta) * old + eta * pot_new;
       } else {
-        const double M = old > pot_new ? old : pot_new;
-        keep = M + eps * log((1.0 - eta) * exp((old - M) / eps) + eta * exp((pot_new - M) / eps));
+        const double top = old > pot_new ? old : pot_new;
+        keep = top + eps * log((1.0 - eta) * exp((old - top) / eps) + eta * exp((pot_new - top) / eps));
       }
     }
     potd[i] = keep;

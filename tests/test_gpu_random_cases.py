@@ -64,6 +64,7 @@ def test_random_dense_problems(orc, seed):
 @pytest.mark.parametrize("seed", [21, 22])
 def test_random_multitarget_problems(orc, seed):
     rng = np.random.default_rng(seed)
+    rng_damp = np.random.default_rng(seed + 1000)
     for case in range(20):
         dtype, td, tol = _pick(rng)
         n = int(rng.choice([rng.integers(1, 100), rng.integers(100, 1500), rng.integers(1500, 3000)]))
@@ -75,15 +76,21 @@ def test_random_multitarget_problems(orc, seed):
         A = rng.exponential(size=(n, m)); A = np.ascontiguousarray((A / A.sum(0)).astype(dtype))
         B = rng.exponential(size=(n, m)); B = np.ascontiguousarray((B / B.sum(0)).astype(dtype))
         full = _padded(K, td, int(rng.integers(0, 2)))
-        opts = api.make_opts(n, td, m=m, max_iters=iters)
+        damping = int(rng_damp.choice([api.FSK_DAMP_NONE, api.FSK_DAMP_ARITHMETIC, api.FSK_DAMP_GEOMETRIC]))
+        eta = float(rng_damp.uniform(0.2, 1.0))
+        opts = api.make_opts(n, td, m=m, max_iters=iters, damping=damping, eta=eta)
         ws = api.alloc_workspace(opts, api.FSK_MODE_BATCHED)
-        if dtype == np.float32 and rng.random() < 0.25:            # no room for K^T: the direct row kernel
-            ws = ws[: ws.numel() - n * n * 4]
+        if dtype == np.float32 and damping == api.FSK_DAMP_NONE and rng.random() < 0.25:
+            ws = ws[: ws.numel() - n * n * 4]                      # no room for K^T: the direct row kernel
         U = torch.ones(n, m, dtype=td, device="cuda"); V = torch.ones(n, m, dtype=td, device="cuda")
         api.fsk_sinkhorn_batched(opts, full[:, :n], dev(A), dev(B), U, V, ws)
         torch.cuda.synchronize()
-        Uo, Vo = orc.sinkhorn_batched(K, A, B, iters)
-        what = (seed, case, n, m, np.dtype(dtype).name, iters)
+        if damping == api.FSK_DAMP_NONE:
+            Uo, Vo = orc.sinkhorn_batched(K, A, B, iters)
+        else:
+            ones = np.ones((n, m))
+            Uo, Vo = orc.sinkhorn_batched_damped(K, A, B, iters, eta, damping == api.FSK_DAMP_GEOMETRIC, ones, ones)
+        what = (seed, case, n, m, np.dtype(dtype).name, iters, damping, eta)
         assert relerr(U.cpu().numpy(), Uo) <= tol and relerr(V.cpu().numpy(), Vo) <= tol, what
 
 
