@@ -131,3 +131,27 @@ def test_multitarget_calls_refuse_what_they_do_not_carry(api):
     with_tol = api.fsk_workspace_bytes(opts, api.FSK_MODE_BATCHED)
     opts.tol = 0.0
     assert with_tol >= api.fsk_workspace_bytes(opts, api.FSK_MODE_BATCHED) + 64 * 8 * 4
+
+
+def test_last_error_is_per_thread(api):
+    """fsk_last_error() reports the calling thread's last failure, not another thread's."""
+    import threading
+    import torch
+    L = api.lib()
+    ok = ctypes.c_void_p(4096)
+    seen = {}
+    gate = threading.Barrier(2)
+
+    def worker(name, n):
+        opts = api.make_opts(64, torch.float32, max_iters=1)
+        opts.n = n                                            # 0 / negative: refused with the value in the text
+        st = L.fsk_sinkhorn_dense(ctypes.byref(opts), ok, ctypes.c_int64(64), ok, ok, ok, ok, ok,
+                                  ctypes.c_size_t(1 << 30), None, None, None)
+        gate.wait()                                           # both calls have failed before either reads
+        seen[name] = (st, bytes(L.fsk_last_error()))
+
+    ts = [threading.Thread(target=worker, args=("first", 0)), threading.Thread(target=worker, args=("second", -7))]
+    [t.start() for t in ts]; [t.join() for t in ts]
+    assert seen["first"][0] == api.FSK_EINVAL and seen["second"][0] == api.FSK_EINVAL
+    assert seen["first"][1] != seen["second"][1]
+    assert b"-7" in seen["second"][1] and b"-7" not in seen["first"][1]
