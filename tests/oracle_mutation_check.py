@@ -1,0 +1,108 @@
+"""Mutation check of the CPU oracle against its pins (CPU only; not collected by pytest).
+
+    python tests/oracle_mutation_check.py [every_kth]
+
+Plants one small mistake at a time in a copy of oracle/sinkhorn_oracle.c (a flipped sign, a
+swapped index, a transposed subscript, a changed constant or comparison, exp for exp2, ...),
+builds the copy into a library of its own and runs tests/test_oracle_pins.py against it.  A
+mutant that passes every pin is printed: either it changes nothing a caller can see (a loop
+bound one past the end, a dead initial value, the thread-count setter) or a pin is missing.
+The oracle in the tree is never touched."""
+import concurrent.futures as cf
+import os
+import re
+import subprocess
+import sys
+import tempfile
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+SRC = os.path.join(ROOT, "oracle", "sinkhorn_oracle.c")
+GCC = ["gcc", "-O2", "-std=c99", "-fopenmp", "-fno-fast-math", "-ffp-contract=off", "-shared", "-fPIC"]
+
+RUNNER = """
+import sys
+sys.path.insert(0, {root!r}); sys.path.insert(0, {tests!r})
+import oracle
+oracle._LIB = sys.argv[1]
+oracle.build = lambda force=False: sys.argv[1]
+import pytest
+sys.exit(pytest.main(["-x", "-q", "-p", "no:cacheprovider", {pins!r}]))
+"""
+
+OPERATORS = [
+    (r"\+=", "-="), (r"-=", "+="), (r"\*=", "/="),
+    (r" \+ ", " - "), (r" - ", " + "), (r" \* ", " + "), (r" / ", " * "),
+    (r"\[i\]", "[j]"), (r"\[j\]", "[i]"), (r"\[k\]", "[0]"),
+    (r"i \* ld \+ j", "j * ld + i"), (r"i \* m \+ k", "k * m + i"),
+    (r" < ", " <= "), (r" > ", " < "), (r" >= ", " > "),
+    (r"\b1\.0\b", "0.5"), (r"\b0\.0\b", "1.0"), (r"\b2\.0\b", "1.0"),
+    (r"\bexp\(", "exp2("), (r"\blog\(", "log2("), (r"\bfabs\(", "("), (r"\bsqrt\(", "("),
+    (r"eta", "(1.0 - eta)"), (r"\+ 1\b", "+ 0"), (r"- 1\b", "- 0"),
+]
+
+
+def mutants(lines):
+    out, in_comment = [], False
+    for ln, text in enumerate(lines):
+        s = text.strip()
+        if in_comment:
+            in_comment = "*/" not in s
+            continue
+        if s.startswith("/*"):
+            in_comment = "*/" not in s
+            continue
+        if not s or s[0] in "#*" or s.startswith("//"):
+            continue
+        code = text.split("//")[0]
+        for pat, rep in OPERATORS:
+            for hit in re.finditer(pat, code):
+                new = text[:hit.start()] + rep + text[hit.end():]
+                if new != text:
+                    out.append((ln, new))
+    return out
+
+
+def main():
+    lines = open(SRC).read().split("\n")
+    todo = mutants(lines)
+    if len(sys.argv) > 1:
+        todo = todo[::int(sys.argv[1])]
+    print(len(todo), "mutants", flush=True)
+    work = tempfile.mkdtemp(prefix="oracle_mut_")
+    runner = os.path.join(work, "run_pins.py")
+    with open(runner, "w") as fh:
+        fh.write(RUNNER.format(root=ROOT, tests=os.path.join(ROOT, "tests"),
+                               pins=os.path.join(ROOT, "tests", "test_oracle_pins.py")))
+
+    def run(job):
+        idx, (ln, new) = job
+        src, lib = os.path.join(work, f"m{idx}.c"), os.path.join(work, f"m{idx}.so")
+        body = list(lines)
+        body[ln] = new
+        with open(src, "w") as fh:
+            fh.write("\n".join(body))
+        verdict = "does not compile"
+        if subprocess.run(GCC + [src, "-o", lib, "-lm"], capture_output=True).returncode == 0:
+            try:
+                rc = subprocess.run([sys.executable, runner, lib], capture_output=True, timeout=600,
+                                    env=dict(os.environ, OMP_NUM_THREADS="2")).returncode
+                verdict = "survived" if rc == 0 else "killed"
+            except subprocess.TimeoutExpired:
+                verdict = "killed"
+            os.remove(lib)
+        os.remove(src)
+        return ln, new, verdict
+
+    survivors = 0
+    with cf.ThreadPoolExecutor(4) as pool:
+        for done, (ln, new, verdict) in enumerate(pool.map(run, list(enumerate(todo)))):
+            if verdict == "survived":
+                survivors += 1
+                print(f"SURVIVED line {ln + 1}: {new.strip()}", flush=True)
+            if done % 100 == 0:
+                print("done", done, flush=True)
+    print("survivors:", survivors, "of", len(todo))
+
+
+if __name__ == "__main__":
+    main()

@@ -60,6 +60,11 @@ def test_gibbs_f32_variant_is_the_rounded_f64_kernel(orc):
         assert np.array_equal(K32, K64.astype(np.float32))
     assert orc.max_sqeuclid(x, y) == pytest.approx(C.max(), rel=1e-15)
     assert orc.max_sqeuclid(x[:5], y) == pytest.approx(C[:5].max(), rel=1e-15)   # rectangular
+    # d > 1 on clouds of different extent (a wrong stride in either operand shows), maximum below 1
+    rng = np.random.default_rng(17)
+    xs = 0.1 * rng.uniform(size=(23, 4)) * np.array([1.0, 5.0, 0.2, 3.0]); ys = 0.1 * rng.uniform(size=(31, 4))
+    want = ((xs[:, None, :] - ys[None, :, :]) ** 2).sum(-1).max()
+    assert want < 1.0 and orc.max_sqeuclid(xs, ys) == pytest.approx(want, rel=1e-14)
 
 
 # ------------------------------------------- single steps vs library routines
@@ -76,6 +81,11 @@ def test_products_against_numpy_matmul(orc):
     assert np.allclose(orc.row_products(K, v, 10, 31), (K @ v)[10:31], rtol=1e-13)
     assert np.allclose(orc.col_products(K, u, 0, 53, 7, 20), (K.T @ u)[7:20], rtol=1e-13)
     assert np.allclose(orc.col_products(K, u, 10, 31), K[10:31].T @ u[10:31], rtol=1e-13)
+    # more columns than one of the loop's column chunks, ragged last chunk, rectangular slab
+    Kb = rng.uniform(0.1, 1.0, (90, 700)); ub = rng.uniform(0.5, 2.0, 90); vb = rng.uniform(0.5, 2.0, 700)
+    assert np.allclose(orc.col_products(Kb, ub), Kb.T @ ub, rtol=1e-13)
+    assert np.allclose(orc.col_products(Kb, ub, 5, 80, 100, 650), (Kb[5:80].T @ ub[5:80])[100:650], rtol=1e-13)
+    assert np.allclose(orc.row_products(Kb, vb), Kb @ vb, rtol=1e-13)
 
 
 def test_first_iteration_against_numpy(orc):
@@ -640,6 +650,7 @@ def test_gibbs_lambda_and_the_role_of_l(orc):
     rng = np.random.default_rng(5)
     l = rng.uniform(-0.3, 0.3, 9)
     assert np.allclose(orc.gibbs_lambda(C, 0.7, l, eps), np.exp(-(0.7 * C - l[None, :]) / eps), rtol=1e-14)
+    assert np.allclose(orc.gibbs_lambda(C, 0.7, None, eps), np.exp(-0.7 * C / eps), rtol=1e-14)   # no l: l = 0
     K32 = orc.gibbs_lambda(C, 0.7, l, eps, True)
     assert np.array_equal(K32, K32.astype(np.float32).astype(np.float64))
     lam, cost, loss, steps, u, v, K = orc.radius_search(C, l, a, b, eps, 0.0, 0.0, 0.0, 1, 0.0, 5)
@@ -676,6 +687,12 @@ def test_radius_search_against_scipy_root_of_the_log_domain_cost(orc):
     root = scipy.optimize.brentq(lambda t: cost_at(t) - delta, 0.0, 4.0, xtol=1e-12)
     lam, cost, loss, steps, u, v, K = orc.radius_search(C, l, a, b, eps, delta, 0.0, 4.0, 45, 0.0, 400)
     assert lam == pytest.approx(root, abs=1e-9) and cost == pytest.approx(delta, rel=1e-9)
+    # every solve is Algorithm 1 from u = v = 1 on the kernel of its lambda: the scalings handed back
+    # are those of the plain iteration on the K handed back (the gauge, not only the plan)
+    lam, cost, loss, steps, u, v, K = orc.radius_search(C, l, a, b, eps, delta, 0.0, 4.0, 6, 0.0, 25)
+    assert steps == 6 and np.array_equal(K, orc.gibbs_lambda(C, lam, l, eps))
+    up, vp = orc.sinkhorn_dense(K, a, b, 25)
+    assert np.array_equal(u, up) and np.array_equal(v, vp)
 
 
 # ---------------------------------------- 2D block grid (HPC baseline appendix) ---
@@ -734,6 +751,17 @@ def test_dp_normals_are_standard_normal_and_counter_based(orc):
     # counter-based: any sub-range can be drawn on its own, in any order
     assert np.array_equal(orc.dp_normals(11, 4, 777, 100), z[777:877])
     assert np.array_equal(orc.dp_normals(11, 4, 2 ** 34 + 3, 5), orc.dp_normals(11, 4, 2 ** 34, 8)[3:])
+    # the map from element to generator call, written out: elements 4q .. 4q+3 come from call q with
+    # counter (q, release) and key seed; Box-Muller on (x0, x1) and on (x2, x3), uniforms (x + 1/2) 2^-32
+    seed, release = (5 << 32) + 11, (3 << 32) + 4
+    z = orc.dp_normals(seed, release, 0, 12)
+    for q in range(3):
+        w = orc.philox4x32_10([q, 0, release & 0xFFFFFFFF, release >> 32], [seed & 0xFFFFFFFF, seed >> 32])
+        for pair in range(2):
+            u1 = (float(w[2 * pair]) + 0.5) / 2.0 ** 32; u2 = (float(w[2 * pair + 1]) + 0.5) / 2.0 ** 32
+            r = np.sqrt(-2.0 * np.log(u1))
+            assert z[4 * q + 2 * pair] == pytest.approx(r * np.cos(2 * np.pi * u2), rel=1e-13, abs=1e-14)
+            assert z[4 * q + 2 * pair + 1] == pytest.approx(r * np.sin(2 * np.pi * u2), rel=1e-13, abs=1e-14)
 
 
 def test_dp_release_clip_and_noise(orc):
@@ -756,6 +784,7 @@ def test_dp_release_clip_and_noise(orc):
     # one target: the row clip is a clamp of the log-scaling to [-S, S]
     x1 = np.exp(rng.normal(scale=3.0, size=40))
     assert np.allclose(np.log(orc.dp_release(x1, 2.0, 0.0, 1, 0))[:, 0], np.clip(np.log(x1), -2.0, 2.0), rtol=1e-12)
+    assert np.allclose(np.log(orc.dp_release(x1, 0.25, 0.0, 1, 0))[:, 0], np.clip(np.log(x1), -0.25, 0.25), rtol=1e-12)
     # noise only: the log-scalings move by sigma times the release's normal numbers, element i*m + k
     sigma = 0.3
     Ln = np.log(orc.dp_release(X, np.inf, sigma, 21, 9))
@@ -799,7 +828,7 @@ def test_rdp_accountant_closed_form(orc):
     grid = np.concatenate([1 + np.arange(1, 100) / 10.0, np.arange(12, 64)])
     eps_g, p_g = orc.rdp_epsilon(S, sigma, T, delta, grid)
     assert best <= eps_g <= 1.01 * best and abs(p_g - p_star) <= 0.1
-    assert orc.rdp_epsilon(S, sigma, T, delta, [0.5, 1.0, 2.0])[1] == 2.0       # orders <= 1 are not RDP orders
+    assert orc.rdp_epsilon(S, sigma, T, delta, [0.5, 0.9, 1.0, 2.0])[1] == 2.0  # orders <= 1 are not RDP orders
     # additive composition: twice the releases, twice the Renyi term
     e1 = orc.rdp_epsilon(S, sigma, T, delta, [3.0])[0] - np.log(1 / delta) / 2
     e2 = orc.rdp_epsilon(S, sigma, 2 * T, delta, [3.0])[0] - np.log(1 / delta) / 2
