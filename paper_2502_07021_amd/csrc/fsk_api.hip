@@ -121,8 +121,9 @@ const char* fsk_last_error(void) { return g_err; }
 
 static size_t plan_ws_bytes(const fsk_opts* opts);
 
-// Multitarget workspace: [partial products | K^T] and, in tolerance mode, a copy of U and the
-// error kernels' scratch behind them.
+// Multitarget workspace: [partial products | K^T]; behind them an n x m scratch matrix (tolerance
+// mode: the copy of U a poll compares against; damped run: where every half-step lands before
+// it is folded in) and, in tolerance mode, the error kernels' scratch.
 static size_t batched_base_bytes(const fsk_opts* o) {
   return align_up(o->dtype == FSK_F64 ? batched_f64_workspace_bytes(o->n, o->m)
                                       : batched_workspace_bytes(o->n, o->m), 256);
