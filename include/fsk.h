@@ -156,10 +156,15 @@ int fsk_sinkhorn_dense(const fsk_opts* opts, const void* K, int64_t ldK, const v
 void fsk_set_barrier_poll_limit(uint32_t polls);
 
 /* Row and column marginals of P = diag(u) K diag(v) (device outputs of n entries each; either
- * may be NULL), and optionally ||P1 - a||_1 (err_l1, host; non-NULL makes the call synchronise). */
+ * may be NULL), and optionally the marginal error on a in two norms (host outputs, either may
+ * be NULL; a non-NULL one makes the call synchronise): err_l1 = ||P1 - a||_1, the quantity the
+ * stop rule of this library tests, and err_l2 = ||P1 - a||_2, the one the paper's convergence
+ * plots and its privacy appendix report (Sec. 5.4, "Marginal error metric").  Both come from one
+ * row pass; the sums are taken in fp64.  err_l2 <= err_l1, so a run stopped at err_l1 < tol also
+ * meets the paper's criterion at the same threshold. */
 int fsk_marginals(const fsk_opts* opts, const void* K, int64_t ldK, const void* a, const void* u,
                   const void* v, void* row_marginal, void* col_marginal, void* workspace,
-                  size_t ws_bytes, double* err_l1, void* stream);
+                  size_t ws_bytes, double* err_l1, double* err_l2, void* stream);
 
 /* ---- objective of Eq. 1 at P = diag(u) K diag(v), without materialising P -----------------
  * One pass over K and the cost matrix C (device, n x n, same dtype, leading dimension ldC).

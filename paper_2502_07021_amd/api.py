@@ -259,12 +259,17 @@ def fsk_sinkhorn_grid(opts, K, a, b, u, v, p_r, p_c, workspace, stream=None) -> 
 
 
 def fsk_marginals(opts, K, a, u, v, row_marginal, col_marginal, workspace, want_err=False,
-                  stream=None):
+                  stream=None, want_l2=False):
+    """Returns None, ||P1 - a||_1 (want_err), or the pair (l1, l2) (want_l2)."""
     wp, wn = _ws(workspace)
     err = ctypes.c_double(float("nan"))
+    err2 = ctypes.c_double(float("nan"))
     _check(lib().fsk_marginals(ctypes.byref(opts), _p(K), _ld(K), _vec(a), _vec(u), _vec(v),
                                _vec(row_marginal), _vec(col_marginal), wp, wn,
-                               ctypes.byref(err) if want_err else None, _stream(stream)))
+                               ctypes.byref(err) if (want_err or want_l2) else None,
+                               ctypes.byref(err2) if want_l2 else None, _stream(stream)))
+    if want_l2:
+        return float(err.value), float(err2.value)
     return float(err.value) if want_err else None
 
 

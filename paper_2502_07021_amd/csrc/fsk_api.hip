@@ -249,15 +249,22 @@ static int dense_iteration(const fsk_opts* o, const DenseWs& w, const char* K, i
 }
 
 // err = ||diag(u) K v - a||_1, synchronising.
+// ||P1 - a||_1 into *err (and, if asked for, ||P1 - a||_2 into *err_l2) from one row pass.
 static int dense_error(const fsk_opts* o, const DenseWs& w, const void* K, int64_t ld,
                        const void* a, const void* u, const void* v, char* ws, double* err,
-                       hipStream_t st) {
+                       hipStream_t st, double* err_l2 = nullptr) {
   void* errvec = ws + w.vec_off;
   double* scalar = (double*)(ws + w.scalar_off);
   FSK_TRY(launch_rowpass(o->dtype, K, ld, o->n, o->n, v, a, u, errvec, kEpiAbsErr, 0.0, st));
   FSK_TRY(launch_sum_to_double(o->dtype, errvec, o->n, scalar, st));
-  FSK_HIP(hipMemcpyAsync(err, scalar, sizeof(double), hipMemcpyDeviceToHost, st));
+  if (err) FSK_HIP(hipMemcpyAsync(err, scalar, sizeof(double), hipMemcpyDeviceToHost, st));
+  if (err_l2) {
+    FSK_HIP(hipStreamSynchronize(st));  // the scalar is reused
+    FSK_TRY(launch_sum_to_double(o->dtype, errvec, o->n, scalar, st, true));
+    FSK_HIP(hipMemcpyAsync(err_l2, scalar, sizeof(double), hipMemcpyDeviceToHost, st));
+  }
   FSK_HIP(hipStreamSynchronize(st));
+  if (err_l2) *err_l2 = sqrt(*err_l2);
   return FSK_OK;
 }
 
@@ -437,7 +444,7 @@ int fsk_dense_profile(const fsk_opts* opts, const void* K, int64_t ldK, const vo
 
 int fsk_marginals(const fsk_opts* opts, const void* K, int64_t ldK, const void* a, const void* u,
                   const void* v, void* row_marginal, void* col_marginal, void* workspace,
-                  size_t ws_bytes, double* err_l1, void* stream) {
+                  size_t ws_bytes, double* err_l1, double* err_l2, void* stream) {
   clear_error();
   FSK_TRY(check_common(opts));
   FSK_TRY(check_matrix("K", K, ldK, opts->n, opts->dtype));
@@ -457,9 +464,9 @@ int fsk_marginals(const fsk_opts* opts, const void* K, int64_t ldK, const void* 
     FSK_TRY(launch_colreduce(dt, ws + w.partial_off, w.ld_ws, col_strips(n), 0, n, nullptr, v,
                              col_marginal, kEpiMarginal, 0.0, st));
   }
-  if (err_l1) {
+  if (err_l1 || err_l2) {
     FSK_TRY(check_vec("a", a, false));
-    FSK_TRY(dense_error(opts, w, K, ldK, a, u, v, ws, err_l1, st));
+    FSK_TRY(dense_error(opts, w, K, ldK, a, u, v, ws, err_l1, st, err_l2));
   }
   return FSK_OK;
 }

@@ -706,11 +706,15 @@ int launch_assemble_view(int dtype, void* dst, const void* remote, const void* o
 }
 
 // ================================================================= fp64 sum of a vector
+// *out = sum_i x_i, or sum_i x_i^2 with `square`, accumulated in fp64 in a fixed order.
 template <typename T>
 __global__ __launch_bounds__(1024) void sum_to_double_kernel(const T* __restrict__ x, int n,
-                                                             double* out) {
+                                                             double* out, int square) {
   double s = 0.0;
-  for (int i = threadIdx.x; i < n; i += 1024) s += (double)x[i];
+  for (int i = threadIdx.x; i < n; i += 1024) {
+    const double t = (double)x[i];
+    s += square ? t * t : t;
+  }
   s = wave_sum(s);
   __shared__ double sm[16];
   if ((threadIdx.x & 63) == 0) sm[threadIdx.x >> 6] = s;
@@ -722,13 +726,13 @@ __global__ __launch_bounds__(1024) void sum_to_double_kernel(const T* __restrict
   }
 }
 
-int launch_sum_to_double(int dtype, const void* x, int n, double* out, hipStream_t stream) {
+int launch_sum_to_double(int dtype, const void* x, int n, double* out, hipStream_t stream, bool square) {
   if (dtype == FSK_F64)
     hipLaunchKernelGGL((sum_to_double_kernel<double>), dim3(1), dim3(1024), 0, stream,
-                       (const double*)x, n, out);
+                       (const double*)x, n, out, square ? 1 : 0);
   else
     hipLaunchKernelGGL((sum_to_double_kernel<float>), dim3(1), dim3(1024), 0, stream,
-                       (const float*)x, n, out);
+                       (const float*)x, n, out, square ? 1 : 0);
   FSK_LAUNCH_CHECK("sum_to_double_kernel");
   return FSK_OK;
 }

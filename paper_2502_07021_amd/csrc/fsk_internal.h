@@ -99,7 +99,8 @@ int launch_assemble_view(int dtype, void* dst, const void* remote, const void* o
                          int hi, hipStream_t stream);
 
 // out (one double) = sum of x[0..n) accumulated in fp64 in a fixed order.
-int launch_sum_to_double(int dtype, const void* x, int n, double* out, hipStream_t stream);
+int launch_sum_to_double(int dtype, const void* x, int n, double* out, hipStream_t stream,
+                         bool square = false);
 
 // ------------------------------------------------------------------ setup kernels
 int launch_gibbs_from_cost(int dtype, const void* C, int64_t ldC, int n, double eps, void* K,

@@ -159,6 +159,18 @@ def test_marginals_entry_point(orc):
     assert relerr(rm.cpu().numpy(), orc.row_marginal(K, u, v)) <= 1e-5
     assert relerr(cm.cpu().numpy(), orc.col_marginal(K, u, v)) <= 1e-5
     assert err == pytest.approx(orc.marginal_error(K, w.a, u, v)[0], rel=1e-3, abs=1e-7)
+    # the paper's own metric, ||P1 - a||_2, from the same row pass (no marginals asked for)
+    e1, e2 = api.fsk_marginals(opts, dev(K), dev(w.a), dev(u), dev(v), None, None, ws, want_l2=True)
+    o1, o2 = orc.marginal_error(K, w.a, u, v)
+    assert e1 == err and e2 == pytest.approx(o2, rel=1e-3, abs=1e-9) and e2 <= e1
+    # fp64 on a state that is not converged: both norms to rounding
+    K64 = K.astype(np.float64); u64 = np.linspace(0.5, 2.0, 1100) / 1100; v64 = np.linspace(1.5, 0.3, 1100) / 1100
+    opts64 = api.make_opts(1100, torch.float64)
+    a64 = w.a.astype(np.float64)
+    e1, e2 = api.fsk_marginals(opts64, dev(K64), dev(a64), dev(u64), dev(v64), None, None,
+                               api.alloc_workspace(opts64), want_l2=True)
+    o1, o2 = orc.marginal_error(K64, a64, u64, v64)
+    assert e1 == pytest.approx(o1, rel=1e-12) and e2 == pytest.approx(o2, rel=1e-12)
 
 
 @pytest.mark.parametrize("dtype", [np.float32, np.float64])
