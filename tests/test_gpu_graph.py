@@ -56,12 +56,15 @@ def test_dense_call_in_a_graph(n, td, flow, c):
     _replay_matches_eager(lambda: api.fsk_sinkhorn_dense(opts, K, a, b, u, v, ws), [u, v], reset)
 
 
-@pytest.mark.parametrize("td,m", [(torch.float32, 64), (torch.float32, 150), (torch.float64, 64)])
-def test_batched_call_in_a_graph(td, m):
+@pytest.mark.parametrize("td,m,damping", [(torch.float32, 64, api.FSK_DAMP_NONE), (torch.float32, 150, api.FSK_DAMP_NONE),
+                                          (torch.float64, 64, api.FSK_DAMP_NONE),
+                                          (torch.float32, 70, api.FSK_DAMP_GEOMETRIC),
+                                          (torch.float64, 33, api.FSK_DAMP_ARITHMETIC)])
+def test_batched_call_in_a_graph(td, m, damping):
     n = 1030
     nd = np.float64 if td == torch.float64 else np.float32
     w = workloads.make(5, n=n, m=m, seed=77)
-    opts = api.make_opts(n, td, m=m, max_iters=10)
+    opts = api.make_opts(n, td, m=m, max_iters=10, damping=damping, eta=0.6)
     pack = 16 // np.dtype(nd).itemsize
     ld = (n + pack - 1) // pack * pack
     K = torch.empty(n, ld, dtype=td, device="cuda")[:, :n]
