@@ -286,8 +286,8 @@ def bench_batched(args):
                                f"Dirichlet(1) histogram pairs, x,y~U[0,1]^2, eps={w.eps}", "n": n, "m": m},
         "roofline": {"bound": "mfma", "achieved": achieved, "peak": peak,
                      "unit": "TFLOP/s", "frac": achieved / peak,
-                     "traffic": traffic_from_profile("batched_mfma_cfg5.txt")
-                     if (n == 16384 and m == 64 and not f64) else None,
+                     "traffic": traffic_from_profile("batched_mfma_f64_cfg5.txt" if f64 else "batched_mfma_cfg5.txt")
+                     if (n == 16384 and m == 64) else None,
                      "kernel": ("batched_prod_f64_kernel" if f64 else "batched_prod_wide_kernel")
                                + " (both products)",
                      "kernel_ms": launch_ms, "launches_per_step": 2,
