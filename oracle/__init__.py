@@ -174,15 +174,17 @@ def sinkhorn_dense(K, a, b, iters: int, u0=None, v0=None):
     return u, v
 
 
-def sinkhorn_dense_tol(K, a, b, max_iters: int, tol: float, check_every: int = 1, u0=None, v0=None):
-    """Tolerance mode; returns (u, v, iterations done, last evaluated L1 error)."""
+def sinkhorn_dense_tol(K, a, b, max_iters: int, tol: float, check_every: int = 1, u0=None, v0=None,
+                       l2: bool = False):
+    """Tolerance mode; returns (u, v, iterations done, last evaluated error): the 1-norm of
+    P1 - a, or with l2 its 2-norm (the paper's own metric)."""
     kp, kf, n, ld = _square(K)
     a, b = _f64(a), _f64(b)
     u, v = _init(K.shape[0], u0), _init(K.shape[0], v0)
     err = _DBL(0.0)
     done = _load().orc_sinkhorn_dense_tol(kp, kf, n, ld, _ptr(a), _ptr(b), _ptr(u), _ptr(v),
                                           _INT(max_iters), _DBL(tol), _INT(check_every),
-                                          ctypes.byref(err))
+                                          ctypes.byref(err), _INT(1 if l2 else 0))
     return u, v, int(done), float(err.value)
 
 
@@ -265,8 +267,9 @@ def sinkhorn_batched_damped(K, A, B, iters: int, eta: float, geometric: bool, U0
     return U, V
 
 
-def sinkhorn_batched_tol(K, A, B, max_iters: int, tol: float, check_every: int = 1, U0=None, V0=None):
-    """Multitarget form until every column's row-marginal L1 error is below tol at a poll.
+def sinkhorn_batched_tol(K, A, B, max_iters: int, tol: float, check_every: int = 1, U0=None, V0=None,
+                         l2: bool = False):
+    """Multitarget form until every column's row-marginal error (1-norm; 2-norm with l2) is below tol at a poll.
     Returns (U, V, iterations done, max over columns of the error at the last poll)."""
     kp, kf, n, ld = _square(K)
     A, B = _f64(A), _f64(B)
@@ -274,7 +277,8 @@ def sinkhorn_batched_tol(K, A, B, max_iters: int, tol: float, check_every: int =
     U, V = _init(K.shape[0], U0, m), _init(K.shape[0], V0, m)
     err = ctypes.c_double(float("inf"))
     done = _load().orc_sinkhorn_batched_tol(kp, kf, n, ld, _INT(m), _ptr(A), _ptr(B), _ptr(U), _ptr(V),
-                                            _INT(max_iters), _DBL(tol), _INT(check_every), ctypes.byref(err))
+                                            _INT(max_iters), _DBL(tol), _INT(check_every), ctypes.byref(err),
+                                            _INT(1 if l2 else 0))
     assert done >= 0
     return U, V, int(done), float(err.value)
 
@@ -440,7 +444,7 @@ def log_row_marginal_points(x, f, y, g, eps: float, rows=None) -> np.ndarray:
 
 
 def sinkhorn_log_points(x, y, eps: float, a, b, max_iters: int, tol: float = 0.0,
-                        check_every: int = 1, f0=None, g0=None):
+                        check_every: int = 1, f0=None, g0=None, l2: bool = False):
     """Log-domain iteration with the cost evaluated on the fly; returns (f, g, iters, err)."""
     x, y, a, b = _f64(x), _f64(y), _f64(a), _f64(b)
     n = x.shape[0]
@@ -449,7 +453,8 @@ def sinkhorn_log_points(x, y, eps: float, a, b, max_iters: int, tol: float = 0.0
     err = _DBL(0.0)
     done = _load().orc_sinkhorn_log_points(_ptr(x), _ptr(y), _I64(n), _INT(x.shape[1]), _DBL(eps),
                                            _ptr(a), _ptr(b), _ptr(f), _ptr(g), _INT(max_iters),
-                                           _DBL(tol), _INT(check_every), ctypes.byref(err))
+                                           _DBL(tol), _INT(check_every), ctypes.byref(err),
+                                           _INT(1 if l2 else 0))
     return f, g, int(done), float(err.value)
 
 

@@ -273,11 +273,13 @@ void orc_radius_search(const double* c, const double* l, const double* a, const 
 }
 
 /* Tolerance mode: iterate; after every `check_every`-th iteration (and after
- * the last one) evaluate err = ||P1 - a||_1 with the scalings just produced;
- * stop at the first such check with err < tol.  Returns iterations done. */
+ * the last one) evaluate err = ||P1 - a|| with the scalings just produced;
+ * stop at the first such check with err < tol.  l2 == 0: the 1-norm; l2 != 0: the 2-norm,
+ * the metric of the paper's convergence plots (Sec. 5.4, err_a) and of its privacy appendix
+ * ("Marginal error metric").  Returns iterations done. */
 int orc_sinkhorn_dense_tol(const void* K, int k_is_f32, int64_t n, int64_t ld, const double* a,
                            const double* b, double* u, double* v, int max_iters, double tol,
-                           int check_every, double* err_out) {
+                           int check_every, double* err_out, int l2) {
   int done = 0;
   double e1 = INFINITY, e2 = INFINITY;
   while (done < max_iters) {
@@ -285,10 +287,10 @@ int orc_sinkhorn_dense_tol(const void* K, int k_is_f32, int64_t n, int64_t ld, c
     ++done;
     if (done % check_every == 0 || done == max_iters) {
       orc_marginal_error(K, k_is_f32, n, ld, a, u, v, &e1, &e2);
-      if (e1 < tol) break;
+      if ((l2 ? e2 : e1) < tol) break;
     }
   }
-  if (err_out) *err_out = e1;
+  if (err_out) *err_out = l2 ? e2 : e1;
   return done;
 }
 
@@ -514,11 +516,12 @@ int orc_sinkhorn_batched_damped(const void* K, int k_is_f32, int64_t n, int64_t 
 
 /* Multitarget form with the stop rule of orc_sinkhorn_dense_tol applied to all targets at once
  * (the multitarget experiment of Sec. 5.3.2 iterates until every target meets the threshold):
- * err = max over columns k of ||P_k 1 - a_k||_1, P_k = diag(u_k) K diag(v_k), evaluated after a
- * V-update every check_every iterations and after the last one.  Returns iterations done. */
+ * err = max over columns k of ||P_k 1 - a_k|| (1-norm, or 2-norm with l2 != 0), P_k = diag(u_k) K
+ * diag(v_k), evaluated after a V-update every check_every iterations and after the last one.
+ * Returns iterations done. */
 int orc_sinkhorn_batched_tol(const void* K, int k_is_f32, int64_t n, int64_t ld, int m,
                              const double* A, const double* B, double* U, double* V, int max_iters,
-                             double tol, int check_every, double* err_out) {
+                             double tol, int check_every, double* err_out, int l2) {
   double* Q = (double*)malloc(sizeof(double) * (size_t)n * (size_t)m);
   double* colerr = (double*)malloc(sizeof(double) * (size_t)m);
   if (!Q || !colerr) return -1;
@@ -539,7 +542,11 @@ int orc_sinkhorn_batched_tol(const void* K, int k_is_f32, int64_t n, int64_t ld,
       err = 0.0;
       for (int k = 0; k < m; ++k) {
         colerr[k] = 0.0;
-        for (int64_t i = 0; i < n; ++i) colerr[k] += fabs(U[i * m + k] * Q[i * m + k] - A[i * m + k]);
+        for (int64_t i = 0; i < n; ++i) {
+          const double dev = U[i * m + k] * Q[i * m + k] - A[i * m + k];
+          colerr[k] += l2 ? dev * dev : fabs(dev);
+        }
+        if (l2) colerr[k] = sqrt(colerr[k]);
         if (colerr[k] > err) err = colerr[k];
       }
       if (err < tol) break;
@@ -719,10 +726,11 @@ void orc_log_row_marginal_points(const double* x, const double* f, const double*
 /* Log-domain Sinkhorn on point clouds, cost evaluated on the fly.  f, g in/out
  * (0 for a cold start, i.e. u = v = 1).  tol <= 0: exactly max_iters
  * iterations.  tol > 0: same polling rule as orc_sinkhorn_dense_tol, with
- * err = ||P1 - a||_1 evaluated after the g-update.  Returns iterations done. */
+ * err = ||P1 - a||_1 (||P1 - a||_2 with l2 != 0) evaluated after the g-update.  Returns
+ * iterations done. */
 int orc_sinkhorn_log_points(const double* x, const double* y, int64_t n, int d, double eps,
                             const double* a, const double* b, double* f, double* g, int max_iters,
-                            double tol, int check_every, double* err_out) {
+                            double tol, int check_every, double* err_out, int l2) {
   double* t1 = (double*)malloc(sizeof(double) * (size_t)n);
   int done = 0;
   double err = INFINITY;
@@ -735,7 +743,8 @@ int orc_sinkhorn_log_points(const double* x, const double* y, int64_t n, int d, 
     if (tol > 0.0 && (done % check_every == 0 || done == max_iters)) {
       orc_log_row_marginal_points(x, f, y, g, n, d, eps, NULL, n, t1);
       err = 0.0;
-      for (int64_t i = 0; i < n; ++i) err += fabs(t1[i] - a[i]);
+      for (int64_t i = 0; i < n; ++i) err += l2 ? (t1[i] - a[i]) * (t1[i] - a[i]) : fabs(t1[i] - a[i]);
+      if (l2) err = sqrt(err);
       if (err < tol) break;
     }
   }

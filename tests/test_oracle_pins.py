@@ -404,6 +404,37 @@ def test_tolerance_mode_polling(orc):
     assert done == 10 and err > 0
 
 
+def test_stop_rule_on_the_two_norm(orc):
+    """The paper's own metric, err_a = ||P1 - a||_2 (Sec. 5.4): the stop iteration is the first
+    poll at which NumPy's evaluation of that norm on the plain iteration's state is below the
+    threshold; it comes no later than the 1-norm's, and the three forms agree on it."""
+    x, y, a, b, C, K = problem(40, 23, eps=0.3)
+    tol, ce = 1e-7, 3
+    u, v, done, err = orc.sinkhorn_dense_tol(K, a, b, 500, tol, check_every=ce, l2=True)
+    norms = []
+    for t in range(ce, done + 1, ce):
+        ut, vt = orc.sinkhorn_dense(K, a, b, t)
+        norms.append(np.linalg.norm((ut[:, None] * K * vt[None, :]).sum(1) - a))
+    assert done % ce == 0 and norms[-1] < tol and all(e >= tol for e in norms[:-1])
+    assert err == pytest.approx(norms[-1], rel=1e-6)
+    u1, v1, done1, err1 = orc.sinkhorn_dense_tol(K, a, b, 500, tol, check_every=ce)
+    assert done <= done1 and err1 < tol
+    ut, vt = orc.sinkhorn_dense(K, a, b, done)
+    assert np.array_equal(u, ut) and np.array_equal(v, vt)
+    # log domain: same state, same count, same error
+    f, g, done_l, err_l = orc.sinkhorn_log_points(x, y, 0.3, a, b, 500, tol, ce, l2=True)
+    assert done_l == done and err_l == pytest.approx(err, rel=1e-4)
+    # multitarget: the slowest column decides, each column in its own 2-norm
+    rng = np.random.default_rng(3)
+    A = rng.uniform(0.5, 1.5, (40, 5)) ** 3; A /= A.sum(0)
+    B = rng.uniform(0.5, 1.5, (40, 5)) ** 3; B /= B.sum(0)
+    U, V, done_b, err_b = orc.sinkhorn_batched_tol(K, A, B, 500, tol, ce, l2=True)
+    singles = [orc.sinkhorn_dense_tol(K, A[:, k], B[:, k], 500, tol, check_every=ce, l2=True) for k in range(5)]
+    assert done_b == max(s[2] for s in singles)
+    col = [np.linalg.norm((U[:, k, None] * K * V[None, :, k]).sum(1) - A[:, k]) for k in range(5)]
+    assert err_b == pytest.approx(max(col), rel=1e-5) and err_b < tol
+
+
 # ------------------------------------------------------------ log domain ---
 
 def test_log_domain_equals_dense(orc):
