@@ -94,6 +94,12 @@ typedef enum {
                               runs the two-pass kernels instead                                */
 } fsk_damping;
 
+typedef enum {
+  FSK_NORM_L1 = 0,  /* ||P1 - a||_1 (the stop rule as configuration 4 of the benchmark states it) */
+  FSK_NORM_L2 = 1   /* ||P1 - a||_2, the paper's own metric (Sec. 5.4, err_a; privacy appendix,
+                       "Marginal error metric")                                                   */
+} fsk_norm;
+
 typedef struct {
   int32_t n;           /* problem size: K is n x n, a, b, u, v have n entries                  */
   int32_t m;           /* histograms per batch (multitarget form); 1 for the vector case       */
@@ -101,14 +107,17 @@ typedef struct {
                           centralised; must divide n                                           */
   int32_t max_iters;   /* IterMax of Algorithm 1                                               */
   double tol;          /* <= 0: run exactly max_iters iterations.  > 0: stop at the first poll
-                          where ||P 1 - a||_1 < tol, P = diag(u) K diag(v), evaluated with the
-                          scalings as they stand after a v-update                              */
+                          where ||P 1 - a|| < tol (norm: err_norm below), P = diag(u) K diag(v),
+                          evaluated with the scalings as they stand after a v-update           */
   int32_t check_every; /* iterations between polls in tolerance mode (>= 1); the last
                           iteration is always polled                                           */
   int32_t dtype;       /* fsk_dtype of K, a, b, u, v (storage and arithmetic)                  */
   int32_t flow;        /* fsk_flow (dense calls only)                                          */
   int32_t damping;     /* fsk_damping (dense and log-domain calls)                             */
   double eta;          /* relaxation parameter in (0, 1]; ignored when damping = NONE          */
+  int32_t err_norm;    /* fsk_norm of the marginal error that tolerance mode tests and reports
+                          (dense, log-domain and multitarget calls; the multitarget call takes
+                          the maximum over the targets of each target's norm)                  */
 } fsk_opts;
 
 typedef enum { FSK_MODE_DENSE = 0, FSK_MODE_LOG = 1, FSK_MODE_BATCHED = 2, FSK_MODE_SETUP = 3,
@@ -143,7 +152,8 @@ int fsk_kernel_from_points(const fsk_opts* opts, const void* x, const void* y, i
  * (1 for a cold start, as in Algorithm 1, or a previous result to resume).  On return (after
  * the stream has drained) they hold the scalings after *iters_done iterations.
  * iters_done (host, may be NULL): iterations performed.  err (host, may be NULL): the last
- * polled ||P1 - a||_1 in tolerance mode, NaN in fixed-iteration mode. */
+ * polled ||P1 - a|| (in the norm opts->err_norm names) in tolerance mode, NaN in fixed-iteration
+ * mode. */
 int fsk_sinkhorn_dense(const fsk_opts* opts, const void* K, int64_t ldK, const void* a,
                        const void* b, void* u, void* v, void* workspace, size_t ws_bytes,
                        int32_t* iters_done, double* err, void* stream);
@@ -157,11 +167,11 @@ void fsk_set_barrier_poll_limit(uint32_t polls);
 
 /* Row and column marginals of P = diag(u) K diag(v) (device outputs of n entries each; either
  * may be NULL), and optionally the marginal error on a in two norms (host outputs, either may
- * be NULL; a non-NULL one makes the call synchronise): err_l1 = ||P1 - a||_1, the quantity the
- * stop rule of this library tests, and err_l2 = ||P1 - a||_2, the one the paper's convergence
- * plots and its privacy appendix report (Sec. 5.4, "Marginal error metric").  Both come from one
- * row pass; the sums are taken in fp64.  err_l2 <= err_l1, so a run stopped at err_l1 < tol also
- * meets the paper's criterion at the same threshold. */
+ * be NULL; a non-NULL one makes the call synchronise): err_l1 = ||P1 - a||_1 and
+ * err_l2 = ||P1 - a||_2, the one the paper's convergence plots and its privacy appendix report
+ * (Sec. 5.4, "Marginal error metric").  Both come from one row pass; the sums are taken in fp64.
+ * opts->err_norm plays no part here; err_l2 <= err_l1, so a run stopped at err_l1 < tol also
+ * meets the 2-norm criterion at the same threshold. */
 int fsk_marginals(const fsk_opts* opts, const void* K, int64_t ldK, const void* a, const void* u,
                   const void* v, void* row_marginal, void* col_marginal, void* workspace,
                   size_t ws_bytes, double* err_l1, double* err_l2, void* stream);
@@ -295,7 +305,8 @@ int fsk_sinkhorn_batched(const fsk_opts* opts, const void* K, int64_t ldK, const
 /* The same with the stop rule of fsk_sinkhorn_dense applied to all targets at once (the
  * multitarget experiment of Sec. 5.3.2 iterates until every target meets the threshold):
  * opts->tol > 0 stops at the first poll (every opts->check_every iterations, and after
- * opts->max_iters) at which max over columns k of ||P_k 1 - a_k||_1 < tol, P_k = diag(u_k) K
+ * opts->max_iters) at which max over columns k of ||P_k 1 - a_k|| < tol (each target in the norm
+ * opts->err_norm names), P_k = diag(u_k) K
  * diag(v_k), with the scalings as they stand after a V-update (damped or not: in a damped run
  * the error is read off the undamped U-update of that state before it is relaxed);
  * opts->tol <= 0 runs max_iters iterations and leaves *err NaN.  iters_done (host, required) and err (host, may be NULL)

@@ -23,6 +23,7 @@ FSK_EINVAL, FSK_EALIGN, FSK_EDIV, FSK_EWORKSPACE, FSK_ENONFINITE, FSK_EHIP, FSK_
 FSK_F32, FSK_F64 = 0, 1
 FSK_FLOW_FUSED, FSK_FLOW_TWO_PASS, FSK_FLOW_PAPER, FSK_FLOW_RESIDENT = 0, 1, 2, 3
 FSK_DAMP_NONE, FSK_DAMP_ARITHMETIC, FSK_DAMP_GEOMETRIC = 0, 1, 2
+FSK_NORM_L1, FSK_NORM_L2 = 0, 1
 FSK_MODE_DENSE, FSK_MODE_LOG, FSK_MODE_BATCHED, FSK_MODE_SETUP, FSK_MODE_PLAN = 0, 1, 2, 3, 4
 FSK_MODE_RADIUS = 5
 
@@ -43,7 +44,7 @@ class fsk_opts(ctypes.Structure):
         ("n", ctypes.c_int32), ("m", ctypes.c_int32), ("c", ctypes.c_int32),
         ("max_iters", ctypes.c_int32), ("tol", ctypes.c_double), ("check_every", ctypes.c_int32),
         ("dtype", ctypes.c_int32), ("flow", ctypes.c_int32), ("damping", ctypes.c_int32),
-        ("eta", ctypes.c_double),
+        ("eta", ctypes.c_double), ("err_norm", ctypes.c_int32),
     ]
 
 
@@ -84,10 +85,11 @@ def _check(status: int) -> int:
 
 def make_opts(n: int, dtype: torch.dtype = torch.float32, m: int = 1, c: int = 1,
               max_iters: int = 0, tol: float = 0.0, check_every: int = 1,
-              flow: int = FSK_FLOW_FUSED, damping: int = FSK_DAMP_NONE, eta: float = 1.0) -> fsk_opts:
+              flow: int = FSK_FLOW_FUSED, damping: int = FSK_DAMP_NONE, eta: float = 1.0,
+              err_norm: int = FSK_NORM_L1) -> fsk_opts:
     return fsk_opts(n=n, m=m, c=c, max_iters=max_iters, tol=tol, check_every=check_every,
                     dtype=FSK_F64 if dtype == torch.float64 else FSK_F32, flow=flow,
-                    damping=damping, eta=eta)
+                    damping=damping, eta=eta, err_norm=err_norm)
 
 
 def _p(t: Optional[torch.Tensor]) -> ctypes.c_void_p:

@@ -55,6 +55,8 @@ static int check_common(const fsk_opts* o) {
   if (o->tol > 0.0 && o->check_every < 1)
     return set_error(FSK_EINVAL, "check_every = %d must be >= 1 in tolerance mode", o->check_every);
   if (std::isnan(o->tol)) return set_error(FSK_EINVAL, "tol is NaN");
+  if (o->err_norm != FSK_NORM_L1 && o->err_norm != FSK_NORM_L2)
+    return set_error(FSK_EINVAL, "unknown err_norm %d", o->err_norm);
   if (o->n % o->c != 0)
     return set_error(FSK_EDIV, "c = %d does not divide n = %d (n = c*m is required)", o->c, o->n);
   return FSK_OK;
@@ -298,6 +300,11 @@ static int dense_solve(const fsk_opts* opts, const DenseWs& w, const void* K, in
     if (err) *err = e;
     return set_error(FSK_ENONFINITE, "marginal error is not finite after %d iterations", at);
   };
+  const bool l2 = opts->err_norm == FSK_NORM_L2;
+  auto state_error = [&]() -> int {  // the chosen norm of P1 - a for the scalings as they stand
+    return l2 ? dense_error(opts, w, K, ldK, a, u, v, workspace, nullptr, st, &e)
+              : dense_error(opts, w, K, ldK, a, u, v, workspace, &e, st);
+  };
   if (resident) {
     for (int it = 0; it < opts->max_iters;) {  // all the iterations up to the next poll in one launch
       int chunk = opts->max_iters - it;
@@ -308,7 +315,7 @@ static int dense_solve(const fsk_opts* opts, const DenseWs& w, const void* K, in
       it += chunk;
       done = it;
       if (check && (done % opts->check_every == 0 || done == opts->max_iters)) {
-        FSK_TRY(dense_error(opts, w, K, ldK, a, u, v, workspace, &e, st));
+        FSK_TRY(state_error());
         if (!std::isfinite(e)) return nonfinite(done);
         if (e < opts->tol) break;
       }
@@ -333,9 +340,10 @@ static int dense_solve(const fsk_opts* opts, const DenseWs& w, const void* K, in
       FSK_TRY(dense_iteration(opts, w, (const char*)K, ldK, (const char*)a, (const char*)b, (char*)u,
                               (char*)v, workspace, st, nullptr, nullptr, poll ? errvec : nullptr));
       if (poll) {
-        FSK_TRY(launch_sum_to_double(opts->dtype, errvec, opts->n, scalar, st));
+        FSK_TRY(launch_sum_to_double(opts->dtype, errvec, opts->n, scalar, st, l2));
         FSK_HIP(hipMemcpyAsync(&e, scalar, sizeof(double), hipMemcpyDeviceToHost, st));
         FSK_HIP(hipStreamSynchronize(st));
+        if (l2) e = sqrt(e);
         if (!std::isfinite(e)) return nonfinite(it);
         if (e < opts->tol) {
           FSK_HIP(hipMemcpyAsync(u, save_u, vec_bytes, hipMemcpyDeviceToDevice, st));
@@ -349,7 +357,7 @@ static int dense_solve(const fsk_opts* opts, const DenseWs& w, const void* K, in
       done = it + 1;
     }
     if (check && !converged && done > 0) {  // the state after the last iteration is always polled
-      FSK_TRY(dense_error(opts, w, K, ldK, a, u, v, workspace, &e, st));
+      FSK_TRY(state_error());
       if (!std::isfinite(e)) return nonfinite(done);
     }
   }

@@ -651,13 +651,14 @@ int run_sinkhorn_batched(const fsk_opts* o, const void* K, int64_t ldK, const vo
 }
 
 // ------------------------------------------------------------------ error of a polled state
-// partial[strip][k] = sum over the 256 rows i of the strip of A_ik |Uold_ik / Unew_ik - 1| (fp64,
-// rows in increasing order per thread, then the four row lanes in order).
+// partial[strip][k] = sum over the 256 rows i of the strip of A_ik |Uold_ik / Unew_ik - 1|, or of
+// its square with `l2` (fp64, rows in increasing order per thread, then the four row lanes in order).
 template <typename T>
 __global__ __launch_bounds__(256) void batched_poll_partial_kernel(const T* __restrict__ A,
                                                                    const T* __restrict__ Uold,
                                                                    const T* __restrict__ Unew, int n,
-                                                                   int m, double* __restrict__ partial) {
+                                                                   int m, double* __restrict__ partial,
+                                                                   int l2) {
   __shared__ double sm[4][64];
   const int cl = threadIdx.x & 63, rl = threadIdx.x >> 6;
   const int k = blockIdx.x * 64 + cl, strip = blockIdx.y;
@@ -666,23 +667,26 @@ __global__ __launch_bounds__(256) void batched_poll_partial_kernel(const T* __re
   if (k < m)
     for (int i = strip * 256 + rl; i < i1; i += 4) {
       const int64_t idx = (int64_t)i * m + k;
-      s += (double)A[idx] * fabs((double)Uold[idx] / (double)Unew[idx] - 1.0);
+      const double term = (double)A[idx] * fabs((double)Uold[idx] / (double)Unew[idx] - 1.0);
+      s += l2 ? term * term : term;
     }
   sm[rl][cl] = s;
   __syncthreads();
   if (rl == 0 && k < m) partial[(int64_t)strip * m + k] = ((sm[0][cl] + sm[1][cl]) + sm[2][cl]) + sm[3][cl];
 }
 
-// out[0] = max over columns of the strips' sum (strips in order); NaN wins the maximum.
+// out[0] = max over columns of the strips' sum (strips in order), or of its square root with `l2`;
+// NaN wins the maximum.
 __global__ __launch_bounds__(256) void batched_poll_final_kernel(const double* __restrict__ partial,
                                                                  int strips, int m,
-                                                                 double* __restrict__ out) {
+                                                                 double* __restrict__ out, int l2) {
   __shared__ double sm[256];
   double best = 0.0;
   bool bad = false;
   for (int k = threadIdx.x; k < m; k += 256) {
     double s = 0.0;
     for (int t = 0; t < strips; ++t) s += partial[(int64_t)t * m + k];
+    if (l2) s = sqrt(s);
     if (!(s == s)) bad = true;
     best = s > best ? s : best;
   }
@@ -731,19 +735,19 @@ int launch_batched_relax(int dtype, void* X, const void* Xnew, int64_t count, do
 size_t batched_poll_scratch_doubles(int n, int m) { return 8 + (size_t)((n + 255) / 256) * (size_t)m; }
 
 int launch_batched_poll_error(int dtype, const void* A, const void* Uold, const void* Unew, int n,
-                              int m, double* scratch, hipStream_t st) {
+                              int m, double* scratch, hipStream_t st, bool l2) {
   const int strips = (n + 255) / 256;
   dim3 grid((m + 63) / 64, strips);
   double* partial = scratch + 8;
   if (dtype == FSK_F64)
     hipLaunchKernelGGL((batched_poll_partial_kernel<double>), grid, dim3(256), 0, st, (const double*)A,
-                       (const double*)Uold, (const double*)Unew, n, m, partial);
+                       (const double*)Uold, (const double*)Unew, n, m, partial, l2 ? 1 : 0);
   else
     hipLaunchKernelGGL((batched_poll_partial_kernel<float>), grid, dim3(256), 0, st, (const float*)A,
-                       (const float*)Uold, (const float*)Unew, n, m, partial);
+                       (const float*)Uold, (const float*)Unew, n, m, partial, l2 ? 1 : 0);
   FSK_LAUNCH_CHECK("batched_poll_partial_kernel");
   hipLaunchKernelGGL(batched_poll_final_kernel, dim3(1), dim3(256), 0, st, (const double*)partial, strips, m,
-                     scratch);
+                     scratch, l2 ? 1 : 0);
   FSK_LAUNCH_CHECK("batched_poll_final_kernel");
   return FSK_OK;
 }

@@ -156,9 +156,10 @@ struct BatchedPoll {
   double* err;         // host, may be null
 };
 size_t batched_poll_scratch_doubles(int n, int m);
-// scratch[0] = max over columns k of sum_i A_ik |Uold_ik / Unew_ik - 1| (fp64, fixed order).
+// scratch[0] = max over columns k of sum_i A_ik |Uold_ik / Unew_ik - 1| (fp64, fixed order); with
+// `l2` of sqrt(sum_i (A_ik |Uold_ik / Unew_ik - 1|)^2).
 int launch_batched_poll_error(int dtype, const void* A, const void* Uold, const void* Unew, int n,
-                              int m, double* scratch, hipStream_t st);
+                              int m, double* scratch, hipStream_t st, bool l2 = false);
 // X <- (1 - eta) X + eta Xnew, or X <- X^(1-eta) Xnew^eta (as exp2 of the weighted log2's), over
 // `count` elements (Sec. 3.3 on every target).
 int launch_batched_relax(int dtype, void* X, const void* Xnew, int64_t count, double eta, int geometric,
@@ -194,7 +195,8 @@ inline int batched_iterate(const fsk_opts* o, const void* A, void* U, void* V, c
   double e = NAN;
   bool converged = false;
   auto read_error = [&](const void* u_old, const void* u_new) -> int {
-    FSK_TRY(launch_batched_poll_error(o->dtype, A, u_old, u_new, n, m, poll->scratch, st));
+    FSK_TRY(launch_batched_poll_error(o->dtype, A, u_old, u_new, n, m, poll->scratch, st,
+                                      o->err_norm == FSK_NORM_L2));
     FSK_HIP(hipMemcpyAsync(&e, poll->scratch, sizeof(double), hipMemcpyDeviceToHost, st));
     FSK_HIP(hipStreamSynchronize(st));
     return FSK_OK;

@@ -609,10 +609,12 @@ static int run_log_typed(const fsk_opts* o, const void* x, const void* y, int d,
     }
     return FSK_OK;
   };
+  const bool l2 = o->err_norm == FSK_NORM_L2;  // ||P1 - a||_2 instead of the 1-norm
   auto read_error = [&](double* out) -> int {
-    FSK_TRY(launch_sum_to_double(FSK_F64, D(w.err), n, D(w.scalar), st));
+    FSK_TRY(launch_sum_to_double(FSK_F64, D(w.err), n, D(w.scalar), st, l2));
     FSK_HIP(hipMemcpyAsync(out, D(w.scalar), sizeof(double), hipMemcpyDeviceToHost, st));
     FSK_HIP(hipStreamSynchronize(st));
+    if (l2) *out = sqrt(*out);
     return FSK_OK;
   };
   auto nonfinite = [&](int at, double e) {

@@ -22,7 +22,8 @@ def relerr(got, ref):
 
 
 def run_dense(K_host, a, b, iters, flow=api.FSK_FLOW_FUSED, c=1, u0=None, v0=None, tol=0.0,
-              check_every=1, damping=api.FSK_DAMP_NONE, eta=1.0, ld=None, K_dev=None):
+              check_every=1, damping=api.FSK_DAMP_NONE, eta=1.0, ld=None, K_dev=None,
+              err_norm=api.FSK_NORM_L1):
     """Runs fsk_sinkhorn_dense; returns (u, v, iters_done, err) with u, v as NumPy arrays."""
     n = K_host.shape[0] if K_dev is None else K_dev.shape[0]
     dt = K_host.dtype if K_dev is None else (np.float64 if K_dev.dtype == torch.float64 else np.float32)
@@ -38,7 +39,7 @@ def run_dense(K_host, a, b, iters, flow=api.FSK_FLOW_FUSED, c=1, u0=None, v0=Non
             full[:, :n] = dev(K_host)
             K_dev = full[:, :n]
     opts = api.make_opts(n, td, c=c, max_iters=iters, tol=tol, check_every=check_every, flow=flow,
-                         damping=damping, eta=eta)
+                         damping=damping, eta=eta, err_norm=err_norm)
     ws = api.alloc_workspace(opts, api.FSK_MODE_DENSE)
     u = torch.ones(n, dtype=td, device="cuda") if u0 is None else dev(np.asarray(u0, dtype=dt))
     v = torch.ones(n, dtype=td, device="cuda") if v0 is None else dev(np.asarray(v0, dtype=dt))

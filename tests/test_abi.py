@@ -35,7 +35,7 @@ def test_header_symbols_are_exported(api):
 
 def test_opts_struct_layout_matches_header(api):
     # int32 x4, double, int32 x4, double  -> 8-byte aligned, 48 bytes
-    assert ctypes.sizeof(api.fsk_opts) == 48
+    assert ctypes.sizeof(api.fsk_opts) == 56 and api.fsk_opts.err_norm.offset == 48
     assert api.fsk_opts.tol.offset == 16 and api.fsk_opts.check_every.offset == 24
     assert api.fsk_opts.eta.offset == 40
 
