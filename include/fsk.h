@@ -95,7 +95,7 @@ typedef enum {
 } fsk_damping;
 
 typedef enum {
-  FSK_NORM_L1 = 0,  /* ||P1 - a||_1 (the stop rule as configuration 4 of the benchmark states it) */
+  FSK_NORM_L1 = 0,  /* ||P1 - a||_1, the default                                                  */
   FSK_NORM_L2 = 1   /* ||P1 - a||_2, the paper's own metric (Sec. 5.4, err_a; privacy appendix,
                        "Marginal error metric")                                                   */
 } fsk_norm;
@@ -113,7 +113,7 @@ typedef struct {
                           iteration is always polled                                           */
   int32_t dtype;       /* fsk_dtype of K, a, b, u, v (storage and arithmetic)                  */
   int32_t flow;        /* fsk_flow (dense calls only)                                          */
-  int32_t damping;     /* fsk_damping (dense and log-domain calls)                             */
+  int32_t damping;     /* fsk_damping (dense, log-domain and multitarget calls)                */
   double eta;          /* relaxation parameter in (0, 1]; ignored when damping = NONE          */
   int32_t err_norm;    /* fsk_norm of the marginal error that tolerance mode tests and reports
                           (dense, log-domain and multitarget calls; the multitarget call takes
