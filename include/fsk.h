@@ -200,7 +200,7 @@ int fsk_kernel_from_cost_lambda(const fsk_opts* opts, const void* c, int64_t ldc
 
 /* fsk_radius_search: bisection on [lambda_lo, lambda_hi] for <P(lambda), c> = delta.  Each
  * step: lambda = (lo + hi)/2; K as above; u = v = 1; the dense solve that fsk_sinkhorn_dense
- * would run with these opts (flow, c, max_iters, tol, check_every, damping); g = <P, c> - delta
+ * would run with these opts (flow, c, max_iters, tol, check_every, err_norm, damping); g = <P, c> - delta
  * from the plan-sum kernel; stop if |g| <= gtol, else lo = lambda if g > 0 (transport too
  * large: raise its price) and hi = lambda otherwise.  At most max_steps (>= 1) solves; the
  * call synchronises once per step.
