@@ -1,7 +1,7 @@
 """Seeded random VALID problems (size, precision, flow, block count, damping, row pitch, iteration
 count drawn at random) through the C ABI against the oracle, at the usual bars: 1e-4 (fp32) and
-1e-10 (fp64) on the scalings (|f - f_oracle| / eps in the log domain).  Complements the
-hand-picked sizes of the other files."""
+1e-10 (fp64) on the scalings (|f - f_oracle| / eps in the log domain), and random stop rules
+against the oracle's.  Complements the hand-picked sizes of the other files."""
 import numpy as np
 import pytest
 import torch
@@ -115,3 +115,71 @@ def test_random_log_domain_problems(orc, seed):
         what = (seed, case, n, d, np.dtype(dtype).name, iters)
         assert np.max(np.abs(f.cpu().numpy() - fo)) / eps <= tol, what
         assert np.max(np.abs(g.cpu().numpy() - go)) / eps <= tol, what
+
+
+@pytest.mark.parametrize("seed", [41, 42])
+def test_random_tolerance_mode_problems(orc, seed):
+    """Stop rules (either norm, any poll period) of the dense flows, the multitarget call and the
+    log domain: stop iteration against the oracle's rule (exact in fp64, within one poll in fp32)
+    and the reported error against the oracle's evaluation of the handed-back state."""
+    rng = np.random.default_rng(seed)
+    cap = 600
+    for case in range(45):
+        dtype = np.float32 if rng.random() < 0.4 else np.float64
+        td = torch.float32 if dtype == np.float32 else torch.float64
+        l2 = bool(rng.random() < 0.5)
+        norm = api.FSK_NORM_L2 if l2 else api.FSK_NORM_L1
+        ce = int(rng.integers(1, 6))
+        tol = float(10 ** rng.uniform(-9, -6)) if dtype == np.float64 else float(10 ** rng.uniform(-5.3, -4))
+        kind = int(rng.integers(0, 3))
+        n = int(rng.choice([rng.integers(2, 100), rng.integers(100, 700)]))
+        x = rng.uniform(size=(n, 2)); y = rng.uniform(size=(n, 2))
+        K64, _ = orc.gibbs_from_points(x, y, float(rng.uniform(0.2, 0.6)), False)
+        K = np.ascontiguousarray(K64.astype(dtype))
+        Kd = _padded(K, td, 0)[:, :n]
+        which = 1 if l2 else 0
+        if kind == 0:      # dense flows
+            flow = int(rng.choice([api.FSK_FLOW_FUSED, api.FSK_FLOW_TWO_PASS, api.FSK_FLOW_PAPER, api.FSK_FLOW_RESIDENT]))
+            if flow == api.FSK_FLOW_RESIDENT and n > (512 if dtype == np.float64 else 1024):
+                flow = api.FSK_FLOW_FUSED
+            c = int(rng.choice([c for c in (1, 2, 4, 8) if n % c == 0]))
+            a = rng.uniform(0.5, 1.5, n) ** 2; a = (a / a.sum()).astype(dtype)
+            b = rng.uniform(0.5, 1.5, n) ** 2; b = (b / b.sum()).astype(dtype)
+            _, _, done_o, err_o = orc.sinkhorn_dense_tol(K, a, b, cap, tol, check_every=ce, l2=l2)
+            opts = api.make_opts(n, td, c=c, max_iters=cap, tol=tol, check_every=ce, flow=flow, err_norm=norm)
+            u = torch.ones(n, dtype=td, device="cuda"); v = torch.ones(n, dtype=td, device="cuda")
+            done, err = api.fsk_sinkhorn_dense(opts, Kd, dev(a), dev(b), u, v, api.alloc_workspace(opts))
+            state = orc.marginal_error(K, a, u.cpu().numpy(), v.cpu().numpy())[which]
+            what = ("dense", seed, case, n, np.dtype(dtype).name, flow, c, ce, l2, tol)
+        elif kind == 1:    # multitarget
+            m = int(rng.choice([1, rng.integers(2, 65), rng.integers(65, 140)]))
+            A = rng.uniform(0.5, 1.5, (n, m)) ** 2; A = np.ascontiguousarray((A / A.sum(0)).astype(dtype))
+            B = rng.uniform(0.5, 1.5, (n, m)) ** 2; B = np.ascontiguousarray((B / B.sum(0)).astype(dtype))
+            _, _, done_o, err_o = orc.sinkhorn_batched_tol(K, A, B, cap, tol, ce, l2=l2)
+            opts = api.make_opts(n, td, m=m, max_iters=cap, tol=tol, check_every=ce, err_norm=norm)
+            U = torch.ones(n, m, dtype=td, device="cuda"); V = torch.ones(n, m, dtype=td, device="cuda")
+            done, err = api.fsk_sinkhorn_batched_tol(opts, Kd, dev(A), dev(B), U, V,
+                                                     api.alloc_workspace(opts, api.FSK_MODE_BATCHED))
+            Un, Vn = U.cpu().numpy(), V.cpu().numpy()
+            state = max(orc.marginal_error(K, A[:, k], Un[:, k], Vn[:, k])[which] for k in range(m))
+            what = ("multitarget", seed, case, n, m, np.dtype(dtype).name, ce, l2, tol)
+        else:              # log domain
+            d = int(rng.integers(1, 20))
+            xl = rng.uniform(size=(n, d)).astype(np.float32); yl = rng.uniform(size=(n, d)).astype(np.float32)
+            eps = float(rng.uniform(0.05, 0.2)) * d
+            a = rng.uniform(0.5, 1.5, n); a = (a / a.sum()).astype(np.float32)
+            b = rng.uniform(0.5, 1.5, n); b = (b / b.sum()).astype(np.float32)
+            _, _, done_o, err_o = orc.sinkhorn_log_points(xl, yl, eps, a, b, cap, tol=tol, check_every=ce, l2=l2)
+            opts = api.make_opts(n, td, max_iters=cap, tol=tol, check_every=ce, err_norm=norm)
+            f = torch.zeros(n, dtype=td, device="cuda"); g = torch.zeros(n, dtype=td, device="cuda")
+            done, err = api.fsk_sinkhorn_log_points(opts, dev(xl.astype(dtype)), dev(yl.astype(dtype)), eps,
+                                                    dev(a.astype(dtype)), dev(b.astype(dtype)), f, g,
+                                                    api.alloc_workspace(opts, api.FSK_MODE_LOG, d))
+            rows = orc.log_row_marginal_points(xl, f.double().cpu().numpy(), yl, g.double().cpu().numpy(), eps)
+            state = float(np.linalg.norm(rows - a) if l2 else np.abs(rows - a).sum())
+            what = ("log", seed, case, n, d, np.dtype(dtype).name, ce, l2, tol)
+        if dtype == np.float64:
+            assert done == done_o, what
+            assert abs(err - err_o) <= 1e-3 * err_o + 1e-13 and abs(err - state) <= 1e-3 * state + 1e-13, what
+        else:              # fp32 sums may cross the threshold one poll earlier or later
+            assert abs(done - done_o) <= ce and abs(err - state) <= 0.2 * state + 2e-6, what
