@@ -221,8 +221,9 @@ int fsk_radius_search(const fsk_opts* opts, const void* c, int64_t ldc, const vo
  *     s(t) = floor((t-1-tau)/sync_every)*sync_every      (the initial vectors if <= 0):
  *   u_{I_j} <- (1-eta) u_{I_j} + eta a_j ./ (K_{I_j,:} v_cached),
  *   v_{I_j} <- (1-eta) v_{I_j} + eta b_j ./ ((K_{:,I_j})^T u_cached)   (u_cached has the new u_{I_j}).
- * eta = opts->eta if opts->damping == FSK_DAMP_ARITHMETIC, else 1.  Runs exactly
- * opts->max_iters iterations (tolerance mode is not offered); u, v are IN/OUT as in
+ * eta = opts->eta if opts->damping == FSK_DAMP_ARITHMETIC, 1 for FSK_DAMP_NONE
+ * (FSK_EUNSUPPORTED for the geometric relaxation: Algorithm 3 uses the arithmetic one).  Runs exactly
+ * opts->max_iters iterations (FSK_EUNSUPPORTED for opts->tol > 0); u, v are IN/OUT as in
  * fsk_sinkhorn_dense.  tau >= 0, sync_every >= 1.  Workspace: fsk_async_workspace_bytes(). */
 size_t fsk_async_workspace_bytes(const fsk_opts* opts, int32_t tau, int32_t sync_every);
 int fsk_sinkhorn_async_emulated(const fsk_opts* opts, const void* K, int64_t ldK, const void* a,
