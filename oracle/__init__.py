@@ -45,7 +45,7 @@ def _load():
         L.orc_rdp_epsilon.restype = ctypes.c_double
         for name in ("orc_num_threads", "orc_sinkhorn_dense", "orc_sinkhorn_dense_tol", "orc_sinkhorn_batched_tol", "orc_sinkhorn_batched_damped",
                      "orc_sinkhorn_blocked", "orc_sinkhorn_dense_damped", "orc_sinkhorn_batched",
-                     "orc_sinkhorn_async_emulated", "orc_sinkhorn_grid", "orc_sinkhorn_batched_dp",
+                     "orc_sinkhorn_async_emulated", "orc_sinkhorn_local_steps", "orc_sinkhorn_grid", "orc_sinkhorn_batched_dp",
                      "orc_sinkhorn_log_points", "orc_sinkhorn_log_cost", "orc_sinkhorn_log_points_damped"):
             getattr(L, name).restype = ctypes.c_int
         _lib = L
@@ -239,6 +239,21 @@ def sinkhorn_async_emulated(K, a, b, iters: int, c: int, eta: float, tau: int, w
                                              _INT(iters), _INT(c), _DBL(eta), _INT(tau), _INT(w))
     if rc == -2:
         raise ValueError("need c | n, tau >= 0, w >= 1")
+    assert rc == 0
+    return u, v
+
+
+def sinkhorn_local_steps(K, a, b, iters: int, c: int, w: int, u0=None, v0=None):
+    """Synchronous federated iteration whose collectives run only every `w` iterations: between
+    them every client works on its own views (own slices current, peers' slices as of the last
+    collective).  w = 1 is Algorithm 1."""
+    kp, kf, n, ld = _square(K)
+    a, b = _f64(a), _f64(b)
+    u, v = _init(K.shape[0], u0), _init(K.shape[0], v0)
+    rc = _load().orc_sinkhorn_local_steps(kp, kf, n, ld, _ptr(a), _ptr(b), _ptr(u), _ptr(v),
+                                          _INT(iters), _INT(c), _INT(w))
+    if rc == -2:
+        raise ValueError("need c | n and w >= 1")
     assert rc == 0
     return u, v
 

@@ -19,6 +19,8 @@
  *   - the objective of Eq. 1 and the expected loss sum P_ij l(x'_j) of the finance example
  *   - damped updates, arithmetic and geometric         (Sec. 3.3 and its Remark)
  *   - bounded-delay emulation of the asynchronous schedule (Algorithm 3, assumption A3)
+ *   - synchronous iteration with w local steps between collectives (Sec. 3.1 Remark,
+ *     App. "Additional details on local steps")
  *   - log-domain form: the paper only names it (Sec. 1, Sec. 2.1); the
  *     formulas here are the exact logarithm of the iteration above with
  *     f = eps*log u, g = eps*log v.
@@ -448,6 +450,60 @@ int orc_sinkhorn_async_emulated(const void* K, int k_is_f32, int64_t n, int64_t 
   memcpy(u, hist_u + (size_t)iters * n, sizeof(double) * (size_t)n);
   memcpy(v, hist_v + (size_t)iters * n, sizeof(double) * (size_t)n);
   free(hist_u); free(hist_v); free(view); free(prod);
+  return 0;
+}
+
+/* Synchronous federated iteration with w local steps between collectives (Sec. 3.1, Remark
+ * "Local steps before communication"; App. "Additional details on local steps"; the
+ * "optional" collectives (i) and (iii) of Sec. 3.2.1).  Every client j keeps its OWN
+ * full-length views uview[j], vview[j] of the global scalings (all equal to the init at the
+ * start).  Iteration k = 1, 2, ..., iters, for every client j:
+ *     q_{I_j} = K_{I_j,:} vview[j],        u_{I_j} = a_j ./ q_{I_j}   (stored in uview[j] only);
+ *     if k is a multiple of w: Allgather u -- every view receives every client's own slice;
+ *     r_{I_j} = (K_{:,I_j})^T uview[j],    v_{I_j} = b_j ./ r_{I_j}   (stored in vview[j] only);
+ *     if k is a multiple of w: Allgather v.
+ * So between collectives a client sees its own slices as current and the peers' slices as of
+ * the last collective; w = 1 is Algorithm 1 line by line.  u, v in/out are the global vectors
+ * (client j's own slice at positions I_j).  Returns -2 unless c | n and w >= 1. */
+int orc_sinkhorn_local_steps(const void* K, int k_is_f32, int64_t n, int64_t ld, const double* a,
+                             const double* b, double* u, double* v, int iters, int c, int w) {
+  if (c < 1 || n % c != 0 || w < 1) return -2;
+  const int64_t m = n / c;
+  double* uview = (double*)malloc(sizeof(double) * (size_t)n * (size_t)c);
+  double* vview = (double*)malloc(sizeof(double) * (size_t)n * (size_t)c);
+  double* prod = (double*)malloc(sizeof(double) * (size_t)n);
+  if (!uview || !vview || !prod) return -1;
+  for (int j = 0; j < c; ++j) { /* "identical at all clients" */
+    memcpy(uview + (size_t)j * n, u, sizeof(double) * (size_t)n);
+    memcpy(vview + (size_t)j * n, v, sizeof(double) * (size_t)n);
+  }
+  for (int k = 1; k <= iters; ++k) {
+    for (int j = 0; j < c; ++j) {
+      double* uj = uview + (size_t)j * n;
+      orc_row_products(K, k_is_f32, n, ld, j * m, (j + 1) * m, vview + (size_t)j * n, prod);
+      for (int64_t i = j * m; i < (j + 1) * m; ++i) uj[i] = a[i] / prod[i];
+    }
+    if (k % w == 0) /* Allgather u: slice I_p of every view <- client p's own slice */
+      for (int p = 0; p < c; ++p)
+        for (int j = 0; j < c; ++j)
+          if (j != p)
+            memcpy(uview + (size_t)j * n + p * m, uview + (size_t)p * n + p * m, sizeof(double) * (size_t)m);
+    for (int j = 0; j < c; ++j) {
+      double* vj = vview + (size_t)j * n;
+      orc_col_products(K, k_is_f32, n, ld, 0, n, j * m, (j + 1) * m, uview + (size_t)j * n, prod);
+      for (int64_t i = j * m; i < (j + 1) * m; ++i) vj[i] = b[i] / prod[i];
+    }
+    if (k % w == 0) /* Allgather v */
+      for (int p = 0; p < c; ++p)
+        for (int j = 0; j < c; ++j)
+          if (j != p)
+            memcpy(vview + (size_t)j * n + p * m, vview + (size_t)p * n + p * m, sizeof(double) * (size_t)m);
+  }
+  for (int j = 0; j < c; ++j) {
+    memcpy(u + j * m, uview + (size_t)j * n + j * m, sizeof(double) * (size_t)m);
+    memcpy(v + j * m, vview + (size_t)j * n + j * m, sizeof(double) * (size_t)m);
+  }
+  free(uview); free(vview); free(prod);
   return 0;
 }
 

@@ -619,6 +619,91 @@ def test_async_emulation_converges_to_the_sinkhorn_plan(orc, c, tau, w, eta):
     assert np.allclose(r, r[0], rtol=1e-7)
 
 
+# ----------------- synchronous local steps w (Sec. 3.1 Remark; App. "local steps") ---
+
+def test_local_steps_w1_is_algorithm_1_and_one_client_is_centralised(orc):
+    """The appendix on local steps: w = 1 is fully synchronous Sinkhorn -- the very values of
+    the row-partitioned iteration as printed in Algorithm 1; and with one client there is no
+    peer whose slice could be stale, so any w gives the centralised iteration."""
+    x, y, a, b, C, K = problem(24, 60, eps=0.2)
+    for c in (1, 2, 4, 8):
+        ub, vb = orc.sinkhorn_blocked(K, a, b, 9, c, 0)
+        ul, vl = orc.sinkhorn_local_steps(K, a, b, 9, c, 1)
+        assert np.array_equal(ul, ub) and np.array_equal(vl, vb)
+    ud, vd = orc.sinkhorn_dense(K, a, b, 9)
+    for w in (2, 3, 9, 50):
+        ul, vl = orc.sinkhorn_local_steps(K, a, b, 9, 1, w)
+        assert np.array_equal(ul, ud) and np.array_equal(vl, vd)
+    with pytest.raises(ValueError):
+        orc.sinkhorn_local_steps(K, a, b, 1, 5, 1)      # 5 does not divide 24
+    with pytest.raises(ValueError):
+        orc.sinkhorn_local_steps(K, a, b, 1, 2, 0)
+
+
+def test_local_steps_first_rounds_by_hand(orc):
+    """c = 2 clients, w = 2, written out with NumPy on per-client views: iteration 1 is local
+    (each client sees the peer's initial slices), iteration 2 gathers u before the v-update and v
+    after it, iteration 3 is local again on the gathered views, iteration 4 gathers.  The
+    asymmetric K tells the row slab from the column slab."""
+    n, m = 10, 5
+    x, y, a, b, C, K = problem(n, 61, eps=0.3)
+    I = [slice(0, m), slice(m, n)]
+    uview = [np.ones(n), np.ones(n)]; vview = [np.ones(n), np.ones(n)]
+    states = []
+    for k in (1, 2, 3, 4):
+        for j in (0, 1):
+            uview[j][I[j]] = a[I[j]] / (K[I[j], :] @ vview[j])
+        if k % 2 == 0:
+            uview[0][I[1]] = uview[1][I[1]]; uview[1][I[0]] = uview[0][I[0]]
+        for j in (0, 1):
+            vview[j][I[j]] = b[I[j]] / (K[:, I[j]].T @ uview[j])
+        if k % 2 == 0:
+            vview[0][I[1]] = vview[1][I[1]]; vview[1][I[0]] = vview[0][I[0]]
+        states.append((np.concatenate([uview[0][I[0]], uview[1][I[1]]]),
+                       np.concatenate([vview[0][I[0]], vview[1][I[1]]])))
+    for k in (1, 2, 3, 4):
+        ul, vl = orc.sinkhorn_local_steps(K, a, b, k, 2, 2)
+        assert np.allclose(ul, states[k - 1][0], rtol=1e-13) and np.allclose(vl, states[k - 1][1], rtol=1e-13)
+    # the local iterations really differ from Algorithm 1 (stale peers), the schedule matters
+    u1, v1 = orc.sinkhorn_dense(K, a, b, 4)
+    assert not np.allclose(states[3][0], u1, rtol=1e-3)
+    # a run is resumable at a collective: 4 iterations == 2 + 2 with the state passed through
+    ua, va = orc.sinkhorn_local_steps(K, a, b, 2, 2, 2)
+    ub, vb = orc.sinkhorn_local_steps(K, a, b, 2, 2, 2, ua, va)
+    u4, v4 = orc.sinkhorn_local_steps(K, a, b, 4, 2, 2)
+    assert np.array_equal(ub, u4) and np.array_equal(vb, v4)
+
+
+def test_local_steps_before_the_first_collective_equal_the_delay_emulation(orc):
+    """Until the first collective a client has its own slices current and the peers' initial
+    ones: exactly what the bounded-delay schedule (undamped, no exchange yet) prescribes.  The
+    two functions are written separately; the emulation is pinned by its own hand-written case."""
+    x, y, a, b, C, K = problem(24, 62, eps=0.25)
+    for c in (2, 3, 4):
+        ul, vl = orc.sinkhorn_local_steps(K, a, b, 5, c, 6)
+        ue, ve = orc.sinkhorn_async_emulated(K, a, b, 5, c, 1.0, 0, 6)
+        assert np.allclose(ul, ue, rtol=1e-14) and np.allclose(vl, ve, rtol=1e-14)
+    # at the collective iteration they part: here the v-update sees every peer's fresh u
+    ul, vl = orc.sinkhorn_local_steps(K, a, b, 6, 3, 6)
+    ue, ve = orc.sinkhorn_async_emulated(K, a, b, 6, 3, 1.0, 0, 6)
+    assert np.allclose(ul, ue, rtol=1e-14) and not np.allclose(vl, ve, rtol=1e-6)
+    # ... exactly as one more step of Algorithm 1's v-update on the gathered u would
+    assert np.allclose(vl, b / (K.T @ ul), rtol=1e-13)
+
+
+@pytest.mark.parametrize("c,w", [(2, 2), (4, 3), (8, 5)])
+def test_local_steps_converge_to_the_sinkhorn_plan(orc, c, w):
+    """The appendix reports that w > 1 slows the iteration but still reaches the tolerance: the
+    limit is a Sinkhorn fixed point, i.e. the same plan P* (scalings up to the scalar gauge)."""
+    x, y, a, b, C, K = problem(32, 63, eps=0.25)
+    us, vs = orc.sinkhorn_dense(K, a, b, 4000)
+    Pstar = us[:, None] * K * vs[None, :]
+    ul, vl = orc.sinkhorn_local_steps(K, a, b, 6000, c, w)
+    assert np.allclose(ul[:, None] * K * vl[None, :], Pstar, rtol=1e-7)
+    r = ul / us
+    assert np.allclose(r, r[0], rtol=1e-7)
+
+
 # ------------------------------------------------------------ plan objective ---
 
 def test_plan_objective_against_numpy_and_duality(orc):
