@@ -21,6 +21,24 @@ def relerr(got, ref):
     return float(np.max(np.abs(got - ref) / np.abs(ref)))
 
 
+def gauge_free(got, ref):
+    """Error of a positive scaling vector that a uniform rescaling cannot hide or cause: the
+    scalings of the iteration are unique up to (u/s, s v) (appendix on convergence, uniqueness up
+    to rescaling), so d = log(got/ref) is split into its mean (the drift along that direction) and
+    max |d - mean|.  Returns (max |d - mean d|, largest |mean d|); an n x m matrix of scalings has
+    one such direction per column (target)."""
+    d = np.log(np.asarray(got, dtype=np.float64) / np.asarray(ref, dtype=np.float64))
+    mean = d.mean(axis=0, keepdims=True)
+    return float(np.max(np.abs(d - mean))), float(np.max(np.abs(mean)))
+
+
+def say(capsys, msg):
+    """A progress line that reaches the terminal although pytest captures output: the long
+    oracle runs print one after every chunk."""
+    with capsys.disabled():
+        print(msg, flush=True)
+
+
 def run_dense(K_host, a, b, iters, flow=api.FSK_FLOW_FUSED, c=1, u0=None, v0=None, tol=0.0,
               check_every=1, damping=api.FSK_DAMP_NONE, eta=1.0, ld=None, K_dev=None,
               err_norm=api.FSK_NORM_L1):

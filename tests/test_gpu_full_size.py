@@ -1,16 +1,19 @@
 """Parity at the full benchmark sizes, in the launch configuration bench.py times.
 
-The oracle cannot follow a full trajectory at these sizes in test time, so each case combines
-(i) a short full run from the cold start compared element by element, and (ii) one-step
-consistency at a late state: the oracle recomputes sampled entries of the next update from the
-GPU's own previous half-step, which pins every later iteration to the definition.
+Two kinds of cases.  The `*_full_*` tests follow a configuration for its own length: the oracle
+runs all 1000 (configuration 3) or 300 (configuration 5) iterations, or the configuration-4 law
+to its stop rule, in chunks that print a progress line, and the GPU's state is compared element
+by element at every chunk boundary -- direct relative error, both marginals, and the error with
+the uniform-rescaling direction taken out (see gpu_util.gauge_free).  The older cases combine a
+short run from the cold start with one-step consistency at a late state: the oracle recomputes
+sampled entries of the next update from the GPU's own previous half-step.
 """
 import numpy as np
 import pytest
 import torch
 
 from paper_2502_07021_amd import api, workloads
-from gpu_util import dev, relerr
+from gpu_util import dev, gauge_free, relerr, say
 
 pytestmark = pytest.mark.gpu
 
@@ -156,3 +159,123 @@ def test_multitarget_instance_n5000_m500(orc):
         api.fsk_sinkhorn_batched(opts, Kd, dev(A.astype(nd)), dev(B.astype(nd)), U, V, ws)
         torch.cuda.synchronize()
         assert relerr(U.cpu().numpy(), Uo) <= tol and relerr(V.cpu().numpy(), Vo) <= tol
+
+
+def test_cfg3_full_1000_iterations_against_oracle(orc, capsys):
+    """Configuration 3 for its own length: 1000 iterations, c = 8, fused flow, against the
+    oracle's row-slab iteration (contributions added in block order) on u, v and both marginals;
+    compared every 100 iterations so that a drift shows where it starts."""
+    w = workloads.make(3)
+    n, T, step = w.n, w.iters, 100
+    K, _ = orc.gibbs_from_points_f32(w.x, w.y, w.eps, True)
+    Kd = dev(K); a = dev(w.a); b = dev(w.b)
+
+    def run(iters):
+        opts = api.make_opts(n, torch.float32, c=8, max_iters=iters, flow=api.FSK_FLOW_FUSED)
+        ws = api.alloc_workspace(opts)
+        u = torch.ones(n, device="cuda"); v = torch.ones(n, device="cuda")
+        api.fsk_sinkhorn_dense(opts, Kd, a, b, u, v, ws)
+        rm = torch.empty(n, device="cuda"); cm = torch.empty(n, device="cuda")
+        api.fsk_marginals(opts, Kd, a, u, v, rm, cm, ws)
+        torch.cuda.synchronize()
+        return u.cpu().numpy(), v.cpu().numpy(), rm.cpu().numpy(), cm.cpu().numpy()
+
+    uo = vo = None
+    worst = 0.0
+    for t in range(step, T + 1, step):
+        uo, vo = orc.sinkhorn_blocked(K, w.a, w.b, step, 8, 1, uo, vo)   # resumes exactly (fp64 state)
+        u, v, rm, cm = run(t)
+        eu, ev = relerr(u, uo), relerr(v, vo)
+        gu, du = gauge_free(u, uo); gv, dv = gauge_free(v, vo)
+        say(capsys, f"cfg3 t={t}: relerr u {eu:.2e} v {ev:.2e}; gauge-free u {gu:.2e} v {gv:.2e}; "
+                    f"uniform drift u {du:.2e} v {dv:.2e}")
+        assert eu <= 1e-4 and ev <= 1e-4 and gu <= 1e-4 and gv <= 1e-4
+        worst = max(worst, eu, ev)
+    # both marginals of the final state against the oracle's
+    assert relerr(rm, orc.row_marginal(K, uo, vo)) <= 1e-4
+    assert relerr(cm, orc.col_marginal(K, uo, vo)) <= 1e-4
+    say(capsys, f"cfg3 full run: worst relative error on u, v over the checkpoints {worst:.2e}")
+
+
+def test_cfg5_full_300_iterations_against_oracle(orc, capsys):
+    """Configuration 5 for its own length: 300 iterations of the 64 stacked targets, compared
+    every 30 iterations; the rescaling direction is taken out per target."""
+    w = workloads.make(5)
+    n, m, T, step = w.n, w.m, w.iters, 30
+    K, _ = orc.gibbs_from_points_f32(w.x, w.y, w.eps, False)
+    Kd = dev(K); A = dev(w.a); B = dev(w.b)
+
+    def run(iters):
+        opts = api.make_opts(n, torch.float32, m=m, max_iters=iters)
+        ws = api.alloc_workspace(opts, api.FSK_MODE_BATCHED)
+        U = torch.ones(n, m, device="cuda"); V = torch.ones(n, m, device="cuda")
+        api.fsk_sinkhorn_batched(opts, Kd, A, B, U, V, ws)
+        torch.cuda.synchronize()
+        return U.cpu().numpy(), V.cpu().numpy()
+
+    Uo = Vo = None
+    for t in range(step, T + 1, step):
+        Uo, Vo = orc.sinkhorn_batched(K, w.a, w.b, step, Uo, Vo)
+        U, V = run(t)
+        eu, ev = relerr(U, Uo), relerr(V, Vo)
+        gu, du = gauge_free(U, Uo); gv, dv = gauge_free(V, Vo)
+        say(capsys, f"cfg5 t={t}: relerr U {eu:.2e} V {ev:.2e}; gauge-free U {gu:.2e} V {gv:.2e}; "
+                    f"largest uniform drift of a target U {du:.2e} V {dv:.2e}")
+        assert eu <= 1e-4 and ev <= 1e-4 and gu <= 1e-4 and gv <= 1e-4
+    # row marginals of the final state, three targets: U_ik (K V)_ik against the oracle's
+    for k in (0, 31, 63):
+        got = U[:, k].astype(np.float64) * orc.row_products(K, V[:, k])
+        assert relerr(got, Uo[:, k] * orc.row_products(K, Vo[:, k])) <= 1e-4
+
+
+def test_cfg4_law_to_its_stop_rule_against_oracle(orc, capsys):
+    """The configuration-4 law at n = 4096 (x, y ~ U[0,1]^16, eps = 0.01, a = b = 1/n) run to a
+    stop rule against the oracle under the same polling.  The configuration's own rule (L1 error
+    below 1e-6 or 2000 iterations) ends at the cap for this law, in fp64 too, so a looser
+    tolerance that IS reached goes first: there the stop iteration is compared and the potentials
+    at the GPU's stop iteration; then both sides go on to the cap."""
+    w = workloads.make(4, n=4096)
+    n, d, eps, every = w.n, w.d, w.eps, 50
+    x, y, a, b = dev(w.x), dev(w.y), dev(w.a), dev(w.b)
+
+    def run(iters, tol):
+        opts = api.make_opts(n, torch.float32, max_iters=iters, tol=tol, check_every=every)
+        ws = api.alloc_workspace(opts, api.FSK_MODE_LOG, d)
+        f = torch.zeros(n, device="cuda"); g = torch.zeros(n, device="cuda")
+        done, err = api.fsk_sinkhorn_log_points(opts, x, y, eps, a, b, f, g, ws)
+        torch.cuda.synchronize()
+        return f.cpu().numpy().astype(np.float64), g.cpu().numpy().astype(np.float64), done, err
+
+    def compare(tag, f, g, fo, go):
+        ef, eg = np.max(np.abs(f - fo)) / eps, np.max(np.abs(g - go)) / eps
+        # u = exp(f/eps): log(u/u_oracle) = (f - f_oracle)/eps, so the rescaling direction is a
+        # constant shift of f (and the opposite one of g)
+        df, dg = (f - fo) / eps, (g - go) / eps
+        gf, gg = np.max(np.abs(df - df.mean())), np.max(np.abs(dg - dg.mean()))
+        say(capsys, f"cfg4 law {tag}: |df|/eps {ef:.2e} |dg|/eps {eg:.2e}; gauge-free {gf:.2e} {gg:.2e}; "
+                    f"uniform shift {df.mean():.2e} {dg.mean():.2e}")
+        assert ef <= 1e-4 and eg <= 1e-4 and gf <= 1e-4 and gg <= 1e-4
+
+    # (a) a tolerance both sides reach
+    tol = 5e-4
+    fo, go, done_o, err_o = orc.sinkhorn_log_points(w.x, w.y, eps, w.a, w.b, 2000, tol, every)
+    say(capsys, f"cfg4 law: oracle stops after {done_o} iterations at L1 error {err_o:.3e} (tol {tol})")
+    assert 0 < done_o < 2000 and err_o < tol
+    f, g, done, err = run(2000, tol)
+    assert done % every == 0 and err < tol
+    assert abs(done - done_o) <= every          # fp32 exponentials may cross the threshold one poll apart
+    if done != done_o:
+        fo, go, _, _ = orc.sinkhorn_log_points(w.x, w.y, eps, w.a, w.b, done)
+        done_o = done
+    else:
+        assert err == pytest.approx(err_o, rel=2e-2)
+    compare(f"at the stop iteration {done}", f, g, fo, go)
+
+    # (b) the configuration's rule: 1e-6 or 2000 iterations; the oracle resumes from (a)
+    fo, go, more, err_o = orc.sinkhorn_log_points(w.x, w.y, eps, w.a, w.b, 2000 - done_o, 1e-6, every, fo, go)
+    say(capsys, f"cfg4 law: oracle at {done_o + more} iterations, L1 error {err_o:.3e}")
+    f, g, done, err = run(2000, 1e-6)
+    assert done == done_o + more                # both at the cap (or both at the same poll)
+    assert (err < 1e-6) == (err_o < 1e-6)
+    assert err == pytest.approx(err_o, rel=5e-2)
+    compare(f"after {done} iterations", f, g, fo, go)
