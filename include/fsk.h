@@ -36,9 +36,12 @@
  *     host before anything is launched; a failed call launches nothing.
  *   - Not checked (assumptions A1-A2 of the paper's convergence section):
  *     K > 0, a, b > 0 with equal total mass.
- *   - Results are deterministic: no floating-point atomics; every reduction has
- *     a fixed order that depends only on (n, dtype, flow, c) and the device's
- *     compute-unit count.
+ *   - Results are deterministic: no floating-point atomics; every reduction has a fixed order.
+ *     For the dense flows FUSED, TWO_PASS and PAPER that order depends on (n, dtype, flow) only --
+ *     not on the device, and not on the block count c (FUSED: as long as n/c is a multiple of the
+ *     strip height, see fsk_flow) -- so c blocks reproduce the iterates of c = 1 bit for bit
+ *     (Proposition 1).  FSK_FLOW_RESIDENT, the grid flow and the multitarget kernels group their
+ *     sums by their own launch shapes (compute-unit count, workspace given): equal to rounding.
  */
 #ifndef FSK_H
 #define FSK_H
@@ -66,12 +69,18 @@ typedef enum { FSK_F32 = 0, FSK_F64 = 1 } fsk_dtype;
 /* How one dense iteration moves through K.  All produce the iterates of
  * Algorithm 1; they differ in memory traffic and in summation order. */
 typedef enum {
-  FSK_FLOW_FUSED = 0,    /* one pass over K per iteration: a workgroup keeps a row strip in
-                            registers, finishes u on it, and accumulates the strip's
-                            contribution K_I^T u_I; a second small kernel sums the
-                            contributions in fixed order and divides.  With c > 1 each block's
-                            row slab yields its own contribution s^(j) = K_{I_j,:}^T u_{I_j}
-                            (what a worker holding only its rows can form).                 */
+  FSK_FLOW_FUSED = 0,    /* one pass over K per iteration: a workgroup keeps rows in registers,
+                            finishes u on them, and accumulates their contribution K_I^T u_I; a
+                            second small kernel sums the contributions in fixed order and
+                            divides.  Every row block I_j is cut into strips of h rows, one row
+                            of partial column sums per strip (per workgroup of a strip); block
+                            j's contribution s^(j) = K_{I_j,:}^T u_{I_j} -- what a worker holding
+                            only its rows can form -- is the sum of its strips'.  h is
+                            ceil(n / S) rounded up to the kernel's row group (S = 256 strips
+                            for n >= 8192, 16 below), i.e. a function of n and dtype alone
+                            whenever c divides S; if n/c is also a multiple of h the strips are
+                            the same for every such c and the iterates equal those of c = 1
+                            bit for bit, otherwise to rounding.                             */
   FSK_FLOW_TWO_PASS = 1, /* q = K v over all rows, then r = K^T u over all rows (two passes)  */
   FSK_FLOW_PAPER = 2,    /* Algorithm 1 as printed: block j forms u_{I_j} from its row slab,
                             then r_{I_j} = (K_{:,I_j})^T u from its column slab              */

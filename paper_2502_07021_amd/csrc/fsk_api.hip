@@ -92,9 +92,7 @@ static DenseWs dense_ws(const fsk_opts* o) {
   const int rows_blk = o->n / o->c;
   size_t rows = (size_t)col_strips(o->n);
   FusedPlan p = fused_plan(o->dtype, o->n, rows_blk, o->c);
-  int wgs = p.ok ? p.wgs : 0;
-  if (p.ok && device_cu_count() == 0) wgs = p.groups < 1024 ? p.groups : 1024;  // no device: be generous
-  if ((size_t)o->c * wgs > rows) rows = (size_t)o->c * wgs;
+  if (p.ok && (size_t)p.partial_rows() > rows) rows = (size_t)p.partial_rows();
   w.partial_rows = rows;
   w.partial_off = 0;
   w.vec_off = align_up(rows * (size_t)w.ld_ws * s, 256);
@@ -217,9 +215,9 @@ static int dense_iteration(const fsk_opts* o, const DenseWs& w, const char* K, i
   }
   if (ev) FSK_HIP(hipEventRecord(ev[0], st));
   if (flow == FSK_FLOW_FUSED) {
-    FSK_TRY(launch_fused(dt, plan, K, ld, n, m, c, a, v, u, u, partial, w.ld_ws, epi, o->eta, st, errvec));
+    FSK_TRY(launch_fused(dt, plan, K, ld, n, m, a, v, u, u, partial, w.ld_ws, epi, o->eta, st, errvec));
     if (ev) FSK_HIP(hipEventRecord(ev[1], st));
-    FSK_TRY(launch_colreduce(dt, partial, w.ld_ws, c * plan.wgs, 0, n, b, v, v, epi, o->eta, st));
+    FSK_TRY(launch_colreduce(dt, partial, w.ld_ws, plan.partial_rows(), 0, n, b, v, v, epi, o->eta, st));
     if (ev) FSK_HIP(hipEventRecord(ev[2], st));
     if (stream_launches) *stream_launches = 1;
     return FSK_OK;
@@ -788,14 +786,14 @@ int fsk_block_fused(const fsk_opts* opts, const void* K_slab, int64_t ldK, int32
                      opts->n);
   const size_t s = elem_size(opts->dtype);
   const int64_t ld_ws = (int64_t)align_up((size_t)opts->n, 64);
-  const size_t need = (size_t)plan.wgs * (size_t)ld_ws * s;
+  const size_t need = (size_t)plan.partial_rows() * (size_t)ld_ws * s;
   if (!workspace || ws_bytes < need)
     return set_error(FSK_EWORKSPACE, "fused block call needs %zu workspace bytes, got %zu", need, ws_bytes);
   if (!aligned16(workspace)) return set_error(FSK_EALIGN, "workspace is not 16-byte aligned");
   hipStream_t st = (hipStream_t)stream;
-  FSK_TRY(launch_fused(opts->dtype, plan, K_slab, ldK, opts->n, rows, 1, a_slab, v_full, u_slab,
+  FSK_TRY(launch_fused(opts->dtype, plan, K_slab, ldK, opts->n, rows, a_slab, v_full, u_slab,
                        u_slab, workspace, ld_ws, epi_of(opts), opts->eta, st));
-  return launch_colreduce(opts->dtype, workspace, ld_ws, plan.wgs, 0, opts->n, nullptr, nullptr,
+  return launch_colreduce(opts->dtype, workspace, ld_ws, plan.partial_rows(), 0, opts->n, nullptr, nullptr,
                           s_partial, kEpiProduct, 0.0, st);
 }
 

@@ -285,16 +285,25 @@ __device__ __forceinline__ double fsk_exp2(double x) { return (double)exp2f((flo
 // set.  v lives in LDS (up to 128 KiB of the 160 KiB), the thread's slice of the
 // column accumulator in registers.  Per group: partial dot products, butterfly
 // wave sums, one barrier, u = a ./ q, then acc += K_row * u from the same
-// registers.  K is read exactly once; row groups are dealt round-robin to the
-// workgroups of a block so every compute unit streams the same number of rows.
+// registers.  K is read exactly once.
+//
+// Rows are handed out in STRIPS: row block j (rows [j*m, (j+1)*m), Sec. 3.1) is cut into
+// strips of h rows (the last one shorter if h does not divide m); a strip is streamed by
+// `gb` workgroups (1 in production) which each leave one row of partial column sums for it.
+// h is a function of (n, dtype) alone when the block height m is a multiple of it, so the
+// strips -- hence every partial sum and the order the reduction adds them in -- are the
+// same for every block count c: the iterates of c blocks equal those of c = 1 bit for bit
+// (Proposition 1 holds in floating point too, not only in exact arithmetic).
 constexpr int kFusedWindow = 5;
 
 template <typename T, int VPT, int R, bool EXACT>
 __global__ __launch_bounds__(512) void fused_kernel(const T* __restrict__ K, int64_t ld, int n,
-                                                    int rows, int nblk, int gb, const T* marg,
+                                                    int m, int h, int spb, int nvb, int gb,
+                                                    int rotmul, const T* marg,
                                                     const T* __restrict__ vin, const T* old_u,
                                                     T* u_out, T* __restrict__ partial,
                                                     int64_t ld_ws, T eta, T* err_out) {
+  // m: rows per row block; h: rows per strip; spb: strips per block; nvb: strips in all.
   // err_out (may be null): |old_u_i (K v)_i - marg_i| per row, the row-marginal error term of
   // the scalings as they stood before this update (free: the product is at hand).
   // VPT = ceil(packs per row / 512), so the packs of slots i < VPT - 1 are whole and inside the
@@ -311,14 +320,12 @@ __global__ __launch_bounds__(512) void fused_kernel(const T* __restrict__ K, int
   T* red = v_lds + VPT * NT * W;              // [2][R][NW]
 
   const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
-  // The grid is `nb` teams of `gb` workgroups.  Team `team` owns the row blocks team,
-  // team + nb, ...; inside a block its row groups are dealt round-robin to the team's
-  // workgroups, so different blocks stream concurrently on disjoint sets of compute units.
+  // The grid is `nb` teams of `gb` workgroups.  Team `team` owns the strips team, team + nb,
+  // ...; inside a strip its row groups are dealt round-robin to the team's workgroups.
   const int G = gb, w = blockIdx.x % gb, team = blockIdx.x / gb, nb = gridDim.x / gb;
   const int nvec = (n + W - 1) / W, nvec_full = n / W;
-  const int groups = (rows + R - 1) / R;               // row groups per row block
-  const int spb = (groups + G - 1) / G;                // steps this workgroup spends on one block
-  const int total = ((nblk - team + nb - 1) / nb) * spb;  // steps over all blocks of the team
+  const int spv = ((h + R - 1) / R + G - 1) / G;          // steps this workgroup spends on one strip
+  const int total = ((nvb - team + nb - 1) / nb) * spv;   // steps over all strips of the team
   const bool geom = eta < T(0);
   const T et = geom ? -eta : eta;
   const bool damped = et < T(1);
@@ -356,26 +363,49 @@ __global__ __launch_bounds__(512) void fused_kernel(const T* __restrict__ K, int
 #pragma unroll
   for (int e = 0; e < W; ++e) tail_ok[e] = tail_vi * W + e < n;
 
-  // Teams start their sweep at different offsets inside their blocks (a rotation of the
-  // group index), which keeps the concurrent streams of different teams from marching
-  // through DRAM in lock step.
-  const int rot = (team * 17) % groups;
-  auto rotate = [&](int g) { return g < groups ? (g + rot) % groups : g; };
+  // Strip vb: rows [rbase, rbase + rows) of K; `groups` row groups, walked from a start
+  // that differs from strip to strip (a rotation of the group index by a multiple of the strip
+  // index), which keeps the concurrent streams from marching through DRAM in lock step.  The
+  // rotation is a function of the strip alone, so it does not disturb the equality over c.
+  // A workgroup's place in its walk: strip `vb`, step `gi` inside it, and the strip's geometry
+  // (recomputed only when the strip changes; no division on the per-step path).
+  struct Cursor { int vb, gi; int64_t rbase; int rows, groups, rot; };
+  auto enter_strip = [&](Cursor& c, int vb) {
+    c.vb = vb;
+    c.gi = 0;
+    if (vb >= nvb) return;  // past the end: never dereferenced
+    const int j = vb / spb, ls = vb - j * spb;
+    c.rbase = (int64_t)j * m + (int64_t)ls * h;
+    const int left = m - ls * h;
+    c.rows = left < h ? left : h;
+    c.groups = (c.rows + R - 1) / R;
+    c.rot = (int)(((unsigned)vb * (unsigned)rotmul) % (unsigned)c.groups);
+  };
+  auto next = [&](const Cursor& c) {
+    Cursor d = c;
+    if (++d.gi == spv) enter_strip(d, c.vb + nb);
+    return d;
+  };
+  auto group_of = [&](const Cursor& c) {  // >= c.groups: nothing to do at this step
+    const int g = w + c.gi * G;
+    if (g >= c.groups) return g;
+    const int x = g + c.rot;
+    return x >= c.groups ? x - c.groups : x;
+  };
 
-  // Step t of this workgroup is row group w + (t % spb)*G of row block t / spb.  Steps
-  // and rows past the end are clamped to the last valid one (a redundant, in-bounds
-  // read) and contribute nothing because their u is forced to 0 in process().
-  auto load_group = [&](Pack<T>(&buf)[R][VPT], T(&mg)[R], T(&od)[R], int t) {
-    t = t < total ? t : total - 1;
-    const int64_t rbase = (int64_t)(team + (t / spb) * nb) * rows;
-    const int g = rotate(w + (t % spb) * G);
+  // Groups past the end of a (short) strip are skipped by every thread alike; rows past the end
+  // inside the last group are clamped to the last valid one (a redundant, in-bounds read) and
+  // contribute nothing because their u is forced to 0 in process().
+  auto load_group = [&](Pack<T>(&buf)[R][VPT], T(&mg)[R], T(&od)[R], const Cursor& sp) {
+    const int g = group_of(sp);
+    if (g >= sp.groups) return;  // the same for every thread of the workgroup
 #pragma unroll
     for (int r = 0; r < R; ++r) {
       int row = g * R + r;
-      row = row < rows ? row : rows - 1;
-      const T* kp = K + (rbase + row) * ld + (int64_t)tid * W;
-      mg[r] = marg[rbase + row];
-      od[r] = (damped || err_out) ? old_u[rbase + row] : T(0);
+      row = row < sp.rows ? row : sp.rows - 1;
+      const T* kp = K + (sp.rbase + row) * ld + (int64_t)tid * W;
+      mg[r] = marg[sp.rbase + row];
+      od[r] = (damped || err_out) ? old_u[sp.rbase + row] : T(0);
 #pragma unroll
       for (int i = 0; i < VPT; ++i) {
         if (EXACT || i < VPT - 1) {
@@ -397,55 +427,62 @@ __global__ __launch_bounds__(512) void fused_kernel(const T* __restrict__ K, int
     }
   };
 
-  auto process = [&](Pack<T>(&buf)[R][VPT], T(&mg)[R], T(&od)[R], int t, int parity) {
-    const int blk = team + (t / spb) * nb;
-    const int64_t rbase = (int64_t)blk * rows;
-    const int g = rotate(w + (t % spb) * G);
-    T d[R];
+  int flip = 0;  // which of the two reduction slots the next processed group uses
+  auto process = [&](Pack<T>(&buf)[R][VPT], T(&mg)[R], T(&od)[R], const Cursor& sp) {
+    const int vb = sp.vb;
+    const int64_t rbase = sp.rbase;
+    const int rows = sp.rows;
+    const int g = group_of(sp);
+    if (g < sp.groups) {  // the same for every thread of the workgroup
+      T d[R];
 #pragma unroll
-    for (int r = 0; r < R; ++r) d[r] = T(0);
+      for (int r = 0; r < R; ++r) d[r] = T(0);
 #pragma unroll
-    for (int i = 0; i < VPT; ++i) {
-      const Pack<T> vv = load_pack(v_lds + (int64_t)(i * NT + tid) * W);
+      for (int i = 0; i < VPT; ++i) {
+        const Pack<T> vv = load_pack(v_lds + (int64_t)(i * NT + tid) * W);
 #pragma unroll
-      for (int r = 0; r < R; ++r)
+        for (int r = 0; r < R; ++r)
 #pragma unroll
-        for (int e = 0; e < W; ++e) d[r] = fma(buf[r][i].e[e], vv.e[e], d[r]);
-    }
-    T* slot = red + parity * R * NW;
-#pragma unroll
-    for (int r = 0; r < R; ++r) {
-      const T s = wave_sum(d[r]);
-      if (lane == 0) slot[r * NW + wave] = s;
-    }
-    __syncthreads();
-#pragma unroll
-    for (int r = 0; r < R; ++r) {
-      T q = T(0);
-#pragma unroll
-      for (int k = 0; k < NW; ++k) q += slot[r * NW + k];
-      const int row = g * R + r;
-      T ur = T(0);
-      if (row < rows) {
-        ur = mg[r] / q;
-        if (damped) {
-          if (sizeof(T) == 4 && geom)  // fp32 only: the fp64 log2 / exp2 would spill
-            ur = fsk_exp2(fma(T(1) - et, fsk_log2(od[r]), et * fsk_log2(ur)));
-          else
-            ur = (T(1) - et) * od[r] + et * ur;
-        }
-        if (tid == 0) {
-          if (err_out) err_out[rbase + row] = fsk_abs(od[r] * q - mg[r]);
-          u_out[rbase + row] = ur;
-        }
+          for (int e = 0; e < W; ++e) d[r] = fma(buf[r][i].e[e], vv.e[e], d[r]);
       }
+      // the slots alternate per PROCESSED group (not per step: a skipped step has no barrier),
+      // so a slot is rewritten only after a barrier that every reader of it has passed
+      T* slot = red + flip * R * NW;
+      flip ^= 1;
 #pragma unroll
-      for (int i = 0; i < VPT; ++i)
+      for (int r = 0; r < R; ++r) {
+        const T s = wave_sum(d[r]);
+        if (lane == 0) slot[r * NW + wave] = s;
+      }
+      __syncthreads();
 #pragma unroll
-        for (int e = 0; e < W; ++e) acc[i].e[e] = fma(buf[r][i].e[e], ur, acc[i].e[e]);
+      for (int r = 0; r < R; ++r) {
+        T q = T(0);
+#pragma unroll
+        for (int k = 0; k < NW; ++k) q += slot[r * NW + k];
+        const int row = g * R + r;
+        T ur = T(0);
+        if (row < rows) {
+          ur = mg[r] / q;
+          if (damped) {
+            if (sizeof(T) == 4 && geom)  // fp32 only: the fp64 log2 / exp2 would spill
+              ur = fsk_exp2(fma(T(1) - et, fsk_log2(od[r]), et * fsk_log2(ur)));
+            else
+              ur = (T(1) - et) * od[r] + et * ur;
+          }
+          if (tid == 0) {
+            if (err_out) err_out[rbase + row] = fsk_abs(od[r] * q - mg[r]);
+            u_out[rbase + row] = ur;
+          }
+        }
+#pragma unroll
+        for (int i = 0; i < VPT; ++i)
+#pragma unroll
+          for (int e = 0; e < W; ++e) acc[i].e[e] = fma(buf[r][i].e[e], ur, acc[i].e[e]);
+      }
     }
-    if (t % spb == spb - 1) {  // last step of a row block: hand over this block's contribution
-      T* prow = partial + ((int64_t)blk * G + w) * ld_ws;
+    if (sp.gi == spv - 1) {  // last step of a strip: hand over this strip's contribution
+      T* prow = partial + ((int64_t)vb * G + w) * ld_ws;
 #pragma unroll
       for (int i = 0; i < VPT; ++i) {
         const int vi = i * NT + tid;
@@ -457,50 +494,74 @@ __global__ __launch_bounds__(512) void fused_kernel(const T* __restrict__ K, int
   };
 
   // Two register sets alternate: while one group is being reduced the next one is
-  // already in flight, across row-block boundaries too.
+  // already in flight, across strip boundaries too.
   // The step after the last one is not fetched: at 8 steps per workgroup (n = 8192) a redundant
   // group would be an eighth of the kernel's reads.
-  load_group(bufA, mgA, odA, 0);
+  Cursor cA, cB;
+  enter_strip(cA, team);
+  load_group(bufA, mgA, odA, cA);
   for (int t = 0; t < total; t += 2) {
-    if (t + 1 < total) load_group(bufB, mgB, odB, t + 1);
-    process(bufA, mgA, odA, t, 0);
+    cB = next(cA);
+    if (t + 1 < total) load_group(bufB, mgB, odB, cB);
+    process(bufA, mgA, odA, cA);
     if (t + 1 >= total) break;
-    if (t + 2 < total) load_group(bufA, mgA, odA, t + 2);
-    process(bufB, mgB, odB, t + 1, 1);
+    cA = next(cB);
+    if (t + 2 < total) load_group(bufA, mgA, odA, cA);
+    process(bufB, mgB, odB, cB);
   }
 }
 
 // Rows held in one register set: 16 packs (64 VGPRs) per thread, at most 8 rows.
 constexpr int fused_rows_per_group(int vpt) { return 16 / vpt < 8 ? 16 / vpt : 8; }
 
-int fused_teams(const FusedPlan& plan, int c) {
-  int cus = device_cu_count();
-  if (cus < 1) cus = 1;
-  int teams = cus / plan.wgs;
-  if (teams < 1) teams = 1;
-  return teams < c ? teams : c;
-}
+// Workgroups the kernel is planned for, and the strips a row block is cut into when it has the
+// device to itself.  Constants, not the device's compute-unit count, so that the partial sums
+// (and the iterates) do not depend on the device either.  Large K: one workgroup per strip, 256
+// strips.  Below n = 8192 a strip per workgroup loses to fewer, taller strips shared by 16
+// workgroups each, which keep the concurrent reads in fewer, wider windows (n = 4096: 22.0 us
+// per iteration with 256 strips, 19.5 with 16; n = 3072: 17.6 against 16.6; n = 8192: 51.6
+// against 52.9); the iterates are then the same for every c that divides 16.
+constexpr int kFusedWorkgroups = 256;
+inline int fused_strips(int n) { return n >= 8192 ? 256 : 16; }
 
-FusedPlan fused_plan(int dtype, int n, int rows, int c) {
+FusedPlan fused_plan(int dtype, int n, int m, int c) {
   FusedPlan p{};
   const int W = pack_width(dtype);
   const int nvec = (n + W - 1) / W;
   const int vpt = (nvec + 511) / 512;
-  p.ok = vpt >= 1 && vpt <= 16 && rows > 0 && n > 0;
+  p.ok = vpt >= 1 && vpt <= 16 && m > 0 && n > 0 && c >= 1;
   if (!p.ok) return p;
   p.vpt = vpt;
   p.r = fused_rows_per_group(vpt);
-  p.groups = (rows + p.r - 1) / p.r;
-  // workgroups per row block: the device's compute units shared out among the c blocks
-  int per_block = device_cu_count() / (c < 1 ? 1 : c);
-  if (per_block < 1) per_block = 1;
-  p.wgs = p.groups < per_block ? p.groups : per_block;
+  const int strips = fused_strips(n);
+  // strip height: the block's share of the strips, in whole row groups.  With c | strips this
+  // is ceil(n / strips) rounded up to row groups, whatever c is.
+  const int share = strips / c > 1 ? strips / c : 1;
+  p.h = ((m + share - 1) / share + p.r - 1) / p.r * p.r;
+  p.spb = (m + p.h - 1) / p.h;
+  p.nvb = c * p.spb;
+  const int groups = (p.h + p.r - 1) / p.r;
+  const int gb = kFusedWorkgroups / strips;
+  p.gb = gb < groups ? gb : groups;
+  // staggered starts pay once a strip has enough row groups to spread over (measured: 615 against
+  // 618 us per iteration at n = 32768, 167 against 172 at 16384, 361 against 377 at 24576; at
+  // n = 8192, 8 groups per strip, 53.3 against 52.3)
+  p.rotmul = groups >= 16 ? 21 : 0;
   p.lds_bytes = (size_t)vpt * 512 * 16 + (size_t)2 * p.r * 8 * elem_size(dtype);
   return p;
 }
 
+// Teams launched: one per strip while the compute units last, else the teams take strips in turn.
+static int fused_teams(const FusedPlan& plan) {
+  int cus = device_cu_count();
+  if (cus < 1) cus = 1;
+  int teams = cus / plan.gb;
+  if (teams < 1) teams = 1;
+  return teams < plan.nvb ? teams : plan.nvb;
+}
+
 template <typename T, int VPT, bool EXACT>
-static int fused_typed(const FusedPlan& plan, const void* K, int64_t ld, int n, int rows, int c,
+static int fused_typed(const FusedPlan& plan, const void* K, int64_t ld, int n, int m,
                        const void* marg, const void* vin, const void* old_u, void* u_out,
                        void* partial, int64_t ld_ws, double eta, void* err_out, hipStream_t stream) {
   constexpr int R = fused_rows_per_group(VPT);
@@ -515,26 +576,25 @@ static int fused_typed(const FusedPlan& plan, const void* K, int64_t ld, int n, 
                                 hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024));
     if (dev >= 0 && dev < 64) attr_set[dev] = true;
   }
-  const int teams = fused_teams(plan, c);
-  dim3 grid(plan.wgs * teams), block(512);
-  hipLaunchKernelGGL(kern, grid, block, plan.lds_bytes, stream, (const T*)K, ld, n, rows, c,
-                     plan.wgs, (const T*)marg, (const T*)vin, (const T*)old_u, (T*)u_out, (T*)partial, ld_ws,
+  dim3 grid(plan.gb * fused_teams(plan)), block(512);
+  hipLaunchKernelGGL(kern, grid, block, plan.lds_bytes, stream, (const T*)K, ld, n, m, plan.h,
+                     plan.spb, plan.nvb, plan.gb, plan.rotmul, (const T*)marg, (const T*)vin, (const T*)old_u, (T*)u_out, (T*)partial, ld_ws,
                      (T)eta, (T*)err_out);
   FSK_LAUNCH_CHECK("fused_kernel");
   return FSK_OK;
 }
 
 template <typename T>
-static int fused_dispatch(const FusedPlan& plan, const void* K, int64_t ld, int n, int rows, int c,
+static int fused_dispatch(const FusedPlan& plan, const void* K, int64_t ld, int n, int m,
                           const void* marg, const void* vin, const void* old_u, void* u_out,
                           void* partial, int64_t ld_ws, double eta, void* err_out,
                           hipStream_t stream) {
   const bool exact = n == plan.vpt * 512 * Pack<T>::W;
 #define FSK_FUSED_CASE(V)                                                                         \
   case V:                                                                                         \
-    return exact ? fused_typed<T, V, true>(plan, K, ld, n, rows, c, marg, vin, old_u, u_out,      \
+    return exact ? fused_typed<T, V, true>(plan, K, ld, n, m, marg, vin, old_u, u_out,            \
                                            partial, ld_ws, eta, err_out, stream)                  \
-                 : fused_typed<T, V, false>(plan, K, ld, n, rows, c, marg, vin, old_u, u_out,     \
+                 : fused_typed<T, V, false>(plan, K, ld, n, m, marg, vin, old_u, u_out,           \
                                             partial, ld_ws, eta, err_out, stream)
   switch (plan.vpt) {
     FSK_FUSED_CASE(1);
@@ -558,8 +618,8 @@ static int fused_dispatch(const FusedPlan& plan, const void* K, int64_t ld, int 
 #undef FSK_FUSED_CASE
 }
 
-int launch_fused(int dtype, const FusedPlan& plan, const void* K, int64_t ld, int n, int rows,
-                 int c, const void* marg, const void* vin, const void* old_u, void* u_out,
+int launch_fused(int dtype, const FusedPlan& plan, const void* K, int64_t ld, int n, int m,
+                 const void* marg, const void* vin, const void* old_u, void* u_out,
                  void* partial, int64_t ld_ws, int epi, double eta, hipStream_t stream,
                  void* err_out) {
   if (!plan.ok) return set_error(FSK_EUNSUPPORTED, "fused kernel: n = %d does not fit in registers", n);
@@ -572,10 +632,10 @@ int launch_fused(int dtype, const FusedPlan& plan, const void* K, int64_t ld, in
     eta = -eta;  // the kernel's encoding of the geometric relaxation
   }
   return dtype == FSK_F64
-             ? fused_dispatch<double>(plan, K, ld, n, rows, c, marg, vin, old_u, u_out, partial,
-                                      ld_ws, eta, err_out, stream)
-             : fused_dispatch<float>(plan, K, ld, n, rows, c, marg, vin, old_u, u_out, partial,
-                                     ld_ws, eta, err_out, stream);
+             ? fused_dispatch<double>(plan, K, ld, n, m, marg, vin, old_u, u_out, partial, ld_ws,
+                                      eta, err_out, stream)
+             : fused_dispatch<float>(plan, K, ld, n, m, marg, vin, old_u, u_out, partial, ld_ws,
+                                     eta, err_out, stream);
 }
 
 // ================================================================= plan sums (Eq. 1)

@@ -64,25 +64,29 @@ int launch_colreduce(int dtype, const void* partial, int64_t ld_ws, int n_partia
                      const void* marg, const void* old, void* out, int epi, double eta,
                      hipStream_t stream);
 
-// Geometry of the fused one-pass kernel for a block of `rows` rows of an n-column K.
+// Geometry of the fused one-pass kernel: every row block of m rows is cut into strips of h rows;
+// a strip is streamed by gb workgroups, each of which leaves one row of partial column sums.
 struct FusedPlan {
   bool ok;          // false: n exceeds what a workgroup can hold in registers
   int vpt;          // 16-byte packs per thread per row
-  int r;            // rows processed together
-  int groups;       // ceil(rows / r)
-  int wgs;          // workgroups per row block (= partial rows per block)
+  int r;            // rows processed together (one row group)
+  int h;            // rows per strip (a multiple of r)
+  int spb;          // strips per row block
+  int nvb;          // strips in all (c * spb)
+  int gb;           // workgroups per strip
+  int rotmul;       // strip s starts its sweep at row group (s * rotmul) % groups
   size_t lds_bytes;
+  int partial_rows() const { return nvb * gb; }
 };
-// `c` row blocks of `rows` rows each share the device: each block gets cus/c workgroups.
-FusedPlan fused_plan(int dtype, int n, int rows, int c);
-// Number of workgroup teams launched (each team walks the blocks team, team+teams, ...).
-int fused_teams(const FusedPlan& plan, int c);
+// `c` row blocks of `m` rows each.  When m is a multiple of the strip height that c = 1 gets for
+// the same n, the strips (and so every partial sum) are the same for every c.
+FusedPlan fused_plan(int dtype, int n, int m, int c);
 
-// For each of `c` row blocks of `rows` rows (block b starts at row b*rows of K, marg, old_u,
-// u_out): u_out = epilogue(marg, K v, old_u) and partial[(b*wgs + w)][:] = contribution of the
-// rows workgroup w handled to K_block^T u_block.
-int launch_fused(int dtype, const FusedPlan& plan, const void* K, int64_t ld, int n, int rows,
-                 int c, const void* marg, const void* vin, const void* old_u, void* u_out,
+// For each strip: u_out = epilogue(marg, K v, old_u) on its rows and
+// partial[strip * gb + w][:] = contribution of the rows workgroup w handled to K^T u.
+// K, marg, old_u, u_out start at the first row of block 0.
+int launch_fused(int dtype, const FusedPlan& plan, const void* K, int64_t ld, int n, int m,
+                 const void* marg, const void* vin, const void* old_u, void* u_out,
                  void* partial, int64_t ld_ws, int epi, double eta, hipStream_t stream,
                  void* err_out = nullptr);
 

@@ -70,9 +70,10 @@ def test_cfg2_n8192_fp32_full_run(orc):
 
 @pytest.mark.parametrize("c", [2, 4, 8])
 def test_blocked_equals_centralised_cfg3_law(orc, c):
-    """Proposition 1 on the GPU: c row blocks give the centralised iterates.  Two-pass and
-    Algorithm-1 flows sum every column in the same order whatever c is, so they agree bit
-    for bit; the fused flow adds per-block contributions and agrees to rounding."""
+    """Proposition 1 on the GPU: c row blocks give the centralised iterates, bit for bit in every
+    flow.  Two-pass and Algorithm-1 flows sum every column over the same fixed row strips whatever
+    c is; the fused flow cuts every block into strips whose height depends on n alone (here
+    2048 / 16 = 128 rows, and 2048 / c is a multiple of it), so its partial sums are the same too."""
     w = workloads.make(3, n=2048)
     K = oracle_kernel(orc, w)
     uo, vo = orc.sinkhorn_blocked(K, w.a, w.b, 60, c, 1)
@@ -82,9 +83,35 @@ def test_blocked_equals_centralised_cfg3_law(orc, c):
         assert np.array_equal(u, u1) and np.array_equal(v, v1)
     uf1, vf1, _, _ = run_dense(K, w.a, w.b, 60, flow=api.FSK_FLOW_FUSED, c=1)
     uf, vf, _, _ = run_dense(K, w.a, w.b, 60, flow=api.FSK_FLOW_FUSED, c=c)
-    assert relerr(uf, uf1) <= 1e-5 and relerr(vf, vf1) <= 1e-5
+    assert np.array_equal(uf, uf1) and np.array_equal(vf, vf1)
     for u, v in ((u1, v1), (uf, vf)):
         assert relerr(u, uo) <= 1e-4 and relerr(v, vo) <= 1e-4
+
+
+@pytest.mark.parametrize("n,dtype,cs,aligned", [
+    (8192, np.float32, (2, 8, 64, 256), True),      # 256 strips of 32 rows: every c | 256 is aligned
+    (4096, np.float64, (2, 16), True),              # 16 strips of 256 rows
+    (4096, np.float32, (32,), False),               # blocks of 128 rows are shorter than a strip
+    (3000, np.float32, (3, 5), False),              # 1000 and 600 rows are not multiples of 192
+    (9000, np.float64, (4, 8), False),              # 36-row strips do not divide 2250 or 1125
+])
+def test_fused_flow_is_bitwise_independent_of_c_when_blocks_are_whole_strips(orc, n, dtype, cs, aligned):
+    """The fused flow's strips: when the block height is a multiple of the strip height that
+    c = 1 gets, every c gives the same bits; otherwise the strips differ and the iterates agree
+    to rounding only (and with the oracle at the usual bar either way)."""
+    w = workloads.make(3, n=n)
+    K = oracle_kernel(orc, w).astype(dtype)
+    a, b = w.a.astype(dtype), w.b.astype(dtype)
+    iters = 12
+    u1, v1, _, _ = run_dense(K, a, b, iters, flow=api.FSK_FLOW_FUSED, c=1)
+    uo, vo = orc.sinkhorn_dense(K, a, b, iters)
+    for c in cs:
+        u, v, _, _ = run_dense(K, a, b, iters, flow=api.FSK_FLOW_FUSED, c=c)
+        if aligned:
+            assert np.array_equal(u, u1) and np.array_equal(v, v1), c
+        else:
+            assert relerr(u, u1) <= 100 * np.finfo(dtype).eps and relerr(v, v1) <= 100 * np.finfo(dtype).eps
+        assert relerr(u, uo) <= TOL[np.dtype(dtype)] and relerr(v, vo) <= TOL[np.dtype(dtype)]
 
 
 def test_c_must_divide_n():
