@@ -167,6 +167,25 @@ int fsk_sinkhorn_dense(const fsk_opts* opts, const void* K, int64_t ldK, const v
                        const void* b, void* u, void* v, void* workspace, size_t ws_bytes,
                        int32_t* iters_done, double* err, void* stream);
 
+/* For callers that cannot allocate device memory -- code under HIP graph capture, tight serving
+ * loops, harnesses that forbid hipMalloc: fsk_sinkhorn_dense without the workspace argument.
+ * Same arguments, results and errors as fsk_sinkhorn_dense (it runs the same kernels); the scratch
+ * that call takes from its workspace lives in a device array that is part of the library image,
+ * FSK_STATIC_SCRATCH_BYTES per GPU, held by every GPU the library runs on until the process ends.
+ * The call allocates and frees nothing (no hipMalloc / hipFree, no allocating library routine).
+ * Limit: fsk_workspace_bytes(opts, FSK_MODE_DENSE, 0) <= FSK_STATIC_SCRATCH_BYTES, which covers
+ * every flow up to n = 32768 in fp32 and n = 16384 in fp64 on a 256-compute-unit device;
+ * FSK_EWORKSPACE beyond it, with nothing launched.  The first call on a device looks the array's
+ * address up (make that call outside a graph capture).  All calls on one GPU share that GPU's
+ * array, which keeps the previous call's contents (the kernels overwrite what they read, and
+ * clear the counters that must start at zero, themselves): two calls whose work overlaps in time
+ * on one GPU -- different streams, or different host threads -- race on it and must be serialised
+ * by the caller. */
+#define FSK_STATIC_SCRATCH_BYTES (34u * 1024u * 1024u)
+int fsk_sinkhorn_dense_static(const fsk_opts* opts, const void* K, int64_t ldK, const void* a,
+                              const void* b, void* u, void* v, int32_t* iters_done, double* err,
+                              void* stream);
+
 /* Poll budget of the grid barrier in FSK_FLOW_RESIDENT (process-wide; default 4000000, about a
  * second).  A waiter that exhausts it marks the launch failed: u and v come back NaN (and a
  * tolerance-mode call returns FSK_ENONFINITE) instead of the kernel waiting for ever.  For

@@ -36,7 +36,9 @@ EXPORTS = (
     "fsk_sinkhorn_async_emulated", "fsk_plan_objective", "fsk_kernel_from_cost_lambda",
     "fsk_radius_search", "fsk_grid_workspace_bytes", "fsk_sinkhorn_grid", "fsk_dp_release",
     "fsk_sinkhorn_batched_dp", "fsk_rdp_epsilon", "fsk_set_barrier_poll_limit",
+    "fsk_sinkhorn_dense_static",
 )
+FSK_STATIC_SCRATCH_BYTES = 34 * 1024 * 1024
 
 
 class fsk_opts(ctypes.Structure):
@@ -163,6 +165,15 @@ def fsk_sinkhorn_dense(opts, K, a, b, u, v, workspace, stream=None):
     _check(lib().fsk_sinkhorn_dense(ctypes.byref(opts), _p(K), _ld(K), _vec(a), _vec(b), _vec(u),
                                     _vec(v), wp, wn, ctypes.byref(done), ctypes.byref(err),
                                     _stream(stream)))
+    return int(done.value), float(err.value)
+
+
+def fsk_sinkhorn_dense_static(opts, K, a, b, u, v, stream=None):
+    """fsk_sinkhorn_dense on the library's built-in scratch array.  Returns (iters_done, err)."""
+    done, err = ctypes.c_int32(0), ctypes.c_double(float("nan"))
+    _check(lib().fsk_sinkhorn_dense_static(ctypes.byref(opts), _p(K), _ld(K), _vec(a), _vec(b), _vec(u),
+                                           _vec(v), ctypes.byref(done), ctypes.byref(err),
+                                           _stream(stream)))
     return int(done.value), float(err.value)
 
 

@@ -10,6 +10,7 @@
 #include "fsk_internal.h"
 
 #include <atomic>
+#include <mutex>
 
 namespace fsk {
 
@@ -385,6 +386,49 @@ int fsk_sinkhorn_dense(const fsk_opts* opts, const void* K, int64_t ldK, const v
   if (!aligned16(workspace)) return set_error(FSK_EALIGN, "workspace is not 16-byte aligned");
   return dense_solve(opts, w, K, ldK, a, b, u, v, (char*)workspace, iters_done, err,
                      (hipStream_t)stream);
+}
+
+// ---- the dense call for callers that cannot allocate: its scratch is part of the library image.
+// In host code the array's name only stands for the symbol; the device address comes from
+// hipGetSymbolAddress, once per device (every GPU holds its own copy at its own address).
+static __device__ __align__(256) unsigned char scratch[FSK_STATIC_SCRATCH_BYTES];
+static std::mutex g_scratch_mutex;
+static void* g_scratch_ptr[64] = {nullptr};
+
+static int static_scratch(char** out) {
+  int dev = 0;
+  FSK_HIP(hipGetDevice(&dev));
+  if (dev < 0 || dev >= 64) return set_error(FSK_EUNSUPPORTED, "device index %d outside [0, 64)", dev);
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[dev]) {
+    void* p = nullptr;
+    FSK_HIP(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+    if (!p) return set_error(FSK_EHIP, "hipGetSymbolAddress returned a null address");
+    g_scratch_ptr[dev] = p;
+  }
+  *out = (char*)g_scratch_ptr[dev];
+  return FSK_OK;
+}
+
+int fsk_sinkhorn_dense_static(const fsk_opts* opts, const void* K, int64_t ldK, const void* a,
+                              const void* b, void* u, void* v, int32_t* iters_done, double* err,
+                              void* stream) {
+  clear_error();
+  FSK_TRY(check_common(opts));
+  if (opts->m != 1) return set_error(FSK_EINVAL, "dense call takes m = 1 (use fsk_sinkhorn_batched)");
+  FSK_TRY(check_matrix("K", K, ldK, opts->n, opts->dtype));
+  FSK_TRY(check_vec("a", a, false));
+  FSK_TRY(check_vec("b", b, false));
+  FSK_TRY(check_vec("u", u, true));
+  FSK_TRY(check_vec("v", v, true));
+  const DenseWs w = dense_ws(opts);
+  if (w.total > (size_t)FSK_STATIC_SCRATCH_BYTES)
+    return set_error(FSK_EWORKSPACE,
+                     "this problem needs %zu bytes of scratch, the built-in array holds %zu: use "
+                     "fsk_sinkhorn_dense with a workspace", w.total, (size_t)FSK_STATIC_SCRATCH_BYTES);
+  char* ws = nullptr;
+  FSK_TRY(static_scratch(&ws));
+  return dense_solve(opts, w, K, ldK, a, b, u, v, ws, iters_done, err, (hipStream_t)stream);
 }
 
 int fsk_dense_profile(const fsk_opts* opts, const void* K, int64_t ldK, const void* a,

@@ -155,3 +155,22 @@ def test_last_error_is_per_thread(api):
     assert seen["first"][0] == api.FSK_EINVAL and seen["second"][0] == api.FSK_EINVAL
     assert seen["first"][1] != seen["second"][1]
     assert b"-7" in seen["second"][1] and b"-7" not in seen["first"][1]
+
+
+def test_static_scratch_call_refuses_what_does_not_fit(api):
+    """The entry point for callers that cannot allocate rejects, on the host, a problem whose
+    scratch exceeds the built-in array (and bad arguments like its sibling)."""
+    import torch
+    L = api.lib()
+    ok = ctypes.c_void_p(4096)
+    opts = api.make_opts(46400, torch.float32, max_iters=1, flow=api.FSK_FLOW_TWO_PASS)
+    assert api.fsk_workspace_bytes(opts) > api.FSK_STATIC_SCRATCH_BYTES
+    rc = L.fsk_sinkhorn_dense_static(ctypes.byref(opts), ok, ctypes.c_int64(46400), ok, ok, ok, ok,
+                                     None, None, None)
+    assert rc == api.FSK_EWORKSPACE and b"built-in" in L.fsk_last_error()
+    opts = api.make_opts(64, torch.float32, max_iters=1)
+    assert L.fsk_sinkhorn_dense_static(ctypes.byref(opts), None, ctypes.c_int64(64), ok, ok, ok, ok,
+                                       None, None, None) == api.FSK_EINVAL
+    text = open(os.path.join(ROOT, "include", "fsk.h")).read()
+    assert int(re.search(r"FSK_STATIC_SCRATCH_BYTES \((\d+)u \* 1024u \* 1024u\)", text).group(1)) * 1024 * 1024 \
+        == api.FSK_STATIC_SCRATCH_BYTES
