@@ -258,6 +258,24 @@ int fsk_sinkhorn_async_emulated(const fsk_opts* opts, const void* K, int64_t ldK
                                 const void* b, void* u, void* v, int32_t tau, int32_t sync_every,
                                 void* workspace, size_t ws_bytes, void* stream);
 
+/* ---- synchronous iteration with w local steps between collectives (Sec. 3.1, Remark "Local
+ * steps before communication"; appendix "Additional details on local steps"; the "optional"
+ * collectives of Sec. 3.2.1) on one device.  Client j (opts->c clients) owns rows/columns I_j and
+ * keeps its own view of u and v: its own slices as it last updated them, the peers' slices as of
+ * the last collective.  Iteration k = 1, 2, ...: every client forms u_{I_j} = a_j ./ (K_{I_j,:} v_view);
+ * if k is a multiple of w the slices of u are gathered; every client forms
+ * v_{I_j} = b_j ./ ((K_{:,I_j})^T u_view); if k is a multiple of w the slices of v are gathered.
+ * w = 1 is Algorithm 1 and gives the bits of FSK_FLOW_PAPER; c = 1 gives them for any w.
+ * Runs exactly opts->max_iters iterations, undamped (FSK_EUNSUPPORTED for a tolerance or a
+ * damping in opts); opts->flow is not used.  u, v are IN/OUT as in fsk_sinkhorn_dense and hold
+ * every client's own slice on return; a resumed call starts with all views equal, so runs are
+ * resumable at multiples of w.  Enqueue only (kernels and device-to-device copies).
+ * Workspace: fsk_local_steps_workspace_bytes(). */
+size_t fsk_local_steps_workspace_bytes(const fsk_opts* opts);
+int fsk_sinkhorn_local_steps(const fsk_opts* opts, const void* K, int64_t ldK, const void* a,
+                             const void* b, void* u, void* v, int32_t w, void* workspace,
+                             size_t ws_bytes, void* stream);
+
 /* ---- 2D block distribution on one device (appendix "HPC baseline: 2D block distribution
  * with row/column Allreduce") --------------------------------------------------------------
  * K is cut into a p_r x p_c grid of blocks K_ij (block rows of n/p_r rows, block columns of

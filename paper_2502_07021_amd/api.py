@@ -36,7 +36,7 @@ EXPORTS = (
     "fsk_sinkhorn_async_emulated", "fsk_plan_objective", "fsk_kernel_from_cost_lambda",
     "fsk_radius_search", "fsk_grid_workspace_bytes", "fsk_sinkhorn_grid", "fsk_dp_release",
     "fsk_sinkhorn_batched_dp", "fsk_rdp_epsilon", "fsk_set_barrier_poll_limit",
-    "fsk_sinkhorn_dense_static",
+    "fsk_sinkhorn_dense_static", "fsk_local_steps_workspace_bytes", "fsk_sinkhorn_local_steps",
 )
 FSK_STATIC_SCRATCH_BYTES = 34 * 1024 * 1024
 
@@ -73,6 +73,8 @@ def lib() -> ctypes.CDLL:
         L.fsk_workspace_bytes.argtypes = [ctypes.POINTER(fsk_opts), ctypes.c_int, ctypes.c_int]
         L.fsk_async_workspace_bytes.restype = ctypes.c_size_t
         L.fsk_async_workspace_bytes.argtypes = [ctypes.POINTER(fsk_opts), ctypes.c_int32, ctypes.c_int32]
+        L.fsk_local_steps_workspace_bytes.restype = ctypes.c_size_t
+        L.fsk_local_steps_workspace_bytes.argtypes = [ctypes.POINTER(fsk_opts)]
         L.fsk_grid_workspace_bytes.restype = ctypes.c_size_t
         L.fsk_grid_workspace_bytes.argtypes = [ctypes.POINTER(fsk_opts), ctypes.c_int32, ctypes.c_int32]
         _lib = L
@@ -225,6 +227,17 @@ def fsk_sinkhorn_async_emulated(opts, K, a, b, u, v, tau, sync_every, workspace,
     return _check(lib().fsk_sinkhorn_async_emulated(
         ctypes.byref(opts), _p(K), _ld(K), _vec(a), _vec(b), _vec(u), _vec(v), ctypes.c_int32(tau),
         ctypes.c_int32(sync_every), wp, wn, _stream(stream)))
+
+
+def fsk_local_steps_workspace_bytes(opts) -> int:
+    return int(lib().fsk_local_steps_workspace_bytes(ctypes.byref(opts)))
+
+
+def fsk_sinkhorn_local_steps(opts, K, a, b, u, v, w, workspace, stream=None) -> int:
+    wp, wn = _ws(workspace)
+    return _check(lib().fsk_sinkhorn_local_steps(
+        ctypes.byref(opts), _p(K), _ld(K), _vec(a), _vec(b), _vec(u), _vec(v), ctypes.c_int32(w),
+        wp, wn, _stream(stream)))
 
 
 class fsk_dp(ctypes.Structure):

@@ -203,7 +203,6 @@ static int dense_iteration(const fsk_opts* o, const DenseWs& w, const char* K, i
                            hipStream_t st, hipEvent_t* ev = nullptr,
                            int32_t* stream_launches = nullptr, char* errvec = nullptr) {
   const int n = o->n, c = o->c, m = n / c, dt = o->dtype;
-  const size_t s = elem_size(dt);
   const int epi = epi_of(o);
   void* partial = ws + w.partial_off;
   int flow = o->flow;
@@ -223,29 +222,17 @@ static int dense_iteration(const fsk_opts* o, const DenseWs& w, const char* K, i
     if (stream_launches) *stream_launches = 1;
     return FSK_OK;
   }
-  for (int j = 0; j < c; ++j) {  // worker j: u_{I_j} from its row slab and the shared v
-    const size_t off = (size_t)j * m;
-    FSK_TRY(launch_rowpass(dt, K + off * (size_t)ld * s, ld, n, m, v, a + off * s, u + off * s,
-                           u + off * s, epi, o->eta, st, errvec ? errvec + off * s : nullptr));
-  }
-  if (flow == FSK_FLOW_TWO_PASS) {
-    FSK_TRY(launch_colpartial(dt, K, ld, n, n, 0, n, u, partial, w.ld_ws, st));
-    if (ev) FSK_HIP(hipEventRecord(ev[1], st));
-    FSK_TRY(launch_colreduce(dt, partial, w.ld_ws, col_strips(n), 0, n, b, v, v, epi, o->eta, st));
-    if (ev) FSK_HIP(hipEventRecord(ev[2], st));
-    if (stream_launches) *stream_launches = c + 1;
-    return FSK_OK;
-  }
-  for (int j = 0; j < c; ++j) {  // worker j: r_{I_j} = (K_{:,I_j})^T u from its column slab
-    FSK_TRY(launch_colpartial(dt, K, ld, n, n, j * m, (j + 1) * m, u, partial, w.ld_ws, st));
-    FSK_TRY(launch_colreduce(dt, partial, w.ld_ws, col_strips(n), j * m, (j + 1) * m, b, v, v, epi,
-                             o->eta, st));
-  }
-  if (ev) {  // the column-slab launches alternate with their reductions: counted as one span
-    FSK_HIP(hipEventRecord(ev[1], st));
-    FSK_HIP(hipEventRecord(ev[2], st));
-  }
-  if (stream_launches) *stream_launches = 2 * c;
+  // every worker j at once (one grid, slab j = its row block): u_{I_j} from K_{I_j,:} and the shared v
+  FSK_TRY(launch_rowpass_slabs(dt, K, ld, n, m, c, v, nullptr, a, u, u, epi, o->eta, st, errvec));
+  // TWO_PASS: r = K^T u over all rows.  PAPER: worker j forms r_{I_j} = (K_{:,I_j})^T u from its
+  // column slab; on one device the c column slabs tile the whole column range and every column is
+  // summed on its own over the same row strips, so one launch over all columns IS the c slab
+  // products (launching them one by one gave the same bits at 16 KiB-wide, slower reads).
+  FSK_TRY(launch_colpartial(dt, K, ld, n, n, 0, n, u, partial, w.ld_ws, st));
+  if (ev) FSK_HIP(hipEventRecord(ev[1], st));
+  FSK_TRY(launch_colreduce(dt, partial, w.ld_ws, col_strips(n), 0, n, b, v, v, epi, o->eta, st));
+  if (ev) FSK_HIP(hipEventRecord(ev[2], st));
+  if (stream_launches) *stream_launches = 2;
   return FSK_OK;
 }
 
@@ -668,7 +655,6 @@ int fsk_sinkhorn_async_emulated(const fsk_opts* opts, const void* K, int64_t ldK
   const int slots = tau + sync_every + 1;
   char* ws = (char*)workspace;
   char* ring = ws + w.total;  // slot k: u at ring + 2k*vec, v at ring + (2k+1)*vec
-  char* view = ring + (size_t)2 * slots * vec;
   auto U = [&](int it) { return ring + (size_t)2 * (it % slots) * vec; };
   auto V = [&](int it) { return ring + ((size_t)2 * (it % slots) + 1) * vec; };
   const int epi = opts->damping == FSK_DAMP_ARITHMETIC ? kEpiDampArith : kEpiDivide;
@@ -681,20 +667,62 @@ int fsk_sinkhorn_async_emulated(const fsk_opts* opts, const void* K, int64_t ldK
     sidx = sidx <= 0 ? 0 : (sidx / sync_every) * sync_every;
     const char *su = U(sidx), *sv = V(sidx), *pu = U(t - 1), *pv = V(t - 1);
     char *nu = U(t), *nv = V(t);
-    for (int j = 0; j < c; ++j) {
-      const int lo = j * m, hi = (j + 1) * m;
-      const size_t off = (size_t)lo * s;
-      FSK_TRY(launch_assemble_view(dt, view, sv, pv, n, lo, hi, st));
-      FSK_TRY(launch_rowpass(dt, Kc + (size_t)lo * (size_t)ldK * s, ldK, n, m, view,
-                             (const char*)a + off, pu + off, nu + off, epi, eta, st));
-      FSK_TRY(launch_assemble_view(dt, view, su, nu, n, lo, hi, st));
-      FSK_TRY(launch_colpartial(dt, K, ldK, n, n, lo, hi, view, ws + w.partial_off, w.ld_ws, st));
-      FSK_TRY(launch_colreduce(dt, ws + w.partial_off, w.ld_ws, col_strips(n), lo, hi, b, pv, nv,
-                               epi, eta, st));
-    }
+    // all clients in one grid each: client j's row pass on its view of v (remote slices from the
+    // snapshot sv, own slice from the previous iteration pv), then its column-slab pass on its
+    // view of u (remote su, own slice just updated)
+    FSK_TRY(launch_rowpass_slabs(dt, Kc, ldK, n, m, c, sv, pv, a, pu, nu, epi, eta, st));
+    FSK_TRY(launch_colpartial_view(dt, Kc, ldK, n, su, nu, m, ws + w.partial_off, w.ld_ws, st));
+    FSK_TRY(launch_colreduce(dt, ws + w.partial_off, w.ld_ws, col_strips(n), 0, n, b, pv, nv, epi, eta, st));
   }
   FSK_HIP(hipMemcpyAsync(u, U(opts->max_iters), (size_t)n * s, hipMemcpyDeviceToDevice, st));
   FSK_HIP(hipMemcpyAsync(v, V(opts->max_iters), (size_t)n * s, hipMemcpyDeviceToDevice, st));
+  return FSK_OK;
+}
+
+// ------------------------------------------------------------- synchronous local steps
+size_t fsk_local_steps_workspace_bytes(const fsk_opts* opts) {
+  if (check_common(opts) != FSK_OK) return 0;
+  return align_up(dense_ws(opts).total, 256) + 2 * align_up((size_t)opts->n * elem_size(opts->dtype), 256);
+}
+
+int fsk_sinkhorn_local_steps(const fsk_opts* opts, const void* K, int64_t ldK, const void* a,
+                             const void* b, void* u, void* v, int32_t w_steps, void* workspace,
+                             size_t ws_bytes, void* stream) {
+  clear_error();
+  FSK_TRY(check_common(opts));
+  if (opts->m != 1) return set_error(FSK_EINVAL, "dense call takes m = 1");
+  if (w_steps < 1) return set_error(FSK_EINVAL, "w = %d local steps must be >= 1", w_steps);
+  if (opts->tol > 0.0) return set_error(FSK_EUNSUPPORTED, "the local-steps call runs a fixed number of iterations");
+  if (opts->damping != FSK_DAMP_NONE) return set_error(FSK_EUNSUPPORTED, "the synchronous variants are undamped");
+  FSK_TRY(check_matrix("K", K, ldK, opts->n, opts->dtype));
+  FSK_TRY(check_vec("a", a, false));
+  FSK_TRY(check_vec("b", b, false));
+  FSK_TRY(check_vec("u", u, true));
+  FSK_TRY(check_vec("v", v, true));
+  const size_t need = fsk_local_steps_workspace_bytes(opts);
+  if (!workspace || ws_bytes < need)
+    return set_error(FSK_EWORKSPACE, "local-steps call needs %zu workspace bytes, got %zu", need, ws_bytes);
+  if (!aligned16(workspace)) return set_error(FSK_EALIGN, "workspace is not 16-byte aligned");
+  hipStream_t st = (hipStream_t)stream;
+  const int n = opts->n, c = opts->c, m = n / c, dt = opts->dtype;
+  const size_t bytes = (size_t)n * elem_size(dt), vec = align_up(bytes, 256);
+  const DenseWs w = dense_ws(opts);
+  char* ws = (char*)workspace;
+  char* u_seen = ws + align_up(w.total, 256);  // the peers' slices as of the last Allgather of u
+  char* v_seen = u_seen + vec;                 // ... of v
+  FSK_HIP(hipMemcpyAsync(u_seen, u, bytes, hipMemcpyDeviceToDevice, st));  // "identical at all clients"
+  FSK_HIP(hipMemcpyAsync(v_seen, v, bytes, hipMemcpyDeviceToDevice, st));
+  for (int k = 1; k <= opts->max_iters; ++k) {
+    const bool collective = k % w_steps == 0;
+    // client j: q = K_{I_j,:} (its view of v), u_{I_j} = a_j ./ q -- all clients in one grid
+    FSK_TRY(launch_rowpass_slabs(dt, K, ldK, n, m, c, v_seen, v, a, nullptr, u, kEpiDivide, 1.0, st));
+    if (collective) FSK_HIP(hipMemcpyAsync(u_seen, u, bytes, hipMemcpyDeviceToDevice, st));  // Allgather u
+    // client j: r = (K_{:,I_j})^T (its view of u), v_{I_j} = b_j ./ r
+    FSK_TRY(launch_colpartial_view(dt, K, ldK, n, u_seen, u, m, ws + w.partial_off, w.ld_ws, st));
+    FSK_TRY(launch_colreduce(dt, ws + w.partial_off, w.ld_ws, col_strips(n), 0, n, b, nullptr, v,
+                             kEpiDivide, 1.0, st));
+    if (collective) FSK_HIP(hipMemcpyAsync(v_seen, v, bytes, hipMemcpyDeviceToDevice, st));  // Allgather v
+  }
   return FSK_OK;
 }
 

@@ -21,11 +21,18 @@ namespace fsk {
 // One workgroup of 256 threads takes ROWS consecutive rows; thread t walks the
 // 16-byte packs t, t+256, ... of each row, so a wave reads 1 KiB contiguous per
 // load and v is fetched once for all ROWS rows.
-template <typename T, int ROWS>
+// blockIdx.y = slab: the launch covers gridDim.y row slabs of `rows` rows each, slab y being
+// rows [y*rows, (y+1)*rows) of K, marg, old, out and err_out -- the row blocks of the c clients
+// (Sec. 3.1) in one grid.
+// VIEW: slab y is client y working on ITS view of the vector (Sec. 3.2.1, "a current global view
+// ... obtained from the previous collective"; Algorithm 3's cached slices): entry j comes from
+// `vown` inside the client's own index range [y*rows, (y+1)*rows) and from `vin` elsewhere.
+template <typename T, int ROWS, bool VIEW>
 __global__ __launch_bounds__(256) void rowpass_kernel(const T* __restrict__ K, int64_t ld, int n,
                                                       int rows, const T* __restrict__ vin,
-                                                      const T* marg, const T* old, T* out, int epi,
-                                                      T eta, T* err_out) {
+                                                      const T* __restrict__ vown, const T* marg,
+                                                      const T* old, T* out, int epi, T eta,
+                                                      T* err_out) {
   // err_out (may be null): |old_i * product_i - marg_i|, the row-marginal error term of the
   // scalings as they stood before this update (old is read before out is written: out may
   // alias old).
@@ -34,6 +41,9 @@ __global__ __launch_bounds__(256) void rowpass_kernel(const T* __restrict__ K, i
   const int tid = threadIdx.x;
   const int r_base = blockIdx.x * ROWS;
   const int nvec_full = n / W;
+  const int64_t slab0 = (int64_t)blockIdx.y * rows;  // first row of this slab
+  const int own_lo = (int)slab0, own_hi = own_lo + rows;
+  K += slab0 * ld;
 
   const T* rowp[ROWS];
 #pragma unroll
@@ -48,7 +58,15 @@ __global__ __launch_bounds__(256) void rowpass_kernel(const T* __restrict__ K, i
 
 #pragma unroll 2
   for (int c = tid; c < nvec_full; c += NT) {
-    const Pack<T> vv = load_pack(vin + (int64_t)c * W);
+    Pack<T> vv = load_pack(vin + (int64_t)c * W);
+    if (VIEW) {
+      const Pack<T> vo = load_pack(vown + (int64_t)c * W);
+#pragma unroll
+      for (int e = 0; e < W; ++e) {
+        const int j = c * W + e;
+        vv.e[e] = (j >= own_lo && j < own_hi) ? vo.e[e] : vv.e[e];
+      }
+    }
 #pragma unroll
     for (int r = 0; r < ROWS; ++r) {
       const Pack<T> kk = load_pack_stream(rowp[r] + (int64_t)c * W);
@@ -58,7 +76,7 @@ __global__ __launch_bounds__(256) void rowpass_kernel(const T* __restrict__ K, i
   }
   if (tid == 0) {  // ragged tail of fewer than W columns
     for (int j = nvec_full * W; j < n; ++j) {
-      const T vj = vin[j];
+      const T vj = (VIEW && j >= own_lo && j < own_hi) ? vown[j] : vin[j];
 #pragma unroll
       for (int r = 0; r < ROWS; ++r) acc[r] = fma(rowp[r][j], vj, acc[r]);
     }
@@ -75,26 +93,33 @@ __global__ __launch_bounds__(256) void rowpass_kernel(const T* __restrict__ K, i
   if (tid < ROWS) {
     const int row = r_base + tid;
     if (row < rows) {
+      const int64_t g = slab0 + row;
       T q = T(0);
 #pragma unroll
       for (int k = 0; k < NW; ++k) q += red[tid][k];
-      const T mg = epi_needs_marg(epi) ? marg[row] : T(0);
-      const T od = (epi_needs_old(epi) || err_out) ? old[row] : T(0);
-      if (err_out) err_out[row] = fsk_abs(od * q - marg[row]);
-      out[row] = apply_epilogue(epi, mg, q, od, eta);
+      const T mg = epi_needs_marg(epi) ? marg[g] : T(0);
+      const T od = (epi_needs_old(epi) || err_out) ? old[g] : T(0);
+      if (err_out) err_out[g] = fsk_abs(od * q - marg[g]);
+      out[g] = apply_epilogue(epi, mg, q, od, eta);
     }
   }
 }
 
 template <typename T>
-static int rowpass_typed(const void* K, int64_t ld, int n, int rows, const void* vin,
-                         const void* marg, const void* old, void* out, int epi, double eta,
-                         void* err_out, hipStream_t stream) {
-  if (rows <= 0) return FSK_OK;
+static int rowpass_typed(const void* K, int64_t ld, int n, int rows, int slabs, const void* vin,
+                         const void* vown, const void* marg, const void* old, void* out, int epi,
+                         double eta, void* err_out, hipStream_t stream) {
+  if (rows <= 0 || slabs <= 0) return FSK_OK;
   constexpr int ROWS = 4;
-  dim3 grid((rows + ROWS - 1) / ROWS), block(256);
-  hipLaunchKernelGGL((rowpass_kernel<T, ROWS>), grid, block, 0, stream, (const T*)K, ld, n, rows,
-                     (const T*)vin, (const T*)marg, (const T*)old, (T*)out, epi, (T)eta, (T*)err_out);
+  dim3 grid((rows + ROWS - 1) / ROWS, slabs), block(256);
+  if (vown)
+    hipLaunchKernelGGL((rowpass_kernel<T, ROWS, true>), grid, block, 0, stream, (const T*)K, ld, n,
+                       rows, (const T*)vin, (const T*)vown, (const T*)marg, (const T*)old, (T*)out,
+                       epi, (T)eta, (T*)err_out);
+  else
+    hipLaunchKernelGGL((rowpass_kernel<T, ROWS, false>), grid, block, 0, stream, (const T*)K, ld, n,
+                       rows, (const T*)vin, (const T*)nullptr, (const T*)marg, (const T*)old,
+                       (T*)out, epi, (T)eta, (T*)err_out);
   FSK_LAUNCH_CHECK("rowpass_kernel");
   return FSK_OK;
 }
@@ -102,9 +127,20 @@ static int rowpass_typed(const void* K, int64_t ld, int n, int rows, const void*
 int launch_rowpass(int dtype, const void* K, int64_t ld, int n, int rows, const void* vin,
                    const void* marg, const void* old, void* out, int epi, double eta,
                    hipStream_t stream, void* err_out) {
-  return dtype == FSK_F64
-             ? rowpass_typed<double>(K, ld, n, rows, vin, marg, old, out, epi, eta, err_out, stream)
-             : rowpass_typed<float>(K, ld, n, rows, vin, marg, old, out, epi, eta, err_out, stream);
+  return dtype == FSK_F64 ? rowpass_typed<double>(K, ld, n, rows, 1, vin, nullptr, marg, old, out,
+                                                  epi, eta, err_out, stream)
+                          : rowpass_typed<float>(K, ld, n, rows, 1, vin, nullptr, marg, old, out, epi,
+                                                 eta, err_out, stream);
+}
+
+int launch_rowpass_slabs(int dtype, const void* K, int64_t ld, int n, int rows, int slabs,
+                         const void* vin, const void* vown, const void* marg, const void* old,
+                         void* out, int epi, double eta, hipStream_t stream, void* err_out) {
+  if (slabs > 65535) return set_error(FSK_EUNSUPPORTED, "more than 65535 row slabs in one launch");
+  return dtype == FSK_F64 ? rowpass_typed<double>(K, ld, n, rows, slabs, vin, vown, marg, old, out,
+                                                  epi, eta, err_out, stream)
+                          : rowpass_typed<float>(K, ld, n, rows, slabs, vin, vown, marg, old, out,
+                                                 epi, eta, err_out, stream);
 }
 
 // ========================================================== column pass (generic)
@@ -113,10 +149,14 @@ int launch_rowpass(int dtype, const void* K, int64_t ld, int n, int rows, const 
 // K[i][cols] * u[i] over the rows of its strip in increasing i; the strip partition depends
 // only on the row count and every column is summed on its own, so a column-restricted launch
 // (and either PPT) sums every column exactly like an unrestricted one.
-template <typename T, int PPT>
+// VIEW: column j belongs to client j / um, who multiplies by ITS view of u: uown[i] for the
+// rows i of its own index range, u[i] elsewhere (the transpose action of Algorithm 1 / 3 on a
+// client's cached vector).  One launch then serves the column slabs of all clients.
+template <typename T, int PPT, bool VIEW>
 __global__ __launch_bounds__(256) void colpartial_kernel(const T* __restrict__ K, int64_t ld,
                                                          int rows, int vec_lo, int vec_hi,
                                                          const T* __restrict__ u,
+                                                         const T* __restrict__ uown, int um,
                                                          T* __restrict__ partial, int64_t ld_ws) {
   constexpr int W = Pack<T>::W;
   const int vc0 = vec_lo + blockIdx.x * 256 * PPT + threadIdx.x;
@@ -128,6 +168,13 @@ __global__ __launch_bounds__(256) void colpartial_kernel(const T* __restrict__ K
   int64_t off[PPT];
 #pragma unroll
   for (int k = 0; k < PPT; ++k) off[k] = (int64_t)(vc0 + k * 256 < vec_hi ? vc0 + k * 256 : vc0) * W;
+  int own_lo[PPT][W];  // first row of the index range of the client that owns the column
+  if (VIEW) {
+#pragma unroll
+    for (int k = 0; k < PPT; ++k)
+#pragma unroll
+      for (int e = 0; e < W; ++e) own_lo[k][e] = (int)((off[k] + e) / um) * um;
+  }
   Pack<T> acc[PPT];
 #pragma unroll
   for (int k = 0; k < PPT; ++k)
@@ -137,11 +184,15 @@ __global__ __launch_bounds__(256) void colpartial_kernel(const T* __restrict__ K
 #pragma unroll 4
   for (int i = i0; i < i1; ++i) {
     const T ui = u[i];
+    const T uo = VIEW ? uown[i] : T(0);
 #pragma unroll
     for (int k = 0; k < PPT; ++k) {
       const Pack<T> kk = load_pack_stream(kp + off[k]);
 #pragma unroll
-      for (int e = 0; e < W; ++e) acc[k].e[e] = fma(kk.e[e], ui, acc[k].e[e]);
+      for (int e = 0; e < W; ++e) {
+        const T ue = (VIEW && (unsigned)(i - own_lo[k][e]) < (unsigned)um) ? uo : ui;
+        acc[k].e[e] = fma(kk.e[e], ue, acc[k].e[e]);
+      }
     }
     kp += ld;
   }
@@ -150,9 +201,10 @@ __global__ __launch_bounds__(256) void colpartial_kernel(const T* __restrict__ K
     if (vc0 + k * 256 < vec_hi) store_pack(partial + (int64_t)s * ld_ws + off[k], acc[k]);
 }
 
-template <typename T>
+template <typename T, bool VIEW>
 static int colpartial_typed(const void* K, int64_t ld, int n, int rows, int c0, int c1,
-                            const void* u, void* partial, int64_t ld_ws, hipStream_t stream) {
+                            const void* u, const void* uown, int um, void* partial, int64_t ld_ws,
+                            hipStream_t stream) {
   constexpr int W = Pack<T>::W;
   if (rows <= 0 || c1 <= c0) return FSK_OK;
   const int vec_lo = c0 / W, vec_hi = (c1 + W - 1) / W;
@@ -162,12 +214,12 @@ static int colpartial_typed(const void* K, int64_t ld, int n, int rows, int c0, 
   // wide and tall enough for >= 1024 workgroups of the wide shape: 16 KiB of every row per workgroup
   if (nvec >= 4096 && (int64_t)((nvec + 1023) / 1024) * col_strips(rows) >= 1024) {
     dim3 grid((nvec + 1023) / 1024, col_strips(rows));
-    hipLaunchKernelGGL((colpartial_kernel<T, 4>), grid, block, 0, stream, (const T*)K, ld, rows,
-                       vec_lo, vec_hi, (const T*)u, (T*)partial, ld_ws);
+    hipLaunchKernelGGL((colpartial_kernel<T, 4, VIEW>), grid, block, 0, stream, (const T*)K, ld, rows,
+                       vec_lo, vec_hi, (const T*)u, (const T*)uown, um, (T*)partial, ld_ws);
   } else {
     dim3 grid((nvec + 255) / 256, col_strips(rows));
-    hipLaunchKernelGGL((colpartial_kernel<T, 1>), grid, block, 0, stream, (const T*)K, ld, rows,
-                       vec_lo, vec_hi, (const T*)u, (T*)partial, ld_ws);
+    hipLaunchKernelGGL((colpartial_kernel<T, 1, VIEW>), grid, block, 0, stream, (const T*)K, ld, rows,
+                       vec_lo, vec_hi, (const T*)u, (const T*)uown, um, (T*)partial, ld_ws);
   }
   FSK_LAUNCH_CHECK("colpartial_kernel");
   return FSK_OK;
@@ -175,8 +227,18 @@ static int colpartial_typed(const void* K, int64_t ld, int n, int rows, int c0, 
 
 int launch_colpartial(int dtype, const void* K, int64_t ld, int n, int rows, int c0, int c1,
                       const void* u, void* partial, int64_t ld_ws, hipStream_t stream) {
-  return dtype == FSK_F64 ? colpartial_typed<double>(K, ld, n, rows, c0, c1, u, partial, ld_ws, stream)
-                          : colpartial_typed<float>(K, ld, n, rows, c0, c1, u, partial, ld_ws, stream);
+  return dtype == FSK_F64
+             ? colpartial_typed<double, false>(K, ld, n, rows, c0, c1, u, nullptr, 1, partial, ld_ws, stream)
+             : colpartial_typed<float, false>(K, ld, n, rows, c0, c1, u, nullptr, 1, partial, ld_ws, stream);
+}
+
+int launch_colpartial_view(int dtype, const void* K, int64_t ld, int n, const void* u,
+                           const void* uown, int um, void* partial, int64_t ld_ws,
+                           hipStream_t stream) {
+  if (um < 1) return set_error(FSK_EINVAL, "client block of %d columns", um);
+  return dtype == FSK_F64
+             ? colpartial_typed<double, true>(K, ld, n, n, 0, n, u, uown, um, partial, ld_ws, stream)
+             : colpartial_typed<float, true>(K, ld, n, n, 0, n, u, uown, um, partial, ld_ws, stream);
 }
 
 // ======================================================= partial sums -> result
@@ -739,29 +801,6 @@ int launch_plan_rows(int dtype, const void* K, int64_t ldK, const void* C, int64
                        (const float*)C, ldC, n, (const float*)u, (const float*)v, (const float*)l,
                        (float*)rows, stride);
   FSK_LAUNCH_CHECK("plan_rows_kernel");
-  return FSK_OK;
-}
-
-// ================================================================= cached view of a vector
-template <typename T>
-__global__ __launch_bounds__(256) void assemble_view_kernel(T* __restrict__ dst,
-                                                            const T* __restrict__ remote,
-                                                            const T* __restrict__ own, int n, int lo,
-                                                            int hi) {
-  const int i = blockIdx.x * 256 + threadIdx.x;
-  if (i < n) dst[i] = (i >= lo && i < hi) ? own[i] : remote[i];
-}
-
-int launch_assemble_view(int dtype, void* dst, const void* remote, const void* own, int n, int lo,
-                         int hi, hipStream_t stream) {
-  dim3 grid((n + 255) / 256), block(256);
-  if (dtype == FSK_F64)
-    hipLaunchKernelGGL((assemble_view_kernel<double>), grid, block, 0, stream, (double*)dst,
-                       (const double*)remote, (const double*)own, n, lo, hi);
-  else
-    hipLaunchKernelGGL((assemble_view_kernel<float>), grid, block, 0, stream, (float*)dst,
-                       (const float*)remote, (const float*)own, n, lo, hi);
-  FSK_LAUNCH_CHECK("assemble_view_kernel");
   return FSK_OK;
 }
 

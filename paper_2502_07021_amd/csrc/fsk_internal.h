@@ -54,6 +54,22 @@ int launch_rowpass(int dtype, const void* K, int64_t ld, int n, int rows, const 
                    const void* marg, const void* old, void* out, int epi, double eta,
                    hipStream_t stream, void* err_out = nullptr);
 
+// The same for `slabs` row slabs of `rows` rows each in ONE grid (slab y = rows [y*rows,
+// (y+1)*rows) of K, marg, old, out, err_out): the row passes of the c clients of Sec. 3.1.
+// vown != NULL: client y multiplies by its own view of the vector -- vown[j] on its own index
+// range [y*rows, (y+1)*rows), vin[j] elsewhere (needs slabs * rows == n).
+int launch_rowpass_slabs(int dtype, const void* K, int64_t ld, int n, int rows, int slabs,
+                         const void* vin, const void* vown, const void* marg, const void* old,
+                         void* out, int epi, double eta, hipStream_t stream,
+                         void* err_out = nullptr);
+
+// The column pass of all clients in one launch, each on its own view of u: column j is
+// multiplied by uown[i] on the rows i of the index range of its owner (client j / um) and by
+// u[i] elsewhere.  Covers all n rows and columns; partial has col_strips(n) rows.
+int launch_colpartial_view(int dtype, const void* K, int64_t ld, int n, const void* u,
+                           const void* uown, int um, void* partial, int64_t ld_ws,
+                           hipStream_t stream);
+
 // partial[s][j] = sum over rows of strip s of K[i][j] u[i], for the 16-byte column packs that
 // intersect [c0, c1).  partial has col_strips(rows) rows of ld_ws elements.
 int launch_colpartial(int dtype, const void* K, int64_t ld, int n, int rows, int c0, int c1,
@@ -97,10 +113,6 @@ int launch_fused(int dtype, const FusedPlan& plan, const void* K, int64_t ld, in
 int launch_plan_rows(int dtype, const void* K, int64_t ldK, const void* C, int64_t ldC, int n,
                      const void* u, const void* v, const void* l, void* rows, int64_t stride,
                      hipStream_t stream);
-
-// dst[i] = own[i] for lo <= i < hi, remote[i] otherwise (a client's cached view of a vector).
-int launch_assemble_view(int dtype, void* dst, const void* remote, const void* own, int n, int lo,
-                         int hi, hipStream_t stream);
 
 // out (one double) = sum of x[0..n) accumulated in fp64 in a fixed order.
 int launch_sum_to_double(int dtype, const void* x, int n, double* out, hipStream_t stream,
