@@ -10,8 +10,9 @@ Prints ONE JSON line: iterations/s (metric), the roofline of the dominant kernel
 with HIP events on the launch stream, and the CPU oracle timed on this machine's host cores on a
 bounded sample of the same workload.
 
-`--workload cfg1|cfg2|cfg4|cfg5` times the other configurations in the same format (secondary
-lines; the driver's default run is cfg3).
+The default run also times short fixed runs of the other four configurations and reports them
+in a `secondary` object of the same line (rate, time per step, roofline of the dominant kernel);
+`--workload cfg1|cfg2|cfg4|cfg5` prints a full line of its own for one of them.
 """
 from __future__ import annotations
 
@@ -112,7 +113,8 @@ def bench_dense(args, cfg):
 
     # dominant kernel alone, same launch configuration, HIP events on the launch stream
     stream_ms, other_ms, launches = api.fsk_dense_profile(opts, K, a, b, u, v, ws, args.profile_reps)
-    spread = repeats(lambda: run(steps), steps, dt)
+    light = getattr(args, "light", False)      # a secondary entry of the default line
+    spread = None if light else repeats(lambda: run(steps), steps, dt)
     # K read once per iteration (fused), twice (two-pass flows), or once per CALL (resident:
     # no HBM roofline applies; the figure below then only says how far from HBM-bound it is)
     alg_bytes = float(n) * n * esz * (2 if args.flow in (1, 2) else 1)
@@ -127,14 +129,20 @@ def bench_dense(args, cfg):
                 "traffic": traffic_from_profile("dense_fused_cfg3_pmc.txt") if headline
                 else traffic_from_profile("dense_fused_cfg2_pmc.txt")
                 if (cfg == 2 and args.flow == 0 and n == 8192 and c == 1) else None,
+                "traffic_source": ("profiles/dense_fused_cfg3_pmc.txt" if headline else
+                                   "profiles/dense_fused_cfg2_pmc.txt"
+                                   if (cfg == 2 and args.flow == 0 and n == 8192 and c == 1) else None),
                 "kernel": {0: "fused_kernel", 3: "resident_kernel"}.get(args.flow, "rowpass_kernel+colpartial_kernel"),
                 "kernel_ms": stream_ms, "launches_per_step": launches,
                 "algorithmic_bytes_per_step": alg_bytes, "other_kernels_ms": other_ms}
     if args.flow == 3:
         roofline["note"] = roofline_note
 
+    if roofline["traffic_source"]:
+        roofline["traffic_source"] += (": HBM bytes per launch from the committed rocprofv3 --pmc runs "
+                                       "(FETCH_SIZE, WRITE_SIZE) of this command, not a counter of this run")
     extra = {}
-    if c != 1:   # the same problem with c = 1 (the iterates the blocked run must reproduce)
+    if c != 1 and not light:   # the same problem with c = 1 (the iterates the blocked run must reproduce)
         o1 = api.make_opts(n, td, c=1, max_iters=steps, flow=args.flow)
         ws1 = api.alloc_workspace(o1, api.FSK_MODE_DENSE)
         u.fill_(1.0); v.fill_(1.0)
@@ -157,8 +165,9 @@ def bench_dense(args, cfg):
                                f"flow={['fused', 'two_pass', 'algorithm1', 'resident'][args.flow]}",
                    "n": n, "c": c, "eps": w.eps, "iterations": steps},
         "roofline": roofline,
-        "repeats": spread,
     }
+    if spread:
+        out["repeats"] = spread
     out.update(extra)
     if not args.no_cpu_baseline:
         del K
@@ -288,6 +297,9 @@ def bench_batched(args):
                      "unit": "TFLOP/s", "frac": achieved / peak,
                      "traffic": traffic_from_profile("batched_mfma_f64_cfg5.txt" if f64 else "batched_mfma_cfg5.txt")
                      if (n == 16384 and m == 64) else None,
+                     "traffic_source": (("profiles/batched_mfma_f64_cfg5.txt" if f64 else "profiles/batched_mfma_cfg5.txt")
+                                        + ": committed rocprofv3 --pmc summary, not a counter of this run")
+                     if (n == 16384 and m == 64) else None,
                      "kernel": ("batched_prod_f64_kernel" if f64 else "batched_prod_wide_kernel")
                                + " (both products)",
                      "kernel_ms": launch_ms, "launches_per_step": 2,
@@ -315,6 +327,32 @@ def bench_batched(args):
     return out
 
 
+def secondary(args):
+    """Short fixed runs of the other four configurations, for the default line's `secondary`."""
+    import torch
+    plan = (("cfg1", 1, 200, 20, 50), ("cfg2", 2, 500, 20, 128), ("cfg4", 4, 20, 2, 10), ("cfg5", 5, 100, 5, 50))
+    keep = ("bound", "achieved", "peak", "unit", "frac", "kernel", "kernel_ms", "launches_per_step",
+            "traffic", "traffic_source", "note")
+    res = {}
+    for name, cfg, steps, warmup, reps in plan:
+        a2 = argparse.Namespace(**vars(args))
+        a2.workload, a2.n, a2.c, a2.m, a2.dtype = name, None, None, None, "f32"
+        a2.flow = 3 if cfg == 1 else 0
+        a2.steps, a2.warmup, a2.profile_reps = steps, warmup, reps
+        a2.no_cpu_baseline, a2.light = True, True
+        try:
+            d = bench_log(a2) if cfg == 4 else bench_batched(a2) if cfg == 5 else bench_dense(a2, cfg)
+        except Exception as exc:      # a failed secondary must not take the headline with it
+            res[name] = {"error": f"{type(exc).__name__}: {exc}"}
+            continue
+        res[name] = {"workload": d["config"]["workload"], "iterations_per_s": d["value"],
+                     "ms_per_step": d["ms_per_step"], "steps": d["steps"], "warmup": d["warmup"],
+                     "dtype": d["dtype"],
+                     "roofline": {k: d["roofline"][k] for k in keep if d["roofline"].get(k) is not None}}
+        torch.cuda.empty_cache()
+    return res
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -331,6 +369,8 @@ def main() -> int:
                     help="dense: 0 fused, 1 two-pass, 2 Algorithm 1, 3 register-resident "
                          "(default: 3 for cfg1, 0 otherwise)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-secondary", action="store_true",
+                    help="headline run only: leave out the short runs of configurations 1, 2, 4, 5")
     ap.add_argument("--profile-reps", type=int, default=50)
     args = ap.parse_args()
     if args.gpus != 1:
@@ -339,14 +379,20 @@ def main() -> int:
         return 2
     import torch
     torch.cuda.set_device(0)
+    headline = (args.workload == "cfg3" and args.n is None and args.c is None and args.flow is None)
     if args.flow is None:
         args.flow = 3 if args.workload == "cfg1" and args.n in (None, 512) else 0
+    sec = None
+    if headline and not args.no_secondary:
+        sec = secondary(args)      # before the headline: its CPU leg would leave the GPU idle first
     if args.workload == "cfg4":
         out = bench_log(args)
     elif args.workload == "cfg5":
         out = bench_batched(args)
     else:
         out = bench_dense(args, int(args.workload[3]))
+    if sec is not None:
+        out["secondary"] = sec
     print(json.dumps(out))
     return 0
 

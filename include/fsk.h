@@ -405,8 +405,10 @@ int fsk_rdp_epsilon(double clip, double sigma, int64_t releases, double delta, c
 /* ---- measurement helpers -----------------------------------------------------------------
  * fsk_dense_profile runs `reps` iterations exactly as fsk_sinkhorn_dense does in
  * fixed-iteration mode (same kernels, same launch shapes, u and v advance), but brackets the
- * launches of each iteration with HIP events recorded on `stream` and synchronises after each
- * iteration.  Outputs (host): stream_ms = average time per iteration spent in the kernels that
+ * launches of each iteration with HIP events recorded on `stream`; iterations are enqueued back
+ * to back and the stream is synchronised once per 64 of them, so a span holds a launch and the
+ * hand-over from the launch before it, not the latency of a launch into an idle queue.
+ * Outputs (host): stream_ms = average time per iteration spent in the kernels that
  * stream K (the HBM-bound ones), other_ms = average time per iteration in the small reduction
  * kernels, stream_launches = number of K-streaming launches per iteration.  */
 int fsk_dense_profile(const fsk_opts* opts, const void* K, int64_t ldK, const void* a,

@@ -457,21 +457,36 @@ int fsk_dense_profile(const fsk_opts* opts, const void* K, int64_t ldK, const vo
     if (stream_launches) *stream_launches = 1;
     return FSK_OK;
   }
-  for (int it = 0; it < reps && rc == FSK_OK; ++it) {
-    rc = dense_iteration(opts, w, (const char*)K, ldK, (const char*)a, (const char*)b, (char*)u,
-                         (char*)v, (char*)workspace, st, ev, &launches);
-    if (rc != FSK_OK) break;
-    if (hipEventSynchronize(ev[2]) != hipSuccess) { rc = set_error(FSK_EHIP, "hipEventSynchronize failed"); break; }
-    float ms01 = 0.f, ms12 = 0.f;
-    if (hipEventElapsedTime(&ms01, ev[0], ev[1]) != hipSuccess ||
-        hipEventElapsedTime(&ms12, ev[1], ev[2]) != hipSuccess) {
-      rc = set_error(FSK_EHIP, "hipEventElapsedTime failed");
-      break;
-    }
-    t_stream += ms01;
-    t_other += ms12;
-  }
+  // Iterations are enqueued back to back in batches, every one with its own three events, and the
+  // stream is synchronised once per batch: an event then stamps the moment the launch before it
+  // drained, and the span ev[0] -> ev[1] is the K-streaming launch plus one hand-over between
+  // kernels (about a microsecond), not the latency of a launch into an idle queue.
   for (int k = 0; k < 3; ++k) (void)hipEventDestroy(ev[k]);
+  constexpr int kBatch = 64;
+  hipEvent_t evs[3 * kBatch];
+  int made = 0;
+  for (; made < 3 * kBatch; ++made)
+    if (hipEventCreate(&evs[made]) != hipSuccess) { rc = set_error(FSK_EHIP, "hipEventCreate failed"); break; }
+  for (int done = 0; done < reps && rc == FSK_OK;) {
+    const int nb = reps - done < kBatch ? reps - done : kBatch;
+    for (int it = 0; it < nb && rc == FSK_OK; ++it)
+      rc = dense_iteration(opts, w, (const char*)K, ldK, (const char*)a, (const char*)b, (char*)u,
+                           (char*)v, (char*)workspace, st, evs + 3 * it, &launches);
+    if (rc != FSK_OK) break;
+    if (hipStreamSynchronize(st) != hipSuccess) { rc = set_error(FSK_EHIP, "hipStreamSynchronize failed"); break; }
+    for (int it = 0; it < nb; ++it) {
+      float ms01 = 0.f, ms12 = 0.f;
+      if (hipEventElapsedTime(&ms01, evs[3 * it], evs[3 * it + 1]) != hipSuccess ||
+          hipEventElapsedTime(&ms12, evs[3 * it + 1], evs[3 * it + 2]) != hipSuccess) {
+        rc = set_error(FSK_EHIP, "hipEventElapsedTime failed");
+        break;
+      }
+      t_stream += ms01;
+      t_other += ms12;
+    }
+    done += nb;
+  }
+  for (int k = 0; k < made; ++k) (void)hipEventDestroy(evs[k]);
   if (rc != FSK_OK) return rc;
   if (stream_ms) *stream_ms = t_stream / reps;
   if (other_ms) *other_ms = t_other / reps;

@@ -42,3 +42,22 @@ def test_bench_line(args, bound, peak):
     if "--no-cpu-baseline" not in args:
         c = d["cpu_baseline"]
         assert c["kind"] == "oracle" and c["value"] > 0 and c["cores"] >= 1 and c["sample"]
+
+
+def test_default_line_carries_the_other_four_configurations():
+    """The driver's command: the headline (configuration 3) with `secondary` holding short runs of
+    configurations 1, 2, 4, 5, each with its rate and the roofline of its dominant kernel."""
+    d = _run("--steps", "20", "--warmup", "5")
+    assert COMMON <= set(d) and d["config"]["n"] == 32768 and d["config"]["c"] == 8
+    assert d["roofline"]["bound"] == "hbm" and d["roofline"]["frac"] > 0.8
+    assert "profiles/" in d["roofline"]["traffic_source"]
+    assert d["cpu_baseline"]["kind"] == "oracle"
+    sec = d["secondary"]
+    assert set(sec) == {"cfg1", "cfg2", "cfg4", "cfg5"}
+    for name, bound in (("cfg1", "hbm"), ("cfg2", "hbm"), ("cfg4", "alu"), ("cfg5", "mfma")):
+        e = sec[name]
+        assert "error" not in e, e
+        assert e["iterations_per_s"] > 0 and e["ms_per_step"] > 0 and name in e["workload"]
+        r = e["roofline"]
+        assert r["bound"] == bound and 0 < r["frac"] < 1.0 and r["kernel_ms"] > 0
+        assert abs(r["frac"] - r["achieved"] / r["peak"]) < 1e-9
