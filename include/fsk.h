@@ -324,7 +324,10 @@ int fsk_block_fused(const fsk_opts* opts, const void* K_slab, int64_t ldK, int32
  * FSK_F32: the cost term runs in fp64, exponentials and their sums in fp32.  FSK_F64: everything in
  * fp64.  1 <= d <= 4096 (FSK_EUNSUPPORTED outside); d <= 32 runs the kernel that keeps a row's
  * coordinates in registers, larger d a generic, slower one.  iters_done / err as in
- * fsk_sinkhorn_dense. */
+ * fsk_sinkhorn_dense.  Within one call the potentials are carried in fp64 and f, g receive their
+ * rounding to the interface type; a later call starts from those rounded values, so with FSK_F32
+ * a run split into several calls agrees with the same run in one call to fp32 rounding of f, g
+ * (about 1e-7 |f|, i.e. up to ~1e-5 in |f|/eps at eps = 0.01), not bit for bit. */
 int fsk_sinkhorn_log_points(const fsk_opts* opts, const void* x, const void* y, int d, double eps,
                             const void* a, const void* b, void* f, void* g, void* workspace,
                             size_t ws_bytes, int32_t* iters_done, double* err, void* stream);
@@ -335,7 +338,10 @@ int fsk_sinkhorn_log_points(const fsk_opts* opts, const void* x, const void* y, 
  * opts->max_iters iterations (FSK_EUNSUPPORTED for opts->tol > 0: see the _tol call below).
  * FSK_F32 (fp32 MFMA) or FSK_F64 (fp64 MFMA; needs the whole workspace, FSK_EWORKSPACE
  * otherwise).  Any m >= 1: the columns go through the kernels in groups of up to 64, one pass
- * over K per group and product, so the time grows with ceil(m / 64).
+ * over K per group and product, so the time grows with ceil(m / 64).  Which kernel forms K V
+ * (hence the order of its sums) depends on (n, m) and on whether the workspace has room for the
+ * transposed copy, never on the iteration count: a run split into several calls with the same
+ * workspace gives the bits of the run in one call.
  * Workspace: fsk_workspace_bytes(opts, FSK_MODE_BATCHED, 0) holds the partial products of all
  * groups and a transposed copy of K; with at least the partial products (the size the error
  * message of a too-small workspace states) an undamped call still runs, with a slower kernel

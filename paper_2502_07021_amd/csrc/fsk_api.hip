@@ -330,7 +330,12 @@ static int dense_solve(const fsk_opts* opts, const DenseWs& w, const void* K, in
         FSK_HIP(hipMemcpyAsync(&e, scalar, sizeof(double), hipMemcpyDeviceToHost, st));
         FSK_HIP(hipStreamSynchronize(st));
         if (l2) e = sqrt(e);
-        if (!std::isfinite(e)) return nonfinite(it);
+        if (!std::isfinite(e)) {  // hand back the polled state itself, not the one advanced past it
+          FSK_HIP(hipMemcpyAsync(u, save_u, vec_bytes, hipMemcpyDeviceToDevice, st));
+          FSK_HIP(hipMemcpyAsync(v, save_v, vec_bytes, hipMemcpyDeviceToDevice, st));
+          FSK_HIP(hipStreamSynchronize(st));
+          return nonfinite(it);
+        }
         if (e < opts->tol) {
           FSK_HIP(hipMemcpyAsync(u, save_u, vec_bytes, hipMemcpyDeviceToDevice, st));
           FSK_HIP(hipMemcpyAsync(v, save_v, vec_bytes, hipMemcpyDeviceToDevice, st));

@@ -583,8 +583,11 @@ int run_sinkhorn_batched(const fsk_opts* o, const void* K, int64_t ldK, const vo
                      "full speed), got %zu", part_bytes, batched_workspace_bytes(n, m), ws_bytes);
   const float *Kf = (const float*)K, *Af = (const float*)A, *Bf = (const float*)B;
   float *Uf = (float*)U, *Vf = (float*)V, *part = (float*)workspace;
-  // K^T in the workspace if it fits and the run is long enough to pay for it
-  const bool use_kt = workspace && ws_bytes >= batched_workspace_bytes(n, m) && o->max_iters >= 2;
+  // K^T in the workspace if it fits.  The choice rests on (n, m, workspace) alone -- not on the
+  // iteration count -- so that a run split into several calls adds every sum in the same order
+  // as the run done in one call (a one-iteration call pays the transpose: n^2 entries read and
+  // written, about one extra product's time).
+  const bool use_kt = workspace && ws_bytes >= batched_workspace_bytes(n, m) && o->max_iters >= 1;
   const int64_t ldt = batched_ldt(n);
   float* Kt = use_kt ? (float*)((char*)workspace + part_bytes) : nullptr;
   if (use_kt) {

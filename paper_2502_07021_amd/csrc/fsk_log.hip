@@ -633,7 +633,11 @@ static int run_log_typed(const fsk_opts* o, const void* x, const void* y, int d,
     FSK_TRY(half_step(false, 0));
     if (poll) {
       FSK_TRY(read_error(&e));
-      if (!std::isfinite(e)) return nonfinite(it, e);
+      if (!std::isfinite(e)) {  // hand back the polled state itself, not the one advanced past it
+        FSK_TRY(copy_state(true));
+        FSK_HIP(hipStreamSynchronize(st));
+        return nonfinite(it, e);
+      }
       if (e < o->tol) {
         FSK_TRY(copy_state(true));
         FSK_HIP(hipStreamSynchronize(st));

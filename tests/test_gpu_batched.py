@@ -11,7 +11,7 @@ from gpu_util import dev, relerr, run_dense
 pytestmark = pytest.mark.gpu
 
 
-def run_batched(K, A, B, iters, ld=None, small_workspace=False, dtype=np.float32):
+def run_batched(K, A, B, iters, ld=None, small_workspace=False, dtype=np.float32, U0=None, V0=None):
     n, m = A.shape
     td = torch.float64 if dtype == np.float64 else torch.float32
     opts = api.make_opts(n, td, m=m, max_iters=iters)
@@ -22,7 +22,8 @@ def run_batched(K, A, B, iters, ld=None, small_workspace=False, dtype=np.float32
         ld = (n + 3) // 4 * 4
     full = torch.full((n, ld), float("nan"), dtype=td, device="cuda")
     full[:, :n] = dev(np.ascontiguousarray(K.astype(dtype)))
-    U = torch.ones(n, m, dtype=td, device="cuda"); V = torch.ones(n, m, dtype=td, device="cuda")
+    U = torch.ones(n, m, dtype=td, device="cuda") if U0 is None else dev(U0)
+    V = torch.ones(n, m, dtype=td, device="cuda") if V0 is None else dev(V0)
     api.fsk_sinkhorn_batched(opts, full[:, :n], dev(np.ascontiguousarray(A.astype(dtype))),
                              dev(np.ascontiguousarray(B.astype(dtype))), U, V, ws)
     torch.cuda.synchronize()
@@ -54,6 +55,18 @@ def test_batched_without_room_for_the_transposed_kernel(orc, n, m):
     Uo, Vo = orc.sinkhorn_batched(K, A, B, 9)
     U, V = run_batched(K, A, B, 9, small_workspace=True)
     assert relerr(U, Uo) <= 1e-4 and relerr(V, Vo) <= 1e-4
+
+
+@pytest.mark.parametrize("dtype,small", [(np.float32, False), (np.float32, True), (np.float64, False)])
+def test_a_split_run_gives_the_bits_of_the_run_in_one_call(orc, dtype, small):
+    """Which kernel forms K V rests on (n, m, workspace), never on the iteration count: 9
+    iterations == 8 + 1 == 1 + 8, bit for bit, with and without room for the transposed copy."""
+    K, A, B = problem(orc, 1030, 64, 77)
+    U, V = run_batched(K, A, B, 9, small_workspace=small, dtype=dtype)
+    for first in (8, 1):
+        Ua, Va = run_batched(K, A, B, first, small_workspace=small, dtype=dtype)
+        Ub, Vb = run_batched(K, A, B, 9 - first, small_workspace=small, dtype=dtype, U0=Ua, V0=Va)
+        assert np.array_equal(U, Ub) and np.array_equal(V, Vb)
 
 
 def test_cfg5_law_full_iteration_count(orc):

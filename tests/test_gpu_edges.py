@@ -54,6 +54,16 @@ def test_underflowed_kernel_row_is_reported(orc, flow):
     # fixed-iteration mode does not poll: the non-finite values are simply there to see
     u, v, _, _ = run_dense(K, w.a, w.b, 3, flow=flow)
     assert not np.isfinite(u[17]) or not np.isfinite(v).all()
+    # what the refused call leaves in u, v is the polled state itself (5 iterations, the first
+    # poll), not the state advanced past it by the update that revealed the error
+    opts = api.make_opts(n, torch.float32, max_iters=20, tol=1e-6, check_every=5, flow=flow)
+    ud = torch.ones(n, device="cuda"); vd = torch.ones(n, device="cuda")
+    with pytest.raises(api.FskError):
+        api.fsk_sinkhorn_dense(opts, dev(K), dev(w.a), dev(w.b), ud, vd, api.alloc_workspace(opts))
+    torch.cuda.synchronize()
+    u5, v5, _, _ = run_dense(K, w.a, w.b, 5, flow=flow)
+    assert np.array_equal(ud.cpu().numpy(), u5, equal_nan=True)
+    assert np.array_equal(vd.cpu().numpy(), v5, equal_nan=True)
 
 
 def test_above_the_fused_limit_the_call_falls_back_to_two_passes(orc):
