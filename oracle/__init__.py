@@ -33,11 +33,28 @@ def build(force: bool = False) -> str:
     return _LIB
 
 
+def build_sanitized() -> str:
+    """The same source with gcc's address and undefined-behaviour sanitizers (host code only): an
+    out-of-bounds read, an overflowing index or a misaligned access inside the oracle then aborts
+    the process instead of passing silently.  Used by tests/test_oracle_sanitized.py, which runs
+    the pins against it in a child process (FSK_ORACLE_LIB selects the library to load)."""
+    lib = os.path.join(_HERE, "liboracle_san.so")
+    if not os.path.exists(lib) or os.path.getmtime(lib) < os.path.getmtime(_SRC):
+        cmd = ["gcc", "-O1", "-g", "-std=c99", "-fopenmp", "-fno-fast-math", "-ffp-contract=off",
+               "-fsanitize=address,undefined", "-fno-sanitize-recover=all", "-fno-omit-frame-pointer",
+               "-shared", "-fPIC", _SRC, "-o", lib, "-lm"]
+        subprocess.run(cmd, check=True)
+    return lib
+
+
 def _load():
     global _lib
     if _lib is None:
-        build()
-        L = ctypes.CDLL(_LIB)
+        path = os.environ.get("FSK_ORACLE_LIB")     # a build of the same source (the sanitized one)
+        if not path:
+            build()
+            path = _LIB
+        L = ctypes.CDLL(path)
         L.orc_max.restype = ctypes.c_double
         L.orc_max_sqeuclid.restype = ctypes.c_double
         L.orc_lse.restype = ctypes.c_double
