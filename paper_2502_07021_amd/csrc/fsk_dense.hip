@@ -149,11 +149,16 @@ int launch_rowpass_slabs(int dtype, const void* K, int64_t ld, int n, int rows, 
 // K[i][cols] * u[i] over the rows of its strip in increasing i; the strip partition depends
 // only on the row count and every column is summed on its own, so a column-restricted launch
 // (and either PPT) sums every column exactly like an unrestricted one.
-// VIEW: column j belongs to client j / um, who multiplies by ITS view of u: uown[i] for the
+// VIEW != 0: column j belongs to client j / um, who multiplies by ITS view of u: uown[i] for the
 // rows i of its own index range, u[i] elsewhere (the transpose action of Algorithm 1 / 3 on a
 // client's cached vector).  One launch then serves the column slabs of all clients.
-template <typename T, int PPT, bool VIEW>
-__global__ __launch_bounds__(256) void colpartial_kernel(const T* __restrict__ K, int64_t ld,
+// VIEW == 1: um is a multiple of the pack width, so the columns of a pack have one owner and the
+// choice is made once per pack and row; VIEW == 2: any um, chosen per column.  Either way the
+// kernel must keep the 8 waves per SIMD of the plain one: the grid is one full round of
+// workgroups at that occupancy and a second, nearly empty round costs 25 % (792 against 622 us
+// at n = 32768 when the view variant needed 71 registers).
+template <typename T, int PPT, int VIEW>
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(8, 8))) void colpartial_kernel(const T* __restrict__ K, int64_t ld,
                                                          int rows, int vec_lo, int vec_hi,
                                                          const T* __restrict__ u,
                                                          const T* __restrict__ uown, int um,
@@ -168,29 +173,27 @@ __global__ __launch_bounds__(256) void colpartial_kernel(const T* __restrict__ K
   int64_t off[PPT];
 #pragma unroll
   for (int k = 0; k < PPT; ++k) off[k] = (int64_t)(vc0 + k * 256 < vec_hi ? vc0 + k * 256 : vc0) * W;
-  int own_lo[PPT][W];  // first row of the index range of the client that owns the column
-  if (VIEW) {
-#pragma unroll
-    for (int k = 0; k < PPT; ++k)
-#pragma unroll
-      for (int e = 0; e < W; ++e) own_lo[k][e] = (int)((off[k] + e) / um) * um;
-  }
   Pack<T> acc[PPT];
 #pragma unroll
   for (int k = 0; k < PPT; ++k)
 #pragma unroll
     for (int e = 0; e < W; ++e) acc[k].e[e] = T(0);
   const T* kp = K + (int64_t)i0 * ld;
+  // [row_lo, row_lo + um): the index range of the client that owns row i (the same for the whole
+  // workgroup, kept on the scalar unit); a column inside it is one of that client's own
+  int row_lo = VIEW ? (i0 / um) * um : 0;
 #pragma unroll 4
   for (int i = i0; i < i1; ++i) {
     const T ui = u[i];
     const T uo = VIEW ? uown[i] : T(0);
+    if (VIEW && i >= row_lo + um) row_lo += um;
 #pragma unroll
     for (int k = 0; k < PPT; ++k) {
       const Pack<T> kk = load_pack_stream(kp + off[k]);
+      const T uk = (VIEW == 1 && (unsigned)((int)off[k] - row_lo) < (unsigned)um) ? uo : ui;
 #pragma unroll
       for (int e = 0; e < W; ++e) {
-        const T ue = (VIEW && (unsigned)(i - own_lo[k][e]) < (unsigned)um) ? uo : ui;
+        const T ue = (VIEW == 2 && (unsigned)((int)off[k] + e - row_lo) < (unsigned)um) ? uo : uk;
         acc[k].e[e] = fma(kk.e[e], ue, acc[k].e[e]);
       }
     }
@@ -201,7 +204,7 @@ __global__ __launch_bounds__(256) void colpartial_kernel(const T* __restrict__ K
     if (vc0 + k * 256 < vec_hi) store_pack(partial + (int64_t)s * ld_ws + off[k], acc[k]);
 }
 
-template <typename T, bool VIEW>
+template <typename T, int VIEW>
 static int colpartial_typed(const void* K, int64_t ld, int n, int rows, int c0, int c1,
                             const void* u, const void* uown, int um, void* partial, int64_t ld_ws,
                             hipStream_t stream) {
@@ -228,17 +231,20 @@ static int colpartial_typed(const void* K, int64_t ld, int n, int rows, int c0, 
 int launch_colpartial(int dtype, const void* K, int64_t ld, int n, int rows, int c0, int c1,
                       const void* u, void* partial, int64_t ld_ws, hipStream_t stream) {
   return dtype == FSK_F64
-             ? colpartial_typed<double, false>(K, ld, n, rows, c0, c1, u, nullptr, 1, partial, ld_ws, stream)
-             : colpartial_typed<float, false>(K, ld, n, rows, c0, c1, u, nullptr, 1, partial, ld_ws, stream);
+             ? colpartial_typed<double, 0>(K, ld, n, rows, c0, c1, u, nullptr, 1, partial, ld_ws, stream)
+             : colpartial_typed<float, 0>(K, ld, n, rows, c0, c1, u, nullptr, 1, partial, ld_ws, stream);
 }
 
 int launch_colpartial_view(int dtype, const void* K, int64_t ld, int n, const void* u,
                            const void* uown, int um, void* partial, int64_t ld_ws,
                            hipStream_t stream) {
   if (um < 1) return set_error(FSK_EINVAL, "client block of %d columns", um);
-  return dtype == FSK_F64
-             ? colpartial_typed<double, true>(K, ld, n, n, 0, n, u, uown, um, partial, ld_ws, stream)
-             : colpartial_typed<float, true>(K, ld, n, n, 0, n, u, uown, um, partial, ld_ws, stream);
+  const bool whole_packs = um % pack_width(dtype) == 0;  // a pack of columns has one owner
+  if (dtype == FSK_F64)
+    return whole_packs ? colpartial_typed<double, 1>(K, ld, n, n, 0, n, u, uown, um, partial, ld_ws, stream)
+                       : colpartial_typed<double, 2>(K, ld, n, n, 0, n, u, uown, um, partial, ld_ws, stream);
+  return whole_packs ? colpartial_typed<float, 1>(K, ld, n, n, 0, n, u, uown, um, partial, ld_ws, stream)
+                     : colpartial_typed<float, 2>(K, ld, n, n, 0, n, u, uown, um, partial, ld_ws, stream);
 }
 
 // ======================================================= partial sums -> result
