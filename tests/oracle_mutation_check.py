@@ -1,13 +1,15 @@
-"""Mutation check of the CPU oracle against its pins (CPU only; not collected by pytest).
+"""Mutation check of the CPU oracle against its pins (CPU only).
 
-    python tests/oracle_mutation_check.py [every_kth]
+    python tests/oracle_mutation_check.py [every_kth] [--write]
 
 Plants one small mistake at a time in a copy of oracle/sinkhorn_oracle.c (a flipped sign, a
 swapped index, a transposed subscript, a changed constant or comparison, exp for exp2, ...),
 builds the copy into a library of its own and runs tests/test_oracle_pins.py against it.  A
 mutant that passes every pin is printed: either it changes nothing a caller can see (a loop
 bound one past the end, a dead initial value, the thread-count setter) or a pin is missing.
-The oracle in the tree is never touched."""
+The oracle in the tree is never touched.  `--write` stores the survivors of a FULL run in
+tests/golden/oracle_mutation_survivors.txt (the mutated source lines, which are what the
+collected test tests/test_oracle_mutation_sample.py allows a sampled mutant to survive as)."""
 import concurrent.futures as cf
 import os
 import re
@@ -62,12 +64,10 @@ def mutants(lines):
     return out
 
 
-def main():
+def run_mutants(todo, workers=4, threads_each=2, progress=None):
+    """Builds and tests every (line number, mutated line) of `todo`; returns (line, text, verdict)
+    triples with verdict in {"killed", "survived", "does not compile"}."""
     lines = open(SRC).read().split("\n")
-    todo = mutants(lines)
-    if len(sys.argv) > 1:
-        todo = todo[::int(sys.argv[1])]
-    print(len(todo), "mutants", flush=True)
     work = tempfile.mkdtemp(prefix="oracle_mut_")
     runner = os.path.join(work, "run_pins.py")
     with open(runner, "w") as fh:
@@ -85,7 +85,7 @@ def main():
         if subprocess.run(GCC + [src, "-o", lib, "-lm"], capture_output=True).returncode == 0:
             try:
                 rc = subprocess.run([sys.executable, runner, lib], capture_output=True, timeout=600,
-                                    env=dict(os.environ, OMP_NUM_THREADS="2")).returncode
+                                    env=dict(os.environ, OMP_NUM_THREADS=str(threads_each))).returncode
                 verdict = "survived" if rc == 0 else "killed"
             except subprocess.TimeoutExpired:
                 verdict = "killed"
@@ -93,15 +93,49 @@ def main():
         os.remove(src)
         return ln, new, verdict
 
-    survivors = 0
-    with cf.ThreadPoolExecutor(4) as pool:
-        for done, (ln, new, verdict) in enumerate(pool.map(run, list(enumerate(todo)))):
-            if verdict == "survived":
-                survivors += 1
-                print(f"SURVIVED line {ln + 1}: {new.strip()}", flush=True)
-            if done % 100 == 0:
-                print("done", done, flush=True)
-    print("survivors:", survivors, "of", len(todo))
+    out = []
+    with cf.ThreadPoolExecutor(workers) as pool:
+        for done, res in enumerate(pool.map(run, list(enumerate(todo)))):
+            out.append(res)
+            if progress:
+                progress(done, res)
+    return out
+
+
+def all_mutants():
+    return mutants(open(SRC).read().split("\n"))
+
+
+SURVIVORS = os.path.join(ROOT, "tests", "golden", "oracle_mutation_survivors.txt")
+
+
+def main():
+    args = [a for a in sys.argv[1:] if not a.startswith("--")]
+    todo = all_mutants()
+    if args:
+        todo = todo[::int(args[0])]
+    print(len(todo), "mutants", flush=True)
+
+    def progress(done, res):
+        ln, new, verdict = res
+        if verdict == "survived":
+            print(f"SURVIVED line {ln + 1}: {new.strip()}", flush=True)
+        if done % 100 == 0:
+            print("done", done, flush=True)
+
+    res = run_mutants(todo, progress=progress)
+    alive = [new.strip() for _, new, verdict in res if verdict == "survived"]
+    print("survivors:", len(alive), "of", len(todo))
+    if "--write" in sys.argv:
+        if args:
+            raise SystemExit("--write needs the full run")
+        with open(SURVIVORS, "w") as fh:
+            fh.write("# Mutated lines of oracle/sinkhorn_oracle.c that pass every pin in a full run of\n"
+                     "# tests/oracle_mutation_check.py (" + str(len(todo)) + " mutants).  Each changes nothing a caller can see:\n"
+                     "# a loop bound or a comparison at a tolerance turned into <=, an over-sized allocation made\n"
+                     "# smaller but still sufficient, the thread-count setter, a dead initial value.\n")
+            for line in sorted(set(alive)):
+                fh.write(line + "\n")
 
 
 if __name__ == "__main__":
