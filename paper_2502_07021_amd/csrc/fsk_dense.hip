@@ -431,49 +431,56 @@ __global__ __launch_bounds__(512) void fused_kernel(const T* __restrict__ K, int
 #pragma unroll
   for (int e = 0; e < W; ++e) tail_ok[e] = tail_vi * W + e < n;
 
-  // Strip vb: rows [rbase, rbase + rows) of K; `groups` row groups, walked from a start
+  // Strip vb: rows [rbase, rbase + rows) of K.  Its `groups` row groups are walked from a start
   // that differs from strip to strip (a rotation of the group index by a multiple of the strip
-  // index), which keeps the concurrent streams from marching through DRAM in lock step.  The
+  // index), which keeps the concurrent streams from marching through DRAM in lock step; the
   // rotation is a function of the strip alone, so it does not disturb the equality over c.
-  // A workgroup's place in its walk: strip `vb`, step `gi` inside it, and the strip's geometry
-  // (recomputed only when the strip changes; no division on the per-step path).
-  struct Cursor { int vb, gi; int64_t rbase; int rows, groups, rot; };
-  auto enter_strip = [&](Cursor& c, int vb) {
-    c.vb = vb;
-    c.gi = 0;
-    if (vb >= nvb) return;  // past the end: never dereferenced
+  auto strip_rows = [&](int vb, int64_t& rbase) {
     const int j = vb / spb, ls = vb - j * spb;
-    c.rbase = (int64_t)j * m + (int64_t)ls * h;
+    rbase = (int64_t)j * m + (int64_t)ls * h;
     const int left = m - ls * h;
-    c.rows = left < h ? left : h;
-    c.groups = (c.rows + R - 1) / R;
-    c.rot = (int)(((unsigned)vb * (unsigned)rotmul) % (unsigned)c.groups);
+    return left < h ? left : h;
   };
-  auto next = [&](const Cursor& c) {
-    Cursor d = c;
-    if (++d.gi == spv) enter_strip(d, c.vb + nb);
-    return d;
-  };
-  auto group_of = [&](const Cursor& c) {  // >= c.groups: nothing to do at this step
-    const int g = w + c.gi * G;
-    if (g >= c.groups) return g;
-    const int x = g + c.rot;
-    return x >= c.groups ? x - c.groups : x;
+  // Step t of this workgroup is row group w + (t % spv)*G of strip team + (t / spv)*nb.  Steps
+  // and rows past the end (of a short strip) are clamped to the last valid one (a redundant,
+  // in-bounds read) and contribute nothing because their u is forced to 0 in process().
+  // The usual case -- the workgroup walks ONE strip -- is located without any division.
+  const bool one_strip = total == spv;
+  int64_t rbase1;
+  const int rows1 = strip_rows(team, rbase1);
+  const int groups1 = (rows1 + R - 1) / R;
+  const int rot1 = (int)(((unsigned)team * (unsigned)rotmul) % (unsigned)groups1);
+  auto locate = [&](int t, int& vb, int64_t& rbase, int& rows, int& g) {
+    if (one_strip) {
+      vb = team;
+      rbase = rbase1;
+      rows = rows1;
+      g = w + t * G;
+      if (g < groups1) {
+        g += rot1;
+        g = g >= groups1 ? g - groups1 : g;
+      }
+    } else {
+      vb = team + (t / spv) * nb;
+      rows = strip_rows(vb, rbase);
+      const int groups = (rows + R - 1) / R;
+      g = w + (t % spv) * G;
+      if (g < groups) g = (int)(((unsigned)g + (unsigned)vb * (unsigned)rotmul) % (unsigned)groups);
+    }
   };
 
-  // Groups past the end of a (short) strip are skipped by every thread alike; rows past the end
-  // inside the last group are clamped to the last valid one (a redundant, in-bounds read) and
-  // contribute nothing because their u is forced to 0 in process().
-  auto load_group = [&](Pack<T>(&buf)[R][VPT], T(&mg)[R], T(&od)[R], const Cursor& sp) {
-    const int g = group_of(sp);
-    if (g >= sp.groups) return;  // the same for every thread of the workgroup
+  auto load_group = [&](Pack<T>(&buf)[R][VPT], T(&mg)[R], T(&od)[R], int t) {
+    t = t < total ? t : total - 1;
+    int vb, rows, g;
+    int64_t rbase;
+    locate(t, vb, rbase, rows, g);
 #pragma unroll
     for (int r = 0; r < R; ++r) {
       int row = g * R + r;
-      row = row < sp.rows ? row : sp.rows - 1;
-      const T* kp = K + (sp.rbase + row) * ld + (int64_t)tid * W;
-      mg[r] = marg[sp.rbase + row];
-      od[r] = (damped || err_out) ? old_u[sp.rbase + row] : T(0);
+      row = row < rows ? row : rows - 1;
+      const T* kp = K + (rbase + row) * ld + (int64_t)tid * W;
+      mg[r] = marg[rbase + row];
+      od[r] = (damped || err_out) ? old_u[rbase + row] : T(0);
 #pragma unroll
       for (int i = 0; i < VPT; ++i) {
         if (EXACT || i < VPT - 1) {
@@ -495,61 +502,54 @@ __global__ __launch_bounds__(512) void fused_kernel(const T* __restrict__ K, int
     }
   };
 
-  int flip = 0;  // which of the two reduction slots the next processed group uses
-  auto process = [&](Pack<T>(&buf)[R][VPT], T(&mg)[R], T(&od)[R], const Cursor& sp) {
-    const int vb = sp.vb;
-    const int64_t rbase = sp.rbase;
-    const int rows = sp.rows;
-    const int g = group_of(sp);
-    if (g < sp.groups) {  // the same for every thread of the workgroup
-      T d[R];
+  auto process = [&](Pack<T>(&buf)[R][VPT], T(&mg)[R], T(&od)[R], int t, int parity) {
+    int vb, rows, g;
+    int64_t rbase;
+    locate(t, vb, rbase, rows, g);
+    T d[R];
 #pragma unroll
-      for (int r = 0; r < R; ++r) d[r] = T(0);
+    for (int r = 0; r < R; ++r) d[r] = T(0);
 #pragma unroll
-      for (int i = 0; i < VPT; ++i) {
-        const Pack<T> vv = load_pack(v_lds + (int64_t)(i * NT + tid) * W);
+    for (int i = 0; i < VPT; ++i) {
+      const Pack<T> vv = load_pack(v_lds + (int64_t)(i * NT + tid) * W);
 #pragma unroll
-        for (int r = 0; r < R; ++r)
+      for (int r = 0; r < R; ++r)
 #pragma unroll
-          for (int e = 0; e < W; ++e) d[r] = fma(buf[r][i].e[e], vv.e[e], d[r]);
-      }
-      // the slots alternate per PROCESSED group (not per step: a skipped step has no barrier),
-      // so a slot is rewritten only after a barrier that every reader of it has passed
-      T* slot = red + flip * R * NW;
-      flip ^= 1;
-#pragma unroll
-      for (int r = 0; r < R; ++r) {
-        const T s = wave_sum(d[r]);
-        if (lane == 0) slot[r * NW + wave] = s;
-      }
-      __syncthreads();
-#pragma unroll
-      for (int r = 0; r < R; ++r) {
-        T q = T(0);
-#pragma unroll
-        for (int k = 0; k < NW; ++k) q += slot[r * NW + k];
-        const int row = g * R + r;
-        T ur = T(0);
-        if (row < rows) {
-          ur = mg[r] / q;
-          if (damped) {
-            if (sizeof(T) == 4 && geom)  // fp32 only: the fp64 log2 / exp2 would spill
-              ur = fsk_exp2(fma(T(1) - et, fsk_log2(od[r]), et * fsk_log2(ur)));
-            else
-              ur = (T(1) - et) * od[r] + et * ur;
-          }
-          if (tid == 0) {
-            if (err_out) err_out[rbase + row] = fsk_abs(od[r] * q - mg[r]);
-            u_out[rbase + row] = ur;
-          }
-        }
-#pragma unroll
-        for (int i = 0; i < VPT; ++i)
-#pragma unroll
-          for (int e = 0; e < W; ++e) acc[i].e[e] = fma(buf[r][i].e[e], ur, acc[i].e[e]);
-      }
+        for (int e = 0; e < W; ++e) d[r] = fma(buf[r][i].e[e], vv.e[e], d[r]);
     }
-    if (sp.gi == spv - 1) {  // last step of a strip: hand over this strip's contribution
+    T* slot = red + parity * R * NW;
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+      const T s = wave_sum(d[r]);
+      if (lane == 0) slot[r * NW + wave] = s;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+      T q = T(0);
+#pragma unroll
+      for (int k = 0; k < NW; ++k) q += slot[r * NW + k];
+      const int row = g * R + r;
+      T ur = T(0);
+      if (row < rows) {
+        ur = mg[r] / q;
+        if (damped) {
+          if (sizeof(T) == 4 && geom)  // fp32 only: the fp64 log2 / exp2 would spill
+            ur = fsk_exp2(fma(T(1) - et, fsk_log2(od[r]), et * fsk_log2(ur)));
+          else
+            ur = (T(1) - et) * od[r] + et * ur;
+        }
+        if (tid == 0) {
+          if (err_out) err_out[rbase + row] = fsk_abs(od[r] * q - mg[r]);
+          u_out[rbase + row] = ur;
+        }
+      }
+#pragma unroll
+      for (int i = 0; i < VPT; ++i)
+#pragma unroll
+        for (int e = 0; e < W; ++e) acc[i].e[e] = fma(buf[r][i].e[e], ur, acc[i].e[e]);
+    }
+    if (one_strip ? t == spv - 1 : t % spv == spv - 1) {  // last step of a strip: hand over its contribution
       T* prow = partial + ((int64_t)vb * G + w) * ld_ws;
 #pragma unroll
       for (int i = 0; i < VPT; ++i) {
@@ -565,17 +565,13 @@ __global__ __launch_bounds__(512) void fused_kernel(const T* __restrict__ K, int
   // already in flight, across strip boundaries too.
   // The step after the last one is not fetched: at 8 steps per workgroup (n = 8192) a redundant
   // group would be an eighth of the kernel's reads.
-  Cursor cA, cB;
-  enter_strip(cA, team);
-  load_group(bufA, mgA, odA, cA);
+  load_group(bufA, mgA, odA, 0);
   for (int t = 0; t < total; t += 2) {
-    cB = next(cA);
-    if (t + 1 < total) load_group(bufB, mgB, odB, cB);
-    process(bufA, mgA, odA, cA);
+    if (t + 1 < total) load_group(bufB, mgB, odB, t + 1);
+    process(bufA, mgA, odA, t, 0);
     if (t + 1 >= total) break;
-    cA = next(cB);
-    if (t + 2 < total) load_group(bufA, mgA, odA, cA);
-    process(bufB, mgB, odB, cB);
+    if (t + 2 < total) load_group(bufA, mgA, odA, t + 2);
+    process(bufB, mgB, odB, t + 1, 1);
   }
 }
 

@@ -99,6 +99,20 @@ def test_cfg4_n65536_log_domain(orc):
     g_ref = orc.log_update_points(w.y, w.b, w.x, f100h, eps, rows)
     assert np.max(np.abs(g100h[rows] - g_ref)) / eps <= 1e-4
 
+    # a tolerance this law reaches: the run stops at a poll before the cap, the reported error is
+    # below it, and the oracle's evaluation of the handed-back state on sampled rows agrees
+    ft, gt, done_t, err_t = run(2000, tol=2e-3, check_every=10)
+    assert 0 < done_t < 2000 and done_t % 10 == 0 and err_t < 2e-3
+    rm = orc.log_row_marginal_points(w.x, ft.cpu().numpy().astype(np.float64), w.y,
+                                     gt.cpu().numpy().astype(np.float64), eps, rows)
+    est = np.abs(rm - w.a[rows]).sum() * (n / rows.size)
+    assert 0.5 * err_t <= est <= 2.0 * err_t
+    # ... and ten iterations earlier (the previous poll) the error was still above it
+    fp_, gp_, _, _ = run(done_t - 10)
+    rm = orc.log_row_marginal_points(w.x, fp_.cpu().numpy().astype(np.float64), w.y,
+                                     gp_.cpu().numpy().astype(np.float64), eps, rows)
+    assert np.abs(rm - w.a[rows]).sum() * (n / rows.size) > 0.6 * 2e-3
+
     # the stop rule of the configuration: L1 row-marginal error < 1e-6 or 2000 iterations
     f, g, done, err = run(2000, f100, g100, tol=1e-6, check_every=50)
     assert done % 50 == 0 and np.isfinite(err)
