@@ -409,14 +409,15 @@ int fsk_rdp_epsilon(double clip, double sigma, int64_t releases, double delta, c
                     int32_t n_orders, double* eps_out, double* order_out);
 
 /* ---- measurement helpers -----------------------------------------------------------------
- * fsk_dense_profile runs `reps` iterations exactly as fsk_sinkhorn_dense does in
- * fixed-iteration mode (same kernels, same launch shapes, u and v advance), but brackets the
- * launches of each iteration with HIP events recorded on `stream`; iterations are enqueued back
- * to back and the stream is synchronised once per 64 of them, so a span holds a launch and the
- * hand-over from the launch before it, not the latency of a launch into an idle queue.
- * Outputs (host): stream_ms = average time per iteration spent in the kernels that
- * stream K (the HBM-bound ones), other_ms = average time per iteration in the small reduction
- * kernels, stream_launches = number of K-streaming launches per iteration.  */
+ * fsk_dense_profile times the launches of fsk_sinkhorn_dense's fixed-iteration mode (same
+ * kernels, same launch shapes) with HIP events recorded on `stream`, in two back-to-back runs:
+ * first `reps` + 1 times the K-streaming launches of an iteration alone (the first one untimed;
+ * they recompute the u-update from the same v, or relax u further if opts asks for a damping),
+ * then `reps` whole iterations (u and v advance as in the solver).  Outputs (host):
+ * stream_ms = average time of the K-streaming (HBM-bound) launches of one iteration,
+ * other_ms = whole iteration minus that: the small reduction kernels and the hand-overs between
+ * launches, stream_launches = number of K-streaming launches per iteration.  Synchronises.
+ * FSK_FLOW_RESIDENT: one launch runs all `reps` iterations; stream_ms is its time / reps.  */
 int fsk_dense_profile(const fsk_opts* opts, const void* K, int64_t ldK, const void* a,
                       const void* b, void* u, void* v, void* workspace, size_t ws_bytes, int reps,
                       double* stream_ms, double* other_ms, int32_t* stream_launches, void* stream);

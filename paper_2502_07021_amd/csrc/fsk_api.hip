@@ -193,14 +193,14 @@ int fsk_kernel_from_points(const fsk_opts* opts, const void* x, const void* y, i
   return FSK_OK;
 }
 
-// One dense iteration, enqueued.  With `ev` (three events) the K-streaming launches lie
-// between ev[0] and ev[1] and the small reduction launches between ev[1] and ev[2];
+// One dense iteration, enqueued.  `stream_only`: just its K-streaming launches (the reduction
+// kernels that finish the v-update are left out: what the profile call times on its own).
 // *stream_launches (if given) receives the number of K-streaming launches.
 // `errvec` (n entries, optional): the u-update also leaves |u_i (K v)_i - a_i| there for the
 // scalings as they stood BEFORE this iteration (the row-marginal error terms, for free).
 static int dense_iteration(const fsk_opts* o, const DenseWs& w, const char* K, int64_t ld,
                            const char* a, const char* b, char* u, char* v, char* ws,
-                           hipStream_t st, hipEvent_t* ev = nullptr,
+                           hipStream_t st, bool stream_only = false,
                            int32_t* stream_launches = nullptr, char* errvec = nullptr) {
   const int n = o->n, c = o->c, m = n / c, dt = o->dtype;
   const int epi = epi_of(o);
@@ -213,12 +213,10 @@ static int dense_iteration(const fsk_opts* o, const DenseWs& w, const char* K, i
     // do not fit the fused kernel's register budget)
     if (!plan.ok || (epi == kEpiDampGeom && dt == FSK_F64)) flow = FSK_FLOW_TWO_PASS;
   }
-  if (ev) FSK_HIP(hipEventRecord(ev[0], st));
   if (flow == FSK_FLOW_FUSED) {
     FSK_TRY(launch_fused(dt, plan, K, ld, n, m, a, v, u, u, partial, w.ld_ws, epi, o->eta, st, errvec));
-    if (ev) FSK_HIP(hipEventRecord(ev[1], st));
-    FSK_TRY(launch_colreduce(dt, partial, w.ld_ws, plan.partial_rows(), 0, n, b, v, v, epi, o->eta, st));
-    if (ev) FSK_HIP(hipEventRecord(ev[2], st));
+    if (!stream_only)
+      FSK_TRY(launch_colreduce(dt, partial, w.ld_ws, plan.partial_rows(), 0, n, b, v, v, epi, o->eta, st));
     if (stream_launches) *stream_launches = 1;
     return FSK_OK;
   }
@@ -229,9 +227,8 @@ static int dense_iteration(const fsk_opts* o, const DenseWs& w, const char* K, i
   // summed on its own over the same row strips, so one launch over all columns IS the c slab
   // products (launching them one by one gave the same bits at 16 KiB-wide, slower reads).
   FSK_TRY(launch_colpartial(dt, K, ld, n, n, 0, n, u, partial, w.ld_ws, st));
-  if (ev) FSK_HIP(hipEventRecord(ev[1], st));
-  FSK_TRY(launch_colreduce(dt, partial, w.ld_ws, col_strips(n), 0, n, b, v, v, epi, o->eta, st));
-  if (ev) FSK_HIP(hipEventRecord(ev[2], st));
+  if (!stream_only)
+    FSK_TRY(launch_colreduce(dt, partial, w.ld_ws, col_strips(n), 0, n, b, v, v, epi, o->eta, st));
   if (stream_launches) *stream_launches = 2;
   return FSK_OK;
 }
@@ -324,7 +321,7 @@ static int dense_solve(const fsk_opts* opts, const DenseWs& w, const void* K, in
         FSK_HIP(hipMemcpyAsync(save_v, v, vec_bytes, hipMemcpyDeviceToDevice, st));
       }
       FSK_TRY(dense_iteration(opts, w, (const char*)K, ldK, (const char*)a, (const char*)b, (char*)u,
-                              (char*)v, workspace, st, nullptr, nullptr, poll ? errvec : nullptr));
+                              (char*)v, workspace, st, false, nullptr, poll ? errvec : nullptr));
       if (poll) {
         FSK_TRY(launch_sum_to_double(opts->dtype, errvec, opts->n, scalar, st, l2));
         FSK_HIP(hipMemcpyAsync(&e, scalar, sizeof(double), hipMemcpyDeviceToHost, st));
@@ -462,39 +459,33 @@ int fsk_dense_profile(const fsk_opts* opts, const void* K, int64_t ldK, const vo
     if (stream_launches) *stream_launches = 1;
     return FSK_OK;
   }
-  // Iterations are enqueued back to back in batches, every one with its own three events, and the
-  // stream is synchronised once per batch: an event then stamps the moment the launch before it
-  // drained, and the span ev[0] -> ev[1] is the K-streaming launch plus one hand-over between
-  // kernels (about a microsecond), not the latency of a launch into an idle queue.
+  // Two back-to-back runs between three events: `reps` times the K-streaming launches alone
+  // (nothing between two of them but the hand-over from one kernel to the next, well under a
+  // microsecond of a 0.05-0.6 ms launch), then `reps` whole iterations; the reduction kernels'
+  // share is the difference.  An event per launch would put a marker packet, and its few
+  // microseconds, inside every span.
+  rc = dense_iteration(opts, w, (const char*)K, ldK, (const char*)a, (const char*)b, (char*)u,
+                       (char*)v, (char*)workspace, st, true, &launches);  // untimed: the queue is busy after it
+  if (rc == FSK_OK && hipEventRecord(ev[0], st) != hipSuccess) rc = set_error(FSK_EHIP, "hipEventRecord failed");
+  for (int it = 0; it < reps && rc == FSK_OK; ++it)
+    rc = dense_iteration(opts, w, (const char*)K, ldK, (const char*)a, (const char*)b, (char*)u,
+                         (char*)v, (char*)workspace, st, true, &launches);
+  if (rc == FSK_OK && hipEventRecord(ev[1], st) != hipSuccess) rc = set_error(FSK_EHIP, "hipEventRecord failed");
+  for (int it = 0; it < reps && rc == FSK_OK; ++it)
+    rc = dense_iteration(opts, w, (const char*)K, ldK, (const char*)a, (const char*)b, (char*)u,
+                         (char*)v, (char*)workspace, st, false, &launches);
+  if (rc == FSK_OK && (hipEventRecord(ev[2], st) != hipSuccess || hipEventSynchronize(ev[2]) != hipSuccess))
+    rc = set_error(FSK_EHIP, "event timing failed");
+  float ms01 = 0.f, ms12 = 0.f;
+  if (rc == FSK_OK && (hipEventElapsedTime(&ms01, ev[0], ev[1]) != hipSuccess ||
+                       hipEventElapsedTime(&ms12, ev[1], ev[2]) != hipSuccess))
+    rc = set_error(FSK_EHIP, "hipEventElapsedTime failed");
   for (int k = 0; k < 3; ++k) (void)hipEventDestroy(ev[k]);
-  constexpr int kBatch = 64;
-  hipEvent_t evs[3 * kBatch];
-  int made = 0;
-  for (; made < 3 * kBatch; ++made)
-    if (hipEventCreate(&evs[made]) != hipSuccess) { rc = set_error(FSK_EHIP, "hipEventCreate failed"); break; }
-  for (int done = 0; done < reps && rc == FSK_OK;) {
-    const int nb = reps - done < kBatch ? reps - done : kBatch;
-    for (int it = 0; it < nb && rc == FSK_OK; ++it)
-      rc = dense_iteration(opts, w, (const char*)K, ldK, (const char*)a, (const char*)b, (char*)u,
-                           (char*)v, (char*)workspace, st, evs + 3 * it, &launches);
-    if (rc != FSK_OK) break;
-    if (hipStreamSynchronize(st) != hipSuccess) { rc = set_error(FSK_EHIP, "hipStreamSynchronize failed"); break; }
-    for (int it = 0; it < nb; ++it) {
-      float ms01 = 0.f, ms12 = 0.f;
-      if (hipEventElapsedTime(&ms01, evs[3 * it], evs[3 * it + 1]) != hipSuccess ||
-          hipEventElapsedTime(&ms12, evs[3 * it + 1], evs[3 * it + 2]) != hipSuccess) {
-        rc = set_error(FSK_EHIP, "hipEventElapsedTime failed");
-        break;
-      }
-      t_stream += ms01;
-      t_other += ms12;
-    }
-    done += nb;
-  }
-  for (int k = 0; k < made; ++k) (void)hipEventDestroy(evs[k]);
   if (rc != FSK_OK) return rc;
-  if (stream_ms) *stream_ms = t_stream / reps;
-  if (other_ms) *other_ms = t_other / reps;
+  t_stream = ms01 / reps;
+  t_other = ms12 / reps - t_stream;
+  if (stream_ms) *stream_ms = t_stream;
+  if (other_ms) *other_ms = t_other > 0.0 ? t_other : 0.0;
   if (stream_launches) *stream_launches = launches;
   return FSK_OK;
 }
