@@ -744,8 +744,8 @@ static GridWs grid_ws(const fsk_opts* o, int p_r, int p_c) {
   g.stride_bytes = align_up((size_t)o->n * elem_size(o->dtype), 256);
   g.stride = (int64_t)(g.stride_bytes / elem_size(o->dtype));
   g.row_off = 0;                                                  // p_c block-row products
-  g.strip_off = g.row_off + (size_t)p_c * g.stride_bytes;         // strips of one block row
-  g.tile_off = g.strip_off + (size_t)col_strips(o->n / p_r) * g.stride_bytes;  // p_r block-column products
+  g.strip_off = g.row_off + (size_t)p_c * g.stride_bytes;         // row strips of the column pass
+  g.tile_off = g.strip_off + (size_t)col_strips(o->n) * g.stride_bytes;  // p_r block-column products
   g.total = g.tile_off + (size_t)p_r * g.stride_bytes;
   return g;
 }
@@ -789,26 +789,31 @@ int fsk_sinkhorn_grid(const fsk_opts* opts, const void* K, int64_t ldK, const vo
   char* ws = (char*)workspace;
   const char* Kc = (const char*)K;
   for (int it = 0; it < opts->max_iters; ++it) {
-    // block products K_ij v_j for every block row at once, one launch per block column j;
-    // the row-wise reduction over j then divides
+    // block products K_ij v_j for every block row and block column; the row-wise reduction over j
+    // then divides
     if (p_c == 1) {
       FSK_TRY(launch_rowpass(dt, K, ldK, n, n, v, a, nullptr, u, kEpiDivide, 1.0, st));
-    } else {
-      for (int j = 0; j < p_c; ++j)
-        FSK_TRY(launch_rowpass(dt, Kc + (size_t)j * nc * s, ldK, nc, n, (const char*)v + (size_t)j * nc * s,
-                               nullptr, nullptr, ws + g.row_off + (size_t)j * g.stride_bytes,
-                               kEpiProduct, 1.0, st));
-      FSK_TRY(launch_colreduce(dt, ws + g.row_off, g.stride, p_c, 0, n, a, nullptr, u, kEpiDivide, 1.0, st));
+    } else {  // all block columns in one grid; then the p_c products of a row in the order j = 0, 1, ...
+      FSK_TRY(launch_rowpass_colblocks(dt, K, ldK, nc, n, p_c, v, ws + g.row_off, g.stride, st));
+      FSK_TRY(launch_colreduce(dt, ws + g.row_off, g.stride, p_c, 0, n, a, nullptr, u, kEpiDivide, 1.0, st, 1));
     }
-    // block products K_ij^T u_i for every block column at once, one block row i at a time;
-    // the column-wise reduction over i then divides
-    for (int i = 0; i < p_r; ++i) {
-      FSK_TRY(launch_colpartial(dt, Kc + (size_t)i * nr * (size_t)ldK * s, ldK, n, nr, 0, n,
-                                (const char*)u + (size_t)i * nr * s, ws + g.strip_off, g.stride, st));
-      FSK_TRY(launch_colreduce(dt, ws + g.strip_off, g.stride, col_strips(nr), 0, n, nullptr, nullptr,
-                               ws + g.tile_off + (size_t)i * g.stride_bytes, kEpiProduct, 1.0, st));
+    // block products K_ij^T u_i for every block column at once; the column-wise reduction over i
+    // then divides
+    if (nr % kColStrip == 0 && p_r <= 256) {
+      // block rows are whole 128-row strips: one pass over all rows, then per column the strips of
+      // a block row in order (= the block product) and the p_r block products in the order i = 0, 1, ...
+      FSK_TRY(launch_colpartial(dt, K, ldK, n, n, 0, n, u, ws + g.strip_off, g.stride, st));
+      FSK_TRY(launch_colreduce(dt, ws + g.strip_off, g.stride, col_strips(n), 0, n, b, nullptr, v, kEpiDivide,
+                               1.0, st, p_r));
+    } else {  // one block row i at a time
+      for (int i = 0; i < p_r; ++i) {
+        FSK_TRY(launch_colpartial(dt, Kc + (size_t)i * nr * (size_t)ldK * s, ldK, n, nr, 0, n,
+                                  (const char*)u + (size_t)i * nr * s, ws + g.strip_off, g.stride, st));
+        FSK_TRY(launch_colreduce(dt, ws + g.strip_off, g.stride, col_strips(nr), 0, n, nullptr, nullptr,
+                                 ws + g.tile_off + (size_t)i * g.stride_bytes, kEpiProduct, 1.0, st));
+      }
+      FSK_TRY(launch_colreduce(dt, ws + g.tile_off, g.stride, p_r, 0, n, b, nullptr, v, kEpiDivide, 1.0, st, 1));
     }
-    FSK_TRY(launch_colreduce(dt, ws + g.tile_off, g.stride, p_r, 0, n, b, nullptr, v, kEpiDivide, 1.0, st));
   }
   return FSK_OK;
 }

@@ -24,6 +24,8 @@ namespace fsk {
 // blockIdx.y = slab: the launch covers gridDim.y row slabs of `rows` rows each, slab y being
 // rows [y*rows, (y+1)*rows) of K, marg, old, out and err_out -- the row blocks of the c clients
 // (Sec. 3.1) in one grid.
+// blockIdx.z = column block (2D block grid): block z multiplies columns [z*n, (z+1)*n) of K by
+// entries [z*n, (z+1)*n) of vin and writes its products to out + z*out_block_stride.
 // VIEW: slab y is client y working on ITS view of the vector (Sec. 3.2.1, "a current global view
 // ... obtained from the previous collective"; Algorithm 3's cached slices): entry j comes from
 // `vown` inside the client's own index range [y*rows, (y+1)*rows) and from `vin` elsewhere.
@@ -32,7 +34,7 @@ __global__ __launch_bounds__(256) void rowpass_kernel(const T* __restrict__ K, i
                                                       int rows, const T* __restrict__ vin,
                                                       const T* __restrict__ vown, const T* marg,
                                                       const T* old, T* out, int epi, T eta,
-                                                      T* err_out) {
+                                                      T* err_out, int64_t out_block_stride) {
   // err_out (may be null): |old_i * product_i - marg_i|, the row-marginal error term of the
   // scalings as they stood before this update (old is read before out is written: out may
   // alias old).
@@ -43,7 +45,9 @@ __global__ __launch_bounds__(256) void rowpass_kernel(const T* __restrict__ K, i
   const int nvec_full = n / W;
   const int64_t slab0 = (int64_t)blockIdx.y * rows;  // first row of this slab
   const int own_lo = (int)slab0, own_hi = own_lo + rows;
-  K += slab0 * ld;
+  K += slab0 * ld + (int64_t)blockIdx.z * n;
+  vin += (int64_t)blockIdx.z * n;
+  out += (int64_t)blockIdx.z * out_block_stride;
 
   const T* rowp[ROWS];
 #pragma unroll
@@ -108,18 +112,19 @@ __global__ __launch_bounds__(256) void rowpass_kernel(const T* __restrict__ K, i
 template <typename T>
 static int rowpass_typed(const void* K, int64_t ld, int n, int rows, int slabs, const void* vin,
                          const void* vown, const void* marg, const void* old, void* out, int epi,
-                         double eta, void* err_out, hipStream_t stream) {
-  if (rows <= 0 || slabs <= 0) return FSK_OK;
+                         double eta, void* err_out, hipStream_t stream, int col_blocks = 1,
+                         int64_t out_block_stride = 0) {
+  if (rows <= 0 || slabs <= 0 || col_blocks <= 0) return FSK_OK;
   constexpr int ROWS = 4;
-  dim3 grid((rows + ROWS - 1) / ROWS, slabs), block(256);
+  dim3 grid((rows + ROWS - 1) / ROWS, slabs, col_blocks), block(256);
   if (vown)
     hipLaunchKernelGGL((rowpass_kernel<T, ROWS, true>), grid, block, 0, stream, (const T*)K, ld, n,
                        rows, (const T*)vin, (const T*)vown, (const T*)marg, (const T*)old, (T*)out,
-                       epi, (T)eta, (T*)err_out);
+                       epi, (T)eta, (T*)err_out, out_block_stride);
   else
     hipLaunchKernelGGL((rowpass_kernel<T, ROWS, false>), grid, block, 0, stream, (const T*)K, ld, n,
                        rows, (const T*)vin, (const T*)nullptr, (const T*)marg, (const T*)old,
-                       (T*)out, epi, (T)eta, (T*)err_out);
+                       (T*)out, epi, (T)eta, (T*)err_out, out_block_stride);
   FSK_LAUNCH_CHECK("rowpass_kernel");
   return FSK_OK;
 }
@@ -131,6 +136,17 @@ int launch_rowpass(int dtype, const void* K, int64_t ld, int n, int rows, const 
                                                   epi, eta, err_out, stream)
                           : rowpass_typed<float>(K, ld, n, rows, 1, vin, nullptr, marg, old, out, epi,
                                                  eta, err_out, stream);
+}
+
+int launch_rowpass_colblocks(int dtype, const void* K, int64_t ld, int ncols, int rows, int blocks,
+                             const void* vin, void* out, int64_t out_block_stride,
+                             hipStream_t stream) {
+  if (blocks > 65535) return set_error(FSK_EUNSUPPORTED, "more than 65535 column blocks in one launch");
+  return dtype == FSK_F64
+             ? rowpass_typed<double>(K, ld, ncols, rows, 1, vin, nullptr, nullptr, nullptr, out,
+                                     kEpiProduct, 1.0, nullptr, stream, blocks, out_block_stride)
+             : rowpass_typed<float>(K, ld, ncols, rows, 1, vin, nullptr, nullptr, nullptr, out,
+                                    kEpiProduct, 1.0, nullptr, stream, blocks, out_block_stride);
 }
 
 int launch_rowpass_slabs(int dtype, const void* K, int64_t ld, int n, int rows, int slabs,
@@ -265,9 +281,11 @@ template <typename T>
 __global__ __launch_bounds__(256) void colreduce_kernel(const T* __restrict__ partial,
                                                         int64_t ld_ws, int n_partials, int c0,
                                                         int c1, const T* marg, const T* old, T* out,
-                                                        int epi, T eta, int aligned) {
+                                                        int epi, T eta, int aligned, int groups) {
+  // groups > 0: exactly that many groups (it divides n_partials): the sums of the 2D block grid,
+  // block products first, then the blocks in block order
   constexpr int W = Pack<T>::W;
-  const int G = colreduce_groups(n_partials, ld_ws / W), Q = 256 / G;
+  const int G = groups > 0 ? groups : colreduce_groups(n_partials, ld_ws / W), Q = 256 / G;
   const int q = threadIdx.x % Q, g = threadIdx.x / Q;
   const int j = c0 + (blockIdx.x * Q + q) * W;  // first column of this thread's pack
   const int per = (n_partials + G - 1) / G;
@@ -277,7 +295,7 @@ __global__ __launch_bounds__(256) void colreduce_kernel(const T* __restrict__ pa
   Pack<T> acc;
 #pragma unroll
   for (int e = 0; e < W; ++e) acc.e[e] = T(0);
-  if (j < c1) {
+  if (j < c1 && g < G) {
     const T* p = partial + (int64_t)s0 * ld_ws + j;
     if (whole) {
 #pragma unroll 8
@@ -320,24 +338,28 @@ __global__ __launch_bounds__(256) void colreduce_kernel(const T* __restrict__ pa
 template <typename T>
 static int colreduce_typed(const void* partial, int64_t ld_ws, int n_partials, int c0, int c1,
                            const void* marg, const void* old, void* out, int epi, double eta,
-                           hipStream_t stream) {
+                           hipStream_t stream, int groups) {
   if (c1 <= c0) return FSK_OK;
   constexpr int W = Pack<T>::W;
-  const int cols_per_wg = 256 / colreduce_groups(n_partials, ld_ws / W) * W;
+  if (groups > 0 && (groups > 256 || n_partials % groups != 0))
+    return set_error(FSK_EINVAL, "%d groups do not divide %d partial sums", groups, n_partials);
+  const int G = groups > 0 ? groups : colreduce_groups(n_partials, ld_ws / W);
+  const int cols_per_wg = 256 / G * W;
   const int aligned = ld_ws % W == 0 && ((uintptr_t)((const T*)partial + c0)) % 16 == 0;
   dim3 grid((c1 - c0 + cols_per_wg - 1) / cols_per_wg), block(256);
   hipLaunchKernelGGL((colreduce_kernel<T>), grid, block, 0, stream, (const T*)partial, ld_ws,
-                     n_partials, c0, c1, (const T*)marg, (const T*)old, (T*)out, epi, (T)eta, aligned);
+                     n_partials, c0, c1, (const T*)marg, (const T*)old, (T*)out, epi, (T)eta, aligned,
+                     groups);
   FSK_LAUNCH_CHECK("colreduce_kernel");
   return FSK_OK;
 }
 
 int launch_colreduce(int dtype, const void* partial, int64_t ld_ws, int n_partials, int c0, int c1,
                      const void* marg, const void* old, void* out, int epi, double eta,
-                     hipStream_t stream) {
+                     hipStream_t stream, int groups) {
   return dtype == FSK_F64
-             ? colreduce_typed<double>(partial, ld_ws, n_partials, c0, c1, marg, old, out, epi, eta, stream)
-             : colreduce_typed<float>(partial, ld_ws, n_partials, c0, c1, marg, old, out, epi, eta, stream);
+             ? colreduce_typed<double>(partial, ld_ws, n_partials, c0, c1, marg, old, out, epi, eta, stream, groups)
+             : colreduce_typed<float>(partial, ld_ws, n_partials, c0, c1, marg, old, out, epi, eta, stream, groups);
 }
 
 __device__ __forceinline__ float fsk_log2(float x) { return log2f(x); }

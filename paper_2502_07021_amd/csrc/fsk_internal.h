@@ -76,9 +76,18 @@ int launch_colpartial(int dtype, const void* K, int64_t ld, int n, int rows, int
                       const void* u, void* partial, int64_t ld_ws, hipStream_t stream);
 
 // out[j] = epilogue(marg[j], sum_s partial[s][j], old[j]) for j in [c0, c1).
+// groups > 0: the partial rows are summed in exactly that many contiguous groups (it must divide
+// n_partials and be at most 256), each in index order, then the group sums in group order -- block
+// products first, then the blocks; 0: a grouping chosen from the number of partials and the pitch.
 int launch_colreduce(int dtype, const void* partial, int64_t ld_ws, int n_partials, int c0, int c1,
                      const void* marg, const void* old, void* out, int epi, double eta,
-                     hipStream_t stream);
+                     hipStream_t stream, int groups = 0);
+
+// The block products K_{:,J_z} v_{J_z} of `blocks` column blocks of `ncols` columns each, over
+// `rows` rows, in ONE grid: out + z*out_block_stride receives block z's `rows` products.
+int launch_rowpass_colblocks(int dtype, const void* K, int64_t ld, int ncols, int rows, int blocks,
+                             const void* vin, void* out, int64_t out_block_stride,
+                             hipStream_t stream);
 
 // Geometry of the fused one-pass kernel: every row block of m rows is cut into strips of h rows;
 // a strip is streamed by gb workgroups, each of which leaves one row of partial column sums.
