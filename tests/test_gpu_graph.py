@@ -91,3 +91,35 @@ def test_log_domain_call_in_a_graph():
         f.zero_(); g.zero_()
 
     _replay_matches_eager(lambda: api.fsk_sinkhorn_log_points(opts, x, y, w.eps, a, b, f, g, ws), [f, g], reset)
+
+
+@pytest.mark.parametrize("which", ["local_steps", "async", "grid", "static"])
+def test_other_dense_calls_in_a_graph(which):
+    """The schedules built from the two-pass kernels (their device-to-device copies become memcpy
+    nodes) and the dense call on the library's built-in scratch, which exists for exactly this
+    caller: code under capture cannot allocate."""
+    n = 1536
+    w = workloads.make(3, n=n)
+    opts = api.make_opts(n, torch.float32, c=4, max_iters=14)
+    K = torch.empty(n, n, device="cuda")
+    api.fsk_kernel_from_points(opts, dev(w.x), dev(w.y), 0.2, True, K,
+                               api.alloc_workspace(opts, api.FSK_MODE_SETUP))
+    a, b = dev(w.a), dev(w.b)
+    u = torch.empty(n, device="cuda"); v = torch.empty(n, device="cuda")
+
+    def reset():
+        u.fill_(1.0); v.fill_(1.0)
+
+    if which == "local_steps":
+        ws = torch.empty(api.fsk_local_steps_workspace_bytes(opts), dtype=torch.uint8, device="cuda")
+        call = lambda: api.fsk_sinkhorn_local_steps(opts, K, a, b, u, v, 3, ws)
+    elif which == "async":
+        opts.damping = api.FSK_DAMP_ARITHMETIC; opts.eta = 0.7
+        ws = torch.empty(api.fsk_async_workspace_bytes(opts, 1, 2), dtype=torch.uint8, device="cuda")
+        call = lambda: api.fsk_sinkhorn_async_emulated(opts, K, a, b, u, v, 1, 2, ws)
+    elif which == "grid":
+        ws = torch.empty(api.fsk_grid_workspace_bytes(opts, 4, 2), dtype=torch.uint8, device="cuda")
+        call = lambda: api.fsk_sinkhorn_grid(opts, K, a, b, u, v, 4, 2, ws)
+    else:
+        call = lambda: api.fsk_sinkhorn_dense_static(opts, K, a, b, u, v)
+    _replay_matches_eager(call, [u, v], reset)
