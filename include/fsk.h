@@ -138,6 +138,17 @@ int fsk_version(void);
 /* Message for the calling thread's last failed call ("" if none). Never NULL. */
 const char* fsk_last_error(void);
 
+/* Error trace (the paper logs the marginal error err_a against the iteration count, Sec. 5.4 and
+ * the convergence plots): lends the calling thread a host buffer of 2*capacity doubles.  From
+ * then on every tolerance-mode call of that thread (dense, log-domain, multitarget) restarts the
+ * trace and appends, at each poll, the pair (iteration whose state was polled, that state's
+ * error in opts->err_norm) -- no extra device work: these are the values the stop rule reads.
+ * fsk_error_trace_count() = polls of the thread's last tolerance-mode call (it keeps counting
+ * beyond the capacity, so a caller sees that the buffer was too small).  buf = NULL or
+ * capacity <= 0 switches the trace off.  The buffer must stay valid while it is lent. */
+void fsk_set_error_trace(double* buf, int32_t capacity);
+int32_t fsk_error_trace_count(void);
+
 /* Minimum workspace, in bytes, that a call of the given mode needs for these
  * options on the current device (0 on invalid options).  `d` is the point
  * dimension for FSK_MODE_LOG / FSK_MODE_SETUP and ignored otherwise. */

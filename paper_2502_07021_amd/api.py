@@ -37,6 +37,7 @@ EXPORTS = (
     "fsk_radius_search", "fsk_grid_workspace_bytes", "fsk_sinkhorn_grid", "fsk_dp_release",
     "fsk_sinkhorn_batched_dp", "fsk_rdp_epsilon", "fsk_set_barrier_poll_limit",
     "fsk_sinkhorn_dense_static", "fsk_local_steps_workspace_bytes", "fsk_sinkhorn_local_steps",
+    "fsk_set_error_trace", "fsk_error_trace_count",
 )
 FSK_STATIC_SCRATCH_BYTES = 34 * 1024 * 1024
 
@@ -267,6 +268,15 @@ def fsk_rdp_epsilon(clip, sigma, releases, delta, orders):
                                  ctypes.c_double(delta), arr, ctypes.c_int32(len(orders)),
                                  ctypes.byref(eps), ctypes.byref(order)))
     return float(eps.value), float(order.value)
+
+
+def fsk_set_error_trace(buf, capacity: int) -> None:
+    """buf: a ctypes array of 2*capacity doubles owned by the caller (None switches the trace off)."""
+    lib().fsk_set_error_trace(buf, ctypes.c_int32(capacity))
+
+
+def fsk_error_trace_count() -> int:
+    return int(lib().fsk_error_trace_count())
 
 
 def fsk_set_barrier_poll_limit(polls: int) -> None:

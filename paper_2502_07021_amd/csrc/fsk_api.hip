@@ -25,6 +25,19 @@ int set_error(int code, const char* fmt, ...) {
 }
 void clear_error() { g_err[0] = '\0'; }
 
+// Error trace of the calling thread: (iteration, error) pairs of the polls of its last
+// tolerance-mode call, in a buffer the caller lent with fsk_set_error_trace.
+static thread_local double* g_trace = nullptr;
+static thread_local int32_t g_trace_cap = 0, g_trace_len = 0;
+void trace_begin() { g_trace_len = 0; }
+void trace_poll(int iteration, double err) {
+  if (g_trace && g_trace_len < g_trace_cap) {
+    g_trace[2 * g_trace_len] = (double)iteration;
+    g_trace[2 * g_trace_len + 1] = err;
+  }
+  if (g_trace) ++g_trace_len;  // counts the polls that did not fit as well
+}
+
 int device_cu_count() {
   static int cached[64] = {0};
   int dev = 0;
@@ -119,6 +132,14 @@ extern "C" {
 int fsk_version(void) { return 100; }
 
 const char* fsk_last_error(void) { return g_err; }
+
+void fsk_set_error_trace(double* buf, int32_t capacity) {
+  g_trace = capacity > 0 ? buf : nullptr;
+  g_trace_cap = g_trace ? capacity : 0;
+  g_trace_len = 0;
+}
+
+int32_t fsk_error_trace_count(void) { return g_trace_len; }
 
 static size_t plan_ws_bytes(const fsk_opts* opts);
 
@@ -278,6 +299,7 @@ static int dense_solve(const fsk_opts* opts, const DenseWs& w, const void* K, in
   const bool resident = opts->flow == FSK_FLOW_RESIDENT;
   if (resident) FSK_TRY(check_resident(opts));
   const bool check = opts->tol > 0.0;
+  if (check) trace_begin();
   auto nonfinite = [&](int at) {
     if (iters_done) *iters_done = at;
     if (err) *err = e;
@@ -299,6 +321,7 @@ static int dense_solve(const fsk_opts* opts, const DenseWs& w, const void* K, in
       done = it;
       if (check && (done % opts->check_every == 0 || done == opts->max_iters)) {
         FSK_TRY(state_error());
+        trace_poll(done, e);
         if (!std::isfinite(e)) return nonfinite(done);
         if (e < opts->tol) break;
       }
@@ -327,6 +350,7 @@ static int dense_solve(const fsk_opts* opts, const DenseWs& w, const void* K, in
         FSK_HIP(hipMemcpyAsync(&e, scalar, sizeof(double), hipMemcpyDeviceToHost, st));
         FSK_HIP(hipStreamSynchronize(st));
         if (l2) e = sqrt(e);
+        trace_poll(it, e);
         if (!std::isfinite(e)) {  // hand back the polled state itself, not the one advanced past it
           FSK_HIP(hipMemcpyAsync(u, save_u, vec_bytes, hipMemcpyDeviceToDevice, st));
           FSK_HIP(hipMemcpyAsync(v, save_v, vec_bytes, hipMemcpyDeviceToDevice, st));
@@ -346,6 +370,7 @@ static int dense_solve(const fsk_opts* opts, const DenseWs& w, const void* K, in
     }
     if (check && !converged && done > 0) {  // the state after the last iteration is always polled
       FSK_TRY(state_error());
+      trace_poll(done, e);
       if (!std::isfinite(e)) return nonfinite(done);
     }
   }

@@ -42,6 +42,11 @@ inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 
 // Compute units of the current device (cached per device), 0 on failure.
 int device_cu_count();
 
+// The calling thread's error trace (fsk_set_error_trace): a tolerance-mode call resets it when it
+// starts and records every poll -- the iteration whose state was polled and that state's error.
+void trace_begin();
+void trace_poll(int iteration, double err);
+
 // ------------------------------------------------------------------ dense kernels
 constexpr int kColStrip = 128;  // rows summed sequentially into one partial column sum
 
@@ -226,6 +231,7 @@ inline int batched_iterate(const fsk_opts* o, const void* A, void* U, void* V, c
     FSK_HIP(hipStreamSynchronize(st));
     return FSK_OK;
   };
+  if (check) trace_begin();
   auto nonfinite = [&](int at) {
     if (poll->iters_done) *poll->iters_done = at;
     if (poll->err) *poll->err = e;
@@ -238,6 +244,7 @@ inline int batched_iterate(const fsk_opts* o, const void* A, void* U, void* V, c
       FSK_TRY(u_update(tmp));
       if (p) {
         FSK_TRY(read_error(U, tmp));
+        trace_poll(it, e);
         if (!(e == e) || e > 1.7e308) return nonfinite(it);
         if (e < poll->tol) {  // U has not been touched yet
           done = it;
@@ -251,6 +258,7 @@ inline int batched_iterate(const fsk_opts* o, const void* A, void* U, void* V, c
       FSK_TRY(u_update(U));
       if (p) {
         FSK_TRY(read_error(tmp, U));
+        trace_poll(it, e);
         if (!(e == e) || e > 1.7e308) return nonfinite(it);
         if (e < poll->tol) {  // undo the update that revealed it
           FSK_HIP(hipMemcpyAsync(U, tmp, bytes, hipMemcpyDeviceToDevice, st));
@@ -274,6 +282,7 @@ inline int batched_iterate(const fsk_opts* o, const void* A, void* U, void* V, c
   if (check && !converged && done > 0) {  // the state after the last iteration is always polled
     FSK_TRY(u_update(tmp));                // its next (undamped) U, only to read the error off it
     FSK_TRY(read_error(U, tmp));
+    trace_poll(done, e);
     if (!(e == e) || e > 1.7e308) return nonfinite(done);
   }
   if (poll) {

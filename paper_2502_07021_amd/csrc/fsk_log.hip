@@ -626,6 +626,7 @@ static int run_log_typed(const fsk_opts* o, const void* x, const void* y, int d,
   int done = 0;
   double e = NAN;
   bool converged = false;
+  if (o->tol > 0.0) trace_begin();
   for (int it = 0; it < o->max_iters; ++it) {
     const bool poll = o->tol > 0.0 && it > 0 && it % o->check_every == 0;
     if (poll) FSK_TRY(copy_state(false));
@@ -633,6 +634,7 @@ static int run_log_typed(const fsk_opts* o, const void* x, const void* y, int d,
     FSK_TRY(half_step(false, 0));
     if (poll) {
       FSK_TRY(read_error(&e));
+      trace_poll(it, e);
       if (!std::isfinite(e)) {  // hand back the polled state itself, not the one advanced past it
         FSK_TRY(copy_state(true));
         FSK_HIP(hipStreamSynchronize(st));
@@ -651,6 +653,7 @@ static int run_log_typed(const fsk_opts* o, const void* x, const void* y, int d,
   if (o->tol > 0.0 && !converged && done > 0) {  // the state after the last iteration is always polled
     FSK_TRY(half_step(true, 1));
     FSK_TRY(read_error(&e));
+    trace_poll(done, e);
     if (!std::isfinite(e)) return nonfinite(done, e);
   }
   if (iters_done) *iters_done = done;
