@@ -81,9 +81,17 @@ typedef enum {
                             whenever c divides S; if n/c is also a multiple of h the strips are
                             the same for every such c and the iterates equal those of c = 1
                             bit for bit, otherwise to rounding.                             */
-  FSK_FLOW_TWO_PASS = 1, /* q = K v over all rows, then r = K^T u over all rows (two passes)  */
+  FSK_FLOW_TWO_PASS = 1, /* q = K v over all rows, then r = K^T u over all rows (two passes);
+                            with c > 1 the c row slabs are one grid                          */
   FSK_FLOW_PAPER = 2,    /* Algorithm 1 as printed: block j forms u_{I_j} from its row slab,
-                            then r_{I_j} = (K_{:,I_j})^T u from its column slab              */
+                            then r_{I_j} = (K_{:,I_j})^T u from its column slab.  On one device
+                            the c column slabs tile the column range and every column is summed
+                            on its own over the same 128-row strips, so the slabs are served by
+                            one launch over all columns: the enqueued kernels, and the bits,
+                            are those of TWO_PASS.  What a client of this flow can see and
+                            TWO_PASS's cannot -- vectors that differ from client to client --
+                            is what fsk_sinkhorn_local_steps and
+                            fsk_sinkhorn_async_emulated run on these slabs.                   */
   FSK_FLOW_RESIDENT = 3  /* small K only (n <= 1024 in fp32, n <= 512 in fp64): a
                             persistent grid of 8-32 workgroups holds K in registers and runs
                             all the iterations between two polls in ONE launch, exchanging the

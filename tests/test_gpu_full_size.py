@@ -186,8 +186,8 @@ def test_cfg3_full_1000_iterations_against_oracle(orc, capsys):
     K, _ = orc.gibbs_from_points_f32(w.x, w.y, w.eps, True)
     Kd = dev(K); a = dev(w.a); b = dev(w.b)
 
-    def run(iters):
-        opts = api.make_opts(n, torch.float32, c=8, max_iters=iters, flow=api.FSK_FLOW_FUSED)
+    def run(iters, flow=api.FSK_FLOW_FUSED):
+        opts = api.make_opts(n, torch.float32, c=8, max_iters=iters, flow=flow)
         ws = api.alloc_workspace(opts)
         u = torch.ones(n, device="cuda"); v = torch.ones(n, device="cuda")
         api.fsk_sinkhorn_dense(opts, Kd, a, b, u, v, ws)
@@ -211,6 +211,14 @@ def test_cfg3_full_1000_iterations_against_oracle(orc, capsys):
     assert relerr(rm, orc.row_marginal(K, uo, vo)) <= 1e-4
     assert relerr(cm, orc.col_marginal(K, uo, vo)) <= 1e-4
     say(capsys, f"cfg3 full run: worst relative error on u, v over the checkpoints {worst:.2e}")
+    # Algorithm 1 as printed (row slabs, then column slabs), the same 1000 iterations
+    u, v, rm, cm = run(T, flow=api.FSK_FLOW_PAPER)
+    eu, ev = relerr(u, uo), relerr(v, vo)
+    gu, du = gauge_free(u, uo); gv, dv = gauge_free(v, vo)
+    say(capsys, f"cfg3 t={T}, Algorithm-1 flow: relerr u {eu:.2e} v {ev:.2e}; gauge-free u {gu:.2e} v {gv:.2e}; "
+                f"uniform drift u {du:.2e} v {dv:.2e}")
+    assert eu <= 1e-4 and ev <= 1e-4 and gu <= 1e-4 and gv <= 1e-4
+    assert relerr(cm, orc.col_marginal(K, uo, vo)) <= 1e-4
 
 
 def test_cfg5_full_300_iterations_against_oracle(orc, capsys):
