@@ -124,6 +124,21 @@ def test_cfg4_n65536_log_domain(orc):
     cm = orc.log_row_marginal_points(w.y, gh, w.x, fh, eps, rows)
     assert np.max(np.abs(cm - w.b[rows]) / w.b[rows]) <= 1e-4
 
+    # the cap binds because of the law's convergence rate, not because of fp32 potentials: the
+    # all-fp64 interface follows the same error curve to the same cap
+    def run64(iters, tol, every):
+        opts = api.make_opts(n, torch.float64, max_iters=iters, tol=tol, check_every=every)
+        ws = api.alloc_workspace(opts, api.FSK_MODE_LOG, d)
+        f = torch.zeros(n, dtype=torch.float64, device="cuda"); g = torch.zeros_like(f)
+        done, err = api.fsk_sinkhorn_log_points(opts, dev(w.x.astype(np.float64)), dev(w.y.astype(np.float64)),
+                                                eps, dev(w.a.astype(np.float64)), dev(w.b.astype(np.float64)),
+                                                f, g, ws)
+        return done, err
+    _, _, done32, err32 = run(2000, tol=1e-6, check_every=500)
+    done64, err64 = run64(2000, 1e-6, 500)
+    assert done32 == done64 == 2000 and err64 > 1e-6
+    assert err32 == pytest.approx(err64, rel=1e-2)
+
 
 def test_cfg5_n16384_m64_batched(orc):
     w = workloads.make(5)
