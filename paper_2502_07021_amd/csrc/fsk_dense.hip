@@ -629,10 +629,13 @@ FusedPlan fused_plan(int dtype, int n, int m, int c) {
   const int groups = (p.h + p.r - 1) / p.r;
   const int gb = kFusedWorkgroups / strips;
   p.gb = gb < groups ? gb : groups;
-  // staggered starts pay once a strip has enough row groups to spread over (measured: 615 against
-  // 618 us per iteration at n = 32768, 167 against 172 at 16384, 361 against 377 at 24576; at
-  // n = 8192, 8 groups per strip, 53.3 against 52.3)
-  p.rotmul = groups >= 16 ? 21 : 0;
+  // Staggered starts (strip s begins at row group 21 s mod groups) pay in the middle of the size
+  // range once a strip has enough row groups to spread over -- n = 24576: 353 against 380 us per
+  // iteration, 16384: 163.0 against 163.4 -- and cost a little where a row is a whole 120-128 KiB
+  // (n = 32768: 609.3 against 605.6-607, 30000: 547 against 544) and at n = 8192 (8 groups per
+  // strip: 53.3 against 52.3).  Measured on the kernel as it stands; an earlier loop structure
+  // preferred them at every large size.
+  p.rotmul = (groups >= 16 && vpt < 15) ? 21 : 0;
   p.lds_bytes = (size_t)vpt * 512 * 16 + (size_t)2 * p.r * 8 * elem_size(dtype);
   return p;
 }
