@@ -13,13 +13,16 @@
 // wave owns a 128 x 64 output tile (4 x 2 MFMA blocks, 128 accumulator registers, one wave
 // per SIMD), a workgroup of 4 waves 512 x 64 and one part of the contraction range, walked in
 // chunks of 32 indices.  K goes straight from global memory into registers (128-bit
-// non-temporal loads, one chunk ahead of the MFMAs); the chunk of the n x m operand (32 x 64
-// values) is shared by the four waves through LDS, double buffered, one barrier per chunk.
+// non-temporal buffer loads, one chunk ahead of the MFMAs, addressed as scalar base + scalar
+// row offset + a fixed lane offset so that no vector instruction stands between two MFMAs);
+// the chunk of the n x m operand (32 x 64 values) is shared by the four waves through LDS,
+// double buffered, one barrier per chunk.
 // Wider problems (the paper stacks N = 500 targets and more) run as ceil(m / 64) column groups
 // inside the same launch.  The 1-D grid is row tiles x column groups x S parts of the
 // contraction range, S chosen so that the grid fills the compute units; for S > 1 the partial
-// tiles go to the workspace and a reduction kernel adds them in fixed order and applies the
-// division (S = 1: the division is fused into the tile store).  When the workspace has no room
+// tiles go to the workspace in the order the wave's registers hold them (whole-KiB stores) and
+// a reduction kernel adds them in fixed order and applies the division (S = 1: the division
+// is fused into the tile store).  When the workspace has no room
 // for K^T, Q = K V falls back to batched_rowprod_kernel, the direct walk with a 64 x 64 tile per
 // wave, one column group per launch.
 //
@@ -29,6 +32,8 @@
 // so lane (.., h = l/32) supplies index (C/2) h + e.
 #include "fsk_device.h"
 #include "fsk_internal.h"
+
+#include <type_traits>
 
 namespace fsk {
 
@@ -220,18 +225,30 @@ __global__ __launch_bounds__(256) void batched_rowprod_kernel(const float* __res
 // kernel above; the loads of the next chunk are in flight under the 128 MFMAs of this one.
 constexpr int kBtWideWaveTile = 128;
 constexpr int kBtWideTile = kBtWideWaveTile * kBtWaves;
+constexpr int kBtWaveTileFloats = kBtWideWaveTile * kBtCols;  // one wave's partial tile
+
+// A partial tile (the grid splits the contraction range) is stored in the order the wave holds it:
+// [MFMA block a][block b][register quad vq][lane][4 registers], one 128-bit store per lane and
+// quad, a whole KiB per instruction.  Element j of that pack is output row
+// 128 wt + 4 (8 vq + 4 (lane / 32) + j) + a and column 32 b + lane % 32 of the wave's tile wt; the
+// partial area of one (column group, slice) holds ceil(n / 128) such tiles.
+__host__ __device__ inline int64_t bt_partial_area(int n) {
+  return (int64_t)((n + kBtWideWaveTile - 1) / kBtWideWaveTile) * kBtWaveTileFloats;
+}
 
 // X, marg and out (final) are n x mtot with row pitch mtot; the grid covers `groups` column
 // groups of up to 64 columns, `slices` contraction slices and the row tiles.  final == 0: the
-// partial product of (group g, slice s) goes, densely packed with pitch = the group's column
-// count, to out + (g * slices + s) * n * 64.
+// partial product of (group g, slice s) goes to out + (g * slices + s) * bt_partial_area(n) in
+// the layout described above.  XVEC: mtot is a multiple of 4 and X is 16-byte aligned, so the
+// X chunk is staged with 128-bit accesses.
+template <bool XVEC>
 __global__ __launch_bounds__(256) void batched_prod_wide_kernel(const float* __restrict__ K,
                                                                 int64_t ld, int n, int mtot,
                                                                 const float* __restrict__ X,
                                                                 const float* __restrict__ marg,
                                                                 float* __restrict__ out, int final,
                                                                 int slices, int groups) {
-  __shared__ float xs[2][kBtChunk][kBtCols];
+  __shared__ __attribute__((aligned(16))) float xs[2][kBtChunk][kBtCols];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int r = lane & 31, h = lane >> 5;
   // 1-D grid, slice fastest: workgroups are dealt to the 8 XCDs round-robin, so the workgroups
@@ -267,9 +284,11 @@ __global__ __launch_bounds__(256) void batched_prod_wide_kernel(const float* __r
   jc = jc < jmax ? jc : jmax;
   const float* kcol = K + jc;
   // Addresses are split into a byte offset that belongs to the lane (its columns and its
-  // half-wave's row inside a chunk; 32 bits, formed once) and a row pointer that is the same for
-  // the whole wave and advances by one row pitch per k-step on the scalar unit.
+  // half-wave's row inside a chunk; 32 bits, formed once) and a wave-uniform part: the chunk's
+  // first row (the base of a buffer descriptor, advanced once per chunk on the scalar unit) plus
+  // e row pitches for k-step e (a scalar offset).
   const uint32_t kb = (uint32_t)(((int64_t)(kBtHalf * h) * ld + jc) * 4);
+  const uint32_t ldb = (uint32_t)(ld * 4), ldmb = (uint32_t)(ldm * 4);
   auto at = [&](const float* row, uint32_t lane_bytes) {
     return reinterpret_cast<const float*>(reinterpret_cast<const char*>(row) + lane_bytes);
   };
@@ -290,9 +309,16 @@ __global__ __launch_bounds__(256) void batched_prod_wide_kernel(const float* __r
     }
   };
 
+  // Staging of the X chunk (32 x 64 values) through registers into LDS.  Scalar form: thread =
+  // (column sc, rows sk + 4 i), 8 values.  Vector form: thread = (four columns from 4 xq, rows xr
+  // and xr + 16), two 128-bit packs.  Columns >= m are clamped duplicates (they only feed output
+  // columns that are never stored).
   const int sc = tid & 63, sk = tid >> 6;
   const float* xcol = X + (sc < m ? sc : m - 1);
   const uint32_t xb = (uint32_t)(((int64_t)sk * ldm + (sc < m ? sc : m - 1)) * 4);  // lane's bytes
+  const int xr = tid >> 4, xq = tid & 15;
+  const int xc4 = 4 * xq + 3 < m ? 4 * xq : (m >= 4 ? m - 4 : 0);
+  const uint32_t xvb = (uint32_t)(((int64_t)xr * ldm + xc4) * 4);
   auto load_x = [&](int c, float(&st)[kBtStage]) {
     const float* row = X + (int64_t)c * kBtChunk * ldm;
 #pragma unroll
@@ -309,6 +335,10 @@ __global__ __launch_bounds__(256) void batched_prod_wide_kernel(const float* __r
   auto store_x = [&](int buf, const float(&st)[kBtStage]) {
 #pragma unroll
     for (int i = 0; i < kBtStage; ++i) xs[buf][sk + 4 * i][sc] = st[i];
+  };
+  auto store_xv = [&](int buf, const Pack<float>(&sv)[2]) {
+    store_pack(&xs[buf][xr][4 * xq], sv[0]);
+    store_pack(&xs[buf][xr + 16][4 * xq], sv[1]);
   };
   auto multiply = [&](int buf, const Pack<float>(&ka)[kBtHalf]) {
     float b0[kBtHalf], b1[kBtHalf];  // the chunk's B operands, fetched from LDS up front
@@ -329,28 +359,36 @@ __global__ __launch_bounds__(256) void batched_prod_wide_kernel(const float* __r
   };
 
   // One chunk of the steady state: the MFMAs of the chunk in `ka` / xs[buf], whose first two
-  // k-steps' B operands arrive in `bcur`, with everything the NEXT chunk (cn) needs spread
-  // between them: one K load per k-step, the X loads on the first kBtStage k-steps (so that they
-  // have landed when they are staged), the staging into xs[buf ^ 1] and the workgroup barrier
-  // after k-step kBtHalf - 2, and the LDS reads of the next chunk's first two k-steps (into
-  // `bnext`) before the last k-step.  A wave issues in order, so a burst of loads, a wait for
-  // memory or a barrier at the chunk boundary would leave the matrix pipe without work; spread
-  // out like this, nothing stands between the last MFMA of one chunk and the first of the next.
-  // The scheduling barriers pin the order (left alone the scheduler sinks the loads to the end
-  // of the chunk).  Two LDS buffers suffice: every read of xs[buf] has completed (the barrier's
-  // own wait) before any wave passes the barrier after which xs[buf] is written again.
-  auto chunk_step = [&](int buf, const Pack<float>(&ka)[kBtHalf], const float(&bcur)[2][2], int cn,
+  // k-steps' B operands arrive in `bcur`.  With NEXT, everything the following chunk needs is
+  // spread between them: its X rows (from `xrow`) are requested first -- before any K load of
+  // this chunk, so that waiting for them later does not also wait for K loads issued since (the
+  // memory counter retires loads in order) --, one K load (rows from `krow` on) follows every
+  // k-step, the X values go to xs[buf ^ 1] and the workgroup meets at a barrier after k-step
+  // kBtHalf - 2, and the following chunk's first two B operands are read (into `bnext`) before the
+  // last k-step.  A wave issues in order, so a burst of loads, a wait for memory or a barrier at
+  // the chunk boundary would leave the matrix pipe without work; spread out like this, nothing
+  // stands between the last MFMA of one chunk and the first of the next.  The scheduling
+  // barriers pin the order (left alone the scheduler sinks the loads to the end of the chunk).
+  // Two LDS buffers suffice: every read of xs[buf] has completed (the barrier's own wait) before
+  // any wave passes the barrier after which xs[buf] is written again.
+  auto chunk_step = [&](auto next_tag, int buf, const Pack<float>(&ka)[kBtHalf],
+                        const float(&bcur)[2][2], const float* krow, const float* xrow,
                         Pack<float>(&kn)[kBtHalf], float(&bnext)[2][2]) {
+    constexpr bool NEXT = decltype(next_tag)::value;
     static_assert(kBtStage <= kBtHalf - 2, "the X loads must be issued before they are staged");
     float b0[kBtHalf], b1[kBtHalf];  // B operands: two k-steps ahead of the MFMAs that use them
     float stn[kBtStage];
-    const float* krow = K + (int64_t)cn * kBtChunk * ld;
-    const float* xrow = X + (int64_t)cn * kBtChunk * ldm;
+    Pack<float> svn[2];
 #pragma unroll
     for (int e = 0; e < 2; ++e) b0[e] = bcur[e][0], b1[e] = bcur[e][1];
+    const __amdgpu_buffer_rsrc_t rk = buffer_over(krow), rx = buffer_over(xrow);
+    if (NEXT && XVEC) {
+      svn[0] = buffer_load_pack<float, false>(rx, xvb, 0);
+      svn[1] = buffer_load_pack<float, false>(rx, xvb, 16 * ldmb);
+    }
 #pragma unroll
     for (int e = 0; e < kBtHalf; ++e) {
-      if (e == kBtHalf - 1) {  // after the barrier: the next chunk's first operands
+      if (NEXT && e == kBtHalf - 1) {  // after the barrier: the next chunk's first operands
 #pragma unroll
         for (int t = 0; t < 2; ++t) {
           bnext[t][0] = xs[buf ^ 1][kBtHalf * h + t][r];
@@ -366,38 +404,19 @@ __global__ __launch_bounds__(256) void batched_prod_wide_kernel(const float* __r
         b0[e + 2] = xs[buf][kBtHalf * h + e + 2][r];
         b1[e + 2] = xs[buf][kBtHalf * h + e + 2][32 + r];
       }
-      kn[e] = load_pack_stream(at(krow, kb));
-      krow += ld;
-      if (e < kBtStage) {
-        stn[e] = *at(xrow, xb);
-        xrow += 4 * ldm;
-      }
-      if (e == kBtHalf - 2) {
-        store_x(buf ^ 1, stn);
-        __syncthreads();
+      if (NEXT) {
+        kn[e] = buffer_load_pack<float, true>(rk, kb, e * ldb);
+        if (!XVEC && e < kBtStage) stn[e] = *at(xrow + (int64_t)4 * e * ldm, xb);
+        if (e == kBtHalf - 2) {
+          if (XVEC) store_xv(buf ^ 1, svn); else store_x(buf ^ 1, stn);
+          __syncthreads();
+        }
       }
       __builtin_amdgcn_sched_barrier(0);
     }
   };
-  // A chunk with no successor to prepare: operands of k-steps 0, 1 in `bcur`, the rest read two
-  // k-steps ahead.
-  auto chunk_last = [&](int buf, const Pack<float>(&ka)[kBtHalf], const float(&bcur)[2][2]) {
-    float b0[kBtHalf], b1[kBtHalf];
-#pragma unroll
-    for (int e = 0; e < 2; ++e) b0[e] = bcur[e][0], b1[e] = bcur[e][1];
-#pragma unroll
-    for (int e = 0; e < kBtHalf; ++e) {
-#pragma unroll
-      for (int a = 0; a < 4; ++a) {
-        acc[a][0] = mfma32(ka[e].e[a], b0[e], acc[a][0]);
-        acc[a][1] = mfma32(ka[e].e[a], b1[e], acc[a][1]);
-      }
-      if (e + 2 < kBtHalf) {
-        b0[e + 2] = xs[buf][kBtHalf * h + e + 2][r];
-        b1[e + 2] = xs[buf][kBtHalf * h + e + 2][32 + r];
-      }
-    }
-  };
+  const std::true_type with_next;
+  const std::false_type last;
 
   Pack<float> kaA[kBtHalf], kaB[kBtHalf];
   float st[kBtStage];
@@ -413,15 +432,20 @@ __global__ __launch_bounds__(256) void batched_prod_wide_kernel(const float* __r
       bA[t][0] = xs[0][kBtHalf * h + t][r];
       bA[t][1] = xs[0][kBtHalf * h + t][32 + r];
     }
+    const int64_t kstep = (int64_t)kBtChunk * ld, xstep = (int64_t)kBtChunk * ldm;
+    const float* kp = K + (int64_t)(c0 + 1) * kstep;  // first rows of the chunk prepared next
+    const float* xp = X + (int64_t)(c0 + 1) * xstep;
     for (; c + 2 < full_end; c += 2) {  // chunks c and c + 1 both have a successor to prepare
-      chunk_step(0, kaA, bA, c + 1, kaB, bB);
-      chunk_step(1, kaB, bB, c + 2, kaA, bA);
+      chunk_step(with_next, 0, kaA, bA, kp, xp, kaB, bB);
+      chunk_step(with_next, 1, kaB, bB, kp + kstep, xp + xstep, kaA, bA);
+      kp += 2 * kstep;
+      xp += 2 * xstep;
     }
     if (c + 1 < full_end) {  // two whole chunks left
-      chunk_step(0, kaA, bA, c + 1, kaB, bB);
-      chunk_last(1, kaB, bB);
+      chunk_step(with_next, 0, kaA, bA, kp, xp, kaB, bB);
+      chunk_step(last, 1, kaB, bB, kp, xp, kaA, bA);
     } else {                 // one
-      chunk_last(0, kaA, bA);
+      chunk_step(last, 0, kaA, bA, kp, xp, kaB, bB);
     }
     __syncthreads();
   }
@@ -434,28 +458,40 @@ __global__ __launch_bounds__(256) void batched_prod_wide_kernel(const float* __r
     multiply(0, kaA);
   }
 
-  float* dst = final ? out + col0 : out + ((int64_t)grp * slices + slice) * n * kBtCols;
+  if (final) {
+    float* dst = out + col0;
 #pragma unroll
-  for (int a = 0; a < 4; ++a)
+    for (int a = 0; a < 4; ++a)
 #pragma unroll
-    for (int v = 0; v < 16; ++v) {
-      const int i = 8 * (v / 4) + 4 * h + (v % 4);
-      const int row = o0 + 4 * i + a;
-      if (row < n) {
+      for (int v = 0; v < 16; ++v) {
+        const int i = 8 * (v / 4) + 4 * h + (v % 4);
+        const int row = o0 + 4 * i + a;
+        if (row < n) {
 #pragma unroll
-        for (int b = 0; b < 2; ++b) {
-          const int col = 32 * b + r;
-          if (col < m) {
-            if (final) {
+          for (int b = 0; b < 2; ++b) {
+            const int col = 32 * b + r;
+            if (col < m) {
               const int64_t idx = (int64_t)row * ldm + col;
               dst[idx] = marg[idx] / acc[a][b][v];
-            } else {
-              dst[(int64_t)row * m + col] = acc[a][b][v];
             }
           }
         }
       }
-    }
+  } else if (o0 < n) {
+    float* dst = out + ((int64_t)grp * slices + slice) * bt_partial_area(n) +
+                 (int64_t)(o0 / kBtWideWaveTile) * kBtWaveTileFloats + 4 * lane;
+#pragma unroll
+    for (int a = 0; a < 4; ++a)
+#pragma unroll
+      for (int b = 0; b < 2; ++b)
+#pragma unroll
+        for (int vq = 0; vq < 4; ++vq) {
+          Pack<float> p;
+#pragma unroll
+          for (int j = 0; j < 4; ++j) p.e[j] = acc[a][b][4 * vq + j];
+          store_pack(dst + ((a * 2 + b) * 4 + vq) * 256, p);
+        }
+  }
 }
 
 // ------------------------------------------------------------------ K^T (setup, once per call)
@@ -510,9 +546,9 @@ static int batched_splits(int n) {
 
 static size_t batched_partial_bytes(int n, int m) {
   const int groups = (m + kBtCols - 1) / kBtCols;
-  const size_t wide = (size_t)batched_splits_wide(n, groups) * groups;  // tiles of n x 64
-  const size_t direct = (size_t)batched_splits(n);                      // one group at a time
-  return align_up((wide > direct ? wide : direct) * (size_t)n * kBtCols * 4, 256);
+  const size_t wide = (size_t)batched_splits_wide(n, groups) * groups * (size_t)bt_partial_area(n);
+  const size_t direct = (size_t)batched_splits(n) * (size_t)n * kBtCols;  // one group at a time
+  return align_up((wide > direct ? wide : direct) * 4, 256);
 }
 static int64_t batched_ldt(int n) { return (int64_t)align_up((size_t)n, 64); }
 
@@ -522,36 +558,44 @@ size_t batched_workspace_bytes(int n, int m) {
 }
 
 // out[row][col] = marg[row][col] / sum_s partial[g][s][row][col] for every column group g
-// (blockIdx.y): the partial tiles of a group are dense with pitch = the group's column count and
-// sit n * 64 apart; marg and out are n x mtot.  The slices are added in slice order.
-template <bool VEC>  // VEC: mtot is a multiple of 4 and marg, out are 16-byte aligned
+// (blockIdx.y).  A thread fetches one 128-bit pack of the wide kernel's partial layout (four rows,
+// 4 apart, of one column) and adds it over the slices in slice order; four adjacent lanes then
+// transpose their 4 x 4 values, so that each ends with four adjacent columns of one row and (vec:
+// mtot a multiple of 4, marg and out 16-byte aligned) reads marg and writes out 128 bits at a
+// time.  marg and out are n x mtot.
 __global__ __launch_bounds__(256) void batched_reduce_kernel(const float* __restrict__ partial,
                                                              int slices, int n, int mtot,
                                                              const float* __restrict__ marg,
-                                                             float* __restrict__ out) {
-  constexpr int E = VEC ? 4 : 1;
+                                                             float* __restrict__ out, int vec) {
   const int grp = blockIdx.y, col0 = grp * kBtCols;
   const int cols = mtot - col0 < kBtCols ? mtot - col0 : kBtCols;
-  const int64_t total = (int64_t)n * cols, stride = (int64_t)n * kBtCols;
-  const int64_t idx = ((int64_t)blockIdx.x * 256 + threadIdx.x) * E;
-  if (idx >= total) return;
-  const float* p = partial + (int64_t)grp * slices * stride + idx;
-  const int64_t o = (idx / cols) * mtot + col0 + idx % cols;
-  if (VEC) {
-    Pack<float> s = load_pack(p);
-    for (int k = 1; k < slices; ++k) {
-      const Pack<float> y = load_pack(p + (int64_t)k * stride);
+  const int64_t area = bt_partial_area(n);  // a multiple of 8192: a workgroup is all in or all out
+  const int64_t f = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (4 * f >= area) return;
+  const int r = (int)(f & 31), b = (int)(f >> 5) & 1, h = (int)(f >> 6) & 1, vq = (int)(f >> 7) & 3;
+  const int a = (int)(f >> 9) & 3, wt = (int)(f >> 11);
+  const float* p = partial + (int64_t)grp * slices * area + (int64_t)wt * kBtWaveTileFloats +
+                   4 * ((((a * 2 + b) * 4 + vq) * 2 + h) * 32 + r);
+  Pack<float> s = load_pack(p);
+  for (int k = 1; k < slices; ++k) {
+    const Pack<float> y = load_pack(p + (int64_t)k * area);
 #pragma unroll
-      for (int e = 0; e < 4; ++e) s.e[e] += y.e[e];
-    }
+    for (int e = 0; e < 4; ++e) s.e[e] += y.e[e];
+  }
+  lanes_transpose4(s.e, r);  // now: row index j = r % 4, columns 4 (r / 4) .. + 3 of block b
+  const int row = wt * kBtWideWaveTile + 4 * (8 * vq + 4 * h + (r & 3)) + a;
+  const int col = 32 * b + (r & ~3);
+  if (row >= n || col >= cols) return;
+  const int64_t o = (int64_t)row * mtot + col0 + col;
+  if (vec) {  // cols is then a multiple of 4
     const Pack<float> mg = load_pack(marg + o);
 #pragma unroll
     for (int e = 0; e < 4; ++e) s.e[e] = mg.e[e] / s.e[e];
     store_pack(out + o, s);
   } else {
-    float s = p[0];
-    for (int k = 1; k < slices; ++k) s += p[(int64_t)k * stride];
-    out[o] = marg[o] / s;
+#pragma unroll
+    for (int e = 0; e < 4; ++e)
+      if (col + e < cols) out[o + e] = marg[o + e] / s.e[e];
   }
 }
 
@@ -604,21 +648,22 @@ int run_sinkhorn_batched(const fsk_opts* o, const void* K, int64_t ldK, const vo
   const int SW = batched_splits_wide(n, groups);
   dim3 gridw(((n + kBtWideTile - 1) / kBtWideTile) * SW * groups);
   auto reduce_all = [&](const float* marg, float* dst) -> int {
-    const bool vec = m % 4 == 0 && ((uintptr_t)marg % 16 == 0) && ((uintptr_t)dst % 16 == 0);
-    const int64_t per_group = (int64_t)n * kBtCols;
-    if (vec)
-      hipLaunchKernelGGL(batched_reduce_kernel<true>, dim3((unsigned)((per_group / 4 + 255) / 256), groups),
-                         dim3(256), 0, st, (const float*)part, SW, n, m, marg, dst);
-    else
-      hipLaunchKernelGGL(batched_reduce_kernel<false>, dim3((unsigned)((per_group + 255) / 256), groups),
-                         dim3(256), 0, st, (const float*)part, SW, n, m, marg, dst);
+    const int64_t packs = bt_partial_area(n) / 4;
+    const int vec = m % 4 == 0 && (uintptr_t)marg % 16 == 0 && (uintptr_t)dst % 16 == 0;
+    hipLaunchKernelGGL(batched_reduce_kernel, dim3((unsigned)((packs + 255) / 256), groups), dim3(256), 0, st,
+                       (const float*)part, SW, n, m, marg, dst, vec);
     FSK_LAUNCH_CHECK("batched_reduce_kernel");
     return FSK_OK;
   };
   auto wide = [&](const float* Km, int64_t ldm_k, const float* X, const float* marg, float* dst,
                   const char* what) -> int {
-    hipLaunchKernelGGL(batched_prod_wide_kernel, gridw, block, 0, st, Km, ldm_k, n, m, X, marg,
-                       SW == 1 ? dst : part, SW == 1 ? 1 : 0, SW, groups);
+    const bool xvec = m % 4 == 0 && (uintptr_t)X % 16 == 0;  // 128-bit staging of the n x m operand
+    if (xvec)
+      hipLaunchKernelGGL(batched_prod_wide_kernel<true>, gridw, block, 0, st, Km, ldm_k, n, m, X, marg,
+                         SW == 1 ? dst : part, SW == 1 ? 1 : 0, SW, groups);
+    else
+      hipLaunchKernelGGL(batched_prod_wide_kernel<false>, gridw, block, 0, st, Km, ldm_k, n, m, X, marg,
+                         SW == 1 ? dst : part, SW == 1 ? 1 : 0, SW, groups);
     FSK_LAUNCH_CHECK(what);
     if (SW > 1) FSK_TRY(reduce_all(marg, dst));
     return FSK_OK;

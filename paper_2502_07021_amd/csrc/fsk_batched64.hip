@@ -15,10 +15,15 @@
 // through LDS (double buffered, one barrier per chunk, placed inside the chunk so that the matrix
 // pipe has work queued while the waves meet); the next chunk's loads are spread between the
 // MFMAs of the current one (a wave issues in order: a burst of loads would starve the matrix
-// pipe).  The contraction range is split over grid slices; partial tiles go to the
-// workspace and a reduction kernel adds them in slice order and divides.
+// pipe).  K and X loads go through buffer descriptors (scalar base, scalar row offset, fixed
+// lane offset), so no vector instruction besides the MFMAs, the loads and the LDS accesses is
+// issued in the steady state.  The contraction range is split over grid slices; partial tiles go
+// to the workspace in the order the wave's registers hold them and a reduction kernel adds
+// them in slice order and divides.
 #include "fsk_device.h"
 #include "fsk_internal.h"
+
+#include <type_traits>
 
 namespace fsk {
 
@@ -33,17 +38,30 @@ constexpr int kB64Stage = kB64Chunk * kB64Cols / 256;
 
 struct K4 { Pack<double> lo, hi; };  // four adjacent columns of one row of K
 
+constexpr int kB64WaveTileDoubles = kB64WaveTile * kB64Cols;  // one wave's partial tile
+
+// A partial tile is stored in the order the wave holds it: [MFMA block a][block b][half hf][lane]
+// [2 accumulator elements], one 128-bit store per lane, a whole KiB per instruction.  Element t
+// of that pack is accumulator element v = 2 hf + t, i.e. output row
+// 64 wt + 32 (a / 2) + 2 (4 v + lane / 16) + a % 2 and column 16 b + lane % 16 of the wave's tile
+// wt; the partial area of one (column group, slice) holds ceil(n / 64) such tiles.
+__host__ __device__ inline int64_t b64_partial_area(int n) {
+  return (int64_t)((n + kB64WaveTile - 1) / kB64WaveTile) * kB64WaveTileDoubles;
+}
+
 // X, marg and out (final) are n x mtot with row pitch mtot; the grid covers `groups` column groups
 // of up to 64 columns, `slices` contraction slices and the row tiles.  final == 0: the partial
-// product of (group g, slice s) goes, densely packed with pitch = the group's column count, to
-// out + (g * slices + s) * n * 64.
+// product of (group g, slice s) goes to out + (g * slices + s) * b64_partial_area(n) in the layout
+// described above.  XVEC: mtot is even and X is 16-byte aligned, so the X chunk is staged with
+// 128-bit accesses.
+template <bool XVEC>
 __global__ __launch_bounds__(256) void batched_prod_f64_kernel(const double* __restrict__ K, int64_t ld,
                                                                int n, int mtot,
                                                                const double* __restrict__ X,
                                                                const double* __restrict__ marg,
                                                                double* __restrict__ out, int final,
                                                                int slices, int groups) {
-  __shared__ double xs[2][kB64Chunk][kB64Cols];
+  __shared__ __attribute__((aligned(16))) double xs[2][kB64Chunk][kB64Cols];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int r = lane & 15, q = lane >> 4;
   // 1-D grid, slice fastest: the workgroups of one contraction slice share rows of X in an XCD's L2
@@ -80,9 +98,10 @@ __global__ __launch_bounds__(256) void batched_prod_f64_kernel(const double* __r
   const double* kc0 = K + j0;
   const double* kc1 = K + j1;
   // Addresses are split into a byte offset that belongs to the lane (its columns and its
-  // quarter-wave's row inside a chunk; 32 bits, formed once) and a row pointer that is the same
-  // for the whole wave and advances by one row pitch per k-step on the scalar unit, so that a
-  // load costs no vector instruction besides itself.
+  // quarter-wave's row inside a chunk; 32 bits, formed once) and a wave-uniform part: the
+  // chunk's first row (the base of a buffer descriptor, advanced once per chunk on the scalar
+  // unit) plus e row pitches for k-step e (a scalar offset).
+  const uint32_t ldb = (uint32_t)(ld * 8), ldmb = (uint32_t)(ldm * 8);
   const uint32_t kb0 = (uint32_t)(((int64_t)(kB64Steps * q) * ld + j0) * 8);
   const uint32_t kb1 = (uint32_t)(((int64_t)(kB64Steps * q) * ld + j1) * 8);
   auto k_at = [&](const double* row, uint32_t lane_bytes) {
@@ -133,6 +152,14 @@ __global__ __launch_bounds__(256) void batched_prod_f64_kernel(const double* __r
 #pragma unroll
     for (int i = 0; i < kB64Stage; ++i) xs[buf][sk + 4 * i][sc] = st[i];
   };
+  // vector form of the staging: thread = (two columns from 2 xq, rows xr + 8 i), four 128-bit packs
+  const int xr = tid >> 5, xq = tid & 31;
+  const int xc2 = 2 * xq + 1 < m ? 2 * xq : (m >= 2 ? m - 2 : 0);
+  const uint32_t xvb = (uint32_t)(((int64_t)xr * ldm + xc2) * 8);
+  auto store_xv = [&](int buf, const Pack<double>(&sv)[4]) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) store_pack(&xs[buf][xr + 8 * i][2 * xq], sv[i]);
+  };
 
   // B operands of k-step e of the chunk in xs[buf]
   auto read_b = [&](int buf, int e, double(&bv)[4]) {
@@ -155,58 +182,56 @@ __global__ __launch_bounds__(256) void batched_prod_f64_kernel(const double* __r
     for (int e = 0; e < kB64Steps; ++e) mfma_step(ka[e], bv[e]);
   };
   // One chunk of the steady state: the MFMAs of the chunk in `ka` / xs[buf], whose first two
-  // k-steps' B operands arrive in `bcur`, with everything the NEXT chunk (cn) needs spread
-  // between them: its K loads (two per k-step), its X loads (all in the first half, so that they
-  // have landed when they are staged), the staging into xs[buf ^ 1] and the workgroup barrier
-  // after k-step kB64Steps - 2, and the LDS reads of its first two k-steps (into `bnext`) before
-  // the last k-step.  The matrix pipe therefore never drains at a chunk boundary: no wait for
-  // memory, for the barrier or for LDS stands between the last MFMA of one chunk and the first
+  // k-steps' B operands arrive in `bcur`.  With NEXT, everything the following chunk needs is
+  // spread between them: its X rows (from `xrow`) are requested first -- before any K load of
+  // this chunk, so that waiting for them later does not also wait for K loads issued since (the
+  // memory counter retires loads in order) --, two K loads (rows from `krow` on) follow every
+  // k-step, the X values go to xs[buf ^ 1] and the workgroup meets at a barrier after k-step
+  // kB64Steps - 2, and the following chunk's first two k-steps' B operands are read (into `bnext`)
+  // before the last k-step.  The matrix pipe therefore never drains at a chunk boundary: no wait
+  // for memory, for the barrier or for LDS stands between the last MFMA of one chunk and the first
   // of the next.  Two LDS buffers suffice: every read of xs[buf] has completed (the barrier's
   // own wait) before any wave passes the barrier after which xs[buf] is written again.
-  auto chunk_step = [&](int buf, const K4(&ka)[kB64Steps], const double(&bcur)[2][4], int cn,
-                        K4(&kn)[kB64Steps], double(&bnext)[2][4]) {
+  auto chunk_step = [&](auto next_tag, int buf, const K4(&ka)[kB64Steps], const double(&bcur)[2][4],
+                        const double* krow, const double* xrow, K4(&kn)[kB64Steps],
+                        double(&bnext)[2][4]) {
+    constexpr bool NEXT = decltype(next_tag)::value;
     static_assert(kB64Stage == kB64Steps, "two X loads on each of the first kB64Steps / 2 k-steps");
     double bv[kB64Steps][4];
     double stn[kB64Stage];
-    const double* krow = K + (int64_t)cn * kB64Chunk * ld;
-    const double* xrow = X + (int64_t)cn * kB64Chunk * ldm;
+    Pack<double> svn[4];
 #pragma unroll
     for (int b = 0; b < 4; ++b) bv[0][b] = bcur[0][b], bv[1][b] = bcur[1][b];
+    const __amdgpu_buffer_rsrc_t rk = buffer_over(krow), rx = buffer_over(xrow);
+    if (NEXT && XVEC) {
+#pragma unroll
+      for (int i = 0; i < 4; ++i) svn[i] = buffer_load_pack<double, false>(rx, xvb, 8 * i * ldmb);
+    }
 #pragma unroll
     for (int e = 0; e < kB64Steps; ++e) {
-      if (e == kB64Steps - 1) {  // after the barrier: the next chunk's first operands
+      if (NEXT && e == kB64Steps - 1) {  // after the barrier: the next chunk's first operands
         read_b(buf ^ 1, 0, bnext[0]);
         read_b(buf ^ 1, 1, bnext[1]);
       }
       mfma_step(ka[e], bv[e]);
       if (e + 2 < kB64Steps) read_b(buf, e + 2, bv[e + 2]);
-      kn[e].lo = load_pack_stream(k_at(krow, kb0));
-      kn[e].hi = load_pack_stream(k_at(krow, kb1));
-      krow += ld;
-      if (e < kB64Steps / 2) {
-        stn[2 * e] = *k_at(xrow, xb);
-        stn[2 * e + 1] = *k_at(xrow + 4 * ldm, xb);
-        xrow += 8 * ldm;
-      }
-      if (e == kB64Steps - 2) {
-        store_x(buf ^ 1, stn);
-        __syncthreads();
+      if (NEXT) {
+        kn[e].lo = buffer_load_pack<double, true>(rk, kb0, e * ldb);
+        kn[e].hi = buffer_load_pack<double, true>(rk, kb1, e * ldb);
+        if (!XVEC && e < kB64Steps / 2) {
+          stn[2 * e] = *k_at(xrow + (int64_t)8 * e * ldm, xb);
+          stn[2 * e + 1] = *k_at(xrow + (int64_t)(8 * e + 4) * ldm, xb);
+        }
+        if (e == kB64Steps - 2) {
+          if (XVEC) store_xv(buf ^ 1, svn); else store_x(buf ^ 1, stn);
+          __syncthreads();
+        }
       }
       __builtin_amdgcn_sched_barrier(0);
     }
   };
-  // A chunk with no successor to prepare: operands of k-steps 0, 1 in `bcur`, the rest read two
-  // k-steps ahead.
-  auto chunk_last = [&](int buf, const K4(&ka)[kB64Steps], const double(&bcur)[2][4]) {
-    double bv[kB64Steps][4];
-#pragma unroll
-    for (int b = 0; b < 4; ++b) bv[0][b] = bcur[0][b], bv[1][b] = bcur[1][b];
-#pragma unroll
-    for (int e = 0; e < kB64Steps; ++e) {
-      mfma_step(ka[e], bv[e]);
-      if (e + 2 < kB64Steps) read_b(buf, e + 2, bv[e + 2]);
-    }
-  };
+  const std::true_type with_next;
+  const std::false_type last;
 
   // Empty statements that name the accumulators as accumulation registers: left alone, the
   // register allocator carries them across the loop's back edge in ordinary vector registers
@@ -230,17 +255,22 @@ __global__ __launch_bounds__(256) void batched_prod_f64_kernel(const double* __r
     read_b(0, 0, bA[0]);
     read_b(0, 1, bA[1]);
     pin_acc();
+    const int64_t kstep = (int64_t)kB64Chunk * ld, xstep = (int64_t)kB64Chunk * ldm;
+    const double* kp = K + (int64_t)(c0 + 1) * kstep;  // first rows of the chunk prepared next
+    const double* xp = X + (int64_t)(c0 + 1) * xstep;
     for (; c + 2 < full_end; c += 2) {  // chunks c and c + 1 both have a successor to prepare
       pin_acc();
-      chunk_step(0, kaA, bA, c + 1, kaB, bB);
-      chunk_step(1, kaB, bB, c + 2, kaA, bA);
+      chunk_step(with_next, 0, kaA, bA, kp, xp, kaB, bB);
+      chunk_step(with_next, 1, kaB, bB, kp + kstep, xp + xstep, kaA, bA);
+      kp += 2 * kstep;
+      xp += 2 * xstep;
       pin_acc();
     }
     if (c + 1 < full_end) {  // two whole chunks left
-      chunk_step(0, kaA, bA, c + 1, kaB, bB);
-      chunk_last(1, kaB, bB);
+      chunk_step(with_next, 0, kaA, bA, kp, xp, kaB, bB);
+      chunk_step(last, 1, kaB, bB, kp, xp, kaA, bA);
     } else {                 // one
-      chunk_last(0, kaA, bA);
+      chunk_step(last, 0, kaA, bA, kp, xp, kaB, bB);
     }
     __syncthreads();
   }
@@ -253,28 +283,40 @@ __global__ __launch_bounds__(256) void batched_prod_f64_kernel(const double* __r
     multiply(0, kaA);
   }
 
-  double* dst = final ? out + col0 : out + ((int64_t)grp * slices + slice) * n * kB64Cols;
+  if (final) {
+    double* dst = out + col0;
 #pragma unroll
-  for (int a = 0; a < 4; ++a)
+    for (int a = 0; a < 4; ++a)
 #pragma unroll
-    for (int v = 0; v < 4; ++v) {
-      const int i = 4 * v + q;  // MFMA row of accumulator element v
-      const int row = o0 + 32 * (a >> 1) + 2 * i + (a & 1);
-      if (row < n) {
+      for (int v = 0; v < 4; ++v) {
+        const int i = 4 * v + q;  // MFMA row of accumulator element v
+        const int row = o0 + 32 * (a >> 1) + 2 * i + (a & 1);
+        if (row < n) {
 #pragma unroll
-        for (int b = 0; b < 4; ++b) {
-          const int col = 16 * b + r;
-          if (col < m) {
-            if (final) {
+          for (int b = 0; b < 4; ++b) {
+            const int col = 16 * b + r;
+            if (col < m) {
               const int64_t idx = (int64_t)row * ldm + col;
               dst[idx] = marg[idx] / acc[a][b][v];
-            } else {
-              dst[(int64_t)row * m + col] = acc[a][b][v];
             }
           }
         }
       }
-    }
+  } else if (o0 < n) {
+    double* dst = out + ((int64_t)grp * slices + slice) * b64_partial_area(n) +
+                  (int64_t)(o0 / kB64WaveTile) * kB64WaveTileDoubles + 2 * lane;
+#pragma unroll
+    for (int a = 0; a < 4; ++a)
+#pragma unroll
+      for (int b = 0; b < 4; ++b)
+#pragma unroll
+        for (int hf = 0; hf < 2; ++hf) {
+          Pack<double> p;
+          p.e[0] = acc[a][b][2 * hf];
+          p.e[1] = acc[a][b][2 * hf + 1];
+          store_pack(dst + ((a * 4 + b) * 2 + hf) * 128, p);
+        }
+  }
 }
 
 __global__ __launch_bounds__(256) void transpose_f64_kernel(const double* __restrict__ K, int64_t ld,
@@ -292,22 +334,45 @@ __global__ __launch_bounds__(256) void transpose_f64_kernel(const double* __rest
 }
 
 // out[row][col] = marg[row][col] / sum_s partial[g][s][row][col] for every column group g
-// (blockIdx.y), the slices added in slice order; partial tiles of a group are dense with pitch =
-// the group's column count and sit n * 64 apart; marg and out are n x mtot.
+// (blockIdx.y), the slices added in slice order.  A thread fetches one 128-bit pack of the product
+// kernel's partial layout (two rows, 8 apart, of one column); two adjacent lanes then exchange
+// one value each, so that each ends with two adjacent columns of one row and (vec: mtot even,
+// marg and out 16-byte aligned) reads marg and writes out 128 bits at a time.  marg and out
+// are n x mtot.
 __global__ __launch_bounds__(256) void batched_reduce_f64_kernel(const double* __restrict__ partial,
                                                                  int slices, int n, int mtot,
                                                                  const double* __restrict__ marg,
-                                                                 double* __restrict__ out) {
+                                                                 double* __restrict__ out, int vec) {
   const int grp = blockIdx.y, col0 = grp * kB64Cols;
   const int cols = mtot - col0 < kB64Cols ? mtot - col0 : kB64Cols;
-  const int64_t total = (int64_t)n * cols, stride = (int64_t)n * kB64Cols;
-  const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
-  if (idx >= total) return;
-  const double* p = partial + (int64_t)grp * slices * stride + idx;
-  double s = p[0];
-  for (int k = 1; k < slices; ++k) s += p[(int64_t)k * stride];
-  const int64_t o = (idx / cols) * mtot + col0 + idx % cols;
-  out[o] = marg[o] / s;
+  const int64_t area = b64_partial_area(n);  // a multiple of 4096: a workgroup is all in or all out
+  const int64_t f = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (2 * f >= area) return;
+  const int r = (int)(f & 15), b = (int)(f >> 4) & 3, q = (int)(f >> 6) & 3, hf = (int)(f >> 8) & 1;
+  const int a = (int)(f >> 9) & 3, wt = (int)(f >> 11);
+  const double* p = partial + (int64_t)grp * slices * area + (int64_t)wt * kB64WaveTileDoubles +
+                    2 * ((((a * 4 + b) * 2 + hf) * 4 + q) * 16 + r);
+  Pack<double> s = load_pack(p);
+  for (int k = 1; k < slices; ++k) {
+    const Pack<double> y = load_pack(p + (int64_t)k * area);
+    s.e[0] += y.e[0];
+    s.e[1] += y.e[1];
+  }
+  lanes_transpose2(s.e, r);  // now: accumulator element v = 2 hf + r % 2, columns 2 (r / 2), + 1 of block b
+  const int row = wt * kB64WaveTile + 32 * (a >> 1) + 2 * (4 * (2 * hf + (r & 1)) + q) + (a & 1);
+  const int col = 16 * b + (r & ~1);
+  if (row >= n || col >= cols) return;
+  const int64_t o = (int64_t)row * mtot + col0 + col;
+  if (vec) {  // cols is then even
+    const Pack<double> mg = load_pack(marg + o);
+    s.e[0] = mg.e[0] / s.e[0];
+    s.e[1] = mg.e[1] / s.e[1];
+    store_pack(out + o, s);
+  } else {
+#pragma unroll
+    for (int e = 0; e < 2; ++e)
+      if (col + e < cols) out[o + e] = marg[o + e] / s.e[e];
+  }
 }
 
 static int b64_groups(int m) { return (m + kB64Cols - 1) / kB64Cols; }
@@ -333,7 +398,7 @@ static int b64_splits(int n, int groups) {
 }
 static size_t b64_partial_bytes(int n, int m) {
   const int groups = b64_groups(m);
-  return align_up((size_t)b64_splits(n, groups) * groups * (size_t)n * kB64Cols * 8, 256);
+  return align_up((size_t)b64_splits(n, groups) * groups * (size_t)b64_partial_area(n) * 8, 256);
 }
 static int64_t b64_ldt(int n) { return (int64_t)align_up((size_t)n, 32); }
 
@@ -364,13 +429,19 @@ int run_sinkhorn_batched_f64(const fsk_opts* o, const void* K, int64_t ldK, cons
   dim3 grid(((n + kB64Tile - 1) / kB64Tile) * S * groups), block(256);
   auto product = [&](const double* Km, int64_t ldm_k, const double* X, const double* marg,
                      double* dst) -> int {
-    hipLaunchKernelGGL(batched_prod_f64_kernel, grid, block, 0, st, Km, ldm_k, n, m, X, marg,
-                       S == 1 ? dst : part, S == 1 ? 1 : 0, S, groups);
+    const bool xvec = m % 2 == 0 && (uintptr_t)X % 16 == 0;  // 128-bit staging of the n x m operand
+    if (xvec)
+      hipLaunchKernelGGL(batched_prod_f64_kernel<true>, grid, block, 0, st, Km, ldm_k, n, m, X, marg,
+                         S == 1 ? dst : part, S == 1 ? 1 : 0, S, groups);
+    else
+      hipLaunchKernelGGL(batched_prod_f64_kernel<false>, grid, block, 0, st, Km, ldm_k, n, m, X, marg,
+                         S == 1 ? dst : part, S == 1 ? 1 : 0, S, groups);
     FSK_LAUNCH_CHECK("batched_prod_f64_kernel");
     if (S > 1) {
-      const int64_t per_group = (int64_t)n * kB64Cols;
-      hipLaunchKernelGGL(batched_reduce_f64_kernel, dim3((unsigned)((per_group + 255) / 256), groups),
-                         dim3(256), 0, st, (const double*)part, S, n, m, marg, dst);
+      const int64_t packs = b64_partial_area(n) / 2;
+      const int vec = m % 2 == 0 && (uintptr_t)marg % 16 == 0 && (uintptr_t)dst % 16 == 0;
+      hipLaunchKernelGGL(batched_reduce_f64_kernel, dim3((unsigned)((packs + 255) / 256), groups),
+                         dim3(256), 0, st, (const double*)part, S, n, m, marg, dst, vec);
       FSK_LAUNCH_CHECK("batched_reduce_f64_kernel");
     }
     return FSK_OK;

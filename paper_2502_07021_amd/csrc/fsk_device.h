@@ -50,6 +50,34 @@ __device__ __forceinline__ Pack<T> load_pack_stream(const T* p) {
   return r;
 }
 
+// Buffer descriptor (raw, untyped, 32-bit elements) over the memory from `base` on; `base` must
+// be the same for every lane of the wave.  A load through it takes a 32-bit lane offset and a
+// 32-bit wave-uniform offset, both in bytes: a loop that walks rows of a matrix then forms each
+// address on the scalar unit (with 64-bit flat addresses every load costs 64-bit vector
+// additions, which the matrix-core kernels cannot hide between two MFMAs).  The range field is
+// set wide, so the hardware range check never fires: the caller keeps every offset inside the
+// operand, exactly as it would with a pointer.
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t buffer_over(const void* base) {
+  const uint64_t bits = (uint64_t)base;
+  const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)bits);
+  const uint32_t hi = __builtin_amdgcn_readfirstlane((uint32_t)(bits >> 32));
+  return __builtin_amdgcn_make_buffer_rsrc((void*)(((uint64_t)hi << 32) | lo), 0, 0x7ffffff0, 0x00020000);
+}
+
+template <typename T, bool STREAM>  // STREAM: with the non-temporal hint
+__device__ __forceinline__ Pack<T> buffer_load_pack(__amdgpu_buffer_rsrc_t rs, uint32_t lane_bytes,
+                                                    uint32_t wave_bytes) {
+  using V = typename NativeVec<T>::type;
+  // (the whole vector is re-typed at once: re-typing its elements one by one through
+  // __builtin_bit_cast made the compiler fetch a single element)
+  const V t = __builtin_bit_cast(V, __builtin_amdgcn_raw_buffer_load_b128(rs, lane_bytes, wave_bytes,
+                                                                          STREAM ? 2 : 0));
+  Pack<T> r;
+#pragma unroll
+  for (int e = 0; e < Pack<T>::W; ++e) r.e[e] = t[e];
+  return r;
+}
+
 template <typename T>
 __device__ __forceinline__ void store_pack_stream(T* p, const Pack<T>& v) {
   using V = typename NativeVec<T>::type;
@@ -91,16 +119,41 @@ __device__ __forceinline__ T pair_sum_swap(T a, T b) {
   return x.value() + y.value();
 }
 
-// The value of lane l ^ MASK for MASK in {8, 7, 3, 1} (DPP inside a row of 16 lanes).
+// The value of lane l ^ MASK for MASK in {8, 7, 3, 2, 1} (DPP inside a row of 16 lanes).
 template <int MASK, typename T>
 __device__ __forceinline__ T lane_xor_dpp(T v) {
-  constexpr int ctrl = MASK == 8 ? 0x128 : MASK == 7 ? 0x141 : MASK == 3 ? 0x1B : 0xB1;
-  static_assert(MASK == 8 || MASK == 7 || MASK == 3 || MASK == 1, "no DPP control for this mask");
+  constexpr int ctrl = MASK == 8 ? 0x128 : MASK == 7 ? 0x141 : MASK == 3 ? 0x1B : MASK == 2 ? 0x4E : 0xB1;
+  static_assert(MASK == 8 || MASK == 7 || MASK == 3 || MASK == 2 || MASK == 1,
+                "no DPP control for this mask");
   LaneWords<T> x(v);
 #pragma unroll
   for (int i = 0; i < LaneWords<T>::N; ++i)
     x.w[i] = (unsigned)__builtin_amdgcn_update_dpp(0, (int)x.w[i], ctrl, 0xf, 0xf, false);
   return x.value();
+}
+
+// Transpose of the W x W block that W adjacent lanes (lane % W = c) hold as s[j] = M[c][j]:
+// afterwards lane c holds s[i] = M[i][c].  W = 4 (two exchange stages) or 2 (one).  Every lane of
+// the group must be active.
+template <typename T>
+__device__ __forceinline__ void lanes_transpose4(T (&s)[4], int lane) {
+  const bool b0 = lane & 1, b1 = lane & 2;
+#pragma unroll
+  for (int j = 0; j < 4; j += 2) {
+    const T got = lane_xor_dpp<1>(b0 ? s[j] : s[j + 1]);
+    if (b0) s[j] = got; else s[j + 1] = got;
+  }
+#pragma unroll
+  for (int j = 0; j < 2; ++j) {
+    const T got = lane_xor_dpp<2>(b1 ? s[j] : s[j + 2]);
+    if (b1) s[j] = got; else s[j + 2] = got;
+  }
+}
+template <typename T>
+__device__ __forceinline__ void lanes_transpose2(T (&s)[2], int lane) {
+  const bool b0 = lane & 1;
+  const T got = lane_xor_dpp<1>(b0 ? s[0] : s[1]);
+  if (b0) s[0] = got; else s[1] = got;
 }
 
 // All-lanes sum of a wave: the pairings ^32, ^16, ^8, ^7, ^3, ^1 span the 64 lanes; every
