@@ -332,7 +332,7 @@ def bench_batched(args):
 def secondary(args):
     """Short fixed runs of the other four configurations, for the default line's `secondary`."""
     import torch
-    plan = (("cfg1", 1, 200, 20, 50), ("cfg2", 2, 500, 20, 128), ("cfg4", 4, 20, 2, 10), ("cfg5", 5, 300, 20, 50))
+    plan = (("cfg1", 1, 200, 20, 50), ("cfg2", 2, 500, 20, 128), ("cfg4", 4, 20, 2, 10), ("cfg5", 5, 300, 100, 50))
     keep = ("bound", "achieved", "peak", "unit", "frac", "kernel", "kernel_ms", "launches_per_step",
             "traffic", "traffic_source", "note")
     res = {}

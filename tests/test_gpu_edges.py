@@ -139,3 +139,27 @@ def test_more_than_2_to_31_matrix_entries(orc):
         api.fsk_sinkhorn_dense(o, Kd, a, b, u, v, api.alloc_workspace(o))
         torch.cuda.synchronize()
         assert relerr(u.cpu().numpy(), uo) <= 1e-4 and relerr(v.cpu().numpy(), vo) <= 1e-4
+
+
+def test_batched_call_refuses_a_row_pitch_beyond_its_32_bit_offsets():
+    """The multitarget kernels address K by 32-bit offsets from a per-chunk base: a pitch above
+    2^23 elements is refused before anything is launched (the widest accepted pitch runs)."""
+    n, m = 8, 4
+    A = torch.full((n, m), 1.0 / n, device="cuda"); B = A.clone()
+    for ld, ok in (((1 << 23), True), ((1 << 23) + 4, False)):
+        store = torch.ones(n * ld, device="cuda")
+        K = store.as_strided((n, n), (ld, 1))
+        U = torch.ones(n, m, device="cuda"); V = torch.ones(n, m, device="cuda")
+        opts = api.make_opts(n, torch.float32, m=m, max_iters=2)
+        ws = api.alloc_workspace(opts, api.FSK_MODE_BATCHED)
+        if ok:
+            api.fsk_sinkhorn_batched(opts, K, A, B, U, V, ws)
+            torch.cuda.synchronize()
+            # K = 1, a = b = 1/n: u = 1/(n n), then v = (1/n) / (n u) = 1
+            assert torch.allclose(U, torch.full_like(U, 1.0 / (n * n)), rtol=1e-6)
+            assert torch.allclose(V, torch.ones_like(V), rtol=1e-6)
+        else:
+            with pytest.raises(api.FskError) as e:
+                api.fsk_sinkhorn_batched(opts, K, A, B, U, V, ws)
+            assert e.value.status == api.FSK_EUNSUPPORTED
+        del store, K
