@@ -5,8 +5,10 @@
 Plants one small mistake at a time in a copy of oracle/sinkhorn_oracle.c (a flipped sign, a
 swapped index, a transposed subscript, a changed constant or comparison, exp for exp2, ...),
 builds the copy into a library of its own and runs tests/test_oracle_pins.py against it.  A
-mutant that passes every pin is printed: either it changes nothing a caller can see (a loop
-bound one past the end, a dead initial value, the thread-count setter) or a pin is missing.
+mutant that passes every pin is built once more with gcc's address and undefined-behaviour
+sanitizers and runs the pins again (a loop bound one past the end passes on the allocator's slack
+and dies there).  What passes both is printed: either it changes nothing a caller can see (a
+comparison at a tolerance, a dead initial value, the thread-count setter) or a pin is missing.
 The oracle in the tree is never touched.  `--write` stores the survivors of a FULL run in
 tests/golden/oracle_mutation_survivors.txt (the mutated source lines, which are what the
 collected test tests/test_oracle_mutation_sample.py allows a sampled mutant to survive as)."""
@@ -20,6 +22,20 @@ import tempfile
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 SRC = os.path.join(ROOT, "oracle", "sinkhorn_oracle.c")
 GCC = ["gcc", "-O2", "-std=c99", "-fopenmp", "-fno-fast-math", "-ffp-contract=off", "-shared", "-fPIC"]
+GCC_SAN = ["gcc", "-O1", "-g", "-std=c99", "-fopenmp", "-fno-fast-math", "-ffp-contract=off",
+           "-fsanitize=address,undefined", "-fno-sanitize-recover=all", "-fno-omit-frame-pointer",
+           "-shared", "-fPIC"]
+
+
+def sanitizer_env(threads_each):
+    """Environment of a child that loads a sanitized library into the uninstrumented interpreter."""
+    asan = subprocess.run(["gcc", "-print-file-name=libasan.so"], check=True, capture_output=True,
+                          text=True).stdout.strip()
+    env = dict(os.environ, OMP_NUM_THREADS=str(threads_each))
+    env["LD_PRELOAD"] = asan + (":" + env["LD_PRELOAD"] if env.get("LD_PRELOAD") else "")
+    env["ASAN_OPTIONS"] = "detect_leaks=0:abort_on_error=1"
+    env["UBSAN_OPTIONS"] = "halt_on_error=1"
+    return env
 
 RUNNER = """
 import sys
@@ -66,7 +82,8 @@ def mutants(lines):
 
 def run_mutants(todo, workers=4, threads_each=2, progress=None):
     """Builds and tests every (line number, mutated line) of `todo`; returns (line, text, verdict)
-    triples with verdict in {"killed", "survived", "does not compile"}."""
+    triples with verdict in {"killed", "killed under the sanitizers", "survived",
+    "does not compile"}."""
     lines = open(SRC).read().split("\n")
     work = tempfile.mkdtemp(prefix="oracle_mut_")
     runner = os.path.join(work, "run_pins.py")
@@ -90,6 +107,16 @@ def run_mutants(todo, workers=4, threads_each=2, progress=None):
             except subprocess.TimeoutExpired:
                 verdict = "killed"
             os.remove(lib)
+            if verdict == "survived" and \
+                    subprocess.run(GCC_SAN + [src, "-o", lib, "-lm"], capture_output=True).returncode == 0:
+                try:
+                    rc = subprocess.run([sys.executable, runner, lib], capture_output=True, timeout=1800,
+                                        env=sanitizer_env(threads_each)).returncode
+                except subprocess.TimeoutExpired:
+                    rc = 1
+                if rc != 0:
+                    verdict = "killed under the sanitizers"
+                os.remove(lib)
         os.remove(src)
         return ln, new, verdict
 
@@ -125,15 +152,17 @@ def main():
 
     res = run_mutants(todo, progress=progress)
     alive = [new.strip() for _, new, verdict in res if verdict == "survived"]
-    print("survivors:", len(alive), "of", len(todo))
+    print("survivors:", len(alive), "of", len(todo), "(killed only under the sanitizers:",
+          sum(verdict == "killed under the sanitizers" for _, _, verdict in res), ")")
     if "--write" in sys.argv:
         if args:
             raise SystemExit("--write needs the full run")
         with open(SURVIVORS, "w") as fh:
             fh.write("# Mutated lines of oracle/sinkhorn_oracle.c that pass every pin in a full run of\n"
-                     "# tests/oracle_mutation_check.py (" + str(len(todo)) + " mutants).  Each changes nothing a caller can see:\n"
-                     "# a loop bound or a comparison at a tolerance turned into <=, an over-sized allocation made\n"
-                     "# smaller but still sufficient, the thread-count setter, a dead initial value.\n")
+                     "# tests/oracle_mutation_check.py (" + str(len(todo)) + " mutants), also when built with the address and\n"
+                     "# undefined-behaviour sanitizers.  Each changes nothing a caller can see: a comparison at a\n"
+                     "# tolerance turned into <=, a loop bound whose extra trip stays inside its buffer, the\n"
+                     "# thread-count setter, a dead initial value.\n")
             for line in sorted(set(alive)):
                 fh.write(line + "\n")
 
