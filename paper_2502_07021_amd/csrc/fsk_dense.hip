@@ -18,8 +18,8 @@
 namespace fsk {
 
 // ============================================================== row pass (generic)
-// One workgroup of 256 threads takes ROWS consecutive rows; thread t walks the
-// 16-byte packs t, t+256, ... of each row, so a wave reads 1 KiB contiguous per
+// One workgroup of 256 threads takes ROWS consecutive rows (2 or 4: see the launcher); thread t
+// walks the 16-byte packs t, t+256, ... of each row, so a wave reads 1 KiB contiguous per
 // load and v is fetched once for all ROWS rows.
 // blockIdx.y = slab: the launch covers gridDim.y row slabs of `rows` rows each, slab y being
 // rows [y*rows, (y+1)*rows) of K, marg, old, out and err_out -- the row blocks of the c clients
@@ -115,16 +115,23 @@ static int rowpass_typed(const void* K, int64_t ld, int n, int rows, int slabs, 
                          double eta, void* err_out, hipStream_t stream, int col_blocks = 1,
                          int64_t out_block_stride = 0) {
   if (rows <= 0 || slabs <= 0 || col_blocks <= 0) return FSK_OK;
-  constexpr int ROWS = 4;
-  dim3 grid((rows + ROWS - 1) / ROWS, slabs, col_blocks), block(256);
-  if (vown)
-    hipLaunchKernelGGL((rowpass_kernel<T, ROWS, true>), grid, block, 0, stream, (const T*)K, ld, n,
+  // Rows per workgroup (the sums are per row, so the choice changes no bit): two for the plain
+  // pass (n = 16384: 348 us per iteration of the two-pass flow against 356 with four, fp64 629
+  // against 645; n = 32768: 1235 against 1249), four where every entry of v is picked from one
+  // of two vectors first (with two that variant loses 4 % at n = 32768).
+  constexpr int kRowsPlain = 2, kRowsView = 4;
+  dim3 block(256);
+  if (vown) {
+    dim3 grid((rows + kRowsView - 1) / kRowsView, slabs, col_blocks);
+    hipLaunchKernelGGL((rowpass_kernel<T, kRowsView, true>), grid, block, 0, stream, (const T*)K, ld, n,
                        rows, (const T*)vin, (const T*)vown, (const T*)marg, (const T*)old, (T*)out,
                        epi, (T)eta, (T*)err_out, out_block_stride);
-  else
-    hipLaunchKernelGGL((rowpass_kernel<T, ROWS, false>), grid, block, 0, stream, (const T*)K, ld, n,
+  } else {
+    dim3 grid((rows + kRowsPlain - 1) / kRowsPlain, slabs, col_blocks);
+    hipLaunchKernelGGL((rowpass_kernel<T, kRowsPlain, false>), grid, block, 0, stream, (const T*)K, ld, n,
                        rows, (const T*)vin, (const T*)nullptr, (const T*)marg, (const T*)old,
                        (T*)out, epi, (T)eta, (T*)err_out, out_block_stride);
+  }
   FSK_LAUNCH_CHECK("rowpass_kernel");
   return FSK_OK;
 }
