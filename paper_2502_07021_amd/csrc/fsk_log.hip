@@ -202,7 +202,7 @@ __device__ __forceinline__ void lse_fold(const double (&zd)[JJ], double& mref, S
   for (int t = 0; t < JJ; ++t) sum += exp2_of(zf[t]);
 }
 
-// part_m[i*slices + sl], part_s[...]: reference exponent and sum of
+// part_m[sl*n_rows + i], part_s[...]: reference exponent and sum of
 // 2^(z_ij - reference) over the columns j of slice sl, z_ij = beta_j + ps_i . qc_j.
 // S: type of the exponentials and of the running sum (float for the fp32 interface: one
 // v_exp_f32 per pair; double for the fp64 interface).
@@ -315,8 +315,8 @@ __global__ __launch_bounds__(kLogThreads) void log_lse_kernel(const double* __re
 #pragma unroll
   for (int r = 0; r < RI; ++r) {
     if (row[r] < n_rows) {
-      part_m[(int64_t)row[r] * slices + sl] = mref[r];
-      part_s[(int64_t)row[r] * slices + sl] = sum[r];
+      part_m[(int64_t)sl * n_rows + row[r]] = mref[r];
+      part_s[(int64_t)sl * n_rows + row[r]] = sum[r];
     }
   }
 }
@@ -401,14 +401,14 @@ __global__ __launch_bounds__(kLogThreads) void log_lse_generic_kernel(const doub
 #pragma unroll
   for (int r = 0; r < RI; ++r) {
     if (row[r] < n_rows) {
-      part_m[(int64_t)row[r] * slices + sl] = mref[r];
-      part_s[(int64_t)row[r] * slices + sl] = sum[r];
+      part_m[(int64_t)sl * n_rows + row[r]] = mref[r];
+      part_s[(int64_t)sl * n_rows + row[r]] = sum[r];
     }
   }
 }
 
 // ------------------------------------------------------------------ merge + update
-// L2_i = log2 sum_j 2^(z_ij) from the slices (merged in slice order), then
+// L2_i = log2 sum_j 2^(z_ij) from the slices (merged in a fixed order), then
 //   pot_new = eps (ln w_i - ln2 (L2_i - s|p~_i|^2)).
 // mode 0: store pot_new (fp64 shadow, caller's array, beta for the column role).
 // mode 1: store |w_i exp((pot_i - pot_new)/eps) - w_i| -- the row-marginal error of the
@@ -425,16 +425,29 @@ __global__ __launch_bounds__(256) void log_finalize_kernel(const double* __restr
                                                            T* __restrict__ pot_out,
                                                            double* __restrict__ beta_out,
                                                            double* __restrict__ errvec) {
-  const int i = blockIdx.x * 256 + threadIdx.x;
-  if (i >= n) return;
-  double M = part_m[(int64_t)i * slices];
-  for (int k = 1; k < slices; ++k) {
-    const double m = part_m[(int64_t)i * slices + k];
+  // Four adjacent lanes share a row: lane g merges slices g, g + 4, ... (a thread alone would
+  // walk all slices with nothing to hide the latency of its loads and fp64 exponentials: one wave
+  // per SIMD), then the four agree on the largest reference and add their sums pairwise, in the
+  // same order in every launch.
+  const int t = blockIdx.x * 256 + threadIdx.x;
+  const int g = t & 3;
+  const bool live = (t >> 2) < n;
+  const int i = live ? t >> 2 : n - 1;  // lanes past the end stay in the exchanges, store nothing
+  double M = -__builtin_huge_val();
+  for (int k = g; k < slices; k += 4) {
+    const double m = part_m[(int64_t)k * n + i];
     M = m > M ? m : M;
   }
+  double other = lane_xor_dpp<1>(M);
+  M = other > M ? other : M;
+  other = lane_xor_dpp<2>(M);
+  M = other > M ? other : M;
   double S = 0.0;
-  for (int k = 0; k < slices; ++k)
-    S += (double)part_s[(int64_t)i * slices + k] * exp2(part_m[(int64_t)i * slices + k] - M);
+  for (int k = g; k < slices; k += 4)
+    S += (double)part_s[(int64_t)k * n + i] * exp2(part_m[(int64_t)k * n + i] - M);
+  S += lane_xor_dpp<1>(S);
+  S += lane_xor_dpp<2>(S);
+  if (!live || g != 0) return;
   const double L2 = M + log2(S);
   const double ln2 = 0.693147180559945309417;
   const double pot_new = eps * (lnw[i] - ln2 * (L2 - norm2[i]));
@@ -478,17 +491,17 @@ static int log_pad_dim(int d) {
 static LogWs log_ws(int n, int d) {
   LogWs w{};
   w.dp = log_pad_dim(d);
-  // enough column slices for ~8 workgroups (32 waves) per compute unit, at most 64, at least
-  // 256 columns each
-  int cus = device_cu_count();
-  if (cus < 1) cus = 256;
-  const int row_tiles = (n + kLogRowTile - 1) / kLogRowTile;
-  int slices = (8 * cus + row_tiles - 1) / row_tiles;
+  // Column slices per row tile: 40, at least 256 columns each.  Measured on MI355X (ms per
+  // half-step, d = 16): n = 65536: 2.87 / 2.85 / 2.78 / 2.72 / 2.73 / 2.75 / 2.84 with 16 / 20 / 30 /
+  // 40 / 50 / 64 / 128 slices (3.14 with 10, which is one full round of resident workgroups);
+  // n = 131072: 11.8 / 10.9 / 10.7 / 10.7 with 8 / 20 / 30 / 40; n = 32768: 0.766 / 0.756 / 0.768 with
+  // 32 / 40 / 80; d = 8, 32 and 3 agree (40-48 best).  Many short workgroups that start at
+  // different times keep the vector unit fed through each other's ramps and tails; beyond ~50
+  // the per-slice ramp and the merge of the slices cost more than that gains.
+  constexpr int kLogSlices = 40;
   const int max_by_cols = n / 256 > 0 ? n / 256 : 1;
-  if (slices > max_by_cols) slices = max_by_cols;
-  if (slices > 64) slices = 64;
-  if (slices < 1) slices = 1;
-  w.cols_per_slice = (n + slices - 1) / slices;
+  const int slices = kLogSlices < max_by_cols ? kLogSlices : max_by_cols;
+  w.cols_per_slice = ((n + slices - 1) / slices + kLogChunk - 1) / kLogChunk * kLogChunk;
   w.slices = (n + w.cols_per_slice - 1) / w.cols_per_slice;
   size_t off = 0;
   auto take = [&](size_t bytes) { size_t o = off; off += align_up(bytes, 256); return o; };
@@ -583,7 +596,7 @@ static int run_log_typed(const fsk_opts* o, const void* x, const void* y, int d,
     // f-update: rows = x (scaled), columns = y with beta_y; g-update: the roles swapped
     FSK_TRY(lse_dispatch<T>(w, n, D(f_side ? w.xs : w.ys), D(f_side ? w.yc : w.xc),
                             D(f_side ? w.by : w.bx), D(w.pm), psum, st));
-    hipLaunchKernelGGL((log_finalize_kernel<T, T>), dim3(nb), dim3(256), 0, st, D(w.pm), psum,
+    hipLaunchKernelGGL((log_finalize_kernel<T, T>), dim3((n + 63) / 64), dim3(256), 0, st, D(w.pm), psum,
                        w.slices, n, D(f_side ? w.nx2 : w.ny2), D(f_side ? w.lna : w.lnb), eps, s,
                        mode, eta, geometric, D(f_side ? w.fd : w.gd), f_side ? ff : gf,
                        D(f_side ? w.bx : w.by),
