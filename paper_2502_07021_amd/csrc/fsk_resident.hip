@@ -20,6 +20,8 @@
 // workgroup writes NaN results and leaves: the grid always drains.
 // The partial area is double buffered by iteration parity: a workgroup can be at most one
 // barrier ahead of the slowest one.
+#include <type_traits>
+
 #include "fsk_device.h"
 #include "fsk_internal.h"
 
@@ -205,14 +207,23 @@ __global__ __launch_bounds__(kResThreads) void resident_kernel(
       Pack<T> r;
 #pragma unroll
       for (int e = 0; e < W; ++e) r.e[e] = T(0);
-      for (int g0 = 0; g0 < G; g0 += 8) {  // G is 8, 16 or 32: eight loads in flight at a time
-        Pack<T> y[8];
+      // G is 8, 16 or 32.  Every load is a round trip beyond the XCD's L2 (~1 us), so as many
+      // as the registers hold are in flight at once: all 8, or 16 at a time.  Added in workgroup
+      // order either way.
+      auto gather = [&](auto batch_tag, int g0) {
+        constexpr int B = decltype(batch_tag)::value;
+        Pack<T> y[B];
 #pragma unroll
-        for (int g = 0; g < 8; ++g) y[g] = load_agent(base + (int64_t)(g0 + g) * ld_ws);
+        for (int g = 0; g < B; ++g) y[g] = load_agent(base + (int64_t)(g0 + g) * ld_ws);
 #pragma unroll
-        for (int g = 0; g < 8; ++g)
+        for (int g = 0; g < B; ++g)
 #pragma unroll
           for (int e = 0; e < W; ++e) r.e[e] += y[g].e[e];
+      };
+      if (G == 8) {
+        gather(std::integral_constant<int, 8>{}, 0);
+      } else {
+        for (int g0 = 0; g0 < G; g0 += 16) gather(std::integral_constant<int, 16>{}, g0);
       }
 #pragma unroll
       for (int e = 0; e < W; ++e) {
