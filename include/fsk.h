@@ -357,7 +357,7 @@ int fsk_sinkhorn_log_points(const fsk_opts* opts, const void* x, const void* y, 
  * opts->max_iters iterations (FSK_EUNSUPPORTED for opts->tol > 0: see the _tol call below).
  * FSK_F32 (fp32 MFMA) or FSK_F64 (fp64 MFMA; needs the whole workspace, FSK_EWORKSPACE
  * otherwise).  Any m >= 1: the columns go through the kernels in groups of up to 64, one pass
- * over K per group and product, so the time grows with ceil(m / 64).  ldK <= 2^23 elements and
+ * over K per group and product, so the time grows with ceil(m / 64).  ldK <= 2^22 elements and
  * m <= 2^20 (FSK_EUNSUPPORTED beyond: the kernels form 32-bit offsets).  Which kernel forms K V
  * (hence the order of its sums) depends on (n, m) and on whether the workspace has room for the
  * transposed copy, never on the iteration count: a run split into several calls with the same

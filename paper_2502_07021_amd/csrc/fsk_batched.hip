@@ -618,10 +618,11 @@ int run_sinkhorn_batched(const fsk_opts* o, const void* K, int64_t ldK, const vo
                          void* U, void* V, void* workspace, size_t ws_bytes, const fsk_dp* dp,
                          hipStream_t st, const BatchedPoll* poll, void* tmp) {
   const int n = o->n, m = o->m;
-  // the product kernels address K through 32-bit offsets from a per-chunk base (a lane's part
-  // spans 16 rows + one row of the chunk), and the n x m operand likewise
-  if (ldK > (int64_t)1 << 23 || m > 1 << 20)
-    return set_error(FSK_EUNSUPPORTED, "batched call takes a row pitch of K up to 2^23 elements and up to 2^20 "
+  // the product kernels address K through 32-bit offsets from a per-chunk base (lane part + scalar
+  // part span at most 32 rows of the chunk: 128 ldK bytes in fp32, 256 ldK in fp64, kept below 2^31
+  // so that they also pass the descriptor's range field), and the n x m operand likewise
+  if (ldK > (int64_t)1 << 22 || m > 1 << 20)
+    return set_error(FSK_EUNSUPPORTED, "batched call takes a row pitch of K up to 2^22 elements and up to 2^20 "
                      "targets (got %lld, %d)", (long long)ldK, m);
   if (o->dtype == FSK_F64)
     return run_sinkhorn_batched_f64(o, K, ldK, A, B, U, V, workspace, ws_bytes, dp, st, poll, tmp);

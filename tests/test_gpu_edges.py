@@ -141,16 +141,18 @@ def test_more_than_2_to_31_matrix_entries(orc):
         assert relerr(u.cpu().numpy(), uo) <= 1e-4 and relerr(v.cpu().numpy(), vo) <= 1e-4
 
 
-def test_batched_call_refuses_a_row_pitch_beyond_its_32_bit_offsets():
+@pytest.mark.parametrize("td", [torch.float32, torch.float64])
+def test_batched_call_refuses_a_row_pitch_beyond_its_32_bit_offsets(td):
     """The multitarget kernels address K by 32-bit offsets from a per-chunk base: a pitch above
-    2^23 elements is refused before anything is launched (the widest accepted pitch runs)."""
-    n, m = 8, 4
-    A = torch.full((n, m), 1.0 / n, device="cuda"); B = A.clone()
-    for ld, ok in (((1 << 23), True), ((1 << 23) + 4, False)):
-        store = torch.ones(n * ld, device="cuda")
+    2^22 elements is refused before anything is launched; the widest accepted pitch runs (three
+    chunks of the contraction range, so the main loop's loads see the largest offsets)."""
+    n, m = 96, 4
+    A = torch.full((n, m), 1.0 / n, dtype=td, device="cuda"); B = A.clone()
+    for ld, ok in (((1 << 22), True), ((1 << 22) + 4, False)):
+        store = torch.ones(n * ld, dtype=td, device="cuda")
         K = store.as_strided((n, n), (ld, 1))
-        U = torch.ones(n, m, device="cuda"); V = torch.ones(n, m, device="cuda")
-        opts = api.make_opts(n, torch.float32, m=m, max_iters=2)
+        U = torch.ones(n, m, dtype=td, device="cuda"); V = torch.ones(n, m, dtype=td, device="cuda")
+        opts = api.make_opts(n, td, m=m, max_iters=2)
         ws = api.alloc_workspace(opts, api.FSK_MODE_BATCHED)
         if ok:
             api.fsk_sinkhorn_batched(opts, K, A, B, U, V, ws)
