@@ -248,8 +248,9 @@ __global__ __launch_bounds__(256) void batched_prod_f64_kernel(const double* __r
   double bA[2][4], bB[2][4];
   int c = c0;
   if (c0 < full_end) {
+    load_x(c0, st);   // asked for first: loads retire in order, and staging X must not wait for K
     load_k(c0, kaA);
-    load_x(c0, st);
+    __builtin_amdgcn_sched_barrier(0);
     store_x(0, st);
     __syncthreads();
     read_b(0, 0, bA[0]);
