@@ -37,9 +37,14 @@ def test_local_steps_match_oracle(orc, dtype, n, c, w, iters):
     """Several (clients, local steps), iteration counts that end inside a round as well as at a
     collective; n = 1000 with c = 8 or 5 gives blocks of 125 / 200 entries, which do not start on
     16-byte boundaries (a pack of four columns then belongs to two clients)."""
-    if n % c != 0:
-        pytest.skip("c must divide n")
     K, a, b = problem(orc, n, dtype)
+    if n % c != 0:                   # both sides refuse blocks of unequal height (n = c m, Sec. 3.1)
+        with pytest.raises(api.FskError) as e:
+            run_local(K, a, b, iters, c, w)
+        assert e.value.status == api.FSK_EDIV
+        with pytest.raises(ValueError):
+            orc.sinkhorn_local_steps(K, a, b, iters, c, w)
+        return
     uo, vo = orc.sinkhorn_local_steps(K, a, b, iters, c, w)
     u, v = run_local(K, a, b, iters, c, w)
     assert relerr(u, uo) <= TOL[np.dtype(dtype)] and relerr(v, vo) <= TOL[np.dtype(dtype)]
